@@ -1,0 +1,216 @@
+"""ctypes binding of libmxblas.so: the same names as include/mxblas.h, argument marshalling only.
+
+Every ``mxb_*`` function takes the handle first and accepts, for each device pointer, either a
+torch CUDA tensor (its ``data_ptr()`` is passed) or a raw integer address.  Nothing is computed
+here and there is no fallback: if the library has not been built, importing this module raises.
+
+:class:`Context` is a small convenience for callers that live in PyTorch: it creates a handle,
+points it at torch's current stream and gives it a workspace tensor.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmxblas.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it with `python -m paper_2411_07211_amd.build` "
+        "(there is no CPU fallback)"
+    )
+# PyTorch bundles its own HIP runtime (soname libamdhip64.so.7).  It has to be in the process
+# before libmxblas.so is loaded, so that the library's kernels are registered with the same
+# runtime that owns torch's device memory and streams; loaded the other way round, the process
+# would hold two runtimes and every launch would fail with "no device".
+import torch  # noqa: E402,F401  (load order matters)
+
+_lib = ctypes.CDLL(LIB_PATH)
+
+ROW_MAJOR, COL_MAJOR = 101, 102
+NO_TRANS, TRANS = 111, 112
+UPPER, LOWER = 121, 122
+NON_UNIT, UNIT = 131, 132
+AXPY, SCAL, DOT, ASUM, NRM2, GEMV, TRMV, SYMV, GER = range(1, 10)
+OK, ERR_HANDLE, ERR_WORKSPACE, ERR_NOT_IMPLEMENTED, ERR_HIP_BASE = 0, 1, 2, 3, 1000
+(OPT_L1_BLOCKS_PER_CU, OPT_REDUCE_BLOCKS, OPT_ROWDOT_XCHUNK, OPT_ROWDOT_BLOCKS_PER_CU,
+ OPT_COLACC_TARGET_BLOCKS, OPT_COLACC_MIN_ROWS, OPT_SYMV_TILE_ROWS, OPT_GER_ROWS_PER_BLOCK) = range(8)
+
+_i64, _int, _ptr, _sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
+_f, _d = ctypes.c_float, ctypes.c_double
+
+
+def _sig(name, restype, *argtypes):
+    fn = getattr(_lib, name)
+    fn.restype = restype
+    fn.argtypes = list(argtypes)
+    return fn
+
+
+_create = _sig("mxb_create", _int, ctypes.POINTER(_ptr))
+_destroy = _sig("mxb_destroy", _int, _ptr)
+_set_stream = _sig("mxb_set_stream", _int, _ptr, _ptr)
+_set_workspace = _sig("mxb_set_workspace", _int, _ptr, _ptr, _sz)
+_workspace_bytes = _sig("mxb_workspace_bytes", _sz, _int, _int, _i64, _i64)
+_set_option = _sig("mxb_set_option", _int, _ptr, _int, _i64)
+_get_option = _sig("mxb_get_option", _i64, _ptr, _int)
+_probe_copy = _sig("mxb_probe_copy", _int, _ptr, _sz, _ptr, _ptr)
+_probe_read = _sig("mxb_probe_read", _int, _ptr, _sz, _ptr)
+_fn = {}
+for _p, _t in (("s", _f), ("d", _d)):
+    _fn[_p + "axpy"] = _sig(f"mxb_{_p}axpy", _int, _ptr, _i64, _t, _ptr, _i64, _ptr, _i64)
+    _fn[_p + "scal"] = _sig(f"mxb_{_p}scal", _int, _ptr, _i64, _t, _ptr, _i64)
+    _fn[_p + "dot"] = _sig(f"mxb_{_p}dot", _int, _ptr, _i64, _ptr, _i64, _ptr, _i64, _ptr)
+    _fn[_p + "asum"] = _sig(f"mxb_{_p}asum", _int, _ptr, _i64, _ptr, _i64, _ptr)
+    _fn[_p + "nrm2"] = _sig(f"mxb_{_p}nrm2", _int, _ptr, _i64, _ptr, _i64, _ptr)
+    _fn[_p + "gemv"] = _sig(f"mxb_{_p}gemv", _int, _ptr, _int, _int, _i64, _i64, _t, _ptr, _i64, _ptr, _i64,
+                            _t, _ptr, _i64)
+    _fn[_p + "trmv"] = _sig(f"mxb_{_p}trmv", _int, _ptr, _int, _int, _int, _int, _i64, _ptr, _i64, _ptr, _i64)
+    _fn[_p + "symv"] = _sig(f"mxb_{_p}symv", _int, _ptr, _int, _int, _i64, _t, _ptr, _i64, _ptr, _i64, _t,
+                            _ptr, _i64)
+    _fn[_p + "ger"] = _sig(f"mxb_{_p}ger", _int, _ptr, _int, _i64, _i64, _t, _ptr, _i64, _ptr, _i64, _ptr, _i64)
+
+
+def _dp(t):
+    """Device address of a torch tensor, or the integer / None given."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t or None
+    return t.data_ptr() or None
+
+
+# ---- handle ------------------------------------------------------------------------------------
+def mxb_create():
+    """Returns (status, handle)."""
+    h = _ptr()
+    st = _create(ctypes.byref(h))
+    return st, h.value
+
+
+def mxb_destroy(h):
+    return _destroy(h)
+
+
+def mxb_set_stream(h, hip_stream):
+    return _set_stream(h, hip_stream)
+
+
+def mxb_set_workspace(h, dev_ptr, nbytes):
+    return _set_workspace(h, _dp(dev_ptr), nbytes)
+
+
+def mxb_workspace_bytes(routine, elem_size, m, n):
+    return _workspace_bytes(routine, elem_size, m, n)
+
+
+def mxb_set_option(h, option, value):
+    return _set_option(h, option, value)
+
+
+def mxb_get_option(h, option):
+    return _get_option(h, option)
+
+
+def mxb_probe_copy(h, nbytes, src, dst):
+    return _probe_copy(h, nbytes, _dp(src), _dp(dst))
+
+
+def mxb_probe_read(h, nbytes, src):
+    return _probe_read(h, nbytes, _dp(src))
+
+
+# ---- level 1 -----------------------------------------------------------------------------------
+def mxb_saxpy(h, n, alpha, x, incx, y, incy): return _fn["saxpy"](h, n, alpha, _dp(x), incx, _dp(y), incy)
+def mxb_daxpy(h, n, alpha, x, incx, y, incy): return _fn["daxpy"](h, n, alpha, _dp(x), incx, _dp(y), incy)
+def mxb_sscal(h, n, alpha, x, incx): return _fn["sscal"](h, n, alpha, _dp(x), incx)
+def mxb_dscal(h, n, alpha, x, incx): return _fn["dscal"](h, n, alpha, _dp(x), incx)
+def mxb_sdot(h, n, x, incx, y, incy, result): return _fn["sdot"](h, n, _dp(x), incx, _dp(y), incy, _dp(result))
+def mxb_ddot(h, n, x, incx, y, incy, result): return _fn["ddot"](h, n, _dp(x), incx, _dp(y), incy, _dp(result))
+def mxb_sasum(h, n, x, incx, result): return _fn["sasum"](h, n, _dp(x), incx, _dp(result))
+def mxb_dasum(h, n, x, incx, result): return _fn["dasum"](h, n, _dp(x), incx, _dp(result))
+def mxb_snrm2(h, n, x, incx, result): return _fn["snrm2"](h, n, _dp(x), incx, _dp(result))
+def mxb_dnrm2(h, n, x, incx, result): return _fn["dnrm2"](h, n, _dp(x), incx, _dp(result))
+
+
+# ---- level 2 -----------------------------------------------------------------------------------
+def mxb_sgemv(h, layout, trans, m, n, alpha, A, lda, x, incx, beta, y, incy):
+    return _fn["sgemv"](h, layout, trans, m, n, alpha, _dp(A), lda, _dp(x), incx, beta, _dp(y), incy)
+
+
+def mxb_dgemv(h, layout, trans, m, n, alpha, A, lda, x, incx, beta, y, incy):
+    return _fn["dgemv"](h, layout, trans, m, n, alpha, _dp(A), lda, _dp(x), incx, beta, _dp(y), incy)
+
+
+def mxb_strmv(h, layout, uplo, trans, diag, n, A, lda, x, incx):
+    return _fn["strmv"](h, layout, uplo, trans, diag, n, _dp(A), lda, _dp(x), incx)
+
+
+def mxb_dtrmv(h, layout, uplo, trans, diag, n, A, lda, x, incx):
+    return _fn["dtrmv"](h, layout, uplo, trans, diag, n, _dp(A), lda, _dp(x), incx)
+
+
+def mxb_ssymv(h, layout, uplo, n, alpha, A, lda, x, incx, beta, y, incy):
+    return _fn["ssymv"](h, layout, uplo, n, alpha, _dp(A), lda, _dp(x), incx, beta, _dp(y), incy)
+
+
+def mxb_dsymv(h, layout, uplo, n, alpha, A, lda, x, incx, beta, y, incy):
+    return _fn["dsymv"](h, layout, uplo, n, alpha, _dp(A), lda, _dp(x), incx, beta, _dp(y), incy)
+
+
+def mxb_sger(h, layout, m, n, alpha, x, incx, y, incy, A, lda):
+    return _fn["sger"](h, layout, m, n, alpha, _dp(x), incx, _dp(y), incy, _dp(A), lda)
+
+
+def mxb_dger(h, layout, m, n, alpha, x, incx, y, incy, A, lda):
+    return _fn["dger"](h, layout, m, n, alpha, _dp(x), incx, _dp(y), incy, _dp(A), lda)
+
+
+def routine(prefix: str, name: str):
+    """``routine('s', 'gemv')`` -> :func:`mxb_sgemv` (for code that is generic over precision)."""
+    return globals()[f"mxb_{prefix}{name}"]
+
+
+class MxbError(RuntimeError):
+    pass
+
+
+def check(status: int, what: str = "mxblas call"):
+    if status != OK:
+        raise MxbError(f"{what} failed with status {status}")
+
+
+class Context:
+    """A handle bound to torch's current stream on ``device`` with a workspace tensor."""
+
+    def __init__(self, device="cuda:0", workspace_bytes: int = 64 << 20):
+        import torch
+
+        if not torch.cuda.is_available():
+            raise MxbError("no GPU: libmxblas has no CPU path")
+        self.device = torch.device(device)
+        st, self.h = mxb_create()
+        check(st, "mxb_create")
+        self._ws = torch.empty(workspace_bytes, dtype=torch.uint8, device=self.device)
+        check(mxb_set_workspace(self.h, self._ws, workspace_bytes), "mxb_set_workspace")
+        self.use_current_stream()
+
+    def use_current_stream(self):
+        import torch
+
+        check(mxb_set_stream(self.h, torch.cuda.current_stream(self.device).cuda_stream), "mxb_set_stream")
+
+    def set_option(self, option, value):
+        check(mxb_set_option(self.h, option, value), "mxb_set_option")
+
+    def close(self):
+        if getattr(self, "h", None):
+            mxb_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

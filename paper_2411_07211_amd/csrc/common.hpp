@@ -1,0 +1,146 @@
+// Shared host/device helpers of libmxblas: the handle, argument checks, launch geometry, 128-bit
+// vector types, streaming loads and wavefront (64-lane) reductions on DPP.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/mxblas.h"
+
+struct mxb_ctx {
+    uint32_t magic;
+    hipStream_t stream;
+    void* ws;
+    size_t ws_bytes;
+    int64_t opt[MXB_OPT_COUNT];
+};
+
+namespace mxb {
+
+constexpr uint32_t kMagic = 0x6d786231u;   // "mxb1"
+constexpr int kWave = 64;                  // CDNA wavefront width
+constexpr int kCUs = 256;                  // MI355X compute units (8 XCDs x 32)
+
+inline bool handle_ok(mxb_handle_t h) { return h != nullptr && h->magic == kMagic; }
+
+inline int launch_status()
+{
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? MXB_OK : MXB_ERR_HIP_BASE + (int)e;
+}
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Pointer to logical element 0 of a strided vector: for a negative increment BLAS stores the
+// vector backwards, so element 0 sits at (n-1)*|inc| and the signed increment walks down.
+template <typename T>
+inline T* vec_base(T* p, int64_t n, int64_t inc)
+{
+    return inc >= 0 ? p : p + (n - 1) * (-inc);
+}
+
+// ------------------------------------------------------------------------------------------------
+// 128-bit vectors: 4 floats or 2 doubles per lane and load, so that one wavefront load moves 1 KiB.
+template <typename T, int VEC> struct VecOf;
+template <> struct VecOf<float, 4> { typedef float type __attribute__((ext_vector_type(4))); };
+template <> struct VecOf<double, 2> { typedef double type __attribute__((ext_vector_type(2))); };
+template <> struct VecOf<float, 1> { typedef float type __attribute__((ext_vector_type(1))); };
+template <> struct VecOf<double, 1> { typedef double type __attribute__((ext_vector_type(1))); };
+
+template <typename T> struct Full { static constexpr int vec = 16 / sizeof(T); };
+
+// Streaming (read-once) load / store: the non-temporal hint keeps a matrix that is touched exactly
+// once from pushing the reused vectors out of L2.
+template <typename V> __device__ __forceinline__ V ld_stream(const V* p) { return __builtin_nontemporal_load(p); }
+template <typename V> __device__ __forceinline__ void st_stream(V* p, V v) { __builtin_nontemporal_store(v, p); }
+
+// ------------------------------------------------------------------------------------------------
+// Wavefront reductions.  Lanes are organised as 4 DPP rows of 16.  Within a row: two quad
+// permutes (xor 1, xor 2), then row_half_mirror and row_mirror fold 4 -> 8 -> 16 lanes, after
+// which every lane of a row holds the row's sum.  Across rows: row_bcast15 adds row r into row
+// r+1 (rows 1 and 3), row_bcast31 adds lane 31 into rows 2 and 3, leaving the wavefront total in
+// lane 63, which readlane returns as a wave-uniform value.  The order of additions is fixed, so
+// results are reproducible.
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ float dpp_mov(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xF, false));
+}
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ double dpp_mov(double v)
+{
+    const uint64_t b = __builtin_bit_cast(uint64_t, v);
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)b, CTRL, ROW_MASK, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(uint32_t)(b >> 32), CTRL, ROW_MASK, 0xF, false);
+    return __builtin_bit_cast(double, ((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+}
+
+constexpr int kDppXor1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141; // row_half_mirror
+constexpr int kDppMirror = 0x140;     // row_mirror
+constexpr int kDppBcast15 = 0x142;    // row_bcast:15
+constexpr int kDppBcast31 = 0x143;    // row_bcast:31
+
+// Sum over each DPP row (16 adjacent lanes); every lane of the row receives the row sum.
+template <typename A>
+__device__ __forceinline__ A row16_sum(A v)
+{
+    v += dpp_mov<kDppXor1>(v);
+    v += dpp_mov<kDppXor2>(v);
+    v += dpp_mov<kDppHalfMirror>(v);
+    v += dpp_mov<kDppMirror>(v);
+    return v;
+}
+
+__device__ __forceinline__ float read_lane63(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+}
+__device__ __forceinline__ double read_lane63(double v)
+{
+    const uint64_t b = __builtin_bit_cast(uint64_t, v);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)b, 63);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(b >> 32), 63);
+    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+
+// Sum over the whole wavefront, returned wave-uniform.
+template <typename A>
+__device__ __forceinline__ A wave_sum(A v)
+{
+    v = row16_sum(v);
+    v += dpp_mov<kDppBcast15, 0xA>(v);
+    v += dpp_mov<kDppBcast31, 0xC>(v);
+    return read_lane63(v);
+}
+
+// Sum over the lanes that share one matrix row: 64 (whole wavefront) or 16 (one DPP row).
+template <int LANES, typename A>
+__device__ __forceinline__ A lanes_sum(A v)
+{
+    static_assert(LANES == 64 || LANES == 16, "lane group is a wavefront or a DPP row");
+    if constexpr (LANES == 64) return wave_sum(v);
+    else return row16_sum(v);
+}
+
+// Sum over a thread block of NW wavefronts in fixed wave order; every thread gets the result.
+// `slots` is LDS room for NW values and may be reused after the call returns.
+template <int NW, typename A>
+__device__ __forceinline__ A block_sum(A v, A* slots)
+{
+    const A w = wave_sum(v);
+    const int wave = threadIdx.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) slots[wave] = w;
+    __syncthreads();
+    A s = slots[0];
+#pragma unroll
+    for (int k = 1; k < NW; ++k) s += slots[k];
+    return s;
+}
+
+}  // namespace mxb

@@ -1,0 +1,175 @@
+// Handle management, workspace sizing and the two bandwidth probes.
+#include <new>
+
+#include "common.hpp"
+#include "options.hpp"
+#include "plan.hpp"
+
+namespace mxb {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kUnroll = 4;
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+__global__ void __launch_bounds__(kThreads) probe_copy_kernel(int64_t nvec, int64_t ntiles, const f4* __restrict__ src,
+                                                              f4* __restrict__ dst)
+{
+    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        const int64_t base = t * (kThreads * kUnroll) + threadIdx.x;
+        f4 a[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u)
+            if (base + u * kThreads < nvec) a[u] = ld_stream(src + base + u * kThreads);
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u)
+            if (base + u * kThreads < nvec) st_stream(dst + base + u * kThreads, a[u]);
+    }
+}
+
+__global__ void __launch_bounds__(kThreads) probe_read_kernel(int64_t nvec, int64_t ntiles, const f4* __restrict__ src,
+                                                              double* __restrict__ out)
+{
+    __shared__ double slots[kThreads / kWave];
+    f4 s = f4(0.f);
+    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        const int64_t base = t * (kThreads * kUnroll) + threadIdx.x;
+        f4 a[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            a[u] = f4(0.f);
+            if (base + u * kThreads < nvec) a[u] = ld_stream(src + base + u * kThreads);
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) s += a[u];
+    }
+    const double tot = block_sum<kThreads / kWave>((double)(s[0] + s[1] + s[2] + s[3]), slots);
+    if (threadIdx.x == 0) out[blockIdx.x] = tot;
+}
+
+}  // namespace
+}  // namespace mxb
+
+extern "C" {
+
+int mxb_create(mxb_handle_t* h)
+{
+    if (!h) return -1;
+    mxb_ctx* c = new (std::nothrow) mxb_ctx;
+    if (!c) return MXB_ERR_HANDLE;
+    c->magic = mxb::kMagic;
+    c->stream = nullptr;
+    c->ws = nullptr;
+    c->ws_bytes = 0;
+    for (int o = 0; o < MXB_OPT_COUNT; ++o) c->opt[o] = 0;
+    *h = c;
+    return MXB_OK;
+}
+
+int mxb_destroy(mxb_handle_t h)
+{
+    if (!mxb::handle_ok(h)) return MXB_ERR_HANDLE;
+    h->magic = 0;
+    delete h;
+    return MXB_OK;
+}
+
+int mxb_set_stream(mxb_handle_t h, void* hip_stream)
+{
+    if (!mxb::handle_ok(h)) return MXB_ERR_HANDLE;
+    h->stream = static_cast<hipStream_t>(hip_stream);
+    return MXB_OK;
+}
+
+int mxb_set_workspace(mxb_handle_t h, void* dev_ptr, size_t bytes)
+{
+    if (!mxb::handle_ok(h)) return MXB_ERR_HANDLE;
+    if ((reinterpret_cast<uintptr_t>(dev_ptr) & 255u) != 0) return -1;
+    if (!dev_ptr && bytes != 0) return -2;
+    h->ws = dev_ptr;
+    h->ws_bytes = bytes;
+    return MXB_OK;
+}
+
+int mxb_set_option(mxb_handle_t h, int option, int64_t value)
+{
+    if (!mxb::handle_ok(h)) return MXB_ERR_HANDLE;
+    if (option < 0 || option >= MXB_OPT_COUNT) return -1;
+    h->opt[option] = value > 0 ? value : 0;
+    return MXB_OK;
+}
+
+int64_t mxb_get_option(mxb_handle_t h, int option)
+{
+    if (!mxb::handle_ok(h) || option < 0 || option >= MXB_OPT_COUNT) return 0;
+    return mxb::option(h, option);
+}
+
+size_t mxb_workspace_bytes(int routine, int elem_size, int64_t m, int64_t n)
+{
+    using namespace mxb;
+    if ((elem_size != 4 && elem_size != 8) || m < 0 || n < 0) return 0;
+    const int full = 16 / elem_size;
+    auto colacc_bound = [&](int64_t rows, int64_t cols) {
+        size_t b = 0;
+        for (int vec : {1, full}) {
+            const ColaccPlan p = colacc_plan(rows, cols, vec, option_default(MXB_OPT_COLACC_TARGET_BLOCKS),
+                                             option_default(MXB_OPT_COLACC_MIN_ROWS));
+            const size_t need = p.nparts > 1 ? (size_t)p.nparts * (size_t)cols * (size_t)elem_size : 0;
+            b = need > b ? need : b;
+        }
+        return align_up(b, 256);
+    };
+    switch (routine) {
+        case MXB_AXPY: case MXB_SCAL: case MXB_GER: return 0;
+        case MXB_DOT: case MXB_ASUM: case MXB_NRM2:
+            return (size_t)option_default(MXB_OPT_REDUCE_BLOCKS) * 3 * sizeof(double);
+        case MXB_GEMV: {
+            const size_t a = colacc_bound(m, n), b = colacc_bound(n, m);
+            return a > b ? a : b;
+        }
+        case MXB_TRMV: return align_up((size_t)n * elem_size, 256) + colacc_bound(n, n);
+        case MXB_SYMV: {
+            size_t b = 0;
+            for (int vec : {1, full}) {
+                const SymvPlan p = symv_plan(n, vec, option_default(MXB_OPT_SYMV_TILE_ROWS));
+                const size_t need = (size_t)(p.ncol_tiles + p.nrow_tiles) * (size_t)n * (size_t)elem_size;
+                b = need > b ? need : b;
+            }
+            return align_up(b, 256);
+        }
+        default: return 0;
+    }
+}
+
+int mxb_probe_copy(mxb_handle_t h, size_t bytes, const void* src, void* dst)
+{
+    using namespace mxb;
+    if (!handle_ok(h)) return MXB_ERR_HANDLE;
+    if (bytes % 16 != 0 || !aligned16(src) || !aligned16(dst)) return -1;
+    if (bytes == 0) return MXB_OK;
+    if (!src) return -2;
+    if (!dst) return -3;
+    const int64_t nvec = (int64_t)(bytes / 16), ntiles = ceil_div(nvec, kThreads * kUnroll);
+    const int64_t cap = kCUs * option(h, MXB_OPT_L1_BLOCKS_PER_CU);
+    hipLaunchKernelGGL(probe_copy_kernel, dim3((unsigned)(ntiles < cap ? ntiles : cap)), dim3(kThreads), 0, h->stream, nvec,
+                       ntiles, static_cast<const f4*>(src), static_cast<f4*>(dst));
+    return launch_status();
+}
+
+int mxb_probe_read(mxb_handle_t h, size_t bytes, const void* src)
+{
+    using namespace mxb;
+    if (!handle_ok(h)) return MXB_ERR_HANDLE;
+    if (bytes % 16 != 0 || !aligned16(src)) return -1;
+    if (bytes == 0) return MXB_OK;
+    if (!src) return -2;
+    const int64_t nvec = (int64_t)(bytes / 16), ntiles = ceil_div(nvec, kThreads * kUnroll);
+    const int64_t cap = option(h, MXB_OPT_REDUCE_BLOCKS);
+    const int64_t grid = ntiles < cap ? ntiles : cap;
+    if (!h->ws || h->ws_bytes < (size_t)grid * sizeof(double)) return MXB_ERR_WORKSPACE;
+    hipLaunchKernelGGL(probe_read_kernel, dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, ntiles,
+                       static_cast<const f4*>(src), static_cast<double*>(h->ws));
+    return launch_status();
+}
+}

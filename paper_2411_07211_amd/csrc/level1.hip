@@ -1,0 +1,445 @@
+// Level-1 kernels (Sec. 6.2.1): axpy, scal (streaming) and dot, asum, nrm2 (reductions).
+//
+// The paper's recipe for these single-loop kernels is vector lanes plus loop interleaving, with
+// per-lane partial sums for the reductions.  On gfx950 the same idea reads: every lane moves
+// 128 bits per load, each thread keeps kUnroll independent loads in flight (the interleave
+// factor), reductions keep per-lane partial sums in registers, fold them across the wavefront
+// with DPP, across the block through LDS, and across blocks in a second, single-block kernel
+// that adds the per-block partials in a fixed order (no atomics).
+#include "common.hpp"
+#include "options.hpp"
+
+namespace mxb {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kUnroll = 4;   // independent 128-bit loads per thread and array
+
+// ---------------------------------------------------------------------------------------------
+// streaming: axpy / scal on contiguous, 16-byte aligned data
+
+template <typename T>
+__global__ void __launch_bounds__(kThreads) axpy_vec_kernel(int64_t nvec, int64_t ntiles, int tail, T alpha,
+                                                            const T* __restrict__ x, T* __restrict__ y)
+{
+    constexpr int VEC = Full<T>::vec;
+    typedef typename VecOf<T, VEC>::type V;
+    const V* xv = reinterpret_cast<const V*>(x);
+    V* yv = reinterpret_cast<V*>(y);
+    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        const int64_t base = t * (kThreads * kUnroll) + threadIdx.x;
+        V a[kUnroll], b[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int64_t i = base + u * kThreads;
+            if (i < nvec) { a[u] = ld_stream(xv + i); b[u] = ld_stream(yv + i); }
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int64_t i = base + u * kThreads;
+            if (i < nvec) {
+#pragma unroll
+                for (int k = 0; k < VEC; ++k) b[u][k] = __builtin_fma(alpha, a[u][k], b[u][k]);
+                st_stream(yv + i, b[u]);
+            }
+        }
+    }
+    if (blockIdx.x == 0 && (int)threadIdx.x < tail) {
+        const int64_t i = nvec * VEC + threadIdx.x;
+        y[i] = __builtin_fma(alpha, x[i], y[i]);
+    }
+}
+
+template <typename T>
+__global__ void __launch_bounds__(kThreads) scal_vec_kernel(int64_t nvec, int64_t ntiles, int tail, T alpha,
+                                                            T* __restrict__ x)
+{
+    constexpr int VEC = Full<T>::vec;
+    typedef typename VecOf<T, VEC>::type V;
+    V* xv = reinterpret_cast<V*>(x);
+    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        const int64_t base = t * (kThreads * kUnroll) + threadIdx.x;
+        V a[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int64_t i = base + u * kThreads;
+            if (i < nvec) a[u] = ld_stream(xv + i);
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int64_t i = base + u * kThreads;
+            if (i < nvec) {
+#pragma unroll
+                for (int k = 0; k < VEC; ++k) a[u][k] = alpha * a[u][k];
+                st_stream(xv + i, a[u]);
+            }
+        }
+    }
+    if (blockIdx.x == 0 && (int)threadIdx.x < tail) {
+        const int64_t i = nvec * VEC + threadIdx.x;
+        x[i] = alpha * x[i];
+    }
+}
+
+// streaming with arbitrary increments (or unaligned data): one element per lane and load,
+// 64-bit offsets because a strided fp64 vector of 2^28 elements spans more than 4 GiB.
+template <typename T>
+__global__ void __launch_bounds__(kThreads) axpy_strided_kernel(int64_t n, T alpha, const T* __restrict__ x, int64_t incx,
+                                                                T* __restrict__ y, int64_t incy)
+{
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    for (int64_t i0 = (int64_t)blockIdx.x * kThreads + threadIdx.x; i0 < n; i0 += stride * kUnroll) {
+        T a[kUnroll], b[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int64_t i = i0 + u * stride;
+            if (i < n) { a[u] = x[i * incx]; b[u] = y[i * incy]; }
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int64_t i = i0 + u * stride;
+            if (i < n) y[i * incy] = __builtin_fma(alpha, a[u], b[u]);
+        }
+    }
+}
+
+template <typename T>
+__global__ void __launch_bounds__(kThreads) scal_strided_kernel(int64_t n, T alpha, T* __restrict__ x, int64_t incx)
+{
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    for (int64_t i0 = (int64_t)blockIdx.x * kThreads + threadIdx.x; i0 < n; i0 += stride * kUnroll) {
+        T a[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int64_t i = i0 + u * stride;
+            if (i < n) a[u] = x[i * incx];
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int64_t i = i0 + u * stride;
+            if (i < n) x[i * incx] = alpha * a[u];
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// reductions
+
+enum { OP_DOT = 0, OP_ASUM = 1, OP_NRM2 = 2 };
+
+// Constants of Blue's scaled sum of squares for fp64 (as restated by Anderson, "Safe scaling in
+// the level 1 BLAS", 2017): values above kBig are scaled down, values below kSmall are scaled up,
+// so that no square overflows or underflows; the rest is summed as is.
+constexpr double kTSmall = 0x1p-511, kTBig = 0x1p+486, kSSmall = 0x1p+537, kSBig = 0x1p-538;
+
+// Per-thread running sums.  K = number of doubles a block hands to the second pass.
+template <typename T, int OP> struct Acc;
+
+template <> struct Acc<float, OP_DOT> {
+    static constexpr int K = 1;
+    float s = 0.f;
+    __device__ __forceinline__ void add(float x, float y) { s = __builtin_fmaf(x, y, s); }
+    __device__ __forceinline__ void get(double* o) const { o[0] = (double)s; }
+};
+template <> struct Acc<double, OP_DOT> {
+    static constexpr int K = 1;
+    double s = 0.0;
+    __device__ __forceinline__ void add(double x, double y) { s = __builtin_fma(x, y, s); }
+    __device__ __forceinline__ void get(double* o) const { o[0] = s; }
+};
+template <> struct Acc<float, OP_ASUM> {
+    static constexpr int K = 1;
+    float s = 0.f;
+    __device__ __forceinline__ void add(float x, float) { s += __builtin_fabsf(x); }
+    __device__ __forceinline__ void get(double* o) const { o[0] = (double)s; }
+};
+template <> struct Acc<double, OP_ASUM> {
+    static constexpr int K = 1;
+    double s = 0.0;
+    __device__ __forceinline__ void add(double x, double) { s += __builtin_fabs(x); }
+    __device__ __forceinline__ void get(double* o) const { o[0] = s; }
+};
+template <> struct Acc<float, OP_NRM2> {   // squares of floats are exact and cannot overflow in fp64
+    static constexpr int K = 1;
+    double s = 0.0;
+    __device__ __forceinline__ void add(float x, float) { const double d = (double)x; s = __builtin_fma(d, d, s); }
+    __device__ __forceinline__ void get(double* o) const { o[0] = s; }
+};
+template <> struct Acc<double, OP_NRM2> {
+    static constexpr int K = 3;
+    double med = 0.0, big = 0.0, sml = 0.0;
+    __device__ __forceinline__ void add(double x, double)
+    {
+        const double ax = __builtin_fabs(x);
+        const bool is_big = ax > kTBig, is_sml = ax < kTSmall;
+        const double m = (is_big || is_sml) ? 0.0 : ax;   // NaN compares false twice: goes to med
+        const double b = is_big ? ax * kSBig : 0.0;
+        const double s = is_sml ? ax * kSSmall : 0.0;
+        med = __builtin_fma(m, m, med);
+        big = __builtin_fma(b, b, big);
+        sml = __builtin_fma(s, s, sml);
+    }
+    __device__ __forceinline__ void get(double* o) const { o[0] = med; o[1] = big; o[2] = sml; }
+};
+
+template <typename T, int OP>
+__device__ __forceinline__ void block_partial(const Acc<T, OP>* acc, int nacc, double* __restrict__ partials)
+{
+    constexpr int K = Acc<T, OP>::K;
+    __shared__ double slots[kThreads / kWave];
+    double v[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) v[k] = 0.0;
+    for (int a = 0; a < nacc; ++a) {
+        double t[K];
+        acc[a].get(t);
+#pragma unroll
+        for (int k = 0; k < K; ++k) v[k] += t[k];
+    }
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const double s = block_sum<kThreads / kWave>(v[k], slots);
+        if (threadIdx.x == 0) partials[(int64_t)blockIdx.x * K + k] = s;
+    }
+}
+
+// pass 1 on contiguous, aligned data.  TWO = the op reads y as well (dot).
+template <typename T, int OP>
+__global__ void __launch_bounds__(kThreads) reduce_vec_kernel(int64_t nvec, int64_t ntiles, int tail,
+                                                              const T* __restrict__ x, const T* __restrict__ y,
+                                                              double* __restrict__ partials)
+{
+    constexpr int VEC = Full<T>::vec;
+    constexpr bool TWO = OP == OP_DOT;
+    typedef typename VecOf<T, VEC>::type V;
+    const V* xv = reinterpret_cast<const V*>(x);
+    const V* yv = reinterpret_cast<const V*>(y);
+    Acc<T, OP> acc[VEC];
+    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        const int64_t base = t * (kThreads * kUnroll) + threadIdx.x;
+        V a[kUnroll], b[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int64_t i = base + u * kThreads;
+            a[u] = V(0); b[u] = V(0);
+            if (i < nvec) {
+                a[u] = ld_stream(xv + i);
+                if (TWO) b[u] = ld_stream(yv + i);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u)
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) acc[k].add(a[u][k], b[u][k]);
+    }
+    if (blockIdx.x == 0 && (int)threadIdx.x < tail) {
+        const int64_t i = nvec * VEC + threadIdx.x;
+        acc[0].add(x[i], TWO ? y[i] : T(0));
+    }
+    block_partial<T, OP>(acc, VEC, partials);
+}
+
+// pass 1 with arbitrary increments (or unaligned data)
+template <typename T, int OP>
+__global__ void __launch_bounds__(kThreads) reduce_strided_kernel(int64_t n, const T* __restrict__ x, int64_t incx,
+                                                                  const T* __restrict__ y, int64_t incy,
+                                                                  double* __restrict__ partials)
+{
+    constexpr bool TWO = OP == OP_DOT;
+    Acc<T, OP> acc[kUnroll];
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    for (int64_t i0 = (int64_t)blockIdx.x * kThreads + threadIdx.x; i0 < n; i0 += stride * kUnroll) {
+        T a[kUnroll], b[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int64_t i = i0 + u * stride;
+            a[u] = T(0); b[u] = T(0);
+            if (i < n) {
+                a[u] = x[i * incx];
+                if (TWO) b[u] = y[i * incy];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) acc[u].add(a[u], b[u]);
+    }
+    block_partial<T, OP>(acc, kUnroll, partials);
+}
+
+// pass 2: one block adds the per-block partials in a fixed order and finishes the result.
+template <typename T, int OP>
+__global__ void __launch_bounds__(kThreads) reduce_final_kernel(int nparts, const double* __restrict__ partials,
+                                                                T* __restrict__ result)
+{
+    constexpr int K = Acc<T, OP>::K;
+    __shared__ double slots[kThreads / kWave];
+    double v[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        double s = 0.0;
+        for (int p = threadIdx.x; p < nparts; p += kThreads) s += partials[(int64_t)p * K + k];
+        v[k] = block_sum<kThreads / kWave>(s, slots);
+    }
+    if (threadIdx.x != 0) return;
+    if constexpr (OP != OP_NRM2) {
+        *result = (T)v[0];
+    } else if constexpr (K == 1) {
+        *result = (T)__builtin_sqrt(v[0]);
+    } else {
+        double med = v[0], big = v[1], sml = v[2], r;
+        if (big > 0.0) {
+            // fold the mid-range sum into the scaled-down one (also carries a NaN across)
+            if (med > 0.0 || med != med) big += (med * kSBig) * kSBig;
+            r = __builtin_sqrt(big) / kSBig;
+        } else if (sml > 0.0) {
+            if (med > 0.0 || med != med) {
+                const double a = __builtin_sqrt(med), b = __builtin_sqrt(sml) / kSSmall;
+                const double lo = a < b ? a : b, hi = a < b ? b : a;
+                r = hi * __builtin_sqrt(1.0 + (lo / hi) * (lo / hi));
+            } else {
+                r = __builtin_sqrt(sml) / kSSmall;
+            }
+        } else {
+            r = __builtin_sqrt(med);
+        }
+        *result = r;
+    }
+}
+
+template <typename T>
+__global__ void store_scalar_kernel(T* p, T v) { *p = v; }
+
+// ---------------------------------------------------------------------------------------------
+// host side
+
+template <typename T>
+int axpy(mxb_handle_t h, int64_t n, T alpha, const T* x, int64_t incx, T* y, int64_t incy)
+{
+    if (!handle_ok(h)) return MXB_ERR_HANDLE;
+    if (n < 0) return -1;
+    if (n == 0 || alpha == T(0)) return MXB_OK;
+    if (!x) return -3;
+    if (incx == 0) return -4;
+    if (!y) return -5;
+    if (incy == 0) return -6;
+    constexpr int VEC = Full<T>::vec;
+    const int64_t bpc = option(h, MXB_OPT_L1_BLOCKS_PER_CU);
+    if (incx == 1 && incy == 1 && aligned16(x) && aligned16(y)) {
+        const int64_t nvec = n / VEC;
+        const int64_t ntiles = ceil_div(nvec, kThreads * kUnroll);
+        const int64_t grid = ntiles < 1 ? 1 : (ntiles < kCUs * bpc ? ntiles : kCUs * bpc);
+        hipLaunchKernelGGL(axpy_vec_kernel<T>, dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, ntiles,
+                           (int)(n % VEC), alpha, x, y);
+    } else {
+        const int64_t want = ceil_div(n, kThreads * kUnroll);
+        const int64_t grid = want < kCUs * bpc ? want : kCUs * bpc;
+        hipLaunchKernelGGL(axpy_strided_kernel<T>, dim3((unsigned)grid), dim3(kThreads), 0, h->stream, n, alpha,
+                           vec_base(x, n, incx), incx, vec_base(y, n, incy), incy);
+    }
+    return launch_status();
+}
+
+template <typename T>
+int scal(mxb_handle_t h, int64_t n, T alpha, T* x, int64_t incx)
+{
+    if (!handle_ok(h)) return MXB_ERR_HANDLE;
+    if (n < 0) return -1;
+    if (n == 0 || incx <= 0) return MXB_OK;
+    if (!x) return -3;
+    constexpr int VEC = Full<T>::vec;
+    const int64_t bpc = option(h, MXB_OPT_L1_BLOCKS_PER_CU);
+    if (incx == 1 && aligned16(x)) {
+        const int64_t nvec = n / VEC;
+        const int64_t ntiles = ceil_div(nvec, kThreads * kUnroll);
+        const int64_t grid = ntiles < 1 ? 1 : (ntiles < kCUs * bpc ? ntiles : kCUs * bpc);
+        hipLaunchKernelGGL(scal_vec_kernel<T>, dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, ntiles,
+                           (int)(n % VEC), alpha, x);
+    } else {
+        const int64_t want = ceil_div(n, kThreads * kUnroll);
+        const int64_t grid = want < kCUs * bpc ? want : kCUs * bpc;
+        hipLaunchKernelGGL(scal_strided_kernel<T>, dim3((unsigned)grid), dim3(kThreads), 0, h->stream, n, alpha, x, incx);
+    }
+    return launch_status();
+}
+
+// x, y already checked.  y == nullptr for the one-vector ops.
+template <typename T, int OP>
+int reduce(mxb_handle_t h, int64_t n, const T* x, int64_t incx, const T* y, int64_t incy, T* result)
+{
+    constexpr int VEC = Full<T>::vec;
+    constexpr int K = Acc<T, OP>::K;
+    const bool empty = n == 0 || (OP != OP_DOT && incx <= 0);
+    if (empty) {
+        hipLaunchKernelGGL(store_scalar_kernel<T>, dim3(1), dim3(1), 0, h->stream, result, T(0));
+        return launch_status();
+    }
+    const int64_t max_blocks = option(h, MXB_OPT_REDUCE_BLOCKS);
+    if (!h->ws || h->ws_bytes < (size_t)max_blocks * K * sizeof(double)) return MXB_ERR_WORKSPACE;
+    double* partials = static_cast<double*>(h->ws);
+    int64_t grid;
+    const bool contiguous = incx == 1 && aligned16(x) && (OP != OP_DOT || (incy == 1 && aligned16(y)));
+    if (contiguous) {
+        const int64_t nvec = n / VEC;
+        const int64_t ntiles = ceil_div(nvec, kThreads * kUnroll);
+        grid = ntiles < 1 ? 1 : (ntiles < max_blocks ? ntiles : max_blocks);
+        hipLaunchKernelGGL((reduce_vec_kernel<T, OP>), dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, ntiles,
+                           (int)(n % VEC), x, y, partials);
+    } else {
+        const int64_t want = ceil_div(n, kThreads * kUnroll);
+        grid = want < max_blocks ? want : max_blocks;
+        hipLaunchKernelGGL((reduce_strided_kernel<T, OP>), dim3((unsigned)grid), dim3(kThreads), 0, h->stream, n,
+                           vec_base(x, n, incx), incx, y ? vec_base(y, n, incy) : nullptr, incy, partials);
+    }
+    int st = launch_status();
+    if (st != MXB_OK) return st;
+    hipLaunchKernelGGL((reduce_final_kernel<T, OP>), dim3(1), dim3(kThreads), 0, h->stream, (int)grid, partials, result);
+    return launch_status();
+}
+
+template <typename T>
+int dot(mxb_handle_t h, int64_t n, const T* x, int64_t incx, const T* y, int64_t incy, T* result)
+{
+    if (!handle_ok(h)) return MXB_ERR_HANDLE;
+    if (n < 0) return -1;
+    if (!result) return -6;
+    if (n > 0) {
+        if (!x) return -2;
+        if (incx == 0) return -3;
+        if (!y) return -4;
+        if (incy == 0) return -5;
+    }
+    return reduce<T, OP_DOT>(h, n, x, incx, y, incy, result);
+}
+
+template <typename T, int OP>
+int one_vector(mxb_handle_t h, int64_t n, const T* x, int64_t incx, T* result)
+{
+    if (!handle_ok(h)) return MXB_ERR_HANDLE;
+    if (n < 0) return -1;
+    if (!result) return -4;
+    if (n > 0 && incx > 0 && !x) return -2;
+    return reduce<T, OP>(h, n, x, incx, nullptr, 0, result);
+}
+
+}  // namespace
+}  // namespace mxb
+
+extern "C" {
+int mxb_saxpy(mxb_handle_t h, int64_t n, float alpha, const float* x, int64_t incx, float* y, int64_t incy)
+{ return mxb::axpy<float>(h, n, alpha, x, incx, y, incy); }
+int mxb_daxpy(mxb_handle_t h, int64_t n, double alpha, const double* x, int64_t incx, double* y, int64_t incy)
+{ return mxb::axpy<double>(h, n, alpha, x, incx, y, incy); }
+int mxb_sscal(mxb_handle_t h, int64_t n, float alpha, float* x, int64_t incx) { return mxb::scal<float>(h, n, alpha, x, incx); }
+int mxb_dscal(mxb_handle_t h, int64_t n, double alpha, double* x, int64_t incx) { return mxb::scal<double>(h, n, alpha, x, incx); }
+int mxb_sdot(mxb_handle_t h, int64_t n, const float* x, int64_t incx, const float* y, int64_t incy, float* r)
+{ return mxb::dot<float>(h, n, x, incx, y, incy, r); }
+int mxb_ddot(mxb_handle_t h, int64_t n, const double* x, int64_t incx, const double* y, int64_t incy, double* r)
+{ return mxb::dot<double>(h, n, x, incx, y, incy, r); }
+int mxb_sasum(mxb_handle_t h, int64_t n, const float* x, int64_t incx, float* r)
+{ return mxb::one_vector<float, mxb::OP_ASUM>(h, n, x, incx, r); }
+int mxb_dasum(mxb_handle_t h, int64_t n, const double* x, int64_t incx, double* r)
+{ return mxb::one_vector<double, mxb::OP_ASUM>(h, n, x, incx, r); }
+int mxb_snrm2(mxb_handle_t h, int64_t n, const float* x, int64_t incx, float* r)
+{ return mxb::one_vector<float, mxb::OP_NRM2>(h, n, x, incx, r); }
+int mxb_dnrm2(mxb_handle_t h, int64_t n, const double* x, int64_t incx, double* r)
+{ return mxb::one_vector<double, mxb::OP_NRM2>(h, n, x, incx, r); }
+}

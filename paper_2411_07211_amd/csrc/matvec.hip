@@ -1,0 +1,508 @@
+// gemv and trmv (Sec. 6.2.2) on a row-major matrix.
+//
+// Two kernels cover both routines and both orientations:
+//
+//  * row-dot (no transpose; Sec. 2: y[i] += A[i,j]*x[j]).  The paper batches r rows so that each
+//    x[j] is loaded once for all of them (unroll-and-jam).  Here a group of LPR lanes walks R
+//    rows at once with 128-bit loads of A; x is staged in LDS once per block and chunk and read
+//    from there by every row of the tile; the R sums are folded across the lane group with DPP
+//    and written with one store per wavefront.
+//
+//  * column-accumulate (transpose; Fig. 7c: y[j] += x[i]*A[i,j]).  Every lane owns VEC adjacent
+//    columns and keeps their sums in registers while the block walks down a slab of rows; x[i]
+//    is wave-uniform and comes through the scalar path.  Slabs are combined by a second kernel
+//    that adds the per-slab partial vectors in slab order and applies alpha/beta (no atomics).
+//
+// trmv runs the same kernels with MODE = upper/lower: the column (row) range of every tile is
+// clipped to the triangle at tile granularity (the paper's bound rounding) and the elements of a
+// straddling 128-bit load that lie outside the triangle are discarded with a select, never by
+// multiplying with zero, so that NaN/Inf stored there cannot leak into the result.
+#include "common.hpp"
+#include "options.hpp"
+#include "plan.hpp"
+
+namespace mxb {
+namespace {
+
+enum { MODE_GENERAL = 0, MODE_UPPER = 1, MODE_LOWER = 2 };
+
+__device__ __forceinline__ int64_t imin(int64_t a, int64_t b) { return a < b ? a : b; }
+__device__ __forceinline__ int64_t imax(int64_t a, int64_t b) { return a > b ? a : b; }
+
+// Value that matrix element (i, j), loaded as `a`, contributes in a triangular mode.
+template <typename T, int MODE, bool UNIT>
+__device__ __forceinline__ T tri_value(T a, int64_t i, int64_t j)
+{
+    if constexpr (MODE == MODE_GENERAL) return a;
+    const bool inside = MODE == MODE_UPPER ? j >= i : j <= i;
+    a = inside ? a : T(0);
+    if constexpr (UNIT) a = (i == j) ? T(1) : a;
+    return a;
+}
+
+// ---------------------------------------------------------------------------------------------
+// row-dot
+
+template <typename T>
+struct RowdotArgs {
+    int64_t M, N;        // rows and columns of the row-major matrix
+    const T* A;
+    int64_t lda;
+    const T* x;          // logical element 0
+    int64_t incx;        // signed
+    T* y;                // logical element 0
+    int64_t incy;
+    T alpha, beta;
+    int xchunk;          // elements of x staged per chunk (multiple of 256)
+    int x_contig;        // x has unit increment and is 16-byte aligned: stage it with 128-bit loads
+};
+
+constexpr int kRowdotWaves = 8;
+constexpr int kRowdotThreads = kRowdotWaves * kWave;
+
+template <typename T, int VEC, int LPR, int R, int MODE, bool UNIT>
+__global__ void __launch_bounds__(kRowdotThreads, 4) rowdot_kernel(const RowdotArgs<T> p)
+{
+    typedef typename VecOf<T, VEC>::type V;
+    constexpr int FV = Full<T>::vec;
+    typedef typename VecOf<T, FV>::type XV;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    T* xs = reinterpret_cast<T*>(smem_raw);
+
+    constexpr int GPW = kWave / LPR;          // lane groups (= concurrent rows) per wavefront
+    constexpr int RW = GPW * R;               // rows per wavefront tile
+    constexpr int RB = kRowdotWaves * RW;     // rows per block tile
+    constexpr int STEP = LPR * VEC;           // columns a lane group covers per load
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int g = lane / LPR, l = lane % LPR;
+    const int64_t ntiles = (p.M + RB - 1) / RB;
+    const int64_t Nv = p.N - p.N % VEC;       // columns that whole vectors cover
+    const int64_t xc = p.xchunk;
+    int64_t staged = -1;
+
+    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
+        // lower triangles are heaviest at the bottom: hand those tiles out first
+        const int64_t tile = MODE == MODE_LOWER ? ntiles - 1 - t : t;
+        const int64_t brow0 = tile * RB;
+        const int64_t wrow0 = brow0 + (int64_t)wave * RW;
+        const int64_t grow0 = wrow0 + g * R;
+
+        // column range the block / the wavefront has to visit
+        int64_t bclo = 0, bchi = p.N, wclo = 0, wchi = Nv;
+        if (MODE == MODE_UPPER) { bclo = imin(brow0, p.N); wclo = wrow0; }
+        if (MODE == MODE_LOWER) { bchi = imin(p.N, brow0 + RB); wchi = imin(Nv, wrow0 + RW); }
+
+        const T* arow[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) arow[r] = p.A + imin(grow0 + r, p.M - 1) * p.lda;   // clamp: loads stay in bounds
+        T acc[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) acc[r] = T(0);
+
+        for (int64_t c0 = bclo / xc * xc; c0 < bchi; c0 += xc) {
+            const int64_t c1 = imin(c0 + xc, p.N);
+            if (c0 != staged) {
+                __syncthreads();
+                const int cnt = (int)(c1 - c0);
+                if (p.x_contig) {
+                    const XV* src = reinterpret_cast<const XV*>(p.x + c0);
+                    XV* dst = reinterpret_cast<XV*>(xs);
+                    const int nv = cnt / FV;
+#pragma unroll 4
+                    for (int j = threadIdx.x; j < nv; j += kRowdotThreads) dst[j] = src[j];
+                    for (int j = nv * FV + threadIdx.x; j < cnt; j += kRowdotThreads) xs[j] = p.x[c0 + j];
+                } else {
+#pragma unroll 4
+                    for (int j = threadIdx.x; j < cnt; j += kRowdotThreads) xs[j] = p.x[(c0 + j) * p.incx];
+                }
+                __syncthreads();
+                staged = c0;
+            }
+            const int64_t lo = imax(wclo, c0), hi = imin(wchi, imin(c0 + xc, Nv));
+            if (lo < hi) {
+                const int64_t first = c0 + (lo - c0) / STEP * STEP + l * VEC;
+#pragma unroll 2
+                for (int64_t c = first; c < hi; c += STEP) {
+                    const V xv = *reinterpret_cast<const V*>(xs + (c - c0));
+                    V av[R];
+#pragma unroll
+                    for (int r = 0; r < R; ++r) av[r] = ld_stream(reinterpret_cast<const V*>(arow[r] + c));
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int k = 0; k < VEC; ++k)
+                            acc[r] = __builtin_fma(tri_value<T, MODE, UNIT>(av[r][k], grow0 + r, c + k), xv[k], acc[r]);
+                }
+            }
+        }
+        // columns past the last whole vector (N not a multiple of VEC): one lane each
+        if (VEC > 1 && Nv < p.N) {
+            const int64_t j = Nv + l;
+            const bool visit = MODE == MODE_LOWER ? wrow0 + RW > Nv : true;
+            if (visit && j < p.N) {
+                const T xj = p.x[j * p.incx];
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+                    acc[r] = __builtin_fma(tri_value<T, MODE, UNIT>(arow[r][j], grow0 + r, j), xj, acc[r]);
+            }
+        }
+
+        // fold the lane group, then lane r of the group stores row r
+        T out = T(0);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const T s = lanes_sum<LPR>(acc[r]);
+            out = (l == r) ? s : out;
+        }
+        const int64_t i = grow0 + l;
+        if (l < R && i < p.M) {
+            T* yp = p.y + i * p.incy;
+            T v = p.alpha * out;
+            if (p.beta != T(0)) v = __builtin_fma(p.beta, *yp, v);
+            *yp = v;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// column-accumulate
+
+template <typename T>
+struct ColaccArgs {
+    int64_t M, N;
+    const T* A;
+    int64_t lda;
+    const T* x;          // logical element 0 (length M)
+    int64_t incx;
+    T* y;                // logical element 0 (length N); written directly when there is one slab
+    int64_t incy;
+    T alpha, beta;
+    T* partials;         // [slabs][N] when there are several slabs
+    int64_t rows_per_block;
+};
+
+constexpr int kColaccThreads = 256;
+constexpr int kColaccUnroll = 8;
+
+template <typename T, int VEC, int WR, int MODE, bool UNIT>
+__global__ void __launch_bounds__(kColaccThreads) colacc_kernel(const ColaccArgs<T> p)
+{
+    typedef typename VecOf<T, VEC>::type V;
+    constexpr int NW = kColaccThreads / kWave, WC = NW / WR, U = kColaccUnroll;
+    __shared__ T red[WR > 1 ? (WR - 1) * WC * kWave * VEC : 1];
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wc = wave % WC, wr = wave / WC;
+    const int64_t cblock0 = (int64_t)blockIdx.x * (WC * kWave * VEC);
+    const int64_t cblock1 = imin(p.N, cblock0 + WC * kWave * VEC);     // exclusive
+    const int64_t c = cblock0 + (int64_t)(wc * kWave + lane) * VEC;
+    const bool col_ok = c + VEC <= p.N;
+
+    int64_t rlo = (int64_t)blockIdx.y * p.rows_per_block;
+    int64_t rhi = imin(p.M, rlo + p.rows_per_block);
+    if (MODE == MODE_UPPER) rhi = imin(rhi, cblock1);   // rows i <= j
+    if (MODE == MODE_LOWER) rlo = imax(rlo, cblock0);   // rows i >= j
+
+    T acc[VEC];
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) acc[k] = T(0);
+
+    if (col_ok) {
+        const T* acol = p.A + c;
+        int64_t i0 = rlo + wr;
+        for (; i0 + (int64_t)(U - 1) * WR < rhi; i0 += (int64_t)U * WR) {
+            V a[U];
+            T xi[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t i = i0 + (int64_t)u * WR;
+                a[u] = ld_stream(reinterpret_cast<const V*>(acol + i * p.lda));
+                xi[u] = p.x[i * p.incx];
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int k = 0; k < VEC; ++k)
+                    acc[k] = __builtin_fma(tri_value<T, MODE, UNIT>(a[u][k], i0 + (int64_t)u * WR, c + k), xi[u], acc[k]);
+        }
+        for (; i0 < rhi; i0 += WR) {
+            const V a = ld_stream(reinterpret_cast<const V*>(acol + i0 * p.lda));
+            const T xi = p.x[i0 * p.incx];
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) acc[k] = __builtin_fma(tri_value<T, MODE, UNIT>(a[k], i0, c + k), xi, acc[k]);
+        }
+    }
+
+    if (WR > 1) {   // fold the wavefronts that split the rows, in wave order
+        T* mine = red + ((int64_t)((wr - 1) * WC + wc) * kWave + lane) * VEC;
+        if (wr > 0)
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) mine[k] = acc[k];
+        __syncthreads();
+        if (wr > 0) return;
+#pragma unroll
+        for (int w = 1; w < WR; ++w)
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) acc[k] += red[((int64_t)((w - 1) * WC + wc) * kWave + lane) * VEC + k];
+    }
+    if (!col_ok) return;
+
+    if (gridDim.y == 1) {
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+            T* yp = p.y + (c + k) * p.incy;
+            T v = p.alpha * acc[k];
+            if (p.beta != T(0)) v = __builtin_fma(p.beta, *yp, v);
+            *yp = v;
+        }
+    } else {
+        V v;
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) v[k] = acc[k];
+        *reinterpret_cast<V*>(p.partials + (int64_t)blockIdx.y * p.N + c) = v;
+    }
+}
+
+constexpr int kCombineGroups = 16;
+
+// y[j] = alpha * sum_p partials[p][j] + beta*y[j], p ascending.  64 columns per block; the 16
+// wavefronts of the block each take every 16th slab, LDS folds them in wave order.
+template <typename T>
+__global__ void __launch_bounds__(kCombineGroups* kWave) colacc_combine_kernel(int64_t nparts, int64_t N,
+                                                                               const T* __restrict__ partials, T alpha, T beta,
+                                                                               T* __restrict__ y, int64_t incy)
+{
+    __shared__ T red[kCombineGroups][kWave];
+    const int tx = threadIdx.x & (kWave - 1), ty = threadIdx.x >> 6;
+    const int64_t j = (int64_t)blockIdx.x * kWave + tx;
+    T s = T(0);
+    if (j < N) {
+#pragma unroll 4
+        for (int64_t q = ty; q < nparts; q += kCombineGroups) s += partials[q * N + j];
+    }
+    red[ty][tx] = s;
+    __syncthreads();
+    if (ty != 0 || j >= N) return;
+    T tot = red[0][tx];
+#pragma unroll
+    for (int k = 1; k < kCombineGroups; ++k) tot += red[k][tx];
+    T* yp = y + j * incy;
+    T v = alpha * tot;
+    if (beta != T(0)) v = __builtin_fma(beta, *yp, v);
+    *yp = v;
+}
+
+// y[k] = beta*y[k] (zeros when beta == 0, without reading y): the alpha == 0 case
+template <typename T>
+__global__ void __launch_bounds__(256) scale_y_kernel(int64_t n, T beta, T* __restrict__ y, int64_t incy)
+{
+    const int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (k < n) y[k * incy] = beta == T(0) ? T(0) : beta * y[k * incy];
+}
+
+// dense copy of a strided vector (trmv's snapshot of x)
+template <typename T>
+__global__ void __launch_bounds__(256) gather_kernel(int64_t n, const T* __restrict__ x, int64_t incx, T* __restrict__ dst)
+{
+    const int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (k < n) dst[k] = x[k * incx];
+}
+
+// ---------------------------------------------------------------------------------------------
+// launchers
+
+template <typename T, int VEC, int LPR, int R, int MODE, bool UNIT>
+void launch_rowdot_inst(mxb_handle_t h, const RowdotArgs<T>& a)
+{
+    constexpr int RB = kRowdotWaves * (kWave / LPR) * R;
+    const int64_t ntiles = ceil_div(a.M, RB);
+    const int64_t cap = kCUs * option(h, MXB_OPT_ROWDOT_BLOCKS_PER_CU);
+    const int64_t grid = ntiles < cap ? ntiles : cap;
+    const size_t lds = (size_t)a.xchunk * sizeof(T);
+    hipLaunchKernelGGL((rowdot_kernel<T, VEC, LPR, R, MODE, UNIT>), dim3((unsigned)grid), dim3(kRowdotThreads), lds, h->stream, a);
+}
+
+template <typename T, int VEC, int MODE, bool UNIT>
+void launch_rowdot_shape(mxb_handle_t h, const RowdotArgs<T>& a)
+{
+    // Narrow matrices: 16 lanes per row, four rows per wavefront side by side.  Few rows: one row
+    // per lane group so that the grid still fills the device.
+    const bool narrow = MODE == MODE_GENERAL && a.N <= 16 * 16 * VEC;
+    if (narrow) {
+        if (a.M >= (int64_t)kCUs * kRowdotWaves * 4 * 4) launch_rowdot_inst<T, VEC, 16, 4, MODE_GENERAL, false>(h, a);
+        else launch_rowdot_inst<T, VEC, 16, 1, MODE_GENERAL, false>(h, a);
+    } else {
+        if (a.M >= (int64_t)kCUs * kRowdotWaves * 4) launch_rowdot_inst<T, VEC, 64, 4, MODE, UNIT>(h, a);
+        else launch_rowdot_inst<T, VEC, 64, 1, MODE, UNIT>(h, a);
+    }
+}
+
+// mode: MODE_*, unit: trmv with unit diagonal.  Checks nothing; a.xchunk / a.x_contig filled here.
+template <typename T>
+int launch_rowdot(mxb_handle_t h, RowdotArgs<T> a, int mode, bool unit)
+{
+    constexpr int FV = Full<T>::vec;
+    const int64_t max_chunk = (int64_t)(64 * 1024 / sizeof(T));
+    int64_t xc = option(h, MXB_OPT_ROWDOT_XCHUNK);
+    const int64_t ncols = ceil_div(a.N, 256) * 256;
+    if (xc > ncols) xc = ncols;
+    if (xc > max_chunk) xc = max_chunk;
+    xc = ceil_div(xc, 256) * 256;
+    a.xchunk = (int)xc;
+    a.x_contig = a.incx == 1 && aligned16(a.x);
+    const bool vec = aligned16(a.A) && (a.lda % FV) == 0;
+#define MXB_ROWDOT(VEC_)                                                                                   \
+    switch (mode) {                                                                                        \
+        case MODE_GENERAL: launch_rowdot_shape<T, VEC_, MODE_GENERAL, false>(h, a); break;                  \
+        case MODE_UPPER:                                                                                   \
+            if (unit) launch_rowdot_shape<T, VEC_, MODE_UPPER, true>(h, a);                                 \
+            else launch_rowdot_shape<T, VEC_, MODE_UPPER, false>(h, a);                                     \
+            break;                                                                                         \
+        default:                                                                                           \
+            if (unit) launch_rowdot_shape<T, VEC_, MODE_LOWER, true>(h, a);                                 \
+            else launch_rowdot_shape<T, VEC_, MODE_LOWER, false>(h, a);                                     \
+    }
+    if (vec) { MXB_ROWDOT(FV) } else { MXB_ROWDOT(1) }
+#undef MXB_ROWDOT
+    return launch_status();
+}
+
+template <typename T, int VEC, int MODE, bool UNIT>
+void launch_colacc_inst(mxb_handle_t h, const ColaccArgs<T>& a, const ColaccPlan& pl)
+{
+    const dim3 grid((unsigned)pl.col_tiles, (unsigned)pl.nparts);
+    if (pl.wr == 4) hipLaunchKernelGGL((colacc_kernel<T, VEC, 4, MODE, UNIT>), grid, dim3(kColaccThreads), 0, h->stream, a);
+    else hipLaunchKernelGGL((colacc_kernel<T, VEC, 1, MODE, UNIT>), grid, dim3(kColaccThreads), 0, h->stream, a);
+}
+
+// ws / ws_bytes: workspace region this call may use for partials.
+template <typename T>
+int launch_colacc(mxb_handle_t h, ColaccArgs<T> a, int mode, bool unit, void* ws, size_t ws_bytes)
+{
+    constexpr int FV = Full<T>::vec;
+    const bool vec = aligned16(a.A) && (a.lda % FV) == 0 && (a.N % FV) == 0;
+    const ColaccPlan pl = colacc_plan(a.M, a.N, vec ? FV : 1, option(h, MXB_OPT_COLACC_TARGET_BLOCKS),
+                                      option(h, MXB_OPT_COLACC_MIN_ROWS));
+    a.rows_per_block = pl.rows_per_block;
+    a.partials = nullptr;
+    if (pl.nparts > 1) {
+        if (!ws || ws_bytes < (size_t)pl.nparts * (size_t)a.N * sizeof(T)) return MXB_ERR_WORKSPACE;
+        a.partials = static_cast<T*>(ws);
+    }
+#define MXB_COLACC(VEC_)                                                                                   \
+    switch (mode) {                                                                                        \
+        case MODE_GENERAL: launch_colacc_inst<T, VEC_, MODE_GENERAL, false>(h, a, pl); break;               \
+        case MODE_UPPER:                                                                                   \
+            if (unit) launch_colacc_inst<T, VEC_, MODE_UPPER, true>(h, a, pl);                              \
+            else launch_colacc_inst<T, VEC_, MODE_UPPER, false>(h, a, pl);                                  \
+            break;                                                                                         \
+        default:                                                                                           \
+            if (unit) launch_colacc_inst<T, VEC_, MODE_LOWER, true>(h, a, pl);                              \
+            else launch_colacc_inst<T, VEC_, MODE_LOWER, false>(h, a, pl);                                  \
+    }
+    if (vec) { MXB_COLACC(FV) } else { MXB_COLACC(1) }
+#undef MXB_COLACC
+    int st = launch_status();
+    if (st != MXB_OK || pl.nparts == 1) return st;
+    hipLaunchKernelGGL(colacc_combine_kernel<T>, dim3((unsigned)ceil_div(a.N, kWave)), dim3(kCombineGroups * kWave), 0,
+                       h->stream, pl.nparts, a.N, a.partials, a.alpha, a.beta, a.y, a.incy);
+    return launch_status();
+}
+
+inline bool layout_ok(int v) { return v == MXB_ROW_MAJOR || v == MXB_COL_MAJOR; }
+inline bool trans_ok(int v) { return v == MXB_NO_TRANS || v == MXB_TRANS; }
+inline bool uplo_ok(int v) { return v == MXB_UPPER || v == MXB_LOWER; }
+inline bool diag_ok(int v) { return v == MXB_NON_UNIT || v == MXB_UNIT; }
+
+template <typename T>
+int gemv(mxb_handle_t h, int layout, int trans, int64_t m, int64_t n, T alpha, const T* A, int64_t lda, const T* x,
+         int64_t incx, T beta, T* y, int64_t incy)
+{
+    if (!handle_ok(h)) return MXB_ERR_HANDLE;
+    if (!layout_ok(layout)) return -1;
+    if (!trans_ok(trans)) return -2;
+    if (m < 0) return -3;
+    if (n < 0) return -4;
+    const int64_t minor = layout == MXB_ROW_MAJOR ? n : m;
+    if (lda < (minor > 1 ? minor : 1)) return -7;
+    if (incx == 0) return -9;
+    if (incy == 0) return -12;
+    if (m == 0 || n == 0 || (alpha == T(0) && beta == T(1))) return MXB_OK;
+    if (!y) return -11;
+    // a column-major m x n matrix is the row-major n x m matrix of the transposed problem
+    const bool row_major = layout == MXB_ROW_MAJOR;
+    const int64_t rows = row_major ? m : n, cols = row_major ? n : m;
+    const bool no_trans = (trans == MXB_NO_TRANS) == row_major;
+    const int64_t lenx = no_trans ? cols : rows, leny = no_trans ? rows : cols;
+    T* y0 = vec_base(y, leny, incy);
+    if (alpha == T(0)) {
+        hipLaunchKernelGGL(scale_y_kernel<T>, dim3((unsigned)ceil_div(leny, 256)), dim3(256), 0, h->stream, leny, beta, y0, incy);
+        return launch_status();
+    }
+    if (!A) return -6;
+    if (!x) return -8;
+    const T* x0 = vec_base(x, lenx, incx);
+    if (no_trans) {
+        RowdotArgs<T> a{rows, cols, A, lda, x0, incx, y0, incy, alpha, beta, 0, 0};
+        return launch_rowdot(h, a, MODE_GENERAL, false);
+    }
+    ColaccArgs<T> a{rows, cols, A, lda, x0, incx, y0, incy, alpha, beta, nullptr, 0};
+    return launch_colacc(h, a, MODE_GENERAL, false, h->ws, h->ws_bytes);
+}
+
+template <typename T>
+int trmv(mxb_handle_t h, int layout, int uplo, int trans, int diag, int64_t n, const T* A, int64_t lda, T* x, int64_t incx)
+{
+    if (!handle_ok(h)) return MXB_ERR_HANDLE;
+    if (!layout_ok(layout)) return -1;
+    if (!uplo_ok(uplo)) return -2;
+    if (!trans_ok(trans)) return -3;
+    if (!diag_ok(diag)) return -4;
+    if (n < 0) return -5;
+    if (lda < (n > 1 ? n : 1)) return -7;
+    if (incx == 0) return -9;
+    if (n == 0) return MXB_OK;
+    if (!A) return -6;
+    if (!x) return -8;
+    // column-major: the same bytes are the row-major transpose, whose stored triangle is the other one
+    const bool row_major = layout == MXB_ROW_MAJOR;
+    const bool upper = (uplo == MXB_UPPER) == row_major;
+    const bool no_trans = (trans == MXB_NO_TRANS) == row_major;
+    const int mode = upper ? MODE_UPPER : MODE_LOWER;
+    const bool unit = diag == MXB_UNIT;
+
+    const size_t snap_bytes = align_up((size_t)n * sizeof(T), 256);
+    if (!h->ws || h->ws_bytes < snap_bytes) return MXB_ERR_WORKSPACE;
+    T* snap = static_cast<T*>(h->ws);
+    T* x0 = vec_base(x, n, incx);
+    hipLaunchKernelGGL(gather_kernel<T>, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, h->stream, n, x0, incx, snap);
+    int st = launch_status();
+    if (st != MXB_OK) return st;
+    if (no_trans) {
+        RowdotArgs<T> a{n, n, A, lda, snap, 1, x0, incx, T(1), T(0), 0, 0};
+        return launch_rowdot(h, a, mode, unit);
+    }
+    ColaccArgs<T> a{n, n, A, lda, snap, 1, x0, incx, T(1), T(0), nullptr, 0};
+    return launch_colacc(h, a, mode, unit, static_cast<char*>(h->ws) + snap_bytes, h->ws_bytes - snap_bytes);
+}
+
+}  // namespace
+}  // namespace mxb
+
+extern "C" {
+int mxb_sgemv(mxb_handle_t h, mxb_layout_t layout, mxb_trans_t trans, int64_t m, int64_t n, float alpha, const float* A,
+              int64_t lda, const float* x, int64_t incx, float beta, float* y, int64_t incy)
+{ return mxb::gemv<float>(h, layout, trans, m, n, alpha, A, lda, x, incx, beta, y, incy); }
+int mxb_dgemv(mxb_handle_t h, mxb_layout_t layout, mxb_trans_t trans, int64_t m, int64_t n, double alpha, const double* A,
+              int64_t lda, const double* x, int64_t incx, double beta, double* y, int64_t incy)
+{ return mxb::gemv<double>(h, layout, trans, m, n, alpha, A, lda, x, incx, beta, y, incy); }
+int mxb_strmv(mxb_handle_t h, mxb_layout_t layout, mxb_uplo_t uplo, mxb_trans_t trans, mxb_diag_t diag, int64_t n,
+              const float* A, int64_t lda, float* x, int64_t incx)
+{ return mxb::trmv<float>(h, layout, uplo, trans, diag, n, A, lda, x, incx); }
+int mxb_dtrmv(mxb_handle_t h, mxb_layout_t layout, mxb_uplo_t uplo, mxb_trans_t trans, mxb_diag_t diag, int64_t n,
+              const double* A, int64_t lda, double* x, int64_t incx)
+{ return mxb::trmv<double>(h, layout, uplo, trans, diag, n, A, lda, x, incx); }
+}

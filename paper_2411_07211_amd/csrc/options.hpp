@@ -1,0 +1,24 @@
+// Default launch geometry and per-handle overrides.
+#pragma once
+#include "common.hpp"
+
+namespace mxb {
+
+inline int64_t option_default(int o)
+{
+    switch (o) {
+        case MXB_OPT_L1_BLOCKS_PER_CU: return 16;
+        case MXB_OPT_REDUCE_BLOCKS: return 2048;
+        case MXB_OPT_ROWDOT_XCHUNK: return 16384;      // elements; capped to 64 KiB of LDS by the launcher
+        case MXB_OPT_ROWDOT_BLOCKS_PER_CU: return 2;
+        case MXB_OPT_COLACC_TARGET_BLOCKS: return 1024;
+        case MXB_OPT_COLACC_MIN_ROWS: return 128;
+        case MXB_OPT_SYMV_TILE_ROWS: return 128;
+        case MXB_OPT_GER_ROWS_PER_BLOCK: return 64;
+        default: return 0;
+    }
+}
+
+inline int64_t option(mxb_handle_t h, int o) { return h->opt[o] > 0 ? h->opt[o] : option_default(o); }
+
+}  // namespace mxb

@@ -1,0 +1,51 @@
+// Host-side launch plans shared by the level-2 launchers and by mxb_workspace_bytes.
+#pragma once
+#include "common.hpp"
+
+namespace mxb {
+
+// Column-accumulate kernels (transposed gemv / trmv on a row-major matrix): a block of 4
+// wavefronts covers `cols_per_block` columns and `rows_per_block` rows and produces one partial
+// vector; `nparts` partial vectors per column are combined by a second kernel (none if 1).
+struct ColaccPlan {
+    int wr;                  // wavefronts of a block that split the rows (1 or 4)
+    int64_t cols_per_block;
+    int64_t col_tiles;
+    int64_t rows_per_block;
+    int64_t nparts;
+};
+
+inline ColaccPlan colacc_plan(int64_t rows, int64_t cols, int vec, int64_t target_blocks, int64_t min_rows)
+{
+    ColaccPlan p;
+    p.wr = cols <= 2 * kWave * vec ? 4 : 1;
+    p.cols_per_block = (int64_t)(4 / p.wr) * kWave * vec;
+    p.col_tiles = ceil_div(cols > 0 ? cols : 1, p.cols_per_block);
+    const int64_t floor_rows = min_rows * p.wr;
+    int64_t parts = ceil_div(target_blocks, p.col_tiles);
+    const int64_t max_parts = ceil_div(rows > 0 ? rows : 1, floor_rows);
+    if (parts > max_parts) parts = max_parts;
+    if (parts < 1) parts = 1;
+    const int64_t quantum = 8 * p.wr;
+    p.rows_per_block = ceil_div(ceil_div(rows > 0 ? rows : 1, parts), quantum) * quantum;
+    p.nparts = ceil_div(rows > 0 ? rows : 1, p.rows_per_block);
+    return p;
+}
+
+// symv: 2-D tiles of tile_rows x (256*vec) over the stored triangle; every active tile yields a
+// partial row-sum vector (indexed by column tile) and a partial column-sum vector (by row tile).
+struct SymvPlan {
+    int64_t tile_rows, tile_cols, nrow_tiles, ncol_tiles;
+};
+
+inline SymvPlan symv_plan(int64_t n, int vec, int64_t tile_rows)
+{
+    SymvPlan p;
+    p.tile_rows = tile_rows < 8 ? 8 : (tile_rows > 256 ? 256 : tile_rows / 8 * 8);
+    p.tile_cols = 256 * (int64_t)vec;
+    p.nrow_tiles = ceil_div(n > 0 ? n : 1, p.tile_rows);
+    p.ncol_tiles = ceil_div(n > 0 ? n : 1, p.tile_cols);
+    return p;
+}
+
+}  // namespace mxb

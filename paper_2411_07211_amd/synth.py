@@ -13,6 +13,9 @@ Tensor ids by convention: A = 0, x = 1, y = 2, scalars = 3.
 """
 from __future__ import annotations
 
+import os
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 
 TENSOR_A, TENSOR_X, TENSOR_Y, TENSOR_SCALARS = 0, 1, 2, 3
@@ -20,19 +23,35 @@ TENSOR_A, TENSOR_X, TENSOR_Y, TENSOR_SCALARS = 0, 1, 2, 3
 _GOLDEN = np.uint64(0x9E3779B97F4A7C15)
 _M1 = np.uint64(0xBF58476D1CE4E5B9)
 _M2 = np.uint64(0x94D049BB133111EB)
-_CHUNK = 1 << 22
+_CHUNK = 1 << 20
+_WORKERS = min(8, os.cpu_count() or 1)
+
+
+def _for_chunks(n: int, fill) -> None:
+    """Calls fill(start, count) for every chunk of [0, n); chunks are independent (the generator
+    is counter-based), so large tensors are filled by a few threads."""
+    starts = range(0, n, _CHUNK)
+    if n <= 4 * _CHUNK:
+        for s in starts:
+            fill(s, min(_CHUNK, n - s))
+        return
+    with ThreadPoolExecutor(_WORKERS) as ex:
+        list(ex.map(lambda s: fill(s, min(_CHUNK, n - s)), starts))
 
 
 def _mix64(z: np.ndarray) -> np.ndarray:
-    z = z + _GOLDEN
-    z = (z ^ (z >> np.uint64(30))) * _M1
-    z = (z ^ (z >> np.uint64(27))) * _M2
-    return z ^ (z >> np.uint64(31))
+    """splitmix64 output function, in place on a fresh uint64 array."""
+    t = np.empty_like(z)
+    z += _GOLDEN
+    np.right_shift(z, np.uint64(30), out=t); z ^= t; z *= _M1
+    np.right_shift(z, np.uint64(27), out=t); z ^= t; z *= _M2
+    np.right_shift(z, np.uint64(31), out=t); z ^= t
+    return z
 
 
 def _stream_key(seed: int, tensor_id: int) -> np.uint64:
     with np.errstate(over="ignore"):
-        k = np.array([np.uint64(seed & 0xFFFFFFFFFFFFFFFF)], np.uint64) * _GOLDEN + np.uint64(tensor_id)
+        k = np.array([seed & 0xFFFFFFFFFFFFFFFF], np.uint64) * _GOLDEN + np.uint64(tensor_id)
         return _mix64(k)[0]
 
 
@@ -41,7 +60,8 @@ def raw_u64(seed: int, tensor_id: int, start: int, count: int) -> np.ndarray:
     key = _stream_key(seed, tensor_id)
     with np.errstate(over="ignore"):
         idx = np.arange(start, start + count, dtype=np.uint64)
-        return _mix64(idx + key)
+        idx += key
+        return _mix64(idx)
 
 
 def uniform(seed: int, tensor_id: int, n: int, dtype=np.float32) -> np.ndarray:
@@ -49,10 +69,12 @@ def uniform(seed: int, tensor_id: int, n: int, dtype=np.float32) -> np.ndarray:
     dtype = np.dtype(dtype)
     bits = 24 if dtype == np.float32 else 53
     out = np.empty(n, dtype)
-    for s in range(0, n, _CHUNK):
-        c = min(_CHUNK, n - s)
+
+    def fill(s, c):
         k = raw_u64(seed, tensor_id, s, c) >> np.uint64(64 - bits)
         out[s:s + c] = (k.astype(np.float64) * (2.0 / float(1 << bits)) - 1.0).astype(dtype)
+
+    _for_chunks(n, fill)
     return out
 
 
@@ -61,13 +83,15 @@ def normal(seed: int, tensor_id: int, n: int, std: float = 1.0, dtype=np.float64
     dtype = np.dtype(dtype)
     out = np.empty(n, dtype)
     two53 = float(1 << 53)
-    for s in range(0, n, _CHUNK):
-        c = min(_CHUNK, n - s)
+
+    def fill(s, c):
         r = raw_u64(seed, tensor_id, 2 * s, 2 * c) >> np.uint64(11)
         u1 = (r[0::2].astype(np.float64) + 1.0) / two53          # (0, 1]
         u2 = r[1::2].astype(np.float64) / two53                  # [0, 1)
         z = np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
         out[s:s + c] = (std * z).astype(dtype)
+
+    _for_chunks(n, fill)
     return out
 
 
@@ -77,10 +101,12 @@ def small_ints(seed: int, tensor_id: int, n: int, lo: int = -2, hi: int = 2,
     dtype = np.dtype(dtype)
     span = np.uint64(hi - lo + 1)
     out = np.empty(n, dtype)
-    for s in range(0, n, _CHUNK):
-        c = min(_CHUNK, n - s)
+
+    def fill(s, c):
         k = (raw_u64(seed, tensor_id, s, c) >> np.uint64(33)) % span
         out[s:s + c] = (k.astype(np.int64) + lo).astype(dtype)
+
+    _for_chunks(n, fill)
     return out
 
 

@@ -1,0 +1,146 @@
+"""Host-only checks of the C ABI: every declared symbol is exported, argument validation and
+quick returns work without a GPU (the library validates before touching the device)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2411_07211_amd import blas
+    return blas
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "mxblas.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mxb_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(B):
+    lib = ctypes.CDLL(B.LIB_PATH)
+    names = declared_symbols()
+    assert len(names) >= 27
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in mxblas.h but not exported"
+    for p in "sd":
+        for r in ("axpy", "scal", "dot", "asum", "nrm2", "gemv", "trmv", "symv", "ger"):
+            assert f"mxb_{p}{r}" in names
+
+
+def test_handle_lifecycle_and_options(B):
+    st, h = B.mxb_create()
+    assert st == 0 and h
+    assert B.mxb_set_stream(h, None) == 0
+    assert B.mxb_set_workspace(h, None, 0) == 0
+    assert B.mxb_set_workspace(h, 0x1001, 16) == -1          # not 256-byte aligned
+    assert B.mxb_get_option(h, B.OPT_REDUCE_BLOCKS) == 2048
+    assert B.mxb_set_option(h, B.OPT_REDUCE_BLOCKS, 7) == 0 and B.mxb_get_option(h, B.OPT_REDUCE_BLOCKS) == 7
+    assert B.mxb_set_option(h, B.OPT_REDUCE_BLOCKS, 0) == 0 and B.mxb_get_option(h, B.OPT_REDUCE_BLOCKS) == 2048
+    assert B.mxb_set_option(h, 99, 1) == -1
+    assert B.mxb_destroy(h) == 0
+    assert B.mxb_saxpy(None, 1, 1.0, 16, 1, 16, 1) == B.ERR_HANDLE
+
+
+def test_argument_errors_name_the_argument(B):
+    st, h = B.mxb_create()
+    P = 0x10000   # never dereferenced: every call below fails validation or returns early
+    try:
+        for p in "sd":
+            f = lambda r: B.routine(p, r)
+            assert f("axpy")(h, -1, 1.0, P, 1, P, 1) == -1
+            assert f("axpy")(h, 4, 1.0, None, 1, P, 1) == -3
+            assert f("axpy")(h, 4, 1.0, P, 0, P, 1) == -4
+            assert f("axpy")(h, 4, 1.0, P, 1, None, 1) == -5
+            assert f("axpy")(h, 4, 1.0, P, 1, P, 0) == -6
+            assert f("axpy")(h, 0, 1.0, None, 0, None, 0) == 0        # quick returns
+            assert f("axpy")(h, 4, 0.0, None, 0, None, 0) == 0
+            assert f("scal")(h, -2, 1.0, P, 1) == -1
+            assert f("scal")(h, 4, 1.0, None, 1) == -3
+            assert f("scal")(h, 4, 1.0, None, 0) == 0
+            assert f("dot")(h, -1, P, 1, P, 1, P) == -1
+            assert f("dot")(h, 4, None, 1, P, 1, P) == -2
+            assert f("dot")(h, 4, P, 0, P, 1, P) == -3
+            assert f("dot")(h, 4, P, 1, None, 1, P) == -4
+            assert f("dot")(h, 4, P, 1, P, 0, P) == -5
+            assert f("dot")(h, 4, P, 1, P, 1, None) == -6
+            for r in ("asum", "nrm2"):
+                assert f(r)(h, -1, P, 1, P) == -1
+                assert f(r)(h, 4, None, 1, P) == -2
+                assert f(r)(h, 4, P, 1, None) == -4
+            g = f("gemv")
+            assert g(h, 7, B.NO_TRANS, 4, 4, 1.0, P, 4, P, 1, 0.0, P, 1) == -1
+            assert g(h, B.ROW_MAJOR, 7, 4, 4, 1.0, P, 4, P, 1, 0.0, P, 1) == -2
+            assert g(h, B.ROW_MAJOR, B.NO_TRANS, -1, 4, 1.0, P, 4, P, 1, 0.0, P, 1) == -3
+            assert g(h, B.ROW_MAJOR, B.NO_TRANS, 4, -1, 1.0, P, 4, P, 1, 0.0, P, 1) == -4
+            assert g(h, B.ROW_MAJOR, B.NO_TRANS, 4, 5, 1.0, None, 5, P, 1, 0.0, P, 1) == -6
+            assert g(h, B.ROW_MAJOR, B.NO_TRANS, 4, 5, 1.0, P, 4, P, 1, 0.0, P, 1) == -7   # lda < n
+            assert g(h, B.COL_MAJOR, B.NO_TRANS, 4, 5, 1.0, P, 4, P, 1, 0.0, P, 1) != -7   # lda >= m is fine
+            assert g(h, B.COL_MAJOR, B.NO_TRANS, 5, 4, 1.0, P, 4, P, 1, 0.0, P, 1) == -7
+            assert g(h, B.ROW_MAJOR, B.NO_TRANS, 4, 4, 1.0, P, 4, None, 1, 0.0, P, 1) == -8
+            assert g(h, B.ROW_MAJOR, B.NO_TRANS, 4, 4, 1.0, P, 4, P, 0, 0.0, P, 1) == -9
+            assert g(h, B.ROW_MAJOR, B.NO_TRANS, 4, 4, 1.0, P, 4, P, 1, 0.0, None, 1) == -11
+            assert g(h, B.ROW_MAJOR, B.NO_TRANS, 4, 4, 1.0, P, 4, P, 1, 0.0, P, 0) == -12
+            assert g(h, B.ROW_MAJOR, B.NO_TRANS, 0, 4, 1.0, None, 4, None, 1, 0.0, None, 1) == 0
+            assert g(h, B.ROW_MAJOR, B.NO_TRANS, 4, 0, 1.0, None, 1, None, 1, 0.0, None, 1) == 0
+            assert g(h, B.ROW_MAJOR, B.NO_TRANS, 4, 4, 0.0, None, 4, None, 1, 1.0, None, 1) == 0
+            # transposed gemv of a tall matrix needs partials: no workspace -> error, no launch
+            assert g(h, B.ROW_MAJOR, B.TRANS, 4096, 4096, 1.0, P, 4096, P, 1, 0.0, P, 1) == B.ERR_WORKSPACE
+            t = f("trmv")
+            ok = (B.ROW_MAJOR, B.UPPER, B.NO_TRANS, B.NON_UNIT)
+            assert t(h, 0, ok[1], ok[2], ok[3], 4, P, 4, P, 1) == -1
+            assert t(h, ok[0], 0, ok[2], ok[3], 4, P, 4, P, 1) == -2
+            assert t(h, ok[0], ok[1], 0, ok[3], 4, P, 4, P, 1) == -3
+            assert t(h, ok[0], ok[1], ok[2], 0, 4, P, 4, P, 1) == -4
+            assert t(h, *ok, -1, P, 4, P, 1) == -5
+            assert t(h, *ok, 4, None, 4, P, 1) == -6
+            assert t(h, *ok, 4, P, 3, P, 1) == -7
+            assert t(h, *ok, 4, P, 4, None, 1) == -8
+            assert t(h, *ok, 4, P, 4, P, 0) == -9
+            assert t(h, *ok, 0, None, 1, None, 1) == 0
+            assert t(h, *ok, 4, P, 4, P, 1) == B.ERR_WORKSPACE
+            s = f("symv")
+            assert s(h, 0, B.LOWER, 4, 1.0, P, 4, P, 1, 0.0, P, 1) == -1
+            assert s(h, B.ROW_MAJOR, 0, 4, 1.0, P, 4, P, 1, 0.0, P, 1) == -2
+            assert s(h, B.ROW_MAJOR, B.LOWER, -1, 1.0, P, 4, P, 1, 0.0, P, 1) == -3
+            assert s(h, B.ROW_MAJOR, B.LOWER, 4, 1.0, None, 4, P, 1, 0.0, P, 1) == -5
+            assert s(h, B.ROW_MAJOR, B.LOWER, 4, 1.0, P, 3, P, 1, 0.0, P, 1) == -6
+            assert s(h, B.ROW_MAJOR, B.LOWER, 4, 1.0, P, 4, None, 1, 0.0, P, 1) == -7
+            assert s(h, B.ROW_MAJOR, B.LOWER, 4, 1.0, P, 4, P, 0, 0.0, P, 1) == -8
+            assert s(h, B.ROW_MAJOR, B.LOWER, 4, 1.0, P, 4, P, 1, 0.0, None, 1) == -10
+            assert s(h, B.ROW_MAJOR, B.LOWER, 4, 1.0, P, 4, P, 1, 0.0, P, 0) == -11
+            assert s(h, B.ROW_MAJOR, B.LOWER, 0, 1.0, None, 1, None, 1, 0.0, None, 1) == 0
+            assert s(h, B.ROW_MAJOR, B.LOWER, 4, 0.0, None, 4, None, 1, 1.0, None, 1) == 0
+            assert s(h, B.ROW_MAJOR, B.LOWER, 4, 1.0, P, 4, P, 1, 0.0, P, 1) == B.ERR_WORKSPACE
+            r = f("ger")
+            assert r(h, 0, 4, 4, 1.0, P, 1, P, 1, P, 4) == -1
+            assert r(h, B.ROW_MAJOR, -1, 4, 1.0, P, 1, P, 1, P, 4) == -2
+            assert r(h, B.ROW_MAJOR, 4, -1, 1.0, P, 1, P, 1, P, 4) == -3
+            assert r(h, B.ROW_MAJOR, 4, 4, 1.0, None, 1, P, 1, P, 4) == -5
+            assert r(h, B.ROW_MAJOR, 4, 4, 1.0, P, 0, P, 1, P, 4) == -6
+            assert r(h, B.ROW_MAJOR, 4, 4, 1.0, P, 1, None, 1, P, 4) == -7
+            assert r(h, B.ROW_MAJOR, 4, 4, 1.0, P, 1, P, 0, P, 4) == -8
+            assert r(h, B.ROW_MAJOR, 4, 4, 1.0, P, 1, P, 1, None, 4) == -9
+            assert r(h, B.ROW_MAJOR, 4, 5, 1.0, P, 1, P, 1, P, 4) == -10
+            assert r(h, B.ROW_MAJOR, 4, 4, 0.0, None, 1, None, 1, None, 4) == 0
+            assert r(h, B.ROW_MAJOR, 0, 4, 1.0, None, 1, None, 1, None, 4) == 0
+    finally:
+        B.mxb_destroy(h)
+
+
+def test_workspace_bound(B):
+    assert B.mxb_workspace_bytes(B.AXPY, 4, 0, 1 << 28) == 0
+    assert B.mxb_workspace_bytes(B.GER, 8, 100, 100) == 0
+    assert B.mxb_workspace_bytes(B.DOT, 4, 0, 1 << 28) >= 2048 * 8
+    assert B.mxb_workspace_bytes(B.NRM2, 8, 0, 1 << 28) >= 2048 * 3 * 8
+    g = B.mxb_workspace_bytes(B.GEMV, 4, 16384, 16384)
+    assert 0 < g <= 0.02 * 16384 * 16384 * 4        # partials stay under 2 % of the matrix
+    assert B.mxb_workspace_bytes(B.GEMV, 8, 16384, 16384) <= 0.02 * 16384 * 16384 * 8
+    assert B.mxb_workspace_bytes(B.GEMV, 4, 1 << 20, 256) == B.mxb_workspace_bytes(B.GEMV, 4, 256, 1 << 20)
+    assert B.mxb_workspace_bytes(B.TRMV, 4, 0, 16384) >= 16384 * 4
+    assert 0 < B.mxb_workspace_bytes(B.SYMV, 4, 0, 16384) <= 0.03 * 16384 * 16384 * 4
+    assert B.mxb_workspace_bytes(B.GEMV, 3, 4, 4) == 0 and B.mxb_workspace_bytes(B.GEMV, 4, -1, 4) == 0

@@ -1,0 +1,177 @@
+"""GPU parity of the level-1 kernels against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+
+import oracle as O
+from paper_2411_07211_amd import synth
+from parity import bits_equal, check_close, prefix_of, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+DT = [np.float32, np.float64]
+SIZES = [1, 2, 3, 4, 5, 63, 64, 65, 255, 256, 257, 1000, 4097, 100003, (1 << 20) + 7]
+INCS = [(1, 1), (2, 3), (-1, 1), (1, -2), (-3, -2)]
+
+
+def dev_scalar(dt):
+    import torch
+    return torch.full((1,), float("nan"), dtype=torch.float32 if dt == np.float32 else torch.float64, device="cuda")
+
+
+def run_axpy(blas, ctx, dt, n, alpha, xb, incx, yb, incy, xoff=0, yoff=0):
+    """xb, yb host buffers; returns the GPU's y buffer."""
+    dx, dy = to_dev(xb), to_dev(yb)
+    st = blas.routine(prefix_of(dt), "axpy")(ctx.h, n, float(alpha), dx[xoff:], incx, dy[yoff:], incy)
+    assert st == 0
+    return to_host(dy)
+
+
+@pytest.mark.parametrize("dt", DT)
+@pytest.mark.parametrize("incx,incy", INCS)
+def test_axpy_scal(blas, ctx, dt, incx, incy):
+    for n in SIZES:
+        xd, yd = synth.uniform(1, 1, n, dt), synth.uniform(1, 2, n, dt)
+        xb, yb = synth.strided(xd, incx), synth.strided(yd, incy)
+        ref = yb.copy()
+        D = O.axpy(n, dt(-0.75), xb, incx, ref, incy, want_D=True)
+        got = run_axpy(blas, ctx, dt, n, -0.75, xb, incx, yb, incy)
+        check_close(synth.gather(got, n, incy), synth.gather(ref, n, incy), D, 1, f"axpy n={n}")
+        gaps = np.ones(got.size, bool); gaps[::abs(incy)] = False
+        assert np.isnan(got[gaps]).all(), "axpy wrote between the strides"
+        if incx > 0:
+            ref = xb.copy(); D = O.scal(n, dt(1.25), ref, incx, want_D=True)
+            dx = to_dev(xb)
+            assert blas.routine(prefix_of(dt), "scal")(ctx.h, n, 1.25, dx, incx) == 0
+            got = to_host(dx)
+            # scaling by 1.25 is a single rounding on both sides: bit-exact
+            assert bits_equal(synth.gather(got, n, incx), synth.gather(ref, n, incx)), f"scal n={n}"
+            gaps = np.ones(got.size, bool); gaps[::incx] = False
+            assert np.isnan(got[gaps]).all()
+
+
+@pytest.mark.parametrize("dt", DT)
+def test_axpy_scal_misaligned_and_noop(blas, ctx, dt):
+    n = 5001
+    x, y = synth.uniform(2, 1, n + 3, dt), synth.uniform(2, 2, n + 3, dt)
+    for xo, yo in ((1, 0), (0, 1), (3, 1)):
+        ref = y.copy(); O.axpy(n, dt(0.5), x[xo:], 1, ref[yo:], 1)
+        got = run_axpy(blas, ctx, dt, n, 0.5, x, 1, y, 1, xo, yo)
+        check_close(got[yo:yo + n], ref[yo:yo + n], np.abs(0.5 * x[xo:xo + n]) + np.abs(y[yo:yo + n]), 1, "axpy misaligned")
+        assert bits_equal(got[:yo], y[:yo]) and bits_equal(got[yo + n:], y[yo + n:])
+        dx = to_dev(x); ref = x.copy(); O.scal(n, dt(-3), ref[xo:], 1)
+        assert blas.routine(prefix_of(dt), "scal")(ctx.h, n, -3.0, dx[xo:], 1) == 0
+        assert bits_equal(to_host(dx), ref)
+    # alpha = 0 / n = 0 / incx <= 0: nothing is touched (x may hold NaN)
+    got = run_axpy(blas, ctx, dt, n, 0.0, np.full(n, np.nan, dt), 1, y, 1)
+    assert bits_equal(got, y)
+    got = run_axpy(blas, ctx, dt, 0, 1.0, x, 1, y, 1)
+    assert bits_equal(got, y)
+    dx = to_dev(x)
+    assert blas.routine(prefix_of(dt), "scal")(ctx.h, n, 2.0, dx, 0) == 0
+    assert blas.routine(prefix_of(dt), "scal")(ctx.h, n, 2.0, dx, -1) == 0
+    assert bits_equal(to_host(dx), x)
+    # scal always multiplies: alpha = 0 turns NaN into NaN, everything else into 0
+    z = x.copy(); z[7] = np.nan; dz = to_dev(z)
+    assert blas.routine(prefix_of(dt), "scal")(ctx.h, n, 0.0, dz, 1) == 0
+    out = to_host(dz)
+    assert np.isnan(out[7]) and np.count_nonzero(out[:n][np.arange(n) != 7]) == 0
+
+
+@pytest.mark.parametrize("dt", DT)
+def test_axpy_integers_bit_exact(blas, ctx, dt):
+    n = (1 << 18) + 13
+    x, y = synth.small_ints(3, 1, n, -50, 50, dt), synth.small_ints(3, 2, n, -50, 50, dt)
+    ref = y.copy(); O.axpy(n, dt(3), x, 1, ref, 1)
+    got = run_axpy(blas, ctx, dt, n, 3.0, x, 1, y, 1)
+    assert bits_equal(got, ref)
+    back = run_axpy(blas, ctx, dt, n, -3.0, x, 1, got, 1)
+    assert bits_equal(back, y)
+
+
+def run_reduce(blas, ctx, dt, name, n, xb, incx, yb=None, incy=0, xoff=0, yoff=0):
+    r = dev_scalar(dt)
+    dx = to_dev(xb)
+    f = blas.routine(prefix_of(dt), name)
+    if name == "dot":
+        dy = to_dev(yb)
+        st = f(ctx.h, n, dx[xoff:], incx, dy[yoff:], incy, r)
+    else:
+        st = f(ctx.h, n, dx[xoff:], incx, r)
+    assert st == 0
+    return to_host(r)[0]
+
+
+@pytest.mark.parametrize("dt", DT)
+@pytest.mark.parametrize("incx,incy", INCS)
+def test_reductions(blas, ctx, dt, incx, incy):
+    for n in SIZES:
+        xd, yd = synth.uniform(4, 1, n, dt), synth.uniform(4, 2, n, dt)
+        xb, yb = synth.strided(xd, incx), synth.strided(yd, incy)
+        ref, D = O.dot(n, xb, incx, yb, incy, want_D=True)
+        got = run_reduce(blas, ctx, dt, "dot", n, xb, incx, yb, incy)
+        check_close([got], [ref], [D], n, f"dot n={n}")
+        for name in ("asum", "nrm2"):
+            ref, D = getattr(O, name)(n, xb, incx, want_D=True)
+            got = run_reduce(blas, ctx, dt, name, n, xb, incx)
+            if incx > 0:
+                check_close([got], [ref], [D], n, f"{name} n={n}")
+            else:
+                assert got == 0 and ref == 0
+
+
+@pytest.mark.parametrize("dt", DT)
+def test_reductions_edge_cases(blas, ctx, dt):
+    x = synth.uniform(5, 1, 1000, dt)
+    for name in ("asum", "nrm2"):
+        assert run_reduce(blas, ctx, dt, name, 0, x, 1) == 0
+        assert run_reduce(blas, ctx, dt, name, 10, x, 0) == 0
+    assert run_reduce(blas, ctx, dt, "dot", 0, x, 1, x, 1) == 0
+    for xo, yo in ((1, 0), (0, 3), (1, 1)):          # misaligned bases
+        n = 990
+        ref, D = O.dot(n, x[xo:], 1, x[yo:], 1, want_D=True)
+        check_close([run_reduce(blas, ctx, dt, "dot", n, x, 1, x, 1, xo, yo)], [ref], [D], n, "dot misaligned")
+        ref, D = O.asum(n, x[xo:], 1, want_D=True)
+        check_close([run_reduce(blas, ctx, dt, "asum", n, x, 1, xoff=xo)], [ref], [D], n, "asum misaligned")
+    # nrm2 range safety
+    big = np.full(64, np.finfo(dt).max / 16, dt)
+    assert run_reduce(blas, ctx, dt, "nrm2", 64, big, 1) == O.nrm2(64, big, 1) == np.finfo(dt).max / 2
+    tiny = np.full(64, np.finfo(dt).tiny * 4, dt)
+    assert run_reduce(blas, ctx, dt, "nrm2", 64, tiny, 1) == O.nrm2(64, tiny, 1)
+    if dt == np.float64:
+        mixed = np.array([1e200, 3.0, 1e-200, 4e200], dt)
+        ref, D = O.nrm2(4, mixed, 1, want_D=True)
+        check_close([run_reduce(blas, ctx, dt, "nrm2", 4, mixed, 1)], [ref], [D], 4, "dnrm2 mixed range")
+
+
+@pytest.mark.parametrize("dt", DT)
+def test_reductions_integers_bit_exact(blas, ctx, dt):
+    n = (1 << 20) + 5         # n * max|term| = 2^20 * 4 < 2^24: every partial sum is exact in fp32
+    x, y = synth.small_ints(6, 1, n, -2, 2, dt), synth.small_ints(6, 2, n, -2, 2, dt)
+    assert run_reduce(blas, ctx, dt, "dot", n, x, 1, y, 1) == O.dot(n, x, 1, y, 1)
+    assert run_reduce(blas, ctx, dt, "asum", n, x, 1) == O.asum(n, x, 1)
+    ones = np.ones(n, dt)
+    assert run_reduce(blas, ctx, dt, "dot", n, ones, 1, ones, 1) == n
+    k = 4 ** 8
+    v = np.concatenate([np.full(k, 3, dt), np.full(k, 4, dt)])
+    assert run_reduce(blas, ctx, dt, "nrm2", 2 * k, v, 1) == 5 * 2 ** 8
+    # strided integers too
+    xb, yb = synth.strided(x[:100001], 2), synth.strided(y[:100001], 3)
+    assert run_reduce(blas, ctx, dt, "dot", 100001, xb, 2, yb, 3) == O.dot(100001, xb, 2, yb, 3)
+
+
+@pytest.mark.parametrize("dt", DT)
+def test_reductions_deterministic_and_grid_invariant(blas, ctx, dt):
+    n = (1 << 21) + 3
+    x, y = synth.uniform(7, 1, n, dt), synth.uniform(7, 2, n, dt)
+    a = run_reduce(blas, ctx, dt, "dot", n, x, 1, y, 1)
+    b = run_reduce(blas, ctx, dt, "dot", n, x, 1, y, 1)
+    assert a.tobytes() == b.tobytes()
+    ref, D = O.dot(n, x, 1, y, 1, want_D=True)
+    try:
+        for blocks in (1, 3, 64, 2048):
+            ctx.set_option(blas.OPT_REDUCE_BLOCKS, blocks)
+            check_close([run_reduce(blas, ctx, dt, "dot", n, x, 1, y, 1)], [ref], [D], n, f"dot blocks={blocks}")
+            r2, D2 = O.nrm2(n, x, 1, want_D=True)
+            check_close([run_reduce(blas, ctx, dt, "nrm2", n, x, 1)], [r2], [D2], n, f"nrm2 blocks={blocks}")
+    finally:
+        ctx.set_option(blas.OPT_REDUCE_BLOCKS, 0)

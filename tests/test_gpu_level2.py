@@ -1,0 +1,254 @@
+"""GPU parity of gemv, trmv, symv and ger against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+
+import oracle as O
+from paper_2411_07211_amd import synth
+from parity import bits_equal, check_close, prefix_of, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+DT = [np.float32, np.float64]
+
+
+def matrix_buffer(A, layout, pad, fill=np.nan):
+    """Host buffer (1-D) holding the logical matrix A in the given layout with lda = minor + pad;
+    padding holds NaN canaries."""
+    m, n = A.shape
+    if layout == O.ROW_MAJOR:
+        lda = max(n + pad, 1); buf = np.full((m, lda), fill, A.dtype); buf[:, :n] = A
+    else:
+        lda = max(m + pad, 1); buf = np.full((n, lda), fill, A.dtype); buf[:, :m] = A.T
+    return buf.ravel(), lda
+
+
+def logical(buf, layout, m, n, lda):
+    v = buf.reshape(-1, lda)
+    return v[:m, :n] if layout == O.ROW_MAJOR else v[:n, :m].T
+
+
+GEMV_SHAPES = [(1, 1), (3, 5), (8, 8), (7, 2), (64, 64), (65, 257), (1000, 40), (40, 1000), (130, 1024),
+               (257, 1030), (1024, 1024), (300, 4097), (2049, 513), (5000, 256), (17, 20000), (9000, 131)]
+
+
+def gemv_case(blas, ctx, dt, layout, trans, m, n, alpha, beta, pad, incx, incy, seed=8, ints=False, xchunk=None):
+    gen = (lambda t, k: synth.small_ints(seed, t, k, -2, 2, dt)) if ints else (lambda t, k: synth.uniform(seed, t, k, dt))
+    A = gen(0, m * n).reshape(m, n)
+    lenx, leny = (n, m) if trans == O.NO_TRANS else (m, n)
+    x, y = gen(1, lenx), gen(2, leny)
+    if beta == 0:
+        y = np.full(leny, np.nan, dt)          # must be overwritten, never read
+    Ab, lda = matrix_buffer(A, layout, pad)
+    xb, yb = synth.strided(x, incx), synth.strided(y, incy)
+    ref = yb.copy()
+    D = O.gemv(layout, trans, m, n, dt(alpha), Ab, lda, xb, incx, dt(beta), ref, incy, want_D=True)
+    dA, dx, dy = to_dev(Ab), to_dev(xb), to_dev(yb)
+    st = blas.routine(prefix_of(dt), "gemv")(ctx.h, layout, trans, m, n, float(alpha), dA, lda, dx, incx, float(beta), dy, incy)
+    assert st == 0, f"status {st}"
+    got = to_host(dy)
+    what = f"gemv {prefix_of(dt)} layout={layout} trans={trans} {m}x{n} pad={pad} a={alpha} b={beta} inc=({incx},{incy})"
+    g, r = synth.gather(got, leny, incy), synth.gather(ref, leny, incy)
+    if ints:
+        assert bits_equal(g, r), what
+    else:
+        check_close(g, r, D, lenx, what)
+    gaps = np.ones(got.size, bool); gaps[::abs(incy)] = False
+    assert np.isnan(got[gaps]).all(), what + ": wrote between the strides"
+
+
+@pytest.mark.parametrize("dt", DT)
+@pytest.mark.parametrize("trans", [O.NO_TRANS, O.TRANS])
+def test_gemv_shapes(blas, ctx, dt, trans):
+    for (m, n) in GEMV_SHAPES:
+        for pad in (0, 3, 4):
+            gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, 1.5, 0.5, pad, 1, 1)
+
+
+@pytest.mark.parametrize("dt", DT)
+@pytest.mark.parametrize("layout", [O.ROW_MAJOR, O.COL_MAJOR])
+@pytest.mark.parametrize("trans", [O.NO_TRANS, O.TRANS])
+def test_gemv_scalars_increments_layouts(blas, ctx, dt, layout, trans):
+    for (m, n) in [(5, 3), (129, 260), (1030, 515), (4100, 300)]:
+        for alpha, beta in [(1, 0), (1, 1), (-1, 0.5), (2, -1), (0, 0), (0, 0.5)]:
+            gemv_case(blas, ctx, dt, layout, trans, m, n, alpha, beta, 4, 1, 1)
+        for incx, incy in [(2, 3), (-1, 1), (1, -2), (-3, -2)]:
+            gemv_case(blas, ctx, dt, layout, trans, m, n, 1.5, 0.5, 1, incx, incy)
+
+
+@pytest.mark.parametrize("dt", DT)
+@pytest.mark.parametrize("trans", [O.NO_TRANS, O.TRANS])
+def test_gemv_integers_bit_exact(blas, ctx, dt, trans):
+    for (m, n) in [(8, 8), (257, 1030), (2049, 513), (4096, 4096)]:
+        gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, 3, -2, 0, 1, 1, ints=True)
+        gemv_case(blas, ctx, dt, O.COL_MAJOR, trans, m, n, 2, 0.5, 4, 1, 1, ints=True)
+
+
+@pytest.mark.parametrize("dt", DT)
+def test_gemv_alpha_zero_reads_nothing_and_identity(blas, ctx, dt):
+    m, n = 300, 200
+    A = np.full(m * n, np.nan, dt); x = np.full(n, np.nan, dt); y = synth.uniform(9, 2, m, dt)
+    dA, dx, dy = to_dev(A), to_dev(x), to_dev(y)
+    f = blas.routine(prefix_of(dt), "gemv")
+    assert f(ctx.h, O.ROW_MAJOR, O.NO_TRANS, m, n, 0.0, dA, n, dx, 1, 0.5, dy, 1) == 0
+    assert bits_equal(to_host(dy), dt(0.5) * y)
+    assert f(ctx.h, O.ROW_MAJOR, O.NO_TRANS, m, n, 0.0, dA, n, dx, 1, 1.0, dy, 1) == 0     # quick return
+    assert bits_equal(to_host(dy), dt(0.5) * y)
+    k = 1000
+    I = np.eye(k, dtype=dt); xv = synth.uniform(9, 1, k, dt)
+    for trans in (O.NO_TRANS, O.TRANS):
+        dy = to_dev(np.full(k, np.nan, dt))
+        assert f(ctx.h, O.ROW_MAJOR, trans, k, k, 1.0, to_dev(I.ravel()), k, to_dev(xv), 1, 0.0, dy, 1) == 0
+        assert bits_equal(to_host(dy), xv)              # identity returns x, bit for bit
+
+
+@pytest.mark.parametrize("dt", DT)
+def test_gemv_deterministic_and_geometry_invariant(blas, ctx, dt):
+    m, n = 3000, 2500
+    A = synth.uniform(10, 0, m * n, dt); Ad = to_dev(A)
+    f = blas.routine(prefix_of(dt), "gemv")
+    try:
+        for trans, lenx, leny in ((O.NO_TRANS, n, m), (O.TRANS, m, n)):
+            x, y = synth.uniform(10, 1, lenx, dt), synth.uniform(10, 2, leny, dt)
+            ref = y.copy(); D = O.gemv(O.ROW_MAJOR, trans, m, n, dt(1.5), A, n, x, 1, dt(0.5), ref, 1, want_D=True)
+            outs = []
+            for opts in ({}, {}, {blas.OPT_ROWDOT_XCHUNK: 256, blas.OPT_COLACC_TARGET_BLOCKS: 64},
+                         {blas.OPT_ROWDOT_XCHUNK: 1024, blas.OPT_ROWDOT_BLOCKS_PER_CU: 1, blas.OPT_COLACC_TARGET_BLOCKS: 4096,
+                          blas.OPT_COLACC_MIN_ROWS: 8}):
+                for o in range(8):
+                    ctx.set_option(o, 0)
+                for o, v in opts.items():
+                    ctx.set_option(o, v)
+                dy = to_dev(y)
+                assert f(ctx.h, O.ROW_MAJOR, trans, m, n, 1.5, Ad, n, to_dev(x), 1, 0.5, dy, 1) == 0
+                outs.append(to_host(dy))
+                check_close(outs[-1], ref, D, lenx, f"gemv trans={trans} opts={opts}")
+            assert outs[0].tobytes() == outs[1].tobytes(), "same launch geometry must give the same bits"
+    finally:
+        for o in range(8):
+            ctx.set_option(o, 0)
+
+
+# ----------------------------------------------------------------------------- trmv
+def trmv_case(blas, ctx, dt, layout, uplo, trans, diag, n, pad, incx, ints=False, seed=11):
+    gen = (lambda t, k: synth.small_ints(seed, t, k, -2, 2, dt)) if ints else (lambda t, k: synth.uniform(seed, t, k, dt))
+    A = gen(0, n * n).reshape(n, n).copy()
+    outside = np.tril(np.ones((n, n), bool), -1) if uplo == O.UPPER else np.triu(np.ones((n, n), bool), 1)
+    A[outside] = np.nan                                   # the opposite triangle must never be used
+    if diag == O.UNIT:
+        np.fill_diagonal(A, np.nan)                       # nor the diagonal
+    x = gen(1, n)
+    Ab, lda = matrix_buffer(A, layout, pad)
+    xb = synth.strided(x, incx)
+    ref = xb.copy()
+    D = O.trmv(layout, uplo, trans, diag, n, Ab, lda, ref, incx, want_D=True)
+    dx = to_dev(xb)
+    st = blas.routine(prefix_of(dt), "trmv")(ctx.h, layout, uplo, trans, diag, n, to_dev(Ab), lda, dx, incx)
+    assert st == 0, f"status {st}"
+    got = to_host(dx)
+    what = f"trmv {prefix_of(dt)} layout={layout} uplo={uplo} trans={trans} diag={diag} n={n} pad={pad} incx={incx}"
+    g, r = synth.gather(got, n, incx), synth.gather(ref, n, incx)
+    if ints:
+        assert bits_equal(g, r), what
+    else:
+        check_close(g, r, D, n, what)
+    gaps = np.ones(got.size, bool); gaps[::abs(incx)] = False
+    assert np.isnan(got[gaps]).all(), what
+
+
+@pytest.mark.parametrize("dt", DT)
+@pytest.mark.parametrize("layout", [O.ROW_MAJOR, O.COL_MAJOR])
+@pytest.mark.parametrize("uplo", [O.UPPER, O.LOWER])
+@pytest.mark.parametrize("trans", [O.NO_TRANS, O.TRANS])
+@pytest.mark.parametrize("diag", [O.NON_UNIT, O.UNIT])
+def test_trmv(blas, ctx, dt, layout, uplo, trans, diag):
+    for n in (1, 2, 3, 5, 17, 64, 65, 130, 257, 1000, 2310):
+        trmv_case(blas, ctx, dt, layout, uplo, trans, diag, n, 0 if n % 2 else 4, 1)
+    trmv_case(blas, ctx, dt, layout, uplo, trans, diag, 515, 1, 2)
+    trmv_case(blas, ctx, dt, layout, uplo, trans, diag, 515, 0, -1)
+    trmv_case(blas, ctx, dt, layout, uplo, trans, diag, 1536, 0, 1, ints=True)
+
+
+# ----------------------------------------------------------------------------- symv
+def symv_case(blas, ctx, dt, layout, uplo, n, alpha, beta, pad, incx, incy, ints=False, seed=12):
+    gen = (lambda t, k: synth.small_ints(seed, t, k, -2, 2, dt)) if ints else (lambda t, k: synth.uniform(seed, t, k, dt))
+    A = gen(0, n * n).reshape(n, n).copy()
+    outside = np.tril(np.ones((n, n), bool), -1) if uplo == O.UPPER else np.triu(np.ones((n, n), bool), 1)
+    A[outside] = np.nan
+    x, y = gen(1, n), gen(2, n)
+    if beta == 0:
+        y = np.full(n, np.nan, dt)
+    Ab, lda = matrix_buffer(A, layout, pad)
+    xb, yb = synth.strided(x, incx), synth.strided(y, incy)
+    ref = yb.copy()
+    D = O.symv(layout, uplo, n, dt(alpha), Ab, lda, xb, incx, dt(beta), ref, incy, want_D=True)
+    dy = to_dev(yb)
+    st = blas.routine(prefix_of(dt), "symv")(ctx.h, layout, uplo, n, float(alpha), to_dev(Ab), lda, to_dev(xb), incx, float(beta), dy, incy)
+    assert st == 0, f"status {st}"
+    got = to_host(dy)
+    what = f"symv {prefix_of(dt)} layout={layout} uplo={uplo} n={n} pad={pad} a={alpha} b={beta} inc=({incx},{incy})"
+    g, r = synth.gather(got, n, incy), synth.gather(ref, n, incy)
+    if ints:
+        assert bits_equal(g, r), what
+    else:
+        check_close(g, r, D, n, what)
+    gaps = np.ones(got.size, bool); gaps[::abs(incy)] = False
+    assert np.isnan(got[gaps]).all(), what
+
+
+@pytest.mark.parametrize("dt", DT)
+@pytest.mark.parametrize("layout", [O.ROW_MAJOR, O.COL_MAJOR])
+@pytest.mark.parametrize("uplo", [O.UPPER, O.LOWER])
+def test_symv(blas, ctx, dt, layout, uplo):
+    for n in (1, 2, 3, 5, 17, 64, 65, 130, 257, 1000, 1024, 2310):
+        symv_case(blas, ctx, dt, layout, uplo, n, 1.5, 0.5, 0 if n % 2 else 4, 1, 1)
+    for alpha, beta in [(1, 0), (1, 1), (0, 0.5), (0, 0), (-2, -1)]:
+        symv_case(blas, ctx, dt, layout, uplo, 700, alpha, beta, 0, 1, 1)
+    symv_case(blas, ctx, dt, layout, uplo, 515, 1.5, 0.5, 1, 2, -3)
+    symv_case(blas, ctx, dt, layout, uplo, 1536, 3, -2, 0, 1, 1, ints=True)
+    try:
+        for tr in (8, 64, 256):
+            ctx.set_option(blas.OPT_SYMV_TILE_ROWS, tr)
+            symv_case(blas, ctx, dt, layout, uplo, 2310, 1.5, 0.5, 2, 1, 1)
+    finally:
+        ctx.set_option(blas.OPT_SYMV_TILE_ROWS, 0)
+
+
+# ----------------------------------------------------------------------------- ger
+def ger_case(blas, ctx, dt, layout, m, n, alpha, pad, incx, incy, ints=False, seed=13):
+    gen = (lambda t, k: synth.small_ints(seed, t, k, -3, 3, dt)) if ints else (lambda t, k: synth.uniform(seed, t, k, dt))
+    A = gen(0, m * n).reshape(m, n)
+    x, y = gen(1, m), gen(2, n)
+    Ab, lda = matrix_buffer(A, layout, pad)
+    xb, yb = synth.strided(x, incx), synth.strided(y, incy)
+    ref = Ab.copy()
+    D = O.ger(layout, m, n, dt(alpha), xb, incx, yb, incy, ref, lda, want_D=True)
+    dA = to_dev(Ab)
+    st = blas.routine(prefix_of(dt), "ger")(ctx.h, layout, m, n, float(alpha), to_dev(xb), incx, to_dev(yb), incy, dA, lda)
+    assert st == 0, f"status {st}"
+    got = to_host(dA)
+    what = f"ger {prefix_of(dt)} layout={layout} {m}x{n} pad={pad} a={alpha} inc=({incx},{incy})"
+    g, r = logical(got, layout, m, n, lda), logical(ref, layout, m, n, lda)
+    if ints:
+        assert bits_equal(g, r), what
+    else:
+        check_close(np.ascontiguousarray(g).ravel(), np.ascontiguousarray(r).ravel(), D, 1, what)
+    # padding untouched (still NaN), nothing else changed
+    mask = np.ones(got.size, bool).reshape(-1, lda)
+    if layout == O.ROW_MAJOR: mask[:m, :n] = False
+    else: mask[:n, :m] = False
+    assert np.isnan(got.reshape(-1, lda)[mask]).all(), what + ": padding written"
+
+
+@pytest.mark.parametrize("dt", DT)
+@pytest.mark.parametrize("layout", [O.ROW_MAJOR, O.COL_MAJOR])
+def test_ger(blas, ctx, dt, layout):
+    for (m, n) in [(1, 1), (3, 5), (64, 64), (65, 257), (1000, 40), (40, 1000), (257, 1030), (1024, 1024), (300, 4097)]:
+        for pad in (0, 3, 4):
+            ger_case(blas, ctx, dt, layout, m, n, 0.3, pad, 1, 1)
+    ger_case(blas, ctx, dt, layout, 515, 260, -1.5, 4, 2, -3)
+    ger_case(blas, ctx, dt, layout, 515, 260, -1.5, 1, -1, 2)
+    ger_case(blas, ctx, dt, layout, 1030, 2052, 3, 0, 1, 1, ints=True)
+    # alpha = 0: A untouched even if x, y hold NaN
+    A = synth.uniform(13, 0, 100 * 100, dt); dA = to_dev(A); nan = to_dev(np.full(100, np.nan, dt))
+    assert blas.routine(prefix_of(dt), "ger")(ctx.h, layout, 100, 100, 0.0, nan, 1, nan, 1, dA, 100) == 0
+    assert bits_equal(to_host(dA), A)

@@ -397,7 +397,7 @@ def test_synth_generators_are_deterministic_and_in_range():
     assert a.tobytes() == b.tobytes() and a.min() >= -1 and a.max() < 1
     assert synth.uniform(1, 2, 100).tobytes() != synth.uniform(1, 1, 100).tobytes()
     # chunk boundaries do not matter: element i depends on (seed, tensor, i) only
-    assert synth.uniform(5, 0, (1 << 22) + 10)[-10:].tobytes() == \
-        np.array([synth.uniform(5, 0, (1 << 22) + k + 1)[-1] for k in range(10)], np.float32).tobytes()
+    assert synth.uniform(5, 0, (1 << 20) + 10)[-10:].tobytes() == \
+        np.array([synth.uniform(5, 0, (1 << 20) + k + 1)[-1] for k in range(10)], np.float32).tobytes()
     z = synth.normal(3, 0, 200000, 1 / 128.0)
     assert abs(z.std() * 128 - 1) < 0.01 and abs(z.mean()) < 1e-3
