@@ -1,0 +1,282 @@
+#!/usr/bin/env python3
+"""Benchmark of the BLAS level-1 / level-2 hot path on one MI355X.
+
+A *step* is one pass over the whole routine family at full size on seeded synthetic data that is
+already resident in HBM: the level-1 suite at n = 2^28 (unit stride and incx=2/incy=3), sgemv N/T
+at 16384^2 and 1048576x256 with beta in {0, 1, 0.5}, dgemv N/T at 16384^2 with lda = 16392,
+strmv (4 variants), ssymv and sger at 16384, plus the small 1024^2 sgemv.  `value` is the
+algorithmic bytes of a step divided by its wall time.  Every routine is also bracketed by events on
+the stream it is launched on; those give the per-routine GB/s and the `roofline` object (for the
+row-dot kernel behind sgemv N at 16384^2, the shape the headline metric is quoted on).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--only NAME[,NAME...]] [--no-cpu-baseline]
+
+`--only` restricts the step to the named routines (see --list), e.g. for profiling one kernel.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+GiB = 1 << 30
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--only", type=str, default="")
+    ap.add_argument("--list", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--scale", type=int, default=1, help="divide every problem size by this (debugging only; "
+                    "a scaled run is not the benchmark and says so in its output)")
+    return ap.parse_args()
+
+
+class Suite:
+    """Device buffers and the list of routine calls that make up one step."""
+
+    def __init__(self, blas, ctx, torch, scale=1):
+        self.B, self.ctx, self.torch = blas, ctx, torch
+        dev = ctx.device
+        g = torch.Generator(device=dev)
+        self.calls = []            # (name, kernel family, fn(step_index), algorithmic bytes)
+        f32, f64 = torch.float32, torch.float64
+
+        def uni(n, dtype, seed):
+            g.manual_seed(seed)
+            return torch.rand(n, dtype=dtype, device=dev, generator=g).mul_(2).sub_(1)
+
+        def nrm(n, dtype, seed, std=1.0):
+            g.manual_seed(seed)
+            return torch.randn(n, dtype=dtype, device=dev, generator=g).mul_(std)
+
+        h, B = ctx.h, blas
+        n1 = (1 << 28) // scale
+        NS = 16384 // (scale if scale <= 16 else 16)
+        MT, NT = (1 << 20) // scale, 256
+
+        # ---- level 1, n = 2^28, seed 1: dense and strided (incx = 2, incy = 3) ----------------
+        self.res = {"s": torch.zeros(1, dtype=f32, device=dev), "d": torch.zeros(1, dtype=f64, device=dev)}
+        for p, dt, e in (("s", f32, 4), ("d", f64, 8)):
+            x, y = uni(n1, dt, 101), uni(n1, dt, 102)
+            xs_, ys_ = uni(2 * n1, dt, 103), uni(3 * n1, dt, 104)
+            r = self.res[p]
+            for tag, xx, ix, yy, iy in (("", x, 1, y, 1), ("_strided", xs_, 2, ys_, 3)):
+                ax = B.routine(p, "axpy")
+                self.add(f"{p}axpy{tag}", "axpy", lambda s, ax=ax, xx=xx, ix=ix, yy=yy, iy=iy: ax(h, n1, -0.75, xx, ix, yy, iy), 3 * n1 * e)
+                dot = B.routine(p, "dot")
+                self.add(f"{p}dot{tag}", "dot", lambda s, dot=dot, xx=xx, ix=ix, yy=yy, iy=iy, r=r: dot(h, n1, xx, ix, yy, iy, r), 2 * n1 * e)
+                if p == "s":
+                    sc, asum, nrm2 = B.mxb_sscal, B.mxb_sasum, B.mxb_snrm2
+                    # alternate 1.25 and 0.8 so that repeated scaling stays bounded
+                    self.add(f"sscal{tag}", "scal", lambda s, xx=xx, ix=ix: sc(h, n1, 1.25 if s % 2 == 0 else 0.8, xx, ix), 2 * n1 * e)
+                    self.add(f"sasum{tag}", "asum", lambda s, xx=xx, ix=ix, r=r: asum(h, n1, xx, ix, r), n1 * e)
+                    self.add(f"snrm2{tag}", "nrm2", lambda s, xx=xx, ix=ix, r=r: nrm2(h, n1, xx, ix, r), n1 * e)
+            self.__dict__[f"keep_{p}"] = (x, y, xs_, ys_)
+
+        # ---- sgemv, seed 2: 16384^2 and 1048576 x 256, rotating over three copies of A --------
+        A32 = [uni(NS * NS, f32, 200 + k) for k in range(3)]
+        assert MT * NT <= NS * NS
+        xs, ys = uni(max(NS, MT), f32, 210), uni(max(NS, MT), f32, 211)
+        self.rot = 0
+
+        def nextA(pool):
+            self.rot += 1
+            return pool[self.rot % len(pool)]
+
+        for beta in (0.0, 1.0, 0.5):
+            for tname, trans in (("n", B.NO_TRANS), ("t", B.TRANS)):
+                rd = 0 if beta == 0 else 1
+                self.add(f"sgemv_{tname}_{NS}_b{beta:g}", "gemv_" + tname,
+                         lambda s, trans=trans, beta=beta: B.mxb_sgemv(h, B.ROW_MAJOR, trans, NS, NS, 1.0, nextA(A32), NS, xs, 1, beta, ys, 1),
+                         4 * (NS * NS + NS + NS * (1 + rd)))
+                lenx, leny = (NT, MT) if trans == B.NO_TRANS else (MT, NT)
+                self.add(f"sgemv_{tname}_{MT}x{NT}_b{beta:g}", "gemv_" + tname,
+                         lambda s, trans=trans, beta=beta: B.mxb_sgemv(h, B.ROW_MAJOR, trans, MT, NT, 1.0, nextA(A32), NT, xs, 1, beta, ys, 1),
+                         4 * (MT * NT + lenx + leny * (1 + rd)))
+        # the small, latency-bound case (1024^2, alpha = 1.5, beta = 0.5)
+        n0 = 1024
+        self.add("sgemv_n_1024", "gemv_n", lambda s: B.mxb_sgemv(h, B.ROW_MAJOR, B.NO_TRANS, n0, n0, 1.5, A32[0], n0, xs, 1, 0.5, ys, 1),
+                 4 * (n0 * n0 + n0 + 2 * n0))
+
+        # ---- dgemv, seed 3: 16384^2, lda = 16392, A ~ N(0, 1/sqrt(N)), beta = 0 ---------------
+        lda = NS + 8
+        A64 = [nrm(NS * lda, f64, 300 + k, 1.0 / np.sqrt(NS)) for k in range(2)]
+        xd, yd = nrm(NS, f64, 310), nrm(NS, f64, 311)
+        for tname, trans in (("n", B.NO_TRANS), ("t", B.TRANS)):
+            self.add(f"dgemv_{tname}_{NS}", "gemv_" + tname,
+                     lambda s, trans=trans: B.mxb_dgemv(h, B.ROW_MAJOR, trans, NS, NS, 2.0, nextA(A64), lda, xd, 1, 0.0, yd, 1),
+                     8 * (NS * NS + NS + NS))
+
+        # ---- structured level 2, fp32, n = 16384, seed 4 ---------------------------------------
+        x0 = uni(NS, f32, 410)
+        xt = x0.clone()
+        tri = NS * (NS + 1) // 2
+        for uname, uplo in (("u", B.UPPER), ("l", B.LOWER)):
+            for dname, diag in (("n", B.NON_UNIT), ("u", B.UNIT)):
+                def trmv(s, uplo=uplo, diag=diag):
+                    xt.copy_(x0)    # x := T x would blow up over repeated steps; restart from the same x
+                    return B.mxb_strmv(h, B.ROW_MAJOR, uplo, B.NO_TRANS, diag, NS, nextA(A32), NS, xt, 1)
+                nel = tri if diag == B.NON_UNIT else tri - NS
+                self.add(f"strmv_{uname}{dname}_{NS}", "trmv", trmv, 4 * (nel + 2 * NS))
+        self.add(f"ssymv_l_{NS}", "symv", lambda s: B.mxb_ssymv(h, B.ROW_MAJOR, B.LOWER, NS, 0.52, nextA(A32), NS, xs, 1, 0.49, ys, 1),
+                 4 * (tri + 3 * NS))
+        self.add(f"sger_{NS}", "ger", lambda s: B.mxb_sger(h, B.ROW_MAJOR, NS, NS, 1e-3, xs, 1, x0, 1, nextA(A32), NS),
+                 4 * (2 * NS * NS + 2 * NS))
+        self.keep = (A32, A64, xs, ys, xd, yd, x0, xt)
+
+        # ---- bandwidth probes: not part of a step, selectable with --only ----------------------
+        nb = NS * NS * 4
+        self.extra = [
+            ("probe_copy", "probe", lambda s: B.mxb_probe_copy(h, nb, A32[1], A32[2]), 2 * nb),
+            ("probe_read", "probe", lambda s: B.mxb_probe_read(h, nb, nextA(A32)), nb),
+        ]
+
+    def add(self, name, family, fn, nbytes):
+        self.calls.append((name, family, fn, int(nbytes)))
+
+
+def cpu_baseline(torch):
+    """The oracle, as it stands, timed single-threaded on this host on a bounded sample of the
+    step: level-1 at n = 2^27 (unit stride), the matrix routines at full size, each once."""
+    import oracle as O
+    from paper_2411_07211_amd import synth
+    n1, ns, mt, nt = 1 << 27, 16384, 1 << 20, 256
+    total = 0
+    t_total = 0.0
+
+    def timed(fn, nbytes):
+        nonlocal total, t_total
+        t0 = time.perf_counter(); fn(); t_total += time.perf_counter() - t0
+        total += nbytes
+
+    for dt, e in ((np.float32, 4), (np.float64, 8)):
+        x, y = synth.uniform(1, 1, n1, dt), synth.uniform(1, 2, n1, dt)
+        timed(lambda: O.axpy(n1, dt(-0.75), x, 1, y, 1), 3 * n1 * e)
+        timed(lambda: O.dot(n1, x, 1, y, 1), 2 * n1 * e)
+        if dt == np.float32:
+            timed(lambda: O.scal(n1, dt(1.25), x, 1), 2 * n1 * e)
+            timed(lambda: O.asum(n1, x, 1), n1 * e)
+            timed(lambda: O.nrm2(n1, x, 1), n1 * e)
+    A = synth.uniform(2, 0, ns * ns, np.float32)
+    xs, ys = synth.uniform(2, 1, mt, np.float32), synth.uniform(2, 2, mt, np.float32)
+    f = np.float32
+    for trans in (O.NO_TRANS, O.TRANS):
+        timed(lambda: O.gemv(O.ROW_MAJOR, trans, ns, ns, f(1), A, ns, xs, 1, f(0.5), ys, 1), 4 * (ns * ns + 3 * ns))
+        timed(lambda: O.gemv(O.ROW_MAJOR, trans, mt, nt, f(1), A, nt, xs, 1, f(0.5), ys, 1), 4 * (mt * nt + mt + nt + (mt if trans == O.NO_TRANS else nt)))
+    Ad = synth.normal(3, 0, ns * ns, 1 / np.sqrt(ns), np.float64)
+    xd, yd = synth.normal(3, 1, ns, 1.0, np.float64), synth.normal(3, 2, ns, 1.0, np.float64)
+    for trans in (O.NO_TRANS, O.TRANS):
+        timed(lambda: O.gemv(O.ROW_MAJOR, trans, ns, ns, 2.0, Ad, ns, xd, 1, 0.0, yd, 1), 8 * (ns * ns + 2 * ns))
+    tri = ns * (ns + 1) // 2
+    xt = xs[:ns].copy()
+    timed(lambda: O.trmv(O.ROW_MAJOR, O.UPPER, O.NO_TRANS, O.NON_UNIT, ns, A, ns, xt, 1), 4 * (tri + 2 * ns))
+    timed(lambda: O.symv(O.ROW_MAJOR, O.LOWER, ns, f(0.5), A, ns, xs, 1, f(0.5), ys, 1), 4 * (tri + 3 * ns))
+    timed(lambda: O.ger(O.ROW_MAJOR, ns, ns, f(1e-3), xs, 1, ys, 1, A, ns), 4 * (2 * ns * ns + 2 * ns))
+    return {
+        "value": round(total / t_total / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+        "sample": "each routine of the step once (level-1 at n=2^27 unit stride, s+d; s/dgemv N,T 16384^2; sgemv N,T "
+                  "1048576x256; strmv, ssymv, sger 16384^2), single thread, gcc -O2, long-double accumulation, "
+                  f"{total / 1e9:.2f} GB algorithmic in {t_total:.1f} s",
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py: this build measures one GPU only (got --gpus {args.gpus}); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2411_07211_amd import blas as B
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    ctx = B.Context("cuda:0", workspace_bytes=256 << 20)
+    suite = Suite(B, ctx, torch, scale=args.scale)
+    calls = suite.calls
+    if args.list:
+        for name, fam, _, nb in calls:
+            print(f"{name:32s} {fam:8s} {nb / GiB:8.3f} GiB")
+        return
+    if args.only:
+        want = set(args.only.split(","))
+        calls = [c for c in calls + suite.extra if c[0] in want or c[1] in want]
+        if not calls:
+            print("bench.py: --only matched nothing (see --list)", file=sys.stderr)
+            sys.exit(2)
+
+    def step(s, events=None):
+        for k, (name, fam, fn, nb) in enumerate(calls):
+            if events is not None:
+                events[k][0].record()
+            st = fn(s)
+            if events is not None:
+                events[k][1].record()
+            if st != 0:
+                raise RuntimeError(f"{name} returned status {st}")
+
+    for w in range(args.warmup):
+        step(w)
+    torch.cuda.synchronize()
+
+    K = args.steps
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in calls] for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(K):
+        step(args.warmup + s, ev[s])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    ms_per_step = (t1 - t0) * 1e3 / K
+    step_bytes = sum(c[3] for c in calls)
+    per = {}
+    for k, (name, fam, fn, nb) in enumerate(calls):
+        ts = sorted(ev[s][k][0].elapsed_time(ev[s][k][1]) for s in range(K))    # ms
+        avg = sum(ts) / len(ts)
+        per[name] = {"bytes": nb, "us_avg": round(avg * 1e3, 2), "us_min": round(ts[0] * 1e3, 2),
+                     "us_med": round(ts[len(ts) // 2] * 1e3, 2), "GBps": round(nb / (avg * 1e-3) / 1e9, 1),
+                     "frac_of_8TBps": round(nb / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+
+    NS = 16384 // (args.scale if args.scale <= 16 else 16)
+    head = f"sgemv_n_{NS}_b0"
+    roofline = None
+    if head in per:
+        p = per[head]
+        roofline = {"bound": "hbm", "kernel": "rowdot_kernel<float,4,64,4,general> (sgemv N 16384x16384, beta=0)",
+                    "achieved": p["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(p["GBps"] / HBM_PEAK_GBS, 4),
+                    "traffic": None, "algorithmic_bytes_per_launch": p["bytes"], "avg_launch_us": p["us_avg"]}
+
+    out = {
+        "metric": "achieved HBM GB/s over one pass of the BLAS level-1/level-2 suite (algorithmic bytes / time)",
+        "value": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32+f64", "data": "synthetic",
+        "config": {"workload": "level-1 n=2^28 (s,d; unit and incx=2/incy=3) + sgemv N,T 16384^2 and 1048576x256 (beta 0,1,0.5) "
+                               "+ dgemv N,T 16384^2 lda=16392 + strmv x4, ssymv, sger at 16384 + sgemv 1024^2"
+                               + ("" if args.scale == 1 else f" [SCALED DOWN by {args.scale}: not the benchmark]")
+                               + ("" if not args.only else f" [ONLY {args.only}]"),
+                   "step_algorithmic_GiB": round(step_bytes / GiB, 3)},
+        "roofline": roofline,
+        "kernels": per,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(torch)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
