@@ -192,6 +192,22 @@ def cpu_baseline(torch):
     }
 
 
+def measured_traffic():
+    """HBM bytes per call taken from the rocprofv3 counter runs recorded in profiles/traffic.json;
+    empty when the kernel sources have changed since those counters were collected."""
+    import hashlib
+    try:
+        rec = json.load(open(os.path.join(ROOT, "profiles", "traffic.json")))
+        h = hashlib.sha256()
+        for f in ("common.hpp", "options.hpp", "plan.hpp", "matvec.hip"):
+            h.update(open(os.path.join(ROOT, "paper_2411_07211_amd", "csrc", f), "rb").read())
+        if h.hexdigest() != rec["source_sha256"]:
+            return {}
+        return {k: v["hbm_bytes"] for k, v in rec["calls"].items()}
+    except (OSError, KeyError, ValueError):
+        return {}
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -253,12 +269,15 @@ def main():
 
     NS = 16384 // (args.scale if args.scale <= 16 else 16)
     head = f"sgemv_n_{NS}_b0"
+    traffic = measured_traffic()
+    for name in per:
+        per[name]["hbm_traffic_bytes"] = traffic.get(name)
     roofline = None
     if head in per:
         p = per[head]
-        roofline = {"bound": "hbm", "kernel": "rowdot_kernel<float,4,64,4,general> (sgemv N 16384x16384, beta=0)",
+        roofline = {"bound": "hbm", "kernel": "rowdot_kernel<float,4,64,2,4,general> (sgemv N 16384x16384, beta=0)",
                     "achieved": p["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(p["GBps"] / HBM_PEAK_GBS, 4),
-                    "traffic": None, "algorithmic_bytes_per_launch": p["bytes"], "avg_launch_us": p["us_avg"]}
+                    "traffic": traffic.get(head), "algorithmic_bytes_per_launch": p["bytes"], "avg_launch_us": p["us_avg"]}
 
     out = {
         "metric": "achieved HBM GB/s over one pass of the BLAS level-1/level-2 suite (algorithmic bytes / time)",

@@ -60,10 +60,31 @@ struct RowdotArgs {
 constexpr int kRowdotWaves = 8;
 constexpr int kRowdotThreads = kRowdotWaves * kWave;
 
-template <typename T, int VEC, int LPR, int R, int MODE, bool UNIT>
-__global__ void __launch_bounds__(kRowdotThreads, 4) rowdot_kernel(const RowdotArgs<T> p)
+// One batch of the row-dot inner loop: U column steps of R rows, all loads issued before the FMAs.
+template <typename T, int VEC, int R, int U, int STEP, int MODE, bool UNIT>
+__device__ __forceinline__ void rowdot_batch(const T* const (&arow)[R], const T* xs_at_c, int64_t c, int64_t grow0, T (&acc)[R])
 {
     typedef typename VecOf<T, VEC>::type V;
+    V av[U][R], xv[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int r = 0; r < R; ++r) av[u][r] = ld_stream(reinterpret_cast<const V*>(arow[r] + c + u * STEP));
+#pragma unroll
+    for (int u = 0; u < U; ++u) xv[u] = *reinterpret_cast<const V*>(xs_at_c + u * STEP);
+    __builtin_amdgcn_sched_barrier(0);   // keep every load of the batch ahead of the first FMA
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int k = 0; k < VEC; ++k)
+                acc[r] = __builtin_fma(tri_value<T, MODE, UNIT>(av[u][r][k], grow0 + r, c + u * STEP + k), xv[u][k], acc[r]);
+}
+
+template <typename T, int VEC, int LPR, int R, int U, int MODE, bool UNIT>
+__global__ void __launch_bounds__(kRowdotThreads, 4) rowdot_kernel(const RowdotArgs<T> p)
+{
     constexpr int FV = Full<T>::vec;
     typedef typename VecOf<T, FV>::type XV;
     extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -73,6 +94,7 @@ __global__ void __launch_bounds__(kRowdotThreads, 4) rowdot_kernel(const RowdotA
     constexpr int RW = GPW * R;               // rows per wavefront tile
     constexpr int RB = kRowdotWaves * RW;     // rows per block tile
     constexpr int STEP = LPR * VEC;           // columns a lane group covers per load
+    constexpr int SUPER = U * STEP;           // columns per batch of U loads
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -122,19 +144,21 @@ __global__ void __launch_bounds__(kRowdotThreads, 4) rowdot_kernel(const RowdotA
             }
             const int64_t lo = imax(wclo, c0), hi = imin(wchi, imin(c0 + xc, Nv));
             if (lo < hi) {
-                const int64_t first = c0 + (lo - c0) / STEP * STEP + l * VEC;
-#pragma unroll 2
-                for (int64_t c = first; c < hi; c += STEP) {
-                    const V xv = *reinterpret_cast<const V*>(xs + (c - c0));
-                    V av[R];
-#pragma unroll
-                    for (int r = 0; r < R; ++r) av[r] = ld_stream(reinterpret_cast<const V*>(arow[r] + c));
-#pragma unroll
-                    for (int r = 0; r < R; ++r)
-#pragma unroll
-                        for (int k = 0; k < VEC; ++k)
-                            acc[r] = __builtin_fma(tri_value<T, MODE, UNIT>(av[r][k], grow0 + r, c + k), xv[k], acc[r]);
+                // Whole batches first.  In the general case every wavefront starts at a different
+                // batch and wraps around, so that the wavefronts that run side by side are not all
+                // pulling the same column range (= the same HBM channels) of their rows at once.
+                const int64_t base = c0 + (lo - c0) / STEP * STEP;
+                const int64_t nfull = (hi - base) / SUPER;
+                if (nfull > 0) {
+                    int64_t s = MODE == MODE_GENERAL ? ((tile * kRowdotWaves + wave) * 3) % nfull : 0;
+                    for (int64_t k = 0; k < nfull; ++k) {
+                        const int64_t c = base + s * SUPER + l * VEC;
+                        s = s + 1 == nfull ? 0 : s + 1;
+                        rowdot_batch<T, VEC, R, U, STEP, MODE, UNIT>(arow, xs + (c - c0), c, grow0, acc);
+                    }
                 }
+                for (int64_t c = base + nfull * SUPER + l * VEC; c < hi; c += STEP)
+                    rowdot_batch<T, VEC, R, 1, STEP, MODE, UNIT>(arow, xs + (c - c0), c, grow0, acc);
             }
         }
         // columns past the last whole vector (N not a multiple of VEC): one lane each
@@ -176,63 +200,102 @@ struct ColaccArgs {
     int64_t lda;
     const T* x;          // logical element 0 (length M)
     int64_t incx;
-    T* y;                // logical element 0 (length N); written directly when there is one slab
+    T* y;                // logical element 0 (length N); written directly when there is one row group
     int64_t incy;
     T alpha, beta;
-    T* partials;         // [slabs][N] when there are several slabs
-    int64_t rows_per_block;
+    T* partials;         // [row groups][N] when there are several row groups
+    int64_t rows_per_block;   // WR == 4 only: rows of one slab
 };
 
 constexpr int kColaccThreads = 256;
-constexpr int kColaccUnroll = 8;
 
-template <typename T, int VEC, int WR, int MODE, bool UNIT>
+// Two shapes:
+//  WR == 1 (wide matrices): the 4 wavefronts of a block sit side by side and every lane owns CV
+//    vectors of VEC adjacent columns, 256*VEC columns apart, so that a block reads runs of
+//    CV*4 KiB from each row.  Rows are taken in batches of U adjacent rows and the batches are
+//    dealt to the gridDim.y row groups cyclically: at any moment the whole grid is reading one
+//    narrow band of adjacent rows, i.e. the matrix is swept front to back like a single
+//    sequential stream, which is what HBM serves fastest.
+//  WR == 4 (narrow matrices, CV == 1): one wavefront spans the row, the 4 wavefronts of a block
+//    interleave over the rows of a contiguous slab and are folded through LDS.
+template <typename T, int VEC, int CV, int WR, int MODE, bool UNIT>
 __global__ void __launch_bounds__(kColaccThreads) colacc_kernel(const ColaccArgs<T> p)
 {
     typedef typename VecOf<T, VEC>::type V;
-    constexpr int NW = kColaccThreads / kWave, WC = NW / WR, U = kColaccUnroll;
+    static_assert(WR == 1 || CV == 1, "narrow shape has one vector per lane");
+    constexpr int NW = kColaccThreads / kWave, WC = NW / WR;
+    constexpr int U = 16 / CV > 8 ? 8 : 16 / CV;          // rows in flight: 16 loads per lane (8 when CV == 1)
+    constexpr int SPAN = WC * kWave * VEC;                // columns one vector index covers across the block
     __shared__ T red[WR > 1 ? (WR - 1) * WC * kWave * VEC : 1];
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wc = wave % WC, wr = wave / WC;
-    const int64_t cblock0 = (int64_t)blockIdx.x * (WC * kWave * VEC);
-    const int64_t cblock1 = imin(p.N, cblock0 + WC * kWave * VEC);     // exclusive
+    const int64_t cblock0 = (int64_t)blockIdx.x * (CV * SPAN);
+    const int64_t cblock1 = imin(p.N, cblock0 + CV * SPAN);     // exclusive
     const int64_t c = cblock0 + (int64_t)(wc * kWave + lane) * VEC;
-    const bool col_ok = c + VEC <= p.N;
-
-    int64_t rlo = (int64_t)blockIdx.y * p.rows_per_block;
-    int64_t rhi = imin(p.M, rlo + p.rows_per_block);
-    if (MODE == MODE_UPPER) rhi = imin(rhi, cblock1);   // rows i <= j
-    if (MODE == MODE_LOWER) rlo = imax(rlo, cblock0);   // rows i >= j
-
-    T acc[VEC];
+    bool col_ok[CV];
 #pragma unroll
-    for (int k = 0; k < VEC; ++k) acc[k] = T(0);
+    for (int v = 0; v < CV; ++v) col_ok[v] = c + v * SPAN + VEC <= p.N;
 
-    if (col_ok) {
-        const T* acol = p.A + c;
-        int64_t i0 = rlo + wr;
-        for (; i0 + (int64_t)(U - 1) * WR < rhi; i0 += (int64_t)U * WR) {
-            V a[U];
-            T xi[U];
+    // Rows are visited in batches of U: rows r0 + u*rstep (u < U), then r0 += radvance.
+    int64_t r0, rstep, radvance, rend = p.M;
+    if (MODE == MODE_UPPER) rend = imin(rend, cblock1);                  // rows i <= j
+    if (WR == 1) {
+        // wide shape: batch = U adjacent rows; the batches are dealt to the row groups cyclically
+        rstep = 1;
+        radvance = (int64_t)gridDim.y * U;
+        r0 = (int64_t)blockIdx.y * U;
+        if (MODE == MODE_LOWER && r0 + U <= cblock0)                     // rows i >= j: skip batches above the tile
+            r0 += (cblock0 - U + 1 - r0 + radvance - 1) / radvance * radvance;
+    } else {
+        // narrow shape: a contiguous slab per block, its rows interleaved over the 4 wavefronts
+        int64_t rlo = (int64_t)blockIdx.y * p.rows_per_block;
+        rend = imin(rend, rlo + p.rows_per_block);
+        if (MODE == MODE_LOWER) rlo = imax(rlo, cblock0);
+        rstep = WR;
+        radvance = (int64_t)U * WR;
+        r0 = rlo + wr;
+    }
+
+    T acc[CV][VEC];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int64_t i = i0 + (int64_t)u * WR;
-                a[u] = ld_stream(reinterpret_cast<const V*>(acol + i * p.lda));
-                xi[u] = p.x[i * p.incx];
-            }
+    for (int v = 0; v < CV; ++v)
 #pragma unroll
-            for (int u = 0; u < U; ++u)
+        for (int k = 0; k < VEC; ++k) acc[v][k] = T(0);
+
+    // Lanes past the last column load the block's first vector instead (in bounds, never stored),
+    // so that the loads below carry no predicate and can all be issued back to back.
+    const T* acol[CV];
+#pragma unroll
+    for (int v = 0; v < CV; ++v) acol[v] = p.A + (col_ok[v] ? c + v * SPAN : cblock0);
+    for (; r0 + (int64_t)(U - 1) * rstep < rend; r0 += radvance) {
+        V a[U][CV];
+        T xi[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t i = r0 + (int64_t)u * rstep;
+#pragma unroll
+            for (int v = 0; v < CV; ++v) a[u][v] = ld_stream(reinterpret_cast<const V*>(acol[v] + i * p.lda));
+            xi[u] = p.x[i * p.incx];
+        }
+        __builtin_amdgcn_sched_barrier(0);   // keep every load of the batch ahead of the first FMA
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int v = 0; v < CV; ++v)
 #pragma unroll
                 for (int k = 0; k < VEC; ++k)
-                    acc[k] = __builtin_fma(tri_value<T, MODE, UNIT>(a[u][k], i0 + (int64_t)u * WR, c + k), xi[u], acc[k]);
-        }
-        for (; i0 < rhi; i0 += WR) {
-            const V a = ld_stream(reinterpret_cast<const V*>(acol + i0 * p.lda));
-            const T xi = p.x[i0 * p.incx];
+                    acc[v][k] = __builtin_fma(tri_value<T, MODE, UNIT>(a[u][v][k], r0 + (int64_t)u * rstep, c + v * SPAN + k), xi[u],
+                                              acc[v][k]);
+    }
+    for (; r0 < rend; r0 += rstep) {   // the one ragged batch
+        const T xi = p.x[r0 * p.incx];
 #pragma unroll
-            for (int k = 0; k < VEC; ++k) acc[k] = __builtin_fma(tri_value<T, MODE, UNIT>(a[k], i0, c + k), xi, acc[k]);
+        for (int v = 0; v < CV; ++v) {
+            const V a = ld_stream(reinterpret_cast<const V*>(acol[v] + r0 * p.lda));
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) acc[v][k] = __builtin_fma(tri_value<T, MODE, UNIT>(a[k], r0, c + v * SPAN + k), xi, acc[v][k]);
         }
     }
 
@@ -240,29 +303,33 @@ __global__ void __launch_bounds__(kColaccThreads) colacc_kernel(const ColaccArgs
         T* mine = red + ((int64_t)((wr - 1) * WC + wc) * kWave + lane) * VEC;
         if (wr > 0)
 #pragma unroll
-            for (int k = 0; k < VEC; ++k) mine[k] = acc[k];
+            for (int k = 0; k < VEC; ++k) mine[k] = acc[0][k];
         __syncthreads();
         if (wr > 0) return;
 #pragma unroll
         for (int w = 1; w < WR; ++w)
 #pragma unroll
-            for (int k = 0; k < VEC; ++k) acc[k] += red[((int64_t)((w - 1) * WC + wc) * kWave + lane) * VEC + k];
+            for (int k = 0; k < VEC; ++k) acc[0][k] += red[((int64_t)((w - 1) * WC + wc) * kWave + lane) * VEC + k];
     }
-    if (!col_ok) return;
 
-    if (gridDim.y == 1) {
 #pragma unroll
-        for (int k = 0; k < VEC; ++k) {
-            T* yp = p.y + (c + k) * p.incy;
-            T v = p.alpha * acc[k];
-            if (p.beta != T(0)) v = __builtin_fma(p.beta, *yp, v);
-            *yp = v;
+    for (int v = 0; v < CV; ++v) {
+        if (!col_ok[v]) continue;
+        const int64_t cv = c + v * SPAN;
+        if (gridDim.y == 1) {
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) {
+                T* yp = p.y + (cv + k) * p.incy;
+                T val = p.alpha * acc[v][k];
+                if (p.beta != T(0)) val = __builtin_fma(p.beta, *yp, val);
+                *yp = val;
+            }
+        } else {
+            V val;
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) val[k] = acc[v][k];
+            *reinterpret_cast<V*>(p.partials + (int64_t)blockIdx.y * p.N + cv) = val;
         }
-    } else {
-        V v;
-#pragma unroll
-        for (int k = 0; k < VEC; ++k) v[k] = acc[k];
-        *reinterpret_cast<V*>(p.partials + (int64_t)blockIdx.y * p.N + c) = v;
     }
 }
 
@@ -314,7 +381,7 @@ __global__ void __launch_bounds__(256) gather_kernel(int64_t n, const T* __restr
 // ---------------------------------------------------------------------------------------------
 // launchers
 
-template <typename T, int VEC, int LPR, int R, int MODE, bool UNIT>
+template <typename T, int VEC, int LPR, int R, int U, int MODE, bool UNIT>
 void launch_rowdot_inst(mxb_handle_t h, const RowdotArgs<T>& a)
 {
     constexpr int RB = kRowdotWaves * (kWave / LPR) * R;
@@ -322,21 +389,23 @@ void launch_rowdot_inst(mxb_handle_t h, const RowdotArgs<T>& a)
     const int64_t cap = kCUs * option(h, MXB_OPT_ROWDOT_BLOCKS_PER_CU);
     const int64_t grid = ntiles < cap ? ntiles : cap;
     const size_t lds = (size_t)a.xchunk * sizeof(T);
-    hipLaunchKernelGGL((rowdot_kernel<T, VEC, LPR, R, MODE, UNIT>), dim3((unsigned)grid), dim3(kRowdotThreads), lds, h->stream, a);
+    hipLaunchKernelGGL((rowdot_kernel<T, VEC, LPR, R, U, MODE, UNIT>), dim3((unsigned)grid), dim3(kRowdotThreads), lds, h->stream, a);
 }
 
 template <typename T, int VEC, int MODE, bool UNIT>
 void launch_rowdot_shape(mxb_handle_t h, const RowdotArgs<T>& a)
 {
-    // Narrow matrices: 16 lanes per row, four rows per wavefront side by side.  Few rows: one row
-    // per lane group so that the grid still fills the device.
-    const bool narrow = MODE == MODE_GENERAL && a.N <= 16 * 16 * VEC;
-    if (narrow) {
-        if (a.M >= (int64_t)kCUs * kRowdotWaves * 4 * 4) launch_rowdot_inst<T, VEC, 16, 4, MODE_GENERAL, false>(h, a);
-        else launch_rowdot_inst<T, VEC, 16, 1, MODE_GENERAL, false>(h, a);
+    // R x U = rows x column steps a lane group keeps in flight (8 loads of 16 bytes per lane).
+    //  * narrow rows (up to 16 vectors): 16 lanes per row, four rows side by side per wavefront;
+    //  * long rows: 2 rows x 4 steps, so that a wavefront reads 4 KiB runs of each row;
+    //  * few rows: one row per wavefront so that the grid still fills the device.
+    if (MODE == MODE_GENERAL && a.N <= 16 * 16 * VEC) {
+        if (a.M >= (int64_t)kCUs * kRowdotWaves * 4 * 4) launch_rowdot_inst<T, VEC, 16, 4, 2, MODE_GENERAL, false>(h, a);
+        else launch_rowdot_inst<T, VEC, 16, 1, 2, MODE_GENERAL, false>(h, a);
+    } else if (a.M >= (int64_t)kCUs * kRowdotWaves * 2) {
+        launch_rowdot_inst<T, VEC, 64, 2, 4, MODE, UNIT>(h, a);
     } else {
-        if (a.M >= (int64_t)kCUs * kRowdotWaves * 4) launch_rowdot_inst<T, VEC, 64, 4, MODE, UNIT>(h, a);
-        else launch_rowdot_inst<T, VEC, 64, 1, MODE, UNIT>(h, a);
+        launch_rowdot_inst<T, VEC, 64, 1, 4, MODE, UNIT>(h, a);
     }
 }
 
@@ -374,8 +443,11 @@ template <typename T, int VEC, int MODE, bool UNIT>
 void launch_colacc_inst(mxb_handle_t h, const ColaccArgs<T>& a, const ColaccPlan& pl)
 {
     const dim3 grid((unsigned)pl.col_tiles, (unsigned)pl.nparts);
-    if (pl.wr == 4) hipLaunchKernelGGL((colacc_kernel<T, VEC, 4, MODE, UNIT>), grid, dim3(kColaccThreads), 0, h->stream, a);
-    else hipLaunchKernelGGL((colacc_kernel<T, VEC, 1, MODE, UNIT>), grid, dim3(kColaccThreads), 0, h->stream, a);
+    const dim3 block(kColaccThreads);
+    if (pl.wr == 4) hipLaunchKernelGGL((colacc_kernel<T, VEC, 1, 4, MODE, UNIT>), grid, block, 0, h->stream, a);
+    else if (pl.cv == 4) hipLaunchKernelGGL((colacc_kernel<T, VEC, 4, 1, MODE, UNIT>), grid, block, 0, h->stream, a);
+    else if (pl.cv == 2) hipLaunchKernelGGL((colacc_kernel<T, VEC, 2, 1, MODE, UNIT>), grid, block, 0, h->stream, a);
+    else hipLaunchKernelGGL((colacc_kernel<T, VEC, 1, 1, MODE, UNIT>), grid, block, 0, h->stream, a);
 }
 
 // ws / ws_bytes: workspace region this call may use for partials.
@@ -384,8 +456,8 @@ int launch_colacc(mxb_handle_t h, ColaccArgs<T> a, int mode, bool unit, void* ws
 {
     constexpr int FV = Full<T>::vec;
     const bool vec = aligned16(a.A) && (a.lda % FV) == 0 && (a.N % FV) == 0;
-    const ColaccPlan pl = colacc_plan(a.M, a.N, vec ? FV : 1, option(h, MXB_OPT_COLACC_TARGET_BLOCKS),
-                                      option(h, MXB_OPT_COLACC_MIN_ROWS));
+    const ColaccPlan pl = colacc_plan(a.M, a.N, vec ? FV : 1, mode != MODE_GENERAL, option(h, MXB_OPT_COLACC_TARGET_BLOCKS),
+                                      colacc_narrow_target(h), option(h, MXB_OPT_COLACC_MIN_ROWS));
     a.rows_per_block = pl.rows_per_block;
     a.partials = nullptr;
     if (pl.nparts > 1) {

@@ -9,10 +9,10 @@ inline int64_t option_default(int o)
     switch (o) {
         case MXB_OPT_L1_BLOCKS_PER_CU: return 16;
         case MXB_OPT_REDUCE_BLOCKS: return 2048;
-        case MXB_OPT_ROWDOT_XCHUNK: return 16384;      // elements; capped to 64 KiB of LDS by the launcher
+        case MXB_OPT_ROWDOT_XCHUNK: return 4096;       // elements; capped to 64 KiB of LDS by the launcher
         case MXB_OPT_ROWDOT_BLOCKS_PER_CU: return 2;
-        case MXB_OPT_COLACC_TARGET_BLOCKS: return 1024;
-        case MXB_OPT_COLACC_MIN_ROWS: return 128;
+        case MXB_OPT_COLACC_TARGET_BLOCKS: return 192;
+        case MXB_OPT_COLACC_MIN_ROWS: return 64;
         case MXB_OPT_SYMV_TILE_ROWS: return 128;
         case MXB_OPT_GER_ROWS_PER_BLOCK: return 64;
         default: return 0;
@@ -20,5 +20,13 @@ inline int64_t option_default(int o)
 }
 
 inline int64_t option(mxb_handle_t h, int o) { return h->opt[o] > 0 ? h->opt[o] : option_default(o); }
+
+// Blocks the narrow column-accumulate shape aims for: two per compute unit, or twice the
+// caller's MXB_OPT_COLACC_TARGET_BLOCKS when that option is set.
+constexpr int64_t kColaccNarrowBlocks = 2 * kCUs;
+inline int64_t colacc_narrow_target(mxb_handle_t h)
+{
+    return h->opt[MXB_OPT_COLACC_TARGET_BLOCKS] > 0 ? 2 * h->opt[MXB_OPT_COLACC_TARGET_BLOCKS] : kColaccNarrowBlocks;
+}
 
 }  // namespace mxb

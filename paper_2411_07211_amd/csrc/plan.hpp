@@ -5,30 +5,50 @@
 namespace mxb {
 
 // Column-accumulate kernels (transposed gemv / trmv on a row-major matrix): a block of 4
-// wavefronts covers `cols_per_block` columns and `rows_per_block` rows and produces one partial
-// vector; `nparts` partial vectors per column are combined by a second kernel (none if 1).
+// wavefronts covers `cols_per_block` columns and one of `nparts` row groups and produces one
+// partial vector; the partial vectors of a column are combined by a second kernel (none if 1).
 struct ColaccPlan {
-    int wr;                  // wavefronts of a block that split the rows (1 or 4)
+    int wr;                  // wavefronts of a block that split the rows (1: wide shape, 4: narrow shape)
+    int cv;                  // column vectors per lane (wide shape)
     int64_t cols_per_block;
     int64_t col_tiles;
-    int64_t rows_per_block;
-    int64_t nparts;
+    int64_t rows_per_block;  // narrow shape: rows of one slab
+    int64_t nparts;          // row groups = partial vectors per column
 };
 
-inline ColaccPlan colacc_plan(int64_t rows, int64_t cols, int vec, int64_t target_blocks, int64_t min_rows)
+inline ColaccPlan colacc_plan(int64_t rows, int64_t cols, int vec, bool triangular, int64_t target_blocks, int64_t narrow_blocks,
+                              int64_t min_rows)
 {
     ColaccPlan p;
+    rows = rows > 0 ? rows : 1;
+    cols = cols > 0 ? cols : 1;
     p.wr = cols <= 2 * kWave * vec ? 4 : 1;
-    p.cols_per_block = (int64_t)(4 / p.wr) * kWave * vec;
-    p.col_tiles = ceil_div(cols > 0 ? cols : 1, p.cols_per_block);
-    const int64_t floor_rows = min_rows * p.wr;
+    p.cv = 1;
+    const int64_t span = (int64_t)(4 / p.wr) * kWave * vec;
+    if (p.wr == 1 && !triangular) {
+        // widest lane footprint that wastes under an eighth of the lanes on the ragged last tile;
+        // triangular shapes keep one vector per lane: more, smaller tiles balance the load better
+        for (int cv : {4, 2}) {
+            const int64_t padded = ceil_div(cols, cv * span) * cv * span;
+            if ((padded - cols) * 8 <= padded) { p.cv = cv; break; }
+        }
+    }
+    p.cols_per_block = p.cv * span;
+    p.col_tiles = ceil_div(cols, p.cols_per_block);
+    if (triangular) target_blocks *= 4;
+    if (p.wr == 4) target_blocks = narrow_blocks;
     int64_t parts = ceil_div(target_blocks, p.col_tiles);
-    const int64_t max_parts = ceil_div(rows > 0 ? rows : 1, floor_rows);
+    const int64_t max_parts = ceil_div(rows, min_rows * p.wr);
     if (parts > max_parts) parts = max_parts;
     if (parts < 1) parts = 1;
-    const int64_t quantum = 8 * p.wr;
-    p.rows_per_block = ceil_div(ceil_div(rows > 0 ? rows : 1, parts), quantum) * quantum;
-    p.nparts = ceil_div(rows > 0 ? rows : 1, p.rows_per_block);
+    if (p.wr == 1) {
+        p.rows_per_block = ceil_div(rows, parts);
+        p.nparts = parts;
+    } else {
+        const int64_t quantum = 8 * p.wr;
+        p.rows_per_block = ceil_div(ceil_div(rows, parts), quantum) * quantum;
+        p.nparts = ceil_div(rows, p.rows_per_block);
+    }
     return p;
 }
 
