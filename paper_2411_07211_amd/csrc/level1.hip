@@ -13,69 +13,82 @@ namespace mxb {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kUnroll = 4;   // independent 128-bit loads per thread and array
+constexpr int kUnroll = 4;      // independent 128-bit loads per thread and array
+constexpr int kScalUnroll = 2;  // scal reads and writes the same lines: shorter batches stream better
 
 // ---------------------------------------------------------------------------------------------
 // streaming: axpy / scal on contiguous, 16-byte aligned data
 
+// Tiles of kThreads*U vectors.  Whole tiles carry no predicate, so that all loads of a tile are
+// issued back to back; the ragged rest (fewer than one tile of vectors, then fewer than VEC
+// elements) is handled by the last block, one vector resp. one element per thread.
 template <typename T>
-__global__ void __launch_bounds__(kThreads) axpy_vec_kernel(int64_t nvec, int64_t ntiles, int tail, T alpha,
+__global__ void __launch_bounds__(kThreads) axpy_vec_kernel(int64_t nvec, int64_t nfull, int tail, T alpha,
                                                             const T* __restrict__ x, T* __restrict__ y)
 {
     constexpr int VEC = Full<T>::vec;
+    constexpr int U = kUnroll;
     typedef typename VecOf<T, VEC>::type V;
     const V* xv = reinterpret_cast<const V*>(x);
     V* yv = reinterpret_cast<V*>(y);
-    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
-        const int64_t base = t * (kThreads * kUnroll) + threadIdx.x;
-        V a[kUnroll], b[kUnroll];
+    for (int64_t t = blockIdx.x; t < nfull; t += gridDim.x) {
+        const int64_t base = t * (kThreads * U) + threadIdx.x;
+        V a[U], b[U];
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int64_t i = base + u * kThreads;
-            if (i < nvec) { a[u] = ld_stream(xv + i); b[u] = ld_stream(yv + i); }
-        }
+        for (int u = 0; u < U; ++u) a[u] = ld_stream(xv + base + u * kThreads);
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int64_t i = base + u * kThreads;
-            if (i < nvec) {
+        for (int u = 0; u < U; ++u) b[u] = ld_stream(yv + base + u * kThreads);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int k = 0; k < VEC; ++k) b[u][k] = __builtin_fma(alpha, a[u][k], b[u][k]);
-                st_stream(yv + i, b[u]);
-            }
+        for (int u = 0; u < U; ++u) {
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) b[u][k] = __builtin_fma(alpha, a[u][k], b[u][k]);
+            st_stream(yv + base + u * kThreads, b[u]);
         }
     }
-    if (blockIdx.x == 0 && (int)threadIdx.x < tail) {
+    if (blockIdx.x != gridDim.x - 1) return;
+    for (int64_t i = nfull * (kThreads * U) + threadIdx.x; i < nvec; i += kThreads) {
+        V b = yv[i];
+        const V a = xv[i];
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) b[k] = __builtin_fma(alpha, a[k], b[k]);
+        yv[i] = b;
+    }
+    if ((int)threadIdx.x < tail) {
         const int64_t i = nvec * VEC + threadIdx.x;
         y[i] = __builtin_fma(alpha, x[i], y[i]);
     }
 }
 
 template <typename T>
-__global__ void __launch_bounds__(kThreads) scal_vec_kernel(int64_t nvec, int64_t ntiles, int tail, T alpha,
+__global__ void __launch_bounds__(kThreads) scal_vec_kernel(int64_t nvec, int64_t nfull, int tail, T alpha,
                                                             T* __restrict__ x)
 {
     constexpr int VEC = Full<T>::vec;
+    constexpr int U = kScalUnroll;
     typedef typename VecOf<T, VEC>::type V;
     V* xv = reinterpret_cast<V*>(x);
-    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
-        const int64_t base = t * (kThreads * kUnroll) + threadIdx.x;
-        V a[kUnroll];
+    for (int64_t t = blockIdx.x; t < nfull; t += gridDim.x) {
+        const int64_t base = t * (kThreads * U) + threadIdx.x;
+        V a[U];
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int64_t i = base + u * kThreads;
-            if (i < nvec) a[u] = ld_stream(xv + i);
-        }
+        for (int u = 0; u < U; ++u) a[u] = ld_stream(xv + base + u * kThreads);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int64_t i = base + u * kThreads;
-            if (i < nvec) {
+        for (int u = 0; u < U; ++u) {
 #pragma unroll
-                for (int k = 0; k < VEC; ++k) a[u][k] = alpha * a[u][k];
-                st_stream(xv + i, a[u]);
-            }
+            for (int k = 0; k < VEC; ++k) a[u][k] = alpha * a[u][k];
+            st_stream(xv + base + u * kThreads, a[u]);
         }
     }
-    if (blockIdx.x == 0 && (int)threadIdx.x < tail) {
+    if (blockIdx.x != gridDim.x - 1) return;
+    for (int64_t i = nfull * (kThreads * U) + threadIdx.x; i < nvec; i += kThreads) {
+        V a = xv[i];
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) a[k] = alpha * a[k];
+        xv[i] = a;
+    }
+    if ((int)threadIdx.x < tail) {
         const int64_t i = nvec * VEC + threadIdx.x;
         x[i] = alpha * x[i];
     }
@@ -203,38 +216,45 @@ __device__ __forceinline__ void block_partial(const Acc<T, OP>* acc, int nacc, d
     }
 }
 
-// pass 1 on contiguous, aligned data.  TWO = the op reads y as well (dot).
+// pass 1 on contiguous, aligned data: whole tiles without predicates, the ragged rest by the
+// last block.
 template <typename T, int OP>
-__global__ void __launch_bounds__(kThreads) reduce_vec_kernel(int64_t nvec, int64_t ntiles, int tail,
+__global__ void __launch_bounds__(kThreads) reduce_vec_kernel(int64_t nvec, int64_t nfull, int tail,
                                                               const T* __restrict__ x, const T* __restrict__ y,
                                                               double* __restrict__ partials)
 {
     constexpr int VEC = Full<T>::vec;
     constexpr bool TWO = OP == OP_DOT;
+    constexpr int U = TWO ? kUnroll : 2 * kUnroll;      // 8 loads in flight per thread either way
     typedef typename VecOf<T, VEC>::type V;
     const V* xv = reinterpret_cast<const V*>(x);
     const V* yv = reinterpret_cast<const V*>(y);
     Acc<T, OP> acc[VEC];
-    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
-        const int64_t base = t * (kThreads * kUnroll) + threadIdx.x;
-        V a[kUnroll], b[kUnroll];
+    for (int64_t t = blockIdx.x; t < nfull; t += gridDim.x) {
+        const int64_t base = t * (kThreads * U) + threadIdx.x;
+        V a[U], b[U];
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int64_t i = base + u * kThreads;
-            a[u] = V(0); b[u] = V(0);
-            if (i < nvec) {
-                a[u] = ld_stream(xv + i);
-                if (TWO) b[u] = ld_stream(yv + i);
-            }
+        for (int u = 0; u < U; ++u) {
+            a[u] = ld_stream(xv + base + u * kThreads);
+            b[u] = TWO ? ld_stream(yv + base + u * kThreads) : V(T(0));
         }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u)
+        for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int k = 0; k < VEC; ++k) acc[k].add(a[u][k], b[u][k]);
     }
-    if (blockIdx.x == 0 && (int)threadIdx.x < tail) {
-        const int64_t i = nvec * VEC + threadIdx.x;
-        acc[0].add(x[i], TWO ? y[i] : T(0));
+    if (blockIdx.x == gridDim.x - 1) {
+        for (int64_t i = nfull * (kThreads * U) + threadIdx.x; i < nvec; i += kThreads) {
+            const V a = xv[i];
+            const V b = TWO ? yv[i] : V(T(0));
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) acc[k].add(a[k], b[k]);
+        }
+        if ((int)threadIdx.x < tail) {
+            const int64_t i = nvec * VEC + threadIdx.x;
+            acc[0].add(x[i], TWO ? y[i] : T(0));
+        }
     }
     block_partial<T, OP>(acc, VEC, partials);
 }
@@ -325,9 +345,9 @@ int axpy(mxb_handle_t h, int64_t n, T alpha, const T* x, int64_t incx, T* y, int
     const int64_t bpc = option(h, MXB_OPT_L1_BLOCKS_PER_CU);
     if (incx == 1 && incy == 1 && aligned16(x) && aligned16(y)) {
         const int64_t nvec = n / VEC;
-        const int64_t ntiles = ceil_div(nvec, kThreads * kUnroll);
-        const int64_t grid = ntiles < 1 ? 1 : (ntiles < kCUs * bpc ? ntiles : kCUs * bpc);
-        hipLaunchKernelGGL(axpy_vec_kernel<T>, dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, ntiles,
+        const int64_t nfull = nvec / (kThreads * kUnroll);
+        const int64_t grid = nfull < 1 ? 1 : (nfull < kCUs * bpc ? nfull : kCUs * bpc);
+        hipLaunchKernelGGL(axpy_vec_kernel<T>, dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, nfull,
                            (int)(n % VEC), alpha, x, y);
     } else {
         const int64_t want = ceil_div(n, kThreads * kUnroll);
@@ -349,9 +369,9 @@ int scal(mxb_handle_t h, int64_t n, T alpha, T* x, int64_t incx)
     const int64_t bpc = option(h, MXB_OPT_L1_BLOCKS_PER_CU);
     if (incx == 1 && aligned16(x)) {
         const int64_t nvec = n / VEC;
-        const int64_t ntiles = ceil_div(nvec, kThreads * kUnroll);
-        const int64_t grid = ntiles < 1 ? 1 : (ntiles < kCUs * bpc ? ntiles : kCUs * bpc);
-        hipLaunchKernelGGL(scal_vec_kernel<T>, dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, ntiles,
+        const int64_t nfull = nvec / (kThreads * kScalUnroll);
+        const int64_t grid = nfull < 1 ? 1 : (nfull < kCUs * bpc ? nfull : kCUs * bpc);
+        hipLaunchKernelGGL(scal_vec_kernel<T>, dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, nfull,
                            (int)(n % VEC), alpha, x);
     } else {
         const int64_t want = ceil_div(n, kThreads * kUnroll);
@@ -379,9 +399,9 @@ int reduce(mxb_handle_t h, int64_t n, const T* x, int64_t incx, const T* y, int6
     const bool contiguous = incx == 1 && aligned16(x) && (OP != OP_DOT || (incy == 1 && aligned16(y)));
     if (contiguous) {
         const int64_t nvec = n / VEC;
-        const int64_t ntiles = ceil_div(nvec, kThreads * kUnroll);
-        grid = ntiles < 1 ? 1 : (ntiles < max_blocks ? ntiles : max_blocks);
-        hipLaunchKernelGGL((reduce_vec_kernel<T, OP>), dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, ntiles,
+        const int64_t nfull = nvec / (kThreads * (OP == OP_DOT ? kUnroll : 2 * kUnroll));
+        grid = nfull < 1 ? 1 : (nfull < max_blocks ? nfull : max_blocks);
+        hipLaunchKernelGGL((reduce_vec_kernel<T, OP>), dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, nfull,
                            (int)(n % VEC), x, y, partials);
     } else {
         const int64_t want = ceil_div(n, kThreads * kUnroll);

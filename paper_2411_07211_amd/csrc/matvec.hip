@@ -104,8 +104,13 @@ __global__ void __launch_bounds__(kRowdotThreads, 4) rowdot_kernel(const RowdotA
     const int64_t xc = p.xchunk;
     int64_t staged = -1;
 
-    for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
-        // lower triangles are heaviest at the bottom: hand those tiles out first
+    for (int64_t pass = 0; pass * gridDim.x < ntiles; ++pass) {
+        // Triangular modes: rows get shorter (upper) or longer (lower) down the matrix, so the
+        // passes alternate direction: the block that took the heaviest tile of one pass takes the
+        // lightest of the next and every block ends up with about the same number of elements.
+        const int64_t slot = (MODE != MODE_GENERAL && (pass & 1)) ? (int64_t)gridDim.x - 1 - blockIdx.x : blockIdx.x;
+        const int64_t t = pass * gridDim.x + slot;
+        if (t >= ntiles) continue;
         const int64_t tile = MODE == MODE_LOWER ? ntiles - 1 - t : t;
         const int64_t brow0 = tile * RB;
         const int64_t wrow0 = brow0 + (int64_t)wave * RW;

@@ -7,14 +7,14 @@ namespace mxb {
 inline int64_t option_default(int o)
 {
     switch (o) {
-        case MXB_OPT_L1_BLOCKS_PER_CU: return 16;
+        case MXB_OPT_L1_BLOCKS_PER_CU: return 1 << 20;   // in effect one 16 KiB tile per block: read+write streams run best unthrottled
         case MXB_OPT_REDUCE_BLOCKS: return 2048;
         case MXB_OPT_ROWDOT_XCHUNK: return 4096;       // elements; capped to 64 KiB of LDS by the launcher
         case MXB_OPT_ROWDOT_BLOCKS_PER_CU: return 2;
         case MXB_OPT_COLACC_TARGET_BLOCKS: return 192;
         case MXB_OPT_COLACC_MIN_ROWS: return 64;
         case MXB_OPT_SYMV_TILE_ROWS: return 128;
-        case MXB_OPT_GER_ROWS_PER_BLOCK: return 64;
+        case MXB_OPT_GER_ROWS_PER_BLOCK: return 8;     // one batch of 8 rows per block: short read-then-write bursts stream best
         default: return 0;
     }
 }

@@ -202,6 +202,7 @@ __global__ void __launch_bounds__(kThreads) ger_kernel(const GerArgs<T> p)
             a[u] = ld_stream(reinterpret_cast<const V*>(acol + (i0 + u) * p.lda));
             ax[u] = p.alpha * p.x[(i0 + u) * p.incx];
         }
+        __builtin_amdgcn_sched_barrier(0);   // all loads of the batch are in flight before the first store
 #pragma unroll
         for (int u = 0; u < U; ++u) {
 #pragma unroll
