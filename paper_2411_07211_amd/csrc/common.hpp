@@ -42,6 +42,11 @@ inline T* vec_base(T* p, int64_t n, int64_t inc)
     return inc >= 0 ? p : p + (n - 1) * (-inc);
 }
 
+// Fused multiply-add in the element type (the bare builtin is the fp64 one and would silently
+// promote floats to double and back).
+__device__ __forceinline__ float fmad(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
+__device__ __forceinline__ double fmad(double a, double b, double c) { return __builtin_fma(a, b, c); }
+
 // ------------------------------------------------------------------------------------------------
 // 128-bit vectors: 4 floats or 2 doubles per lane and load, so that one wavefront load moves 1 KiB.
 template <typename T, int VEC> struct VecOf;

@@ -133,8 +133,8 @@ size_t mxb_workspace_bytes(int routine, int elem_size, int64_t m, int64_t n)
         case MXB_SYMV: {
             size_t b = 0;
             for (int vec : {1, full}) {
-                const SymvPlan p = symv_plan(n, vec, option_default(MXB_OPT_SYMV_TILE_ROWS));
-                const size_t need = (size_t)(p.ncol_tiles + p.nrow_tiles) * (size_t)n * (size_t)elem_size;
+                const SymvPlan p = symv_plan(n, vec, false, option_default(MXB_OPT_SYMV_TARGET_BLOCKS));
+                const size_t need = ((size_t)p.ntiles * 4 + (size_t)p.max_groups) * (size_t)n * (size_t)elem_size;
                 b = need > b ? need : b;
             }
             return align_up(b, 256);

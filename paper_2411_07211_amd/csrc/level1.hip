@@ -42,7 +42,7 @@ __global__ void __launch_bounds__(kThreads) axpy_vec_kernel(int64_t nvec, int64_
 #pragma unroll
         for (int u = 0; u < U; ++u) {
 #pragma unroll
-            for (int k = 0; k < VEC; ++k) b[u][k] = __builtin_fma(alpha, a[u][k], b[u][k]);
+            for (int k = 0; k < VEC; ++k) b[u][k] = fmad(alpha, a[u][k], b[u][k]);
             st_stream(yv + base + u * kThreads, b[u]);
         }
     }
@@ -51,12 +51,12 @@ __global__ void __launch_bounds__(kThreads) axpy_vec_kernel(int64_t nvec, int64_
         V b = yv[i];
         const V a = xv[i];
 #pragma unroll
-        for (int k = 0; k < VEC; ++k) b[k] = __builtin_fma(alpha, a[k], b[k]);
+        for (int k = 0; k < VEC; ++k) b[k] = fmad(alpha, a[k], b[k]);
         yv[i] = b;
     }
     if ((int)threadIdx.x < tail) {
         const int64_t i = nvec * VEC + threadIdx.x;
-        y[i] = __builtin_fma(alpha, x[i], y[i]);
+        y[i] = fmad(alpha, x[i], y[i]);
     }
 }
 
@@ -111,7 +111,7 @@ __global__ void __launch_bounds__(kThreads) axpy_strided_kernel(int64_t n, T alp
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const int64_t i = i0 + u * stride;
-            if (i < n) y[i * incy] = __builtin_fma(alpha, a[u], b[u]);
+            if (i < n) y[i * incy] = fmad(alpha, a[u], b[u]);
         }
     }
 }
@@ -157,7 +157,7 @@ template <> struct Acc<float, OP_DOT> {
 template <> struct Acc<double, OP_DOT> {
     static constexpr int K = 1;
     double s = 0.0;
-    __device__ __forceinline__ void add(double x, double y) { s = __builtin_fma(x, y, s); }
+    __device__ __forceinline__ void add(double x, double y) { s = fmad(x, y, s); }
     __device__ __forceinline__ void get(double* o) const { o[0] = s; }
 };
 template <> struct Acc<float, OP_ASUM> {
@@ -175,7 +175,7 @@ template <> struct Acc<double, OP_ASUM> {
 template <> struct Acc<float, OP_NRM2> {   // squares of floats are exact and cannot overflow in fp64
     static constexpr int K = 1;
     double s = 0.0;
-    __device__ __forceinline__ void add(float x, float) { const double d = (double)x; s = __builtin_fma(d, d, s); }
+    __device__ __forceinline__ void add(float x, float) { const double d = (double)x; s = fmad(d, d, s); }
     __device__ __forceinline__ void get(double* o) const { o[0] = s; }
 };
 template <> struct Acc<double, OP_NRM2> {
@@ -188,9 +188,9 @@ template <> struct Acc<double, OP_NRM2> {
         const double m = (is_big || is_sml) ? 0.0 : ax;   // NaN compares false twice: goes to med
         const double b = is_big ? ax * kSBig : 0.0;
         const double s = is_sml ? ax * kSSmall : 0.0;
-        med = __builtin_fma(m, m, med);
-        big = __builtin_fma(b, b, big);
-        sml = __builtin_fma(s, s, sml);
+        med = fmad(m, m, med);
+        big = fmad(b, b, big);
+        sml = fmad(s, s, sml);
     }
     __device__ __forceinline__ void get(double* o) const { o[0] = med; o[1] = big; o[2] = sml; }
 };

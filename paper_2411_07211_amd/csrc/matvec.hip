@@ -79,7 +79,7 @@ __device__ __forceinline__ void rowdot_batch(const T* const (&arow)[R], const T*
         for (int r = 0; r < R; ++r)
 #pragma unroll
             for (int k = 0; k < VEC; ++k)
-                acc[r] = __builtin_fma(tri_value<T, MODE, UNIT>(av[u][r][k], grow0 + r, c + u * STEP + k), xv[u][k], acc[r]);
+                acc[r] = fmad(tri_value<T, MODE, UNIT>(av[u][r][k], grow0 + r, c + u * STEP + k), xv[u][k], acc[r]);
 }
 
 template <typename T, int VEC, int LPR, int R, int U, int MODE, bool UNIT>
@@ -174,7 +174,7 @@ __global__ void __launch_bounds__(kRowdotThreads, 4) rowdot_kernel(const RowdotA
                 const T xj = p.x[j * p.incx];
 #pragma unroll
                 for (int r = 0; r < R; ++r)
-                    acc[r] = __builtin_fma(tri_value<T, MODE, UNIT>(arow[r][j], grow0 + r, j), xj, acc[r]);
+                    acc[r] = fmad(tri_value<T, MODE, UNIT>(arow[r][j], grow0 + r, j), xj, acc[r]);
             }
         }
 
@@ -189,7 +189,7 @@ __global__ void __launch_bounds__(kRowdotThreads, 4) rowdot_kernel(const RowdotA
         if (l < R && i < p.M) {
             T* yp = p.y + i * p.incy;
             T v = p.alpha * out;
-            if (p.beta != T(0)) v = __builtin_fma(p.beta, *yp, v);
+            if (p.beta != T(0)) v = fmad(p.beta, *yp, v);
             *yp = v;
         }
     }
@@ -291,7 +291,7 @@ __global__ void __launch_bounds__(kColaccThreads) colacc_kernel(const ColaccArgs
             for (int v = 0; v < CV; ++v)
 #pragma unroll
                 for (int k = 0; k < VEC; ++k)
-                    acc[v][k] = __builtin_fma(tri_value<T, MODE, UNIT>(a[u][v][k], r0 + (int64_t)u * rstep, c + v * SPAN + k), xi[u],
+                    acc[v][k] = fmad(tri_value<T, MODE, UNIT>(a[u][v][k], r0 + (int64_t)u * rstep, c + v * SPAN + k), xi[u],
                                               acc[v][k]);
     }
     for (; r0 < rend; r0 += rstep) {   // the one ragged batch
@@ -300,7 +300,7 @@ __global__ void __launch_bounds__(kColaccThreads) colacc_kernel(const ColaccArgs
         for (int v = 0; v < CV; ++v) {
             const V a = ld_stream(reinterpret_cast<const V*>(acol[v] + r0 * p.lda));
 #pragma unroll
-            for (int k = 0; k < VEC; ++k) acc[v][k] = __builtin_fma(tri_value<T, MODE, UNIT>(a[k], r0, c + v * SPAN + k), xi, acc[v][k]);
+            for (int k = 0; k < VEC; ++k) acc[v][k] = fmad(tri_value<T, MODE, UNIT>(a[k], r0, c + v * SPAN + k), xi, acc[v][k]);
         }
     }
 
@@ -326,7 +326,7 @@ __global__ void __launch_bounds__(kColaccThreads) colacc_kernel(const ColaccArgs
             for (int k = 0; k < VEC; ++k) {
                 T* yp = p.y + (cv + k) * p.incy;
                 T val = p.alpha * acc[v][k];
-                if (p.beta != T(0)) val = __builtin_fma(p.beta, *yp, val);
+                if (p.beta != T(0)) val = fmad(p.beta, *yp, val);
                 *yp = val;
             }
         } else {
@@ -363,7 +363,7 @@ __global__ void __launch_bounds__(kCombineGroups* kWave) colacc_combine_kernel(i
     for (int k = 1; k < kCombineGroups; ++k) tot += red[k][tx];
     T* yp = y + j * incy;
     T v = alpha * tot;
-    if (beta != T(0)) v = __builtin_fma(beta, *yp, v);
+    if (beta != T(0)) v = fmad(beta, *yp, v);
     *yp = v;
 }
 

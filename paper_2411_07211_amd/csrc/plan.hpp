@@ -52,19 +52,59 @@ inline ColaccPlan colacc_plan(int64_t rows, int64_t cols, int vec, bool triangul
     return p;
 }
 
-// symv: 2-D tiles of tile_rows x (256*vec) over the stored triangle; every active tile yields a
-// partial row-sum vector (indexed by column tile) and a partial column-sum vector (by row tile).
+// symv: the stored triangle is cut into column tiles of cv*256*vec columns.  Tile t owns the
+// rows that have stored elements in its columns (lower: from its first column down; upper: from
+// the top to its last column) and gets a share of the blocks proportional to that row count, so
+// that all blocks stream about the same number of bytes.  Block s of a tile takes batches of
+// adjacent rows cyclically.  Every block yields one partial column-sum vector over its tile
+// (colpart[s]) and every wavefront one partial row sum per row it visits (rowpart[4*t + wave]).
+constexpr int kSymvMaxTiles = 128;
+
 struct SymvPlan {
-    int64_t tile_rows, tile_cols, nrow_tiles, ncol_tiles;
+    int cv;                              // column vectors per lane
+    int64_t tile_cols;
+    int ntiles;
+    int first_block[kSymvMaxTiles + 1];  // blocks of tile t: [first_block[t], first_block[t+1])
+    int max_groups;                      // largest number of blocks any tile has
+    bool ok;                             // false: n needs more than kSymvMaxTiles tiles
 };
 
-inline SymvPlan symv_plan(int64_t n, int vec, int64_t tile_rows)
+inline SymvPlan symv_plan(int64_t n, int vec, bool upper, int64_t target_blocks, int64_t force_cv = 0)
 {
     SymvPlan p;
-    p.tile_rows = tile_rows < 8 ? 8 : (tile_rows > 256 ? 256 : tile_rows / 8 * 8);
-    p.tile_cols = 256 * (int64_t)vec;
-    p.nrow_tiles = ceil_div(n > 0 ? n : 1, p.tile_rows);
-    p.ncol_tiles = ceil_div(n > 0 ? n : 1, p.tile_cols);
+    n = n > 0 ? n : 1;
+    const int64_t span = 256 * (int64_t)vec;
+    // two vectors per lane unless that wastes over an eighth of the lanes on the ragged last tile
+    // (wider tiles spend more of their batches in the masked code along the diagonal)
+    p.cv = 1;
+    {
+        const int64_t padded = ceil_div(n, 2 * span) * 2 * span;
+        if ((padded - n) * 8 <= padded) p.cv = 2;
+    }
+    if (force_cv == 1 || force_cv == 2 || force_cv == 4) p.cv = (int)force_cv;
+    while (p.cv < 4 && ceil_div(n, p.cv * span) > kSymvMaxTiles) p.cv *= 2;
+    p.tile_cols = p.cv * span;
+    const int64_t nt = ceil_div(n, p.tile_cols);
+    p.ok = nt <= kSymvMaxTiles;
+    p.ntiles = (int)(p.ok ? nt : kSymvMaxTiles);
+    const int batch = p.cv == 1 ? 8 : 4;
+    int64_t total_rows = 0;
+    for (int t = 0; t < p.ntiles; ++t) {
+        const int64_t c0 = t * p.tile_cols, c1 = c0 + p.tile_cols < n ? c0 + p.tile_cols : n;
+        total_rows += upper ? c1 : n - c0;
+    }
+    p.first_block[0] = 0;
+    p.max_groups = 1;
+    for (int t = 0; t < p.ntiles; ++t) {
+        const int64_t c0 = t * p.tile_cols, c1 = c0 + p.tile_cols < n ? c0 + p.tile_cols : n;
+        const int64_t rows = upper ? c1 : n - c0;
+        int64_t g = (target_blocks * rows + total_rows / 2) / total_rows;
+        const int64_t cap = ceil_div(rows, batch);
+        if (g > cap) g = cap;
+        if (g < 1) g = 1;
+        p.first_block[t + 1] = p.first_block[t] + (int)g;
+        if (g > p.max_groups) p.max_groups = (int)g;
+    }
     return p;
 }
 

@@ -1,12 +1,15 @@
 // symv and ger (Sec. 6.2.2) on a row-major matrix.
 //
-// symv reads the stored triangle once.  The triangle is cut into tiles of TR rows by 256*VEC
-// columns (tile-granular triangular bounds, as in the paper's bound rounding; elements of a
-// diagonal tile that fall outside the triangle are discarded with a select).  Every stored
-// element A[i,j] is used twice: A[i,j]*x[j] goes to row i (folded across the wavefront with DPP,
-// across the block through LDS) and, off the diagonal, A[i,j]*x[i] goes to column j (a register
-// of the lane that owns the column).  Each tile hands a partial row-sum vector and a partial
-// column-sum vector to a second kernel, which adds them in tile order and applies alpha/beta.
+// symv reads the stored triangle exactly once, as one front-to-back sweep.  The triangle is cut
+// into column tiles (tile-granular triangular bounds, as in the paper's bound rounding); a block
+// owns one tile and takes batches of adjacent rows cyclically with the other blocks of the tile.
+// Every stored element A[i,j] is used twice: A[i,j]*x[j] goes to row i (folded across the
+// wavefront with DPP, one partial per wavefront) and, off the diagonal, A[i,j]*x[i] goes to
+// column j (a register of the lane that owns the column).  In the rows that cross the diagonal,
+// elements outside the triangle are discarded with a select, and a 128-bit load that would lie
+// wholly outside the triangle is redirected to the vector that holds the diagonal element (a line
+// the neighbouring lanes fetch anyway), so no byte outside the triangle is pulled from HBM.
+// A second kernel adds the partials in a fixed order and applies alpha/beta.
 //
 // ger is a streaming read-modify-write of A with the y slice of every lane held in registers.
 #include "common.hpp"
@@ -21,7 +24,6 @@ __device__ __forceinline__ int64_t imax(int64_t a, int64_t b) { return a > b ? a
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
-constexpr int kMaxTileRows = 256;
 
 template <typename T>
 struct SymvArgs {
@@ -30,131 +32,166 @@ struct SymvArgs {
     int64_t lda;
     const T* x;        // logical element 0
     int64_t incx;
-    T* rowpart;        // [ncol_tiles][n]
-    T* colpart;        // [nrow_tiles][n]
-    int tile_rows;
+    T* rowpart;        // [ntiles * 4 wavefronts][n]
+    T* colpart;        // [max_groups][n]
+    int ntiles;
+    int first_block[kSymvMaxTiles + 1];
 };
 
-// Is tile (row tile rt, column tile ct) touched by the stored triangle?
-__host__ __device__ __forceinline__ bool symv_tile_active(bool upper, int64_t rt, int64_t ct, int64_t TR, int64_t TC)
-{
-    return upper ? ct * TC + TC - 1 >= rt * TR : rt * TR + TR - 1 >= ct * TC;
-}
-
-template <typename T, int VEC, bool UPPER>
-__global__ void __launch_bounds__(kThreads) symv_tile_kernel(const SymvArgs<T> p)
+// One batch: U adjacent rows starting at rb, CV vectors per lane.  Rows and columns are below
+// 2^31 (the tile table caps n), so the index arithmetic is 32-bit; only addresses are 64-bit.
+template <typename T, int VEC, int CV, bool UPPER, bool MASKED>
+__device__ __forceinline__ void symv_batch(const SymvArgs<T>& p, int rb, int rlo, int rend, int c, const T* const (&acol)[CV],
+                                           const bool (&col_ok)[CV], const T (&xj)[CV][VEC], T (&cacc)[CV][VEC], T* rowpart_wave,
+                                           int lane)
 {
     typedef typename VecOf<T, VEC>::type V;
-    constexpr int U = 4;
-    constexpr int TC = kThreads * VEC;
-    __shared__ T rowsum[kMaxTileRows][kWaves];
+    constexpr int U = CV == 1 ? 8 : 4;
+    constexpr int SPAN = kThreads * VEC;
+    V a[U][CV];
+    T xi[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        int i = rb + u;
+        if (MASKED) i = min(max(i, rlo), rend - 1);              // clamp: the load stays inside the tile's rows
+        const T* arow = p.A + (int64_t)i * p.lda;
+#pragma unroll
+        for (int v = 0; v < CV; ++v) {
+            if (MASKED) {
+                int cc = c + v * SPAN;
+                const int diag = i / VEC * VEC;                  // vector that holds the diagonal element of row i
+                cc = UPPER ? max(cc, diag) : min(cc, diag);      // wholly outside the triangle: read that one instead
+                cc = min(cc, (int)p.n - VEC);                    // lanes past the last column
+                a[u][v] = ld_stream(reinterpret_cast<const V*>(arow + cc));
+            } else {
+                a[u][v] = ld_stream(reinterpret_cast<const V*>(acol[v] + (int64_t)i * p.lda));
+            }
+        }
+        xi[u] = p.x[(int64_t)i * p.incx];
+    }
+    __builtin_amdgcn_sched_barrier(0);   // keep every load of the batch ahead of the first FMA
+    T rs[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int i = rb + u;
+        T r = T(0);
+#pragma unroll
+        for (int v = 0; v < CV; ++v) {
+            // d = position of the diagonal inside this vector: element k is stored iff k <= d (lower) / k >= d (upper)
+            const int d = i - (c + v * SPAN);
+            const bool live = MASKED ? (i >= rlo && i < rend && col_ok[v]) : true;
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) {
+                T val = a[u][v][k];
+                if (MASKED) {
+                    const T in_row = (live && (UPPER ? k >= d : k <= d)) ? val : T(0);
+                    const T in_col = (live && (UPPER ? k > d : k < d)) ? val : T(0);
+                    r = fmad(in_row, xj[v][k], r);
+                    cacc[v][k] = fmad(in_col, xi[u], cacc[v][k]);
+                } else {
+                    r = fmad(val, xj[v][k], r);
+                    cacc[v][k] = fmad(val, xi[u], cacc[v][k]);
+                }
+            }
+        }
+        rs[u] = r;
+    }
+    // fold each row over the wavefront; lane u then stores row u's partial
+    T out = T(0);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const T sum = wave_sum(rs[u]);
+        out = lane == u ? sum : out;
+    }
+    const int i = rb + lane;
+    if (lane < U && i >= rlo && i < rend) rowpart_wave[i] = out;
+}
 
-    const int64_t ct = blockIdx.x, rt = blockIdx.y;
-    const int64_t TR = p.tile_rows;
-    if (!symv_tile_active(UPPER, rt, ct, TR, TC)) return;
+template <typename T, int VEC, int CV, bool UPPER>
+__global__ void __launch_bounds__(kThreads) symv_sweep_kernel(const SymvArgs<T> p)
+{
+    constexpr int U = CV == 1 ? 8 : 4;
+    constexpr int SPAN = kThreads * VEC;
+    constexpr int TC = CV * SPAN;
+
+    int t = 0;
+    while (t + 1 < p.ntiles && (int)blockIdx.x >= p.first_block[t + 1]) ++t;
+    const int64_t s = (int)blockIdx.x - p.first_block[t];
+    const int64_t S = p.first_block[t + 1] - p.first_block[t];
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t cb0 = ct * TC, rb0 = rt * TR;
-    const int64_t c = cb0 + (int64_t)threadIdx.x * VEC;
-    const bool col_ok = c + VEC <= p.n;
-    const int64_t cb1 = imin(p.n, cb0 + TC);
-    // rows of this tile that have stored elements in these columns
-    int64_t rlo = rb0, rhi = imin(p.n, rb0 + TR);
-    if (UPPER) rhi = imin(rhi, cb1);       // i <= j
-    else rlo = imax(rlo, cb0);             // i >= j
+    const int n = (int)p.n;
+    const int cb0 = t * TC, cb1 = min(n, cb0 + TC);
+    const int c = cb0 + (int)threadIdx.x * VEC;
+    const int rlo = UPPER ? 0 : cb0, rend = UPPER ? cb1 : n;     // rows with stored elements in these columns
+    const bool full_tile = cb0 + TC <= n;
 
-    T xj[VEC], cacc[VEC];
+    bool col_ok[CV];
+    const T* acol[CV];
+    T xj[CV][VEC], cacc[CV][VEC];
 #pragma unroll
-    for (int k = 0; k < VEC; ++k) {
-        xj[k] = col_ok ? p.x[(c + k) * p.incx] : T(0);
-        cacc[k] = T(0);
+    for (int v = 0; v < CV; ++v) {
+        col_ok[v] = c + v * SPAN + VEC <= n;
+        acol[v] = p.A + (col_ok[v] ? c + v * SPAN : cb0);
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+            xj[v][k] = col_ok[v] ? p.x[(int64_t)(c + v * SPAN + k) * p.incx] : T(0);
+            cacc[v][k] = T(0);
+        }
     }
-    const T* acol = p.A + (col_ok ? c : 0);
+    T* rowpart_wave = p.rowpart + ((int64_t)t * kWaves + wave) * p.n;
 
-    for (int64_t i0 = rlo; i0 < rhi; i0 += U) {
-        V a[U];
-        T xi[U], rsum[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t i = imin(i0 + u, rhi - 1);           // clamp: the load stays in bounds
-            a[u] = V(T(0));
-            if (col_ok) a[u] = ld_stream(reinterpret_cast<const V*>(acol + i * p.lda));
-            xi[u] = p.x[i * p.incx];
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t i = i0 + u;
-            const bool row_ok = i < rhi;
-            T rs = T(0);
-#pragma unroll
-            for (int k = 0; k < VEC; ++k) {
-                const int64_t j = c + k;
-                const bool stored = row_ok && col_ok && (UPPER ? j >= i : j <= i);
-                const T v = stored ? a[u][k] : T(0);
-                rs = __builtin_fma(v, xj[k], rs);
-                cacc[k] = __builtin_fma((i != j) ? v : T(0), xi[u], cacc[k]);
-            }
-            rsum[u] = rs;
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const T s = wave_sum(rsum[u]);
-            if (lane == 0 && i0 + u < rhi) rowsum[i0 + u - rb0][wave] = s;
-        }
+    // batches of U adjacent rows, dealt cyclically to the S blocks of this tile
+    const int rbase = rlo / U * U;
+    for (int64_t rb64 = rbase + s * U; rb64 < rend; rb64 += S * U) {
+        const int rb = (int)rb64;
+        // no element of the batch touches the diagonal or the ragged edges: no masks needed
+        const bool interior = full_tile && rb + U <= rend && (UPPER ? rb + U <= cb0 : rb >= cb1);
+        if (interior) symv_batch<T, VEC, CV, UPPER, false>(p, rb, rlo, rend, c, acol, col_ok, xj, cacc, rowpart_wave, lane);
+        else symv_batch<T, VEC, CV, UPPER, true>(p, rb, rlo, rend, c, acol, col_ok, xj, cacc, rowpart_wave, lane);
     }
-    __syncthreads();
-    for (int64_t i = rlo + threadIdx.x; i < rhi; i += kThreads) {
-        T s = rowsum[i - rb0][0];
+
+    typedef typename VecOf<T, VEC>::type V;
 #pragma unroll
-        for (int w = 1; w < kWaves; ++w) s += rowsum[i - rb0][w];
-        p.rowpart[ct * p.n + i] = s;
-    }
-    if (col_ok) {
-        V v;
+    for (int v = 0; v < CV; ++v) {
+        if (!col_ok[v]) continue;
+        V val;
 #pragma unroll
-        for (int k = 0; k < VEC; ++k) v[k] = cacc[k];
-        *reinterpret_cast<V*>(p.colpart + rt * p.n + c) = v;
+        for (int k = 0; k < VEC; ++k) val[k] = cacc[v][k];
+        *reinterpret_cast<V*>(p.colpart + s * p.n + c + v * SPAN) = val;
     }
 }
 
 constexpr int kCombineGroups = 16;
 
-// y[i] = alpha*(sum over active column tiles of rowpart + sum over active row tiles of colpart)
-//        + beta*y[i], each list in ascending tile order.
+// y[i] = alpha*(column partials of i's tile, then the row partials of every tile whose rows
+//        include i, each list in ascending order) + beta*y[i].
 template <typename T, bool UPPER>
-__global__ void __launch_bounds__(kCombineGroups* kWave) symv_combine_kernel(int64_t n, int64_t TR, int64_t TC, int64_t nrt, int64_t nct,
-                                                                             const T* __restrict__ rowpart,
-                                                                             const T* __restrict__ colpart, T alpha, T beta,
+__global__ void __launch_bounds__(kCombineGroups* kWave) symv_combine_kernel(const SymvArgs<T> p, int64_t TC, T alpha, T beta,
                                                                              T* __restrict__ y, int64_t incy)
 {
     __shared__ T red[kCombineGroups][kWave];
     const int tx = threadIdx.x & (kWave - 1), ty = threadIdx.x >> 6;
     const int64_t i = (int64_t)blockIdx.x * kWave + tx;
     T s = T(0);
-    if (i < n) {
-        const int64_t rt = i / TR, ct = i / TC;
-        // A row tile rt wrote rowpart[q][i] for its active column tiles q with a non-empty row
-        // range containing i; column tile ct wrote colpart[q][i] for its active row tiles q.
-        // Rows of a tile outside the clipped range [rlo, rhi) were not written: skip them.
-        for (int64_t q = ty; q < nct; q += kCombineGroups) {
-            if (!symv_tile_active(UPPER, rt, q, TR, TC)) continue;
-            const int64_t cb0 = q * TC, cb1 = (q + 1) * TC < n ? (q + 1) * TC : n;
-            const bool wrote = UPPER ? i < cb1 : i >= cb0;
-            if (wrote) s += rowpart[q * n + i];
-        }
-        for (int64_t q = ty; q < nrt; q += kCombineGroups)
-            if (symv_tile_active(UPPER, q, ct, TR, TC)) s += colpart[q * n + i];
+    if (i < p.n) {
+        const int64_t t = i / TC;
+        const int64_t ngroups = p.first_block[t + 1] - p.first_block[t];
+        for (int64_t q = ty; q < ngroups; q += kCombineGroups) s += p.colpart[q * p.n + i];
+        // tile q visited row i iff i >= its first column (lower) / i < its end column (upper)
+        const int64_t q0 = UPPER ? t : 0, q1 = UPPER ? p.ntiles : t + 1;
+        for (int64_t e = q0 * kWaves + ty; e < q1 * kWaves; e += kCombineGroups) s += p.rowpart[e * p.n + i];
     }
     red[ty][tx] = s;
     __syncthreads();
-    if (ty != 0 || i >= n) return;
+    if (ty != 0 || i >= p.n) return;
     T tot = red[0][tx];
 #pragma unroll
     for (int k = 1; k < kCombineGroups; ++k) tot += red[k][tx];
     T* yp = y + i * incy;
     T v = alpha * tot;
-    if (beta != T(0)) v = __builtin_fma(beta, *yp, v);
+    if (beta != T(0)) v = fmad(beta, *yp, v);
     *yp = v;
 }
 
@@ -206,7 +243,7 @@ __global__ void __launch_bounds__(kThreads) ger_kernel(const GerArgs<T> p)
 #pragma unroll
         for (int u = 0; u < U; ++u) {
 #pragma unroll
-            for (int k = 0; k < VEC; ++k) a[u][k] = __builtin_fma(ax[u], yj[k], a[u][k]);
+            for (int k = 0; k < VEC; ++k) a[u][k] = fmad(ax[u], yj[k], a[u][k]);
             st_stream(reinterpret_cast<V*>(acol + (i0 + u) * p.lda), a[u]);
         }
     }
@@ -214,7 +251,7 @@ __global__ void __launch_bounds__(kThreads) ger_kernel(const GerArgs<T> p)
         V a = ld_stream(reinterpret_cast<const V*>(acol + i0 * p.lda));
         const T ax = p.alpha * p.x[i0 * p.incx];
 #pragma unroll
-        for (int k = 0; k < VEC; ++k) a[k] = __builtin_fma(ax, yj[k], a[k]);
+        for (int k = 0; k < VEC; ++k) a[k] = fmad(ax, yj[k], a[k]);
         st_stream(reinterpret_cast<V*>(acol + i0 * p.lda), a);
     }
 }
@@ -225,28 +262,37 @@ __global__ void __launch_bounds__(kThreads) ger_kernel(const GerArgs<T> p)
 inline bool layout_ok(int v) { return v == MXB_ROW_MAJOR || v == MXB_COL_MAJOR; }
 inline bool uplo_ok(int v) { return v == MXB_UPPER || v == MXB_LOWER; }
 
+template <typename T, int VEC, int CV>
+void symv_launch_inst(mxb_handle_t h, bool upper, const SymvArgs<T>& a, int blocks)
+{
+    if (upper) hipLaunchKernelGGL((symv_sweep_kernel<T, VEC, CV, true>), dim3((unsigned)blocks), dim3(kThreads), 0, h->stream, a);
+    else hipLaunchKernelGGL((symv_sweep_kernel<T, VEC, CV, false>), dim3((unsigned)blocks), dim3(kThreads), 0, h->stream, a);
+}
+
 template <typename T, int VEC>
 int symv_launch(mxb_handle_t h, bool upper, int64_t n, T alpha, const T* A, int64_t lda, const T* x0, int64_t incx, T beta,
                 T* y0, int64_t incy)
 {
-    const SymvPlan pl = symv_plan(n, VEC, option(h, MXB_OPT_SYMV_TILE_ROWS));
-    const size_t need = (size_t)(pl.ncol_tiles + pl.nrow_tiles) * (size_t)n * sizeof(T);
+    if (n > 0x7fffffff - 4096) return MXB_ERR_NOT_IMPLEMENTED;
+    const SymvPlan pl = symv_plan(n, VEC, upper, option(h, MXB_OPT_SYMV_TARGET_BLOCKS), option(h, MXB_OPT_SYMV_TILE_VECTORS));
+    if (!pl.ok) return MXB_ERR_NOT_IMPLEMENTED;
+    const size_t need = ((size_t)pl.ntiles * kWaves + (size_t)pl.max_groups) * (size_t)n * sizeof(T);
     if (!h->ws || h->ws_bytes < need) return MXB_ERR_WORKSPACE;
-    T* rowpart = static_cast<T*>(h->ws);
-    T* colpart = rowpart + pl.ncol_tiles * n;
-    SymvArgs<T> a{n, A, lda, x0, incx, rowpart, colpart, (int)pl.tile_rows};
-    const dim3 grid((unsigned)pl.ncol_tiles, (unsigned)pl.nrow_tiles);
-    if (upper) hipLaunchKernelGGL((symv_tile_kernel<T, VEC, true>), grid, dim3(kThreads), 0, h->stream, a);
-    else hipLaunchKernelGGL((symv_tile_kernel<T, VEC, false>), grid, dim3(kThreads), 0, h->stream, a);
+    SymvArgs<T> a;
+    a.n = n; a.A = A; a.lda = lda; a.x = x0; a.incx = incx;
+    a.rowpart = static_cast<T*>(h->ws);
+    a.colpart = a.rowpart + (int64_t)pl.ntiles * kWaves * n;
+    a.ntiles = pl.ntiles;
+    for (int t = 0; t <= pl.ntiles; ++t) a.first_block[t] = pl.first_block[t];
+    const int blocks = pl.first_block[pl.ntiles];
+    if (pl.cv == 4) symv_launch_inst<T, VEC, 4>(h, upper, a, blocks);
+    else if (pl.cv == 2) symv_launch_inst<T, VEC, 2>(h, upper, a, blocks);
+    else symv_launch_inst<T, VEC, 1>(h, upper, a, blocks);
     int st = launch_status();
     if (st != MXB_OK) return st;
-    const dim3 cgrid((unsigned)ceil_div(n, kWave));
-    if (upper)
-        hipLaunchKernelGGL((symv_combine_kernel<T, true>), cgrid, dim3(kCombineGroups * kWave), 0, h->stream, n, pl.tile_rows,
-                           pl.tile_cols, pl.nrow_tiles, pl.ncol_tiles, rowpart, colpart, alpha, beta, y0, incy);
-    else
-        hipLaunchKernelGGL((symv_combine_kernel<T, false>), cgrid, dim3(kCombineGroups * kWave), 0, h->stream, n, pl.tile_rows,
-                           pl.tile_cols, pl.nrow_tiles, pl.ncol_tiles, rowpart, colpart, alpha, beta, y0, incy);
+    const dim3 cgrid((unsigned)ceil_div(n, kWave)), cblock(kCombineGroups * kWave);
+    if (upper) hipLaunchKernelGGL((symv_combine_kernel<T, true>), cgrid, cblock, 0, h->stream, a, pl.tile_cols, alpha, beta, y0, incy);
+    else hipLaunchKernelGGL((symv_combine_kernel<T, false>), cgrid, cblock, 0, h->stream, a, pl.tile_cols, alpha, beta, y0, incy);
     return launch_status();
 }
 

@@ -206,11 +206,12 @@ def test_symv(blas, ctx, dt, layout, uplo):
     symv_case(blas, ctx, dt, layout, uplo, 515, 1.5, 0.5, 1, 2, -3)
     symv_case(blas, ctx, dt, layout, uplo, 1536, 3, -2, 0, 1, 1, ints=True)
     try:
-        for tr in (8, 64, 256):
-            ctx.set_option(blas.OPT_SYMV_TILE_ROWS, tr)
+        for tb in (1, 7, 64, 1000):
+            ctx.set_option(blas.OPT_SYMV_TARGET_BLOCKS, tb)
             symv_case(blas, ctx, dt, layout, uplo, 2310, 1.5, 0.5, 2, 1, 1)
+            symv_case(blas, ctx, dt, layout, uplo, 5000, 1.5, 0.5, 0, 1, 1)
     finally:
-        ctx.set_option(blas.OPT_SYMV_TILE_ROWS, 0)
+        ctx.set_option(blas.OPT_SYMV_TARGET_BLOCKS, 0)
 
 
 # ----------------------------------------------------------------------------- ger
