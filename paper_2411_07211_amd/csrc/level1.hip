@@ -95,44 +95,46 @@ __global__ void __launch_bounds__(kThreads) scal_vec_kernel(int64_t nvec, int64_
 }
 
 // streaming with arbitrary increments (or unaligned data): one element per lane and load,
-// 64-bit offsets because a strided fp64 vector of 2^28 elements spans more than 4 GiB.
+// 64-bit offsets because a strided fp64 vector of 2^28 elements spans more than 4 GiB.  Tiles of
+// kThreads*kStridedUnroll logical elements; whole tiles carry no predicate, the last block takes
+// the ragged rest.
+constexpr int kStridedUnroll = 8;
+
 template <typename T>
-__global__ void __launch_bounds__(kThreads) axpy_strided_kernel(int64_t n, T alpha, const T* __restrict__ x, int64_t incx,
-                                                                T* __restrict__ y, int64_t incy)
+__global__ void __launch_bounds__(kThreads) axpy_strided_kernel(int64_t n, int64_t nfull, T alpha, const T* __restrict__ x,
+                                                                int64_t incx, T* __restrict__ y, int64_t incy)
 {
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
-    for (int64_t i0 = (int64_t)blockIdx.x * kThreads + threadIdx.x; i0 < n; i0 += stride * kUnroll) {
-        T a[kUnroll], b[kUnroll];
+    constexpr int U = kStridedUnroll;
+    for (int64_t t = blockIdx.x; t < nfull; t += gridDim.x) {
+        const int64_t base = t * (kThreads * U) + threadIdx.x;
+        T a[U], b[U];
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int64_t i = i0 + u * stride;
-            if (i < n) { a[u] = x[i * incx]; b[u] = y[i * incy]; }
-        }
+        for (int u = 0; u < U; ++u) a[u] = ld_stream(x + (base + u * kThreads) * incx);
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int64_t i = i0 + u * stride;
-            if (i < n) y[i * incy] = fmad(alpha, a[u], b[u]);
-        }
+        for (int u = 0; u < U; ++u) b[u] = y[(base + u * kThreads) * incy];   // plain load: the line is written next and should stay in L2
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < U; ++u) y[(base + u * kThreads) * incy] = fmad(alpha, a[u], b[u]);
     }
+    if (blockIdx.x != gridDim.x - 1) return;
+    for (int64_t i = nfull * (kThreads * U) + threadIdx.x; i < n; i += kThreads) y[i * incy] = fmad(alpha, x[i * incx], y[i * incy]);
 }
 
 template <typename T>
-__global__ void __launch_bounds__(kThreads) scal_strided_kernel(int64_t n, T alpha, T* __restrict__ x, int64_t incx)
+__global__ void __launch_bounds__(kThreads) scal_strided_kernel(int64_t n, int64_t nfull, T alpha, T* __restrict__ x, int64_t incx)
 {
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
-    for (int64_t i0 = (int64_t)blockIdx.x * kThreads + threadIdx.x; i0 < n; i0 += stride * kUnroll) {
-        T a[kUnroll];
+    constexpr int U = kStridedUnroll;
+    for (int64_t t = blockIdx.x; t < nfull; t += gridDim.x) {
+        const int64_t base = t * (kThreads * U) + threadIdx.x;
+        T a[U];
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int64_t i = i0 + u * stride;
-            if (i < n) a[u] = x[i * incx];
-        }
+        for (int u = 0; u < U; ++u) a[u] = x[(base + u * kThreads) * incx];   // plain load: the line is written next and should stay in L2
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int64_t i = i0 + u * stride;
-            if (i < n) x[i * incx] = alpha * a[u];
-        }
+        for (int u = 0; u < U; ++u) x[(base + u * kThreads) * incx] = alpha * a[u];
     }
+    if (blockIdx.x != gridDim.x - 1) return;
+    for (int64_t i = nfull * (kThreads * U) + threadIdx.x; i < n; i += kThreads) x[i * incx] = alpha * x[i * incx];
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -261,28 +263,29 @@ __global__ void __launch_bounds__(kThreads) reduce_vec_kernel(int64_t nvec, int6
 
 // pass 1 with arbitrary increments (or unaligned data)
 template <typename T, int OP>
-__global__ void __launch_bounds__(kThreads) reduce_strided_kernel(int64_t n, const T* __restrict__ x, int64_t incx,
+__global__ void __launch_bounds__(kThreads) reduce_strided_kernel(int64_t n, int64_t nfull, const T* __restrict__ x, int64_t incx,
                                                                   const T* __restrict__ y, int64_t incy,
                                                                   double* __restrict__ partials)
 {
     constexpr bool TWO = OP == OP_DOT;
-    Acc<T, OP> acc[kUnroll];
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
-    for (int64_t i0 = (int64_t)blockIdx.x * kThreads + threadIdx.x; i0 < n; i0 += stride * kUnroll) {
-        T a[kUnroll], b[kUnroll];
+    constexpr int U = kStridedUnroll;
+    constexpr int NACC = 4;
+    Acc<T, OP> acc[NACC];
+    for (int64_t t = blockIdx.x; t < nfull; t += gridDim.x) {
+        const int64_t base = t * (kThreads * U) + threadIdx.x;
+        T a[U], b[U];
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int64_t i = i0 + u * stride;
-            a[u] = T(0); b[u] = T(0);
-            if (i < n) {
-                a[u] = x[i * incx];
-                if (TWO) b[u] = y[i * incy];
-            }
+        for (int u = 0; u < U; ++u) {
+            a[u] = ld_stream(x + (base + u * kThreads) * incx);
+            b[u] = TWO ? ld_stream(y + (base + u * kThreads) * incy) : T(0);
         }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) acc[u].add(a[u], b[u]);
+        for (int u = 0; u < U; ++u) acc[u % NACC].add(a[u], b[u]);
     }
-    block_partial<T, OP>(acc, kUnroll, partials);
+    if (blockIdx.x == gridDim.x - 1)
+        for (int64_t i = nfull * (kThreads * U) + threadIdx.x; i < n; i += kThreads) acc[0].add(x[i * incx], TWO ? y[i * incy] : T(0));
+    block_partial<T, OP>(acc, NACC, partials);
 }
 
 // pass 2: one block adds the per-block partials in a fixed order and finishes the result.
@@ -350,9 +353,9 @@ int axpy(mxb_handle_t h, int64_t n, T alpha, const T* x, int64_t incx, T* y, int
         hipLaunchKernelGGL(axpy_vec_kernel<T>, dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, nfull,
                            (int)(n % VEC), alpha, x, y);
     } else {
-        const int64_t want = ceil_div(n, kThreads * kUnroll);
-        const int64_t grid = want < kCUs * bpc ? want : kCUs * bpc;
-        hipLaunchKernelGGL(axpy_strided_kernel<T>, dim3((unsigned)grid), dim3(kThreads), 0, h->stream, n, alpha,
+        const int64_t nfull = n / (kThreads * kStridedUnroll);
+        const int64_t grid = nfull < 1 ? 1 : (nfull < kCUs * bpc ? nfull : kCUs * bpc);
+        hipLaunchKernelGGL(axpy_strided_kernel<T>, dim3((unsigned)grid), dim3(kThreads), 0, h->stream, n, nfull, alpha,
                            vec_base(x, n, incx), incx, vec_base(y, n, incy), incy);
     }
     return launch_status();
@@ -374,9 +377,9 @@ int scal(mxb_handle_t h, int64_t n, T alpha, T* x, int64_t incx)
         hipLaunchKernelGGL(scal_vec_kernel<T>, dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, nfull,
                            (int)(n % VEC), alpha, x);
     } else {
-        const int64_t want = ceil_div(n, kThreads * kUnroll);
-        const int64_t grid = want < kCUs * bpc ? want : kCUs * bpc;
-        hipLaunchKernelGGL(scal_strided_kernel<T>, dim3((unsigned)grid), dim3(kThreads), 0, h->stream, n, alpha, x, incx);
+        const int64_t nfull = n / (kThreads * kStridedUnroll);
+        const int64_t grid = nfull < 1 ? 1 : (nfull < kCUs * bpc ? nfull : kCUs * bpc);
+        hipLaunchKernelGGL(scal_strided_kernel<T>, dim3((unsigned)grid), dim3(kThreads), 0, h->stream, n, nfull, alpha, x, incx);
     }
     return launch_status();
 }
@@ -404,9 +407,9 @@ int reduce(mxb_handle_t h, int64_t n, const T* x, int64_t incx, const T* y, int6
         hipLaunchKernelGGL((reduce_vec_kernel<T, OP>), dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, nfull,
                            (int)(n % VEC), x, y, partials);
     } else {
-        const int64_t want = ceil_div(n, kThreads * kUnroll);
-        grid = want < max_blocks ? want : max_blocks;
-        hipLaunchKernelGGL((reduce_strided_kernel<T, OP>), dim3((unsigned)grid), dim3(kThreads), 0, h->stream, n,
+        const int64_t nfull = n / (kThreads * kStridedUnroll);
+        grid = nfull < 1 ? 1 : (nfull < max_blocks ? nfull : max_blocks);
+        hipLaunchKernelGGL((reduce_strided_kernel<T, OP>), dim3((unsigned)grid), dim3(kThreads), 0, h->stream, n, nfull,
                            vec_base(x, n, incx), incx, y ? vec_base(y, n, incy) : nullptr, incy, partials);
     }
     int st = launch_status();

@@ -461,7 +461,7 @@ int launch_colacc(mxb_handle_t h, ColaccArgs<T> a, int mode, bool unit, void* ws
 {
     constexpr int FV = Full<T>::vec;
     const bool vec = aligned16(a.A) && (a.lda % FV) == 0 && (a.N % FV) == 0;
-    const ColaccPlan pl = colacc_plan(a.M, a.N, vec ? FV : 1, mode != MODE_GENERAL, option(h, MXB_OPT_COLACC_TARGET_BLOCKS),
+    const ColaccPlan pl = colacc_plan(a.M, a.N, (int)sizeof(T), vec ? FV : 1, mode != MODE_GENERAL, option(h, MXB_OPT_COLACC_TARGET_BLOCKS),
                                       colacc_narrow_target(h), option(h, MXB_OPT_COLACC_MIN_ROWS));
     a.rows_per_block = pl.rows_per_block;
     a.partials = nullptr;

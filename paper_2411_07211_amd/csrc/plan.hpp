@@ -16,8 +16,8 @@ struct ColaccPlan {
     int64_t nparts;          // row groups = partial vectors per column
 };
 
-inline ColaccPlan colacc_plan(int64_t rows, int64_t cols, int vec, bool triangular, int64_t target_blocks, int64_t narrow_blocks,
-                              int64_t min_rows)
+inline ColaccPlan colacc_plan(int64_t rows, int64_t cols, int elem_size, int vec, bool triangular, int64_t target_blocks,
+                              int64_t narrow_blocks, int64_t min_rows)
 {
     ColaccPlan p;
     rows = rows > 0 ? rows : 1;
@@ -25,7 +25,10 @@ inline ColaccPlan colacc_plan(int64_t rows, int64_t cols, int vec, bool triangul
     p.wr = cols <= 2 * kWave * vec ? 4 : 1;
     p.cv = 1;
     const int64_t span = (int64_t)(4 / p.wr) * kWave * vec;
-    if (p.wr == 1 && !triangular) {
+    // A matrix that fits the 256 MiB last-level cache is not an HBM stream: it wants many small
+    // blocks (latency), not a few long sweeping ones.
+    const bool cache_sized = rows * cols * elem_size <= ((int64_t)128 << 20);
+    if (p.wr == 1 && !triangular && !cache_sized) {
         // widest lane footprint that wastes under an eighth of the lanes on the ragged last tile;
         // triangular shapes keep one vector per lane: more, smaller tiles balance the load better
         for (int cv : {4, 2}) {
@@ -35,7 +38,7 @@ inline ColaccPlan colacc_plan(int64_t rows, int64_t cols, int vec, bool triangul
     }
     p.cols_per_block = p.cv * span;
     p.col_tiles = ceil_div(cols, p.cols_per_block);
-    if (triangular) target_blocks *= 4;
+    if (triangular || cache_sized) target_blocks *= 4;
     if (p.wr == 4) target_blocks = narrow_blocks;
     int64_t parts = ceil_div(target_blocks, p.col_tiles);
     const int64_t max_parts = ceil_div(rows, min_rows * p.wr);
