@@ -149,17 +149,21 @@ __global__ void __launch_bounds__(kRowdotThreads, 4) rowdot_kernel(const RowdotA
             }
             const int64_t lo = imax(wclo, c0), hi = imin(wchi, imin(c0 + xc, Nv));
             if (lo < hi) {
-                // Whole batches first.  In the general case every wavefront starts at a different
-                // batch and wraps around, so that the wavefronts that run side by side are not all
-                // pulling the same column range (= the same HBM channels) of their rows at once.
+                // Whole batches first.  Every wavefront starts at a different batch and wraps
+                // around, so that the wavefronts that run side by side are not all pulling the
+                // same column range (= the same HBM channels) of their rows at once.
                 const int64_t base = c0 + (lo - c0) / STEP * STEP;
                 const int64_t nfull = (hi - base) / SUPER;
                 if (nfull > 0) {
-                    int64_t s = MODE == MODE_GENERAL ? ((tile * kRowdotWaves + wave) * 3) % nfull : 0;
+                    int64_t s = ((tile * kRowdotWaves + wave) * 3) % nfull;
                     for (int64_t k = 0; k < nfull; ++k) {
-                        const int64_t c = base + s * SUPER + l * VEC;
+                        const int64_t cw = base + s * SUPER;     // first column of the batch (wave-uniform)
+                        const int64_t c = cw + l * VEC;
                         s = s + 1 == nfull ? 0 : s + 1;
-                        rowdot_batch<T, VEC, R, U, STEP, MODE, UNIT>(arow, xs + (c - c0), c, grow0, acc);
+                        // a batch that lies wholly inside the triangle for every row of the wavefront needs no masks
+                        const bool inside = MODE == MODE_GENERAL || (MODE == MODE_UPPER ? cw > wrow0 + RW - 1 : cw + SUPER <= wrow0);
+                        if (inside) rowdot_batch<T, VEC, R, U, STEP, MODE_GENERAL, false>(arow, xs + (c - c0), c, grow0, acc);
+                        else rowdot_batch<T, VEC, R, U, STEP, MODE, UNIT>(arow, xs + (c - c0), c, grow0, acc);
                     }
                 }
                 for (int64_t c = base + nfull * SUPER + l * VEC; c < hi; c += STEP)

@@ -90,7 +90,7 @@ inline SymvPlan symv_plan(int64_t n, int vec, bool upper, int64_t target_blocks,
     const int64_t nt = ceil_div(n, p.tile_cols);
     p.ok = nt <= kSymvMaxTiles;
     p.ntiles = (int)(p.ok ? nt : kSymvMaxTiles);
-    const int batch = p.cv == 1 ? 8 : 4;
+    const int batch = p.cv == 4 ? 4 : 8;
     int64_t total_rows = 0;
     for (int t = 0; t < p.ntiles; ++t) {
         const int64_t c0 = t * p.tile_cols, c1 = c0 + p.tile_cols < n ? c0 + p.tile_cols : n;

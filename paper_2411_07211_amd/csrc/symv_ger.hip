@@ -46,10 +46,18 @@ __device__ __forceinline__ void symv_batch(const SymvArgs<T>& p, int rb, int rlo
                                            int lane)
 {
     typedef typename VecOf<T, VEC>::type V;
-    constexpr int U = CV == 1 ? 8 : 4;
+    constexpr int U = CV == 4 ? 4 : 8;
     constexpr int SPAN = kThreads * VEC;
     V a[U][CV];
     T xi[U];
+    // Masked batches: a vector index whose 64 lanes all lie outside the triangle for every row of
+    // the batch is skipped by the whole wavefront (a scalar branch): no loads, no arithmetic.
+    bool dead[CV];
+#pragma unroll
+    for (int v = 0; v < CV; ++v) {
+        const int cw = __builtin_amdgcn_readfirstlane(c - lane * VEC) + v * SPAN;      // first column of the wavefront's vector v
+        dead[v] = MASKED && (UPPER ? cw + kWave * VEC - 1 < rb : cw > rb + U - 1);
+    }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         int i = rb + u;
@@ -57,7 +65,9 @@ __device__ __forceinline__ void symv_batch(const SymvArgs<T>& p, int rb, int rlo
         const T* arow = p.A + (int64_t)i * p.lda;
 #pragma unroll
         for (int v = 0; v < CV; ++v) {
-            if (MASKED) {
+            if (MASKED && dead[v]) {
+                a[u][v] = V(T(0));
+            } else if (MASKED) {
                 int cc = c + v * SPAN;
                 const int diag = i / VEC * VEC;                  // vector that holds the diagonal element of row i
                 cc = UPPER ? max(cc, diag) : min(cc, diag);      // wholly outside the triangle: read that one instead
@@ -78,6 +88,7 @@ __device__ __forceinline__ void symv_batch(const SymvArgs<T>& p, int rb, int rlo
 #pragma unroll
         for (int v = 0; v < CV; ++v) {
             // d = position of the diagonal inside this vector: element k is stored iff k <= d (lower) / k >= d (upper)
+            if (MASKED && dead[v]) continue;
             const int d = i - (c + v * SPAN);
             const bool live = MASKED ? (i >= rlo && i < rend && col_ok[v]) : true;
 #pragma unroll
@@ -110,7 +121,7 @@ __device__ __forceinline__ void symv_batch(const SymvArgs<T>& p, int rb, int rlo
 template <typename T, int VEC, int CV, bool UPPER>
 __global__ void __launch_bounds__(kThreads) symv_sweep_kernel(const SymvArgs<T> p)
 {
-    constexpr int U = CV == 1 ? 8 : 4;
+    constexpr int U = CV == 4 ? 4 : 8;
     constexpr int SPAN = kThreads * VEC;
     constexpr int TC = CV * SPAN;
 
