@@ -47,6 +47,7 @@ def _load():
         build()
         _lib = ctypes.CDLL(_SO)
         _declare(_lib)
+        _declare_mixed(_lib)
     return _lib
 
 
@@ -70,6 +71,21 @@ def _declare(lib):
             f = getattr(lib, f"oracle_{p}{name}")
             f.argtypes = [_i64, _ptr, _i64, _ptr]
             f.restype = ct
+        f = getattr(lib, f"oracle_{p}copy")
+        f.argtypes = [_i64, _ptr, _i64, _ptr, _i64]
+        f.restype = None
+        f = getattr(lib, f"oracle_{p}swap")
+        f.argtypes = [_i64, _ptr, _i64, _ptr, _i64]
+        f.restype = None
+        f = getattr(lib, f"oracle_{p}rot")
+        f.argtypes = [_i64, _ptr, _i64, _ptr, _i64, ct, ct, _ptr]
+        f.restype = None
+        f = getattr(lib, f"oracle_{p}rotm")
+        f.argtypes = [_i64, _ptr, _i64, _ptr, _i64, _ptr, _ptr]
+        f.restype = None
+        f = getattr(lib, f"oracle_{p}iamax")
+        f.argtypes = [_i64, _ptr, _i64]
+        f.restype = _i64
         f = getattr(lib, f"oracle_{p}gemv")
         f.argtypes = [_int, _int, _i64, _i64, ct, _ptr, _i64, _ptr, _i64, ct, _ptr, _i64, _ptr]
         f.restype = None
@@ -82,6 +98,11 @@ def _declare(lib):
         f = getattr(lib, f"oracle_{p}ger")
         f.argtypes = [_int, _i64, _i64, ct, _ptr, _i64, _ptr, _i64, _ptr, _i64, _ptr]
         f.restype = None
+
+
+def _declare_mixed(lib):
+    lib.oracle_dsdot.argtypes = [_i64, _ptr, _i64, _ptr, _i64, _ptr]
+    lib.oracle_dsdot.restype = ctypes.c_double
 
 
 def _prefix(a: np.ndarray) -> str:
@@ -196,3 +217,47 @@ def ger(layout, m, n, alpha, x, incx, y, incy, A, lda, want_D=False):
     getattr(_load(), f"oracle_{p}ger")(layout, m, n, alpha, _p(x), incx, _p(y), incy, _p(A),
                                        lda, _p(D))
     return D
+
+
+def copy(n, x, incx, y, incy):
+    p = _same(x, y)
+    _need(x, n, incx, "x"); _need(y, n, incy, "y")
+    getattr(_load(), f"oracle_{p}copy")(n, _p(x), incx, _p(y), incy)
+
+
+def swap(n, x, incx, y, incy):
+    p = _same(x, y)
+    _need(x, n, incx, "x"); _need(y, n, incy, "y")
+    getattr(_load(), f"oracle_{p}swap")(n, _p(x), incx, _p(y), incy)
+
+
+def rot(n, x, incx, y, incy, c, s, want_D=False):
+    p = _same(x, y)
+    _need(x, n, incx, "x"); _need(y, n, incy, "y")
+    D = np.zeros(2 * max(n, 0), np.float64) if want_D else None
+    getattr(_load(), f"oracle_{p}rot")(n, _p(x), incx, _p(y), incy, c, s, _p(D))
+    return D
+
+
+def rotm(n, x, incx, y, incy, param, want_D=False):
+    p = _same(x, y, param)
+    assert param.size >= 5
+    _need(x, n, incx, "x"); _need(y, n, incy, "y")
+    D = np.zeros(2 * max(n, 0), np.float64) if want_D else None
+    getattr(_load(), f"oracle_{p}rotm")(n, _p(x), incx, _p(y), incy, _p(param), _p(D))
+    return D
+
+
+def iamax(n, x, incx):
+    p = _prefix(x)
+    if incx > 0:
+        _need(x, n, incx, "x")
+    return int(getattr(_load(), f"oracle_{p}iamax")(n, _p(x), incx))
+
+
+def dsdot(n, x, incx, y, incy, want_D=False):
+    assert x.dtype == np.float32 and y.dtype == np.float32
+    _need(x, n, incx, "x"); _need(y, n, incy, "y")
+    D = np.zeros(1, np.float64)
+    r = np.float64(_load().oracle_dsdot(n, _p(x), incx, _p(y), incy, _p(D)))
+    return (r, D[0]) if want_D else r

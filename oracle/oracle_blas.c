@@ -39,3 +39,18 @@ enum { ORACLE_NON_UNIT = 131, ORACLE_UNIT = 132 };
 #include "oracle_blas_impl.h"
 #undef T
 #undef FN
+
+/* dsdot, Sec. 6.2.1: fp32 inputs, products and sum in (at least) double, double result. */
+double oracle_dsdot(int64_t n, const float* x, int64_t incx, const float* y, int64_t incy, double* D)
+{
+    acc_t acc = 0;
+    double d = 0;
+    for (int64_t k = 0; k < n; ++k) {
+        const float xv = x[oracle_spos(k, n, incx)], yv = y[oracle_spos(k, n, incy)];
+        acc += (acc_t)xv * (acc_t)yv;
+        d += fabs((double)xv * (double)yv);
+    }
+    if (D) *D = d;
+    return (double)acc;
+}
+

@@ -214,3 +214,81 @@ void FN(ger)(int layout, int64_t m, int64_t n, T alpha, const T* x, int64_t incx
         }
     }
 }
+
+/* ---- rest of the level-1 set of Sec. 6.2.1 (copy, swap, rot, rotm) and iamax (which, like nrm2,
+ *      the paper could not express; plain definition) ------------------------------------------ */
+
+/* copy: y[i] = x[i]. */
+void FN(copy)(int64_t n, const T* x, int64_t incx, T* y, int64_t incy)
+{
+    for (int64_t k = 0; k < n; ++k) y[FN(pos)(k, n, incy)] = x[FN(pos)(k, n, incx)];
+}
+
+/* swap: x[i] <-> y[i]. */
+void FN(swap)(int64_t n, T* x, int64_t incx, T* y, int64_t incy)
+{
+    for (int64_t k = 0; k < n; ++k) {
+        T* xp = &x[FN(pos)(k, n, incx)];
+        T* yp = &y[FN(pos)(k, n, incy)];
+        const T t = *xp;
+        *xp = *yp;
+        *yp = t;
+    }
+}
+
+/* rot: (x[i], y[i]) := (c*x[i] + s*y[i], c*y[i] - s*x[i]).  D (if given) holds 2n entries:
+ * D[2k] for the new x, D[2k+1] for the new y. */
+void FN(rot)(int64_t n, T* x, int64_t incx, T* y, int64_t incy, T c, T s, double* D)
+{
+    for (int64_t k = 0; k < n; ++k) {
+        T* xp = &x[FN(pos)(k, n, incx)];
+        T* yp = &y[FN(pos)(k, n, incy)];
+        const acc_t xv = *xp, yv = *yp;
+        if (D) {
+            D[2 * k] = fabs((double)c * (double)*xp) + fabs((double)s * (double)*yp);
+            D[2 * k + 1] = fabs((double)c * (double)*yp) + fabs((double)s * (double)*xp);
+        }
+        *xp = (T)((acc_t)c * xv + (acc_t)s * yv);
+        *yp = (T)((acc_t)c * yv - (acc_t)s * xv);
+    }
+}
+
+/* rotm: (x[i], y[i]) := H (x[i], y[i]) with H given by param[0] = flag and param[1..4] =
+ * h11, h21, h12, h22:  flag -1: H = [h11 h12; h21 h22];  flag 0: H = [1 h12; h21 1];
+ * flag 1: H = [h11 1; -1 h22];  flag -2: H = identity (nothing is touched). */
+void FN(rotm)(int64_t n, T* x, int64_t incx, T* y, int64_t incy, const T* param, double* D)
+{
+    const T flag = param[0];
+    if (n <= 0 || flag == (T)-2) return;
+    acc_t h11, h12, h21, h22;
+    if (flag < (T)0) { h11 = param[1]; h21 = param[2]; h12 = param[3]; h22 = param[4]; }
+    else if (flag == (T)0) { h11 = 1; h21 = param[2]; h12 = param[3]; h22 = 1; }
+    else { h11 = param[1]; h21 = -1; h12 = 1; h22 = param[4]; }
+    for (int64_t k = 0; k < n; ++k) {
+        T* xp = &x[FN(pos)(k, n, incx)];
+        T* yp = &y[FN(pos)(k, n, incy)];
+        const acc_t xv = *xp, yv = *yp;
+        if (D) {
+            D[2 * k] = fabs((double)(h11 * xv)) + fabs((double)(h12 * yv));
+            D[2 * k + 1] = fabs((double)(h21 * xv)) + fabs((double)(h22 * yv));
+        }
+        *xp = (T)(h11 * xv + h12 * yv);
+        *yp = (T)(h21 * xv + h22 * yv);
+    }
+}
+
+/* iamax: 0-based index of the first element of largest absolute value, found by the sequential
+ * scan "best = |x[0]|; for k >= 1: if |x[k]| > best, take k" (so a NaN is never taken, and a NaN
+ * in x[0] wins by default).  n <= 0 or incx <= 0 gives 0. */
+int64_t FN(iamax)(int64_t n, const T* x, int64_t incx)
+{
+    if (n <= 0 || incx <= 0) return 0;
+    int64_t best = 0;
+    T bv = (T)fabs((double)x[0]);
+    for (int64_t k = 1; k < n; ++k) {
+        const T v = (T)fabs((double)x[k * incx]);
+        if (v > bv) { bv = v; best = k; }
+    }
+    return best;
+}
+

@@ -401,3 +401,100 @@ def test_synth_generators_are_deterministic_and_in_range():
         np.array([synth.uniform(5, 0, (1 << 20) + k + 1)[-1] for k in range(10)], np.float32).tobytes()
     z = synth.normal(3, 0, 200000, 1 / 128.0)
     assert abs(z.std() * 128 - 1) < 0.01 and abs(z.mean()) < 1e-3
+
+
+# ----------------------------------------------------------------------------- rest of level 1
+@pytest.mark.parametrize("dt", DT)
+@pytest.mark.parametrize("incx,incy", [(1, 1), (2, 3), (-1, 2), (3, -2)])
+def test_copy_swap(dt, incx, incy):
+    n = 301
+    xd, yd = synth.uniform(20, 1, n, dt), synth.uniform(20, 2, n, dt)
+    xb, yb = synth.strided(xd, incx), synth.strided(yd, incy)
+    O.copy(n, xb, incx, yb, incy)
+    assert np.array_equal(synth.gather(yb, n, incy), xd) and np.array_equal(synth.gather(xb, n, incx), xd)
+    gaps = np.ones(yb.size, bool); gaps[::abs(incy)] = False
+    assert np.isnan(yb[gaps]).all()
+    xb, yb = synth.strided(xd, incx), synth.strided(yd, incy)
+    O.swap(n, xb, incx, yb, incy)
+    assert np.array_equal(synth.gather(xb, n, incx), yd) and np.array_equal(synth.gather(yb, n, incy), xd)
+    O.swap(n, xb, incx, yb, incy)                                  # twice = identity
+    assert np.array_equal(synth.gather(xb, n, incx), xd) and np.array_equal(synth.gather(yb, n, incy), yd)
+
+
+@pytest.mark.parametrize("dt", DT)
+def test_rot(dt):
+    n = 200
+    x, y = ints(21, 1, n, dt, -9, 9), ints(21, 2, n, dt, -9, 9)
+    a, b = x.copy(), y.copy(); O.rot(n, a, 1, b, 1, dt(1), dt(0))
+    assert np.array_equal(a, x) and np.array_equal(b, y)          # c=1, s=0: identity
+    a, b = x.copy(), y.copy(); O.rot(n, a, 1, b, 1, dt(0), dt(1))
+    assert np.array_equal(a, y) and np.array_equal(b, -x)         # c=0, s=1: (y, -x)
+    a, b = x.copy(), y.copy(); O.rot(n, a, 1, b, 1, dt(3), dt(4))  # integer brute force, not symmetric in x, y
+    xi, yi = x.astype(np.int64), y.astype(np.int64)
+    assert np.array_equal(a.astype(np.int64), 3 * xi + 4 * yi) and np.array_equal(b.astype(np.int64), 3 * yi - 4 * xi)
+    # a true rotation keeps x^2 + y^2
+    u, v = synth.uniform(21, 1, n, dt), synth.uniform(21, 2, n, dt)
+    c, s = dt(np.cos(0.7)), dt(np.sin(0.7))
+    a, b = u.copy(), v.copy(); O.rot(n, a, 1, b, 1, c, s)
+    assert np.allclose(a.astype(np.float64) ** 2 + b.astype(np.float64) ** 2, u.astype(np.float64) ** 2 + v.astype(np.float64) ** 2,
+                       rtol=20 * np.finfo(dt).eps)
+    # strided = gathered
+    ub, vb = synth.strided(u, -2), synth.strided(v, 3)
+    O.rot(n, ub, -2, vb, 3, c, s)
+    assert np.array_equal(synth.gather(ub, n, -2), a) and np.array_equal(synth.gather(vb, n, 3), b)
+
+
+@pytest.mark.parametrize("dt", DT)
+def test_rotm(dt):
+    n = 100
+    x, y = ints(22, 1, n, dt, -9, 9), ints(22, 2, n, dt, -9, 9)
+    xi, yi = x.astype(np.int64), y.astype(np.int64)
+    h11, h21, h12, h22 = 2, 3, 5, 7
+    cases = {
+        -1: (h11 * xi + h12 * yi, h21 * xi + h22 * yi),
+        0: (xi + h12 * yi, h21 * xi + yi),
+        1: (h11 * xi + yi, -xi + h22 * yi),
+        -2: (xi, yi),
+    }
+    for flag, (ex, ey) in cases.items():
+        a, b = x.copy(), y.copy()
+        O.rotm(n, a, 1, b, 1, np.array([flag, h11, h21, h12, h22], dt))
+        assert np.array_equal(a.astype(np.int64), ex) and np.array_equal(b.astype(np.int64), ey), flag
+    # flag -2 does not even read H
+    a, b = x.copy(), y.copy(); O.rotm(n, a, 1, b, 1, np.array([-2, np.nan, np.nan, np.nan, np.nan], dt))
+    assert np.array_equal(a, x) and np.array_equal(b, y)
+    # rotm with flag -1 and H = [c s; -s c] is rot
+    c, s = dt(0.6), dt(0.8)
+    u, v = synth.uniform(22, 1, n, dt), synth.uniform(22, 2, n, dt)
+    a, b = u.copy(), v.copy(); O.rotm(n, a, 1, b, 1, np.array([-1, c, -s, s, c], dt))
+    a2, b2 = u.copy(), v.copy(); O.rot(n, a2, 1, b2, 1, c, s)
+    assert np.array_equal(a, a2) and np.array_equal(b, b2)
+
+
+def test_dsdot():
+    n = 1001
+    x, y = ints(23, 1, n, np.float32, -99, 99), ints(23, 2, n, np.float32, -99, 99)
+    assert O.dsdot(n, x, 1, y, 1) == int(np.dot(x.astype(np.int64), y.astype(np.int64)))
+    xb, yb = synth.strided(x, 2), synth.strided(y, -3)
+    assert O.dsdot(n, xb, 2, yb, -3) == int(np.dot(x.astype(np.int64), y.astype(np.int64)))
+    # products and the sum are carried wider than fp32: 1 + 2^-30 - 1
+    a = np.array([1, 2.0 ** -30, -1], np.float32); one = np.ones(3, np.float32)
+    assert O.dsdot(3, a, 1, one, 1) == 2.0 ** -30 and O.dot(3, a, 1, one, 1) == np.float32(2.0 ** -30)
+    big = np.array([3e20, 3e20], np.float32)            # product overflows fp32, not fp64
+    assert O.dsdot(2, big, 1, big, 1) == 2 * float(np.float32(3e20)) ** 2
+    assert O.dsdot(0, x, 1, y, 1) == 0
+
+
+@pytest.mark.parametrize("dt", DT)
+def test_iamax(dt):
+    assert O.iamax(5, np.array([1, -7, 3, 7, -2], dt), 1) == 1          # first of equal maxima, sign ignored
+    assert O.iamax(5, np.array([0, 0, 0, 0, 0], dt), 1) == 0
+    assert O.iamax(4, np.array([1, np.nan, 5, 2], dt), 1) == 2          # a NaN is never taken ...
+    assert O.iamax(4, np.array([np.nan, 9, 5, 2], dt), 1) == 0          # ... unless it comes first
+    assert O.iamax(3, np.array([1, np.inf, -np.inf], dt), 1) == 1
+    assert O.iamax(0, np.array([1.0], dt), 1) == 0 and O.iamax(3, np.array([1, 2, 3], dt), 0) == 0
+    assert O.iamax(3, np.array([1, 2, 3], dt), -1) == 0
+    x = synth.uniform(24, 1, 5000, dt)
+    assert O.iamax(5000, x, 1) == int(np.argmax(np.abs(x)))
+    xb = synth.strided(x, 3, fill=99.0)                                  # the gaps must not be looked at
+    assert O.iamax(5000, xb, 3) == int(np.argmax(np.abs(x)))
