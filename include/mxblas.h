@@ -125,6 +125,34 @@ int mxb_dasum(mxb_handle_t h, int64_t n, const double* x, int64_t incx, double* 
 int mxb_snrm2(mxb_handle_t h, int64_t n, const float* x, int64_t incx, float* result);
 int mxb_dnrm2(mxb_handle_t h, int64_t n, const double* x, int64_t incx, double* result);
 
+/* ---- rest of the paper's level-1 set (Sec. 6.2.1: copy, swap, rot, rotm, dsdot) and iamax -------
+ * Common errors of the two-vector routines: n < 0 (-1), x NULL (-2), incx == 0 (-3), y NULL (-4),
+ * incy == 0 (-5).  n == 0 launches nothing. */
+
+/* y[i] = x[i]. */
+int mxb_scopy(mxb_handle_t h, int64_t n, const float* x, int64_t incx, float* y, int64_t incy);
+int mxb_dcopy(mxb_handle_t h, int64_t n, const double* x, int64_t incx, double* y, int64_t incy);
+/* x[i] <-> y[i]. */
+int mxb_sswap(mxb_handle_t h, int64_t n, float* x, int64_t incx, float* y, int64_t incy);
+int mxb_dswap(mxb_handle_t h, int64_t n, double* x, int64_t incx, double* y, int64_t incy);
+/* (x[i], y[i]) := (c*x[i] + s*y[i], c*y[i] - s*x[i]). */
+int mxb_srot(mxb_handle_t h, int64_t n, float* x, int64_t incx, float* y, int64_t incy, float c, float s);
+int mxb_drot(mxb_handle_t h, int64_t n, double* x, int64_t incx, double* y, int64_t incy, double c, double s);
+/* (x[i], y[i]) := H (x[i], y[i]).  param is a HOST pointer to 5 values {flag, h11, h21, h12, h22}:
+ * flag -1: H = [h11 h12; h21 h22]; 0: [1 h12; h21 1]; 1: [h11 1; -1 h22]; -2: identity (no launch).
+ * Extra error: param NULL (-6). */
+int mxb_srotm(mxb_handle_t h, int64_t n, float* x, int64_t incx, float* y, int64_t incy, const float* param);
+int mxb_drotm(mxb_handle_t h, int64_t n, double* x, int64_t incx, double* y, int64_t incy, const double* param);
+/* *result (double, device) = sum_i x[i]*y[i] with fp32 inputs, exact fp64 products and fp64 sums.
+ * Errors as mxb_sdot. */
+int mxb_dsdot(mxb_handle_t h, int64_t n, const float* x, int64_t incx, const float* y, int64_t incy, double* result);
+/* *result (int64, device) = 0-based index of the first element of largest |x[i]|, as found by the
+ * sequential scan that only replaces its candidate on a strictly greater magnitude (so NaN is
+ * never chosen unless it is x[0]).  n <= 0 or incx <= 0 writes 0.  Uses the workspace.
+ * Errors: n < 0 (-1), x NULL (-2), result NULL (-4). */
+int mxb_isamax(mxb_handle_t h, int64_t n, const float* x, int64_t incx, int64_t* result);
+int mxb_idamax(mxb_handle_t h, int64_t n, const double* x, int64_t incx, int64_t* result);
+
 /* ---- level 2 (Sec. 6.2.2) ------------------------------------------------------------------ */
 
 /* y = alpha*op(A)*x + beta*y, A m x n (Sec. 2: y[i] += A[i,j]*x[j]; Fig. 7c for op = transpose:

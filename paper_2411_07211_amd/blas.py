@@ -65,12 +65,20 @@ for _p, _t in (("s", _f), ("d", _d)):
     _fn[_p + "dot"] = _sig(f"mxb_{_p}dot", _int, _ptr, _i64, _ptr, _i64, _ptr, _i64, _ptr)
     _fn[_p + "asum"] = _sig(f"mxb_{_p}asum", _int, _ptr, _i64, _ptr, _i64, _ptr)
     _fn[_p + "nrm2"] = _sig(f"mxb_{_p}nrm2", _int, _ptr, _i64, _ptr, _i64, _ptr)
+    _fn[_p + "copy"] = _sig(f"mxb_{_p}copy", _int, _ptr, _i64, _ptr, _i64, _ptr, _i64)
+    _fn[_p + "swap"] = _sig(f"mxb_{_p}swap", _int, _ptr, _i64, _ptr, _i64, _ptr, _i64)
+    _fn[_p + "rot"] = _sig(f"mxb_{_p}rot", _int, _ptr, _i64, _ptr, _i64, _ptr, _i64, _t, _t)
+    _fn[_p + "rotm"] = _sig(f"mxb_{_p}rotm", _int, _ptr, _i64, _ptr, _i64, _ptr, _i64, _ptr)
+    _fn["i" + _p + "amax"] = _sig(f"mxb_i{_p}amax", _int, _ptr, _i64, _ptr, _i64, _ptr)
     _fn[_p + "gemv"] = _sig(f"mxb_{_p}gemv", _int, _ptr, _int, _int, _i64, _i64, _t, _ptr, _i64, _ptr, _i64,
                             _t, _ptr, _i64)
     _fn[_p + "trmv"] = _sig(f"mxb_{_p}trmv", _int, _ptr, _int, _int, _int, _int, _i64, _ptr, _i64, _ptr, _i64)
     _fn[_p + "symv"] = _sig(f"mxb_{_p}symv", _int, _ptr, _int, _int, _i64, _t, _ptr, _i64, _ptr, _i64, _t,
                             _ptr, _i64)
     _fn[_p + "ger"] = _sig(f"mxb_{_p}ger", _int, _ptr, _int, _i64, _i64, _t, _ptr, _i64, _ptr, _i64, _ptr, _i64)
+
+
+_fn["dsdot"] = _sig("mxb_dsdot", _int, _ptr, _i64, _ptr, _i64, _ptr, _i64, _ptr)
 
 
 def _dp(t):
@@ -133,6 +141,28 @@ def mxb_sasum(h, n, x, incx, result): return _fn["sasum"](h, n, _dp(x), incx, _d
 def mxb_dasum(h, n, x, incx, result): return _fn["dasum"](h, n, _dp(x), incx, _dp(result))
 def mxb_snrm2(h, n, x, incx, result): return _fn["snrm2"](h, n, _dp(x), incx, _dp(result))
 def mxb_dnrm2(h, n, x, incx, result): return _fn["dnrm2"](h, n, _dp(x), incx, _dp(result))
+
+
+def mxb_scopy(h, n, x, incx, y, incy): return _fn["scopy"](h, n, _dp(x), incx, _dp(y), incy)
+def mxb_dcopy(h, n, x, incx, y, incy): return _fn["dcopy"](h, n, _dp(x), incx, _dp(y), incy)
+def mxb_sswap(h, n, x, incx, y, incy): return _fn["sswap"](h, n, _dp(x), incx, _dp(y), incy)
+def mxb_dswap(h, n, x, incx, y, incy): return _fn["dswap"](h, n, _dp(x), incx, _dp(y), incy)
+def mxb_srot(h, n, x, incx, y, incy, c, s): return _fn["srot"](h, n, _dp(x), incx, _dp(y), incy, c, s)
+def mxb_drot(h, n, x, incx, y, incy, c, s): return _fn["drot"](h, n, _dp(x), incx, _dp(y), incy, c, s)
+
+
+def _host5(param, ctype):
+    """rotm's parameter block is a HOST array of 5 values."""
+    if param is None:
+        return None
+    return (ctype * 5)(*[float(v) for v in param])
+
+
+def mxb_srotm(h, n, x, incx, y, incy, param): return _fn["srotm"](h, n, _dp(x), incx, _dp(y), incy, _host5(param, _f))
+def mxb_drotm(h, n, x, incx, y, incy, param): return _fn["drotm"](h, n, _dp(x), incx, _dp(y), incy, _host5(param, _d))
+def mxb_dsdot(h, n, x, incx, y, incy, result): return _fn["dsdot"](h, n, _dp(x), incx, _dp(y), incy, _dp(result))
+def mxb_isamax(h, n, x, incx, result): return _fn["isamax"](h, n, _dp(x), incx, _dp(result))
+def mxb_idamax(h, n, x, incx, result): return _fn["idamax"](h, n, _dp(x), incx, _dp(result))
 
 
 # ---- level 2 -----------------------------------------------------------------------------------

@@ -140,7 +140,7 @@ __global__ void __launch_bounds__(kThreads) scal_strided_kernel(int64_t n, int64
 // ---------------------------------------------------------------------------------------------
 // reductions
 
-enum { OP_DOT = 0, OP_ASUM = 1, OP_NRM2 = 2 };
+enum { OP_DOT = 0, OP_ASUM = 1, OP_NRM2 = 2, OP_DSDOT = 3 };
 
 // Constants of Blue's scaled sum of squares for fp64 (as restated by Anderson, "Safe scaling in
 // the level 1 BLAS", 2017): values above kBig are scaled down, values below kSmall are scaled up,
@@ -160,6 +160,12 @@ template <> struct Acc<double, OP_DOT> {
     static constexpr int K = 1;
     double s = 0.0;
     __device__ __forceinline__ void add(double x, double y) { s = fmad(x, y, s); }
+    __device__ __forceinline__ void get(double* o) const { o[0] = s; }
+};
+template <> struct Acc<float, OP_DSDOT> {   // fp32 inputs, exact fp64 products, fp64 sum
+    static constexpr int K = 1;
+    double s = 0.0;
+    __device__ __forceinline__ void add(float x, float y) { s = fmad((double)x, (double)y, s); }
     __device__ __forceinline__ void get(double* o) const { o[0] = s; }
 };
 template <> struct Acc<float, OP_ASUM> {
@@ -226,7 +232,7 @@ __global__ void __launch_bounds__(kThreads) reduce_vec_kernel(int64_t nvec, int6
                                                               double* __restrict__ partials)
 {
     constexpr int VEC = Full<T>::vec;
-    constexpr bool TWO = OP == OP_DOT;
+    constexpr bool TWO = OP == OP_DOT || OP == OP_DSDOT;
     constexpr int U = TWO ? kUnroll : 2 * kUnroll;      // 8 loads in flight per thread either way
     typedef typename VecOf<T, VEC>::type V;
     const V* xv = reinterpret_cast<const V*>(x);
@@ -267,7 +273,7 @@ __global__ void __launch_bounds__(kThreads) reduce_strided_kernel(int64_t n, int
                                                                   const T* __restrict__ y, int64_t incy,
                                                                   double* __restrict__ partials)
 {
-    constexpr bool TWO = OP == OP_DOT;
+    constexpr bool TWO = OP == OP_DOT || OP == OP_DSDOT;
     constexpr int U = kStridedUnroll;
     constexpr int NACC = 4;
     Acc<T, OP> acc[NACC];
@@ -289,9 +295,9 @@ __global__ void __launch_bounds__(kThreads) reduce_strided_kernel(int64_t n, int
 }
 
 // pass 2: one block adds the per-block partials in a fixed order and finishes the result.
-template <typename T, int OP>
+template <typename T, int OP, typename RES>
 __global__ void __launch_bounds__(kThreads) reduce_final_kernel(int nparts, const double* __restrict__ partials,
-                                                                T* __restrict__ result)
+                                                                RES* __restrict__ result)
 {
     constexpr int K = Acc<T, OP>::K;
     __shared__ double slots[kThreads / kWave];
@@ -304,9 +310,9 @@ __global__ void __launch_bounds__(kThreads) reduce_final_kernel(int nparts, cons
     }
     if (threadIdx.x != 0) return;
     if constexpr (OP != OP_NRM2) {
-        *result = (T)v[0];
+        *result = (RES)v[0];
     } else if constexpr (K == 1) {
-        *result = (T)__builtin_sqrt(v[0]);
+        *result = (RES)__builtin_sqrt(v[0]);
     } else {
         double med = v[0], big = v[1], sml = v[2], r;
         if (big > 0.0) {
@@ -385,24 +391,25 @@ int scal(mxb_handle_t h, int64_t n, T alpha, T* x, int64_t incx)
 }
 
 // x, y already checked.  y == nullptr for the one-vector ops.
-template <typename T, int OP>
-int reduce(mxb_handle_t h, int64_t n, const T* x, int64_t incx, const T* y, int64_t incy, T* result)
+template <typename T, int OP, typename RES = T>
+int reduce(mxb_handle_t h, int64_t n, const T* x, int64_t incx, const T* y, int64_t incy, RES* result)
 {
+    constexpr bool TWO = OP == OP_DOT || OP == OP_DSDOT;
     constexpr int VEC = Full<T>::vec;
     constexpr int K = Acc<T, OP>::K;
-    const bool empty = n == 0 || (OP != OP_DOT && incx <= 0);
+    const bool empty = n == 0 || (!TWO && incx <= 0);
     if (empty) {
-        hipLaunchKernelGGL(store_scalar_kernel<T>, dim3(1), dim3(1), 0, h->stream, result, T(0));
+        hipLaunchKernelGGL(store_scalar_kernel<RES>, dim3(1), dim3(1), 0, h->stream, result, RES(0));
         return launch_status();
     }
     const int64_t max_blocks = option(h, MXB_OPT_REDUCE_BLOCKS);
     if (!h->ws || h->ws_bytes < (size_t)max_blocks * K * sizeof(double)) return MXB_ERR_WORKSPACE;
     double* partials = static_cast<double*>(h->ws);
     int64_t grid;
-    const bool contiguous = incx == 1 && aligned16(x) && (OP != OP_DOT || (incy == 1 && aligned16(y)));
+    const bool contiguous = incx == 1 && aligned16(x) && (!TWO || (incy == 1 && aligned16(y)));
     if (contiguous) {
         const int64_t nvec = n / VEC;
-        const int64_t nfull = nvec / (kThreads * (OP == OP_DOT ? kUnroll : 2 * kUnroll));
+        const int64_t nfull = nvec / (kThreads * (TWO ? kUnroll : 2 * kUnroll));
         grid = nfull < 1 ? 1 : (nfull < max_blocks ? nfull : max_blocks);
         hipLaunchKernelGGL((reduce_vec_kernel<T, OP>), dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, nfull,
                            (int)(n % VEC), x, y, partials);
@@ -414,12 +421,12 @@ int reduce(mxb_handle_t h, int64_t n, const T* x, int64_t incx, const T* y, int6
     }
     int st = launch_status();
     if (st != MXB_OK) return st;
-    hipLaunchKernelGGL((reduce_final_kernel<T, OP>), dim3(1), dim3(kThreads), 0, h->stream, (int)grid, partials, result);
+    hipLaunchKernelGGL((reduce_final_kernel<T, OP, RES>), dim3(1), dim3(kThreads), 0, h->stream, (int)grid, partials, result);
     return launch_status();
 }
 
-template <typename T>
-int dot(mxb_handle_t h, int64_t n, const T* x, int64_t incx, const T* y, int64_t incy, T* result)
+template <typename T, int OP = OP_DOT, typename RES = T>
+int dot(mxb_handle_t h, int64_t n, const T* x, int64_t incx, const T* y, int64_t incy, RES* result)
 {
     if (!handle_ok(h)) return MXB_ERR_HANDLE;
     if (n < 0) return -1;
@@ -430,7 +437,7 @@ int dot(mxb_handle_t h, int64_t n, const T* x, int64_t incx, const T* y, int64_t
         if (!y) return -4;
         if (incy == 0) return -5;
     }
-    return reduce<T, OP_DOT>(h, n, x, incx, y, incy, result);
+    return reduce<T, OP, RES>(h, n, x, incx, y, incy, result);
 }
 
 template <typename T, int OP>
@@ -441,6 +448,97 @@ int one_vector(mxb_handle_t h, int64_t n, const T* x, int64_t incx, T* result)
     if (!result) return -4;
     if (n > 0 && incx > 0 && !x) return -2;
     return reduce<T, OP>(h, n, x, incx, nullptr, 0, result);
+}
+
+
+// ---------------------------------------------------------------------------------------------
+// iamax: index of the first element of largest magnitude.  A candidate is (|x|, index); the
+// better of two has the larger magnitude or, at equal magnitude, the smaller index, which makes
+// the result independent of how the elements are split over lanes and blocks.  NaN never compares
+// greater, so it is mapped to -1 (below every magnitude); the reference scan keeps index 0 when
+// x[0] is NaN, and the final kernel restores exactly that.
+struct Cand {
+    double v;
+    int64_t i;
+};
+__device__ __forceinline__ Cand better(Cand a, Cand b) { return (b.v > a.v || (b.v == a.v && b.i < a.i)) ? b : a; }
+
+template <typename T>
+__device__ __forceinline__ Cand cand_of(T x, int64_t i)
+{
+    const double a = (double)(x < T(0) ? -x : x);
+    return Cand{a == a ? a : -1.0, i};
+}
+
+__device__ __forceinline__ Cand block_best(Cand c, Cand* slots)
+{
+    // fold through LDS in a fixed tree (once per block: speed is irrelevant here)
+    slots[threadIdx.x] = c;
+    __syncthreads();
+    for (int w = kThreads / 2; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) slots[threadIdx.x] = better(slots[threadIdx.x], slots[threadIdx.x + w]);
+        __syncthreads();
+    }
+    return slots[0];
+}
+
+template <typename T>
+__global__ void __launch_bounds__(kThreads) iamax_kernel(int64_t n, int64_t nfull, const T* __restrict__ x, int64_t incx,
+                                                         Cand* __restrict__ partials)
+{
+    constexpr int U = kStridedUnroll;
+    __shared__ Cand slots[kThreads];
+    Cand best{-2.0, 0};
+    for (int64_t t = blockIdx.x; t < nfull; t += gridDim.x) {
+        const int64_t base = t * (kThreads * U) + threadIdx.x;
+        T a[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) a[u] = ld_stream(x + (base + u * kThreads) * incx);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < U; ++u) best = better(best, cand_of(a[u], base + u * kThreads));
+    }
+    if (blockIdx.x == gridDim.x - 1)
+        for (int64_t i = nfull * (kThreads * U) + threadIdx.x; i < n; i += kThreads) best = better(best, cand_of(x[i * incx], i));
+    const Cand b = block_best(best, slots);
+    if (threadIdx.x == 0) partials[blockIdx.x] = b;
+}
+
+template <typename T>
+__global__ void __launch_bounds__(kThreads) iamax_final_kernel(int nparts, const Cand* __restrict__ partials,
+                                                               const T* __restrict__ x, int64_t* __restrict__ result)
+{
+    __shared__ Cand slots[kThreads];
+    Cand best{-2.0, 0};
+    for (int p = threadIdx.x; p < nparts; p += kThreads) best = better(best, partials[p]);
+    const Cand b = block_best(best, slots);
+    if (threadIdx.x == 0) {
+        const T x0 = x[0];
+        *result = (x0 != x0) ? 0 : b.i;      // a NaN in front wins the reference scan by default
+    }
+}
+
+template <typename T>
+int iamax(mxb_handle_t h, int64_t n, const T* x, int64_t incx, int64_t* result)
+{
+    if (!handle_ok(h)) return MXB_ERR_HANDLE;
+    if (n < 0) return -1;
+    if (!result) return -4;
+    if (n == 0 || incx <= 0) {
+        hipLaunchKernelGGL(store_scalar_kernel<int64_t>, dim3(1), dim3(1), 0, h->stream, result, (int64_t)0);
+        return launch_status();
+    }
+    if (!x) return -2;
+    const int64_t max_blocks = option(h, MXB_OPT_REDUCE_BLOCKS);
+    if (!h->ws || h->ws_bytes < (size_t)max_blocks * sizeof(Cand)) return MXB_ERR_WORKSPACE;
+    Cand* partials = static_cast<Cand*>(h->ws);
+    const int64_t nfull = n / (kThreads * kStridedUnroll);
+    const int64_t grid = nfull < 1 ? 1 : (nfull < max_blocks ? nfull : max_blocks);
+    hipLaunchKernelGGL(iamax_kernel<T>, dim3((unsigned)grid), dim3(kThreads), 0, h->stream, n, nfull, x, incx, partials);
+    int st = launch_status();
+    if (st != MXB_OK) return st;
+    hipLaunchKernelGGL(iamax_final_kernel<T>, dim3(1), dim3(kThreads), 0, h->stream, (int)grid, partials, x, result);
+    return launch_status();
 }
 
 }  // namespace
@@ -465,4 +563,8 @@ int mxb_snrm2(mxb_handle_t h, int64_t n, const float* x, int64_t incx, float* r)
 { return mxb::one_vector<float, mxb::OP_NRM2>(h, n, x, incx, r); }
 int mxb_dnrm2(mxb_handle_t h, int64_t n, const double* x, int64_t incx, double* r)
 { return mxb::one_vector<double, mxb::OP_NRM2>(h, n, x, incx, r); }
+int mxb_dsdot(mxb_handle_t h, int64_t n, const float* x, int64_t incx, const float* y, int64_t incy, double* r)
+{ return mxb::dot<float, mxb::OP_DSDOT, double>(h, n, x, incx, y, incy, r); }
+int mxb_isamax(mxb_handle_t h, int64_t n, const float* x, int64_t incx, int64_t* r) { return mxb::iamax<float>(h, n, x, incx, r); }
+int mxb_idamax(mxb_handle_t h, int64_t n, const double* x, int64_t incx, int64_t* r) { return mxb::iamax<double>(h, n, x, incx, r); }
 }

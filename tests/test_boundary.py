@@ -24,7 +24,8 @@ def declared_symbols():
 def test_every_declared_symbol_is_exported(B):
     lib = ctypes.CDLL(B.LIB_PATH)
     names = declared_symbols()
-    assert len(names) >= 27
+    assert len(names) >= 38
+    assert "mxb_dsdot" in names and "mxb_isamax" in names and "mxb_idamax" in names
     for n in names:
         assert hasattr(lib, n), f"{n} declared in mxblas.h but not exported"
     for p in "sd":
@@ -68,6 +69,20 @@ def test_argument_errors_name_the_argument(B):
             assert f("dot")(h, 4, P, 1, None, 1, P) == -4
             assert f("dot")(h, 4, P, 1, P, 0, P) == -5
             assert f("dot")(h, 4, P, 1, P, 1, None) == -6
+            for r in ("copy", "swap"):
+                assert f(r)(h, -1, P, 1, P, 1) == -1
+                assert f(r)(h, 4, None, 1, P, 1) == -2
+                assert f(r)(h, 4, P, 0, P, 1) == -3
+                assert f(r)(h, 4, P, 1, None, 1) == -4
+                assert f(r)(h, 4, P, 1, P, 0) == -5
+                assert f(r)(h, 0, None, 0, None, 0) == 0
+            assert f("rot")(h, 4, P, 1, None, 1, 1.0, 0.0) == -4
+            assert f("rotm")(h, 4, P, 1, P, 1, None) == -6
+            assert f("rotm")(h, 4, None, 1, None, 1, [-2, 0, 0, 0, 0]) == 0        # identity flag: no launch
+            assert f("rotm")(h, 4, None, 1, P, 1, [-1, 1, 0, 0, 1]) == -2
+            amax = getattr(B, f"mxb_i{p}amax")
+            assert amax(h, -1, P, 1, P) == -1 and amax(h, 4, None, 1, P) == -2 and amax(h, 4, P, 1, None) == -4
+            assert amax(h, 4, P, 1, P) == B.ERR_WORKSPACE
             for r in ("asum", "nrm2"):
                 assert f(r)(h, -1, P, 1, P) == -1
                 assert f(r)(h, 4, None, 1, P) == -2

@@ -175,3 +175,131 @@ def test_reductions_deterministic_and_grid_invariant(blas, ctx, dt):
             check_close([run_reduce(blas, ctx, dt, "nrm2", n, x, 1)], [r2], [D2], n, f"nrm2 blocks={blocks}")
     finally:
         ctx.set_option(blas.OPT_REDUCE_BLOCKS, 0)
+
+
+# ----------------------------------------------------------------------------- copy, swap, rot, rotm, dsdot, iamax
+@pytest.mark.parametrize("dt", DT)
+@pytest.mark.parametrize("incx,incy", INCS)
+def test_copy_swap_rot_rotm(blas, ctx, dt, incx, incy):
+    p = prefix_of(dt)
+    for n in SIZES:
+        xd, yd = synth.uniform(30, 1, n, dt), synth.uniform(30, 2, n, dt)
+        xb, yb = synth.strided(xd, incx), synth.strided(yd, incy)
+
+        def gaps_untouched(buf, inc):
+            g = np.ones(buf.size, bool); g[::abs(inc)] = False
+            return np.isnan(buf[g]).all()
+
+        # copy
+        rx, ry = xb.copy(), yb.copy(); O.copy(n, rx, incx, ry, incy)
+        dx, dy = to_dev(xb), to_dev(yb)
+        assert blas.routine(p, "copy")(ctx.h, n, dx, incx, dy, incy) == 0
+        assert bits_equal(synth.gather(to_host(dy), n, incy), synth.gather(ry, n, incy)) and gaps_untouched(to_host(dy), incy)
+        assert bits_equal(synth.gather(to_host(dx), n, incx), xd)
+        # swap
+        rx, ry = xb.copy(), yb.copy(); O.swap(n, rx, incx, ry, incy)
+        dx, dy = to_dev(xb), to_dev(yb)
+        assert blas.routine(p, "swap")(ctx.h, n, dx, incx, dy, incy) == 0
+        gx, gy = to_host(dx), to_host(dy)
+        assert bits_equal(synth.gather(gx, n, incx), synth.gather(rx, n, incx)) and bits_equal(synth.gather(gy, n, incy), synth.gather(ry, n, incy))
+        assert gaps_untouched(gx, incx) and gaps_untouched(gy, incy)
+        # rot
+        c, s = dt(np.cos(0.7)), dt(np.sin(0.7))
+        rx, ry = xb.copy(), yb.copy(); D = O.rot(n, rx, incx, ry, incy, c, s, want_D=True)
+        dx, dy = to_dev(xb), to_dev(yb)
+        assert blas.routine(p, "rot")(ctx.h, n, dx, incx, dy, incy, float(c), float(s)) == 0
+        gx, gy = to_host(dx), to_host(dy)
+        check_close(synth.gather(gx, n, incx), synth.gather(rx, n, incx), D[0::2], 1, f"rot x n={n}")
+        check_close(synth.gather(gy, n, incy), synth.gather(ry, n, incy), D[1::2], 1, f"rot y n={n}")
+        assert gaps_untouched(gx, incx) and gaps_untouched(gy, incy)
+        # rotm, every flag
+        for flag in (-1, 0, 1, -2):
+            param = np.array([flag, 0.9, -0.3, 0.4, 1.1], dt)
+            rx, ry = xb.copy(), yb.copy(); D = O.rotm(n, rx, incx, ry, incy, param, want_D=True)
+            dx, dy = to_dev(xb), to_dev(yb)
+            assert blas.routine(p, "rotm")(ctx.h, n, dx, incx, dy, incy, param) == 0
+            gx, gy = to_host(dx), to_host(dy)
+            if flag == -2:
+                assert bits_equal(synth.gather(gx, n, incx), xd) and bits_equal(synth.gather(gy, n, incy), yd)
+            else:
+                check_close(synth.gather(gx, n, incx), synth.gather(rx, n, incx), D[0::2], 1, f"rotm flag={flag} x n={n}")
+                check_close(synth.gather(gy, n, incy), synth.gather(ry, n, incy), D[1::2], 1, f"rotm flag={flag} y n={n}")
+
+
+@pytest.mark.parametrize("dt", DT)
+def test_rot_rotm_integers_bit_exact_and_misaligned(blas, ctx, dt):
+    p = prefix_of(dt)
+    n = (1 << 16) + 11
+    x, y = synth.small_ints(31, 1, n + 3, -9, 9, dt), synth.small_ints(31, 2, n + 3, -9, 9, dt)
+    for xo, yo in ((0, 0), (1, 0), (3, 1)):
+        rx, ry = x.copy(), y.copy(); O.rot(n, rx[xo:], 1, ry[yo:], 1, dt(3), dt(4))
+        dx, dy = to_dev(x), to_dev(y)
+        assert blas.routine(p, "rot")(ctx.h, n, dx[xo:], 1, dy[yo:], 1, 3.0, 4.0) == 0
+        assert bits_equal(to_host(dx), rx) and bits_equal(to_host(dy), ry)
+        param = np.array([-1, 2, 3, 5, 7], dt)
+        rx, ry = x.copy(), y.copy(); O.rotm(n, rx[xo:], 1, ry[yo:], 1, param)
+        dx, dy = to_dev(x), to_dev(y)
+        assert blas.routine(p, "rotm")(ctx.h, n, dx[xo:], 1, dy[yo:], 1, param) == 0
+        assert bits_equal(to_host(dx), rx) and bits_equal(to_host(dy), ry)
+        rx, ry = x.copy(), y.copy(); O.swap(n, rx[xo:], 1, ry[yo:], 1)
+        dx, dy = to_dev(x), to_dev(y)
+        assert blas.routine(p, "swap")(ctx.h, n, dx[xo:], 1, dy[yo:], 1) == 0
+        assert bits_equal(to_host(dx), rx) and bits_equal(to_host(dy), ry)
+    dx = to_dev(x)
+    assert blas.routine(p, "copy")(ctx.h, 0, dx, 1, dx, 1) == 0
+
+
+def test_dsdot(blas, ctx):
+    import torch
+    r = torch.full((1,), float("nan"), dtype=torch.float64, device="cuda")
+    for n in SIZES:
+        for incx, incy in ((1, 1), (2, -3)):
+            x, y = synth.uniform(32, 1, n, np.float32), synth.uniform(32, 2, n, np.float32)
+            xb, yb = synth.strided(x, incx), synth.strided(y, incy)
+            ref, D = O.dsdot(n, xb, incx, yb, incy, want_D=True)
+            assert blas.mxb_dsdot(ctx.h, n, to_dev(xb), incx, to_dev(yb), incy, r) == 0
+            got = to_host(r)
+            assert abs(got[0] - ref) <= 16 * np.finfo(np.float64).eps * np.sqrt(n) * D, f"dsdot n={n}"
+    n = 100003
+    x, y = synth.small_ints(32, 1, n, -99, 99, np.float32), synth.small_ints(32, 2, n, -99, 99, np.float32)
+    assert blas.mxb_dsdot(ctx.h, n, to_dev(x), 1, to_dev(y), 1, r) == 0
+    assert to_host(r)[0] == O.dsdot(n, x, 1, y, 1)
+    big = np.full(1000, 3e20, np.float32)                # products overflow fp32 but not fp64
+    assert blas.mxb_dsdot(ctx.h, 1000, to_dev(big), 1, to_dev(big), 1, r) == 0
+    assert to_host(r)[0] == O.dsdot(1000, big, 1, big, 1)
+    assert blas.mxb_dsdot(ctx.h, 0, to_dev(big), 1, to_dev(big), 1, r) == 0 and to_host(r)[0] == 0
+
+
+@pytest.mark.parametrize("dt", DT)
+def test_iamax(blas, ctx, dt):
+    import torch
+    f = blas.routine("i" + prefix_of(dt), "amax") if False else getattr(blas, f"mxb_i{prefix_of(dt)}amax")
+    r = torch.full((1,), -7, dtype=torch.int64, device="cuda")
+
+    def gpu(n, xb, incx, off=0):
+        dx = to_dev(xb)
+        assert f(ctx.h, n, dx[off:], incx, r) == 0
+        return int(to_host(r)[0])
+
+    for n in SIZES:
+        x = synth.uniform(33, 1, n, dt)
+        assert gpu(n, x, 1) == O.iamax(n, x, 1)
+        xb = synth.strided(x, 3, fill=99.0)
+        assert gpu(n, xb, 3) == O.iamax(n, xb, 3)
+        # many equal maxima: the first one wins, wherever the block boundaries fall
+        t = synth.small_ints(33, 2, n, -3, 3, dt)
+        assert gpu(n, t, 1) == O.iamax(n, t, 1)
+    for case in ([1, -7, 3, 7, -2], [0, 0, 0], [1, np.nan, 5, 2], [np.nan, 9, 5, 2], [1, np.inf, -np.inf], [np.nan, np.nan]):
+        a = np.array(case, dt)
+        assert gpu(a.size, a, 1) == O.iamax(a.size, a, 1), case
+    x = synth.uniform(33, 3, 100000, dt); x[77777] = np.nan; x[5] = -3.0
+    assert gpu(100000, x, 1) == O.iamax(100000, x, 1) == 5
+    assert gpu(99990, x, 1, off=1) == O.iamax(99990, x[1:], 1)      # misaligned base
+    assert gpu(0, x, 1) == 0 and gpu(10, x, 0) == 0 and gpu(10, x, -1) == 0
+    try:
+        for blocks in (1, 3, 2048):
+            ctx.set_option(blas.OPT_REDUCE_BLOCKS, blocks)
+            t = synth.small_ints(33, 4, (1 << 20) + 3, -3, 3, dt)
+            assert gpu(t.size, t, 1) == O.iamax(t.size, t, 1)
+    finally:
+        ctx.set_option(blas.OPT_REDUCE_BLOCKS, 0)
