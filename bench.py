@@ -50,7 +50,7 @@ class Suite:
         self.B, self.ctx, self.torch = blas, ctx, torch
         dev = ctx.device
         g = torch.Generator(device=dev)
-        self.calls = []            # (name, kernel family, fn(step_index), algorithmic bytes)
+        self.calls = []            # (name, kernel family, fn(step_index), algorithmic bytes, untimed set-up or None)
         f32, f64 = torch.float32, torch.float64
 
         def uni(n, dtype, seed):
@@ -126,10 +126,11 @@ class Suite:
         for uname, uplo in (("u", B.UPPER), ("l", B.LOWER)):
             for dname, diag in (("n", B.NON_UNIT), ("u", B.UNIT)):
                 def trmv(s, uplo=uplo, diag=diag):
-                    xt.copy_(x0)    # x := T x would blow up over repeated steps; restart from the same x
                     return B.mxb_strmv(h, B.ROW_MAJOR, uplo, B.NO_TRANS, diag, NS, nextA(A32), NS, xt, 1)
                 nel = tri if diag == B.NON_UNIT else tri - NS
-                self.add(f"strmv_{uname}{dname}_{NS}", "trmv", trmv, 4 * (nel + 2 * NS))
+                # x := T x would blow up over repeated steps: restart from the same x before every call
+                # (a torch copy, outside the call's own events)
+                self.add(f"strmv_{uname}{dname}_{NS}", "trmv", trmv, 4 * (nel + 2 * NS), pre=lambda: xt.copy_(x0))
         self.add(f"ssymv_l_{NS}", "symv", lambda s: B.mxb_ssymv(h, B.ROW_MAJOR, B.LOWER, NS, 0.52, nextA(A32), NS, xs, 1, 0.49, ys, 1),
                  4 * (tri + 3 * NS))
         self.add(f"sger_{NS}", "ger", lambda s: B.mxb_sger(h, B.ROW_MAJOR, NS, NS, 1e-3, xs, 1, x0, 1, nextA(A32), NS),
@@ -138,13 +139,23 @@ class Suite:
 
         # ---- bandwidth probes: not part of a step, selectable with --only ----------------------
         nb = NS * NS * 4
+        reset = lambda: xt.copy_(x0)
         self.extra = [
-            ("probe_copy", "probe", lambda s: B.mxb_probe_copy(h, nb, A32[1], A32[2]), 2 * nb),
-            ("probe_read", "probe", lambda s: B.mxb_probe_read(h, nb, nextA(A32)), nb),
+            ("probe_copy", "probe", lambda s: B.mxb_probe_copy(h, nb, A32[1], A32[2]), 2 * nb, None),
+            ("probe_read", "probe", lambda s: B.mxb_probe_read(h, nb, nextA(A32)), nb, None),
+            # the variants of the structured routines that the step does not contain
+            (f"strmv_ut_{NS}", "trmv_t", lambda s: B.mxb_strmv(h, B.ROW_MAJOR, B.UPPER, B.TRANS, B.NON_UNIT, NS, nextA(A32), NS, xt, 1),
+             4 * (tri + 2 * NS), reset),
+            (f"strmv_lt_{NS}", "trmv_t", lambda s: B.mxb_strmv(h, B.ROW_MAJOR, B.LOWER, B.TRANS, B.NON_UNIT, NS, nextA(A32), NS, xt, 1),
+             4 * (tri + 2 * NS), reset),
+            (f"ssymv_u_{NS}", "symv", lambda s: B.mxb_ssymv(h, B.ROW_MAJOR, B.UPPER, NS, 0.52, nextA(A32), NS, xs, 1, 0.49, ys, 1),
+             4 * (tri + 3 * NS), None),
+            (f"dsymv_l_{NS}", "symv", lambda s: B.mxb_dsymv(h, B.ROW_MAJOR, B.LOWER, NS, 0.52, nextA(A64), lda, xd, 1, 0.49, yd, 1),
+             8 * (tri + 3 * NS), None),
         ]
 
-    def add(self, name, family, fn, nbytes):
-        self.calls.append((name, family, fn, int(nbytes)))
+    def add(self, name, family, fn, nbytes, pre=None):
+        self.calls.append((name, family, fn, int(nbytes), pre))
 
 
 def cpu_baseline(torch):
@@ -224,7 +235,7 @@ def main():
     suite = Suite(B, ctx, torch, scale=args.scale)
     calls = suite.calls
     if args.list:
-        for name, fam, _, nb in calls:
+        for name, fam, _, nb, _ in calls + suite.extra:
             print(f"{name:32s} {fam:8s} {nb / GiB:8.3f} GiB")
         return
     if args.only:
@@ -235,7 +246,9 @@ def main():
             sys.exit(2)
 
     def step(s, events=None):
-        for k, (name, fam, fn, nb) in enumerate(calls):
+        for k, (name, fam, fn, nb, pre) in enumerate(calls):
+            if pre is not None:
+                pre()
             if events is not None:
                 events[k][0].record()
             st = fn(s)
@@ -260,7 +273,7 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / K
     step_bytes = sum(c[3] for c in calls)
     per = {}
-    for k, (name, fam, fn, nb) in enumerate(calls):
+    for k, (name, fam, fn, nb, pre) in enumerate(calls):
         ts = sorted(ev[s][k][0].elapsed_time(ev[s][k][1]) for s in range(K))    # ms
         avg = sum(ts) / len(ts)
         per[name] = {"bytes": nb, "us_avg": round(avg * 1e3, 2), "us_min": round(ts[0] * 1e3, 2),

@@ -87,10 +87,11 @@ typedef enum {
     MXB_OPT_ROWDOT_BLOCKS_PER_CU = 3,
     MXB_OPT_COLACC_TARGET_BLOCKS = 4, /* column-accumulate kernels: blocks to aim for when splitting rows */
     MXB_OPT_COLACC_MIN_ROWS = 5,    /* ... and the fewest rows one block may take */
-    MXB_OPT_SYMV_TARGET_BLOCKS = 6, /* symv: blocks to aim for over the whole triangle */
+    MXB_OPT_SYMV_TARGET_BLOCKS = 6, /* symv and transposed trmv (triangle sweep): grid size */
     MXB_OPT_GER_ROWS_PER_BLOCK = 7,
-    MXB_OPT_SYMV_TILE_VECTORS = 8,  /* symv: 128-bit vectors per lane and row (1, 2 or 4); tile = 256 lanes x this */
-    MXB_OPT_COUNT = 9
+    MXB_OPT_SYMV_TILE_VECTORS = 8,  /* triangle sweep: 128-bit vectors per lane and row (1, 2 or 4); tile = 256 lanes x this */
+    MXB_OPT_TRI_DIAG_WEIGHT = 9,    /* triangle sweep: cost of a row that crosses the diagonal, in quarters of a row that does not (1..8) */
+    MXB_OPT_COUNT = 10
 } mxb_option_t;
 int mxb_set_option(mxb_handle_t h, int option, int64_t value);
 int64_t mxb_get_option(mxb_handle_t h, int option);

@@ -4,6 +4,7 @@
 #include "common.hpp"
 #include "options.hpp"
 #include "plan.hpp"
+#include "trisweep.hpp"
 
 namespace mxb {
 namespace {
@@ -112,13 +113,12 @@ size_t mxb_workspace_bytes(int routine, int elem_size, int64_t m, int64_t n)
     const int full = 16 / elem_size;
     auto colacc_bound = [&](int64_t rows, int64_t cols) {
         size_t b = 0;
-        for (int vec : {1, full})
-            for (bool tri : {false, true}) {
-                const ColaccPlan p = colacc_plan(rows, cols, elem_size, vec, tri, option_default(MXB_OPT_COLACC_TARGET_BLOCKS),
-                                                 kColaccNarrowBlocks, option_default(MXB_OPT_COLACC_MIN_ROWS));
-                const size_t need = p.nparts > 1 ? (size_t)p.nparts * (size_t)cols * (size_t)elem_size : 0;
-                b = need > b ? need : b;
-            }
+        for (int vec : {1, full}) {
+            const ColaccPlan p = colacc_plan(rows, cols, elem_size, vec, option_default(MXB_OPT_COLACC_TARGET_BLOCKS),
+                                             kColaccNarrowBlocks, option_default(MXB_OPT_COLACC_MIN_ROWS));
+            const size_t need = p.nparts > 1 ? (size_t)p.nparts * (size_t)cols * (size_t)elem_size : 0;
+            b = need > b ? need : b;
+        }
         return align_up(b, 256);
     };
     switch (routine) {
@@ -129,16 +129,11 @@ size_t mxb_workspace_bytes(int routine, int elem_size, int64_t m, int64_t n)
             const size_t a = colacc_bound(m, n), b = colacc_bound(n, m);
             return a > b ? a : b;
         }
-        case MXB_TRMV: return align_up((size_t)n * elem_size, 256) + colacc_bound(n, n);
-        case MXB_SYMV: {
-            size_t b = 0;
-            for (int vec : {1, full}) {
-                const SymvPlan p = symv_plan(n, vec, false, option_default(MXB_OPT_SYMV_TARGET_BLOCKS));
-                const size_t need = ((size_t)p.ntiles * 4 + (size_t)p.max_groups) * (size_t)n * (size_t)elem_size;
-                b = need > b ? need : b;
-            }
-            return align_up(b, 256);
+        case MXB_TRMV: {
+            const size_t a = align_up((size_t)n * elem_size, 256), b = tri_workspace_bound(n, elem_size);
+            return a > b ? a : b;
         }
+        case MXB_SYMV: return tri_workspace_bound(n, elem_size);
         default: return 0;
     }
 }

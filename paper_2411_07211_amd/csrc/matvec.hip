@@ -13,13 +13,15 @@
 //    is wave-uniform and comes through the scalar path.  Slabs are combined by a second kernel
 //    that adds the per-slab partial vectors in slab order and applies alpha/beta (no atomics).
 //
-// trmv runs the same kernels with MODE = upper/lower: the column (row) range of every tile is
-// clipped to the triangle at tile granularity (the paper's bound rounding) and the elements of a
-// straddling 128-bit load that lie outside the triangle are discarded with a select, never by
-// multiplying with zero, so that NaN/Inf stored there cannot leak into the result.
+// trmv without transposition runs the row-dot kernel with MODE = upper/lower: the column range
+// of every tile is clipped to the triangle at tile granularity (the paper's bound rounding) and
+// the elements of a straddling 128-bit load that lie outside the triangle are discarded with a
+// select, never by multiplying with zero, so that NaN/Inf stored there cannot leak into the
+// result.  Transposed trmv is the triangle sweep of trisweep.hip.
 #include "common.hpp"
 #include "options.hpp"
 #include "plan.hpp"
+#include "trisweep.hpp"
 
 namespace mxb {
 namespace {
@@ -227,7 +229,7 @@ constexpr int kColaccThreads = 256;
 //    sequential stream, which is what HBM serves fastest.
 //  WR == 4 (narrow matrices, CV == 1): one wavefront spans the row, the 4 wavefronts of a block
 //    interleave over the rows of a contiguous slab and are folded through LDS.
-template <typename T, int VEC, int CV, int WR, int MODE, bool UNIT>
+template <typename T, int VEC, int CV, int WR>
 __global__ void __launch_bounds__(kColaccThreads) colacc_kernel(const ColaccArgs<T> p)
 {
     typedef typename VecOf<T, VEC>::type V;
@@ -241,7 +243,6 @@ __global__ void __launch_bounds__(kColaccThreads) colacc_kernel(const ColaccArgs
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wc = wave % WC, wr = wave / WC;
     const int64_t cblock0 = (int64_t)blockIdx.x * (CV * SPAN);
-    const int64_t cblock1 = imin(p.N, cblock0 + CV * SPAN);     // exclusive
     const int64_t c = cblock0 + (int64_t)(wc * kWave + lane) * VEC;
     bool col_ok[CV];
 #pragma unroll
@@ -249,19 +250,15 @@ __global__ void __launch_bounds__(kColaccThreads) colacc_kernel(const ColaccArgs
 
     // Rows are visited in batches of U: rows r0 + u*rstep (u < U), then r0 += radvance.
     int64_t r0, rstep, radvance, rend = p.M;
-    if (MODE == MODE_UPPER) rend = imin(rend, cblock1);                  // rows i <= j
     if (WR == 1) {
         // wide shape: batch = U adjacent rows; the batches are dealt to the row groups cyclically
         rstep = 1;
         radvance = (int64_t)gridDim.y * U;
         r0 = (int64_t)blockIdx.y * U;
-        if (MODE == MODE_LOWER && r0 + U <= cblock0)                     // rows i >= j: skip batches above the tile
-            r0 += (cblock0 - U + 1 - r0 + radvance - 1) / radvance * radvance;
     } else {
         // narrow shape: a contiguous slab per block, its rows interleaved over the 4 wavefronts
         int64_t rlo = (int64_t)blockIdx.y * p.rows_per_block;
         rend = imin(rend, rlo + p.rows_per_block);
-        if (MODE == MODE_LOWER) rlo = imax(rlo, cblock0);
         rstep = WR;
         radvance = (int64_t)U * WR;
         r0 = rlo + wr;
@@ -295,8 +292,7 @@ __global__ void __launch_bounds__(kColaccThreads) colacc_kernel(const ColaccArgs
             for (int v = 0; v < CV; ++v)
 #pragma unroll
                 for (int k = 0; k < VEC; ++k)
-                    acc[v][k] = fmad(tri_value<T, MODE, UNIT>(a[u][v][k], r0 + (int64_t)u * rstep, c + v * SPAN + k), xi[u],
-                                              acc[v][k]);
+                    acc[v][k] = fmad(a[u][v][k], xi[u], acc[v][k]);
     }
     for (; r0 < rend; r0 += rstep) {   // the one ragged batch
         const T xi = p.x[r0 * p.incx];
@@ -304,7 +300,7 @@ __global__ void __launch_bounds__(kColaccThreads) colacc_kernel(const ColaccArgs
         for (int v = 0; v < CV; ++v) {
             const V a = ld_stream(reinterpret_cast<const V*>(acol[v] + r0 * p.lda));
 #pragma unroll
-            for (int k = 0; k < VEC; ++k) acc[v][k] = fmad(tri_value<T, MODE, UNIT>(a[k], r0, c + v * SPAN + k), xi, acc[v][k]);
+            for (int k = 0; k < VEC; ++k) acc[v][k] = fmad(a[k], xi, acc[v][k]);
         }
     }
 
@@ -448,44 +444,32 @@ int launch_rowdot(mxb_handle_t h, RowdotArgs<T> a, int mode, bool unit)
     return launch_status();
 }
 
-template <typename T, int VEC, int MODE, bool UNIT>
+template <typename T, int VEC>
 void launch_colacc_inst(mxb_handle_t h, const ColaccArgs<T>& a, const ColaccPlan& pl)
 {
     const dim3 grid((unsigned)pl.col_tiles, (unsigned)pl.nparts);
     const dim3 block(kColaccThreads);
-    if (pl.wr == 4) hipLaunchKernelGGL((colacc_kernel<T, VEC, 1, 4, MODE, UNIT>), grid, block, 0, h->stream, a);
-    else if (pl.cv == 4) hipLaunchKernelGGL((colacc_kernel<T, VEC, 4, 1, MODE, UNIT>), grid, block, 0, h->stream, a);
-    else if (pl.cv == 2) hipLaunchKernelGGL((colacc_kernel<T, VEC, 2, 1, MODE, UNIT>), grid, block, 0, h->stream, a);
-    else hipLaunchKernelGGL((colacc_kernel<T, VEC, 1, 1, MODE, UNIT>), grid, block, 0, h->stream, a);
+    if (pl.wr == 4) hipLaunchKernelGGL((colacc_kernel<T, VEC, 1, 4>), grid, block, 0, h->stream, a);
+    else if (pl.cv == 4) hipLaunchKernelGGL((colacc_kernel<T, VEC, 4, 1>), grid, block, 0, h->stream, a);
+    else if (pl.cv == 2) hipLaunchKernelGGL((colacc_kernel<T, VEC, 2, 1>), grid, block, 0, h->stream, a);
+    else hipLaunchKernelGGL((colacc_kernel<T, VEC, 1, 1>), grid, block, 0, h->stream, a);
 }
 
-// ws / ws_bytes: workspace region this call may use for partials.
 template <typename T>
-int launch_colacc(mxb_handle_t h, ColaccArgs<T> a, int mode, bool unit, void* ws, size_t ws_bytes)
+int launch_colacc(mxb_handle_t h, ColaccArgs<T> a)
 {
     constexpr int FV = Full<T>::vec;
     const bool vec = aligned16(a.A) && (a.lda % FV) == 0 && (a.N % FV) == 0;
-    const ColaccPlan pl = colacc_plan(a.M, a.N, (int)sizeof(T), vec ? FV : 1, mode != MODE_GENERAL, option(h, MXB_OPT_COLACC_TARGET_BLOCKS),
+    const ColaccPlan pl = colacc_plan(a.M, a.N, (int)sizeof(T), vec ? FV : 1, option(h, MXB_OPT_COLACC_TARGET_BLOCKS),
                                       colacc_narrow_target(h), option(h, MXB_OPT_COLACC_MIN_ROWS));
     a.rows_per_block = pl.rows_per_block;
     a.partials = nullptr;
     if (pl.nparts > 1) {
-        if (!ws || ws_bytes < (size_t)pl.nparts * (size_t)a.N * sizeof(T)) return MXB_ERR_WORKSPACE;
-        a.partials = static_cast<T*>(ws);
+        if (!h->ws || h->ws_bytes < (size_t)pl.nparts * (size_t)a.N * sizeof(T)) return MXB_ERR_WORKSPACE;
+        a.partials = static_cast<T*>(h->ws);
     }
-#define MXB_COLACC(VEC_)                                                                                   \
-    switch (mode) {                                                                                        \
-        case MODE_GENERAL: launch_colacc_inst<T, VEC_, MODE_GENERAL, false>(h, a, pl); break;               \
-        case MODE_UPPER:                                                                                   \
-            if (unit) launch_colacc_inst<T, VEC_, MODE_UPPER, true>(h, a, pl);                              \
-            else launch_colacc_inst<T, VEC_, MODE_UPPER, false>(h, a, pl);                                  \
-            break;                                                                                         \
-        default:                                                                                           \
-            if (unit) launch_colacc_inst<T, VEC_, MODE_LOWER, true>(h, a, pl);                              \
-            else launch_colacc_inst<T, VEC_, MODE_LOWER, false>(h, a, pl);                                  \
-    }
-    if (vec) { MXB_COLACC(FV) } else { MXB_COLACC(1) }
-#undef MXB_COLACC
+    if (vec) launch_colacc_inst<T, FV>(h, a, pl);
+    else launch_colacc_inst<T, 1>(h, a, pl);
     int st = launch_status();
     if (st != MXB_OK || pl.nparts == 1) return st;
     hipLaunchKernelGGL(colacc_combine_kernel<T>, dim3((unsigned)ceil_div(a.N, kWave)), dim3(kCombineGroups * kWave), 0,
@@ -531,7 +515,7 @@ int gemv(mxb_handle_t h, int layout, int trans, int64_t m, int64_t n, T alpha, c
         return launch_rowdot(h, a, MODE_GENERAL, false);
     }
     ColaccArgs<T> a{rows, cols, A, lda, x0, incx, y0, incy, alpha, beta, nullptr, 0};
-    return launch_colacc(h, a, MODE_GENERAL, false, h->ws, h->ws_bytes);
+    return launch_colacc(h, a);
 }
 
 template <typename T>
@@ -555,19 +539,19 @@ int trmv(mxb_handle_t h, int layout, int uplo, int trans, int diag, int64_t n, c
     const int mode = upper ? MODE_UPPER : MODE_LOWER;
     const bool unit = diag == MXB_UNIT;
 
+    T* x0 = vec_base(x, n, incx);
+    // transposed: the triangle sweep reads x, its combine pass writes x afterwards: no copy needed
+    if (!no_trans) return trisweep_trmv_t<T>(h, upper, unit, n, A, lda, x0, incx);
+
+    // not transposed: rows are written while other blocks still read x, so work from a snapshot
     const size_t snap_bytes = align_up((size_t)n * sizeof(T), 256);
     if (!h->ws || h->ws_bytes < snap_bytes) return MXB_ERR_WORKSPACE;
     T* snap = static_cast<T*>(h->ws);
-    T* x0 = vec_base(x, n, incx);
     hipLaunchKernelGGL(gather_kernel<T>, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, h->stream, n, x0, incx, snap);
     int st = launch_status();
     if (st != MXB_OK) return st;
-    if (no_trans) {
-        RowdotArgs<T> a{n, n, A, lda, snap, 1, x0, incx, T(1), T(0), 0, 0};
-        return launch_rowdot(h, a, mode, unit);
-    }
-    ColaccArgs<T> a{n, n, A, lda, snap, 1, x0, incx, T(1), T(0), nullptr, 0};
-    return launch_colacc(h, a, mode, unit, static_cast<char*>(h->ws) + snap_bytes, h->ws_bytes - snap_bytes);
+    RowdotArgs<T> a{n, n, A, lda, snap, 1, x0, incx, T(1), T(0), 0, 0};
+    return launch_rowdot(h, a, mode, unit);
 }
 
 }  // namespace

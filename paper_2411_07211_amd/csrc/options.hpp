@@ -13,9 +13,10 @@ inline int64_t option_default(int o)
         case MXB_OPT_ROWDOT_BLOCKS_PER_CU: return 2;
         case MXB_OPT_COLACC_TARGET_BLOCKS: return 192;
         case MXB_OPT_COLACC_MIN_ROWS: return 64;
-        case MXB_OPT_SYMV_TARGET_BLOCKS: return 512;
+        case MXB_OPT_SYMV_TARGET_BLOCKS: return 192;   // grid of the triangle sweep (symv, transposed trmv)
         case MXB_OPT_GER_ROWS_PER_BLOCK: return 8;     // one batch of 8 rows per block: short read-then-write bursts stream best
         case MXB_OPT_SYMV_TILE_VECTORS: return 0;     // 0: chosen from n
+        case MXB_OPT_TRI_DIAG_WEIGHT: return 3;
         default: return 0;
     }
 }

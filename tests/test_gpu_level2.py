@@ -114,7 +114,7 @@ def test_gemv_deterministic_and_geometry_invariant(blas, ctx, dt):
             for opts in ({}, {}, {blas.OPT_ROWDOT_XCHUNK: 256, blas.OPT_COLACC_TARGET_BLOCKS: 64},
                          {blas.OPT_ROWDOT_XCHUNK: 1024, blas.OPT_ROWDOT_BLOCKS_PER_CU: 1, blas.OPT_COLACC_TARGET_BLOCKS: 4096,
                           blas.OPT_COLACC_MIN_ROWS: 8}):
-                for o in range(8):
+                for o in range(10):
                     ctx.set_option(o, 0)
                 for o, v in opts.items():
                     ctx.set_option(o, v)
@@ -124,7 +124,7 @@ def test_gemv_deterministic_and_geometry_invariant(blas, ctx, dt):
                 check_close(outs[-1], ref, D, lenx, f"gemv trans={trans} opts={opts}")
             assert outs[0].tobytes() == outs[1].tobytes(), "same launch geometry must give the same bits"
     finally:
-        for o in range(8):
+        for o in range(10):
             ctx.set_option(o, 0)
 
 
@@ -166,6 +166,18 @@ def test_trmv(blas, ctx, dt, layout, uplo, trans, diag):
     trmv_case(blas, ctx, dt, layout, uplo, trans, diag, 515, 1, 2)
     trmv_case(blas, ctx, dt, layout, uplo, trans, diag, 515, 0, -1)
     trmv_case(blas, ctx, dt, layout, uplo, trans, diag, 1536, 0, 1, ints=True)
+    # the triangle sweep behind the transposed product with wider tiles and other grid sizes
+    try:
+        for cv, n in ((2, 4100), (4, 6000)):
+            ctx.set_option(blas.OPT_SYMV_TILE_VECTORS, cv)
+            trmv_case(blas, ctx, dt, layout, uplo, trans, diag, n, 0, 1)
+        ctx.set_option(blas.OPT_SYMV_TILE_VECTORS, 0)
+        for tb in (1, 7, 1000):
+            ctx.set_option(blas.OPT_SYMV_TARGET_BLOCKS, tb)
+            trmv_case(blas, ctx, dt, layout, uplo, trans, diag, 2310, 2, 1)
+    finally:
+        ctx.set_option(blas.OPT_SYMV_TARGET_BLOCKS, 0)
+        ctx.set_option(blas.OPT_SYMV_TILE_VECTORS, 0)
 
 
 # ----------------------------------------------------------------------------- symv
@@ -210,8 +222,14 @@ def test_symv(blas, ctx, dt, layout, uplo):
             ctx.set_option(blas.OPT_SYMV_TARGET_BLOCKS, tb)
             symv_case(blas, ctx, dt, layout, uplo, 2310, 1.5, 0.5, 2, 1, 1)
             symv_case(blas, ctx, dt, layout, uplo, 5000, 1.5, 0.5, 0, 1, 1)
+        # wider tiles (2 and 4 vectors per lane) over several row bands, ragged last tile included
+        ctx.set_option(blas.OPT_SYMV_TARGET_BLOCKS, 0)
+        for cv, n in ((2, 4100), (4, 4096), (4, 9000)):
+            ctx.set_option(blas.OPT_SYMV_TILE_VECTORS, cv)
+            symv_case(blas, ctx, dt, layout, uplo, n, 1.5, 0.5, 0, 1, 1)
     finally:
         ctx.set_option(blas.OPT_SYMV_TARGET_BLOCKS, 0)
+        ctx.set_option(blas.OPT_SYMV_TILE_VECTORS, 0)
 
 
 # ----------------------------------------------------------------------------- ger
