@@ -98,6 +98,15 @@ def _declare(lib):
         f = getattr(lib, f"oracle_{p}ger")
         f.argtypes = [_int, _i64, _i64, ct, _ptr, _i64, _ptr, _i64, _ptr, _i64, _ptr]
         f.restype = None
+        f = getattr(lib, f"oracle_{p}syr")
+        f.argtypes = [_int, _int, _i64, ct, _ptr, _i64, _ptr, _i64, _ptr]
+        f.restype = None
+        f = getattr(lib, f"oracle_{p}syr2")
+        f.argtypes = [_int, _int, _i64, ct, _ptr, _i64, _ptr, _i64, _ptr, _i64, _ptr]
+        f.restype = None
+        f = getattr(lib, f"oracle_{p}trsv")
+        f.argtypes = [_int, _int, _int, _int, _i64, _ptr, _i64, _ptr, _i64, _ptr]
+        f.restype = None
 
 
 def _declare_mixed(lib):
@@ -216,6 +225,32 @@ def ger(layout, m, n, alpha, x, incx, y, incy, A, lda, want_D=False):
     D = np.zeros(max(m * n, 0), np.float64) if want_D else None
     getattr(_load(), f"oracle_{p}ger")(layout, m, n, alpha, _p(x), incx, _p(y), incy, _p(A),
                                        lda, _p(D))
+    return D
+
+
+def syr(layout, uplo, n, alpha, x, incx, A, lda, want_D=False):
+    p = _same(A, x)
+    _mat_need(A, layout, n, n, lda); _need(x, n, incx, "x")
+    D = np.zeros(max(n * n, 0), np.float64) if want_D else None
+    getattr(_load(), f"oracle_{p}syr")(layout, uplo, n, alpha, _p(x), incx, _p(A), lda, _p(D))
+    return D
+
+
+def syr2(layout, uplo, n, alpha, x, incx, y, incy, A, lda, want_D=False):
+    p = _same(A, x, y)
+    _mat_need(A, layout, n, n, lda); _need(x, n, incx, "x"); _need(y, n, incy, "y")
+    D = np.zeros(max(n * n, 0), np.float64) if want_D else None
+    getattr(_load(), f"oracle_{p}syr2")(layout, uplo, n, alpha, _p(x), incx, _p(y), incy, _p(A),
+                                        lda, _p(D))
+    return D
+
+
+def trsv(layout, uplo, trans, diag, n, A, lda, x, incx, want_D=False):
+    p = _same(A, x)
+    _mat_need(A, layout, n, n, lda); _need(x, n, incx, "x")
+    D = np.zeros(max(n, 0), np.float64) if want_D else None
+    getattr(_load(), f"oracle_{p}trsv")(layout, uplo, trans, diag, n, _p(A), lda, _p(x), incx,
+                                        _p(D))
     return D
 
 

@@ -215,6 +215,83 @@ void FN(ger)(int layout, int64_t m, int64_t n, T alpha, const T* x, int64_t incx
     }
 }
 
+/* ---- rest of the level-2 set of Sec. 6.2.2 (syr, syr2, trsv) ---------------------------------- */
+
+/* syr: A[i][j] += alpha * x[i] * x[j] for (i, j) in the uplo triangle of the n x n matrix A;
+ * nothing outside the triangle is read or written.  D (if given) is n*n, D[i*n + j], 0 outside. */
+void FN(syr)(int layout, int uplo, int64_t n, T alpha, const T* x, int64_t incx, T* A, int64_t lda,
+             double* D)
+{
+    if (n <= 0 || alpha == (T)0) return;
+    for (int64_t i = 0; i < n; ++i)
+        for (int64_t j = 0; j < n; ++j) {
+            if (D) D[i * n + j] = 0;
+            if (!FN(in_tri)(uplo, i, j)) continue;
+            const T xi = x[FN(pos)(i, n, incx)], xj = x[FN(pos)(j, n, incx)];
+            T* ap = layout == ORACLE_ROW_MAJOR ? &A[i * lda + j] : &A[j * lda + i];
+            const acc_t t = (acc_t)alpha * (acc_t)xi * (acc_t)xj;
+            if (D) D[i * n + j] = fabs((double)*ap) + fabs((double)t);
+            *ap = (T)((acc_t)*ap + t);
+        }
+}
+
+/* syr2: A[i][j] += alpha * x[i] * y[j] + alpha * y[i] * x[j] for (i, j) in the uplo triangle. */
+void FN(syr2)(int layout, int uplo, int64_t n, T alpha, const T* x, int64_t incx, const T* y,
+              int64_t incy, T* A, int64_t lda, double* D)
+{
+    if (n <= 0 || alpha == (T)0) return;
+    for (int64_t i = 0; i < n; ++i)
+        for (int64_t j = 0; j < n; ++j) {
+            if (D) D[i * n + j] = 0;
+            if (!FN(in_tri)(uplo, i, j)) continue;
+            const T xi = x[FN(pos)(i, n, incx)], xj = x[FN(pos)(j, n, incx)];
+            const T yi = y[FN(pos)(i, n, incy)], yj = y[FN(pos)(j, n, incy)];
+            T* ap = layout == ORACLE_ROW_MAJOR ? &A[i * lda + j] : &A[j * lda + i];
+            const acc_t t1 = (acc_t)alpha * (acc_t)xi * (acc_t)yj;
+            const acc_t t2 = (acc_t)alpha * (acc_t)yi * (acc_t)xj;
+            if (D) D[i * n + j] = fabs((double)*ap) + fabs((double)t1) + fabs((double)t2);
+            *ap = (T)((acc_t)*ap + t1 + t2);
+        }
+}
+
+/* trsv: solve op(T) z = b for z, where T is the uplo triangle of the n x n matrix A (unit: the
+ * diagonal is taken as 1 and never read) and b is the x passed in; z overwrites x.  Plain
+ * substitution in the order the dependences impose (first unknown first), every unknown kept in
+ * the accumulator's precision until the end and rounded to T once.  No test for singularity.
+ * D[o] (if given) = (|b_o| + sum_{k != o} |op(T)[o][k] z_k|) / |op(T)[o][o]|. */
+void FN(trsv)(int layout, int uplo, int trans, int diag, int64_t n, const T* A, int64_t lda, T* x,
+              int64_t incx, double* D)
+{
+    if (n <= 0) return;
+    acc_t* z = (acc_t*)malloc((size_t)n * sizeof(acc_t));
+    /* op(T) is lower triangular iff (uplo == lower) != (trans == transpose): then the first
+     * unknown is z_0 and unknown o depends on k < o; otherwise the last one and k > o. */
+    const int op_lower = (uplo == ORACLE_LOWER) != (trans == ORACLE_TRANS);
+    for (int64_t step = 0; step < n; ++step) {
+        const int64_t o = op_lower ? step : n - 1 - step;
+        acc_t acc = (acc_t)x[FN(pos)(o, n, incx)];
+        double d = fabs((double)acc);
+        const int64_t k0 = op_lower ? 0 : o + 1, k1 = op_lower ? o : n;
+        for (int64_t k = k0; k < k1; ++k) {
+            /* op(T)[o][k] = T[o][k] (no transpose) or T[k][o] (transpose) */
+            const int64_t i = trans == ORACLE_NO_TRANS ? o : k;
+            const int64_t j = trans == ORACLE_NO_TRANS ? k : o;
+            const T a = FN(elem)(A, lda, layout, i, j);
+            acc -= (acc_t)a * z[k];
+            d += fabs((double)((acc_t)a * z[k]));
+        }
+        if (diag == ORACLE_NON_UNIT) {
+            const T a = FN(elem)(A, lda, layout, o, o);
+            acc /= (acc_t)a;
+            d /= fabs((double)a);
+        }
+        z[o] = acc;
+        if (D) D[o] = d;
+    }
+    for (int64_t o = 0; o < n; ++o) x[FN(pos)(o, n, incx)] = (T)z[o];
+    free(z);
+}
+
 /* ---- rest of the level-1 set of Sec. 6.2.1 (copy, swap, rot, rotm) and iamax (which, like nrm2,
  *      the paper could not express; plain definition) ------------------------------------------ */
 

@@ -498,3 +498,149 @@ def test_iamax(dt):
     assert O.iamax(5000, x, 1) == int(np.argmax(np.abs(x)))
     xb = synth.strided(x, 3, fill=99.0)                                  # the gaps must not be looked at
     assert O.iamax(5000, xb, 3) == int(np.argmax(np.abs(x)))
+
+
+# ----------------------------------------------------------------------------- syr, syr2, trsv
+def tri_buffer(A, layout, uplo, pad, dt, unit=False):
+    """Row- or column-major buffer of the square matrix A with NaN in the padding, in the triangle
+    opposite to uplo and (unit) on the diagonal."""
+    n = A.shape[0]
+    P = A.astype(dt).copy()
+    outside = np.tril(np.ones((n, n), bool), -1) if uplo == O.UPPER else np.triu(np.ones((n, n), bool), 1)
+    P[outside] = np.nan
+    if unit:
+        np.fill_diagonal(P, np.nan)
+    lda = n + pad
+    buf = np.full((n, lda), np.nan, dt)
+    buf[:, :n] = P if layout == O.ROW_MAJOR else P.T
+    return buf, lda, outside
+
+
+def tri_logical(buf, layout, n):
+    return buf[:, :n] if layout == O.ROW_MAJOR else buf[:, :n].T
+
+
+@pytest.mark.parametrize("dt", DT)
+@pytest.mark.parametrize("layout", [O.ROW_MAJOR, O.COL_MAJOR])
+@pytest.mark.parametrize("uplo", [O.UPPER, O.LOWER])
+def test_syr_syr2_int64_brute_force_and_untouched_rest(dt, layout, uplo):
+    n = 13
+    A = ints(21, 0, n * n, dt, -5, 5).reshape(n, n)
+    x, y = ints(21, 1, n, dt, -5, 5), ints(21, 2, n, dt, -5, 5)
+    xi, yi, Ai = x.astype(np.int64), y.astype(np.int64), A.astype(np.int64)
+    buf, lda, outside = tri_buffer(A, layout, uplo, 3, dt)
+    for incx, incy in ((1, 1), (2, -3), (-1, 2)):
+        xb, yb = synth.strided(x, incx), synth.strided(y, incy)
+        b = buf.copy(); O.syr(layout, uplo, n, dt(3), xb, incx, b.ravel(), lda)
+        got = tri_logical(b, layout, n)
+        want = Ai + 3 * np.outer(xi, xi)
+        assert np.array_equal(got[~outside].astype(np.int64), want[~outside])
+        assert np.isnan(got[outside]).all() and np.isnan(b[:, n:]).all()     # never read, never written
+        b = buf.copy(); O.syr2(layout, uplo, n, dt(-2), xb, incx, yb, incy, b.ravel(), lda)
+        got = tri_logical(b, layout, n)
+        want = Ai - 2 * (np.outer(xi, yi) + np.outer(yi, xi))
+        assert np.array_equal(got[~outside].astype(np.int64), want[~outside])
+        assert np.isnan(got[outside]).all() and np.isnan(b[:, n:]).all()
+    b = buf.copy(); O.syr(layout, uplo, n, dt(0), x, 1, b.ravel(), lda)
+    assert b.tobytes() == buf.tobytes()                                      # alpha = 0: untouched
+    b = buf.copy(); O.syr2(layout, uplo, n, dt(0), x, 1, y, 1, b.ravel(), lda)
+    assert b.tobytes() == buf.tobytes()
+
+
+@pytest.mark.parametrize("dt", DT)
+def test_syr_syr2_tie_to_ger_symv_and_each_other(dt):
+    n = 11
+    A = ints(22, 0, n * n, dt, -4, 4).reshape(n, n)
+    A = np.tril(A) + np.tril(A, -1).T                                        # symmetric, integer
+    x, y, z = ints(22, 1, n, dt, -4, 4), ints(22, 2, n, dt, -4, 4), ints(22, 3, n, dt, -4, 4)
+    for uplo in (O.UPPER, O.LOWER):
+        keep = np.triu(np.ones((n, n), bool)) if uplo == O.UPPER else np.tril(np.ones((n, n), bool))
+        # syr == ger(x, x) inside the triangle
+        S = A.copy(); O.syr(O.ROW_MAJOR, uplo, n, dt(2), x, 1, S.ravel(), n)
+        Gm = A.copy(); O.ger(O.ROW_MAJOR, n, n, dt(2), x, 1, x, 1, Gm.ravel(), n)
+        assert np.array_equal(S[keep], Gm[keep]) and np.array_equal(S[~keep], A[~keep])
+        # syr2 == ger(x, y) then ger(y, x) inside the triangle; symmetric in x <-> y; syr2(x, x, a) == syr(x, 2a)
+        S2 = A.copy(); O.syr2(O.ROW_MAJOR, uplo, n, dt(3), x, 1, y, 1, S2.ravel(), n)
+        G2 = A.copy(); O.ger(O.ROW_MAJOR, n, n, dt(3), x, 1, y, 1, G2.ravel(), n); O.ger(O.ROW_MAJOR, n, n, dt(3), y, 1, x, 1, G2.ravel(), n)
+        assert np.array_equal(S2[keep], G2[keep])
+        S3 = A.copy(); O.syr2(O.ROW_MAJOR, uplo, n, dt(3), y, 1, x, 1, S3.ravel(), n)
+        assert np.array_equal(S2, S3)
+        S4 = A.copy(); O.syr2(O.ROW_MAJOR, uplo, n, dt(1), x, 1, x, 1, S4.ravel(), n)
+        assert np.array_equal(S4, S)
+        # (A + a x x^T) z = A z + a x (x^T z): symv of the updated triangle against symv + dot + axpy
+        lhs = np.zeros(n, dt); O.symv(O.ROW_MAJOR, uplo, n, dt(1), S.ravel(), n, z, 1, dt(0), lhs, 1)
+        rhs = np.zeros(n, dt); O.symv(O.ROW_MAJOR, uplo, n, dt(1), A.ravel(), n, z, 1, dt(0), rhs, 1)
+        O.axpy(n, dt(2) * O.dot(n, x, 1, z, 1), x, 1, rhs, 1)
+        assert np.array_equal(lhs, rhs)
+    # one rounding: A = 0 gives alpha*x_i*x_j rounded once
+    xu = synth.uniform(22, 4, n, dt)
+    Z = np.zeros((n, n), dt); O.syr(O.ROW_MAJOR, O.LOWER, n, dt(0.3), xu, 1, Z.ravel(), n)
+    ref = np.float64(dt(0.3)) * np.outer(xu.astype(np.float64), xu.astype(np.float64))
+    low = np.tril(np.ones((n, n), bool))
+    assert np.max(np.abs(Z[low] - ref[low].astype(dt)) / np.abs(ref[low])) <= 2 * np.finfo(dt).eps
+    assert (Z[~low] == 0).all()
+
+
+def test_trsv_hand_worked():
+    # L = [[2,.,.],[1,4,.],[3,5,10]]: L z = (2, 9, 66) has z = (1, 2, 5.3); L^T z = (13, 23, 30) has z = (1, 2, 3)
+    L = np.array([2, np.nan, np.nan, 1, 4, np.nan, 3, 5, 10], np.float64)
+    x = np.array([2, 9, 66], np.float64); O.trsv(O.ROW_MAJOR, O.LOWER, O.NO_TRANS, O.NON_UNIT, 3, L, 3, x, 1)
+    assert list(x) == [1, 2, 5.3]
+    x = np.array([13, 23, 30], np.float64); O.trsv(O.ROW_MAJOR, O.LOWER, O.TRANS, O.NON_UNIT, 3, L, 3, x, 1)
+    assert list(x) == [1, 2, 3]
+    # unit diagonal: L1 = [[1,.,.],[1,1,.],[3,5,1]]: L1 z = (1, 3, 16) has z = (1, 2, 3)
+    L[0] = L[4] = L[8] = np.nan
+    x = np.array([1, 3, 16], np.float64); O.trsv(O.ROW_MAJOR, O.LOWER, O.NO_TRANS, O.UNIT, 3, L, 3, x, 1)
+    assert list(x) == [1, 2, 3]
+    # U = [[2,3],[.,5]]: U z = (32, 50) has z = (1, 10); U^T z = (2, 53) has z = (1, 10)
+    U = np.array([2, 3, np.nan, 5], np.float32)
+    x = np.array([32, 50], np.float32); O.trsv(O.ROW_MAJOR, O.UPPER, O.NO_TRANS, O.NON_UNIT, 2, U, 2, x, 1)
+    assert list(x) == [1, 10]
+    x = np.array([2, 53], np.float32); O.trsv(O.ROW_MAJOR, O.UPPER, O.TRANS, O.NON_UNIT, 2, U, 2, x, 1)
+    assert list(x) == [1, 10]
+    # a diagonal matrix divides: one correctly rounded division per element
+    d = np.array([3, 7, 0.3], np.float32); b = np.array([1, 2, 5], np.float32)
+    x = b.copy(); O.trsv(O.ROW_MAJOR, O.UPPER, O.NO_TRANS, O.NON_UNIT, 3, np.diag(d).ravel(), 3, x, 1)
+    assert np.array_equal(x, b / d)
+
+
+@pytest.mark.parametrize("dt", DT)
+@pytest.mark.parametrize("layout", [O.ROW_MAJOR, O.COL_MAJOR])
+@pytest.mark.parametrize("uplo", [O.UPPER, O.LOWER])
+@pytest.mark.parametrize("trans", [O.NO_TRANS, O.TRANS])
+def test_trsv_inverts_trmv_exactly_on_unit_integer_triangles(dt, layout, uplo, trans):
+    # unit triangular integer T and integer z: b = op(T) z is exact, and substitution stays in the integers
+    n = 24
+    A = ints(23, 0, n * n, dt, -1, 1).reshape(n, n)
+    z = ints(23, 1, n, dt, -2, 2)
+    buf, lda, _ = tri_buffer(A, layout, uplo, 2, dt, unit=True)
+    for incx in (1, 3, -2):
+        xb = synth.strided(z, incx)
+        O.trmv(layout, uplo, trans, O.UNIT, n, buf.ravel(), lda, xb, incx)
+        assert np.abs(synth.gather(xb, n, incx)).max() < 2 ** 20
+        O.trsv(layout, uplo, trans, O.UNIT, n, buf.ravel(), lda, xb, incx)
+        assert np.array_equal(synth.gather(xb, n, incx), z)
+        gaps = np.ones(xb.size, bool); gaps[::abs(incx)] = False
+        assert np.isnan(xb[gaps]).all()
+
+
+@pytest.mark.parametrize("dt,tol", [(np.float32, 2e-6), (np.float64, 4e-15)])
+@pytest.mark.parametrize("uplo", [O.UPPER, O.LOWER])
+@pytest.mark.parametrize("trans", [O.NO_TRANS, O.TRANS])
+@pytest.mark.parametrize("diag", [O.NON_UNIT, O.UNIT])
+def test_trsv_against_independent_fp64_library(dt, tol, uplo, trans, diag):
+    import scipy.linalg
+    n = 60
+    A = synth.uniform(24, 0, n * n, dt).reshape(n, n) / dt(8)               # off-diagonal small: well conditioned
+    A[np.arange(n), np.arange(n)] = dt(1) + np.abs(synth.uniform(24, 5, n, dt))
+    b = synth.uniform(24, 1, n, dt)
+    Tm = explicit_tri(A.copy(), uplo, diag).astype(np.float64)
+    want = scipy.linalg.solve_triangular(Tm, b.astype(np.float64), lower=(uplo == O.LOWER), trans=1 if trans == O.TRANS else 0)
+    buf, lda, _ = tri_buffer(A, O.ROW_MAJOR, uplo, 1, dt, unit=(diag == O.UNIT))
+    x = b.copy(); D = O.trsv(O.ROW_MAJOR, uplo, trans, diag, n, buf.ravel(), lda, x, 1, want_D=True)
+    assert np.max(np.abs(x - want) / np.abs(want).max()) <= tol
+    assert (D >= np.abs(x.astype(np.float64)) * (1 - 1e-6)).all()            # D bounds the terms of each unknown
+    # the residual of the rounded solution is at rounding level: |b - op(T) x| <= eps * (|op(T)| |x| + |b|)
+    opT = Tm if trans == O.NO_TRANS else Tm.T
+    r = np.abs(b.astype(np.float64) - opT @ x.astype(np.float64))
+    assert (r <= 2 * np.finfo(dt).eps * (np.abs(opT) @ np.abs(x.astype(np.float64)) + np.abs(b))).all()
