@@ -197,6 +197,24 @@ int mxb_sger(mxb_handle_t h, mxb_layout_t layout, int64_t m, int64_t n, float al
 int mxb_dger(mxb_handle_t h, mxb_layout_t layout, int64_t m, int64_t n, double alpha, const double* x, int64_t incx,
              const double* y, int64_t incy, double* A, int64_t lda);
 
+/* A[i,j] += alpha*x[i]*x[j] for (i, j) in the uplo triangle of the n x n matrix A (Sec. 6.2.2,
+ * syr).  Nothing outside the triangle is read or written.  Quick return: n == 0 or alpha == 0.
+ * Errors: layout (-1), uplo (-2), n < 0 (-3), x NULL (-5), incx == 0 (-6), A NULL (-7),
+ *         lda < max(1,n) (-8). */
+int mxb_ssyr(mxb_handle_t h, mxb_layout_t layout, mxb_uplo_t uplo, int64_t n, float alpha, const float* x, int64_t incx,
+             float* A, int64_t lda);
+int mxb_dsyr(mxb_handle_t h, mxb_layout_t layout, mxb_uplo_t uplo, int64_t n, double alpha, const double* x, int64_t incx,
+             double* A, int64_t lda);
+
+/* A[i,j] += alpha*x[i]*y[j] + alpha*y[i]*x[j] for (i, j) in the uplo triangle (Sec. 6.2.2, syr2).
+ * Quick return: n == 0 or alpha == 0.
+ * Errors: layout (-1), uplo (-2), n < 0 (-3), x NULL (-5), incx == 0 (-6), y NULL (-7),
+ *         incy == 0 (-8), A NULL (-9), lda < max(1,n) (-10). */
+int mxb_ssyr2(mxb_handle_t h, mxb_layout_t layout, mxb_uplo_t uplo, int64_t n, float alpha, const float* x, int64_t incx,
+              const float* y, int64_t incy, float* A, int64_t lda);
+int mxb_dsyr2(mxb_handle_t h, mxb_layout_t layout, mxb_uplo_t uplo, int64_t n, double alpha, const double* x, int64_t incx,
+              const double* y, int64_t incy, double* A, int64_t lda);
+
 /* ---- bandwidth probes (measurement aids, not BLAS) ----------------------------------------- */
 
 /* dst[0..bytes) = src[0..bytes) with the same 128-bit streaming loads/stores the kernels use.

@@ -76,6 +76,8 @@ for _p, _t in (("s", _f), ("d", _d)):
     _fn[_p + "symv"] = _sig(f"mxb_{_p}symv", _int, _ptr, _int, _int, _i64, _t, _ptr, _i64, _ptr, _i64, _t,
                             _ptr, _i64)
     _fn[_p + "ger"] = _sig(f"mxb_{_p}ger", _int, _ptr, _int, _i64, _i64, _t, _ptr, _i64, _ptr, _i64, _ptr, _i64)
+    _fn[_p + "syr"] = _sig(f"mxb_{_p}syr", _int, _ptr, _int, _int, _i64, _t, _ptr, _i64, _ptr, _i64)
+    _fn[_p + "syr2"] = _sig(f"mxb_{_p}syr2", _int, _ptr, _int, _int, _i64, _t, _ptr, _i64, _ptr, _i64, _ptr, _i64)
 
 
 _fn["dsdot"] = _sig("mxb_dsdot", _int, _ptr, _i64, _ptr, _i64, _ptr, _i64, _ptr)
@@ -196,6 +198,22 @@ def mxb_sger(h, layout, m, n, alpha, x, incx, y, incy, A, lda):
 
 def mxb_dger(h, layout, m, n, alpha, x, incx, y, incy, A, lda):
     return _fn["dger"](h, layout, m, n, alpha, _dp(x), incx, _dp(y), incy, _dp(A), lda)
+
+
+def mxb_ssyr(h, layout, uplo, n, alpha, x, incx, A, lda):
+    return _fn["ssyr"](h, layout, uplo, n, alpha, _dp(x), incx, _dp(A), lda)
+
+
+def mxb_dsyr(h, layout, uplo, n, alpha, x, incx, A, lda):
+    return _fn["dsyr"](h, layout, uplo, n, alpha, _dp(x), incx, _dp(A), lda)
+
+
+def mxb_ssyr2(h, layout, uplo, n, alpha, x, incx, y, incy, A, lda):
+    return _fn["ssyr2"](h, layout, uplo, n, alpha, _dp(x), incx, _dp(y), incy, _dp(A), lda)
+
+
+def mxb_dsyr2(h, layout, uplo, n, alpha, x, incx, y, incy, A, lda):
+    return _fn["dsyr2"](h, layout, uplo, n, alpha, _dp(x), incx, _dp(y), incy, _dp(A), lda)
 
 
 def routine(prefix: str, name: str):

@@ -38,6 +38,7 @@ struct GerArgs {
     int64_t incy;
     T alpha;
     int64_t rows_per_block;
+    uint32_t col_tiles;    // blocks side by side along a row; the grid is col_tiles x row groups, flattened
 };
 
 template <typename T, int VEC>
@@ -45,12 +46,13 @@ __global__ void __launch_bounds__(kThreads) ger_kernel(const GerArgs<T> p)
 {
     typedef typename VecOf<T, VEC>::type V;
     constexpr int U = 8;
-    const int64_t c = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * VEC;
+    const int64_t bx = blockIdx.x % p.col_tiles, by = blockIdx.x / p.col_tiles;   // 32-bit division
+    const int64_t c = (bx * kThreads + threadIdx.x) * VEC;
     if (c + VEC > p.N) return;
     T yj[VEC];
 #pragma unroll
     for (int k = 0; k < VEC; ++k) yj[k] = p.y[(c + k) * p.incy];
-    const int64_t rlo = (int64_t)blockIdx.y * p.rows_per_block, rhi = imin(p.M, rlo + p.rows_per_block);
+    const int64_t rlo = by * p.rows_per_block, rhi = imin(p.M, rlo + p.rows_per_block);
     T* acol = p.A + c;
     int64_t i0 = rlo;
     for (; i0 + U <= rhi; i0 += U) {
@@ -75,6 +77,120 @@ __global__ void __launch_bounds__(kThreads) ger_kernel(const GerArgs<T> p)
 #pragma unroll
         for (int k = 0; k < VEC; ++k) a[k] = fmad(ax, yj[k], a[k]);
         st_stream(reinterpret_cast<V*>(acol + i0 * p.lda), a);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// syr / syr2: the same streaming read-modify-write restricted to the stored triangle
+
+template <typename T>
+struct SyrArgs {
+    int64_t n;
+    T* A;
+    int64_t lda;
+    const T* x;        // logical element 0
+    int64_t incx;
+    const T* y;        // syr2 only
+    int64_t incy;
+    T alpha;
+    uint32_t ntiles;       // tiles of kThreads*VEC columns across the matrix
+};
+
+// One block: 8 adjacent rows x kThreads*VEC columns (a tile).  Only tiles that hold stored
+// elements are launched: the rows are cut into bands of one tile width, band q holds q+1 tiles
+// per batch of rows if lower (ntiles-q if upper), and bands q and ntiles-1-q are enumerated
+// together, so that every batch index of a pair owns exactly ntiles+1 blocks and a block finds its
+// tile with two 32-bit divisions.  Tiles wholly inside the triangle run the unpredicated ger code;
+// in the tiles that straddle the diagonal every lane decides per row whether its vector lies
+// inside (vector access), outside (nothing is loaded or stored) or across the diagonal (loaded
+// whole, stored element by element).
+template <typename T, int VEC, bool UPPER, bool TWO>
+__global__ void __launch_bounds__(kThreads) syr_kernel(const SyrArgs<T> p)
+{
+    typedef typename VecOf<T, VEC>::type V;
+    constexpr int U = 8;
+    constexpr uint32_t W = kThreads * VEC, BPB = W / U;     // tile width; batches of rows per band
+    const uint32_t nt = p.ntiles, per_pair = (nt + 1) * BPB, pairs = nt / 2;
+    uint32_t band, tile, batch;
+    if (blockIdx.x < pairs * per_pair) {
+        const uint32_t q = blockIdx.x / per_pair, rest = blockIdx.x % per_pair, j = rest % (nt + 1);
+        batch = rest / (nt + 1);
+        const uint32_t first = UPPER ? nt - q : q + 1;     // tiles of band q; the rest belong to band nt-1-q
+        band = j < first ? q : nt - 1 - q;
+        tile = UPPER ? band + (j < first ? j : j - first) : (j < first ? j : j - first);
+    } else {                                               // the middle band of an odd number of bands
+        const uint32_t rest = blockIdx.x - pairs * per_pair, m = pairs;
+        band = m;
+        batch = rest / (m + 1);
+        tile = (UPPER ? m : 0) + rest % (m + 1);
+    }
+    const int64_t c0 = (int64_t)tile * W, r0 = (int64_t)band * W + (int64_t)batch * U;
+    if (r0 >= p.n) return;                                  // the last band may be short
+    const int64_t r1 = imin(p.n, r0 + U);   // exclusive
+    const int64_t c = c0 + (int64_t)threadIdx.x * VEC;
+    const bool col_ok = c + VEC <= p.n;
+    T xj[VEC], yj[VEC];
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) {
+        xj[k] = col_ok ? p.x[(c + k) * p.incx] : T(0);
+        yj[k] = (TWO && col_ok) ? p.y[(c + k) * p.incy] : T(0);
+    }
+    T* acol = p.A + c;
+    const bool inside = tile != band && r0 + U <= p.n && c0 + W <= p.n;
+    V a[U];
+    T ax[U], ay[U];
+    if (inside) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            a[u] = ld_stream(reinterpret_cast<const V*>(acol + (r0 + u) * p.lda));
+            ax[u] = p.alpha * p.x[(r0 + u) * p.incx];
+            ay[u] = TWO ? p.alpha * p.y[(r0 + u) * p.incy] : T(0);
+        }
+        __builtin_amdgcn_sched_barrier(0);   // all loads of the batch are in flight before the first store
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) {
+                if (TWO) a[u][k] = fmad(ax[u], yj[k], fmad(ay[u], xj[k], a[u][k]));
+                else a[u][k] = fmad(ax[u], xj[k], a[u][k]);
+            }
+            st_stream(reinterpret_cast<V*>(acol + (r0 + u) * p.lda), a[u]);
+        }
+        return;
+    }
+    if (!col_ok) return;
+    // d = position of the diagonal inside the lane's vector in row i: element k is stored iff
+    // k <= d (lower) / k >= d (upper)
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t i = imin(r0 + u, r1 - 1), d = i - c;
+        const bool none = (UPPER ? d > VEC - 1 : d < 0) || r0 + u >= r1;
+        a[u] = V(T(0));
+        if (!none) a[u] = ld_stream(reinterpret_cast<const V*>(acol + i * p.lda));
+        ax[u] = p.alpha * p.x[i * p.incx];
+        ay[u] = TWO ? p.alpha * p.y[i * p.incy] : T(0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t i = r0 + u, d = i - c;
+        if (i >= r1) break;
+        const bool all = UPPER ? d <= 0 : d >= VEC - 1;
+        const bool none = UPPER ? d > VEC - 1 : d < 0;
+        if (none) continue;
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+            if (TWO) a[u][k] = fmad(ax[u], yj[k], fmad(ay[u], xj[k], a[u][k]));
+            else a[u][k] = fmad(ax[u], xj[k], a[u][k]);
+        }
+        T* ap = acol + i * p.lda;
+        if (all) {
+            st_stream(reinterpret_cast<V*>(ap), a[u]);
+        } else {
+#pragma unroll
+            for (int k = 0; k < VEC; ++k)
+                if (UPPER ? k >= d : k <= d) ap[k] = a[u][k];
+        }
     }
 }
 
@@ -128,15 +244,54 @@ int ger(mxb_handle_t h, int layout, int64_t m, int64_t n, T alpha, const T* x, i
     if (!A) return -9;
     // column-major A (m x n) is the row-major n x m matrix: A^T += alpha * y x^T
     GerArgs<T> a;
-    if (layout == MXB_ROW_MAJOR) a = GerArgs<T>{m, n, A, lda, vec_base(x, m, incx), incx, vec_base(y, n, incy), incy, alpha, 0};
-    else a = GerArgs<T>{n, m, A, lda, vec_base(y, n, incy), incy, vec_base(x, m, incx), incx, alpha, 0};
+    if (layout == MXB_ROW_MAJOR) a = GerArgs<T>{m, n, A, lda, vec_base(x, m, incx), incx, vec_base(y, n, incy), incy, alpha, 0, 0};
+    else a = GerArgs<T>{n, m, A, lda, vec_base(y, n, incy), incy, vec_base(x, m, incx), incx, alpha, 0, 0};
     a.rows_per_block = option(h, MXB_OPT_GER_ROWS_PER_BLOCK);
     constexpr int FV = Full<T>::vec;
     const bool vec = aligned16(A) && (lda % FV) == 0 && (a.N % FV) == 0;
     const int v = vec ? FV : 1;
-    const dim3 grid((unsigned)ceil_div(a.N, (int64_t)kThreads * v), (unsigned)ceil_div(a.M, a.rows_per_block));
+    a.col_tiles = (uint32_t)ceil_div(a.N, (int64_t)kThreads * v);
+    const int64_t blocks = (int64_t)a.col_tiles * ceil_div(a.M, a.rows_per_block);
+    if (blocks > 0x7fffffff) return MXB_ERR_NOT_IMPLEMENTED;
+    const dim3 grid((unsigned)blocks);
     if (vec) hipLaunchKernelGGL((ger_kernel<T, FV>), grid, dim3(kThreads), 0, h->stream, a);
     else hipLaunchKernelGGL((ger_kernel<T, 1>), grid, dim3(kThreads), 0, h->stream, a);
+    return launch_status();
+}
+
+// syr (y == nullptr) and syr2.  Both updates are symmetric, so the column-major uplo triangle is
+// the row-major opposite triangle of the same bytes.
+template <typename T, bool TWO>
+int syr(mxb_handle_t h, int layout, int uplo, int64_t n, T alpha, const T* x, int64_t incx, const T* y, int64_t incy, T* A,
+        int64_t lda)
+{
+    if (!handle_ok(h)) return MXB_ERR_HANDLE;
+    if (!layout_ok(layout)) return -1;
+    if (!uplo_ok(uplo)) return -2;
+    if (n < 0) return -3;
+    if (incx == 0) return -6;
+    if (TWO && incy == 0) return -8;
+    if (lda < (n > 1 ? n : 1)) return TWO ? -10 : -8;
+    if (n == 0 || alpha == T(0)) return MXB_OK;
+    if (!x) return -5;
+    if (TWO && !y) return -7;
+    if (!A) return TWO ? -9 : -7;
+    const bool upper = (uplo == MXB_UPPER) == (layout == MXB_ROW_MAJOR);
+    SyrArgs<T> a{n, A, lda, vec_base(x, n, incx), incx, TWO ? vec_base(y, n, incy) : nullptr, incy, alpha, 0};
+    constexpr int FV = Full<T>::vec;
+    const bool vec = aligned16(A) && (lda % FV) == 0 && (n % FV) == 0;
+    const int v = vec ? FV : 1;
+    const int64_t w = (int64_t)kThreads * v, nt = ceil_div(n, w);
+    a.ntiles = (uint32_t)nt;
+    // pairs of bands with nt+1 tiles per batch of 8 rows, plus the middle band of an odd count
+    const int64_t blocks = (nt / 2) * (nt + 1) * (w / 8) + (nt % 2) * (nt / 2 + 1) * (w / 8);
+    if (blocks > 0x7fffffff) return MXB_ERR_NOT_IMPLEMENTED;
+    const dim3 grid((unsigned)blocks);
+#define MXB_SYR(VEC_)                                                                                        \
+    if (upper) hipLaunchKernelGGL((syr_kernel<T, VEC_, true, TWO>), grid, dim3(kThreads), 0, h->stream, a);  \
+    else hipLaunchKernelGGL((syr_kernel<T, VEC_, false, TWO>), grid, dim3(kThreads), 0, h->stream, a);
+    if (vec) { MXB_SYR(FV) } else { MXB_SYR(1) }
+#undef MXB_SYR
     return launch_status();
 }
 
@@ -156,4 +311,16 @@ int mxb_sger(mxb_handle_t h, mxb_layout_t layout, int64_t m, int64_t n, float al
 int mxb_dger(mxb_handle_t h, mxb_layout_t layout, int64_t m, int64_t n, double alpha, const double* x, int64_t incx,
              const double* y, int64_t incy, double* A, int64_t lda)
 { return mxb::ger<double>(h, layout, m, n, alpha, x, incx, y, incy, A, lda); }
+int mxb_ssyr(mxb_handle_t h, mxb_layout_t layout, mxb_uplo_t uplo, int64_t n, float alpha, const float* x, int64_t incx, float* A,
+             int64_t lda)
+{ return mxb::syr<float, false>(h, layout, uplo, n, alpha, x, incx, nullptr, 1, A, lda); }
+int mxb_dsyr(mxb_handle_t h, mxb_layout_t layout, mxb_uplo_t uplo, int64_t n, double alpha, const double* x, int64_t incx, double* A,
+             int64_t lda)
+{ return mxb::syr<double, false>(h, layout, uplo, n, alpha, x, incx, nullptr, 1, A, lda); }
+int mxb_ssyr2(mxb_handle_t h, mxb_layout_t layout, mxb_uplo_t uplo, int64_t n, float alpha, const float* x, int64_t incx,
+              const float* y, int64_t incy, float* A, int64_t lda)
+{ return mxb::syr<float, true>(h, layout, uplo, n, alpha, x, incx, y, incy, A, lda); }
+int mxb_dsyr2(mxb_handle_t h, mxb_layout_t layout, mxb_uplo_t uplo, int64_t n, double alpha, const double* x, int64_t incx,
+              const double* y, int64_t incy, double* A, int64_t lda)
+{ return mxb::syr<double, true>(h, layout, uplo, n, alpha, x, incx, y, incy, A, lda); }
 }

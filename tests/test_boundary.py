@@ -143,6 +143,27 @@ def test_argument_errors_name_the_argument(B):
             assert r(h, B.ROW_MAJOR, 4, 5, 1.0, P, 1, P, 1, P, 4) == -10
             assert r(h, B.ROW_MAJOR, 4, 4, 0.0, None, 1, None, 1, None, 4) == 0
             assert r(h, B.ROW_MAJOR, 0, 4, 1.0, None, 1, None, 1, None, 4) == 0
+            r = f("syr")
+            assert r(h, 0, B.LOWER, 4, 1.0, P, 1, P, 4) == -1
+            assert r(h, B.ROW_MAJOR, 0, 4, 1.0, P, 1, P, 4) == -2
+            assert r(h, B.ROW_MAJOR, B.LOWER, -1, 1.0, P, 1, P, 4) == -3
+            assert r(h, B.ROW_MAJOR, B.LOWER, 4, 1.0, None, 1, P, 4) == -5
+            assert r(h, B.ROW_MAJOR, B.LOWER, 4, 1.0, P, 0, P, 4) == -6
+            assert r(h, B.ROW_MAJOR, B.LOWER, 4, 1.0, P, 1, None, 4) == -7
+            assert r(h, B.ROW_MAJOR, B.LOWER, 4, 1.0, P, 1, P, 3) == -8
+            assert r(h, B.ROW_MAJOR, B.LOWER, 4, 0.0, None, 1, None, 4) == 0
+            assert r(h, B.ROW_MAJOR, B.LOWER, 0, 1.0, None, 1, None, 1) == 0
+            r = f("syr2")
+            assert r(h, 0, B.LOWER, 4, 1.0, P, 1, P, 1, P, 4) == -1
+            assert r(h, B.ROW_MAJOR, 0, 4, 1.0, P, 1, P, 1, P, 4) == -2
+            assert r(h, B.ROW_MAJOR, B.LOWER, -1, 1.0, P, 1, P, 1, P, 4) == -3
+            assert r(h, B.ROW_MAJOR, B.LOWER, 4, 1.0, None, 1, P, 1, P, 4) == -5
+            assert r(h, B.ROW_MAJOR, B.LOWER, 4, 1.0, P, 0, P, 1, P, 4) == -6
+            assert r(h, B.ROW_MAJOR, B.LOWER, 4, 1.0, P, 1, None, 1, P, 4) == -7
+            assert r(h, B.ROW_MAJOR, B.LOWER, 4, 1.0, P, 1, P, 0, P, 4) == -8
+            assert r(h, B.ROW_MAJOR, B.LOWER, 4, 1.0, P, 1, P, 1, None, 4) == -9
+            assert r(h, B.ROW_MAJOR, B.LOWER, 4, 1.0, P, 1, P, 1, P, 3) == -10
+            assert r(h, B.ROW_MAJOR, B.LOWER, 4, 0.0, None, 1, None, 1, None, 4) == 0
     finally:
         B.mxb_destroy(h)
 

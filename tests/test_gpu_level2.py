@@ -271,3 +271,55 @@ def test_ger(blas, ctx, dt, layout):
     A = synth.uniform(13, 0, 100 * 100, dt); dA = to_dev(A); nan = to_dev(np.full(100, np.nan, dt))
     assert blas.routine(prefix_of(dt), "ger")(ctx.h, layout, 100, 100, 0.0, nan, 1, nan, 1, dA, 100) == 0
     assert bits_equal(to_host(dA), A)
+
+
+# ----------------------------------------------------------------------------- syr, syr2
+def syr_case(blas, ctx, dt, layout, uplo, n, alpha, pad, incx, incy, two, ints=False, seed=14):
+    gen = (lambda t, k: synth.small_ints(seed, t, k, -3, 3, dt)) if ints else (lambda t, k: synth.uniform(seed, t, k, dt))
+    A = gen(0, n * n).reshape(n, n).copy()
+    outside = np.tril(np.ones((n, n), bool), -1) if uplo == O.UPPER else np.triu(np.ones((n, n), bool), 1)
+    A[outside] = np.nan                                   # never read, never written
+    x, y = gen(1, n), gen(2, n)
+    Ab, lda = matrix_buffer(A, layout, pad)
+    xb, yb = synth.strided(x, incx), synth.strided(y, incy)
+    ref = Ab.copy()
+    if two:
+        D = O.syr2(layout, uplo, n, dt(alpha), xb, incx, yb, incy, ref, lda, want_D=True)
+    else:
+        D = O.syr(layout, uplo, n, dt(alpha), xb, incx, ref, lda, want_D=True)
+    dA = to_dev(Ab)
+    f = blas.routine(prefix_of(dt), "syr2" if two else "syr")
+    if two:
+        st = f(ctx.h, layout, uplo, n, float(alpha), to_dev(xb), incx, to_dev(yb), incy, dA, lda)
+    else:
+        st = f(ctx.h, layout, uplo, n, float(alpha), to_dev(xb), incx, dA, lda)
+    assert st == 0, f"status {st}"
+    got = to_host(dA)
+    what = f"{'syr2' if two else 'syr'} {prefix_of(dt)} layout={layout} uplo={uplo} n={n} pad={pad} a={alpha} inc=({incx},{incy})"
+    g, r = logical(got, layout, n, n, lda), logical(ref, layout, n, n, lda)
+    keep = ~outside
+    if ints:
+        assert bits_equal(g[keep], r[keep]), what
+    else:
+        check_close(g[keep], r[keep], D.reshape(n, n)[keep], 1, what)
+    # opposite triangle and padding untouched (still NaN)
+    assert np.isnan(g[outside]).all(), what + ": wrote outside the triangle"
+    mask = np.ones(got.size, bool).reshape(-1, lda); mask[:n, :n] = False
+    assert np.isnan(got.reshape(-1, lda)[mask]).all(), what + ": padding written"
+
+
+@pytest.mark.parametrize("dt", DT)
+@pytest.mark.parametrize("layout", [O.ROW_MAJOR, O.COL_MAJOR])
+@pytest.mark.parametrize("uplo", [O.UPPER, O.LOWER])
+@pytest.mark.parametrize("two", [False, True])
+def test_syr_syr2(blas, ctx, dt, layout, uplo, two):
+    for n in (1, 2, 3, 7, 8, 9, 64, 65, 257, 1000, 1024, 1030, 2310):
+        syr_case(blas, ctx, dt, layout, uplo, n, 0.3, 0 if n % 2 else 4, 1, 1, two)
+    syr_case(blas, ctx, dt, layout, uplo, 515, -1.5, 1, 2, -3, two)
+    syr_case(blas, ctx, dt, layout, uplo, 515, -1.5, 3, -1, 2, two)
+    syr_case(blas, ctx, dt, layout, uplo, 2052, 3, 0, 1, 1, two, ints=True)
+    # alpha = 0: A untouched even if x, y hold NaN
+    A = synth.uniform(14, 0, 100 * 100, dt); dA = to_dev(A); nan = to_dev(np.full(100, np.nan, dt))
+    f = blas.routine(prefix_of(dt), "syr2" if two else "syr")
+    st = f(ctx.h, layout, uplo, 100, 0.0, nan, 1, nan, 1, dA, 100) if two else f(ctx.h, layout, uplo, 100, 0.0, nan, 1, dA, 100)
+    assert st == 0 and bits_equal(to_host(dA), A)
