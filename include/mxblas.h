@@ -179,6 +179,17 @@ int mxb_strmv(mxb_handle_t h, mxb_layout_t layout, mxb_uplo_t uplo, mxb_trans_t 
 int mxb_dtrmv(mxb_handle_t h, mxb_layout_t layout, mxb_uplo_t uplo, mxb_trans_t trans, mxb_diag_t diag,
               int64_t n, const double* A, int64_t lda, double* x, int64_t incx);
 
+/* Solves op(T)*z = x for z, which overwrites x: T is the uplo triangle of the n x n matrix A
+ * (Sec. 6.2.2, trsv); with MXB_UNIT the diagonal is taken as 1 and never used.  Elements outside
+ * the triangle are never used.  No test for singularity.  Blocked substitution: the diagonal
+ * elements enter as reciprocals (one extra rounding per unknown).  Uses the workspace when the
+ * product is transposed (as gemv does).  Quick return: n == 0.
+ * Errors: as mxb_strmv. */
+int mxb_strsv(mxb_handle_t h, mxb_layout_t layout, mxb_uplo_t uplo, mxb_trans_t trans, mxb_diag_t diag,
+              int64_t n, const float* A, int64_t lda, float* x, int64_t incx);
+int mxb_dtrsv(mxb_handle_t h, mxb_layout_t layout, mxb_uplo_t uplo, mxb_trans_t trans, mxb_diag_t diag,
+              int64_t n, const double* A, int64_t lda, double* x, int64_t incx);
+
 /* y = alpha*S*x + beta*y, S symmetric n x n, only the uplo triangle of A is used (Sec. 6.2.2).
  * beta == 0 / alpha == 0 as for gemv.  Quick return: n == 0 or (alpha == 0 and beta == 1).
  * Errors: layout (-1), uplo (-2), n < 0 (-3), A NULL (-5), lda < max(1,n) (-6), x NULL (-7),

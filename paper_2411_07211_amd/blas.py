@@ -73,6 +73,7 @@ for _p, _t in (("s", _f), ("d", _d)):
     _fn[_p + "gemv"] = _sig(f"mxb_{_p}gemv", _int, _ptr, _int, _int, _i64, _i64, _t, _ptr, _i64, _ptr, _i64,
                             _t, _ptr, _i64)
     _fn[_p + "trmv"] = _sig(f"mxb_{_p}trmv", _int, _ptr, _int, _int, _int, _int, _i64, _ptr, _i64, _ptr, _i64)
+    _fn[_p + "trsv"] = _sig(f"mxb_{_p}trsv", _int, _ptr, _int, _int, _int, _int, _i64, _ptr, _i64, _ptr, _i64)
     _fn[_p + "symv"] = _sig(f"mxb_{_p}symv", _int, _ptr, _int, _int, _i64, _t, _ptr, _i64, _ptr, _i64, _t,
                             _ptr, _i64)
     _fn[_p + "ger"] = _sig(f"mxb_{_p}ger", _int, _ptr, _int, _i64, _i64, _t, _ptr, _i64, _ptr, _i64, _ptr, _i64)
@@ -182,6 +183,14 @@ def mxb_strmv(h, layout, uplo, trans, diag, n, A, lda, x, incx):
 
 def mxb_dtrmv(h, layout, uplo, trans, diag, n, A, lda, x, incx):
     return _fn["dtrmv"](h, layout, uplo, trans, diag, n, _dp(A), lda, _dp(x), incx)
+
+
+def mxb_strsv(h, layout, uplo, trans, diag, n, A, lda, x, incx):
+    return _fn["strsv"](h, layout, uplo, trans, diag, n, _dp(A), lda, _dp(x), incx)
+
+
+def mxb_dtrsv(h, layout, uplo, trans, diag, n, A, lda, x, incx):
+    return _fn["dtrsv"](h, layout, uplo, trans, diag, n, _dp(A), lda, _dp(x), incx)
 
 
 def mxb_ssymv(h, layout, uplo, n, alpha, A, lda, x, incx, beta, y, incy):

@@ -118,6 +118,17 @@ def test_argument_errors_name_the_argument(B):
             assert t(h, *ok, 4, P, 4, P, 0) == -9
             assert t(h, *ok, 0, None, 1, None, 1) == 0
             assert t(h, *ok, 4, P, 4, P, 1) == B.ERR_WORKSPACE
+            for t in (f("trsv"),):
+                assert t(h, 0, ok[1], ok[2], ok[3], 4, P, 4, P, 1) == -1
+                assert t(h, ok[0], 0, ok[2], ok[3], 4, P, 4, P, 1) == -2
+                assert t(h, ok[0], ok[1], 0, ok[3], 4, P, 4, P, 1) == -3
+                assert t(h, ok[0], ok[1], ok[2], 0, 4, P, 4, P, 1) == -4
+                assert t(h, *ok, -1, P, 4, P, 1) == -5
+                assert t(h, *ok, 4, None, 4, P, 1) == -6
+                assert t(h, *ok, 4, P, 3, P, 1) == -7
+                assert t(h, *ok, 4, P, 4, None, 1) == -8
+                assert t(h, *ok, 4, P, 4, P, 0) == -9
+                assert t(h, *ok, 0, None, 1, None, 1) == 0
             s = f("symv")
             assert s(h, 0, B.LOWER, 4, 1.0, P, 4, P, 1, 0.0, P, 1) == -1
             assert s(h, B.ROW_MAJOR, 0, 4, 1.0, P, 4, P, 1, 0.0, P, 1) == -2

@@ -323,3 +323,71 @@ def test_syr_syr2(blas, ctx, dt, layout, uplo, two):
     f = blas.routine(prefix_of(dt), "syr2" if two else "syr")
     st = f(ctx.h, layout, uplo, 100, 0.0, nan, 1, nan, 1, dA, 100) if two else f(ctx.h, layout, uplo, 100, 0.0, nan, 1, dA, 100)
     assert st == 0 and bits_equal(to_host(dA), A)
+
+
+# ----------------------------------------------------------------------------- trsv
+def trsv_matrix(dt, n, uplo, diag, seed, exact):
+    """A triangular system that substitution solves stably: small off-diagonal elements and a
+    diagonal in [1, 2) (exact: entries in {-1, 0, 1} and power-of-two diagonals, so that products
+    with an integer solution and the reciprocal of the diagonal are exact).  The opposite triangle
+    and, for a unit diagonal, the diagonal hold NaN."""
+    if exact:
+        A = synth.small_ints(seed, 0, n * n, -1, 1, dt).reshape(n, n).copy()
+        d = np.array([1, 2, 0.5, -1, -2, 4], dt)[np.arange(n) % 6]
+    else:
+        A = (synth.uniform(seed, 0, n * n, dt).reshape(n, n) / dt(2 * np.sqrt(n))).astype(dt)
+        d = (dt(1) + np.abs(synth.uniform(seed, 5, n, dt))).astype(dt)
+    A[np.arange(n), np.arange(n)] = d
+    outside = np.tril(np.ones((n, n), bool), -1) if uplo == O.UPPER else np.triu(np.ones((n, n), bool), 1)
+    A[outside] = np.nan
+    if diag == O.UNIT:
+        np.fill_diagonal(A, np.nan)
+    return A
+
+
+def trsv_case(blas, ctx, dt, layout, uplo, trans, diag, n, pad, incx, exact=False, seed=15):
+    A = trsv_matrix(dt, n, uplo, diag, seed, exact)
+    Ab, lda = matrix_buffer(A, layout, pad)
+    z = synth.small_ints(seed, 1, n, -2, 2, dt) if exact else synth.uniform(seed, 1, n, dt)
+    # right-hand side b = op(T) z from the oracle's trmv, so that the solution is known (exact case) and O(1)
+    bb = synth.strided(z, incx)
+    O.trmv(layout, uplo, trans, diag, n, Ab, lda, bb, incx)
+    ref = bb.copy()
+    D = O.trsv(layout, uplo, trans, diag, n, Ab, lda, ref, incx, want_D=True)
+    dx = to_dev(bb)
+    st = blas.routine(prefix_of(dt), "trsv")(ctx.h, layout, uplo, trans, diag, n, to_dev(Ab), lda, dx, incx)
+    assert st == 0, f"status {st}"
+    got = to_host(dx)
+    what = f"trsv {prefix_of(dt)} layout={layout} uplo={uplo} trans={trans} diag={diag} n={n} pad={pad} incx={incx}"
+    g, r = synth.gather(got, n, incx), synth.gather(ref, n, incx)
+    if exact:
+        assert bits_equal(r, z), what + ": oracle"
+        assert bits_equal(g, z), what
+    else:
+        check_close(g, r, D, n, what)
+        # backward error: |b - op(T) g| <= tol * (|op(T)| |g| + |b|), evaluated in fp64
+        Tm = np.nan_to_num(logical(Ab, layout, n, n, lda).astype(np.float64))
+        if diag == O.UNIT:
+            np.fill_diagonal(Tm, 1.0)
+        opT = Tm if trans == O.NO_TRANS else Tm.T
+        b = synth.gather(bb, n, incx).astype(np.float64)
+        res = np.abs(b - opT @ g.astype(np.float64))
+        bound = np.abs(opT) @ np.abs(g.astype(np.float64)) + np.abs(b)
+        from parity import tight_tolerance
+        assert (res <= tight_tolerance(dt, n) * bound).all(), what + f": residual {np.max(res / bound):.3e}"
+    gaps = np.ones(got.size, bool); gaps[::abs(incx)] = False
+    assert np.isnan(got[gaps]).all(), what
+
+
+@pytest.mark.parametrize("dt", DT)
+@pytest.mark.parametrize("layout", [O.ROW_MAJOR, O.COL_MAJOR])
+@pytest.mark.parametrize("uplo", [O.UPPER, O.LOWER])
+@pytest.mark.parametrize("trans", [O.NO_TRANS, O.TRANS])
+@pytest.mark.parametrize("diag", [O.NON_UNIT, O.UNIT])
+def test_trsv(blas, ctx, dt, layout, uplo, trans, diag):
+    for n in (1, 2, 3, 5, 17, 63, 64, 65, 130, 255, 256, 257, 511, 512, 513, 1000, 1030, 2310):
+        trsv_case(blas, ctx, dt, layout, uplo, trans, diag, n, 0 if n % 2 else 4, 1)
+    trsv_case(blas, ctx, dt, layout, uplo, trans, diag, 700, 1, 2)
+    trsv_case(blas, ctx, dt, layout, uplo, trans, diag, 700, 0, -1)
+    for n in (64, 515, 1536):
+        trsv_case(blas, ctx, dt, layout, uplo, trans, diag, n, 0, 1, exact=True)
