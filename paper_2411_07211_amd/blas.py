@@ -3,6 +3,10 @@
 Every ``mxb_*`` function takes the handle first and accepts, for each device pointer, either a
 torch CUDA tensor (its ``data_ptr()`` is passed) or a raw integer address.  Nothing is computed
 here and there is no fallback: if the library has not been built, importing this module raises.
+For tensors the binding also checks, on the host, that the element type matches the routine and
+that the tensor is as large as the call's n / lda / increments require (ValueError / TypeError
+otherwise): the C ABI cannot know a buffer's size, and an overrun on the GPU can take the device
+down.
 
 :class:`Context` is a small convenience for callers that live in PyTorch: it creates a handle,
 points it at torch's current stream and gives it a workspace tensor.
@@ -125,33 +129,97 @@ def mxb_get_option(h, option):
     return _get_option(h, option)
 
 
+def _bytes(t):
+    return t.numel() * t.element_size() if hasattr(t, "numel") else None
+
+
 def mxb_probe_copy(h, nbytes, src, dst):
+    for t, what in ((src, "src"), (dst, "dst")):
+        if _bytes(t) is not None and nbytes > _bytes(t):
+            raise ValueError(f"{what}: {nbytes} bytes requested, the tensor holds {_bytes(t)}")
     return _probe_copy(h, nbytes, _dp(src), _dp(dst))
 
 
 def mxb_probe_read(h, nbytes, src):
+    if _bytes(src) is not None and nbytes > _bytes(src):
+        raise ValueError(f"src: {nbytes} bytes requested, the tensor holds {_bytes(src)}")
     return _probe_read(h, nbytes, _dp(src))
 
 
+# ---- operand checks ------------------------------------------------------------------------------
+# The C ABI takes bare device pointers and cannot know how large the buffers behind them are.  When a
+# torch tensor is passed, the binding knows, and refuses a call whose operands the routine would
+# overrun (or whose element type does not match the routine) before anything is launched: an
+# out-of-bounds access on the GPU can take the whole device down.  Raw integer addresses pass unchecked.
+_DT = {"s": torch.float32, "d": torch.float64}
+
+
+def _chk(t, need, what, p=None):
+    if t is None or t.__class__ is int:
+        return
+    if p is not None and t.dtype is not _DT[p]:
+        raise TypeError(f"{what}: tensor of {t.dtype} passed to a {_DT[p]} routine")
+    if need > t.numel():
+        raise ValueError(f"{what}: the call reads or writes {need} elements, the tensor holds {t.numel()}")
+
+
+def _v(t, n, inc, what, p):
+    """Device address of a vector operand of n logical elements with increment inc."""
+    _chk(t, 0 if n <= 0 else 1 + (n - 1) * abs(inc), what, p)
+    return _dp(t)
+
+
+def _m(t, layout, rows, cols, lda, what, p):
+    """Device address of a rows x cols matrix operand with leading dimension lda."""
+    major, minor = (rows, cols) if layout == ROW_MAJOR else (cols, rows)
+    _chk(t, 0 if major <= 0 or minor <= 0 else (major - 1) * lda + minor, what, p)
+    return _dp(t)
+
+
 # ---- level 1 -----------------------------------------------------------------------------------
-def mxb_saxpy(h, n, alpha, x, incx, y, incy): return _fn["saxpy"](h, n, alpha, _dp(x), incx, _dp(y), incy)
-def mxb_daxpy(h, n, alpha, x, incx, y, incy): return _fn["daxpy"](h, n, alpha, _dp(x), incx, _dp(y), incy)
-def mxb_sscal(h, n, alpha, x, incx): return _fn["sscal"](h, n, alpha, _dp(x), incx)
-def mxb_dscal(h, n, alpha, x, incx): return _fn["dscal"](h, n, alpha, _dp(x), incx)
-def mxb_sdot(h, n, x, incx, y, incy, result): return _fn["sdot"](h, n, _dp(x), incx, _dp(y), incy, _dp(result))
-def mxb_ddot(h, n, x, incx, y, incy, result): return _fn["ddot"](h, n, _dp(x), incx, _dp(y), incy, _dp(result))
-def mxb_sasum(h, n, x, incx, result): return _fn["sasum"](h, n, _dp(x), incx, _dp(result))
-def mxb_dasum(h, n, x, incx, result): return _fn["dasum"](h, n, _dp(x), incx, _dp(result))
-def mxb_snrm2(h, n, x, incx, result): return _fn["snrm2"](h, n, _dp(x), incx, _dp(result))
-def mxb_dnrm2(h, n, x, incx, result): return _fn["dnrm2"](h, n, _dp(x), incx, _dp(result))
+def _mk_level1():
+    g = globals()
+    for p in "sd":
+        fn = _fn
 
+        def axpy(h, n, alpha, x, incx, y, incy, p=p):
+            return fn[p + "axpy"](h, n, alpha, _v(x, n, incx, "x", p), incx, _v(y, n, incy, "y", p), incy)
 
-def mxb_scopy(h, n, x, incx, y, incy): return _fn["scopy"](h, n, _dp(x), incx, _dp(y), incy)
-def mxb_dcopy(h, n, x, incx, y, incy): return _fn["dcopy"](h, n, _dp(x), incx, _dp(y), incy)
-def mxb_sswap(h, n, x, incx, y, incy): return _fn["sswap"](h, n, _dp(x), incx, _dp(y), incy)
-def mxb_dswap(h, n, x, incx, y, incy): return _fn["dswap"](h, n, _dp(x), incx, _dp(y), incy)
-def mxb_srot(h, n, x, incx, y, incy, c, s): return _fn["srot"](h, n, _dp(x), incx, _dp(y), incy, c, s)
-def mxb_drot(h, n, x, incx, y, incy, c, s): return _fn["drot"](h, n, _dp(x), incx, _dp(y), incy, c, s)
+        def scal(h, n, alpha, x, incx, p=p):
+            return fn[p + "scal"](h, n, alpha, _v(x, n, max(incx, 0), "x", p), incx)
+
+        def dot(h, n, x, incx, y, incy, result, p=p):
+            return fn[p + "dot"](h, n, _v(x, n, incx, "x", p), incx, _v(y, n, incy, "y", p), incy, _v(result, 1, 1, "result", p))
+
+        def asum(h, n, x, incx, result, p=p):
+            return fn[p + "asum"](h, n, _v(x, n, max(incx, 0), "x", p), incx, _v(result, 1, 1, "result", p))
+
+        def nrm2(h, n, x, incx, result, p=p):
+            return fn[p + "nrm2"](h, n, _v(x, n, max(incx, 0), "x", p), incx, _v(result, 1, 1, "result", p))
+
+        def copy(h, n, x, incx, y, incy, p=p):
+            return fn[p + "copy"](h, n, _v(x, n, incx, "x", p), incx, _v(y, n, incy, "y", p), incy)
+
+        def swap(h, n, x, incx, y, incy, p=p):
+            return fn[p + "swap"](h, n, _v(x, n, incx, "x", p), incx, _v(y, n, incy, "y", p), incy)
+
+        def rot(h, n, x, incx, y, incy, c, s, p=p):
+            return fn[p + "rot"](h, n, _v(x, n, incx, "x", p), incx, _v(y, n, incy, "y", p), incy, c, s)
+
+        def rotm(h, n, x, incx, y, incy, param, p=p):
+            return fn[p + "rotm"](h, n, _v(x, n, incx, "x", p), incx, _v(y, n, incy, "y", p), incy,
+                                  _host5(param, _f if p == "s" else _d))
+
+        def iamax(h, n, x, incx, result, p=p):
+            _chk(result, 1, "result")
+            return fn["i" + p + "amax"](h, n, _v(x, n, max(incx, 0), "x", p), incx, _dp(result))
+
+        for name, f in (("axpy", axpy), ("scal", scal), ("dot", dot), ("asum", asum), ("nrm2", nrm2), ("copy", copy),
+                        ("swap", swap), ("rot", rot), ("rotm", rotm)):
+            f.__name__ = f"mxb_{p}{name}"
+            g[f.__name__] = f
+        iamax.__name__ = f"mxb_i{p}amax"
+        g[iamax.__name__] = iamax
 
 
 def _host5(param, ctype):
@@ -161,68 +229,51 @@ def _host5(param, ctype):
     return (ctype * 5)(*[float(v) for v in param])
 
 
-def mxb_srotm(h, n, x, incx, y, incy, param): return _fn["srotm"](h, n, _dp(x), incx, _dp(y), incy, _host5(param, _f))
-def mxb_drotm(h, n, x, incx, y, incy, param): return _fn["drotm"](h, n, _dp(x), incx, _dp(y), incy, _host5(param, _d))
-def mxb_dsdot(h, n, x, incx, y, incy, result): return _fn["dsdot"](h, n, _dp(x), incx, _dp(y), incy, _dp(result))
-def mxb_isamax(h, n, x, incx, result): return _fn["isamax"](h, n, _dp(x), incx, _dp(result))
-def mxb_idamax(h, n, x, incx, result): return _fn["idamax"](h, n, _dp(x), incx, _dp(result))
+_mk_level1()
+
+
+def mxb_dsdot(h, n, x, incx, y, incy, result):
+    return _fn["dsdot"](h, n, _v(x, n, incx, "x", "s"), incx, _v(y, n, incy, "y", "s"), incy, _v(result, 1, 1, "result", "d"))
 
 
 # ---- level 2 -----------------------------------------------------------------------------------
-def mxb_sgemv(h, layout, trans, m, n, alpha, A, lda, x, incx, beta, y, incy):
-    return _fn["sgemv"](h, layout, trans, m, n, alpha, _dp(A), lda, _dp(x), incx, beta, _dp(y), incy)
+def _mk_level2():
+    g = globals()
+    for p in "sd":
+        fn = _fn
+
+        def gemv(h, layout, trans, m, n, alpha, A, lda, x, incx, beta, y, incy, p=p):
+            lenx, leny = (n, m) if trans == NO_TRANS else (m, n)
+            return fn[p + "gemv"](h, layout, trans, m, n, alpha, _m(A, layout, m, n, lda, "A", p), lda,
+                                  _v(x, lenx, incx, "x", p), incx, beta, _v(y, leny, incy, "y", p), incy)
+
+        def trmv(h, layout, uplo, trans, diag, n, A, lda, x, incx, p=p):
+            return fn[p + "trmv"](h, layout, uplo, trans, diag, n, _m(A, layout, n, n, lda, "A", p), lda, _v(x, n, incx, "x", p), incx)
+
+        def trsv(h, layout, uplo, trans, diag, n, A, lda, x, incx, p=p):
+            return fn[p + "trsv"](h, layout, uplo, trans, diag, n, _m(A, layout, n, n, lda, "A", p), lda, _v(x, n, incx, "x", p), incx)
+
+        def symv(h, layout, uplo, n, alpha, A, lda, x, incx, beta, y, incy, p=p):
+            return fn[p + "symv"](h, layout, uplo, n, alpha, _m(A, layout, n, n, lda, "A", p), lda, _v(x, n, incx, "x", p), incx,
+                                  beta, _v(y, n, incy, "y", p), incy)
+
+        def ger(h, layout, m, n, alpha, x, incx, y, incy, A, lda, p=p):
+            return fn[p + "ger"](h, layout, m, n, alpha, _v(x, m, incx, "x", p), incx, _v(y, n, incy, "y", p), incy,
+                                 _m(A, layout, m, n, lda, "A", p), lda)
+
+        def syr(h, layout, uplo, n, alpha, x, incx, A, lda, p=p):
+            return fn[p + "syr"](h, layout, uplo, n, alpha, _v(x, n, incx, "x", p), incx, _m(A, layout, n, n, lda, "A", p), lda)
+
+        def syr2(h, layout, uplo, n, alpha, x, incx, y, incy, A, lda, p=p):
+            return fn[p + "syr2"](h, layout, uplo, n, alpha, _v(x, n, incx, "x", p), incx, _v(y, n, incy, "y", p), incy,
+                                  _m(A, layout, n, n, lda, "A", p), lda)
+
+        for name, f in (("gemv", gemv), ("trmv", trmv), ("trsv", trsv), ("symv", symv), ("ger", ger), ("syr", syr), ("syr2", syr2)):
+            f.__name__ = f"mxb_{p}{name}"
+            g[f.__name__] = f
 
 
-def mxb_dgemv(h, layout, trans, m, n, alpha, A, lda, x, incx, beta, y, incy):
-    return _fn["dgemv"](h, layout, trans, m, n, alpha, _dp(A), lda, _dp(x), incx, beta, _dp(y), incy)
-
-
-def mxb_strmv(h, layout, uplo, trans, diag, n, A, lda, x, incx):
-    return _fn["strmv"](h, layout, uplo, trans, diag, n, _dp(A), lda, _dp(x), incx)
-
-
-def mxb_dtrmv(h, layout, uplo, trans, diag, n, A, lda, x, incx):
-    return _fn["dtrmv"](h, layout, uplo, trans, diag, n, _dp(A), lda, _dp(x), incx)
-
-
-def mxb_strsv(h, layout, uplo, trans, diag, n, A, lda, x, incx):
-    return _fn["strsv"](h, layout, uplo, trans, diag, n, _dp(A), lda, _dp(x), incx)
-
-
-def mxb_dtrsv(h, layout, uplo, trans, diag, n, A, lda, x, incx):
-    return _fn["dtrsv"](h, layout, uplo, trans, diag, n, _dp(A), lda, _dp(x), incx)
-
-
-def mxb_ssymv(h, layout, uplo, n, alpha, A, lda, x, incx, beta, y, incy):
-    return _fn["ssymv"](h, layout, uplo, n, alpha, _dp(A), lda, _dp(x), incx, beta, _dp(y), incy)
-
-
-def mxb_dsymv(h, layout, uplo, n, alpha, A, lda, x, incx, beta, y, incy):
-    return _fn["dsymv"](h, layout, uplo, n, alpha, _dp(A), lda, _dp(x), incx, beta, _dp(y), incy)
-
-
-def mxb_sger(h, layout, m, n, alpha, x, incx, y, incy, A, lda):
-    return _fn["sger"](h, layout, m, n, alpha, _dp(x), incx, _dp(y), incy, _dp(A), lda)
-
-
-def mxb_dger(h, layout, m, n, alpha, x, incx, y, incy, A, lda):
-    return _fn["dger"](h, layout, m, n, alpha, _dp(x), incx, _dp(y), incy, _dp(A), lda)
-
-
-def mxb_ssyr(h, layout, uplo, n, alpha, x, incx, A, lda):
-    return _fn["ssyr"](h, layout, uplo, n, alpha, _dp(x), incx, _dp(A), lda)
-
-
-def mxb_dsyr(h, layout, uplo, n, alpha, x, incx, A, lda):
-    return _fn["dsyr"](h, layout, uplo, n, alpha, _dp(x), incx, _dp(A), lda)
-
-
-def mxb_ssyr2(h, layout, uplo, n, alpha, x, incx, y, incy, A, lda):
-    return _fn["ssyr2"](h, layout, uplo, n, alpha, _dp(x), incx, _dp(y), incy, _dp(A), lda)
-
-
-def mxb_dsyr2(h, layout, uplo, n, alpha, x, incx, y, incy, A, lda):
-    return _fn["dsyr2"](h, layout, uplo, n, alpha, _dp(x), incx, _dp(y), incy, _dp(A), lda)
+_mk_level2()
 
 
 def routine(prefix: str, name: str):

@@ -4,6 +4,7 @@
 #include "common.hpp"
 #include "options.hpp"
 #include "plan.hpp"
+#include "skinny.hpp"
 #include "trisweep.hpp"
 
 namespace mxb {
@@ -126,7 +127,11 @@ size_t mxb_workspace_bytes(int routine, int elem_size, int64_t m, int64_t n)
         case MXB_DOT: case MXB_ASUM: case MXB_NRM2:
             return (size_t)option_default(MXB_OPT_REDUCE_BLOCKS) * 3 * sizeof(double);
         case MXB_GEMV: {
-            const size_t a = colacc_bound(m, n), b = colacc_bound(n, m);
+            size_t a = colacc_bound(m, n), b = colacc_bound(n, m);
+            a = a > b ? a : b;
+            // the skinny transposed product keeps one partial vector per block
+            const int64_t narrow = m < n ? m : n;
+            b = narrow <= 48 ? skinny_workspace_bytes(narrow, elem_size) : 0;
             return a > b ? a : b;
         }
         case MXB_TRMV: {

@@ -21,6 +21,7 @@
 #include "common.hpp"
 #include "options.hpp"
 #include "plan.hpp"
+#include "skinny.hpp"
 #include "trisweep.hpp"
 
 namespace mxb {
@@ -510,6 +511,11 @@ int gemv(mxb_handle_t h, int layout, int trans, int64_t m, int64_t n, T alpha, c
     if (!A) return -6;
     if (!x) return -8;
     const T* x0 = vec_base(x, lenx, incx);
+    // very short rows: several rows side by side per wavefront
+    if (no_trans && skinny_takes(SKINNY_GEMV_N, rows, cols, A, lda))
+        return skinny_gemv_n<T>(h, rows, cols, alpha, A, lda, x0, incx, beta, y0, incy);
+    if (!no_trans && skinny_takes(SKINNY_GEMV_T, rows, cols, A, lda))
+        return skinny_gemv_t<T>(h, rows, cols, alpha, A, lda, x0, incx, beta, y0, incy);
     if (no_trans) {
         RowdotArgs<T> a{rows, cols, A, lda, x0, incx, y0, incy, alpha, beta, 0, 0};
         return launch_rowdot(h, a, MODE_GENERAL, false);

@@ -1,0 +1,317 @@
+// Skinny matrices (Sec. 6.2.2, skinny matrix).  The paper loads the whole short vector into
+// registers before the quadratic loop and specialises the code for each register count.  Here a
+// row is so short (nv <= 20 vectors of 16 bytes) that a wavefront takes
+// G = 64 / nv rows side by side: lane l works on vector k = l % nv of row g = l / nv of the
+// wavefront's current G rows, so that the lanes read one contiguous run of G rows (the lanes past
+// G*nv idle), and every lane needs just ONE vector of the short operand, which it keeps in
+// registers for its whole life.  U such slots are in flight per lane.
+//   A*x:      per slot a 4-term dot, then a sum over the nv lanes of each row (ds_bpermute
+//             shuffles; the groups are not powers of two, so DPP rows do not fit);
+//   A^t*x:    per lane one running sum per owned column; at the end the G lanes that own the same
+//             columns and then the wavefronts of the block are folded through LDS, and a second
+//             kernel adds the per-block partial vectors in a fixed order;
+//   x*y^t:    a read-modify-write with y's vector in registers.
+#include "skinny.hpp"
+
+#include "options.hpp"
+
+namespace mxb {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / kWave;
+constexpr int kSlots = 8;                     // rows in flight per lane
+constexpr int64_t kSkinnyBlocksT = 1024;      // blocks (= partial vectors) of the transposed product
+
+template <typename T>
+struct SkinnyArgs {
+    int64_t M;           // rows
+    int N;               // columns
+    int nv;              // vectors per row = N / VEC
+    int64_t lda;
+    int64_t incs, incl;  // increments of the short (length N) and the long (length M) vector
+    T alpha, beta;
+};
+
+__device__ __forceinline__ float shfl_down(float v, int lane, int off)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((lane + off) << 2, __builtin_bit_cast(int, v)));
+}
+__device__ __forceinline__ double shfl_down(double v, int lane, int off)
+{
+    const uint64_t b = __builtin_bit_cast(uint64_t, v);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_ds_bpermute((lane + off) << 2, (int)(uint32_t)b);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_ds_bpermute((lane + off) << 2, (int)(uint32_t)(b >> 32));
+    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+
+// What a lane works on: vector k of row g (of the wavefront's G rows per slot).
+struct LaneMap {
+    int lane, G, g, k;
+    bool active;
+};
+__device__ __forceinline__ LaneMap lane_map(int nv)
+{
+    LaneMap m;
+    m.lane = threadIdx.x & (kWave - 1);
+    m.G = kWave / nv;
+    m.g = m.lane / nv;
+    m.k = m.lane - m.g * nv;
+    m.active = m.g < m.G;
+    if (!m.active) m.g = m.k = 0;      // idle lanes shadow lane 0: their loads stay in bounds and are discarded
+    return m;
+}
+
+// Rows are dealt in tiles of kSlots*G adjacent rows per wavefront, tiles cyclically to all
+// wavefronts of the grid: slot u of a tile holds rows tile*kSlots*G + u*G + g.
+template <typename T, int VEC>
+__global__ void __launch_bounds__(kThreads) skinny_gemv_n_kernel(const SkinnyArgs<T> p, const T* __restrict__ A,
+                                                                 const T* __restrict__ x, T* __restrict__ y)
+{
+    typedef typename VecOf<T, VEC>::type V;
+    const LaneMap m = lane_map(p.nv);
+    T xr[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) xr[e] = m.active ? x[(int64_t)(m.k * VEC + e) * p.incs] : T(0);
+    const int64_t rows_per_tile = (int64_t)kSlots * m.G;
+    const int64_t ntiles = (p.M + rows_per_tile - 1) / rows_per_tile;
+    const int64_t wave0 = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6), nwaves = (int64_t)gridDim.x * kWaves;
+    for (int64_t t = wave0; t < ntiles; t += nwaves) {
+        const int64_t row0 = t * rows_per_tile + m.g;
+        V a[kSlots];
+        if ((t + 1) * rows_per_tile <= p.M) {      // whole tile: no predicate, so that all loads issue back to back
+#pragma unroll
+            for (int u = 0; u < kSlots; ++u) a[u] = ld_stream(reinterpret_cast<const V*>(A + (row0 + (int64_t)u * m.G) * p.lda) + m.k);
+        } else {
+#pragma unroll
+            for (int u = 0; u < kSlots; ++u) {
+                const int64_t i = row0 + (int64_t)u * m.G;
+                a[u] = V(T(0));
+                if (i < p.M) a[u] = ld_stream(reinterpret_cast<const V*>(A + i * p.lda) + m.k);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);   // every load of the tile is in flight before the first FMA
+#pragma unroll
+        for (int u = 0; u < kSlots; ++u) {
+            T s = T(0);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) s = fmad(a[u][e], xr[e], s);
+            // sum over the nv lanes of the row: lane k adds lane k+off while that is still in the row
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) {
+                if (off < p.nv) {            // wave-uniform
+                    const T o = shfl_down(s, m.lane, off);
+                    s += (m.k + off < p.nv) ? o : T(0);
+                }
+            }
+            const int64_t i = row0 + (int64_t)u * m.G;
+            if (m.active && m.k == 0 && i < p.M) {
+                T* yp = y + i * p.incl;
+                T v = p.alpha * s;
+                if (p.beta != T(0)) v = fmad(p.beta, *yp, v);
+                *yp = v;
+            }
+        }
+    }
+}
+
+template <typename T, int VEC>
+__global__ void __launch_bounds__(kThreads) skinny_gemv_t_kernel(const SkinnyArgs<T> p, const T* __restrict__ A,
+                                                                 const T* __restrict__ x, T* __restrict__ partials)
+{
+    typedef typename VecOf<T, VEC>::type V;
+    __shared__ T red[kWaves][kWave][VEC];
+    const LaneMap m = lane_map(p.nv);
+    const int wave = threadIdx.x >> 6;
+    T acc[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e] = T(0);
+    const int64_t rows_per_tile = (int64_t)kSlots * m.G;
+    const int64_t ntiles = (p.M + rows_per_tile - 1) / rows_per_tile;
+    const int64_t wave0 = (int64_t)blockIdx.x * kWaves + wave, nwaves = (int64_t)gridDim.x * kWaves;
+    for (int64_t t = wave0; t < ntiles; t += nwaves) {
+        const int64_t row0 = t * rows_per_tile + m.g;
+        V a[kSlots];
+        T xi[kSlots];
+        if ((t + 1) * rows_per_tile <= p.M) {      // whole tile: no predicate
+#pragma unroll
+            for (int u = 0; u < kSlots; ++u) {
+                const int64_t i = row0 + (int64_t)u * m.G;
+                a[u] = ld_stream(reinterpret_cast<const V*>(A + i * p.lda) + m.k);
+                xi[u] = x[i * p.incl];
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < kSlots; ++u) {
+                const int64_t i = row0 + (int64_t)u * m.G;
+                a[u] = V(T(0));
+                xi[u] = T(0);
+                if (i < p.M) {
+                    a[u] = ld_stream(reinterpret_cast<const V*>(A + i * p.lda) + m.k);
+                    xi[u] = x[i * p.incl];
+                }
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < kSlots; ++u)
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[e] = fmad(a[u][e], xi[u], acc[e]);
+    }
+    // fold the lanes that own the same columns (g = 0..G-1, in that order), then the wavefronts
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) red[wave][m.lane][e] = m.active ? acc[e] : T(0);
+    __syncthreads();
+    for (int j = threadIdx.x; j < p.N; j += kThreads) {
+        const int k = j / VEC, e = j - k * VEC;
+        T s = T(0);
+        for (int w = 0; w < kWaves; ++w)
+            for (int g = 0; g < m.G; ++g) s += red[w][g * p.nv + k][e];
+        partials[(int64_t)blockIdx.x * p.N + j] = s;
+    }
+}
+
+constexpr int kCombineGroups = 16;
+
+// y[j] = alpha * sum_b partials[b][j] + beta*y[j], b ascending; 64 columns per block, 16
+// wavefronts each take every 16th partial vector, LDS folds them in wave order.
+template <typename T>
+__global__ void __launch_bounds__(kCombineGroups* kWave) skinny_combine_kernel(int64_t nparts, int N, const T* __restrict__ partials,
+                                                                               T alpha, T beta, T* __restrict__ y, int64_t incy)
+{
+    __shared__ T red[kCombineGroups][kWave];
+    const int tx = threadIdx.x & (kWave - 1), ty = threadIdx.x >> 6;
+    const int j = (int)blockIdx.x * kWave + tx;
+    T s = T(0);
+    if (j < N)
+        for (int64_t q = ty; q < nparts; q += kCombineGroups) s += partials[q * N + j];
+    red[ty][tx] = s;
+    __syncthreads();
+    if (ty != 0 || j >= N) return;
+    T tot = red[0][tx];
+#pragma unroll
+    for (int k = 1; k < kCombineGroups; ++k) tot += red[k][tx];
+    T* yp = y + (int64_t)j * incy;
+    T v = alpha * tot;
+    if (beta != T(0)) v = fmad(beta, *yp, v);
+    *yp = v;
+}
+
+template <typename T, int VEC>
+__global__ void __launch_bounds__(kThreads) skinny_ger_kernel(const SkinnyArgs<T> p, T* __restrict__ A, const T* __restrict__ x,
+                                                              const T* __restrict__ y)
+{
+    typedef typename VecOf<T, VEC>::type V;
+    const LaneMap m = lane_map(p.nv);
+    if (!m.active) return;               // no barrier below: idle lanes can leave
+    T yr[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) yr[e] = y[(int64_t)(m.k * VEC + e) * p.incs];
+    const int64_t rows_per_tile = (int64_t)kSlots * m.G;
+    const int64_t ntiles = (p.M + rows_per_tile - 1) / rows_per_tile;
+    const int64_t wave0 = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6), nwaves = (int64_t)gridDim.x * kWaves;
+    for (int64_t t = wave0; t < ntiles; t += nwaves) {
+        const int64_t row0 = t * rows_per_tile + m.g;
+        V a[kSlots];
+        T ax[kSlots];
+        if ((t + 1) * rows_per_tile <= p.M) {      // whole tile: no predicate
+#pragma unroll
+            for (int u = 0; u < kSlots; ++u) {
+                const int64_t i = row0 + (int64_t)u * m.G;
+                a[u] = ld_stream(reinterpret_cast<const V*>(A + i * p.lda) + m.k);
+                ax[u] = p.alpha * x[i * p.incl];
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < kSlots; ++u) {
+                const int64_t i = row0 + (int64_t)u * m.G;
+                a[u] = V(T(0));
+                ax[u] = T(0);
+                if (i < p.M) {
+                    a[u] = ld_stream(reinterpret_cast<const V*>(A + i * p.lda) + m.k);
+                    ax[u] = p.alpha * x[i * p.incl];
+                }
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);   // all loads of the tile are in flight before the first store
+#pragma unroll
+        for (int u = 0; u < kSlots; ++u) {
+            const int64_t i = row0 + (int64_t)u * m.G;
+            if (i < p.M) {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) a[u][e] = fmad(ax[u], yr[e], a[u][e]);
+                st_stream(reinterpret_cast<V*>(A + i * p.lda) + m.k, a[u]);
+            }
+        }
+    }
+}
+
+template <typename T>
+SkinnyArgs<T> make_args(int64_t rows, int64_t cols, int vec, int64_t lda, int64_t incs, int64_t incl, T alpha, T beta)
+{
+    SkinnyArgs<T> a;
+    a.M = rows; a.N = (int)cols; a.nv = (int)(cols / vec); a.lda = lda; a.incs = incs; a.incl = incl; a.alpha = alpha; a.beta = beta;
+    return a;
+}
+
+// Grid: one wavefront per tile of kSlots * (64 / nv) rows, capped.
+inline int64_t tile_blocks(int64_t rows, int nv, int64_t cap)
+{
+    const int64_t tiles = ceil_div(rows, (int64_t)kSlots * (kWave / nv));
+    const int64_t b = ceil_div(tiles, kWaves);
+    return b < cap ? b : cap;
+}
+
+#define MXB_SKINNY_DISPATCH(KERNEL, GRID, ...) \
+    hipLaunchKernelGGL((KERNEL<T, Full<T>::vec>), dim3((unsigned)(GRID)), dim3(kThreads), 0, h->stream, a, __VA_ARGS__)
+
+}  // namespace
+
+size_t skinny_workspace_bytes(int64_t cols, int elem_size)
+{
+    return align_up((size_t)kSkinnyBlocksT * (size_t)cols * (size_t)elem_size, 256);
+}
+
+template <typename T>
+int skinny_gemv_n(mxb_handle_t h, int64_t rows, int64_t cols, T alpha, const T* A, int64_t lda, const T* x0, int64_t incx, T beta,
+                  T* y0, int64_t incy)
+{
+    const SkinnyArgs<T> a = make_args<T>(rows, cols, Full<T>::vec, lda, incx, incy, alpha, beta);
+    MXB_SKINNY_DISPATCH(skinny_gemv_n_kernel, tile_blocks(rows, a.nv, (int64_t)kCUs * 16), A, x0, y0);
+    return launch_status();
+}
+
+template <typename T>
+int skinny_gemv_t(mxb_handle_t h, int64_t rows, int64_t cols, T alpha, const T* A, int64_t lda, const T* x0, int64_t incx, T beta,
+                  T* y0, int64_t incy)
+{
+    const SkinnyArgs<T> a = make_args<T>(rows, cols, Full<T>::vec, lda, incy, incx, alpha, beta);
+    const int64_t blocks = tile_blocks(rows, a.nv, kSkinnyBlocksT);
+    if (!h->ws || h->ws_bytes < (size_t)blocks * (size_t)cols * sizeof(T)) return MXB_ERR_WORKSPACE;
+    T* partials = static_cast<T*>(h->ws);
+    MXB_SKINNY_DISPATCH(skinny_gemv_t_kernel, blocks, A, x0, partials);
+    const int st = launch_status();
+    if (st != MXB_OK) return st;
+    hipLaunchKernelGGL(skinny_combine_kernel<T>, dim3((unsigned)ceil_div(cols, kWave)), dim3(kCombineGroups * kWave), 0, h->stream, blocks,
+                       (int)cols, partials, alpha, beta, y0, incy);
+    return launch_status();
+}
+
+template <typename T>
+int skinny_ger(mxb_handle_t h, int64_t rows, int64_t cols, T alpha, const T* x0, int64_t incx, const T* y0, int64_t incy, T* A,
+               int64_t lda)
+{
+    const SkinnyArgs<T> a = make_args<T>(rows, cols, Full<T>::vec, lda, incy, incx, alpha, T(0));
+    MXB_SKINNY_DISPATCH(skinny_ger_kernel, tile_blocks(rows, a.nv, (int64_t)kCUs * 16), A, x0, y0);
+    return launch_status();
+}
+
+#define MXB_SKINNY_INST(T)                                                                                                        \
+    template int skinny_gemv_n<T>(mxb_handle_t, int64_t, int64_t, T, const T*, int64_t, const T*, int64_t, T, T*, int64_t);       \
+    template int skinny_gemv_t<T>(mxb_handle_t, int64_t, int64_t, T, const T*, int64_t, const T*, int64_t, T, T*, int64_t);       \
+    template int skinny_ger<T>(mxb_handle_t, int64_t, int64_t, T, const T*, int64_t, const T*, int64_t, T*, int64_t);
+MXB_SKINNY_INST(float)
+MXB_SKINNY_INST(double)
+#undef MXB_SKINNY_INST
+
+}  // namespace mxb

@@ -8,6 +8,7 @@
 #include "common.hpp"
 #include "options.hpp"
 #include "plan.hpp"
+#include "skinny.hpp"
 #include "trisweep.hpp"
 
 namespace mxb {
@@ -246,6 +247,8 @@ int ger(mxb_handle_t h, int layout, int64_t m, int64_t n, T alpha, const T* x, i
     GerArgs<T> a;
     if (layout == MXB_ROW_MAJOR) a = GerArgs<T>{m, n, A, lda, vec_base(x, m, incx), incx, vec_base(y, n, incy), incy, alpha, 0, 0};
     else a = GerArgs<T>{n, m, A, lda, vec_base(y, n, incy), incy, vec_base(x, m, incx), incx, alpha, 0, 0};
+    if (skinny_takes(SKINNY_GER, a.M, a.N, a.A, a.lda))   // very short rows: several rows side by side per wavefront
+        return skinny_ger<T>(h, a.M, a.N, alpha, a.x, a.incx, a.y, a.incy, a.A, a.lda);
     a.rows_per_block = option(h, MXB_OPT_GER_ROWS_PER_BLOCK);
     constexpr int FV = Full<T>::vec;
     const bool vec = aligned16(A) && (lda % FV) == 0 && (a.N % FV) == 0;

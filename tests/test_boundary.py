@@ -191,3 +191,37 @@ def test_workspace_bound(B):
     assert B.mxb_workspace_bytes(B.TRMV, 4, 0, 16384) >= 16384 * 4
     assert 0 < B.mxb_workspace_bytes(B.SYMV, 4, 0, 16384) <= 0.03 * 16384 * 16384 * 4
     assert B.mxb_workspace_bytes(B.GEMV, 3, 4, 4) == 0 and B.mxb_workspace_bytes(B.GEMV, 4, -1, 4) == 0
+
+
+def test_binding_refuses_operands_that_are_too_small_or_of_the_wrong_type(B):
+    """The Python binding knows the size of a tensor operand and refuses, on the host, a call that
+    would overrun it (nothing is launched; CPU tensors suffice to show it)."""
+    import torch
+    st, h = B.mxb_create()
+    try:
+        f32, f64 = torch.float32, torch.float64
+        v = lambda n, dt=f32: torch.zeros(n, dtype=dt)
+        with pytest.raises(ValueError):
+            B.mxb_saxpy(h, 100, 1.0, v(50), 1, v(100), 1)
+        with pytest.raises(ValueError):
+            B.mxb_saxpy(h, 100, 1.0, v(100), 1, v(100), 2)            # y needs 199
+        with pytest.raises(ValueError):
+            B.mxb_sdot(h, 10, v(10), -3, v(10), 1, v(1))               # x needs 28
+        with pytest.raises(TypeError):
+            B.mxb_daxpy(h, 10, 1.0, v(10), 1, v(10, f64), 1)
+        with pytest.raises(ValueError):
+            B.mxb_sgemv(h, B.ROW_MAJOR, B.NO_TRANS, 8, 8, 1.0, v(8 * 10 - 3), 10, v(8), 1, 0.0, v(8), 1)   # needs 7*10+8
+        with pytest.raises(ValueError):
+            B.mxb_sgemv(h, B.ROW_MAJOR, B.TRANS, 8, 4, 1.0, v(32), 4, v(4), 1, 0.0, v(4), 1)               # x needs 8 when transposed
+        with pytest.raises(ValueError):
+            B.mxb_dgemv(h, B.COL_MAJOR, B.NO_TRANS, 8, 4, 1.0, v(8 * 4 - 1, f64), 8, v(4, f64), 1, 0.0, v(8, f64), 1)
+        with pytest.raises(ValueError):
+            B.mxb_strsv(h, B.ROW_MAJOR, B.LOWER, B.NO_TRANS, B.UNIT, 16, v(16 * 16 - 1), 16, v(16), 1)
+        with pytest.raises(ValueError):
+            B.mxb_ssyr2(h, B.ROW_MAJOR, B.LOWER, 16, 1.0, v(16), 1, v(15), 1, v(256), 16)
+        with pytest.raises(ValueError):
+            B.mxb_probe_read(h, 1024, v(100))
+        # exactly large enough: passes the binding's checks and reaches the library's own validation
+        assert B.mxb_sgemv(h, B.ROW_MAJOR, B.NO_TRANS, 8, 8, 1.0, v(7 * 10 + 8), 10, v(8), 0, 0.0, v(8), 1) == -9
+    finally:
+        B.mxb_destroy(h)

@@ -391,3 +391,32 @@ def test_trsv(blas, ctx, dt, layout, uplo, trans, diag):
     trsv_case(blas, ctx, dt, layout, uplo, trans, diag, 700, 0, -1)
     for n in (64, 515, 1536):
         trsv_case(blas, ctx, dt, layout, uplo, trans, diag, n, 0, 1, exact=True)
+
+
+# ----------------------------------------------------------------------------- skinny matrices
+def test_gemv_skinny(blas, ctx):
+    """Very short fp32 rows take the kernels that put several rows side by side in a wavefront
+    (row-major m x n with small n, or column-major with small m)."""
+    dt = np.float32
+    for trans in (O.NO_TRANS, O.TRANS):
+        for (m, n) in [(500000, 40), (600001, 12), (524288, 48), (500003, 4), (500000, 44)]:
+            for pad in (0, 4):
+                gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, 1.5, 0.5, pad, 1, 1)
+        for alpha, beta in [(1, 0), (1, 1), (-1, 0.5), (0, 0.5)]:
+            gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, 500000, 40, alpha, beta, 0, 1, 1)
+        for incx, incy in [(2, 3), (-1, 1), (1, -2)]:
+            gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, 500000, 24, 1.5, 0.5, 4, incx, incy)
+        gemv_case(blas, ctx, dt, O.COL_MAJOR, trans, 40, 500000, 1.5, 0.5, 0, 1, 1)       # the same bytes seen column-major
+        gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, 500000, 16, 3, -2, 0, 1, 1, ints=True)
+    for (m, n) in [(100000, 40), (131072, 16), (100001, 24), (150000, 48)]:             # not transposed: from 100000 rows
+        gemv_case(blas, ctx, dt, O.ROW_MAJOR, O.NO_TRANS, m, n, 1.5, 0.5, 0, 1, 1)
+
+
+@pytest.mark.parametrize("dt", DT)
+def test_ger_skinny(blas, ctx, dt):
+    for (m, n) in [(100000, 40), (131072, 16), (100001, 24), (150000, 4), (100000, 8)] + ([(120000, 48)] if dt == np.float32 else []):
+        for pad in (0, 4):
+            ger_case(blas, ctx, dt, O.ROW_MAJOR, m, n, 0.3, pad, 1, 1)
+    ger_case(blas, ctx, dt, O.ROW_MAJOR, 100000, 40, -1.5, 4, 2, -3)
+    ger_case(blas, ctx, dt, O.COL_MAJOR, 40, 100000, -1.5, 0, 1, 1)
+    ger_case(blas, ctx, dt, O.ROW_MAJOR, 100000, 32, 3, 0, 1, 1, ints=True)
