@@ -38,6 +38,10 @@ def parse():
     ap.add_argument("--only", type=str, default="")
     ap.add_argument("--list", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-from", nargs=2, metavar=("FETCH_DIR", "WRITE_DIR"),
+                    help="no GPU work: parse two rocprofv3 --pmc output folders of `bench.py --only $(bench.py --traffic-list)` "
+                         "(FETCH_SIZE, WRITE_SIZE) into profiles/traffic.json")
+    ap.add_argument("--traffic-list", action="store_true", help="print the --only list the traffic counters are collected on")
     ap.add_argument("--scale", type=int, default=1, help="divide every problem size by this (debugging only; "
                     "a scaled run is not the benchmark and says so in its output)")
     return ap.parse_args()
@@ -203,24 +207,102 @@ def cpu_baseline(torch):
     }
 
 
+CSRC = os.path.join(ROOT, "paper_2411_07211_amd", "csrc")
+TRAFFIC_JSON = os.path.join(ROOT, "profiles", "traffic.json")
+# Kernels (demangled-name fragments) behind the calls whose HBM traffic is recorded; the calls are
+# chosen so that no kernel is shared between two of them within one profiling run.
+TRAFFIC_KERNELS = {
+    "sgemv_n_16384_b0": ["rowdot_kernel<float, 4, 64, 2, 4, 0, false>"],
+    "sgemv_t_16384_b0": ["colacc_kernel<float, 4, 4, 1>", "colacc_combine_kernel<float>"],
+    "dgemv_n_16384": ["rowdot_kernel<double, 2, 64, 2, 4, 0, false>"],
+    "dgemv_t_16384": ["colacc_kernel<double, 2, 4, 1>", "colacc_combine_kernel<double>"],
+    "strmv_un_16384": ["gather_kernel<float>", "rowdot_kernel<float, 4, 64, 2, 4, 1, false>"],
+    "ssymv_l_16384": ["trisweep_kernel<float, 4, 2, false, 0, false>", "trisweep_combine_kernel<float, false, 0>"],
+    "sger_16384": ["ger_kernel<float, 4>"],
+    "saxpy": ["axpy_vec_kernel<float>"],
+    "sscal": ["scal_vec_kernel<float>"],
+    "sdot": ["reduce_vec_kernel<float, 0>", "reduce_final_kernel<float, 0, float>"],
+    "probe_copy": ["probe_copy_kernel"],
+    "probe_read": ["probe_read_kernel"],
+}
+TRAFFIC_ONLY = ",".join(TRAFFIC_KERNELS)
+
+
+def source_hash():
+    import hashlib
+    h = hashlib.sha256()
+    for f in sorted(os.listdir(CSRC)):
+        if f.endswith((".hip", ".hpp")):
+            h.update(open(os.path.join(CSRC, f), "rb").read())
+    return h.hexdigest()
+
+
 def measured_traffic():
     """HBM bytes per call taken from the rocprofv3 counter runs recorded in profiles/traffic.json;
     empty when the kernel sources have changed since those counters were collected."""
-    import hashlib
     try:
-        rec = json.load(open(os.path.join(ROOT, "profiles", "traffic.json")))
-        h = hashlib.sha256()
-        for f in ("common.hpp", "options.hpp", "plan.hpp", "matvec.hip"):
-            h.update(open(os.path.join(ROOT, "paper_2411_07211_amd", "csrc", f), "rb").read())
-        if h.hexdigest() != rec["source_sha256"]:
+        rec = json.load(open(TRAFFIC_JSON))
+        if source_hash() != rec["source_sha256"]:
             return {}
         return {k: v["hbm_bytes"] for k, v in rec["calls"].items()}
     except (OSError, KeyError, ValueError):
         return {}
 
 
+def write_traffic(fetch_dir, write_dir):
+    """Turns two rocprofv3 --pmc runs of `bench.py --only TRAFFIC_ONLY` (FETCH_SIZE in fetch_dir,
+    WRITE_SIZE in write_dir; both counters are KiB per dispatch) into profiles/traffic.json.  Each
+    counter is scaled by what it reports for mxb_probe_copy of 1 GiB, whose true traffic is known."""
+    import csv
+    import glob
+
+    def means(d, counter):
+        acc = {}
+        for f in glob.glob(os.path.join(d, "**", "*counter_collection.csv"), recursive=True):
+            for r in csv.DictReader(open(f)):
+                if r["Counter_Name"] == counter:
+                    acc.setdefault(r["Kernel_Name"], []).append(float(r["Counter_Value"]))
+        return {k: sum(v) / len(v) for k, v in acc.items()}
+
+    fetch, write = means(fetch_dir, "FETCH_SIZE"), means(write_dir, "WRITE_SIZE")
+
+    def find(table, frag):
+        hits = [v for k, v in table.items() if frag in k]
+        if len(hits) != 1:
+            raise SystemExit(f"bench.py: {len(hits)} kernels match '{frag}' in the counter run")
+        return hits[0]
+
+    copy_kib = 16384 * 16384 * 4 / 1024.0          # probe_copy moves this much each way
+    fscale = copy_kib / find(fetch, "probe_copy_kernel")
+    wscale = copy_kib / find(write, "probe_copy_kernel")
+    calls = {}
+    for call, frags in TRAFFIC_KERNELS.items():
+        ks, total = {}, 0.0
+        for frag in frags:
+            f, w = find(fetch, frag), find(write, frag)
+            ks[frag] = {"FETCH_SIZE_KiB": round(f, 1), "WRITE_SIZE_KiB": round(w, 1)}
+            total += (f * fscale + w * wscale) * 1024.0
+        calls[call] = {"kernels": ks, "hbm_bytes": int(round(total))}
+    rec = {
+        "note": "HBM traffic per call from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch, mean over the "
+                "dispatches of the run), each scaled by what the same counter reports for mxb_probe_copy of 1 GiB "
+                "(1048576 KiB each way).  Valid only for the kernel sources whose hash is recorded here; bench.py "
+                "reports null otherwise.  Written by `python bench.py --traffic-from FETCH_DIR WRITE_DIR`.",
+        "source_sha256": source_hash(), "fetch_scale": round(fscale, 6), "write_scale": round(wscale, 6), "calls": calls,
+    }
+    json.dump(rec, open(TRAFFIC_JSON, "w"), indent=1)
+    for call, v in calls.items():
+        print(f"{call:24s} {v['hbm_bytes']:>14d} B")
+
+
 def main():
     args = parse()
+    if args.traffic_list:
+        print(TRAFFIC_ONLY)
+        return
+    if args.traffic_from:
+        write_traffic(*args.traffic_from)
+        return
     if args.gpus != 1:
         print(f"bench.py: this build measures one GPU only (got --gpus {args.gpus}); run with --gpus 1", file=sys.stderr)
         sys.exit(2)

@@ -63,6 +63,27 @@ template <typename V> __device__ __forceinline__ V ld_stream(const V* p) { retur
 template <typename V> __device__ __forceinline__ void st_stream(V* p, V v) { __builtin_nontemporal_store(v, p); }
 
 // ------------------------------------------------------------------------------------------------
+// Tiles of a flat, contiguous stream of 16-byte vectors for 256-thread blocks that keep U vectors
+// per thread in flight.  Where whole groups of U*64 KiB are left, a tile is U runs of 4 KiB that
+// lie 64 KiB apart (the stream seen as rows of 64 KiB, 16 tiles side by side, as in the rank-1
+// update of a 16384-column matrix): read-modify-write streams run 4-9 points closer to the HBM
+// peak in this shape than in contiguous tiles of U*4 KiB.  The rest of the stream is cut into
+// contiguous tiles.  t: tile index; n2d: tiles in the 2-D part = (vectors / (U*4096)) * 16.
+constexpr int kPitchVec = 4096;
+template <int U>
+__device__ __forceinline__ void stream_tile(int64_t t, int64_t n2d, int64_t& base, int64_t& step)
+{
+    if (t < n2d) {
+        base = (t >> 4) * (int64_t)(U * kPitchVec) + (t & 15) * 256 + threadIdx.x;
+        step = kPitchVec;
+    } else {
+        base = t * (int64_t)(256 * U) + threadIdx.x;
+        step = 256;
+    }
+}
+inline int64_t stream_tiles_2d(int64_t nvec, int u) { return nvec / ((int64_t)u * kPitchVec) * 16; }
+
+// ------------------------------------------------------------------------------------------------
 // Wavefront reductions.  Lanes are organised as 4 DPP rows of 16.  Within a row: two quad
 // permutes (xor 1, xor 2), then row_half_mirror and row_mirror fold 4 -> 8 -> 16 lanes, after
 // which every lane of a row holds the row's sum.  Across rows: row_bcast15 adds row r into row

@@ -14,18 +14,26 @@ constexpr int kThreads = 256;
 constexpr int kUnroll = 4;
 typedef float f4 __attribute__((ext_vector_type(4)));
 
-__global__ void __launch_bounds__(kThreads) probe_copy_kernel(int64_t nvec, int64_t ntiles, const f4* __restrict__ src,
+__global__ void __launch_bounds__(kThreads) probe_copy_kernel(int64_t nvec, int64_t ntiles, int64_t n2d, const f4* __restrict__ src,
                                                               f4* __restrict__ dst)
 {
     for (int64_t t = blockIdx.x; t < ntiles; t += gridDim.x) {
-        const int64_t base = t * (kThreads * kUnroll) + threadIdx.x;
+        int64_t base, step;
+        stream_tile<kUnroll>(t, n2d, base, step);
         f4 a[kUnroll];
+        if (t < n2d) {      // whole tiles of the 2-D part: no predicate
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u)
-            if (base + u * kThreads < nvec) a[u] = ld_stream(src + base + u * kThreads);
+            for (int u = 0; u < kUnroll; ++u) a[u] = ld_stream(src + base + u * step);
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u)
-            if (base + u * kThreads < nvec) st_stream(dst + base + u * kThreads, a[u]);
+            for (int u = 0; u < kUnroll; ++u) st_stream(dst + base + u * step, a[u]);
+        } else {
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u)
+                if (base + u * step < nvec) a[u] = ld_stream(src + base + u * step);
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u)
+                if (base + u * step < nvec) st_stream(dst + base + u * step, a[u]);
+        }
     }
 }
 
@@ -154,7 +162,7 @@ int mxb_probe_copy(mxb_handle_t h, size_t bytes, const void* src, void* dst)
     const int64_t nvec = (int64_t)(bytes / 16), ntiles = ceil_div(nvec, kThreads * kUnroll);
     const int64_t cap = kCUs * option(h, MXB_OPT_L1_BLOCKS_PER_CU);
     hipLaunchKernelGGL(probe_copy_kernel, dim3((unsigned)(ntiles < cap ? ntiles : cap)), dim3(kThreads), 0, h->stream, nvec,
-                       ntiles, static_cast<const f4*>(src), static_cast<f4*>(dst));
+                       ntiles, stream_tiles_2d(nvec, kUnroll), static_cast<const f4*>(src), static_cast<f4*>(dst));
     return launch_status();
 }
 

@@ -19,11 +19,11 @@ constexpr int kScalUnroll = 2;  // scal reads and writes the same lines: shorter
 // ---------------------------------------------------------------------------------------------
 // streaming: axpy / scal on contiguous, 16-byte aligned data
 
-// Tiles of kThreads*U vectors.  Whole tiles carry no predicate, so that all loads of a tile are
-// issued back to back; the ragged rest (fewer than one tile of vectors, then fewer than VEC
-// elements) is handled by the last block, one vector resp. one element per thread.
+// Tiles of kThreads*U vectors (shaped by stream_tile).  Whole tiles carry no predicate, so that
+// all loads of a tile are issued back to back; the ragged rest (fewer than one tile of vectors,
+// then fewer than VEC elements) is handled by the last block, one vector resp. one element per thread.
 template <typename T>
-__global__ void __launch_bounds__(kThreads) axpy_vec_kernel(int64_t nvec, int64_t nfull, int tail, T alpha,
+__global__ void __launch_bounds__(kThreads) axpy_vec_kernel(int64_t nvec, int64_t nfull, int64_t n2d, int tail, T alpha,
                                                             const T* __restrict__ x, T* __restrict__ y)
 {
     constexpr int VEC = Full<T>::vec;
@@ -32,18 +32,19 @@ __global__ void __launch_bounds__(kThreads) axpy_vec_kernel(int64_t nvec, int64_
     const V* xv = reinterpret_cast<const V*>(x);
     V* yv = reinterpret_cast<V*>(y);
     for (int64_t t = blockIdx.x; t < nfull; t += gridDim.x) {
-        const int64_t base = t * (kThreads * U) + threadIdx.x;
+        int64_t base, step;
+        stream_tile<U>(t, n2d, base, step);
         V a[U], b[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) a[u] = ld_stream(xv + base + u * kThreads);
+        for (int u = 0; u < U; ++u) a[u] = ld_stream(xv + base + u * step);
 #pragma unroll
-        for (int u = 0; u < U; ++u) b[u] = ld_stream(yv + base + u * kThreads);
+        for (int u = 0; u < U; ++u) b[u] = ld_stream(yv + base + u * step);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
 #pragma unroll
             for (int k = 0; k < VEC; ++k) b[u][k] = fmad(alpha, a[u][k], b[u][k]);
-            st_stream(yv + base + u * kThreads, b[u]);
+            st_stream(yv + base + u * step, b[u]);
         }
     }
     if (blockIdx.x != gridDim.x - 1) return;
@@ -61,7 +62,7 @@ __global__ void __launch_bounds__(kThreads) axpy_vec_kernel(int64_t nvec, int64_
 }
 
 template <typename T>
-__global__ void __launch_bounds__(kThreads) scal_vec_kernel(int64_t nvec, int64_t nfull, int tail, T alpha,
+__global__ void __launch_bounds__(kThreads) scal_vec_kernel(int64_t nvec, int64_t nfull, int64_t n2d, int tail, T alpha,
                                                             T* __restrict__ x)
 {
     constexpr int VEC = Full<T>::vec;
@@ -69,16 +70,17 @@ __global__ void __launch_bounds__(kThreads) scal_vec_kernel(int64_t nvec, int64_
     typedef typename VecOf<T, VEC>::type V;
     V* xv = reinterpret_cast<V*>(x);
     for (int64_t t = blockIdx.x; t < nfull; t += gridDim.x) {
-        const int64_t base = t * (kThreads * U) + threadIdx.x;
+        int64_t base, step;
+        stream_tile<U>(t, n2d, base, step);
         V a[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) a[u] = ld_stream(xv + base + u * kThreads);
+        for (int u = 0; u < U; ++u) a[u] = ld_stream(xv + base + u * step);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
 #pragma unroll
             for (int k = 0; k < VEC; ++k) a[u][k] = alpha * a[u][k];
-            st_stream(xv + base + u * kThreads, a[u]);
+            st_stream(xv + base + u * step, a[u]);
         }
     }
     if (blockIdx.x != gridDim.x - 1) return;
@@ -357,7 +359,7 @@ int axpy(mxb_handle_t h, int64_t n, T alpha, const T* x, int64_t incx, T* y, int
         const int64_t nfull = nvec / (kThreads * kUnroll);
         const int64_t grid = nfull < 1 ? 1 : (nfull < kCUs * bpc ? nfull : kCUs * bpc);
         hipLaunchKernelGGL(axpy_vec_kernel<T>, dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, nfull,
-                           (int)(n % VEC), alpha, x, y);
+                           stream_tiles_2d(nvec, kUnroll), (int)(n % VEC), alpha, x, y);
     } else {
         const int64_t nfull = n / (kThreads * kStridedUnroll);
         const int64_t grid = nfull < 1 ? 1 : (nfull < kCUs * bpc ? nfull : kCUs * bpc);
@@ -381,7 +383,7 @@ int scal(mxb_handle_t h, int64_t n, T alpha, T* x, int64_t incx)
         const int64_t nfull = nvec / (kThreads * kScalUnroll);
         const int64_t grid = nfull < 1 ? 1 : (nfull < kCUs * bpc ? nfull : kCUs * bpc);
         hipLaunchKernelGGL(scal_vec_kernel<T>, dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, nfull,
-                           (int)(n % VEC), alpha, x);
+                           stream_tiles_2d(nvec, kScalUnroll), (int)(n % VEC), alpha, x);
     } else {
         const int64_t nfull = n / (kThreads * kStridedUnroll);
         const int64_t grid = nfull < 1 ? 1 : (nfull < kCUs * bpc ? nfull : kCUs * bpc);

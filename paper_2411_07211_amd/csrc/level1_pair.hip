@@ -34,8 +34,8 @@ template <typename T> struct OpLinear {
 };
 
 template <typename T, typename Op>
-__global__ void __launch_bounds__(kThreads) pair_vec_kernel(int64_t nvec, int64_t nfull, int tail, T* __restrict__ x, T* __restrict__ y,
-                                                            const Op op)
+__global__ void __launch_bounds__(kThreads) pair_vec_kernel(int64_t nvec, int64_t nfull, int64_t n2d, int tail, T* __restrict__ x,
+                                                            T* __restrict__ y, const Op op)
 {
     constexpr int VEC = Full<T>::vec;
     constexpr int U = kUnroll;
@@ -43,12 +43,13 @@ __global__ void __launch_bounds__(kThreads) pair_vec_kernel(int64_t nvec, int64_
     V* xv = reinterpret_cast<V*>(x);
     V* yv = reinterpret_cast<V*>(y);
     for (int64_t t = blockIdx.x; t < nfull; t += gridDim.x) {
-        const int64_t base = t * (kThreads * U) + threadIdx.x;
+        int64_t base, step;
+        stream_tile<U>(t, n2d, base, step);
         V a[U], b[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) a[u] = ld_stream(xv + base + u * kThreads);
+        for (int u = 0; u < U; ++u) a[u] = ld_stream(xv + base + u * step);
 #pragma unroll
-        for (int u = 0; u < U; ++u) b[u] = Op::kReadY ? ld_stream(yv + base + u * kThreads) : V(T(0));
+        for (int u = 0; u < U; ++u) b[u] = Op::kReadY ? ld_stream(yv + base + u * step) : V(T(0));
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -59,8 +60,8 @@ __global__ void __launch_bounds__(kThreads) pair_vec_kernel(int64_t nvec, int64_
                 a[u][k] = p;
                 b[u][k] = q;
             }
-            if (Op::kWriteX) st_stream(xv + base + u * kThreads, a[u]);
-            st_stream(yv + base + u * kThreads, b[u]);
+            if (Op::kWriteX) st_stream(xv + base + u * step, a[u]);
+            st_stream(yv + base + u * step, b[u]);
         }
     }
     if (blockIdx.x != gridDim.x - 1) return;
@@ -119,8 +120,8 @@ int pair_op(mxb_handle_t h, int64_t n, T* x, int64_t incx, T* y, int64_t incy, c
     if (incx == 1 && incy == 1 && aligned16(x) && aligned16(y)) {
         const int64_t nvec = n / VEC, nfull = nvec / (kThreads * kUnroll);
         const int64_t grid = nfull < 1 ? 1 : (nfull < cap ? nfull : cap);
-        hipLaunchKernelGGL((pair_vec_kernel<T, Op>), dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, nfull, (int)(n % VEC), x, y,
-                           op);
+        hipLaunchKernelGGL((pair_vec_kernel<T, Op>), dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, nfull,
+                           stream_tiles_2d(nvec, kUnroll), (int)(n % VEC), x, y, op);
     } else {
         const int64_t nfull = n / (kThreads * kStridedUnroll);
         const int64_t grid = nfull < 1 ? 1 : (nfull < cap ? nfull : cap);

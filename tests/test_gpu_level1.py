@@ -9,7 +9,7 @@ from parity import bits_equal, check_close, prefix_of, to_dev, to_host
 pytestmark = pytest.mark.gpu
 
 DT = [np.float32, np.float64]
-SIZES = [1, 2, 3, 4, 5, 63, 64, 65, 255, 256, 257, 1000, 4097, 100003, (1 << 20) + 7]
+SIZES = [1, 2, 3, 4, 5, 63, 64, 65, 255, 256, 257, 1000, 4097, 32768, 65536, 65540, 100003, 131071, (1 << 20) + 7]
 INCS = [(1, 1), (2, 3), (-1, 1), (1, -2), (-3, -2)]
 
 
