@@ -221,7 +221,7 @@ TRAFFIC_KERNELS = {
     "sger_16384": ["ger_kernel<float, 4>"],
     "saxpy": ["axpy_vec_kernel<float>"],
     "sscal": ["scal_vec_kernel<float>"],
-    "sdot": ["reduce_vec_kernel<float, 0>", "reduce_final_kernel<float, 0, float>"],
+    "sdot": ["reduce_vec_kernel<float, 0, float>", "reduce_final_kernel<float, 0, float>"],
     "probe_copy": ["probe_copy_kernel"],
     "probe_read": ["probe_read_kernel"],
 }

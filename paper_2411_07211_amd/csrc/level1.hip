@@ -144,6 +144,9 @@ __global__ void __launch_bounds__(kThreads) scal_strided_kernel(int64_t n, int64
 
 enum { OP_DOT = 0, OP_ASUM = 1, OP_NRM2 = 2, OP_DSDOT = 3 };
 
+// Up to this many tiles one block does everything (a second launch costs more than a few tiles).
+constexpr int64_t kSingleBlockTiles = 4;
+
 // Constants of Blue's scaled sum of squares for fp64 (as restated by Anderson, "Safe scaling in
 // the level 1 BLAS", 2017): values above kBig are scaled down, values below kSmall are scaled up,
 // so that no square overflows or underflows; the rest is summed as is.
@@ -205,8 +208,13 @@ template <> struct Acc<double, OP_NRM2> {
     __device__ __forceinline__ void get(double* o) const { o[0] = med; o[1] = big; o[2] = sml; }
 };
 
-template <typename T, int OP>
-__device__ __forceinline__ void block_partial(const Acc<T, OP>* acc, int nacc, double* __restrict__ partials)
+template <typename T, int OP, typename RES> __device__ __forceinline__ void finish(const double* v, RES* __restrict__ result);
+
+// Folds the block's running sums.  A grid of several blocks hands them to the second pass; a
+// grid of one block (short vectors, where a second launch would double the latency) finishes
+// the result itself.
+template <typename T, int OP, typename RES>
+__device__ __forceinline__ void block_partial(const Acc<T, OP>* acc, int nacc, double* __restrict__ partials, RES* __restrict__ result)
 {
     constexpr int K = Acc<T, OP>::K;
     __shared__ double slots[kThreads / kWave];
@@ -220,18 +228,22 @@ __device__ __forceinline__ void block_partial(const Acc<T, OP>* acc, int nacc, d
         for (int k = 0; k < K; ++k) v[k] += t[k];
     }
 #pragma unroll
-    for (int k = 0; k < K; ++k) {
-        const double s = block_sum<kThreads / kWave>(v[k], slots);
-        if (threadIdx.x == 0) partials[(int64_t)blockIdx.x * K + k] = s;
+    for (int k = 0; k < K; ++k) v[k] = block_sum<kThreads / kWave>(v[k], slots);
+    if (threadIdx.x != 0) return;
+    if (gridDim.x == 1) {
+        finish<T, OP, RES>(v, result);
+    } else {
+#pragma unroll
+        for (int k = 0; k < K; ++k) partials[(int64_t)blockIdx.x * K + k] = v[k];
     }
 }
 
 // pass 1 on contiguous, aligned data: whole tiles without predicates, the ragged rest by the
 // last block.
-template <typename T, int OP>
+template <typename T, int OP, typename RES>
 __global__ void __launch_bounds__(kThreads) reduce_vec_kernel(int64_t nvec, int64_t nfull, int tail,
                                                               const T* __restrict__ x, const T* __restrict__ y,
-                                                              double* __restrict__ partials)
+                                                              double* __restrict__ partials, RES* __restrict__ result)
 {
     constexpr int VEC = Full<T>::vec;
     constexpr bool TWO = OP == OP_DOT || OP == OP_DSDOT;
@@ -266,14 +278,14 @@ __global__ void __launch_bounds__(kThreads) reduce_vec_kernel(int64_t nvec, int6
             acc[0].add(x[i], TWO ? y[i] : T(0));
         }
     }
-    block_partial<T, OP>(acc, VEC, partials);
+    block_partial<T, OP, RES>(acc, VEC, partials, result);
 }
 
 // pass 1 with arbitrary increments (or unaligned data)
-template <typename T, int OP>
+template <typename T, int OP, typename RES>
 __global__ void __launch_bounds__(kThreads) reduce_strided_kernel(int64_t n, int64_t nfull, const T* __restrict__ x, int64_t incx,
                                                                   const T* __restrict__ y, int64_t incy,
-                                                                  double* __restrict__ partials)
+                                                                  double* __restrict__ partials, RES* __restrict__ result)
 {
     constexpr bool TWO = OP == OP_DOT || OP == OP_DSDOT;
     constexpr int U = kStridedUnroll;
@@ -293,24 +305,14 @@ __global__ void __launch_bounds__(kThreads) reduce_strided_kernel(int64_t n, int
     }
     if (blockIdx.x == gridDim.x - 1)
         for (int64_t i = nfull * (kThreads * U) + threadIdx.x; i < n; i += kThreads) acc[0].add(x[i * incx], TWO ? y[i * incy] : T(0));
-    block_partial<T, OP>(acc, NACC, partials);
+    block_partial<T, OP, RES>(acc, NACC, partials, result);
 }
 
-// pass 2: one block adds the per-block partials in a fixed order and finishes the result.
+// Turns the K sums of a reduction into its result (thread 0 of the last pass).
 template <typename T, int OP, typename RES>
-__global__ void __launch_bounds__(kThreads) reduce_final_kernel(int nparts, const double* __restrict__ partials,
-                                                                RES* __restrict__ result)
+__device__ __forceinline__ void finish(const double* v, RES* __restrict__ result)
 {
     constexpr int K = Acc<T, OP>::K;
-    __shared__ double slots[kThreads / kWave];
-    double v[K];
-#pragma unroll
-    for (int k = 0; k < K; ++k) {
-        double s = 0.0;
-        for (int p = threadIdx.x; p < nparts; p += kThreads) s += partials[(int64_t)p * K + k];
-        v[k] = block_sum<kThreads / kWave>(s, slots);
-    }
-    if (threadIdx.x != 0) return;
     if constexpr (OP != OP_NRM2) {
         *result = (RES)v[0];
     } else if constexpr (K == 1) {
@@ -334,6 +336,23 @@ __global__ void __launch_bounds__(kThreads) reduce_final_kernel(int nparts, cons
         }
         *result = r;
     }
+}
+
+// pass 2: one block adds the per-block partials in a fixed order and finishes the result.
+template <typename T, int OP, typename RES>
+__global__ void __launch_bounds__(kThreads) reduce_final_kernel(int nparts, const double* __restrict__ partials,
+                                                                RES* __restrict__ result)
+{
+    constexpr int K = Acc<T, OP>::K;
+    __shared__ double slots[kThreads / kWave];
+    double v[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        double s = 0.0;
+        for (int p = threadIdx.x; p < nparts; p += kThreads) s += partials[(int64_t)p * K + k];
+        v[k] = block_sum<kThreads / kWave>(s, slots);
+    }
+    if (threadIdx.x == 0) finish<T, OP, RES>(v, result);
 }
 
 template <typename T>
@@ -412,17 +431,17 @@ int reduce(mxb_handle_t h, int64_t n, const T* x, int64_t incx, const T* y, int6
     if (contiguous) {
         const int64_t nvec = n / VEC;
         const int64_t nfull = nvec / (kThreads * (TWO ? kUnroll : 2 * kUnroll));
-        grid = nfull < 1 ? 1 : (nfull < max_blocks ? nfull : max_blocks);
-        hipLaunchKernelGGL((reduce_vec_kernel<T, OP>), dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, nfull,
-                           (int)(n % VEC), x, y, partials);
+        grid = nfull <= kSingleBlockTiles ? 1 : (nfull < max_blocks ? nfull : max_blocks);
+        hipLaunchKernelGGL((reduce_vec_kernel<T, OP, RES>), dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, nfull,
+                           (int)(n % VEC), x, y, partials, result);
     } else {
         const int64_t nfull = n / (kThreads * kStridedUnroll);
-        grid = nfull < 1 ? 1 : (nfull < max_blocks ? nfull : max_blocks);
-        hipLaunchKernelGGL((reduce_strided_kernel<T, OP>), dim3((unsigned)grid), dim3(kThreads), 0, h->stream, n, nfull,
-                           vec_base(x, n, incx), incx, y ? vec_base(y, n, incy) : nullptr, incy, partials);
+        grid = nfull <= kSingleBlockTiles ? 1 : (nfull < max_blocks ? nfull : max_blocks);
+        hipLaunchKernelGGL((reduce_strided_kernel<T, OP, RES>), dim3((unsigned)grid), dim3(kThreads), 0, h->stream, n, nfull,
+                           vec_base(x, n, incx), incx, y ? vec_base(y, n, incy) : nullptr, incy, partials, result);
     }
     int st = launch_status();
-    if (st != MXB_OK) return st;
+    if (st != MXB_OK || grid == 1) return st;      // a single block has written the result itself
     hipLaunchKernelGGL((reduce_final_kernel<T, OP, RES>), dim3(1), dim3(kThreads), 0, h->stream, (int)grid, partials, result);
     return launch_status();
 }
@@ -535,7 +554,7 @@ int iamax(mxb_handle_t h, int64_t n, const T* x, int64_t incx, int64_t* result)
     if (!h->ws || h->ws_bytes < (size_t)max_blocks * sizeof(Cand)) return MXB_ERR_WORKSPACE;
     Cand* partials = static_cast<Cand*>(h->ws);
     const int64_t nfull = n / (kThreads * kStridedUnroll);
-    const int64_t grid = nfull < 1 ? 1 : (nfull < max_blocks ? nfull : max_blocks);
+    const int64_t grid = nfull <= kSingleBlockTiles ? 1 : (nfull < max_blocks ? nfull : max_blocks);
     hipLaunchKernelGGL(iamax_kernel<T>, dim3((unsigned)grid), dim3(kThreads), 0, h->stream, n, nfull, x, incx, partials);
     int st = launch_status();
     if (st != MXB_OK) return st;
