@@ -62,6 +62,22 @@ template <typename T> struct Full { static constexpr int vec = 16 / sizeof(T); }
 template <typename V> __device__ __forceinline__ V ld_stream(const V* p) { return __builtin_nontemporal_load(p); }
 template <typename V> __device__ __forceinline__ void st_stream(V* p, V v) { __builtin_nontemporal_store(v, p); }
 
+// The same for VEC elements of a matrix row.  A 128-bit global load or store needs the alignment
+// of one element only, so the rows of a matrix may start anywhere (any pitch, any base address):
+// the vector is declared with element alignment and still moves as one 128-bit access.
+template <typename T, int VEC>
+__device__ __forceinline__ typename VecOf<T, VEC>::type ld_matrix(const T* p)
+{
+    typedef typename VecOf<T, VEC>::type Loose __attribute__((aligned(sizeof(T))));
+    return __builtin_nontemporal_load(reinterpret_cast<const Loose*>(p));
+}
+template <typename T, int VEC>
+__device__ __forceinline__ void st_matrix(T* p, typename VecOf<T, VEC>::type v)
+{
+    typedef typename VecOf<T, VEC>::type Loose __attribute__((aligned(sizeof(T))));
+    __builtin_nontemporal_store(v, reinterpret_cast<Loose*>(p));
+}
+
 // ------------------------------------------------------------------------------------------------
 // Tiles of a flat, contiguous stream of 16-byte vectors for 256-thread blocks that keep U vectors
 // per thread in flight.  Where whole groups of U*64 KiB are left, a tile is U runs of 4 KiB that

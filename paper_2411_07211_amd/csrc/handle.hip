@@ -125,7 +125,7 @@ size_t mxb_workspace_bytes(int routine, int elem_size, int64_t m, int64_t n)
         for (int vec : {1, full}) {
             const ColaccPlan p = colacc_plan(rows, cols, elem_size, vec, option_default(MXB_OPT_COLACC_TARGET_BLOCKS),
                                              kColaccNarrowBlocks, option_default(MXB_OPT_COLACC_MIN_ROWS));
-            const size_t need = p.nparts > 1 ? (size_t)p.nparts * (size_t)cols * (size_t)elem_size : 0;
+            const size_t need = p.nparts > 1 ? (size_t)p.nparts * (size_t)(ceil_div(cols, full) * full) * (size_t)elem_size : 0;
             b = need > b ? need : b;
         }
         return align_up(b, 256);

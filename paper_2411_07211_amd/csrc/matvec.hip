@@ -72,7 +72,7 @@ __device__ __forceinline__ void rowdot_batch(const T* const (&arow)[R], const T*
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
-        for (int r = 0; r < R; ++r) av[u][r] = ld_stream(reinterpret_cast<const V*>(arow[r] + c + u * STEP));
+        for (int r = 0; r < R; ++r) av[u][r] = ld_matrix<T, VEC>(arow[r] + c + u * STEP);
 #pragma unroll
     for (int u = 0; u < U; ++u) xv[u] = *reinterpret_cast<const V*>(xs_at_c + u * STEP);
     __builtin_amdgcn_sched_barrier(0);   // keep every load of the batch ahead of the first FMA
@@ -215,7 +215,8 @@ struct ColaccArgs {
     T* y;                // logical element 0 (length N); written directly when there is one row group
     int64_t incy;
     T alpha, beta;
-    T* partials;         // [row groups][N] when there are several row groups
+    T* partials;         // [row groups][ppitch] when there are several row groups
+    int64_t ppitch;      // N rounded up to whole vectors
     int64_t rows_per_block;   // WR == 4 only: rows of one slab
 };
 
@@ -245,9 +246,17 @@ __global__ void __launch_bounds__(kColaccThreads) colacc_kernel(const ColaccArgs
     const int wc = wave % WC, wr = wave / WC;
     const int64_t cblock0 = (int64_t)blockIdx.x * (CV * SPAN);
     const int64_t c = cblock0 + (int64_t)(wc * kWave + lane) * VEC;
+    // A vector that would run past column N is moved back so that it ends at N (the host makes sure
+    // that N >= VEC; element alignment is all a matrix load needs): its first `shift` elements are
+    // the neighbouring lane's columns and are dropped when the sums are written.
     bool col_ok[CV];
+    int shift[CV];
 #pragma unroll
-    for (int v = 0; v < CV; ++v) col_ok[v] = c + v * SPAN + VEC <= p.N;
+    for (int v = 0; v < CV; ++v) {
+        const int64_t cv = c + v * SPAN;
+        col_ok[v] = cv < p.N;
+        shift[v] = (VEC > 1 && col_ok[v] && cv + VEC > p.N) ? (int)(cv + VEC - p.N) : 0;
+    }
 
     // Rows are visited in batches of U: rows r0 + u*rstep (u < U), then r0 += radvance.
     int64_t r0, rstep, radvance, rend = p.M;
@@ -275,7 +284,7 @@ __global__ void __launch_bounds__(kColaccThreads) colacc_kernel(const ColaccArgs
     // so that the loads below carry no predicate and can all be issued back to back.
     const T* acol[CV];
 #pragma unroll
-    for (int v = 0; v < CV; ++v) acol[v] = p.A + (col_ok[v] ? c + v * SPAN : cblock0);
+    for (int v = 0; v < CV; ++v) acol[v] = p.A + (col_ok[v] ? c + v * SPAN - shift[v] : imin(cblock0, p.N - VEC));
     for (; r0 + (int64_t)(U - 1) * rstep < rend; r0 += radvance) {
         V a[U][CV];
         T xi[U];
@@ -283,7 +292,7 @@ __global__ void __launch_bounds__(kColaccThreads) colacc_kernel(const ColaccArgs
         for (int u = 0; u < U; ++u) {
             const int64_t i = r0 + (int64_t)u * rstep;
 #pragma unroll
-            for (int v = 0; v < CV; ++v) a[u][v] = ld_stream(reinterpret_cast<const V*>(acol[v] + i * p.lda));
+            for (int v = 0; v < CV; ++v) a[u][v] = ld_matrix<T, VEC>(acol[v] + i * p.lda);
             xi[u] = p.x[i * p.incx];
         }
         __builtin_amdgcn_sched_barrier(0);   // keep every load of the batch ahead of the first FMA
@@ -299,7 +308,7 @@ __global__ void __launch_bounds__(kColaccThreads) colacc_kernel(const ColaccArgs
         const T xi = p.x[r0 * p.incx];
 #pragma unroll
         for (int v = 0; v < CV; ++v) {
-            const V a = ld_stream(reinterpret_cast<const V*>(acol[v] + r0 * p.lda));
+            const V a = ld_matrix<T, VEC>(acol[v] + r0 * p.lda);
 #pragma unroll
             for (int k = 0; k < VEC; ++k) acc[v][k] = fmad(a[k], xi, acc[v][k]);
         }
@@ -321,20 +330,25 @@ __global__ void __launch_bounds__(kColaccThreads) colacc_kernel(const ColaccArgs
 #pragma unroll
     for (int v = 0; v < CV; ++v) {
         if (!col_ok[v]) continue;
-        const int64_t cv = c + v * SPAN;
+        const int64_t cv = c + v * SPAN - shift[v];      // column of element 0 of the vector
         if (gridDim.y == 1) {
 #pragma unroll
             for (int k = 0; k < VEC; ++k) {
+                if (k < shift[v]) continue;
                 T* yp = p.y + (cv + k) * p.incy;
                 T val = p.alpha * acc[v][k];
                 if (p.beta != T(0)) val = fmad(p.beta, *yp, val);
                 *yp = val;
             }
-        } else {
+        } else if (shift[v] == 0) {
             V val;
 #pragma unroll
             for (int k = 0; k < VEC; ++k) val[k] = acc[v][k];
-            *reinterpret_cast<V*>(p.partials + (int64_t)blockIdx.y * p.N + cv) = val;
+            *reinterpret_cast<V*>(p.partials + (int64_t)blockIdx.y * p.ppitch + cv) = val;
+        } else {
+#pragma unroll
+            for (int k = 0; k < VEC; ++k)
+                if (k >= shift[v]) p.partials[(int64_t)blockIdx.y * p.ppitch + cv + k] = acc[v][k];
         }
     }
 }
@@ -344,7 +358,7 @@ constexpr int kCombineGroups = 16;
 // y[j] = alpha * sum_p partials[p][j] + beta*y[j], p ascending.  64 columns per block; the 16
 // wavefronts of the block each take every 16th slab, LDS folds them in wave order.
 template <typename T>
-__global__ void __launch_bounds__(kCombineGroups* kWave) colacc_combine_kernel(int64_t nparts, int64_t N,
+__global__ void __launch_bounds__(kCombineGroups* kWave) colacc_combine_kernel(int64_t nparts, int64_t N, int64_t ppitch,
                                                                                const T* __restrict__ partials, T alpha, T beta,
                                                                                T* __restrict__ y, int64_t incy)
 {
@@ -354,7 +368,7 @@ __global__ void __launch_bounds__(kCombineGroups* kWave) colacc_combine_kernel(i
     T s = T(0);
     if (j < N) {
 #pragma unroll 4
-        for (int64_t q = ty; q < nparts; q += kCombineGroups) s += partials[q * N + j];
+        for (int64_t q = ty; q < nparts; q += kCombineGroups) s += partials[q * ppitch + j];
     }
     red[ty][tx] = s;
     __syncthreads();
@@ -428,7 +442,6 @@ int launch_rowdot(mxb_handle_t h, RowdotArgs<T> a, int mode, bool unit)
     xc = ceil_div(xc, 256) * 256;
     a.xchunk = (int)xc;
     a.x_contig = a.incx == 1 && aligned16(a.x);
-    const bool vec = aligned16(a.A) && (a.lda % FV) == 0;
 #define MXB_ROWDOT(VEC_)                                                                                   \
     switch (mode) {                                                                                        \
         case MODE_GENERAL: launch_rowdot_shape<T, VEC_, MODE_GENERAL, false>(h, a); break;                  \
@@ -440,7 +453,8 @@ int launch_rowdot(mxb_handle_t h, RowdotArgs<T> a, int mode, bool unit)
             if (unit) launch_rowdot_shape<T, VEC_, MODE_LOWER, true>(h, a);                                 \
             else launch_rowdot_shape<T, VEC_, MODE_LOWER, false>(h, a);                                     \
     }
-    if (vec) { MXB_ROWDOT(FV) } else { MXB_ROWDOT(1) }
+    MXB_ROWDOT(FV)   // rows may start at any element: the loads need element alignment only, and the kernel
+                     // takes the columns past the last whole vector one by one
 #undef MXB_ROWDOT
     return launch_status();
 }
@@ -460,13 +474,17 @@ template <typename T>
 int launch_colacc(mxb_handle_t h, ColaccArgs<T> a)
 {
     constexpr int FV = Full<T>::vec;
-    const bool vec = aligned16(a.A) && (a.lda % FV) == 0 && (a.N % FV) == 0;
+    // Any pitch, any base address and any width of at least one vector: matrix loads need element
+    // alignment only and the kernel moves the last vector of a ragged row back.
+    // (a ragged row of up to 64 elements keeps more lanes busy with one element per lane)
+    const bool vec = a.N % FV == 0 || a.N > kWave;
     const ColaccPlan pl = colacc_plan(a.M, a.N, (int)sizeof(T), vec ? FV : 1, option(h, MXB_OPT_COLACC_TARGET_BLOCKS),
                                       colacc_narrow_target(h), option(h, MXB_OPT_COLACC_MIN_ROWS));
     a.rows_per_block = pl.rows_per_block;
     a.partials = nullptr;
+    a.ppitch = ceil_div(a.N, FV) * FV;
     if (pl.nparts > 1) {
-        if (!h->ws || h->ws_bytes < (size_t)pl.nparts * (size_t)a.N * sizeof(T)) return MXB_ERR_WORKSPACE;
+        if (!h->ws || h->ws_bytes < (size_t)pl.nparts * (size_t)a.ppitch * sizeof(T)) return MXB_ERR_WORKSPACE;
         a.partials = static_cast<T*>(h->ws);
     }
     if (vec) launch_colacc_inst<T, FV>(h, a, pl);
@@ -474,7 +492,7 @@ int launch_colacc(mxb_handle_t h, ColaccArgs<T> a)
     int st = launch_status();
     if (st != MXB_OK || pl.nparts == 1) return st;
     hipLaunchKernelGGL(colacc_combine_kernel<T>, dim3((unsigned)ceil_div(a.N, kWave)), dim3(kCombineGroups * kWave), 0,
-                       h->stream, pl.nparts, a.N, a.partials, a.alpha, a.beta, a.y, a.incy);
+                       h->stream, pl.nparts, a.N, a.ppitch, a.partials, a.alpha, a.beta, a.y, a.incy);
     return launch_status();
 }
 
@@ -520,7 +538,7 @@ int gemv(mxb_handle_t h, int layout, int trans, int64_t m, int64_t n, T alpha, c
         RowdotArgs<T> a{rows, cols, A, lda, x0, incx, y0, incy, alpha, beta, 0, 0};
         return launch_rowdot(h, a, MODE_GENERAL, false);
     }
-    ColaccArgs<T> a{rows, cols, A, lda, x0, incx, y0, incy, alpha, beta, nullptr, 0};
+    ColaccArgs<T> a{rows, cols, A, lda, x0, incx, y0, incy, alpha, beta, nullptr, 0, 0};
     return launch_colacc(h, a);
 }
 
@@ -741,7 +759,7 @@ int trsv(mxb_handle_t h, int layout, int uplo, int trans, int diag, int64_t n, c
                 RowdotArgs<T> a{nb, ns, A + r0 * lda + s0, lda, x0 + s0 * incx, incx, x0 + r0 * incx, incx, T(-1), T(1), 0, 0};
                 st = launch_rowdot(h, a, MODE_GENERAL, false);
             } else {          // b_k -= T[solved rows, block columns]^t * z[solved]
-                ColaccArgs<T> a{ns, nb, A + s0 * lda + r0, lda, x0 + s0 * incx, incx, x0 + r0 * incx, incx, T(-1), T(1), nullptr, 0};
+                ColaccArgs<T> a{ns, nb, A + s0 * lda + r0, lda, x0 + s0 * incx, incx, x0 + r0 * incx, incx, T(-1), T(1), nullptr, 0, 0};
                 st = launch_colacc(h, a);
             }
             if (st != MXB_OK) return st;

@@ -42,14 +42,31 @@ struct GerArgs {
     uint32_t col_tiles;    // blocks side by side along a row; the grid is col_tiles x row groups, flattened
 };
 
+// A vector that would run past column N is moved back so that it ends at N (the host makes sure
+// that N >= VEC; element alignment is all a matrix access needs): its first `shift` elements are
+// the neighbouring lane's columns, they are updated in registers like the rest and not stored.
+template <typename T, int VEC>
+__device__ __forceinline__ void st_matrix_from(T* p, typename VecOf<T, VEC>::type v, int shift)
+{
+    if (shift == 0) {
+        st_matrix<T, VEC>(p, v);
+    } else {
+#pragma unroll
+        for (int k = 1; k < VEC; ++k)
+            if (k >= shift) p[k] = v[k];
+    }
+}
+
 template <typename T, int VEC>
 __global__ void __launch_bounds__(kThreads) ger_kernel(const GerArgs<T> p)
 {
     typedef typename VecOf<T, VEC>::type V;
     constexpr int U = 8;
     const int64_t bx = blockIdx.x % p.col_tiles, by = blockIdx.x / p.col_tiles;   // 32-bit division
-    const int64_t c = (bx * kThreads + threadIdx.x) * VEC;
-    if (c + VEC > p.N) return;
+    int64_t c = (bx * kThreads + threadIdx.x) * VEC;
+    if (c >= p.N) return;
+    const int shift = c + VEC > p.N ? (int)(c + VEC - p.N) : 0;
+    c -= shift;
     T yj[VEC];
 #pragma unroll
     for (int k = 0; k < VEC; ++k) yj[k] = p.y[(c + k) * p.incy];
@@ -61,7 +78,7 @@ __global__ void __launch_bounds__(kThreads) ger_kernel(const GerArgs<T> p)
         T ax[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            a[u] = ld_stream(reinterpret_cast<const V*>(acol + (i0 + u) * p.lda));
+            a[u] = ld_matrix<T, VEC>(acol + (i0 + u) * p.lda);
             ax[u] = p.alpha * p.x[(i0 + u) * p.incx];
         }
         __builtin_amdgcn_sched_barrier(0);   // all loads of the batch are in flight before the first store
@@ -69,15 +86,15 @@ __global__ void __launch_bounds__(kThreads) ger_kernel(const GerArgs<T> p)
         for (int u = 0; u < U; ++u) {
 #pragma unroll
             for (int k = 0; k < VEC; ++k) a[u][k] = fmad(ax[u], yj[k], a[u][k]);
-            st_stream(reinterpret_cast<V*>(acol + (i0 + u) * p.lda), a[u]);
+            st_matrix_from<T, VEC>(acol + (i0 + u) * p.lda, a[u], shift);
         }
     }
     for (; i0 < rhi; ++i0) {
-        V a = ld_stream(reinterpret_cast<const V*>(acol + i0 * p.lda));
+        V a = ld_matrix<T, VEC>(acol + i0 * p.lda);
         const T ax = p.alpha * p.x[i0 * p.incx];
 #pragma unroll
         for (int k = 0; k < VEC; ++k) a[k] = fmad(ax, yj[k], a[k]);
-        st_stream(reinterpret_cast<V*>(acol + i0 * p.lda), a);
+        st_matrix_from<T, VEC>(acol + i0 * p.lda, a, shift);
     }
 }
 
@@ -128,8 +145,11 @@ __global__ void __launch_bounds__(kThreads) syr_kernel(const SyrArgs<T> p)
     const int64_t c0 = (int64_t)tile * W, r0 = (int64_t)band * W + (int64_t)batch * U;
     if (r0 >= p.n) return;                                  // the last band may be short
     const int64_t r1 = imin(p.n, r0 + U);   // exclusive
-    const int64_t c = c0 + (int64_t)threadIdx.x * VEC;
-    const bool col_ok = c + VEC <= p.n;
+    int64_t c = c0 + (int64_t)threadIdx.x * VEC;
+    const bool col_ok = c < p.n;
+    // ragged last vector of a row: moved back to end at n, its first `shift` elements not stored
+    const int shift = col_ok && c + VEC > p.n ? (int)(c + VEC - p.n) : 0;
+    c -= shift;
     T xj[VEC], yj[VEC];
 #pragma unroll
     for (int k = 0; k < VEC; ++k) {
@@ -143,7 +163,7 @@ __global__ void __launch_bounds__(kThreads) syr_kernel(const SyrArgs<T> p)
     if (inside) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            a[u] = ld_stream(reinterpret_cast<const V*>(acol + (r0 + u) * p.lda));
+            a[u] = ld_matrix<T, VEC>(acol + (r0 + u) * p.lda);
             ax[u] = p.alpha * p.x[(r0 + u) * p.incx];
             ay[u] = TWO ? p.alpha * p.y[(r0 + u) * p.incy] : T(0);
         }
@@ -155,7 +175,7 @@ __global__ void __launch_bounds__(kThreads) syr_kernel(const SyrArgs<T> p)
                 if (TWO) a[u][k] = fmad(ax[u], yj[k], fmad(ay[u], xj[k], a[u][k]));
                 else a[u][k] = fmad(ax[u], xj[k], a[u][k]);
             }
-            st_stream(reinterpret_cast<V*>(acol + (r0 + u) * p.lda), a[u]);
+            st_matrix<T, VEC>(acol + (r0 + u) * p.lda, a[u]);
         }
         return;
     }
@@ -167,7 +187,7 @@ __global__ void __launch_bounds__(kThreads) syr_kernel(const SyrArgs<T> p)
         const int64_t i = imin(r0 + u, r1 - 1), d = i - c;
         const bool none = (UPPER ? d > VEC - 1 : d < 0) || r0 + u >= r1;
         a[u] = V(T(0));
-        if (!none) a[u] = ld_stream(reinterpret_cast<const V*>(acol + i * p.lda));
+        if (!none) a[u] = ld_matrix<T, VEC>(acol + i * p.lda);
         ax[u] = p.alpha * p.x[i * p.incx];
         ay[u] = TWO ? p.alpha * p.y[i * p.incy] : T(0);
     }
@@ -185,12 +205,12 @@ __global__ void __launch_bounds__(kThreads) syr_kernel(const SyrArgs<T> p)
             else a[u][k] = fmad(ax[u], xj[k], a[u][k]);
         }
         T* ap = acol + i * p.lda;
-        if (all) {
-            st_stream(reinterpret_cast<V*>(ap), a[u]);
+        if (all && shift == 0) {
+            st_matrix<T, VEC>(ap, a[u]);
         } else {
 #pragma unroll
             for (int k = 0; k < VEC; ++k)
-                if (UPPER ? k >= d : k <= d) ap[k] = a[u][k];
+                if (k >= shift && (UPPER ? k >= d : k <= d)) ap[k] = a[u][k];
         }
     }
 }
@@ -251,9 +271,11 @@ int ger(mxb_handle_t h, int layout, int64_t m, int64_t n, T alpha, const T* x, i
         return skinny_ger<T>(h, a.M, a.N, alpha, a.x, a.incx, a.y, a.incy, a.A, a.lda);
     a.rows_per_block = option(h, MXB_OPT_GER_ROWS_PER_BLOCK);
     constexpr int FV = Full<T>::vec;
-    const bool vec = aligned16(A) && (lda % FV) == 0 && (a.N % FV) == 0;
-    const int v = vec ? FV : 1;
-    a.col_tiles = (uint32_t)ceil_div(a.N, (int64_t)kThreads * v);
+    // Any pitch, any base address and any width of at least one vector: matrix accesses need element
+    // alignment only and the kernel moves the last vector of a ragged row back.
+    // (a short ragged row keeps more lanes busy with one element per lane)
+    const bool vec = a.N % FV == 0 || a.N >= kThreads;
+    a.col_tiles = (uint32_t)ceil_div(a.N, (int64_t)kThreads * (vec ? FV : 1));
     const int64_t blocks = (int64_t)a.col_tiles * ceil_div(a.M, a.rows_per_block);
     if (blocks > 0x7fffffff) return MXB_ERR_NOT_IMPLEMENTED;
     const dim3 grid((unsigned)blocks);
@@ -282,9 +304,10 @@ int syr(mxb_handle_t h, int layout, int uplo, int64_t n, T alpha, const T* x, in
     const bool upper = (uplo == MXB_UPPER) == (layout == MXB_ROW_MAJOR);
     SyrArgs<T> a{n, A, lda, vec_base(x, n, incx), incx, TWO ? vec_base(y, n, incy) : nullptr, incy, alpha, 0};
     constexpr int FV = Full<T>::vec;
-    const bool vec = aligned16(A) && (lda % FV) == 0 && (n % FV) == 0;
-    const int v = vec ? FV : 1;
-    const int64_t w = (int64_t)kThreads * v, nt = ceil_div(n, w);
+    // Any pitch, any base address and any n of at least one vector: matrix accesses need element
+    // alignment only and the kernel moves the last vector of a ragged row back.
+    const bool vec = n >= FV;
+    const int64_t w = (int64_t)kThreads * (vec ? FV : 1), nt = ceil_div(n, w);
     a.ntiles = (uint32_t)nt;
     // pairs of bands with nt+1 tiles per batch of 8 rows, plus the middle band of an odd count
     const int64_t blocks = (nt / 2) * (nt + 1) * (w / 8) + (nt % 2) * (nt / 2 + 1) * (w / 8);

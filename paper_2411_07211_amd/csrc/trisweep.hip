@@ -43,7 +43,7 @@ namespace {
 // ragged edge (element-wise selects).
 template <typename T, int VEC, int CV, int U, bool UPPER, int KIND, bool UNIT, bool MASKED>
 __device__ __forceinline__ void tri_batch(const TriArgs& p, const T* __restrict__ A, const T* __restrict__ x, int rb, int r1, int c,
-                                          const bool (&col_ok)[CV], const T (&xj)[CV][VEC], T (&cacc)[CV][VEC],
+                                          const int (&col)[CV], const int (&kmin)[CV], const bool (&col_ok)[CV], const T (&xj)[CV][VEC], T (&cacc)[CV][VEC],
                                           T* __restrict__ rowpart_wave, int lane)
 {
     typedef typename VecOf<T, VEC>::type V;
@@ -69,13 +69,15 @@ __device__ __forceinline__ void tri_batch(const TriArgs& p, const T* __restrict_
             if (MASKED && dead[v]) {
                 a[u][v] = V(T(0));
             } else if (MASKED) {
-                int cc = c + v * SPAN;
+                int cc = col[v];
                 const int diag = i / VEC * VEC;              // vector that holds the diagonal element of row i
-                cc = UPPER ? max(cc, diag) : min(cc, diag);  // wholly outside the triangle: read that one instead
+                // wholly outside the triangle: read that one instead (a vector moved back from the
+                // ragged end is not on the vector grid and stays where it is)
+                if (kmin[v] == 0) cc = UPPER ? max(cc, diag) : min(cc, diag);
                 cc = min(cc, p.n - VEC);                     // lanes past the last column
-                a[u][v] = ld_stream(reinterpret_cast<const V*>(arow + cc));
+                a[u][v] = ld_matrix<T, VEC>(arow + cc);
             } else {
-                a[u][v] = ld_stream(reinterpret_cast<const V*>(arow + (c + v * SPAN)));
+                a[u][v] = ld_matrix<T, VEC>(arow + (c + v * SPAN));
             }
         }
         xi[u] = x[(int64_t)i * p.incx];
@@ -101,13 +103,14 @@ __device__ __forceinline__ void tri_batch(const TriArgs& p, const T* __restrict_
                 const int i = rb + u;
                 // d = position of the diagonal inside this vector: element k lies strictly inside the
                 // triangle iff k < d (lower) / k > d (upper) and on the diagonal iff k == d
-                const int d = i - (c + v * SPAN);
+                const int d = i - col[v];
                 const bool live = i < r1 && col_ok[v];
 #pragma unroll
                 for (int k = 0; k < VEC; ++k) {
                     const T val = a[u][v][k];
-                    const bool off = live && (UPPER ? k > d : k < d);
-                    const bool on = live && k == d;
+                    const bool mine = live && k >= kmin[v];
+                    const bool off = mine && (UPPER ? k > d : k < d);
+                    const bool on = mine && k == d;
                     if (ROWS) {
                         // symv: the diagonal goes to the row sum only
                         rs[u] = (off || on) ? fmad(val, xj[v][k], rs[u]) : rs[u];
@@ -158,14 +161,21 @@ __global__ void __launch_bounds__(kTriThreads) trisweep_kernel(const TriArgs p, 
     const bool full_tile = cb0 + TC <= n;
     const int c = cb0 + (int)threadIdx.x * VEC;
 
+    // col[v]: first column of the lane's vector v.  A vector that would run past column n is moved
+    // back so that it ends at n (n >= VEC here; element alignment is all a matrix load needs); its
+    // first kmin[v] elements are the neighbouring lane's columns and never count.
+    int col[CV], kmin[CV];
     bool col_ok[CV];
     T xj[CV][VEC], cacc[CV][VEC];
 #pragma unroll
     for (int v = 0; v < CV; ++v) {
-        col_ok[v] = c + v * SPAN + VEC <= n;
+        const int cv = c + v * SPAN;
+        col_ok[v] = cv < n;
+        kmin[v] = (VEC > 1 && col_ok[v] && cv + VEC > n) ? cv + VEC - n : 0;
+        col[v] = cv - kmin[v];
 #pragma unroll
         for (int k = 0; k < VEC; ++k) {
-            xj[v][k] = (ROWS && col_ok[v]) ? x[(int64_t)(c + v * SPAN + k) * p.incx] : T(0);
+            xj[v][k] = (ROWS && col_ok[v]) ? x[(int64_t)(col[v] + k) * p.incx] : T(0);
             cacc[v][k] = T(0);
         }
     }
@@ -177,28 +187,34 @@ __global__ void __launch_bounds__(kTriThreads) trisweep_kernel(const TriArgs p, 
     const int f0 = UPPER ? 0 : cb1, f1 = UPPER ? cb0 : n;
     auto diagonal_rows = [&]() {
         for (int64_t rb = cb0 + (int64_t)s * UD; rb < cb1; rb += (int64_t)S * UD)
-            tri_batch<T, VEC, CV, UD, UPPER, KIND, UNIT, true>(p, A, x, (int)rb, cb1, c, col_ok, xj, cacc, rowpart_wave, lane);
+            tri_batch<T, VEC, CV, UD, UPPER, KIND, UNIT, true>(p, A, x, (int)rb, cb1, c, col, kmin, col_ok, xj, cacc, rowpart_wave, lane);
     };
     auto inside_rows = [&]() {
         for (int64_t rb64 = f0 + (int64_t)s * U; rb64 < f1; rb64 += (int64_t)S * U) {
             const int rb = (int)rb64;
             if (full_tile && rb + U <= f1)
-                tri_batch<T, VEC, CV, U, UPPER, KIND, UNIT, false>(p, A, x, rb, f1, c, col_ok, xj, cacc, rowpart_wave, lane);
+                tri_batch<T, VEC, CV, U, UPPER, KIND, UNIT, false>(p, A, x, rb, f1, c, col, kmin, col_ok, xj, cacc, rowpart_wave, lane);
             else
-                tri_batch<T, VEC, CV, U, UPPER, KIND, UNIT, true>(p, A, x, rb, f1, c, col_ok, xj, cacc, rowpart_wave, lane);
+                tri_batch<T, VEC, CV, U, UPPER, KIND, UNIT, true>(p, A, x, rb, f1, c, col, kmin, col_ok, xj, cacc, rowpart_wave, lane);
         }
     };
     if (UPPER) { inside_rows(); diagonal_rows(); }
     else { diagonal_rows(); inside_rows(); }
 
     // column sums of this block over its tile
-    T* slot = colpart + (int64_t)g * TC + (int)threadIdx.x * VEC;
+    T* slot = colpart + (int64_t)g * TC - cb0;
 #pragma unroll
     for (int v = 0; v < CV; ++v) {
-        V val;
+        if (kmin[v] == 0) {
+            V val;
 #pragma unroll
-        for (int k = 0; k < VEC; ++k) val[k] = cacc[v][k];
-        *reinterpret_cast<V*>(slot + v * SPAN) = val;
+            for (int k = 0; k < VEC; ++k) val[k] = cacc[v][k];
+            *reinterpret_cast<V*>(slot + col[v]) = val;
+        } else {
+#pragma unroll
+            for (int k = 0; k < VEC; ++k)
+                if (k >= kmin[v]) slot[col[v] + k] = cacc[v][k];
+        }
     }
 }
 
@@ -261,7 +277,9 @@ int trisweep(mxb_handle_t h, bool upper, bool unit, int64_t n, T alpha, const T*
 {
     constexpr int FV = Full<T>::vec;
     if (n > 0x7fffffff - 65536) return MXB_ERR_NOT_IMPLEMENTED;
-    const bool vec = aligned16(A) && (lda % FV) == 0 && (n % FV) == 0;
+    // Any pitch, any base address and any n of at least one vector: matrix loads need element
+    // alignment only and the kernel moves the last vector of a ragged row back.
+    const bool vec = n >= FV;
     const TriPlan pl = tri_plan(n, vec ? FV : 1, upper, h->opt[MXB_OPT_SYMV_TARGET_BLOCKS], h->opt[MXB_OPT_SYMV_TILE_VECTORS],
                                 option(h, MXB_OPT_TRI_DIAG_WEIGHT));
     if (!pl.ok) return MXB_ERR_NOT_IMPLEMENTED;

@@ -22,6 +22,18 @@ def matrix_buffer(A, layout, pad, fill=np.nan):
     return buf.ravel(), lda
 
 
+# Elements by which every matrix of a case is displaced from the start of its allocation: a base
+# address that is a multiple of the element size only.
+A_OFFSET = [0]
+
+
+def mat_dev(buf):
+    off = A_OFFSET[0]
+    if off == 0:
+        return to_dev(buf)
+    return to_dev(np.concatenate([np.full(off, np.nan, buf.dtype), buf]))[off:]
+
+
 def logical(buf, layout, m, n, lda):
     v = buf.reshape(-1, lda)
     return v[:m, :n] if layout == O.ROW_MAJOR else v[:n, :m].T
@@ -42,7 +54,7 @@ def gemv_case(blas, ctx, dt, layout, trans, m, n, alpha, beta, pad, incx, incy, 
     xb, yb = synth.strided(x, incx), synth.strided(y, incy)
     ref = yb.copy()
     D = O.gemv(layout, trans, m, n, dt(alpha), Ab, lda, xb, incx, dt(beta), ref, incy, want_D=True)
-    dA, dx, dy = to_dev(Ab), to_dev(xb), to_dev(yb)
+    dA, dx, dy = mat_dev(Ab), to_dev(xb), to_dev(yb)
     st = blas.routine(prefix_of(dt), "gemv")(ctx.h, layout, trans, m, n, float(alpha), dA, lda, dx, incx, float(beta), dy, incy)
     assert st == 0, f"status {st}"
     got = to_host(dy)
@@ -128,6 +140,43 @@ def test_gemv_deterministic_and_geometry_invariant(blas, ctx, dt):
             ctx.set_option(o, 0)
 
 
+# ----------------------------------------------------------------------------- any base address, pitch and width
+@pytest.mark.parametrize("dt", DT)
+@pytest.mark.parametrize("off", [1, 2, 3])
+def test_matrices_at_any_element_offset_pitch_and_width(blas, ctx, dt, off):
+    """Rows that start at arbitrary elements (odd pitch, displaced base) and widths that are not a
+    whole number of 16-byte vectors take the same kernels as aligned matrices."""
+    A_OFFSET[0] = off
+    try:
+        for (m, n) in [(130, 1027), (1030, 515), (300, 4101), (2049, 6), (9000, 131), (700, 2050)]:
+            for trans in (O.NO_TRANS, O.TRANS):
+                gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, 1.5, 0.5, off, 1, 1)
+            gemv_case(blas, ctx, dt, O.COL_MAJOR, O.NO_TRANS, m, n, 1.5, 0.0, 0, 1, 1)
+            ger_case(blas, ctx, dt, O.ROW_MAJOR, m, n, 0.75, off, 1, 1)
+        gemv_case(blas, ctx, dt, O.ROW_MAJOR, O.TRANS, 2049, 1030 + off, 3, -2, 0, 1, 1, ints=True)
+        ger_case(blas, ctx, dt, O.ROW_MAJOR, 300, 1030 + off, 2, 0, 1, 1, ints=True)
+        for n in (5, 259, 1031, 2310, 4101):
+            for uplo in (O.UPPER, O.LOWER):
+                symv_case(blas, ctx, dt, O.ROW_MAJOR, uplo, n, 1.5, 0.5, off - 1, 1, 1)
+                syr_case(blas, ctx, dt, O.ROW_MAJOR, uplo, n, 0.75, off - 1, 1, 1, False)
+                syr_case(blas, ctx, dt, O.ROW_MAJOR, uplo, n, 0.75, off, 1, 1, True)
+                for trans in (O.NO_TRANS, O.TRANS):
+                    for diag in (O.NON_UNIT, O.UNIT):
+                        trmv_case(blas, ctx, dt, O.ROW_MAJOR, uplo, trans, diag, n, off - 1, 1)
+                    trsv_case(blas, ctx, dt, O.ROW_MAJOR, uplo, trans, O.NON_UNIT, n, off, 1)
+        for uplo in (O.UPPER, O.LOWER):
+            symv_case(blas, ctx, dt, O.ROW_MAJOR, uplo, 1535 + off, 3, -2, 0, 1, 1, ints=True)
+            trmv_case(blas, ctx, dt, O.ROW_MAJOR, uplo, O.TRANS, O.NON_UNIT, 1535 + off, 0, 1, ints=True)
+        # wide tiles of the triangle sweep with a ragged last vector
+        ctx.set_option(blas.OPT_SYMV_TILE_VECTORS, 2)
+        for uplo in (O.UPPER, O.LOWER):
+            symv_case(blas, ctx, dt, O.ROW_MAJOR, uplo, 8190 + off, 1.5, 0.5, 0, 1, 1)
+            trmv_case(blas, ctx, dt, O.ROW_MAJOR, uplo, O.TRANS, O.UNIT, 8190 + off, 0, 1)
+    finally:
+        A_OFFSET[0] = 0
+        ctx.set_option(blas.OPT_SYMV_TILE_VECTORS, 0)
+
+
 # ----------------------------------------------------------------------------- trmv
 def trmv_case(blas, ctx, dt, layout, uplo, trans, diag, n, pad, incx, ints=False, seed=11):
     gen = (lambda t, k: synth.small_ints(seed, t, k, -2, 2, dt)) if ints else (lambda t, k: synth.uniform(seed, t, k, dt))
@@ -142,7 +191,7 @@ def trmv_case(blas, ctx, dt, layout, uplo, trans, diag, n, pad, incx, ints=False
     ref = xb.copy()
     D = O.trmv(layout, uplo, trans, diag, n, Ab, lda, ref, incx, want_D=True)
     dx = to_dev(xb)
-    st = blas.routine(prefix_of(dt), "trmv")(ctx.h, layout, uplo, trans, diag, n, to_dev(Ab), lda, dx, incx)
+    st = blas.routine(prefix_of(dt), "trmv")(ctx.h, layout, uplo, trans, diag, n, mat_dev(Ab), lda, dx, incx)
     assert st == 0, f"status {st}"
     got = to_host(dx)
     what = f"trmv {prefix_of(dt)} layout={layout} uplo={uplo} trans={trans} diag={diag} n={n} pad={pad} incx={incx}"
@@ -194,7 +243,7 @@ def symv_case(blas, ctx, dt, layout, uplo, n, alpha, beta, pad, incx, incy, ints
     ref = yb.copy()
     D = O.symv(layout, uplo, n, dt(alpha), Ab, lda, xb, incx, dt(beta), ref, incy, want_D=True)
     dy = to_dev(yb)
-    st = blas.routine(prefix_of(dt), "symv")(ctx.h, layout, uplo, n, float(alpha), to_dev(Ab), lda, to_dev(xb), incx, float(beta), dy, incy)
+    st = blas.routine(prefix_of(dt), "symv")(ctx.h, layout, uplo, n, float(alpha), mat_dev(Ab), lda, to_dev(xb), incx, float(beta), dy, incy)
     assert st == 0, f"status {st}"
     got = to_host(dy)
     what = f"symv {prefix_of(dt)} layout={layout} uplo={uplo} n={n} pad={pad} a={alpha} b={beta} inc=({incx},{incy})"
@@ -241,7 +290,7 @@ def ger_case(blas, ctx, dt, layout, m, n, alpha, pad, incx, incy, ints=False, se
     xb, yb = synth.strided(x, incx), synth.strided(y, incy)
     ref = Ab.copy()
     D = O.ger(layout, m, n, dt(alpha), xb, incx, yb, incy, ref, lda, want_D=True)
-    dA = to_dev(Ab)
+    dA = mat_dev(Ab)
     st = blas.routine(prefix_of(dt), "ger")(ctx.h, layout, m, n, float(alpha), to_dev(xb), incx, to_dev(yb), incy, dA, lda)
     assert st == 0, f"status {st}"
     got = to_host(dA)
@@ -287,7 +336,7 @@ def syr_case(blas, ctx, dt, layout, uplo, n, alpha, pad, incx, incy, two, ints=F
         D = O.syr2(layout, uplo, n, dt(alpha), xb, incx, yb, incy, ref, lda, want_D=True)
     else:
         D = O.syr(layout, uplo, n, dt(alpha), xb, incx, ref, lda, want_D=True)
-    dA = to_dev(Ab)
+    dA = mat_dev(Ab)
     f = blas.routine(prefix_of(dt), "syr2" if two else "syr")
     if two:
         st = f(ctx.h, layout, uplo, n, float(alpha), to_dev(xb), incx, to_dev(yb), incy, dA, lda)
@@ -355,7 +404,7 @@ def trsv_case(blas, ctx, dt, layout, uplo, trans, diag, n, pad, incx, exact=Fals
     ref = bb.copy()
     D = O.trsv(layout, uplo, trans, diag, n, Ab, lda, ref, incx, want_D=True)
     dx = to_dev(bb)
-    st = blas.routine(prefix_of(dt), "trsv")(ctx.h, layout, uplo, trans, diag, n, to_dev(Ab), lda, dx, incx)
+    st = blas.routine(prefix_of(dt), "trsv")(ctx.h, layout, uplo, trans, diag, n, mat_dev(Ab), lda, dx, incx)
     assert st == 0, f"status {st}"
     got = to_host(dx)
     what = f"trsv {prefix_of(dt)} layout={layout} uplo={uplo} trans={trans} diag={diag} n={n} pad={pad} incx={incx}"
