@@ -42,6 +42,9 @@ def parse():
                     help="no GPU work: parse two rocprofv3 --pmc output folders of `bench.py --only $(bench.py --traffic-list)` "
                          "(FETCH_SIZE, WRITE_SIZE) into profiles/traffic.json")
     ap.add_argument("--traffic-list", action="store_true", help="print the --only list the traffic counters are collected on")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the step: time every routine over a sweep of sizes (small, medium, large buckets, "
+                         "skinny N = 40 shapes) and print a markdown table with the geometric mean per bucket")
     ap.add_argument("--scale", type=int, default=1, help="divide every problem size by this (debugging only; "
                     "a scaled run is not the benchmark and says so in its output)")
     return ap.parse_args()
@@ -207,6 +210,116 @@ def cpu_baseline(torch):
     }
 
 
+def sweep(B, ctx, torch):
+    """Size sweeps in the style of the paper's evaluation (Sec. 6.2: problem sizes in buckets,
+    one geometric mean per bucket; skinny matrices with N = 40 and M powers of 2 and 3).  Buckets
+    by the bytes a call moves: small < 4 MiB (launch latency), medium < 256 MiB (fits the
+    last-level cache), large beyond.  Times are medians of 20 event-timed calls after 3 warm-ups."""
+    h, dev = ctx.h, ctx.device
+    f32 = torch.float32
+
+    def timed(fn, pre=None, iters=20, warm=3):
+        for _ in range(warm):
+            if pre: pre()
+            assert fn() == 0
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+        for a, b in ev:
+            if pre: pre()
+            a.record(); st = fn(); b.record()
+            assert st == 0, st
+        torch.cuda.synchronize()
+        ts = sorted(a.elapsed_time(b) for a, b in ev)
+        return ts[len(ts) // 2] * 1e3          # us
+
+    def replayed(fn, pre=None, calls=20, reps=5):
+        """us per call when `calls` calls in a row are captured into one HIP graph and replayed:
+        what the GPU needs for a call once the host's launch cost is out of the way."""
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            ctx.use_current_stream()
+            for _ in range(calls):
+                if pre: pre()
+                assert fn() == 0
+        ctx.use_current_stream()
+        g.replay()
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for a, b in ev:
+            a.record(); g.replay(); b.record()
+        torch.cuda.synchronize()
+        ts = sorted(a.elapsed_time(b) for a, b in ev)
+        return ts[len(ts) // 2] * 1e3 / calls
+
+    rows = []          # (routine, shape text, bytes, us of a single call, us per call in a replayed graph or None)
+
+    def rec(name, shape, nbytes, fn, pre=None):
+        us = timed(fn, pre)
+        gus = replayed(fn, pre) if us < 60 else None
+        rows.append((name, shape, nbytes, us, gus))
+        print(f"{name:10s} {shape:>16s} {nbytes / 2**20:10.2f} MiB {us:9.1f} us {nbytes / us / 1e3:8.1f} GB/s"
+              + (f"   in a graph {gus:7.1f} us {nbytes / gus / 1e3:8.1f} GB/s" if gus else ""), file=sys.stderr, flush=True)
+
+    nmax = 1 << 28
+    x = torch.rand(nmax, dtype=f32, device=dev); y = torch.rand(nmax, dtype=f32, device=dev)
+    r = torch.zeros(1, dtype=f32, device=dev)
+    for e in range(10, 29, 2):
+        n = 1 << e
+        for n_ in (n, n - 3 if e < 28 else n):
+            t = f"n={n_}"
+            rec("saxpy", t, 12 * n_, lambda: B.mxb_saxpy(h, n_, -0.75, x, 1, y, 1))
+            rec("sscal", t, 8 * n_, lambda: B.mxb_sscal(h, n_, 1.0, x, 1))
+            rec("sdot", t, 8 * n_, lambda: B.mxb_sdot(h, n_, x, 1, y, 1, r))
+            rec("sasum", t, 4 * n_, lambda: B.mxb_sasum(h, n_, x, 1, r))
+            rec("snrm2", t, 4 * n_, lambda: B.mxb_snrm2(h, n_, x, 1, r))
+    NS = 16384
+    A = x                       # 2^28 floats hold a 16384 x 16384 matrix
+    xv = torch.rand(1 << 22, dtype=f32, device=dev); yv = torch.rand(1 << 22, dtype=f32, device=dev)
+    x0 = torch.rand(NS, dtype=f32, device=dev); xt = x0.clone()
+    reset = lambda: xt.copy_(x0)
+    for n in (256, 512, 1000, 1024, 2048, 3000, 4096, 6001, 8192, 12000, 16384):
+        t, full, tri = f"{n}x{n}", 4 * n * n, 4 * (n * (n + 1) // 2)
+        rec("sgemv_n", t, full, lambda: B.mxb_sgemv(h, B.ROW_MAJOR, B.NO_TRANS, n, n, 1.0, A, n, xv, 1, 0.0, yv, 1))
+        rec("sgemv_t", t, full, lambda: B.mxb_sgemv(h, B.ROW_MAJOR, B.TRANS, n, n, 1.0, A, n, xv, 1, 0.0, yv, 1))
+        rec("sger", t, 2 * full, lambda: B.mxb_sger(h, B.ROW_MAJOR, n, n, 1e-6, xv, 1, yv, 1, A, n))
+        rec("ssymv_l", t, tri, lambda: B.mxb_ssymv(h, B.ROW_MAJOR, B.LOWER, n, 0.5, A, n, xv, 1, 0.5, yv, 1))
+        rec("ssyr_l", t, 2 * tri, lambda: B.mxb_ssyr(h, B.ROW_MAJOR, B.LOWER, n, 1e-6, xv, 1, A, n))
+        rec("strmv_un", t, tri, lambda: B.mxb_strmv(h, B.ROW_MAJOR, B.UPPER, B.NO_TRANS, B.NON_UNIT, n, A, n, xt, 1), reset)
+        rec("strmv_lt", t, tri, lambda: B.mxb_strmv(h, B.ROW_MAJOR, B.LOWER, B.TRANS, B.NON_UNIT, n, A, n, xt, 1), reset)
+    # trsv wants a well-conditioned triangle: unit diagonal, small off-diagonal elements
+    T = torch.rand(4096 * 4096, dtype=f32, device=dev).mul_(1e-4)
+    for n in (256, 1024, 4096):
+        rec("strsv_lu", f"{n}x{n}", 4 * (n * (n + 1) // 2), lambda: B.mxb_strsv(h, B.ROW_MAJOR, B.LOWER, B.NO_TRANS, B.UNIT, n, T, n, xt, 1), reset)
+    # skinny matrices (Sec. 6.2.2): N = 40, M powers of 2 and 3
+    for M in (2 ** 10, 3 ** 7, 2 ** 13, 3 ** 9, 2 ** 16, 3 ** 11, 2 ** 19, 3 ** 13, 2 ** 22):
+        t, full = f"{M}x40", 4 * M * 40
+        rec("sgemv_n", t, full, lambda: B.mxb_sgemv(h, B.ROW_MAJOR, B.NO_TRANS, M, 40, 1.0, A, 40, xv, 1, 0.0, yv, 1))
+        rec("sgemv_t", t, full, lambda: B.mxb_sgemv(h, B.ROW_MAJOR, B.TRANS, M, 40, 1.0, A, 40, xv, 1, 0.0, yv, 1))
+        rec("sger", t, 2 * full, lambda: B.mxb_sger(h, B.ROW_MAJOR, M, 40, 1e-6, xv, 1, yv, 1, A, 40))
+
+    def bucket(nb):
+        return "small (< 4 MiB)" if nb < (4 << 20) else "medium (< 256 MiB)" if nb < (256 << 20) else "large"
+
+    print("| routine | shape | MiB | us, one call | GB/s | % of 8 TB/s | us per call, 20 calls in a replayed graph | GB/s |")
+    print("|---|---|---|---|---|---|---|---|")
+    for name, shape, nb, us, gus in rows:
+        print(f"| {name} | {shape} | {nb / 2**20:.2f} | {us:.1f} | {nb / us / 1e3:.0f} | {nb / us / 1e3 / 80:.1f} | "
+              + (f"{gus:.1f} | {nb / gus / 1e3:.0f} |" if gus else "| |"))
+    print()
+    print("| routine | bucket | cases | geometric mean GB/s, one call | in a replayed graph |")
+    print("|---|---|---|---|---|")
+    label = lambda name, shape: name + (" (N=40)" if shape.endswith("x40") else "")
+    keys = []
+    for name, shape, nb, us, gus in rows:
+        k = (label(name, shape), bucket(nb))
+        if k not in keys: keys.append(k)
+    for k in keys:
+        sel = [(nb, us, gus) for name, shape, nb, us, gus in rows if (label(name, shape), bucket(nb)) == k]
+        gm = float(np.exp(np.mean([np.log(nb / us / 1e3) for nb, us, gus in sel])))
+        gg = float(np.exp(np.mean([np.log(nb / (gus or us) / 1e3) for nb, us, gus in sel])))
+        print(f"| {k[0]} | {k[1]} | {len(sel)} | {gm:.0f} | {gg:.0f} |")
+
+
 CSRC = os.path.join(ROOT, "paper_2411_07211_amd", "csrc")
 TRAFFIC_JSON = os.path.join(ROOT, "profiles", "traffic.json")
 # Kernels (demangled-name fragments) behind the calls whose HBM traffic is recorded; the calls are
@@ -314,6 +427,9 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     ctx = B.Context("cuda:0", workspace_bytes=256 << 20)
+    if args.sweep:
+        sweep(B, ctx, torch)
+        return
     suite = Suite(B, ctx, torch, scale=args.scale)
     calls = suite.calls
     if args.list:

@@ -89,6 +89,9 @@ def _declare(lib):
         f = getattr(lib, f"oracle_{p}gemv")
         f.argtypes = [_int, _int, _i64, _i64, ct, _ptr, _i64, _ptr, _i64, ct, _ptr, _i64, _ptr]
         f.restype = None
+        f = getattr(lib, f"oracle_{p}gemv_batched")
+        f.argtypes = [_int, _int, _i64, _i64, ct, _ptr, _i64, _i64, _ptr, _i64, _i64, ct, _ptr, _i64, _i64, _i64, _ptr]
+        f.restype = None
         f = getattr(lib, f"oracle_{p}trmv")
         f.argtypes = [_int, _int, _int, _int, _i64, _ptr, _i64, _ptr, _i64, _ptr]
         f.restype = None
@@ -198,6 +201,21 @@ def gemv(layout, trans, m, n, alpha, A, lda, x, incx, beta, y, incy, want_D=Fals
     D = np.zeros(max(leny, 0), np.float64) if want_D else None
     getattr(_load(), f"oracle_{p}gemv")(layout, trans, m, n, alpha, _p(A), lda, _p(x), incx,
                                         beta, _p(y), incy, _p(D))
+    return D
+
+
+def gemv_batched(layout, trans, m, n, alpha, A, lda, strideA, x, incx, stridex, beta, y, incy, stridey, batch, want_D=False):
+    """batch independent gemv problems; problem b uses A[b*strideA:], x[b*stridex:], y[b*stridey:]."""
+    p = _same(A, x, y)
+    lenx, leny = (n, m) if trans == NO_TRANS else (m, n)
+    assert min(strideA, stridex, stridey) >= 0 and batch >= 0
+    if batch > 0:
+        last = batch - 1
+        _mat_need(A[last * strideA:], layout, m, n, lda)
+        _need(x[last * stridex:], lenx, incx, "x"); _need(y[last * stridey:], leny, incy, "y")
+    D = np.zeros(max(leny, 0) * max(batch, 0), np.float64) if want_D else None
+    getattr(_load(), f"oracle_{p}gemv_batched")(layout, trans, m, n, alpha, _p(A), lda, strideA, _p(x), incx, stridex,
+                                                beta, _p(y), incy, stridey, batch, _p(D))
     return D
 
 

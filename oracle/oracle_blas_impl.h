@@ -129,6 +129,20 @@ void FN(gemv)(int layout, int trans, int64_t m, int64_t n, T alpha, const T* A, 
     }
 }
 
+/* A batch of independent gemv calls on operands that lie at fixed distances in memory (Sec. 6.2.2
+ * times the standard strided-batch convention): problem b uses A + b*strideA, x + b*stridex and
+ * y + b*stridey (element counts; 0 shares an operand among all problems).  D, if given, holds
+ * len(y) denominators per problem, one problem after the other. */
+void FN(gemv_batched)(int layout, int trans, int64_t m, int64_t n, T alpha, const T* A, int64_t lda,
+                      int64_t strideA, const T* x, int64_t incx, int64_t stridex, T beta, T* y,
+                      int64_t incy, int64_t stridey, int64_t batch, double* D)
+{
+    const int64_t leny = trans == ORACLE_NO_TRANS ? m : n;
+    for (int64_t b = 0; b < batch; ++b)
+        FN(gemv)(layout, trans, m, n, alpha, A + b * strideA, lda, x + b * stridex, incx, beta,
+                 y + b * stridey, incy, D ? D + b * leny : 0);
+}
+
 /* Is (i, j) inside the stored triangle? */
 static int FN(in_tri)(int uplo, int64_t i, int64_t j)
 {

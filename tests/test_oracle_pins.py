@@ -169,6 +169,48 @@ def test_gemv_int64_brute_force(dt, layout, trans, m, n):
 
 
 @pytest.mark.parametrize("dt", DT)
+@pytest.mark.parametrize("trans", [O.NO_TRANS, O.TRANS])
+def test_gemv_batched_int64_brute_force_and_shared_operands(dt, trans):
+    # every problem of a batch against exact integer arithmetic on its own slice; gaps between
+    # the problems hold NaN (operands) or a marker (y) and must be neither read nor written
+    m, n, batch = 5, 7, 4
+    lenx, leny = (n, m) if trans == O.NO_TRANS else (m, n)
+    for lda, incx, incy, gapA, gapx, gapy in [(n, 1, 1, 0, 0, 0), (n + 2, 2, -3, 5, 3, 4)]:
+        sA = m * lda + gapA
+        sx, sy = 1 + (lenx - 1) * abs(incx) + gapx, 1 + (leny - 1) * abs(incy) + gapy
+        Ab = np.full(batch * sA, np.nan, dt); xb = np.full(batch * sx, np.nan, dt); yb = np.full(batch * sy, 77, dt)
+        want = []
+        for b in range(batch):
+            A = ints(21, 3 * b, m * n, dt, -4, 4).reshape(m, n)
+            x, y = ints(21, 3 * b + 1, lenx, dt, -4, 4), ints(21, 3 * b + 2, leny, dt, -4, 4)
+            Ab[b * sA:b * sA + m * lda].reshape(m, lda)[:, :n] = A
+            xb[b * sx:b * sx + 1 + (lenx - 1) * abs(incx)] = synth.strided(x, incx)
+            ys = synth.strided(y, incy); ys[np.isnan(ys)] = 77
+            yb[b * sy:b * sy + ys.size] = ys
+            want.append(brute_gemv(trans, m, n, 3, A, x, -2, y))
+        before = yb.copy()
+        O.gemv_batched(O.ROW_MAJOR, trans, m, n, dt(3), Ab, lda, sA, xb, incx, sx, dt(-2), yb, incy, sy, batch)
+        touched = np.zeros(yb.size, bool)
+        for b in range(batch):
+            got = synth.gather(yb[b * sy:], leny, incy)
+            assert np.array_equal(got.astype(np.int64), want[b]), (b, lda, incx, incy)
+            idx = b * sy + np.arange(leny) * abs(incy)
+            touched[idx] = True
+        assert np.array_equal(yb[~touched], before[~touched])       # nothing between or after the vectors
+    # stride 0 shares an operand: one matrix, `batch` vectors = the columns of a matrix product
+    A = ints(22, 0, m * n, dt, -3, 3).reshape(m, n)
+    X = ints(22, 1, batch * lenx, dt, -3, 3).reshape(batch, lenx)
+    Y = np.zeros((batch, leny), dt)
+    O.gemv_batched(O.ROW_MAJOR, trans, m, n, dt(1), A.ravel(), n, 0, X.ravel(), 1, lenx, dt(0), Y.ravel(), 1, leny, batch)
+    op = A.astype(np.int64) if trans == O.NO_TRANS else A.astype(np.int64).T
+    assert np.array_equal(Y.astype(np.int64), (op @ X.astype(np.int64).T).T)
+    # an empty batch touches nothing
+    Y0 = Y.copy()
+    O.gemv_batched(O.ROW_MAJOR, trans, m, n, dt(1), A.ravel(), n, 0, X.ravel(), 1, lenx, dt(0), Y.ravel(), 1, leny, 0)
+    assert Y.tobytes() == Y0.tobytes()
+
+
+@pytest.mark.parametrize("dt", DT)
 def test_gemv_closed_forms(dt):
     n = 64
     x, y = synth.uniform(9, 1, n, dt), synth.uniform(9, 2, n, dt)
