@@ -54,7 +54,7 @@ typedef enum { MXB_NON_UNIT = 131, MXB_UNIT = 132 } mxb_diag_t;
 
 typedef enum {
     MXB_AXPY = 1, MXB_SCAL = 2, MXB_DOT = 3, MXB_ASUM = 4, MXB_NRM2 = 5,
-    MXB_GEMV = 6, MXB_TRMV = 7, MXB_SYMV = 8, MXB_GER = 9
+    MXB_GEMV = 6, MXB_TRMV = 7, MXB_SYMV = 8, MXB_GER = 9, MXB_GEMV_BATCHED = 10
 } mxb_routine_t;
 
 #define MXB_OK 0
@@ -167,6 +167,25 @@ int mxb_sgemv(mxb_handle_t h, mxb_layout_t layout, mxb_trans_t trans, int64_t m,
               const float* A, int64_t lda, const float* x, int64_t incx, float beta, float* y, int64_t incy);
 int mxb_dgemv(mxb_handle_t h, mxb_layout_t layout, mxb_trans_t trans, int64_t m, int64_t n, double alpha,
               const double* A, int64_t lda, const double* x, int64_t incx, double beta, double* y, int64_t incy);
+
+/* `batch` independent gemv problems of one shape in one call (Sec. 6.2.2 gemv; for matrices so
+ * small that a single product cannot fill the device): for b in [0, batch)
+ *     y_b = alpha*op(A_b)*x_b + beta*y_b,   A_b = A + b*strideA, x_b = x + b*stridex, y_b = y + b*stridey
+ * with the strides in elements.  Every other argument means what it means for gemv and holds for
+ * all problems.  strideA == 0 or stridex == 0 shares that operand among the problems; the y_b must
+ * not overlap each other (stridey == 0 is rejected for batch > 1; other overlaps are undefined).
+ * All pointers are device pointers; the caller owns them.  Workspace: the bound of
+ * mxb_workspace_bytes(MXB_GEMV_BATCHED, ..) holds for any batch.
+ * Quick return: m == 0, n == 0, batch == 0, or (alpha == 0 and beta == 1).
+ * Errors: layout (-1), trans (-2), m < 0 (-3), n < 0 (-4), A NULL (-6), lda (-7), strideA < 0 (-8),
+ *         x NULL (-9), incx == 0 (-10), stridex < 0 (-11), y NULL (-13), incy == 0 (-14),
+ *         stridey (-15), batch < 0 (-16). */
+int mxb_sgemv_batched(mxb_handle_t h, mxb_layout_t layout, mxb_trans_t trans, int64_t m, int64_t n, float alpha,
+                      const float* A, int64_t lda, int64_t strideA, const float* x, int64_t incx, int64_t stridex,
+                      float beta, float* y, int64_t incy, int64_t stridey, int64_t batch);
+int mxb_dgemv_batched(mxb_handle_t h, mxb_layout_t layout, mxb_trans_t trans, int64_t m, int64_t n, double alpha,
+                      const double* A, int64_t lda, int64_t strideA, const double* x, int64_t incx, int64_t stridex,
+                      double beta, double* y, int64_t incy, int64_t stridey, int64_t batch);
 
 /* x := op(T)*x, T the uplo triangle of the n x n matrix A (Sec. 6.2.2, triangular matrices).
  * Elements outside the triangle are never used; with MXB_UNIT the diagonal is taken as 1 and

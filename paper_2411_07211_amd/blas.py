@@ -36,7 +36,7 @@ ROW_MAJOR, COL_MAJOR = 101, 102
 NO_TRANS, TRANS = 111, 112
 UPPER, LOWER = 121, 122
 NON_UNIT, UNIT = 131, 132
-AXPY, SCAL, DOT, ASUM, NRM2, GEMV, TRMV, SYMV, GER = range(1, 10)
+AXPY, SCAL, DOT, ASUM, NRM2, GEMV, TRMV, SYMV, GER, GEMV_BATCHED = range(1, 11)
 OK, ERR_HANDLE, ERR_WORKSPACE, ERR_NOT_IMPLEMENTED, ERR_HIP_BASE = 0, 1, 2, 3, 1000
 (OPT_L1_BLOCKS_PER_CU, OPT_REDUCE_BLOCKS, OPT_ROWDOT_XCHUNK, OPT_ROWDOT_BLOCKS_PER_CU,
  OPT_COLACC_TARGET_BLOCKS, OPT_COLACC_MIN_ROWS, OPT_SYMV_TARGET_BLOCKS, OPT_GER_ROWS_PER_BLOCK,
@@ -76,6 +76,8 @@ for _p, _t in (("s", _f), ("d", _d)):
     _fn["i" + _p + "amax"] = _sig(f"mxb_i{_p}amax", _int, _ptr, _i64, _ptr, _i64, _ptr)
     _fn[_p + "gemv"] = _sig(f"mxb_{_p}gemv", _int, _ptr, _int, _int, _i64, _i64, _t, _ptr, _i64, _ptr, _i64,
                             _t, _ptr, _i64)
+    _fn[_p + "gemv_batched"] = _sig(f"mxb_{_p}gemv_batched", _int, _ptr, _int, _int, _i64, _i64, _t, _ptr, _i64, _i64, _ptr, _i64,
+                                    _i64, _t, _ptr, _i64, _i64, _i64)
     _fn[_p + "trmv"] = _sig(f"mxb_{_p}trmv", _int, _ptr, _int, _int, _int, _int, _i64, _ptr, _i64, _ptr, _i64)
     _fn[_p + "trsv"] = _sig(f"mxb_{_p}trsv", _int, _ptr, _int, _int, _int, _int, _i64, _ptr, _i64, _ptr, _i64)
     _fn[_p + "symv"] = _sig(f"mxb_{_p}symv", _int, _ptr, _int, _int, _i64, _t, _ptr, _i64, _ptr, _i64, _t,
@@ -247,6 +249,18 @@ def _mk_level2():
             return fn[p + "gemv"](h, layout, trans, m, n, alpha, _m(A, layout, m, n, lda, "A", p), lda,
                                   _v(x, lenx, incx, "x", p), incx, beta, _v(y, leny, incy, "y", p), incy)
 
+        def gemv_batched(h, layout, trans, m, n, alpha, A, lda, strideA, x, incx, stridex, beta, y, incy, stridey, batch, p=p):
+            lenx, leny = (n, m) if trans == NO_TRANS else (m, n)
+            major, minor = (m, n) if layout == ROW_MAJOR else (n, m)
+            last = max(batch - 1, 0)
+            empty = batch <= 0 or m <= 0 or n <= 0
+            # the last problem reaches furthest (negative strides are rejected by the library)
+            _chk(A, 0 if empty else last * max(strideA, 0) + (major - 1) * lda + minor, "A", p)
+            _chk(x, 0 if empty else last * max(stridex, 0) + 1 + (lenx - 1) * abs(incx), "x", p)
+            _chk(y, 0 if empty else last * max(stridey, 0) + 1 + (leny - 1) * abs(incy), "y", p)
+            return fn[p + "gemv_batched"](h, layout, trans, m, n, alpha, _dp(A), lda, strideA, _dp(x), incx, stridex, beta,
+                                          _dp(y), incy, stridey, batch)
+
         def trmv(h, layout, uplo, trans, diag, n, A, lda, x, incx, p=p):
             return fn[p + "trmv"](h, layout, uplo, trans, diag, n, _m(A, layout, n, n, lda, "A", p), lda, _v(x, n, incx, "x", p), incx)
 
@@ -268,7 +282,7 @@ def _mk_level2():
             return fn[p + "syr2"](h, layout, uplo, n, alpha, _v(x, n, incx, "x", p), incx, _v(y, n, incy, "y", p), incy,
                                   _m(A, layout, n, n, lda, "A", p), lda)
 
-        for name, f in (("gemv", gemv), ("trmv", trmv), ("trsv", trsv), ("symv", symv), ("ger", ger), ("syr", syr), ("syr2", syr2)):
+        for name, f in (("gemv", gemv), ("gemv_batched", gemv_batched), ("trmv", trmv), ("trsv", trsv), ("symv", symv), ("ger", ger), ("syr", syr), ("syr2", syr2)):
             f.__name__ = f"mxb_{p}{name}"
             g[f.__name__] = f
 

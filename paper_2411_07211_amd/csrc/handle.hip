@@ -142,6 +142,14 @@ size_t mxb_workspace_bytes(int routine, int elem_size, int64_t m, int64_t n)
             b = narrow <= 48 ? skinny_workspace_bytes(narrow, elem_size) : 0;
             return a > b ? a : b;
         }
+        case MXB_GEMV_BATCHED: {
+            // the blocks a plan aims at are shared among the problems: over all problems there are at most
+            // one and a half times as many partial vectors as the largest target
+            int64_t t = 4 * option_default(MXB_OPT_COLACC_TARGET_BLOCKS);
+            if (t < kColaccNarrowBlocks) t = kColaccNarrowBlocks;
+            const int64_t len = ceil_div(m > n ? m : n, (int64_t)full) * full;
+            return align_up((size_t)(t + t / 2) * (size_t)len * (size_t)elem_size, 256);
+        }
         case MXB_TRMV: {
             const size_t a = align_up((size_t)n * elem_size, 256), b = tri_workspace_bound(n, elem_size);
             return a > b ? a : b;

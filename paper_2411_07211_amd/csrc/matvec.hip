@@ -58,6 +58,8 @@ struct RowdotArgs {
     T alpha, beta;
     int xchunk;          // elements of x staged per chunk (multiple of 256)
     int x_contig;        // x has unit increment and is 16-byte aligned: stage it with 128-bit loads
+    // a batch of problems of this shape: problem b uses A + b*sA, x + b*sx, y + b*sy
+    int64_t batch = 1, sA = 0, sx = 0, sy = 0;
 };
 
 constexpr int kRowdotWaves = 8;
@@ -105,15 +107,21 @@ __global__ void __launch_bounds__(kRowdotThreads, 4) rowdot_kernel(const RowdotA
     const int64_t ntiles = (p.M + RB - 1) / RB;
     const int64_t Nv = p.N - p.N % VEC;       // columns that whole vectors cover
     const int64_t xc = p.xchunk;
-    int64_t staged = -1;
+    const int64_t total = ntiles * p.batch;   // tiles of all problems, one problem after the other
+    int64_t staged = -1, staged_b = -1;
 
-    for (int64_t pass = 0; pass * gridDim.x < ntiles; ++pass) {
+    for (int64_t pass = 0; pass * gridDim.x < total; ++pass) {
         // Triangular modes: rows get shorter (upper) or longer (lower) down the matrix, so the
         // passes alternate direction: the block that took the heaviest tile of one pass takes the
         // lightest of the next and every block ends up with about the same number of elements.
         const int64_t slot = (MODE != MODE_GENERAL && (pass & 1)) ? (int64_t)gridDim.x - 1 - blockIdx.x : blockIdx.x;
-        const int64_t t = pass * gridDim.x + slot;
-        if (t >= ntiles) continue;
+        int64_t t = pass * gridDim.x + slot;
+        if (t >= total) continue;
+        int64_t b = 0;
+        if (p.batch > 1) { b = t / ntiles; t -= b * ntiles; }
+        const T* __restrict__ A = p.A + b * p.sA;
+        const T* __restrict__ x = p.x + b * p.sx;
+        T* __restrict__ y = p.y + b * p.sy;
         const int64_t tile = MODE == MODE_LOWER ? ntiles - 1 - t : t;
         const int64_t brow0 = tile * RB;
         const int64_t wrow0 = brow0 + (int64_t)wave * RW;
@@ -126,29 +134,30 @@ __global__ void __launch_bounds__(kRowdotThreads, 4) rowdot_kernel(const RowdotA
 
         const T* arow[R];
 #pragma unroll
-        for (int r = 0; r < R; ++r) arow[r] = p.A + imin(grow0 + r, p.M - 1) * p.lda;   // clamp: loads stay in bounds
+        for (int r = 0; r < R; ++r) arow[r] = A + imin(grow0 + r, p.M - 1) * p.lda;   // clamp: loads stay in bounds
         T acc[R];
 #pragma unroll
         for (int r = 0; r < R; ++r) acc[r] = T(0);
 
         for (int64_t c0 = bclo / xc * xc; c0 < bchi; c0 += xc) {
             const int64_t c1 = imin(c0 + xc, p.N);
-            if (c0 != staged) {
+            if (c0 != staged || b != staged_b) {
                 __syncthreads();
                 const int cnt = (int)(c1 - c0);
                 if (p.x_contig) {
-                    const XV* src = reinterpret_cast<const XV*>(p.x + c0);
+                    const XV* src = reinterpret_cast<const XV*>(x + c0);
                     XV* dst = reinterpret_cast<XV*>(xs);
                     const int nv = cnt / FV;
 #pragma unroll 4
                     for (int j = threadIdx.x; j < nv; j += kRowdotThreads) dst[j] = src[j];
-                    for (int j = nv * FV + threadIdx.x; j < cnt; j += kRowdotThreads) xs[j] = p.x[c0 + j];
+                    for (int j = nv * FV + threadIdx.x; j < cnt; j += kRowdotThreads) xs[j] = x[c0 + j];
                 } else {
 #pragma unroll 4
-                    for (int j = threadIdx.x; j < cnt; j += kRowdotThreads) xs[j] = p.x[(c0 + j) * p.incx];
+                    for (int j = threadIdx.x; j < cnt; j += kRowdotThreads) xs[j] = x[(c0 + j) * p.incx];
                 }
                 __syncthreads();
                 staged = c0;
+                staged_b = b;
             }
             const int64_t lo = imax(wclo, c0), hi = imin(wchi, imin(c0 + xc, Nv));
             if (lo < hi) {
@@ -178,7 +187,7 @@ __global__ void __launch_bounds__(kRowdotThreads, 4) rowdot_kernel(const RowdotA
             const int64_t j = Nv + l;
             const bool visit = MODE == MODE_LOWER ? wrow0 + RW > Nv : true;
             if (visit && j < p.N) {
-                const T xj = p.x[j * p.incx];
+                const T xj = x[j * p.incx];
 #pragma unroll
                 for (int r = 0; r < R; ++r)
                     acc[r] = fmad(tri_value<T, MODE, UNIT>(arow[r][j], grow0 + r, j), xj, acc[r]);
@@ -194,7 +203,7 @@ __global__ void __launch_bounds__(kRowdotThreads, 4) rowdot_kernel(const RowdotA
         }
         const int64_t i = grow0 + l;
         if (l < R && i < p.M) {
-            T* yp = p.y + i * p.incy;
+            T* yp = y + i * p.incy;
             T v = p.alpha * out;
             if (p.beta != T(0)) v = fmad(p.beta, *yp, v);
             *yp = v;
@@ -218,6 +227,9 @@ struct ColaccArgs {
     T* partials;         // [row groups][ppitch] when there are several row groups
     int64_t ppitch;      // N rounded up to whole vectors
     int64_t rows_per_block;   // WR == 4 only: rows of one slab
+    // a batch of problems of this shape (blockIdx.z): problem b uses A + b*sA, x + b*sx, y + b*sy
+    // and the partials at partials + b*spart
+    int64_t sA = 0, sx = 0, sy = 0, spart = 0;
 };
 
 constexpr int kColaccThreads = 256;
@@ -234,6 +246,10 @@ constexpr int kColaccThreads = 256;
 template <typename T, int VEC, int CV, int WR>
 __global__ void __launch_bounds__(kColaccThreads) colacc_kernel(const ColaccArgs<T> p)
 {
+    const T* __restrict__ A = p.A + (int64_t)blockIdx.z * p.sA;
+    const T* __restrict__ x = p.x + (int64_t)blockIdx.z * p.sx;
+    T* __restrict__ y = p.y + (int64_t)blockIdx.z * p.sy;
+    T* __restrict__ partials = p.partials + (int64_t)blockIdx.z * p.spart;
     typedef typename VecOf<T, VEC>::type V;
     static_assert(WR == 1 || CV == 1, "narrow shape has one vector per lane");
     constexpr int NW = kColaccThreads / kWave, WC = NW / WR;
@@ -284,7 +300,7 @@ __global__ void __launch_bounds__(kColaccThreads) colacc_kernel(const ColaccArgs
     // so that the loads below carry no predicate and can all be issued back to back.
     const T* acol[CV];
 #pragma unroll
-    for (int v = 0; v < CV; ++v) acol[v] = p.A + (col_ok[v] ? c + v * SPAN - shift[v] : imin(cblock0, p.N - VEC));
+    for (int v = 0; v < CV; ++v) acol[v] = A + (col_ok[v] ? c + v * SPAN - shift[v] : imin(cblock0, p.N - VEC));
     for (; r0 + (int64_t)(U - 1) * rstep < rend; r0 += radvance) {
         V a[U][CV];
         T xi[U];
@@ -293,7 +309,7 @@ __global__ void __launch_bounds__(kColaccThreads) colacc_kernel(const ColaccArgs
             const int64_t i = r0 + (int64_t)u * rstep;
 #pragma unroll
             for (int v = 0; v < CV; ++v) a[u][v] = ld_matrix<T, VEC>(acol[v] + i * p.lda);
-            xi[u] = p.x[i * p.incx];
+            xi[u] = x[i * p.incx];
         }
         __builtin_amdgcn_sched_barrier(0);   // keep every load of the batch ahead of the first FMA
 #pragma unroll
@@ -305,7 +321,7 @@ __global__ void __launch_bounds__(kColaccThreads) colacc_kernel(const ColaccArgs
                     acc[v][k] = fmad(a[u][v][k], xi[u], acc[v][k]);
     }
     for (; r0 < rend; r0 += rstep) {   // the one ragged batch
-        const T xi = p.x[r0 * p.incx];
+        const T xi = x[r0 * p.incx];
 #pragma unroll
         for (int v = 0; v < CV; ++v) {
             const V a = ld_matrix<T, VEC>(acol[v] + r0 * p.lda);
@@ -335,7 +351,7 @@ __global__ void __launch_bounds__(kColaccThreads) colacc_kernel(const ColaccArgs
 #pragma unroll
             for (int k = 0; k < VEC; ++k) {
                 if (k < shift[v]) continue;
-                T* yp = p.y + (cv + k) * p.incy;
+                T* yp = y + (cv + k) * p.incy;
                 T val = p.alpha * acc[v][k];
                 if (p.beta != T(0)) val = fmad(p.beta, *yp, val);
                 *yp = val;
@@ -344,11 +360,11 @@ __global__ void __launch_bounds__(kColaccThreads) colacc_kernel(const ColaccArgs
             V val;
 #pragma unroll
             for (int k = 0; k < VEC; ++k) val[k] = acc[v][k];
-            *reinterpret_cast<V*>(p.partials + (int64_t)blockIdx.y * p.ppitch + cv) = val;
+            *reinterpret_cast<V*>(partials + (int64_t)blockIdx.y * p.ppitch + cv) = val;
         } else {
 #pragma unroll
             for (int k = 0; k < VEC; ++k)
-                if (k >= shift[v]) p.partials[(int64_t)blockIdx.y * p.ppitch + cv + k] = acc[v][k];
+                if (k >= shift[v]) partials[(int64_t)blockIdx.y * p.ppitch + cv + k] = acc[v][k];
         }
     }
 }
@@ -360,8 +376,11 @@ constexpr int kCombineGroups = 16;
 template <typename T>
 __global__ void __launch_bounds__(kCombineGroups* kWave) colacc_combine_kernel(int64_t nparts, int64_t N, int64_t ppitch,
                                                                                const T* __restrict__ partials, T alpha, T beta,
-                                                                               T* __restrict__ y, int64_t incy)
+                                                                               T* __restrict__ y, int64_t incy, int64_t spart,
+                                                                               int64_t sy)
 {
+    partials += (int64_t)blockIdx.y * spart;   // blockIdx.y: problem of a batch
+    y += (int64_t)blockIdx.y * sy;
     __shared__ T red[kCombineGroups][kWave];
     const int tx = threadIdx.x & (kWave - 1), ty = threadIdx.x >> 6;
     const int64_t j = (int64_t)blockIdx.x * kWave + tx;
@@ -384,8 +403,9 @@ __global__ void __launch_bounds__(kCombineGroups* kWave) colacc_combine_kernel(i
 
 // y[k] = beta*y[k] (zeros when beta == 0, without reading y): the alpha == 0 case
 template <typename T>
-__global__ void __launch_bounds__(256) scale_y_kernel(int64_t n, T beta, T* __restrict__ y, int64_t incy)
+__global__ void __launch_bounds__(256) scale_y_kernel(int64_t n, T beta, T* __restrict__ y, int64_t incy, int64_t sy)
 {
+    y += (int64_t)blockIdx.y * sy;             // blockIdx.y: problem of a batch
     const int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (k < n) y[k * incy] = beta == T(0) ? T(0) : beta * y[k * incy];
 }
@@ -405,7 +425,7 @@ template <typename T, int VEC, int LPR, int R, int U, int MODE, bool UNIT>
 void launch_rowdot_inst(mxb_handle_t h, const RowdotArgs<T>& a)
 {
     constexpr int RB = kRowdotWaves * (kWave / LPR) * R;
-    const int64_t ntiles = ceil_div(a.M, RB);
+    const int64_t ntiles = ceil_div(a.M, RB) * a.batch;
     const int64_t cap = kCUs * option(h, MXB_OPT_ROWDOT_BLOCKS_PER_CU);
     const int64_t grid = ntiles < cap ? ntiles : cap;
     const size_t lds = (size_t)a.xchunk * sizeof(T);
@@ -419,10 +439,11 @@ void launch_rowdot_shape(mxb_handle_t h, const RowdotArgs<T>& a)
     //  * narrow rows (up to 16 vectors): 16 lanes per row, four rows side by side per wavefront;
     //  * long rows: 2 rows x 4 steps, so that a wavefront reads 4 KiB runs of each row;
     //  * few rows: one row per wavefront so that the grid still fills the device.
+    const int64_t allrows = a.M * a.batch;   // rows of all problems of a batch
     if (MODE == MODE_GENERAL && a.N <= 16 * 16 * VEC) {
-        if (a.M >= (int64_t)kCUs * kRowdotWaves * 4 * 4) launch_rowdot_inst<T, VEC, 16, 4, 2, MODE_GENERAL, false>(h, a);
+        if (allrows >= (int64_t)kCUs * kRowdotWaves * 4 * 4) launch_rowdot_inst<T, VEC, 16, 4, 2, MODE_GENERAL, false>(h, a);
         else launch_rowdot_inst<T, VEC, 16, 1, 2, MODE_GENERAL, false>(h, a);
-    } else if (a.M >= (int64_t)kCUs * kRowdotWaves * 2) {
+    } else if (allrows >= (int64_t)kCUs * kRowdotWaves * 2) {
         launch_rowdot_inst<T, VEC, 64, 2, 4, MODE, UNIT>(h, a);
     } else {
         launch_rowdot_inst<T, VEC, 64, 1, 4, MODE, UNIT>(h, a);
@@ -460,9 +481,9 @@ int launch_rowdot(mxb_handle_t h, RowdotArgs<T> a, int mode, bool unit)
 }
 
 template <typename T, int VEC>
-void launch_colacc_inst(mxb_handle_t h, const ColaccArgs<T>& a, const ColaccPlan& pl)
+void launch_colacc_inst(mxb_handle_t h, const ColaccArgs<T>& a, const ColaccPlan& pl, int64_t batch)
 {
-    const dim3 grid((unsigned)pl.col_tiles, (unsigned)pl.nparts);
+    const dim3 grid((unsigned)pl.col_tiles, (unsigned)pl.nparts, (unsigned)batch);
     const dim3 block(kColaccThreads);
     if (pl.wr == 4) hipLaunchKernelGGL((colacc_kernel<T, VEC, 1, 4>), grid, block, 0, h->stream, a);
     else if (pl.cv == 4) hipLaunchKernelGGL((colacc_kernel<T, VEC, 4, 1>), grid, block, 0, h->stream, a);
@@ -470,36 +491,84 @@ void launch_colacc_inst(mxb_handle_t h, const ColaccArgs<T>& a, const ColaccPlan
     else hipLaunchKernelGGL((colacc_kernel<T, VEC, 1, 1>), grid, block, 0, h->stream, a);
 }
 
+constexpr int64_t kMaxGridZ = 65535;
+
+// `batch` problems of one shape (a.sA, a.sx, a.sy apart); the blocks the plan aims at are shared
+// among them, so that a large batch of small matrices runs one block per column tile and problem
+// and needs neither partial vectors nor the second kernel.
 template <typename T>
-int launch_colacc(mxb_handle_t h, ColaccArgs<T> a)
+int launch_colacc(mxb_handle_t h, ColaccArgs<T> a, int64_t batch = 1)
 {
     constexpr int FV = Full<T>::vec;
     // Any pitch, any base address and any width of at least one vector: matrix loads need element
     // alignment only and the kernel moves the last vector of a ragged row back.
     // (a ragged row of up to 64 elements keeps more lanes busy with one element per lane)
     const bool vec = a.N % FV == 0 || a.N > kWave;
-    const ColaccPlan pl = colacc_plan(a.M, a.N, (int)sizeof(T), vec ? FV : 1, option(h, MXB_OPT_COLACC_TARGET_BLOCKS),
-                                      colacc_narrow_target(h), option(h, MXB_OPT_COLACC_MIN_ROWS));
+    auto share = [&](int64_t blocks) { return blocks / batch > 1 ? blocks / batch : 1; };
+    const ColaccPlan pl = colacc_plan(a.M, a.N, (int)sizeof(T), vec ? FV : 1, share(option(h, MXB_OPT_COLACC_TARGET_BLOCKS)),
+                                      share(colacc_narrow_target(h)), option(h, MXB_OPT_COLACC_MIN_ROWS));
     a.rows_per_block = pl.rows_per_block;
     a.partials = nullptr;
     a.ppitch = ceil_div(a.N, FV) * FV;
+    a.spart = pl.nparts * a.ppitch;
     if (pl.nparts > 1) {
-        if (!h->ws || h->ws_bytes < (size_t)pl.nparts * (size_t)a.ppitch * sizeof(T)) return MXB_ERR_WORKSPACE;
+        if (!h->ws || h->ws_bytes < (size_t)batch * (size_t)a.spart * sizeof(T)) return MXB_ERR_WORKSPACE;
         a.partials = static_cast<T*>(h->ws);
     }
-    if (vec) launch_colacc_inst<T, FV>(h, a, pl);
-    else launch_colacc_inst<T, 1>(h, a, pl);
-    int st = launch_status();
-    if (st != MXB_OK || pl.nparts == 1) return st;
-    hipLaunchKernelGGL(colacc_combine_kernel<T>, dim3((unsigned)ceil_div(a.N, kWave)), dim3(kCombineGroups * kWave), 0,
-                       h->stream, pl.nparts, a.N, a.ppitch, a.partials, a.alpha, a.beta, a.y, a.incy);
-    return launch_status();
+    for (int64_t b0 = 0; b0 < batch; b0 += kMaxGridZ) {       // the grid's z extent is limited
+        const int64_t nb = batch - b0 < kMaxGridZ ? batch - b0 : kMaxGridZ;
+        ColaccArgs<T> c = a;
+        c.A += b0 * a.sA; c.x += b0 * a.sx; c.y += b0 * a.sy;
+        if (c.partials) c.partials += b0 * a.spart;
+        if (vec) launch_colacc_inst<T, FV>(h, c, pl, nb);
+        else launch_colacc_inst<T, 1>(h, c, pl, nb);
+        int st = launch_status();
+        if (st != MXB_OK) return st;
+        if (pl.nparts == 1) continue;
+        hipLaunchKernelGGL(colacc_combine_kernel<T>, dim3((unsigned)ceil_div(a.N, kWave), (unsigned)nb), dim3(kCombineGroups * kWave),
+                           0, h->stream, pl.nparts, a.N, a.ppitch, c.partials, a.alpha, a.beta, c.y, a.incy, a.spart, a.sy);
+        st = launch_status();
+        if (st != MXB_OK) return st;
+    }
+    return MXB_OK;
 }
 
 inline bool layout_ok(int v) { return v == MXB_ROW_MAJOR || v == MXB_COL_MAJOR; }
 inline bool trans_ok(int v) { return v == MXB_NO_TRANS || v == MXB_TRANS; }
 inline bool uplo_ok(int v) { return v == MXB_UPPER || v == MXB_LOWER; }
 inline bool diag_ok(int v) { return v == MXB_NON_UNIT || v == MXB_UNIT; }
+
+// gemv on a row-major rows x cols matrix, arguments validated, x0 / y0 at logical element 0;
+// `batch` problems of this shape lie sA, sx, sy elements apart.
+template <typename T>
+int gemv_rows(mxb_handle_t h, bool no_trans, int64_t rows, int64_t cols, T alpha, const T* A, int64_t lda, int64_t sA, const T* x0,
+              int64_t incx, int64_t sx, T beta, T* y0, int64_t incy, int64_t sy, int64_t batch)
+{
+    const int64_t leny = no_trans ? rows : cols;
+    if (alpha == T(0)) {
+        for (int64_t b0 = 0; b0 < batch; b0 += kMaxGridZ) {
+            const int64_t nb = batch - b0 < kMaxGridZ ? batch - b0 : kMaxGridZ;
+            hipLaunchKernelGGL(scale_y_kernel<T>, dim3((unsigned)ceil_div(leny, 256), (unsigned)nb), dim3(256), 0, h->stream, leny,
+                               beta, y0 + b0 * sy, incy, sy);
+            const int st = launch_status();
+            if (st != MXB_OK) return st;
+        }
+        return MXB_OK;
+    }
+    if (batch == 1) {
+        // very short rows: several rows side by side per wavefront
+        if (no_trans && skinny_takes(SKINNY_GEMV_N, rows, cols, A, lda))
+            return skinny_gemv_n<T>(h, rows, cols, alpha, A, lda, x0, incx, beta, y0, incy);
+        if (!no_trans && skinny_takes(SKINNY_GEMV_T, rows, cols, A, lda))
+            return skinny_gemv_t<T>(h, rows, cols, alpha, A, lda, x0, incx, beta, y0, incy);
+    }
+    if (no_trans) {
+        RowdotArgs<T> a{rows, cols, A, lda, x0, incx, y0, incy, alpha, beta, 0, 0, batch, sA, sx, sy};
+        return launch_rowdot(h, a, MODE_GENERAL, false);
+    }
+    ColaccArgs<T> a{rows, cols, A, lda, x0, incx, y0, incy, alpha, beta, nullptr, 0, 0, sA, sx, sy, 0};
+    return launch_colacc(h, a, batch);
+}
 
 template <typename T>
 int gemv(mxb_handle_t h, int layout, int trans, int64_t m, int64_t n, T alpha, const T* A, int64_t lda, const T* x,
@@ -521,25 +590,44 @@ int gemv(mxb_handle_t h, int layout, int trans, int64_t m, int64_t n, T alpha, c
     const int64_t rows = row_major ? m : n, cols = row_major ? n : m;
     const bool no_trans = (trans == MXB_NO_TRANS) == row_major;
     const int64_t lenx = no_trans ? cols : rows, leny = no_trans ? rows : cols;
-    T* y0 = vec_base(y, leny, incy);
-    if (alpha == T(0)) {
-        hipLaunchKernelGGL(scale_y_kernel<T>, dim3((unsigned)ceil_div(leny, 256)), dim3(256), 0, h->stream, leny, beta, y0, incy);
-        return launch_status();
+    if (alpha != T(0)) {
+        if (!A) return -6;
+        if (!x) return -8;
     }
-    if (!A) return -6;
-    if (!x) return -8;
-    const T* x0 = vec_base(x, lenx, incx);
-    // very short rows: several rows side by side per wavefront
-    if (no_trans && skinny_takes(SKINNY_GEMV_N, rows, cols, A, lda))
-        return skinny_gemv_n<T>(h, rows, cols, alpha, A, lda, x0, incx, beta, y0, incy);
-    if (!no_trans && skinny_takes(SKINNY_GEMV_T, rows, cols, A, lda))
-        return skinny_gemv_t<T>(h, rows, cols, alpha, A, lda, x0, incx, beta, y0, incy);
-    if (no_trans) {
-        RowdotArgs<T> a{rows, cols, A, lda, x0, incx, y0, incy, alpha, beta, 0, 0};
-        return launch_rowdot(h, a, MODE_GENERAL, false);
+    return gemv_rows<T>(h, no_trans, rows, cols, alpha, A, lda, 0, x ? vec_base(x, lenx, incx) : x, incx, 0, beta,
+                        vec_base(y, leny, incy), incy, 0, 1);
+}
+
+// `batch` gemv problems of one shape; problem b uses A + b*strideA, x + b*stridex, y + b*stridey.
+template <typename T>
+int gemv_batched(mxb_handle_t h, int layout, int trans, int64_t m, int64_t n, T alpha, const T* A, int64_t lda, int64_t strideA,
+                 const T* x, int64_t incx, int64_t stridex, T beta, T* y, int64_t incy, int64_t stridey, int64_t batch)
+{
+    if (!handle_ok(h)) return MXB_ERR_HANDLE;
+    if (!layout_ok(layout)) return -1;
+    if (!trans_ok(trans)) return -2;
+    if (m < 0) return -3;
+    if (n < 0) return -4;
+    const int64_t minor = layout == MXB_ROW_MAJOR ? n : m;
+    if (lda < (minor > 1 ? minor : 1)) return -7;
+    if (strideA < 0) return -8;
+    if (incx == 0) return -10;
+    if (stridex < 0) return -11;
+    if (incy == 0) return -14;
+    if (batch < 0) return -16;
+    if (stridey < 0 || (stridey == 0 && batch > 1)) return -15;      // the results of two problems would collide
+    if (m == 0 || n == 0 || batch == 0 || (alpha == T(0) && beta == T(1))) return MXB_OK;
+    if (!y) return -13;
+    const bool row_major = layout == MXB_ROW_MAJOR;
+    const int64_t rows = row_major ? m : n, cols = row_major ? n : m;
+    const bool no_trans = (trans == MXB_NO_TRANS) == row_major;
+    const int64_t lenx = no_trans ? cols : rows, leny = no_trans ? rows : cols;
+    if (alpha != T(0)) {
+        if (!A) return -6;
+        if (!x) return -9;
     }
-    ColaccArgs<T> a{rows, cols, A, lda, x0, incx, y0, incy, alpha, beta, nullptr, 0, 0};
-    return launch_colacc(h, a);
+    return gemv_rows<T>(h, no_trans, rows, cols, alpha, A, lda, strideA, x ? vec_base(x, lenx, incx) : x, incx, stridex, beta,
+                        vec_base(y, leny, incy), incy, stridey, batch);
 }
 
 template <typename T>
@@ -783,6 +871,14 @@ int mxb_sgemv(mxb_handle_t h, mxb_layout_t layout, mxb_trans_t trans, int64_t m,
 int mxb_dgemv(mxb_handle_t h, mxb_layout_t layout, mxb_trans_t trans, int64_t m, int64_t n, double alpha, const double* A,
               int64_t lda, const double* x, int64_t incx, double beta, double* y, int64_t incy)
 { return mxb::gemv<double>(h, layout, trans, m, n, alpha, A, lda, x, incx, beta, y, incy); }
+int mxb_sgemv_batched(mxb_handle_t h, mxb_layout_t layout, mxb_trans_t trans, int64_t m, int64_t n, float alpha,
+                      const float* A, int64_t lda, int64_t strideA, const float* x, int64_t incx, int64_t stridex,
+                      float beta, float* y, int64_t incy, int64_t stridey, int64_t batch)
+{ return mxb::gemv_batched<float>(h, layout, trans, m, n, alpha, A, lda, strideA, x, incx, stridex, beta, y, incy, stridey, batch); }
+int mxb_dgemv_batched(mxb_handle_t h, mxb_layout_t layout, mxb_trans_t trans, int64_t m, int64_t n, double alpha,
+                      const double* A, int64_t lda, int64_t strideA, const double* x, int64_t incx, int64_t stridex,
+                      double beta, double* y, int64_t incy, int64_t stridey, int64_t batch)
+{ return mxb::gemv_batched<double>(h, layout, trans, m, n, alpha, A, lda, strideA, x, incx, stridex, beta, y, incy, stridey, batch); }
 int mxb_strmv(mxb_handle_t h, mxb_layout_t layout, mxb_uplo_t uplo, mxb_trans_t trans, mxb_diag_t diag, int64_t n,
               const float* A, int64_t lda, float* x, int64_t incx)
 { return mxb::trmv<float>(h, layout, uplo, trans, diag, n, A, lda, x, incx); }

@@ -105,6 +105,28 @@ def test_argument_errors_name_the_argument(B):
             assert g(h, B.ROW_MAJOR, B.NO_TRANS, 4, 4, 0.0, None, 4, None, 1, 1.0, None, 1) == 0
             # transposed gemv of a tall matrix needs partials: no workspace -> error, no launch
             assert g(h, B.ROW_MAJOR, B.TRANS, 4096, 4096, 1.0, P, 4096, P, 1, 0.0, P, 1) == B.ERR_WORKSPACE
+            gb = f("gemv_batched")
+            R, N = B.ROW_MAJOR, B.NO_TRANS
+            assert gb(h, 7, N, 4, 4, 1.0, P, 4, 16, P, 1, 4, 0.0, P, 1, 4, 2) == -1
+            assert gb(h, R, 7, 4, 4, 1.0, P, 4, 16, P, 1, 4, 0.0, P, 1, 4, 2) == -2
+            assert gb(h, R, N, -1, 4, 1.0, P, 4, 16, P, 1, 4, 0.0, P, 1, 4, 2) == -3
+            assert gb(h, R, N, 4, -1, 1.0, P, 4, 16, P, 1, 4, 0.0, P, 1, 4, 2) == -4
+            assert gb(h, R, N, 4, 4, 1.0, None, 4, 16, P, 1, 4, 0.0, P, 1, 4, 2) == -6
+            assert gb(h, R, N, 4, 5, 1.0, P, 4, 16, P, 1, 4, 0.0, P, 1, 4, 2) == -7
+            assert gb(h, R, N, 4, 4, 1.0, P, 4, -1, P, 1, 4, 0.0, P, 1, 4, 2) == -8
+            assert gb(h, R, N, 4, 4, 1.0, P, 4, 16, None, 1, 4, 0.0, P, 1, 4, 2) == -9
+            assert gb(h, R, N, 4, 4, 1.0, P, 4, 16, P, 0, 4, 0.0, P, 1, 4, 2) == -10
+            assert gb(h, R, N, 4, 4, 1.0, P, 4, 16, P, 1, -4, 0.0, P, 1, 4, 2) == -11
+            assert gb(h, R, N, 4, 4, 1.0, P, 4, 16, P, 1, 4, 0.0, None, 1, 4, 2) == -13
+            assert gb(h, R, N, 4, 4, 1.0, P, 4, 16, P, 1, 4, 0.0, P, 0, 4, 2) == -14
+            assert gb(h, R, N, 4, 4, 1.0, P, 4, 16, P, 1, 4, 0.0, P, 1, -4, 2) == -15
+            assert gb(h, R, N, 4, 4, 1.0, P, 4, 16, P, 1, 4, 0.0, P, 1, 0, 2) == -15      # two results in one place
+            assert gb(h, R, N, 4, 4, 1.0, P, 4, 16, P, 1, 4, 0.0, P, 1, 4, -1) == -16
+            assert gb(h, R, N, 4, 4, 1.0, None, 4, 16, None, 1, 4, 0.0, None, 1, 4, 0) == 0   # empty batch
+            assert gb(h, R, N, 0, 4, 1.0, None, 4, 16, None, 1, 4, 0.0, None, 1, 4, 3) == 0
+            assert gb(h, R, N, 4, 4, 0.0, None, 4, 16, None, 1, 4, 1.0, None, 1, 4, 3) == 0
+            # few problems of a tall transposed product need partial vectors: no workspace -> error, no launch
+            assert gb(h, R, B.TRANS, 4096, 4096, 1.0, P, 4096, 0, P, 1, 0, 0.0, P, 1, 4096, 2) == B.ERR_WORKSPACE
             t = f("trmv")
             ok = (B.ROW_MAJOR, B.UPPER, B.NO_TRANS, B.NON_UNIT)
             assert t(h, 0, ok[1], ok[2], ok[3], 4, P, 4, P, 1) == -1
@@ -221,6 +243,10 @@ def test_binding_refuses_operands_that_are_too_small_or_of_the_wrong_type(B):
             B.mxb_ssyr2(h, B.ROW_MAJOR, B.LOWER, 16, 1.0, v(16), 1, v(15), 1, v(256), 16)
         with pytest.raises(ValueError):
             B.mxb_probe_read(h, 1024, v(100))
+        with pytest.raises(ValueError):   # the third problem's matrix ends past the tensor
+            B.mxb_sgemv_batched(h, B.ROW_MAJOR, B.NO_TRANS, 4, 4, 1.0, v(2 * 20 + 15), 4, 20, v(12), 1, 4, 0.0, v(12), 1, 4, 3)
+        with pytest.raises(ValueError):   # y of the last problem
+            B.mxb_sgemv_batched(h, B.ROW_MAJOR, B.NO_TRANS, 4, 4, 1.0, v(16), 4, 0, v(4), 1, 0, 0.0, v(11), 1, 4, 3)
         # exactly large enough: passes the binding's checks and reaches the library's own validation
         assert B.mxb_sgemv(h, B.ROW_MAJOR, B.NO_TRANS, 8, 8, 1.0, v(7 * 10 + 8), 10, v(8), 0, 0.0, v(8), 1) == -9
     finally:

@@ -140,6 +140,72 @@ def test_gemv_deterministic_and_geometry_invariant(blas, ctx, dt):
             ctx.set_option(o, 0)
 
 
+# ----------------------------------------------------------------------------- gemv, strided batch
+def gemv_batched_case(blas, ctx, dt, layout, trans, m, n, batch, alpha, beta, pad, incx, incy, gaps=(0, 0, 0), share=(False, False),
+                      ints=False, seed=16):
+    """`batch` problems with canaries (NaN) in the padding and between the problems; share = (A, x)
+    shared among the problems through a stride of 0."""
+    gen = (lambda t, k: synth.small_ints(seed, t, k, -2, 2, dt)) if ints else (lambda t, k: synth.uniform(seed, t, k, dt))
+    lenx, leny = (n, m) if trans == O.NO_TRANS else (m, n)
+    major = m if layout == O.ROW_MAJOR else n
+    minor = n if layout == O.ROW_MAJOR else m
+    lda = max(minor + pad, 1)
+    spanx, spany = 1 + (lenx - 1) * abs(incx), 1 + (leny - 1) * abs(incy)
+    sA = 0 if share[0] else major * lda + gaps[0]
+    sx = 0 if share[1] else spanx + gaps[1]
+    sy = spany + gaps[2]
+    Ab = np.full(major * lda + (batch - 1) * sA, np.nan, dt)
+    xb = np.full(spanx + (batch - 1) * sx, np.nan, dt)
+    yb = np.full(spany + (batch - 1) * sy, np.nan, dt)
+    ymask = np.zeros(yb.size, bool)
+    for b in range(batch):
+        if b == 0 or not share[0]:
+            A = gen(3 * b, m * n).reshape(m, n)
+            buf, _ = matrix_buffer(A, layout, pad)
+            Ab[b * sA:b * sA + buf.size] = buf
+        if b == 0 or not share[1]:
+            xb[b * sx:b * sx + spanx] = synth.strided(gen(3 * b + 1, lenx), incx)
+        y = np.full(leny, np.nan, dt) if beta == 0 else gen(3 * b + 2, leny)
+        yb[b * sy:b * sy + spany] = synth.strided(y, incy)
+        ymask[b * sy + np.arange(leny) * abs(incy)] = True
+    ref = yb.copy()
+    D = O.gemv_batched(layout, trans, m, n, dt(alpha), Ab, lda, sA, xb, incx, sx, dt(beta), ref, incy, sy, batch, want_D=True)
+    dA, dx, dy = mat_dev(Ab), to_dev(xb), to_dev(yb)
+    st = blas.routine(prefix_of(dt), "gemv_batched")(ctx.h, layout, trans, m, n, float(alpha), dA, lda, sA, dx, incx, sx,
+                                                     float(beta), dy, incy, sy, batch)
+    assert st == 0, f"status {st}"
+    got = to_host(dy)
+    what = (f"gemv_batched {prefix_of(dt)} layout={layout} trans={trans} {m}x{n} batch={batch} pad={pad} a={alpha} b={beta} "
+            f"inc=({incx},{incy}) strides=({sA},{sx},{sy})")
+    if ints:
+        assert bits_equal(got[ymask], ref[ymask]), what
+    else:
+        g = np.concatenate([synth.gather(got[b * sy:], leny, incy) for b in range(batch)])
+        r = np.concatenate([synth.gather(ref[b * sy:], leny, incy) for b in range(batch)])
+        check_close(g, r, D, lenx, what)
+    assert np.isnan(got[~ymask]).all(), what + ": wrote outside the result vectors"
+
+
+@pytest.mark.parametrize("dt", DT)
+@pytest.mark.parametrize("trans", [O.NO_TRANS, O.TRANS])
+def test_gemv_batched(blas, ctx, dt, trans):
+    for (m, n, batch) in [(1, 1, 1), (4, 4, 5), (33, 17, 7), (64, 64, 100), (130, 257, 9), (1000, 40, 6), (40, 1000, 6),
+                          (513, 1030, 3), (2049, 300, 2), (300, 4100, 2)]:
+        gemv_batched_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, batch, 1.5, 0.5, 0, 1, 1)
+        gemv_batched_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, batch, -1, 0, 3, 1, 1, gaps=(5, 2, 3))
+    for layout in (O.ROW_MAJOR, O.COL_MAJOR):
+        gemv_batched_case(blas, ctx, dt, layout, trans, 129, 260, 5, 1.5, 0.5, 1, 2, -3, gaps=(1, 1, 1))
+        gemv_batched_case(blas, ctx, dt, layout, trans, 129, 260, 5, 2, -1, 0, -1, 1, share=(True, False))
+        gemv_batched_case(blas, ctx, dt, layout, trans, 129, 260, 5, 2, 1, 0, 1, 1, share=(False, True))
+        gemv_batched_case(blas, ctx, dt, layout, trans, 96, 200, 11, 3, -2, 2, 1, 1, ints=True)
+        gemv_batched_case(blas, ctx, dt, layout, trans, 96, 200, 4, 0, 0.5, 0, 1, 2)          # alpha == 0: A, x never read
+        gemv_batched_case(blas, ctx, dt, layout, trans, 96, 200, 4, 0, 0, 0, 1, 1)
+    # more problems than one grid dimension holds
+    gemv_batched_case(blas, ctx, dt, O.ROW_MAJOR, trans, 3, 5, 70000, 1.5, 0.5, 0, 1, 1, share=(True, False), ints=True)
+    # one large problem goes the same way as gemv
+    gemv_batched_case(blas, ctx, dt, O.ROW_MAJOR, trans, 3000, 2500, 1, 1.5, 0.5, 0, 1, 1)
+
+
 # ----------------------------------------------------------------------------- any base address, pitch and width
 @pytest.mark.parametrize("dt", DT)
 @pytest.mark.parametrize("off", [1, 2, 3])
