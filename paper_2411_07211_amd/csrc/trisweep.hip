@@ -41,7 +41,12 @@ namespace {
 // wave-uniformly: wholly outside the triangle for every row of the batch (skipped: no loads, no
 // arithmetic), wholly and strictly inside (plain arithmetic), or straddling the diagonal or a
 // ragged edge (element-wise selects).
-template <typename T, int VEC, int CV, int U, bool UPPER, int KIND, bool UNIT, bool MASKED>
+// MODE: TRI_PLAIN, a whole tile and rows wholly off the diagonal, nothing is masked; TRI_MASKED, as
+// above; TRI_EDGE, rows wholly off the diagonal in the ragged last tile: a vector is outside (past
+// column n), inside, or straddles column n, and the lane's column is the same for every row.
+enum { TRI_PLAIN = 0, TRI_MASKED = 1, TRI_EDGE = 2 };
+
+template <typename T, int VEC, int CV, int U, bool UPPER, int KIND, bool UNIT, int MODE>
 __device__ __forceinline__ void tri_batch(const TriArgs& p, const T* __restrict__ A, const T* __restrict__ x, int rb, int r1, int c,
                                           const int (&col)[CV], const int (&kmin)[CV], const bool (&col_ok)[CV], const T (&xj)[CV][VEC], T (&cacc)[CV][VEC],
                                           T* __restrict__ rowpart_wave, int lane)
@@ -52,12 +57,14 @@ __device__ __forceinline__ void tri_batch(const TriArgs& p, const T* __restrict_
     constexpr bool ROWS = KIND == TRI_SYMV;
     V a[U][CV];
     T xi[U];
+    constexpr bool MASKED = MODE == TRI_MASKED, EDGE = MODE == TRI_EDGE;
     bool dead[CV], plain[CV];
 #pragma unroll
     for (int v = 0; v < CV; ++v) {
         const int cw = __builtin_amdgcn_readfirstlane(c - lane * VEC) + v * SPAN;   // first column of the wavefront's vector v
-        dead[v] = MASKED && (UPPER ? cw + WSPAN - 1 < rb : cw > rb + U - 1);
-        plain[v] = !MASKED || ((UPPER ? cw > rb + U - 1 : cw + WSPAN - 1 < rb) && rb + U <= r1 && cw + WSPAN <= p.n);
+        dead[v] = (MASKED && (UPPER ? cw + WSPAN - 1 < rb : cw > rb + U - 1)) || (EDGE && cw >= p.n);
+        plain[v] = MODE == TRI_PLAIN || (EDGE && cw + WSPAN <= p.n) ||
+                   (MASKED && (UPPER ? cw > rb + U - 1 : cw + WSPAN - 1 < rb) && rb + U <= r1 && cw + WSPAN <= p.n);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -66,8 +73,10 @@ __device__ __forceinline__ void tri_batch(const TriArgs& p, const T* __restrict_
         const T* arow = A + (int64_t)i * p.lda;
 #pragma unroll
         for (int v = 0; v < CV; ++v) {
-            if (MASKED && dead[v]) {
+            if (dead[v]) {
                 a[u][v] = V(T(0));
+            } else if (EDGE) {
+                a[u][v] = ld_matrix<T, VEC>(arow + min(col[v], p.n - VEC));   // lanes past the last column stay in bounds
             } else if (MASKED) {
                 int cc = col[v];
                 const int diag = i / VEC * VEC;              // vector that holds the diagonal element of row i
@@ -88,7 +97,7 @@ __device__ __forceinline__ void tri_batch(const TriArgs& p, const T* __restrict_
     for (int u = 0; u < U; ++u) rs[u] = T(0);
 #pragma unroll
     for (int v = 0; v < CV; ++v) {
-        if (MASKED && dead[v]) continue;
+        if (dead[v]) continue;
         if (plain[v]) {
 #pragma unroll
             for (int u = 0; u < U; ++u)
@@ -104,13 +113,14 @@ __device__ __forceinline__ void tri_batch(const TriArgs& p, const T* __restrict_
                 // d = position of the diagonal inside this vector: element k lies strictly inside the
                 // triangle iff k < d (lower) / k > d (upper) and on the diagonal iff k == d
                 const int d = i - col[v];
-                const bool live = i < r1 && col_ok[v];
+                const bool live = (EDGE || i < r1) && col_ok[v];
 #pragma unroll
                 for (int k = 0; k < VEC; ++k) {
                     const T val = a[u][v][k];
                     const bool mine = live && k >= kmin[v];
-                    const bool off = mine && (UPPER ? k > d : k < d);
-                    const bool on = mine && k == d;
+                    // rows off the diagonal: every column below n is inside the triangle
+                    const bool off = mine && (EDGE || (UPPER ? k > d : k < d));
+                    const bool on = !EDGE && mine && k == d;
                     if (ROWS) {
                         // symv: the diagonal goes to the row sum only
                         rs[u] = (off || on) ? fmad(val, xj[v][k], rs[u]) : rs[u];
@@ -138,12 +148,12 @@ __device__ __forceinline__ void tri_batch(const TriArgs& p, const T* __restrict_
 }
 
 // x: logical element 0.  rowpart: [ntiles * 8 wavefronts][n] (symv).  colpart: [blocks][TC].
-template <typename T, int VEC, int CV, bool UPPER, int KIND, bool UNIT>
+template <typename T, int VEC, int CV, int UB, bool UPPER, int KIND, bool UNIT>
 __global__ void __launch_bounds__(kTriThreads) trisweep_kernel(const TriArgs p, const T* __restrict__ A, const T* __restrict__ x,
                                                                T* __restrict__ rowpart, T* __restrict__ colpart)
 {
     typedef typename VecOf<T, VEC>::type V;
-    constexpr int U = 16 / CV, UD = 2 * U;   // rows per batch: off the diagonal / across it
+    constexpr int U = UB / CV, UD = 2 * U;   // rows per batch: off the diagonal / across it
     constexpr int SPAN = kTriThreads * VEC;
     constexpr int TC = CV * SPAN;
     constexpr bool ROWS = KIND == TRI_SYMV;
@@ -187,15 +197,17 @@ __global__ void __launch_bounds__(kTriThreads) trisweep_kernel(const TriArgs p, 
     const int f0 = UPPER ? 0 : cb1, f1 = UPPER ? cb0 : n;
     auto diagonal_rows = [&]() {
         for (int64_t rb = cb0 + (int64_t)s * UD; rb < cb1; rb += (int64_t)S * UD)
-            tri_batch<T, VEC, CV, UD, UPPER, KIND, UNIT, true>(p, A, x, (int)rb, cb1, c, col, kmin, col_ok, xj, cacc, rowpart_wave, lane);
+            tri_batch<T, VEC, CV, UD, UPPER, KIND, UNIT, TRI_MASKED>(p, A, x, (int)rb, cb1, c, col, kmin, col_ok, xj, cacc, rowpart_wave, lane);
     };
     auto inside_rows = [&]() {
         for (int64_t rb64 = f0 + (int64_t)s * U; rb64 < f1; rb64 += (int64_t)S * U) {
             const int rb = (int)rb64;
-            if (full_tile && rb + U <= f1)
-                tri_batch<T, VEC, CV, U, UPPER, KIND, UNIT, false>(p, A, x, rb, f1, c, col, kmin, col_ok, xj, cacc, rowpart_wave, lane);
+            if (rb + U > f1)
+                tri_batch<T, VEC, CV, U, UPPER, KIND, UNIT, TRI_MASKED>(p, A, x, rb, f1, c, col, kmin, col_ok, xj, cacc, rowpart_wave, lane);
+            else if (full_tile)
+                tri_batch<T, VEC, CV, U, UPPER, KIND, UNIT, TRI_PLAIN>(p, A, x, rb, f1, c, col, kmin, col_ok, xj, cacc, rowpart_wave, lane);
             else
-                tri_batch<T, VEC, CV, U, UPPER, KIND, UNIT, true>(p, A, x, rb, f1, c, col, kmin, col_ok, xj, cacc, rowpart_wave, lane);
+                tri_batch<T, VEC, CV, U, UPPER, KIND, UNIT, TRI_EDGE>(p, A, x, rb, f1, c, col, kmin, col_ok, xj, cacc, rowpart_wave, lane);
         }
     };
     if (UPPER) { inside_rows(); diagonal_rows(); }
@@ -255,12 +267,12 @@ __global__ void __launch_bounds__(kCombineGroups* kWave) trisweep_combine_kernel
     *op = v;
 }
 
-template <typename T, int VEC, int CV, int KIND>
+template <typename T, int VEC, int CV, int UB, int KIND>
 void launch_sweep(mxb_handle_t h, bool upper, bool unit, const TriArgs& a, const T* A, const T* x, T* rowpart, T* colpart)
 {
     const dim3 grid((unsigned)a.blocks), block(kTriThreads);
 #define MXB_TRI(UP_, KIND_, UNIT_) \
-    hipLaunchKernelGGL((trisweep_kernel<T, VEC, CV, UP_, KIND_, UNIT_>), grid, block, 0, h->stream, a, A, x, rowpart, colpart)
+    hipLaunchKernelGGL((trisweep_kernel<T, VEC, CV, UB, UP_, KIND_, UNIT_>), grid, block, 0, h->stream, a, A, x, rowpart, colpart)
     if (KIND == TRI_SYMV) {
         if (upper) MXB_TRI(true, TRI_SYMV, false); else MXB_TRI(false, TRI_SYMV, false);
     } else if (upper) {
@@ -280,8 +292,8 @@ int trisweep(mxb_handle_t h, bool upper, bool unit, int64_t n, T alpha, const T*
     // Any pitch, any base address and any n of at least one vector: matrix loads need element
     // alignment only and the kernel moves the last vector of a ragged row back.
     const bool vec = n >= FV;
-    const TriPlan pl = tri_plan(n, vec ? FV : 1, upper, h->opt[MXB_OPT_SYMV_TARGET_BLOCKS], h->opt[MXB_OPT_SYMV_TILE_VECTORS],
-                                option(h, MXB_OPT_TRI_DIAG_WEIGHT));
+    const TriPlan pl = tri_plan(n, vec ? FV : 1, (int)sizeof(T), upper, h->opt[MXB_OPT_SYMV_TARGET_BLOCKS],
+                                h->opt[MXB_OPT_SYMV_TILE_VECTORS], option(h, MXB_OPT_TRI_DIAG_WEIGHT));
     if (!pl.ok) return MXB_ERR_NOT_IMPLEMENTED;
     const size_t need = tri_workspace_elems(n, pl, KIND == TRI_SYMV) * sizeof(T);
     if (!h->ws || h->ws_bytes < need) return MXB_ERR_WORKSPACE;
@@ -291,15 +303,12 @@ int trisweep(mxb_handle_t h, bool upper, bool unit, int64_t n, T alpha, const T*
     for (int t = 0; t <= kTriMaxTiles; ++t) a.first_block[t] = pl.first_block[t <= pl.ntiles ? t : pl.ntiles];
     T* rowpart = static_cast<T*>(h->ws);
     T* colpart = rowpart + (KIND == TRI_SYMV ? (int64_t)pl.ntiles * kTriWaves * n : 0);
-    if (vec) {
-        if (pl.cv == 4) launch_sweep<T, FV, 4, KIND>(h, upper, unit, a, A, x0, rowpart, colpart);
-        else if (pl.cv == 2) launch_sweep<T, FV, 2, KIND>(h, upper, unit, a, A, x0, rowpart, colpart);
-        else launch_sweep<T, FV, 1, KIND>(h, upper, unit, a, A, x0, rowpart, colpart);
-    } else {
-        if (pl.cv == 4) launch_sweep<T, 1, 4, KIND>(h, upper, unit, a, A, x0, rowpart, colpart);
-        else if (pl.cv == 2) launch_sweep<T, 1, 2, KIND>(h, upper, unit, a, A, x0, rowpart, colpart);
-        else launch_sweep<T, 1, 1, KIND>(h, upper, unit, a, A, x0, rowpart, colpart);
-    }
+    if (!vec) launch_sweep<T, 1, 1, 4, KIND>(h, upper, unit, a, A, x0, rowpart, colpart);
+    else if (pl.cv == 4) launch_sweep<T, FV, 4, 16, KIND>(h, upper, unit, a, A, x0, rowpart, colpart);
+    else if (pl.cv == 2) launch_sweep<T, FV, 2, 16, KIND>(h, upper, unit, a, A, x0, rowpart, colpart);
+    else if (pl.ub == 16) launch_sweep<T, FV, 1, 16, KIND>(h, upper, unit, a, A, x0, rowpart, colpart);
+    else if (pl.ub == 8) launch_sweep<T, FV, 1, 8, KIND>(h, upper, unit, a, A, x0, rowpart, colpart);
+    else launch_sweep<T, FV, 1, 4, KIND>(h, upper, unit, a, A, x0, rowpart, colpart);
     const int st = launch_status();
     if (st != MXB_OK) return st;
     const dim3 cgrid((unsigned)ceil_div(n, kWave)), cblock(kCombineGroups * kWave);

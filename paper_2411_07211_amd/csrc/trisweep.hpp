@@ -19,6 +19,7 @@ constexpr int64_t kTriDefaultBlocks = 192;
 struct TriPlan {
     int vec;         // elements per load (16-byte vectors, or 1 for unaligned data)
     int cv;          // vectors per lane and row
+    int ub;          // loads a lane keeps in flight in a batch of rows off the diagonal: 4, 8 or 16
     int tile_cols;   // cv * 512 * vec
     int ntiles;
     int blocks;      // grid size; at least ntiles
@@ -26,7 +27,7 @@ struct TriPlan {
     bool ok;         // false: n needs more than kTriMaxTiles tiles
 };
 
-inline TriPlan tri_plan(int64_t n, int vec, bool upper, int64_t want_blocks, int64_t force_cv, int64_t diag_weight)
+inline TriPlan tri_plan(int64_t n, int vec, int elem_size, bool upper, int64_t want_blocks, int64_t force_cv, int64_t diag_weight)
 {
     TriPlan p;
     n = n > 0 ? n : 1;
@@ -36,22 +37,30 @@ inline TriPlan tri_plan(int64_t n, int vec, bool upper, int64_t want_blocks, int
     // row, but the rows that cross the diagonal run masked code and should stay a small part
     p.cv = n >= 4 * 2 * span ? 2 : 1;
     if (force_cv == 1 || force_cv == 2 || force_cv == 4) p.cv = (int)force_cv;
+    if (vec == 1) p.cv = 1;      // scalar loads serve only matrices narrower than one vector
     while (p.cv < 4 && ceil_div(n, p.cv * span) > kTriMaxTiles) p.cv *= 2;
+    // Long batches (16 loads in flight per lane) sweep a triangle that streams from HBM fastest; a
+    // triangle that fits the last-level cache is bound by the latency of its few batches per
+    // block and wants short ones (measured: 4 loads below 72 MiB, 8 below 288 MiB).
+    const int64_t tri_bytes = n * (n + 1) / 2 * elem_size;
+    p.ub = (p.cv > 1 || tri_bytes >= ((int64_t)288 << 20)) ? 16 : tri_bytes >= ((int64_t)72 << 20) ? 8 : 4;
+    if (vec == 1) p.ub = 4;
     p.tile_cols = (int)(p.cv * span);
     const int64_t nt = ceil_div(n, p.tile_cols);
     p.ok = nt <= kTriMaxTiles;
     p.ntiles = (int)(p.ok ? nt : kTriMaxTiles);
     const int64_t dw = diag_weight < 1 ? 1 : (diag_weight > 8 ? 8 : diag_weight);
-    // work of a tile in quarter rows, scaled by its width
+    // work of a tile in quarter rows
     int64_t work[kTriMaxTiles], total = 0;
     for (int t = 0; t < p.ntiles; ++t) {
         const int64_t c0 = (int64_t)t * p.tile_cols, c1 = c0 + p.tile_cols < n ? c0 + p.tile_cols : n;
         const int64_t inside = upper ? c0 : n - c1, across = c1 - c0;
-        work[t] = (4 * inside + dw * across) * (c1 - c0);
+        // (a narrow last tile saves bytes, but a batch of its rows takes as long as a full one)
+        work[t] = 4 * inside + dw * across;
         total += work[t];
     }
     int64_t g = want_blocks > 0 ? want_blocks : kTriDefaultBlocks;
-    const int64_t batches = ceil_div(n, 16 / p.cv);
+    const int64_t batches = ceil_div(n, p.ub / p.cv);
     if (g > batches * p.ntiles) g = batches * p.ntiles;      // more blocks than batches of rows are of no use
     if (g < p.ntiles) g = p.ntiles;
     p.blocks = (int)g;
@@ -84,7 +93,7 @@ inline size_t tri_workspace_bound(int64_t n, int elem_size)
     size_t b = 0;
     for (int vec : {1, 16 / elem_size})
         for (bool upper : {false, true}) {
-            const TriPlan p = tri_plan(n, vec, upper, 0, 0, 3);
+            const TriPlan p = tri_plan(n, vec, elem_size, upper, 0, 0, 3);
             const size_t need = tri_workspace_elems(n, p, true) * (size_t)elem_size;
             b = need > b ? need : b;
         }

@@ -281,6 +281,10 @@ def test_trmv(blas, ctx, dt, layout, uplo, trans, diag):
     trmv_case(blas, ctx, dt, layout, uplo, trans, diag, 515, 1, 2)
     trmv_case(blas, ctx, dt, layout, uplo, trans, diag, 515, 0, -1)
     trmv_case(blas, ctx, dt, layout, uplo, trans, diag, 1536, 0, 1, ints=True)
+    # sizes at which the triangle sweep takes its medium and its long batches
+    trmv_case(blas, ctx, dt, layout, uplo, trans, diag, 7001, 0, 1)
+    if dt == np.float32 and layout == O.ROW_MAJOR and diag == O.NON_UNIT:
+        trmv_case(blas, ctx, dt, layout, uplo, trans, diag, 12500, 0, 1)
     # the triangle sweep behind the transposed product with wider tiles and other grid sizes
     try:
         for cv, n in ((2, 4100), (4, 6000)):
@@ -332,6 +336,10 @@ def test_symv(blas, ctx, dt, layout, uplo):
         symv_case(blas, ctx, dt, layout, uplo, 700, alpha, beta, 0, 1, 1)
     symv_case(blas, ctx, dt, layout, uplo, 515, 1.5, 0.5, 1, 2, -3)
     symv_case(blas, ctx, dt, layout, uplo, 1536, 3, -2, 0, 1, 1, ints=True)
+    # sizes at which the triangle sweep takes its medium and its long batches
+    symv_case(blas, ctx, dt, layout, uplo, 7001, 1.5, 0.5, 0, 1, 1)
+    if dt == np.float32 and layout == O.ROW_MAJOR:
+        symv_case(blas, ctx, dt, layout, uplo, 12500, 1.5, 0.5, 0, 1, 1)
     try:
         for tb in (1, 7, 64, 1000):
             ctx.set_option(blas.OPT_SYMV_TARGET_BLOCKS, tb)
