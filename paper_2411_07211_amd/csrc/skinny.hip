@@ -27,7 +27,7 @@ template <typename T>
 struct SkinnyArgs {
     int64_t M;           // rows
     int N;               // columns
-    int nv;              // vectors per row = N / VEC
+    int nv;              // vectors per row = ceil(N / VEC); the last one is moved back to end at N
     int64_t lda;
     int64_t incs, incl;  // increments of the short (length N) and the long (length M) vector
     T alpha, beta;
@@ -45,12 +45,15 @@ __device__ __forceinline__ double shfl_down(double v, int lane, int off)
     return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
 }
 
-// What a lane works on: vector k of row g (of the wavefront's G rows per slot).
+// What a lane works on: vector k of row g (of the wavefront's G rows per slot).  The vector
+// starts at column c; when N is not a whole number of vectors the last vector of a row is moved
+// back so that it ends at N (rows may start at any element: a matrix access needs element
+// alignment only) and its first kmin elements, which the lane before it owns, do not count.
 struct LaneMap {
-    int lane, G, g, k;
+    int lane, G, g, k, c, kmin;
     bool active;
 };
-__device__ __forceinline__ LaneMap lane_map(int nv)
+__device__ __forceinline__ LaneMap lane_map(int nv, int N, int vec)
 {
     LaneMap m;
     m.lane = threadIdx.x & (kWave - 1);
@@ -59,6 +62,8 @@ __device__ __forceinline__ LaneMap lane_map(int nv)
     m.k = m.lane - m.g * nv;
     m.active = m.g < m.G;
     if (!m.active) m.g = m.k = 0;      // idle lanes shadow lane 0: their loads stay in bounds and are discarded
+    m.c = m.k * vec < N - vec ? m.k * vec : N - vec;
+    m.kmin = m.k * vec - m.c;
     return m;
 }
 
@@ -69,10 +74,10 @@ __global__ void __launch_bounds__(kThreads) skinny_gemv_n_kernel(const SkinnyArg
                                                                  const T* __restrict__ x, T* __restrict__ y)
 {
     typedef typename VecOf<T, VEC>::type V;
-    const LaneMap m = lane_map(p.nv);
+    const LaneMap m = lane_map(p.nv, p.N, VEC);
     T xr[VEC];
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) xr[e] = m.active ? x[(int64_t)(m.k * VEC + e) * p.incs] : T(0);
+    for (int e = 0; e < VEC; ++e) xr[e] = m.active ? x[(int64_t)(m.c + e) * p.incs] : T(0);
     const int64_t rows_per_tile = (int64_t)kSlots * m.G;
     const int64_t ntiles = (p.M + rows_per_tile - 1) / rows_per_tile;
     const int64_t wave0 = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6), nwaves = (int64_t)gridDim.x * kWaves;
@@ -81,13 +86,13 @@ __global__ void __launch_bounds__(kThreads) skinny_gemv_n_kernel(const SkinnyArg
         V a[kSlots];
         if ((t + 1) * rows_per_tile <= p.M) {      // whole tile: no predicate, so that all loads issue back to back
 #pragma unroll
-            for (int u = 0; u < kSlots; ++u) a[u] = ld_stream(reinterpret_cast<const V*>(A + (row0 + (int64_t)u * m.G) * p.lda) + m.k);
+            for (int u = 0; u < kSlots; ++u) a[u] = ld_matrix<T, VEC>(A + (row0 + (int64_t)u * m.G) * p.lda + m.c);
         } else {
 #pragma unroll
             for (int u = 0; u < kSlots; ++u) {
                 const int64_t i = row0 + (int64_t)u * m.G;
                 a[u] = V(T(0));
-                if (i < p.M) a[u] = ld_stream(reinterpret_cast<const V*>(A + i * p.lda) + m.k);
+                if (i < p.M) a[u] = ld_matrix<T, VEC>(A + i * p.lda + m.c);
             }
         }
         __builtin_amdgcn_sched_barrier(0);   // every load of the tile is in flight before the first FMA
@@ -95,7 +100,7 @@ __global__ void __launch_bounds__(kThreads) skinny_gemv_n_kernel(const SkinnyArg
         for (int u = 0; u < kSlots; ++u) {
             T s = T(0);
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) s = fmad(a[u][e], xr[e], s);
+            for (int e = 0; e < VEC; ++e) s = e >= m.kmin ? fmad(a[u][e], xr[e], s) : s;
             // sum over the nv lanes of the row: lane k adds lane k+off while that is still in the row
 #pragma unroll
             for (int off = 32; off > 0; off >>= 1) {
@@ -121,7 +126,7 @@ __global__ void __launch_bounds__(kThreads) skinny_gemv_t_kernel(const SkinnyArg
 {
     typedef typename VecOf<T, VEC>::type V;
     __shared__ T red[kWaves][kWave][VEC];
-    const LaneMap m = lane_map(p.nv);
+    const LaneMap m = lane_map(p.nv, p.N, VEC);
     const int wave = threadIdx.x >> 6;
     T acc[VEC];
 #pragma unroll
@@ -137,7 +142,7 @@ __global__ void __launch_bounds__(kThreads) skinny_gemv_t_kernel(const SkinnyArg
 #pragma unroll
             for (int u = 0; u < kSlots; ++u) {
                 const int64_t i = row0 + (int64_t)u * m.G;
-                a[u] = ld_stream(reinterpret_cast<const V*>(A + i * p.lda) + m.k);
+                a[u] = ld_matrix<T, VEC>(A + i * p.lda + m.c);
                 xi[u] = x[i * p.incl];
             }
         } else {
@@ -147,7 +152,7 @@ __global__ void __launch_bounds__(kThreads) skinny_gemv_t_kernel(const SkinnyArg
                 a[u] = V(T(0));
                 xi[u] = T(0);
                 if (i < p.M) {
-                    a[u] = ld_stream(reinterpret_cast<const V*>(A + i * p.lda) + m.k);
+                    a[u] = ld_matrix<T, VEC>(A + i * p.lda + m.c);
                     xi[u] = x[i * p.incl];
                 }
             }
@@ -163,7 +168,9 @@ __global__ void __launch_bounds__(kThreads) skinny_gemv_t_kernel(const SkinnyArg
     for (int e = 0; e < VEC; ++e) red[wave][m.lane][e] = m.active ? acc[e] : T(0);
     __syncthreads();
     for (int j = threadIdx.x; j < p.N; j += kThreads) {
-        const int k = j / VEC, e = j - k * VEC;
+        int k = j / VEC;
+        k = k < p.nv - 1 ? k : p.nv - 1;
+        const int c = k * VEC < p.N - VEC ? k * VEC : p.N - VEC, e = j - c;     // as in lane_map
         T s = T(0);
         for (int w = 0; w < kWaves; ++w)
             for (int g = 0; g < m.G; ++g) s += red[w][g * p.nv + k][e];
@@ -202,11 +209,11 @@ __global__ void __launch_bounds__(kThreads) skinny_ger_kernel(const SkinnyArgs<T
                                                               const T* __restrict__ y)
 {
     typedef typename VecOf<T, VEC>::type V;
-    const LaneMap m = lane_map(p.nv);
+    const LaneMap m = lane_map(p.nv, p.N, VEC);
     if (!m.active) return;               // no barrier below: idle lanes can leave
     T yr[VEC];
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) yr[e] = y[(int64_t)(m.k * VEC + e) * p.incs];
+    for (int e = 0; e < VEC; ++e) yr[e] = y[(int64_t)(m.c + e) * p.incs];
     const int64_t rows_per_tile = (int64_t)kSlots * m.G;
     const int64_t ntiles = (p.M + rows_per_tile - 1) / rows_per_tile;
     const int64_t wave0 = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6), nwaves = (int64_t)gridDim.x * kWaves;
@@ -218,7 +225,7 @@ __global__ void __launch_bounds__(kThreads) skinny_ger_kernel(const SkinnyArgs<T
 #pragma unroll
             for (int u = 0; u < kSlots; ++u) {
                 const int64_t i = row0 + (int64_t)u * m.G;
-                a[u] = ld_stream(reinterpret_cast<const V*>(A + i * p.lda) + m.k);
+                a[u] = ld_matrix<T, VEC>(A + i * p.lda + m.c);
                 ax[u] = p.alpha * x[i * p.incl];
             }
         } else {
@@ -228,7 +235,7 @@ __global__ void __launch_bounds__(kThreads) skinny_ger_kernel(const SkinnyArgs<T
                 a[u] = V(T(0));
                 ax[u] = T(0);
                 if (i < p.M) {
-                    a[u] = ld_stream(reinterpret_cast<const V*>(A + i * p.lda) + m.k);
+                    a[u] = ld_matrix<T, VEC>(A + i * p.lda + m.c);
                     ax[u] = p.alpha * x[i * p.incl];
                 }
             }
@@ -240,7 +247,14 @@ __global__ void __launch_bounds__(kThreads) skinny_ger_kernel(const SkinnyArgs<T
             if (i < p.M) {
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) a[u][e] = fmad(ax[u], yr[e], a[u][e]);
-                st_stream(reinterpret_cast<V*>(A + i * p.lda) + m.k, a[u]);
+                T* ap = A + i * p.lda + m.c;
+                if (m.kmin == 0) {
+                    st_matrix<T, VEC>(ap, a[u]);
+                } else {
+#pragma unroll
+                    for (int e = 1; e < VEC; ++e)
+                        if (e >= m.kmin) ap[e] = a[u][e];
+                }
             }
         }
     }
@@ -250,7 +264,7 @@ template <typename T>
 SkinnyArgs<T> make_args(int64_t rows, int64_t cols, int vec, int64_t lda, int64_t incs, int64_t incl, T alpha, T beta)
 {
     SkinnyArgs<T> a;
-    a.M = rows; a.N = (int)cols; a.nv = (int)(cols / vec); a.lda = lda; a.incs = incs; a.incl = incl; a.alpha = alpha; a.beta = beta;
+    a.M = rows; a.N = (int)cols; a.nv = (int)ceil_div(cols, (int64_t)vec); a.lda = lda; a.incs = incs; a.incl = incl; a.alpha = alpha; a.beta = beta;
     return a;
 }
 

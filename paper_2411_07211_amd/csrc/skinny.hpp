@@ -10,15 +10,15 @@ enum SkinnyOp { SKINNY_GEMV_N, SKINNY_GEMV_T, SKINNY_GER };
 // Does the skinny path take this operation on a rows x cols row-major matrix with this base and
 // pitch?  The limits are where the skinny kernels measured faster than the general ones: rows of
 // up to 12 vectors of 16 bytes in fp32 (48 columns; in fp64 only the rank-1 update, up to 20
-// vectors = 40 columns), a whole number of vectors per row, aligned base and pitch, and enough
-// rows that the run is not launch-bound (the transposed product also has to pay for its
-// second kernel).
+// vectors = 40 columns), at least one vector per row, and enough rows that the run is not
+// launch-bound (the transposed product also has to pay for its second kernel).
 template <typename T>
 inline bool skinny_takes(SkinnyOp op, int64_t rows, int64_t cols, const T* A, int64_t lda)
 {
     const int64_t fv = 16 / (int64_t)sizeof(T);
-    if (cols < 1 || cols % fv != 0 || lda % fv != 0 || !aligned16(A)) return false;
-    const int64_t nv = cols / fv;
+    (void)A; (void)lda;                       // any base and pitch: matrix accesses need element alignment only
+    if (cols < fv) return false;
+    const int64_t nv = (cols + fv - 1) / fv;  // a ragged last vector is moved back to end at the last column
     if (sizeof(T) == 8) return op == SKINNY_GER && nv <= 20 && rows >= 100000;
     return nv <= 12 && rows >= (op == SKINNY_GEMV_T ? 500000 : 100000);
 }

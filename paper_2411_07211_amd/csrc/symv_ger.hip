@@ -274,7 +274,7 @@ int ger(mxb_handle_t h, int layout, int64_t m, int64_t n, T alpha, const T* x, i
     // Any pitch, any base address and any width of at least one vector: matrix accesses need element
     // alignment only and the kernel moves the last vector of a ragged row back.
     // (a short ragged row keeps more lanes busy with one element per lane)
-    const bool vec = a.N % FV == 0 || a.N >= kThreads;
+    const bool vec = a.N % FV == 0 || a.N >= 2 * kWave;
     a.col_tiles = (uint32_t)ceil_div(a.N, (int64_t)kThreads * (vec ? FV : 1));
     const int64_t blocks = (int64_t)a.col_tiles * ceil_div(a.M, a.rows_per_block);
     if (blocks > 0x7fffffff) return MXB_ERR_NOT_IMPLEMENTED;

@@ -533,6 +533,17 @@ def test_gemv_skinny(blas, ctx):
         gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, 500000, 16, 3, -2, 0, 1, 1, ints=True)
     for (m, n) in [(100000, 40), (131072, 16), (100001, 24), (150000, 48)]:             # not transposed: from 100000 rows
         gemv_case(blas, ctx, dt, O.ROW_MAJOR, O.NO_TRANS, m, n, 1.5, 0.5, 0, 1, 1)
+    # rows that are not a whole number of vectors, odd pitches, a displaced base
+    for off in (0, 1):
+        A_OFFSET[0] = off
+        try:
+            for trans in (O.NO_TRANS, O.TRANS):
+                for (m, n) in [(500000, 41), (500001, 5), (500000, 47), (500000, 6), (500000, 39)]:
+                    for pad in (0, 1):
+                        gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, 1.5, 0.5, pad, 1, 1)
+                gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, 500000, 41, 3, -2, 0, 1, 1, ints=True)
+        finally:
+            A_OFFSET[0] = 0
 
 
 @pytest.mark.parametrize("dt", DT)
@@ -543,3 +554,13 @@ def test_ger_skinny(blas, ctx, dt):
     ger_case(blas, ctx, dt, O.ROW_MAJOR, 100000, 40, -1.5, 4, 2, -3)
     ger_case(blas, ctx, dt, O.COL_MAJOR, 40, 100000, -1.5, 0, 1, 1)
     ger_case(blas, ctx, dt, O.ROW_MAJOR, 100000, 32, 3, 0, 1, 1, ints=True)
+    # rows that are not a whole number of vectors, odd pitches, a displaced base
+    for off in (0, 1):
+        A_OFFSET[0] = off
+        try:
+            for (m, n) in [(100000, 41), (100001, 5), (100000, 39), (100000, 3 if dt == np.float64 else 6)]:
+                for pad in (0, 1):
+                    ger_case(blas, ctx, dt, O.ROW_MAJOR, m, n, 0.3, pad, 1, 1)
+            ger_case(blas, ctx, dt, O.ROW_MAJOR, 100000, 37, 3, 1, 1, 1, ints=True)
+        finally:
+            A_OFFSET[0] = 0
