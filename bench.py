@@ -330,7 +330,7 @@ TRAFFIC_KERNELS = {
     "dgemv_n_16384": ["rowdot_kernel<double, 2, 64, 2, 4, 0, false>"],
     "dgemv_t_16384": ["colacc_kernel<double, 2, 4, 1>", "colacc_combine_kernel<double>"],
     "strmv_un_16384": ["gather_kernel<float>", "rowdot_kernel<float, 4, 64, 2, 4, 1, false>"],
-    "ssymv_l_16384": ["trisweep_kernel<float, 4, 2, false, 0, false>", "trisweep_combine_kernel<float, false, 0>"],
+    "ssymv_l_16384": ["trisweep_kernel<float, 4, 2, 16, false, 0, false>", "trisweep_combine_kernel<float, false, 0>"],
     "sger_16384": ["ger_kernel<float, 4>"],
     "saxpy": ["axpy_vec_kernel<float>"],
     "sscal": ["scal_vec_kernel<float>"],
