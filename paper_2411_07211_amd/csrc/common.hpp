@@ -62,7 +62,7 @@ template <typename T> struct Full { static constexpr int vec = 16 / sizeof(T); }
 template <typename V> __device__ __forceinline__ V ld_stream(const V* p) { return __builtin_nontemporal_load(p); }
 template <typename V> __device__ __forceinline__ void st_stream(V* p, V v) { __builtin_nontemporal_store(v, p); }
 
-// The same for VEC elements of a matrix row.  A 128-bit global load or store needs the alignment
+// The same for VEC adjacent elements of a matrix row or of a contiguous vector.  A 128-bit global load or store needs the alignment
 // of one element only, so the rows of a matrix may start anywhere (any pitch, any base address):
 // the vector is declared with element alignment and still moves as one 128-bit access.
 template <typename T, int VEC>

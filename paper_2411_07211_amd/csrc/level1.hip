@@ -17,7 +17,7 @@ constexpr int kUnroll = 4;      // independent 128-bit loads per thread and arra
 constexpr int kScalUnroll = 2;  // scal reads and writes the same lines: shorter batches stream better
 
 // ---------------------------------------------------------------------------------------------
-// streaming: axpy / scal on contiguous, 16-byte aligned data
+// streaming: axpy / scal on contiguous data (any base address: 128-bit accesses at element alignment)
 
 // Tiles of kThreads*U vectors (shaped by stream_tile).  Whole tiles carry no predicate, so that
 // all loads of a tile are issued back to back; the ragged rest (fewer than one tile of vectors,
@@ -29,31 +29,29 @@ __global__ void __launch_bounds__(kThreads) axpy_vec_kernel(int64_t nvec, int64_
     constexpr int VEC = Full<T>::vec;
     constexpr int U = kUnroll;
     typedef typename VecOf<T, VEC>::type V;
-    const V* xv = reinterpret_cast<const V*>(x);
-    V* yv = reinterpret_cast<V*>(y);
     for (int64_t t = blockIdx.x; t < nfull; t += gridDim.x) {
         int64_t base, step;
         stream_tile<U>(t, n2d, base, step);
         V a[U], b[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) a[u] = ld_stream(xv + base + u * step);
+        for (int u = 0; u < U; ++u) a[u] = ld_matrix<T, VEC>(x + (base + u * step) * VEC);
 #pragma unroll
-        for (int u = 0; u < U; ++u) b[u] = ld_stream(yv + base + u * step);
+        for (int u = 0; u < U; ++u) b[u] = ld_matrix<T, VEC>(y + (base + u * step) * VEC);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
 #pragma unroll
             for (int k = 0; k < VEC; ++k) b[u][k] = fmad(alpha, a[u][k], b[u][k]);
-            st_stream(yv + base + u * step, b[u]);
+            st_matrix<T, VEC>(y + (base + u * step) * VEC, b[u]);
         }
     }
     if (blockIdx.x != gridDim.x - 1) return;
     for (int64_t i = nfull * (kThreads * U) + threadIdx.x; i < nvec; i += kThreads) {
-        V b = yv[i];
-        const V a = xv[i];
+        V b = ld_matrix<T, VEC>(y + i * VEC);
+        const V a = ld_matrix<T, VEC>(x + i * VEC);
 #pragma unroll
         for (int k = 0; k < VEC; ++k) b[k] = fmad(alpha, a[k], b[k]);
-        yv[i] = b;
+        st_matrix<T, VEC>(y + i * VEC, b);
     }
     if ((int)threadIdx.x < tail) {
         const int64_t i = nvec * VEC + threadIdx.x;
@@ -68,27 +66,26 @@ __global__ void __launch_bounds__(kThreads) scal_vec_kernel(int64_t nvec, int64_
     constexpr int VEC = Full<T>::vec;
     constexpr int U = kScalUnroll;
     typedef typename VecOf<T, VEC>::type V;
-    V* xv = reinterpret_cast<V*>(x);
     for (int64_t t = blockIdx.x; t < nfull; t += gridDim.x) {
         int64_t base, step;
         stream_tile<U>(t, n2d, base, step);
         V a[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) a[u] = ld_stream(xv + base + u * step);
+        for (int u = 0; u < U; ++u) a[u] = ld_matrix<T, VEC>(x + (base + u * step) * VEC);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
 #pragma unroll
             for (int k = 0; k < VEC; ++k) a[u][k] = alpha * a[u][k];
-            st_stream(xv + base + u * step, a[u]);
+            st_matrix<T, VEC>(x + (base + u * step) * VEC, a[u]);
         }
     }
     if (blockIdx.x != gridDim.x - 1) return;
     for (int64_t i = nfull * (kThreads * U) + threadIdx.x; i < nvec; i += kThreads) {
-        V a = xv[i];
+        V a = ld_matrix<T, VEC>(x + i * VEC);
 #pragma unroll
         for (int k = 0; k < VEC; ++k) a[k] = alpha * a[k];
-        xv[i] = a;
+        st_matrix<T, VEC>(x + i * VEC, a);
     }
     if ((int)threadIdx.x < tail) {
         const int64_t i = nvec * VEC + threadIdx.x;
@@ -96,7 +93,7 @@ __global__ void __launch_bounds__(kThreads) scal_vec_kernel(int64_t nvec, int64_
     }
 }
 
-// streaming with arbitrary increments (or unaligned data): one element per lane and load,
+// streaming with arbitrary increments: one element per lane and load,
 // 64-bit offsets because a strided fp64 vector of 2^28 elements spans more than 4 GiB.  Tiles of
 // kThreads*kStridedUnroll logical elements; whole tiles carry no predicate, the last block takes
 // the ragged rest.
@@ -238,7 +235,7 @@ __device__ __forceinline__ void block_partial(const Acc<T, OP>* acc, int nacc, d
     }
 }
 
-// pass 1 on contiguous, aligned data: whole tiles without predicates, the ragged rest by the
+// pass 1 on contiguous data: whole tiles without predicates, the ragged rest by the
 // last block.
 template <typename T, int OP, typename RES>
 __global__ void __launch_bounds__(kThreads) reduce_vec_kernel(int64_t nvec, int64_t nfull, int tail,
@@ -249,16 +246,14 @@ __global__ void __launch_bounds__(kThreads) reduce_vec_kernel(int64_t nvec, int6
     constexpr bool TWO = OP == OP_DOT || OP == OP_DSDOT;
     constexpr int U = TWO ? kUnroll : 2 * kUnroll;      // 8 loads in flight per thread either way
     typedef typename VecOf<T, VEC>::type V;
-    const V* xv = reinterpret_cast<const V*>(x);
-    const V* yv = reinterpret_cast<const V*>(y);
     Acc<T, OP> acc[VEC];
     for (int64_t t = blockIdx.x; t < nfull; t += gridDim.x) {
         const int64_t base = t * (kThreads * U) + threadIdx.x;
         V a[U], b[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            a[u] = ld_stream(xv + base + u * kThreads);
-            b[u] = TWO ? ld_stream(yv + base + u * kThreads) : V(T(0));
+            a[u] = ld_matrix<T, VEC>(x + (base + u * kThreads) * VEC);
+            b[u] = TWO ? ld_matrix<T, VEC>(y + (base + u * kThreads) * VEC) : V(T(0));
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -268,8 +263,8 @@ __global__ void __launch_bounds__(kThreads) reduce_vec_kernel(int64_t nvec, int6
     }
     if (blockIdx.x == gridDim.x - 1) {
         for (int64_t i = nfull * (kThreads * U) + threadIdx.x; i < nvec; i += kThreads) {
-            const V a = xv[i];
-            const V b = TWO ? yv[i] : V(T(0));
+            const V a = ld_matrix<T, VEC>(x + i * VEC);
+            const V b = TWO ? ld_matrix<T, VEC>(y + i * VEC) : V(T(0));
 #pragma unroll
             for (int k = 0; k < VEC; ++k) acc[k].add(a[k], b[k]);
         }
@@ -281,7 +276,7 @@ __global__ void __launch_bounds__(kThreads) reduce_vec_kernel(int64_t nvec, int6
     block_partial<T, OP, RES>(acc, VEC, partials, result);
 }
 
-// pass 1 with arbitrary increments (or unaligned data)
+// pass 1 with arbitrary increments
 template <typename T, int OP, typename RES>
 __global__ void __launch_bounds__(kThreads) reduce_strided_kernel(int64_t n, int64_t nfull, const T* __restrict__ x, int64_t incx,
                                                                   const T* __restrict__ y, int64_t incy,
@@ -373,7 +368,7 @@ int axpy(mxb_handle_t h, int64_t n, T alpha, const T* x, int64_t incx, T* y, int
     if (incy == 0) return -6;
     constexpr int VEC = Full<T>::vec;
     const int64_t bpc = option(h, MXB_OPT_L1_BLOCKS_PER_CU);
-    if (incx == 1 && incy == 1 && aligned16(x) && aligned16(y)) {
+    if (incx == 1 && incy == 1) {   // any base address: the vector accesses need element alignment only
         const int64_t nvec = n / VEC;
         const int64_t nfull = nvec / (kThreads * kUnroll);
         const int64_t grid = nfull < 1 ? 1 : (nfull < kCUs * bpc ? nfull : kCUs * bpc);
@@ -397,7 +392,7 @@ int scal(mxb_handle_t h, int64_t n, T alpha, T* x, int64_t incx)
     if (!x) return -3;
     constexpr int VEC = Full<T>::vec;
     const int64_t bpc = option(h, MXB_OPT_L1_BLOCKS_PER_CU);
-    if (incx == 1 && aligned16(x)) {
+    if (incx == 1) {   // any base address: the vector accesses need element alignment only
         const int64_t nvec = n / VEC;
         const int64_t nfull = nvec / (kThreads * kScalUnroll);
         const int64_t grid = nfull < 1 ? 1 : (nfull < kCUs * bpc ? nfull : kCUs * bpc);
@@ -427,7 +422,7 @@ int reduce(mxb_handle_t h, int64_t n, const T* x, int64_t incx, const T* y, int6
     if (!h->ws || h->ws_bytes < (size_t)max_blocks * K * sizeof(double)) return MXB_ERR_WORKSPACE;
     double* partials = static_cast<double*>(h->ws);
     int64_t grid;
-    const bool contiguous = incx == 1 && aligned16(x) && (!TWO || (incy == 1 && aligned16(y)));
+    const bool contiguous = incx == 1 && (!TWO || incy == 1);   // any base address: element alignment suffices
     if (contiguous) {
         const int64_t nvec = n / VEC;
         const int64_t nfull = nvec / (kThreads * (TWO ? kUnroll : 2 * kUnroll));

@@ -40,16 +40,14 @@ __global__ void __launch_bounds__(kThreads) pair_vec_kernel(int64_t nvec, int64_
     constexpr int VEC = Full<T>::vec;
     constexpr int U = kUnroll;
     typedef typename VecOf<T, VEC>::type V;
-    V* xv = reinterpret_cast<V*>(x);
-    V* yv = reinterpret_cast<V*>(y);
     for (int64_t t = blockIdx.x; t < nfull; t += gridDim.x) {
         int64_t base, step;
         stream_tile<U>(t, n2d, base, step);
         V a[U], b[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) a[u] = ld_stream(xv + base + u * step);
+        for (int u = 0; u < U; ++u) a[u] = ld_matrix<T, VEC>(x + (base + u * step) * VEC);
 #pragma unroll
-        for (int u = 0; u < U; ++u) b[u] = Op::kReadY ? ld_stream(yv + base + u * step) : V(T(0));
+        for (int u = 0; u < U; ++u) b[u] = Op::kReadY ? ld_matrix<T, VEC>(y + (base + u * step) * VEC) : V(T(0));
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -60,8 +58,8 @@ __global__ void __launch_bounds__(kThreads) pair_vec_kernel(int64_t nvec, int64_
                 a[u][k] = p;
                 b[u][k] = q;
             }
-            if (Op::kWriteX) st_stream(xv + base + u * step, a[u]);
-            st_stream(yv + base + u * step, b[u]);
+            if (Op::kWriteX) st_matrix<T, VEC>(x + (base + u * step) * VEC, a[u]);
+            st_matrix<T, VEC>(y + (base + u * step) * VEC, b[u]);
         }
     }
     if (blockIdx.x != gridDim.x - 1) return;
@@ -117,7 +115,7 @@ int pair_op(mxb_handle_t h, int64_t n, T* x, int64_t incx, T* y, int64_t incy, c
     if (incy == 0) return -5;
     constexpr int VEC = Full<T>::vec;
     const int64_t cap = kCUs * option(h, MXB_OPT_L1_BLOCKS_PER_CU);
-    if (incx == 1 && incy == 1 && aligned16(x) && aligned16(y)) {
+    if (incx == 1 && incy == 1) {   // any base address: the vector accesses need element alignment only
         const int64_t nvec = n / VEC, nfull = nvec / (kThreads * kUnroll);
         const int64_t grid = nfull < 1 ? 1 : (nfull < cap ? nfull : cap);
         hipLaunchKernelGGL((pair_vec_kernel<T, Op>), dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, nfull,

@@ -51,16 +51,18 @@ def test_axpy_scal(blas, ctx, dt, incx, incy):
 
 @pytest.mark.parametrize("dt", DT)
 def test_axpy_scal_misaligned_and_noop(blas, ctx, dt):
-    n = 5001
-    x, y = synth.uniform(2, 1, n + 3, dt), synth.uniform(2, 2, n + 3, dt)
-    for xo, yo in ((1, 0), (0, 1), (3, 1)):
-        ref = y.copy(); O.axpy(n, dt(0.5), x[xo:], 1, ref[yo:], 1)
-        got = run_axpy(blas, ctx, dt, n, 0.5, x, 1, y, 1, xo, yo)
-        check_close(got[yo:yo + n], ref[yo:yo + n], np.abs(0.5 * x[xo:xo + n]) + np.abs(y[yo:yo + n]), 1, "axpy misaligned")
-        assert bits_equal(got[:yo], y[:yo]) and bits_equal(got[yo + n:], y[yo + n:])
-        dx = to_dev(x); ref = x.copy(); O.scal(n, dt(-3), ref[xo:], 1)
-        assert blas.routine(prefix_of(dt), "scal")(ctx.h, n, -3.0, dx[xo:], 1) == 0
-        assert bits_equal(to_host(dx), ref)
+    # bases that are a multiple of the element size only: the ragged rest alone (n = 5001), then
+    # whole tiles with their 64 KiB-pitch part
+    for n in ((1 << 20) + 7, 5001):
+        x, y = synth.uniform(2, 1, n + 3, dt), synth.uniform(2, 2, n + 3, dt)
+        for xo, yo in ((1, 0), (0, 1), (3, 1)):
+            ref = y.copy(); O.axpy(n, dt(0.5), x[xo:], 1, ref[yo:], 1)
+            got = run_axpy(blas, ctx, dt, n, 0.5, x, 1, y, 1, xo, yo)
+            check_close(got[yo:yo + n], ref[yo:yo + n], np.abs(0.5 * x[xo:xo + n]) + np.abs(y[yo:yo + n]), 1, "axpy misaligned")
+            assert bits_equal(got[:yo], y[:yo]) and bits_equal(got[yo + n:], y[yo + n:])
+            dx = to_dev(x); ref = x.copy(); O.scal(n, dt(-3), ref[xo:], 1)
+            assert blas.routine(prefix_of(dt), "scal")(ctx.h, n, -3.0, dx[xo:], 1) == 0
+            assert bits_equal(to_host(dx), ref)
     # alpha = 0 / n = 0 / incx <= 0: nothing is touched (x may hold NaN)
     got = run_axpy(blas, ctx, dt, n, 0.0, np.full(n, np.nan, dt), 1, y, 1)
     assert bits_equal(got, y)
@@ -126,12 +128,14 @@ def test_reductions_edge_cases(blas, ctx, dt):
         assert run_reduce(blas, ctx, dt, name, 0, x, 1) == 0
         assert run_reduce(blas, ctx, dt, name, 10, x, 0) == 0
     assert run_reduce(blas, ctx, dt, "dot", 0, x, 1, x, 1) == 0
-    for xo, yo in ((1, 0), (0, 3), (1, 1)):          # misaligned bases
-        n = 990
-        ref, D = O.dot(n, x[xo:], 1, x[yo:], 1, want_D=True)
-        check_close([run_reduce(blas, ctx, dt, "dot", n, x, 1, x, 1, xo, yo)], [ref], [D], n, "dot misaligned")
-        ref, D = O.asum(n, x[xo:], 1, want_D=True)
-        check_close([run_reduce(blas, ctx, dt, "asum", n, x, 1, xoff=xo)], [ref], [D], n, "asum misaligned")
+    for n, v in ((990, x), (300001, synth.uniform(5, 2, 300005, dt))):     # misaligned bases: the rest alone, whole tiles
+        for xo, yo in ((1, 0), (0, 3), (1, 1)):
+            ref, D = O.dot(n, v[xo:], 1, v[yo:], 1, want_D=True)
+            check_close([run_reduce(blas, ctx, dt, "dot", n, v, 1, v, 1, xo, yo)], [ref], [D], n, "dot misaligned")
+            ref, D = O.asum(n, v[xo:], 1, want_D=True)
+            check_close([run_reduce(blas, ctx, dt, "asum", n, v, 1, xoff=xo)], [ref], [D], n, "asum misaligned")
+            ref, D = O.nrm2(n, v[xo:], 1, want_D=True)
+            check_close([run_reduce(blas, ctx, dt, "nrm2", n, v, 1, xoff=xo)], [ref], [D], n, "nrm2 misaligned")
     # nrm2 range safety
     big = np.full(64, np.finfo(dt).max / 16, dt)
     assert run_reduce(blas, ctx, dt, "nrm2", 64, big, 1) == O.nrm2(64, big, 1) == np.finfo(dt).max / 2
@@ -229,7 +233,7 @@ def test_copy_swap_rot_rotm(blas, ctx, dt, incx, incy):
 @pytest.mark.parametrize("dt", DT)
 def test_rot_rotm_integers_bit_exact_and_misaligned(blas, ctx, dt):
     p = prefix_of(dt)
-    n = (1 << 16) + 11
+    n = (1 << 18) + 11          # whole tiles with their 64 KiB-pitch part and a ragged rest
     x, y = synth.small_ints(31, 1, n + 3, -9, 9, dt), synth.small_ints(31, 2, n + 3, -9, 9, dt)
     for xo, yo in ((0, 0), (1, 0), (3, 1)):
         rx, ry = x.copy(), y.copy(); O.rot(n, rx[xo:], 1, ry[yo:], 1, dt(3), dt(4))
@@ -245,6 +249,10 @@ def test_rot_rotm_integers_bit_exact_and_misaligned(blas, ctx, dt):
         dx, dy = to_dev(x), to_dev(y)
         assert blas.routine(p, "swap")(ctx.h, n, dx[xo:], 1, dy[yo:], 1) == 0
         assert bits_equal(to_host(dx), rx) and bits_equal(to_host(dy), ry)
+        ry = y.copy(); O.copy(n, x[xo:], 1, ry[yo:], 1)
+        dx, dy = to_dev(x), to_dev(y)
+        assert blas.routine(p, "copy")(ctx.h, n, dx[xo:], 1, dy[yo:], 1) == 0
+        assert bits_equal(to_host(dx), x) and bits_equal(to_host(dy), ry)
     dx = to_dev(x)
     assert blas.routine(p, "copy")(ctx.h, 0, dx, 1, dx, 1) == 0
 
