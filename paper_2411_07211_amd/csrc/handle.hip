@@ -133,7 +133,7 @@ size_t mxb_workspace_bytes(int routine, int elem_size, int64_t m, int64_t n)
     switch (routine) {
         case MXB_AXPY: case MXB_SCAL: case MXB_GER: return 0;
         case MXB_DOT: case MXB_ASUM: case MXB_NRM2:
-            return (size_t)option_default(MXB_OPT_REDUCE_BLOCKS) * 3 * sizeof(double);
+            return (size_t)option_default(MXB_OPT_REDUCE_BLOCKS) * kStridedBlocksFactor * 3 * sizeof(double);
         case MXB_GEMV: {
             size_t a = colacc_bound(m, n), b = colacc_bound(n, m);
             a = a > b ? a : b;
@@ -182,8 +182,7 @@ int mxb_probe_read(mxb_handle_t h, size_t bytes, const void* src)
     if (bytes == 0) return MXB_OK;
     if (!src) return -2;
     const int64_t nvec = (int64_t)(bytes / 16), ntiles = ceil_div(nvec, kThreads * kUnroll);
-    const int64_t cap = option(h, MXB_OPT_REDUCE_BLOCKS);
-    const int64_t grid = ntiles < cap ? ntiles : cap;
+    const int64_t grid = ntiles < kProbeReadBlocks ? ntiles : kProbeReadBlocks;
     if (!h->ws || h->ws_bytes < (size_t)grid * sizeof(double)) return MXB_ERR_WORKSPACE;
     hipLaunchKernelGGL(probe_read_kernel, dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, ntiles,
                        static_cast<const f4*>(src), static_cast<double*>(h->ws));

@@ -418,11 +418,13 @@ int reduce(mxb_handle_t h, int64_t n, const T* x, int64_t incx, const T* y, int6
         hipLaunchKernelGGL(store_scalar_kernel<RES>, dim3(1), dim3(1), 0, h->stream, result, RES(0));
         return launch_status();
     }
-    const int64_t max_blocks = option(h, MXB_OPT_REDUCE_BLOCKS);
+    const bool contiguous = incx == 1 && (!TWO || incy == 1);   // any base address: element alignment suffices
+    // One block per compute unit with 16 vector loads in flight per lane reads fastest; a single
+    // strided operand, one element per lane and load, wants eight times as many blocks (measured).
+    const int64_t max_blocks = option(h, MXB_OPT_REDUCE_BLOCKS) * ((contiguous || TWO) ? 1 : kStridedBlocksFactor);
     if (!h->ws || h->ws_bytes < (size_t)max_blocks * K * sizeof(double)) return MXB_ERR_WORKSPACE;
     double* partials = static_cast<double*>(h->ws);
     int64_t grid;
-    const bool contiguous = incx == 1 && (!TWO || incy == 1);   // any base address: element alignment suffices
     if (contiguous) {
         const int64_t nvec = n / VEC;
         const int64_t nfull = nvec / (kThreads * (TWO ? kUnroll : 2 * kUnroll));

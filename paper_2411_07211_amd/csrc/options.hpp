@@ -8,7 +8,7 @@ inline int64_t option_default(int o)
 {
     switch (o) {
         case MXB_OPT_L1_BLOCKS_PER_CU: return 1 << 20;   // in effect one 16 KiB tile per block: read+write streams run best unthrottled
-        case MXB_OPT_REDUCE_BLOCKS: return 2048;
+        case MXB_OPT_REDUCE_BLOCKS: return 256;
         case MXB_OPT_ROWDOT_XCHUNK: return 4096;       // elements; capped to 64 KiB of LDS by the launcher
         case MXB_OPT_ROWDOT_BLOCKS_PER_CU: return 2;
         case MXB_OPT_COLACC_TARGET_BLOCKS: return 192;
@@ -26,6 +26,8 @@ inline int64_t option(mxb_handle_t h, int o) { return h->opt[o] > 0 ? h->opt[o] 
 // Blocks the narrow column-accumulate shape aims for: two per compute unit, or twice the
 // caller's MXB_OPT_COLACC_TARGET_BLOCKS when that option is set.
 constexpr int64_t kColaccNarrowBlocks = 2 * kCUs;
+constexpr int64_t kStridedBlocksFactor = 8;   // first-pass blocks of a strided one-operand reduction per MXB_OPT_REDUCE_BLOCKS
+constexpr int64_t kProbeReadBlocks = 2048;    // the read probe keeps 8 loads in flight per lane and needs many blocks
 inline int64_t colacc_narrow_target(mxb_handle_t h)
 {
     return h->opt[MXB_OPT_COLACC_TARGET_BLOCKS] > 0 ? 2 * h->opt[MXB_OPT_COLACC_TARGET_BLOCKS] : kColaccNarrowBlocks;

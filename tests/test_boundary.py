@@ -39,9 +39,9 @@ def test_handle_lifecycle_and_options(B):
     assert B.mxb_set_stream(h, None) == 0
     assert B.mxb_set_workspace(h, None, 0) == 0
     assert B.mxb_set_workspace(h, 0x1001, 16) == -1          # not 256-byte aligned
-    assert B.mxb_get_option(h, B.OPT_REDUCE_BLOCKS) == 2048
+    assert B.mxb_get_option(h, B.OPT_REDUCE_BLOCKS) == 256
     assert B.mxb_set_option(h, B.OPT_REDUCE_BLOCKS, 7) == 0 and B.mxb_get_option(h, B.OPT_REDUCE_BLOCKS) == 7
-    assert B.mxb_set_option(h, B.OPT_REDUCE_BLOCKS, 0) == 0 and B.mxb_get_option(h, B.OPT_REDUCE_BLOCKS) == 2048
+    assert B.mxb_set_option(h, B.OPT_REDUCE_BLOCKS, 0) == 0 and B.mxb_get_option(h, B.OPT_REDUCE_BLOCKS) == 256
     assert B.mxb_set_option(h, 99, 1) == -1
     assert B.mxb_destroy(h) == 0
     assert B.mxb_saxpy(None, 1, 1.0, 16, 1, 16, 1) == B.ERR_HANDLE
