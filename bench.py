@@ -297,6 +297,12 @@ def sweep(B, ctx, torch):
         rec("sgemv_t", t, full, lambda: B.mxb_sgemv(h, B.ROW_MAJOR, B.TRANS, M, 40, 1.0, A, 40, xv, 1, 0.0, yv, 1))
         rec("sger", t, 2 * full, lambda: B.mxb_sger(h, B.ROW_MAJOR, M, 40, 1e-6, xv, 1, yv, 1, A, 40))
 
+    # batches of small matrices in one call: 1 GiB of matrices per case (half for 32 x 32), both orientations
+    for n, batch in ((32, 1 << 17), (64, 1 << 16), (128, 1 << 14), (256, 1 << 12), (512, 1 << 10), (1024, 1 << 8), (4096, 1 << 4)):
+        for tn, tr in (("n", B.NO_TRANS), ("t", B.TRANS)):
+            rec(f"sgemv_{tn}_b", f"{n}x{n} x{batch}", 4 * n * n * batch,
+                lambda: B.mxb_sgemv_batched(h, B.ROW_MAJOR, tr, n, n, 1.0, A, n, n * n, xv, 1, n, 0.0, yv, 1, n, batch))
+
     def bucket(nb):
         return "small (< 4 MiB)" if nb < (4 << 20) else "medium (< 256 MiB)" if nb < (256 << 20) else "large"
 
