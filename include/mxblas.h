@@ -91,7 +91,8 @@ typedef enum {
     MXB_OPT_GER_ROWS_PER_BLOCK = 7,
     MXB_OPT_SYMV_TILE_VECTORS = 8,  /* triangle sweep: 128-bit vectors per lane and row (1, 2 or 4); tile = 256 lanes x this */
     MXB_OPT_TRI_DIAG_WEIGHT = 9,    /* triangle sweep: cost of a row that crosses the diagonal, in quarters of a row that does not (1..8) */
-    MXB_OPT_COUNT = 10
+    MXB_OPT_SYMV_SMALL_MAX = 10,    /* symv: largest n that takes the single-kernel path (every element read twice, no workspace) */
+    MXB_OPT_COUNT = 11
 } mxb_option_t;
 int mxb_set_option(mxb_handle_t h, int option, int64_t value);
 int64_t mxb_get_option(mxb_handle_t h, int option);

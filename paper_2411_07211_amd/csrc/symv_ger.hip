@@ -216,6 +216,114 @@ __global__ void __launch_bounds__(kThreads) syr_kernel(const SyrArgs<T> p)
 }
 
 // ---------------------------------------------------------------------------------------------
+// symv of a small matrix in one kernel (no workspace, no second pass): a call on a few thousand
+// unknowns is bound by launches and latency, not by bytes, so every stored element is read twice
+// instead of once.  Block b owns the 32 unknowns I = [32b, 32b + 32) and forms both halves of
+// their results itself:
+//   row part     sum over the stored part of rows I (columns <= i if lower, >= i if upper): each
+//                wavefront takes 8 rows, its lanes stride across the columns with 128-bit loads;
+//   column part  sum over the stored part of columns I in the other rows (rows > j if lower,
+//                < j if upper), i.e. the mirrored elements: 32 columns = CL lanes, 64 / CL rows
+//                side by side per wavefront load, column sums in registers, folded through LDS.
+// Every block reads about 32 n elements, whatever b is.  The order of all sums is fixed.
+constexpr int kSmallTile = 32;
+
+template <typename T, int VEC, bool UPPER>
+__global__ void __launch_bounds__(kThreads) symv_small_kernel(int n, T alpha, const T* __restrict__ A, int64_t lda,
+                                                              const T* __restrict__ x, int64_t incx, T beta, T* __restrict__ y,
+                                                              int64_t incy)
+{
+    typedef typename VecOf<T, VEC>::type V;
+    constexpr int NW = kThreads / kWave, RPW = kSmallTile / NW;   // wavefronts; rows of the row part per wavefront
+    constexpr int CL = kSmallTile / VEC, RL = kWave / CL;         // column part: lanes per row, rows per wavefront load
+    constexpr int UB = 4;                                         // column part: loads in flight per lane
+    __shared__ T ya[kSmallTile];
+    __shared__ T red[NW][kWave][VEC];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int i0 = (int)blockIdx.x * kSmallTile, i1 = min(n, i0 + kSmallTile);
+
+    // ---- row part: rows i0 + wave*RPW + u, columns [ca, cb)
+    {
+        const int ca = UPPER ? i0 / (kWave * VEC) * (kWave * VEC) : 0, cb = UPPER ? n : i1;
+        T acc[RPW];
+#pragma unroll
+        for (int u = 0; u < RPW; ++u) acc[u] = T(0);
+        for (int c0 = ca; c0 < cb; c0 += kWave * VEC) {
+            const int c = c0 + lane * VEC;                 // my columns: [c, c + VEC)
+            const int cl = min(c, n - VEC);                // a vector past the end is moved back into the row
+            V a[RPW];
+            T xv[VEC];
+#pragma unroll
+            for (int u = 0; u < RPW; ++u) a[u] = ld_matrix<T, VEC>(A + (int64_t)min(i0 + wave * RPW + u, n - 1) * lda + cl);
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) xv[k] = x[(int64_t)(cl + k) * incx];
+#pragma unroll
+            for (int u = 0; u < RPW; ++u) {
+                const int i = i0 + wave * RPW + u;
+#pragma unroll
+                for (int k = 0; k < VEC; ++k) {
+                    const int j = cl + k;
+                    const bool use = j >= c && j < cb && (UPPER ? j >= i : j <= i);
+                    acc[u] = use ? fmad(a[u][k], xv[k], acc[u]) : acc[u];
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < RPW; ++u) {
+            const T s = wave_sum(acc[u]);
+            if (lane == 0) ya[wave * RPW + u] = s;
+        }
+    }
+
+    // ---- column part: columns i0 + [0, 32), rows [ra, rb) in groups of RL, the groups dealt to the wavefronts
+    {
+        const int ra = UPPER ? 0 : i0, rb = UPPER ? i1 : n;
+        const int cq = lane % CL, rl = lane / CL;
+        const int c = i0 + cq * VEC;                        // my columns: [c, c + VEC)
+        const int cl = max(min(c, n - VEC), 0);
+        T acc[VEC];
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) acc[k] = T(0);
+        for (int r0 = ra + wave * RL; r0 < rb; r0 += NW * RL * UB) {
+            V a[UB];
+            T xr[UB];
+#pragma unroll
+            for (int u = 0; u < UB; ++u) {
+                const int r = min(r0 + u * NW * RL + rl, n - 1);
+                a[u] = ld_matrix<T, VEC>(A + (int64_t)r * lda + cl);
+                xr[u] = x[(int64_t)r * incx];
+            }
+#pragma unroll
+            for (int u = 0; u < UB; ++u) {
+                const int r = r0 + u * NW * RL + rl;
+#pragma unroll
+                for (int k = 0; k < VEC; ++k) {
+                    const int j = cl + k;
+                    const bool use = j >= c && j < i1 && r < rb && (UPPER ? r < j : r > j);
+                    acc[k] = use ? fmad(a[u][k], xr[u], acc[k]) : acc[k];
+                }
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) red[wave][lane][k] = acc[k];
+    }
+    __syncthreads();
+    const int t = threadIdx.x;
+    if (t < kSmallTile && i0 + t < n) {
+        // column i0 + t sits in element k of the vector of lanes cq + CL*rl (rl = 0..RL-1)
+        const int cq = t / VEC, cl = max(min(i0 + cq * VEC, n - VEC), 0), k = i0 + t - cl;
+        T s = ya[t];
+        for (int w = 0; w < NW; ++w)
+            for (int rl = 0; rl < RL; ++rl) s += red[w][cq + CL * rl][k];
+        T* yp = y + (int64_t)(i0 + t) * incy;
+        T v = alpha * s;
+        if (beta != T(0)) v = fmad(beta, *yp, v);
+        *yp = v;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // launchers
 
 inline bool layout_ok(int v) { return v == MXB_ROW_MAJOR || v == MXB_COL_MAJOR; }
@@ -244,6 +352,13 @@ int symv(mxb_handle_t h, int layout, int uplo, int64_t n, T alpha, const T* A, i
     // the column-major upper triangle occupies the bytes of the row-major lower triangle
     const bool upper = (uplo == MXB_UPPER) == (layout == MXB_ROW_MAJOR);
     const T* x0 = vec_base(x, n, incx);
+    constexpr int FV = Full<T>::vec;
+    if (n >= FV && n <= option(h, MXB_OPT_SYMV_SMALL_MAX)) {
+        const dim3 grid((unsigned)ceil_div(n, (int64_t)kSmallTile));
+        if (upper) hipLaunchKernelGGL((symv_small_kernel<T, FV, true>), grid, dim3(kThreads), 0, h->stream, (int)n, alpha, A, lda, x0, incx, beta, y0, incy);
+        else hipLaunchKernelGGL((symv_small_kernel<T, FV, false>), grid, dim3(kThreads), 0, h->stream, (int)n, alpha, A, lda, x0, incx, beta, y0, incy);
+        return launch_status();
+    }
     return trisweep_symv<T>(h, upper, n, alpha, A, lda, x0, incx, beta, y0, incy);
 }
 

@@ -126,7 +126,7 @@ def test_gemv_deterministic_and_geometry_invariant(blas, ctx, dt):
             for opts in ({}, {}, {blas.OPT_ROWDOT_XCHUNK: 256, blas.OPT_COLACC_TARGET_BLOCKS: 64},
                          {blas.OPT_ROWDOT_XCHUNK: 1024, blas.OPT_ROWDOT_BLOCKS_PER_CU: 1, blas.OPT_COLACC_TARGET_BLOCKS: 4096,
                           blas.OPT_COLACC_MIN_ROWS: 8}):
-                for o in range(10):
+                for o in range(11):
                     ctx.set_option(o, 0)
                 for o, v in opts.items():
                     ctx.set_option(o, v)
@@ -136,7 +136,7 @@ def test_gemv_deterministic_and_geometry_invariant(blas, ctx, dt):
                 check_close(outs[-1], ref, D, lenx, f"gemv trans={trans} opts={opts}")
             assert outs[0].tobytes() == outs[1].tobytes(), "same launch geometry must give the same bits"
     finally:
-        for o in range(10):
+        for o in range(11):
             ctx.set_option(o, 0)
 
 
@@ -330,8 +330,17 @@ def symv_case(blas, ctx, dt, layout, uplo, n, alpha, beta, pad, incx, incy, ints
 @pytest.mark.parametrize("layout", [O.ROW_MAJOR, O.COL_MAJOR])
 @pytest.mark.parametrize("uplo", [O.UPPER, O.LOWER])
 def test_symv(blas, ctx, dt, layout, uplo):
-    for n in (1, 2, 3, 5, 17, 64, 65, 130, 257, 1000, 1024, 2310):
-        symv_case(blas, ctx, dt, layout, uplo, n, 1.5, 0.5, 0 if n % 2 else 4, 1, 1)
+    # small n twice: the single-kernel path, then (switched off) the triangle sweep
+    for small_max in (0, 1):
+        ctx.set_option(blas.OPT_SYMV_SMALL_MAX, small_max)
+        try:
+            for n in (1, 2, 3, 4, 5, 17, 31, 32, 33, 64, 65, 130, 257, 1000, 1024, 2047, 2048, 2310):
+                symv_case(blas, ctx, dt, layout, uplo, n, 1.5, 0.5, 0 if n % 2 else 4, 1, 1)
+            symv_case(blas, ctx, dt, layout, uplo, 515, 1.5, 0.5, 1, 2, -3)
+            symv_case(blas, ctx, dt, layout, uplo, 1536, 3, -2, 0, 1, 1, ints=True)
+            symv_case(blas, ctx, dt, layout, uplo, 700, 1, 0, 0, 1, 1)
+        finally:
+            ctx.set_option(blas.OPT_SYMV_SMALL_MAX, 0)
     for alpha, beta in [(1, 0), (1, 1), (0, 0.5), (0, 0), (-2, -1)]:
         symv_case(blas, ctx, dt, layout, uplo, 700, alpha, beta, 0, 1, 1)
     symv_case(blas, ctx, dt, layout, uplo, 515, 1.5, 0.5, 1, 2, -3)
