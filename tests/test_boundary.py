@@ -163,7 +163,8 @@ def test_argument_errors_name_the_argument(B):
             assert s(h, B.ROW_MAJOR, B.LOWER, 4, 1.0, P, 4, P, 1, 0.0, P, 0) == -11
             assert s(h, B.ROW_MAJOR, B.LOWER, 0, 1.0, None, 1, None, 1, 0.0, None, 1) == 0
             assert s(h, B.ROW_MAJOR, B.LOWER, 4, 0.0, None, 4, None, 1, 1.0, None, 1) == 0
-            assert s(h, B.ROW_MAJOR, B.LOWER, 4, 1.0, P, 4, P, 1, 0.0, P, 1) == B.ERR_WORKSPACE
+            # beyond the single-kernel size symv needs partials: no workspace -> error, no launch
+            assert s(h, B.ROW_MAJOR, B.LOWER, 4096, 1.0, P, 4096, P, 1, 0.0, P, 1) == B.ERR_WORKSPACE
             r = f("ger")
             assert r(h, 0, 4, 4, 1.0, P, 1, P, 1, P, 4) == -1
             assert r(h, B.ROW_MAJOR, -1, 4, 1.0, P, 1, P, 1, P, 4) == -2
