@@ -484,6 +484,23 @@ def main():
                      "us_med": round(ts[len(ts) // 2] * 1e3, 2), "GBps": round(nb / (avg * 1e-3) / 1e9, 1),
                      "frac_of_8TBps": round(nb / (avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
 
+    # what this machine reaches with the plainest kernels (a read-only and a copy kernel over 1 GiB), beside the 8 TB/s peak
+    ceiling = {}
+    if not args.only:
+        for name, fam, fn, nb, pre in suite.extra:
+            if fam != "probe":
+                continue
+            pe = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(10)]
+            for w in range(3):
+                fn(w)
+            for i, (a, b) in enumerate(pe):
+                a.record(); st = fn(i); b.record()
+                if st != 0:
+                    raise RuntimeError(f"{name} returned status {st}")
+            torch.cuda.synchronize()
+            avg = sum(a.elapsed_time(b) for a, b in pe) / len(pe)
+            ceiling[name + "_GBps"] = round(nb / (avg * 1e-3) / 1e9, 1)
+
     NS = 16384 // (args.scale if args.scale <= 16 else 16)
     head = f"sgemv_n_{NS}_b0"
     traffic = measured_traffic()
@@ -495,6 +512,8 @@ def main():
         roofline = {"bound": "hbm", "kernel": "rowdot_kernel<float,4,64,2,4,general> (sgemv N 16384x16384, beta=0)",
                     "achieved": p["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(p["GBps"] / HBM_PEAK_GBS, 4),
                     "traffic": traffic.get(head), "algorithmic_bytes_per_launch": p["bytes"], "avg_launch_us": p["us_avg"]}
+        if "probe_read_GBps" in ceiling:
+            roofline["frac_of_measured_read_ceiling"] = round(p["GBps"] / ceiling["probe_read_GBps"], 4)
 
     out = {
         "metric": "achieved HBM GB/s over one pass of the BLAS level-1/level-2 suite (algorithmic bytes / time)",
@@ -507,6 +526,7 @@ def main():
                                + ("" if not args.only else f" [ONLY {args.only}]"),
                    "step_algorithmic_GiB": round(step_bytes / GiB, 3)},
         "roofline": roofline,
+        "stream_ceiling": ceiling or None,
         "kernels": per,
     }
     if not args.no_cpu_baseline:
