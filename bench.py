@@ -515,8 +515,17 @@ def main():
         if "probe_read_GBps" in ceiling:
             roofline["frac_of_measured_read_ceiling"] = round(p["GBps"] / ceiling["probe_read_GBps"], 4)
 
+    # the figures the headline metric names, one by one: gemv N/T at 16384^2 against the peak, level-1 GB/s
+    headline = {}
+    for name in (f"sgemv_n_{NS}_b0", f"sgemv_t_{NS}_b0", f"dgemv_n_{NS}", f"dgemv_t_{NS}", "saxpy", "daxpy", "sscal", "sdot", "ddot",
+                 "sasum", "snrm2", "saxpy_strided", "daxpy_strided", "sscal_strided", "sdot_strided", "ddot_strided", "sasum_strided",
+                 "snrm2_strided"):
+        if name in per:
+            headline[name] = {"GBps": per[name]["GBps"], "frac_of_8TBps": per[name]["frac_of_8TBps"]}
+
     out = {
-        "metric": "achieved HBM GB/s over one pass of the BLAS level-1/level-2 suite (algorithmic bytes / time)",
+        "metric": "achieved HBM GB/s (% of peak) for sgemv/dgemv N,T at 16384^2; level-1 GB/s: algorithmic bytes / time over "
+                  "one pass of the whole level-1/level-2 suite (`headline` lists the named figures one by one)",
         "value": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1), "unit": "GB/s",
         "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32+f64", "data": "synthetic",
@@ -526,6 +535,7 @@ def main():
                                + ("" if not args.only else f" [ONLY {args.only}]"),
                    "step_algorithmic_GiB": round(step_bytes / GiB, 3)},
         "roofline": roofline,
+        "headline": headline,
         "stream_ceiling": ceiling or None,
         "kernels": per,
     }
