@@ -1,0 +1,114 @@
+// Batches of matrices with very short rows, not transposed (see tiny.hpp).  The row-dot kernel
+// gives every problem a block tile of its own and stages x in LDS per tile, which leaves most of a
+// block idle when a matrix has a few dozen rows.  Here the rows of all problems form one long
+// list: a group of LPR lanes (4, 8 or 16: one DPP quad, half row or row) takes one row with one
+// 128-bit load per lane, 64 / LPR rows side by side per wavefront load and U such loads in
+// flight; the matching vector of the row's own x comes straight from memory (every x is re-read
+// once per row, from cache), the group folds its 4-term dots with DPP and one lane writes y.
+#include "tiny.hpp"
+
+namespace mxb {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / kWave;
+constexpr int kSlots = 8;                     // rows in flight per lane group
+
+template <typename T>
+struct TinyArgs {
+    int M, N;            // rows and columns of one problem
+    uint32_t total;      // rows of all problems
+    const T* A;
+    int64_t lda, sA;
+    const T* x;
+    int64_t incx, sx;
+    T* y;
+    int64_t incy, sy;
+    T alpha, beta;
+};
+
+// Sum over a group of LPR adjacent lanes; every lane of the group receives it.
+template <int LPR, typename T>
+__device__ __forceinline__ T group_sum(T v)
+{
+    v += dpp_mov<kDppXor1>(v);
+    v += dpp_mov<kDppXor2>(v);
+    if (LPR >= 8) v += dpp_mov<kDppHalfMirror>(v);
+    if (LPR >= 16) v += dpp_mov<kDppMirror>(v);
+    return v;
+}
+
+template <typename T, int VEC, int LPR>
+__global__ void __launch_bounds__(kThreads) tiny_gemv_n_kernel(const TinyArgs<T> p)
+{
+    typedef typename VecOf<T, VEC>::type V;
+    constexpr int G = kWave / LPR;            // rows per wavefront load
+    const int lane = threadIdx.x & (kWave - 1);
+    const int g = lane / LPR, l = lane % LPR;
+    // my columns [c, c + VEC); a vector past the end of the row is moved back to end at N, and only
+    // the elements from column c on are mine (none if the row ends before c)
+    const int c = l * VEC, cl = min(c, p.N - VEC);
+    const uint32_t rows_per_tile = kSlots * G;
+    const uint32_t ntiles = (p.total + rows_per_tile - 1) / rows_per_tile;
+    const uint32_t wave0 = blockIdx.x * kWaves + (threadIdx.x >> 6), nwaves = gridDim.x * kWaves;
+    for (uint32_t t = wave0; t < ntiles; t += nwaves) {
+        V a[kSlots], xv[kSlots];
+        uint32_t b[kSlots], i[kSlots];
+#pragma unroll
+        for (int u = 0; u < kSlots; ++u) {
+            const uint32_t row = min(t * rows_per_tile + u * G + g, p.total - 1);     // clamp: loads stay in bounds
+            b[u] = row / (uint32_t)p.M;
+            i[u] = row - b[u] * (uint32_t)p.M;
+            a[u] = ld_matrix<T, VEC>(p.A + (int64_t)b[u] * p.sA + (int64_t)i[u] * p.lda + cl);
+            const T* xb = p.x + (int64_t)b[u] * p.sx;
+            if (p.incx == 1) {
+                xv[u] = ld_matrix<T, VEC>(xb + cl);
+            } else {
+#pragma unroll
+                for (int k = 0; k < VEC; ++k) xv[u][k] = xb[(int64_t)(cl + k) * p.incx];
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);   // every load of the tile is in flight before the first FMA
+#pragma unroll
+        for (int u = 0; u < kSlots; ++u) {
+            T s = T(0);
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) s = (cl + k >= c) ? fmad(a[u][k], xv[u][k], s) : s;
+            s = group_sum<LPR>(s);
+            const uint32_t row = t * rows_per_tile + u * G + g;
+            if (l == 0 && row < p.total) {
+                T* yp = p.y + (int64_t)b[u] * p.sy + (int64_t)i[u] * p.incy;
+                T v = p.alpha * s;
+                if (p.beta != T(0)) v = fmad(p.beta, *yp, v);
+                *yp = v;
+            }
+        }
+    }
+}
+
+}  // namespace
+
+template <typename T>
+int tiny_gemv_n(mxb_handle_t h, int64_t rows, int64_t cols, T alpha, const T* A, int64_t lda, int64_t sA, const T* x0, int64_t incx,
+                int64_t sx, T beta, T* y0, int64_t incy, int64_t sy, int64_t batch)
+{
+    constexpr int VEC = Full<T>::vec;
+    TinyArgs<T> a{(int)rows, (int)cols, (uint32_t)(rows * batch), A, lda, sA, x0, incx, sx, y0, incy, sy, alpha, beta};
+    const int64_t nv = ceil_div(cols, (int64_t)VEC);
+    const int lpr = nv <= 4 ? 4 : nv <= 8 ? 8 : 16;
+    const int64_t tiles = ceil_div((int64_t)a.total, (int64_t)kSlots * (kWave / lpr));
+    int64_t grid = ceil_div(tiles, (int64_t)kWaves);
+    if (grid > (int64_t)kCUs * 16) grid = (int64_t)kCUs * 16;
+    const dim3 g((unsigned)grid), blk(kThreads);
+    if (lpr == 4) hipLaunchKernelGGL((tiny_gemv_n_kernel<T, VEC, 4>), g, blk, 0, h->stream, a);
+    else if (lpr == 8) hipLaunchKernelGGL((tiny_gemv_n_kernel<T, VEC, 8>), g, blk, 0, h->stream, a);
+    else hipLaunchKernelGGL((tiny_gemv_n_kernel<T, VEC, 16>), g, blk, 0, h->stream, a);
+    return launch_status();
+}
+
+template int tiny_gemv_n<float>(mxb_handle_t, int64_t, int64_t, float, const float*, int64_t, int64_t, const float*, int64_t, int64_t,
+                                float, float*, int64_t, int64_t, int64_t);
+template int tiny_gemv_n<double>(mxb_handle_t, int64_t, int64_t, double, const double*, int64_t, int64_t, const double*, int64_t,
+                                 int64_t, double, double*, int64_t, int64_t, int64_t);
+
+}  // namespace mxb
