@@ -564,8 +564,9 @@ int gemv_rows(mxb_handle_t h, bool no_trans, int64_t rows, int64_t cols, T alpha
             return skinny_gemv_t<T>(h, rows, cols, alpha, A, lda, x0, incx, beta, y0, incy);
     }
     // a batch of matrices with very short rows: the rows of all problems as one list
-    if (no_trans && tiny_takes<T>(rows, cols, batch))
-        return tiny_gemv_n<T>(h, rows, cols, alpha, A, lda, sA, x0, incx, sx, beta, y0, incy, sy, batch);
+    if (tiny_takes<T>(rows, cols, batch))
+        return no_trans ? tiny_gemv_n<T>(h, rows, cols, alpha, A, lda, sA, x0, incx, sx, beta, y0, incy, sy, batch)
+                        : tiny_gemv_t<T>(h, rows, cols, alpha, A, lda, sA, x0, incx, sx, beta, y0, incy, sy, batch);
     if (no_trans) {
         RowdotArgs<T> a{rows, cols, A, lda, x0, incx, y0, incy, alpha, beta, 0, 0, batch, sA, sx, sy};
         return launch_rowdot(h, a, MODE_GENERAL, false);

@@ -1,4 +1,4 @@
-// Batches of matrices with very short rows, not transposed (see tiny.hpp).  The row-dot kernel
+// Batches of matrices with very short rows (see tiny.hpp).  Not transposed: the row-dot kernel
 // gives every problem a block tile of its own and stages x in LDS per tile, which leaves most of a
 // block idle when a matrix has a few dozen rows.  Here the rows of all problems form one long
 // list: a group of LPR lanes (4, 8 or 16: one DPP quad, half row or row) takes one row with one
@@ -86,6 +86,94 @@ __global__ void __launch_bounds__(kThreads) tiny_gemv_n_kernel(const TinyArgs<T>
     }
 }
 
+// Transposed: y_b[j] = sum_i A_b[i][j] x_b[i].  A lane owns one vector of columns (l = lane % LPR)
+// and one of the 64 / LPR rows that a wavefront load covers; a wavefront works through whole
+// problems, one after the other: the (problem, group of rows) pairs form a list that is taken
+// kSlots at a time, column sums run in registers while the problem stays the same and are folded
+// over the lanes that own the same columns when it ends (DPP rotations inside a row of 16 lanes,
+// shuffles across rows), after which the first LPR lanes write y.
+constexpr int kDppRor4 = 0x124, kDppRor8 = 0x128;     // row_ror:4, row_ror:8
+
+__device__ __forceinline__ float shfl_xor(float v, int lane, int mask)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((lane ^ mask) << 2, __builtin_bit_cast(int, v)));
+}
+__device__ __forceinline__ double shfl_xor(double v, int lane, int mask)
+{
+    const uint64_t b = __builtin_bit_cast(uint64_t, v);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ mask) << 2, (int)(uint32_t)b);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ mask) << 2, (int)(uint32_t)(b >> 32));
+    return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+
+// Sum over the lanes lane % LPR == const of a wavefront; every such lane receives it.
+template <int LPR, typename T>
+__device__ __forceinline__ T strided_sum(T v, int lane)
+{
+    if (LPR <= 4) v += dpp_mov<kDppRor4>(v);      // lanes 4 apart: i, i-4 ...
+    if (LPR <= 8) v += dpp_mov<kDppRor8>(v);      // ... then 8 apart: all lanes of the row with the same lane % LPR
+    v += shfl_xor(v, lane, 16);
+    v += shfl_xor(v, lane, 32);
+    return v;
+}
+
+template <typename T, int VEC, int LPR>
+__global__ void __launch_bounds__(kThreads) tiny_gemv_t_kernel(const TinyArgs<T> p, uint32_t batch)
+{
+    typedef typename VecOf<T, VEC>::type V;
+    constexpr int G = kWave / LPR;            // rows per wavefront load
+    const int lane = threadIdx.x & (kWave - 1);
+    const int g = lane / LPR, l = lane % LPR;
+    const int c = l * VEC, cl = min(c, p.N - VEC);      // as in the not-transposed kernel
+    const uint32_t groups = ((uint32_t)p.M + G - 1) / G;                 // groups of G rows per problem
+    const uint32_t wave0 = blockIdx.x * kWaves + (threadIdx.x >> 6), nwaves = gridDim.x * kWaves;
+    // problems are dealt to the wavefronts in contiguous runs, so that a wavefront reads one stream
+    const uint32_t per = (batch + nwaves - 1) / nwaves;
+    const uint32_t b0 = min(wave0 * per, batch), b1 = min(b0 + per, batch);
+    const uint64_t items = (uint64_t)(b1 - b0) * groups;
+    T acc[VEC];
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) acc[k] = T(0);
+    uint32_t b = b0, s = 0;                   // the (problem, group) of the next item
+    for (uint64_t it = 0; it < items; it += kSlots) {
+        V a[kSlots];
+        T xi[kSlots];
+        uint32_t bb = b, ss = s;
+#pragma unroll
+        for (int u = 0; u < kSlots; ++u) {
+            const uint32_t bu = min(bb, b1 - 1);                          // items past the end repeat the last problem; unused
+            const uint32_t i = min(ss * G + g, (uint32_t)p.M - 1);        // clamp: loads stay in bounds
+            a[u] = ld_matrix<T, VEC>(p.A + (int64_t)bu * p.sA + (int64_t)i * p.lda + cl);
+            xi[u] = p.x[(int64_t)bu * p.sx + (int64_t)i * p.incx];
+            if (++ss == groups) { ss = 0; ++bb; }
+        }
+        __builtin_amdgcn_sched_barrier(0);   // every load of the batch is in flight before the first FMA
+#pragma unroll
+        for (int u = 0; u < kSlots; ++u) {
+            if (b < b1) {                     // the same for the whole wavefront
+                const bool row_ok = s * G + g < (uint32_t)p.M;
+#pragma unroll
+                for (int k = 0; k < VEC; ++k) acc[k] = row_ok ? fmad(a[u][k], xi[u], acc[k]) : acc[k];
+                if (++s == groups) {          // the problem is complete: fold and write
+#pragma unroll
+                    for (int k = 0; k < VEC; ++k) {
+                        const T tot = strided_sum<LPR>(acc[k], lane);
+                        if (g == 0 && cl + k >= c) {
+                            T* yp = p.y + (int64_t)b * p.sy + (int64_t)(cl + k) * p.incy;
+                            T v = p.alpha * tot;
+                            if (p.beta != T(0)) v = fmad(p.beta, *yp, v);
+                            *yp = v;
+                        }
+                        acc[k] = T(0);
+                    }
+                    s = 0;
+                    ++b;
+                }
+            }
+        }
+    }
+}
+
 }  // namespace
 
 template <typename T>
@@ -106,6 +194,28 @@ int tiny_gemv_n(mxb_handle_t h, int64_t rows, int64_t cols, T alpha, const T* A,
     return launch_status();
 }
 
+template <typename T>
+int tiny_gemv_t(mxb_handle_t h, int64_t rows, int64_t cols, T alpha, const T* A, int64_t lda, int64_t sA, const T* x0, int64_t incx,
+                int64_t sx, T beta, T* y0, int64_t incy, int64_t sy, int64_t batch)
+{
+    constexpr int VEC = Full<T>::vec;
+    TinyArgs<T> a{(int)rows, (int)cols, (uint32_t)(rows * batch), A, lda, sA, x0, incx, sx, y0, incy, sy, alpha, beta};
+    const int64_t nv = ceil_div(cols, (int64_t)VEC);
+    const int lpr = nv <= 4 ? 4 : nv <= 8 ? 8 : 16;
+    // enough wavefronts to fill the device, but whole problems per wavefront
+    int64_t waves = (int64_t)kCUs * 16 * kWaves;
+    if (waves > batch) waves = batch;
+    const dim3 g((unsigned)ceil_div(waves, (int64_t)kWaves)), blk(kThreads);
+    if (lpr == 4) hipLaunchKernelGGL((tiny_gemv_t_kernel<T, VEC, 4>), g, blk, 0, h->stream, a, (uint32_t)batch);
+    else if (lpr == 8) hipLaunchKernelGGL((tiny_gemv_t_kernel<T, VEC, 8>), g, blk, 0, h->stream, a, (uint32_t)batch);
+    else hipLaunchKernelGGL((tiny_gemv_t_kernel<T, VEC, 16>), g, blk, 0, h->stream, a, (uint32_t)batch);
+    return launch_status();
+}
+
+template int tiny_gemv_t<float>(mxb_handle_t, int64_t, int64_t, float, const float*, int64_t, int64_t, const float*, int64_t, int64_t,
+                                float, float*, int64_t, int64_t, int64_t);
+template int tiny_gemv_t<double>(mxb_handle_t, int64_t, int64_t, double, const double*, int64_t, int64_t, const double*, int64_t,
+                                 int64_t, double, double*, int64_t, int64_t, int64_t);
 template int tiny_gemv_n<float>(mxb_handle_t, int64_t, int64_t, float, const float*, int64_t, int64_t, const float*, int64_t, int64_t,
                                 float, float*, int64_t, int64_t, int64_t);
 template int tiny_gemv_n<double>(mxb_handle_t, int64_t, int64_t, double, const double*, int64_t, int64_t, const double*, int64_t,

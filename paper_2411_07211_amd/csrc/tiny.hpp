@@ -1,12 +1,12 @@
-// Batches of matrices with very short rows (at most 16 vectors of 16 bytes): the not-transposed
-// product of gemv_batched (Sec. 6.2.2 gemv, many small problems in one call).  Entry points; the
-// kernel lives in tiny.hip.
+// Batches of matrices with very short rows (at most 16 vectors of 16 bytes): both products of
+// gemv_batched (Sec. 6.2.2 gemv, many small problems in one call).  Entry points; the kernels
+// live in tiny.hip.
 #pragma once
 #include "common.hpp"
 
 namespace mxb {
 
-// Does the tiny path take `batch` not-transposed products with rows x cols row-major matrices?
+// Does the tiny path take `batch` products with rows x cols row-major matrices?
 template <typename T>
 inline bool tiny_takes(int64_t rows, int64_t cols, int64_t batch)
 {
@@ -18,6 +18,11 @@ inline bool tiny_takes(int64_t rows, int64_t cols, int64_t batch)
 // Pointers at logical element 0 of problem 0.  No workspace.
 template <typename T>
 int tiny_gemv_n(mxb_handle_t h, int64_t rows, int64_t cols, T alpha, const T* A, int64_t lda, int64_t sA, const T* x0, int64_t incx,
+                int64_t sx, T beta, T* y0, int64_t incy, int64_t sy, int64_t batch);
+
+// y_b = alpha*A_b^t*x_b + beta*y_b (x_b has rows elements, y_b has cols).
+template <typename T>
+int tiny_gemv_t(mxb_handle_t h, int64_t rows, int64_t cols, T alpha, const T* A, int64_t lda, int64_t sA, const T* x0, int64_t incx,
                 int64_t sx, T beta, T* y0, int64_t incy, int64_t sy, int64_t batch);
 
 }  // namespace mxb
