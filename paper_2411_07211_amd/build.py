@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmxblas.so")
-SOURCES = ["handle.hip", "level1.hip", "level1_pair.hip", "matvec.hip", "symv_ger.hip", "trisweep.hip", "skinny.hip", "tiny.hip"]
+SOURCES = ["handle.hip", "level1.hip", "level1_pair.hip", "matvec.hip", "symv_ger.hip", "trisweep.hip", "skinny.hip", "tiny.hip", "trsv.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",

@@ -185,4 +185,21 @@ __device__ __forceinline__ A block_sum(A v, A* slots)
     return s;
 }
 
+// ------------------------------------------------------------------------------------------------
+// Argument checks and the alpha == 0 case shared by the level-2 routines.
+inline bool layout_ok(int v) { return v == MXB_ROW_MAJOR || v == MXB_COL_MAJOR; }
+inline bool trans_ok(int v) { return v == MXB_NO_TRANS || v == MXB_TRANS; }
+inline bool uplo_ok(int v) { return v == MXB_UPPER || v == MXB_LOWER; }
+inline bool diag_ok(int v) { return v == MXB_NON_UNIT || v == MXB_UNIT; }
+
+// y[k] = beta*y[k] (zeros when beta == 0, without reading y): what gemv and symv leave of y when
+// alpha == 0.  blockIdx.y: problem of a batch, sy elements apart.
+template <typename T>
+__global__ void __launch_bounds__(256) scale_y_kernel(int64_t n, T beta, T* __restrict__ y, int64_t incy, int64_t sy)
+{
+    y += (int64_t)blockIdx.y * sy;
+    const int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (k < n) y[k * incy] = beta == T(0) ? T(0) : beta * y[k * incy];
+}
+
 }  // namespace mxb

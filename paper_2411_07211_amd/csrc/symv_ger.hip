@@ -18,13 +18,6 @@ __device__ __forceinline__ int64_t imin(int64_t a, int64_t b) { return a < b ? a
 
 constexpr int kThreads = 256;
 
-template <typename T>
-__global__ void __launch_bounds__(256) scale_y_kernel(int64_t n, T beta, T* __restrict__ y, int64_t incy)
-{
-    const int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (k < n) y[k * incy] = beta == T(0) ? T(0) : beta * y[k * incy];
-}
-
 // ---------------------------------------------------------------------------------------------
 // ger
 
@@ -326,8 +319,6 @@ __global__ void __launch_bounds__(kThreads) symv_small_kernel(int n, T alpha, co
 // ---------------------------------------------------------------------------------------------
 // launchers
 
-inline bool layout_ok(int v) { return v == MXB_ROW_MAJOR || v == MXB_COL_MAJOR; }
-inline bool uplo_ok(int v) { return v == MXB_UPPER || v == MXB_LOWER; }
 
 template <typename T>
 int symv(mxb_handle_t h, int layout, int uplo, int64_t n, T alpha, const T* A, int64_t lda, const T* x, int64_t incx, T beta,
@@ -344,7 +335,7 @@ int symv(mxb_handle_t h, int layout, int uplo, int64_t n, T alpha, const T* A, i
     if (!y) return -10;
     T* y0 = vec_base(y, n, incy);
     if (alpha == T(0)) {
-        hipLaunchKernelGGL(scale_y_kernel<T>, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, h->stream, n, beta, y0, incy);
+        hipLaunchKernelGGL(scale_y_kernel<T>, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, h->stream, n, beta, y0, incy, (int64_t)0);
         return launch_status();
     }
     if (!A) return -5;

@@ -17,7 +17,7 @@ constexpr int kTriMaxTiles = 128;
 constexpr int64_t kTriDefaultBlocks = 192;
 
 struct TriPlan {
-    int vec;         // elements per load (16-byte vectors, or 1 for unaligned data)
+    int vec;         // elements per load (16-byte vectors; 1 only for matrices narrower than one vector)
     int cv;          // vectors per lane and row
     int ub;          // loads a lane keeps in flight in a batch of rows off the diagonal: 4, 8 or 16
     int tile_cols;   // cv * 512 * vec
