@@ -92,7 +92,8 @@ typedef enum {
     MXB_OPT_SYMV_TILE_VECTORS = 8,  /* triangle sweep: 128-bit vectors per lane and row (1, 2 or 4); tile = 256 lanes x this */
     MXB_OPT_TRI_DIAG_WEIGHT = 9,    /* triangle sweep: cost of a row that crosses the diagonal, in quarters of a row that does not (1..8) */
     MXB_OPT_SYMV_SMALL_MAX = 10,    /* symv: largest n that takes the single-kernel path (every element read twice, no workspace) */
-    MXB_OPT_COUNT = 11
+    MXB_OPT_TRSV_CHAIN_MIN = 11,    /* trsv: smallest n solved by the single chained kernel instead of one launch per block */
+    MXB_OPT_COUNT = 12
 } mxb_option_t;
 int mxb_set_option(mxb_handle_t h, int option, int64_t value);
 int64_t mxb_get_option(mxb_handle_t h, int option);
@@ -202,8 +203,15 @@ int mxb_dtrmv(mxb_handle_t h, mxb_layout_t layout, mxb_uplo_t uplo, mxb_trans_t 
 /* Solves op(T)*z = x for z, which overwrites x: T is the uplo triangle of the n x n matrix A
  * (Sec. 6.2.2, trsv); with MXB_UNIT the diagonal is taken as 1 and never used.  Elements outside
  * the triangle are never used.  No test for singularity.  Blocked substitution: the diagonal
- * elements enter as reciprocals (one extra rounding per unknown).  Uses the workspace when the
- * product is transposed (as gemv does).  Quick return: n == 0.
+ * elements enter as reciprocals (one extra rounding per unknown).  Below MXB_OPT_TRSV_CHAIN_MIN
+ * unknowns: one launch per block of 512 (fp32) or 256 (fp64) unknowns, with the workspace used when
+ * the product is transposed (as gemv does).  From there on: one kernel whose workgroups solve 256
+ * unknowns each, in order, and hand the solved values on through x and one flag per 64 unknowns
+ * in the workspace (4*(ceil(n/64) + 2) bytes, cleared by the call; MXB_ERR_WORKSPACE if it is
+ * smaller).  A workgroup waits for a flag a bounded number of polls only; the bound (tens of
+ * seconds) is reached only if the device stops scheduling the workgroup that owns the flag, and x
+ * is then left unfinished.  mxb_workspace_bytes(MXB_TRMV, ...) covers both paths.
+ * Quick return: n == 0.
  * Errors: as mxb_strmv. */
 int mxb_strsv(mxb_handle_t h, mxb_layout_t layout, mxb_uplo_t uplo, mxb_trans_t trans, mxb_diag_t diag,
               int64_t n, const float* A, int64_t lda, float* x, int64_t incx);

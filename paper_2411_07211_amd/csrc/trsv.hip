@@ -105,30 +105,32 @@ __global__ void __launch_bounds__(NW* kWave) trsv_diag_kernel(const TrsvArgs<T> 
     // my row of the triangle on the diagonal: zero on and outside the diagonal
     T e[kWave];
     fetch(wave * kWave, e);
+    // Row i is scaled by 1 / T[i][i] once, so that the chain of 64 dependent steps below is one
+    // broadcast and one FMA per step: with c = b / T[i][i] the unknown j is c of lane j when its
+    // turn comes, and c no longer changes after a lane's own turn (its row is zero from there).
     T dv = T(1);
 #pragma unroll
-    for (int j = 0; j < kWave; ++j) {
-        dv = (!UNIT && active && j == lane) ? e[j] : dv;
-        const bool inside = OPLOWER ? j < lane : j > lane;
-        e[j] = inside ? e[j] : T(0);
-    }
+    for (int j = 0; j < kWave; ++j) dv = (!UNIT && active && j == lane) ? e[j] : dv;
     const T rinv = T(1) / dv;      // 1 in the lanes past the block: their zeros stay zeros
+#pragma unroll
+    for (int j = 0; j < kWave; ++j) {
+        const bool inside = OPLOWER ? j < lane : j > lane;
+        e[j] = inside ? (UNIT ? e[j] : e[j] * rinv) : T(0);
+    }
 
     for (int step = 0; step < nsub; ++step) {
         const int s = OPLOWER ? step : nsub - 1 - step;
         const bool later = OPLOWER ? wave > s : wave < s;
         T ev[kWave];
         if (wave == s) {
-            T xv = T(0);
+            T c = UNIT ? b : b * rinv;
 #pragma unroll
             for (int jj = 0; jj < kWave; ++jj) {
                 const int j = OPLOWER ? jj : kWave - 1 - jj;
-                const T xj = lane_bcast(UNIT ? b : b * rinv, j);
-                xv = lane == j ? xj : xv;
-                b = fmad(-e[j], xj, b);
+                c = fmad(-e[j], lane_bcast(c, j), c);
             }
-            xs[i] = xv;
-            if (active) p.x[(int64_t)i * p.incx] = xv;
+            xs[i] = c;
+            if (active) p.x[(int64_t)i * p.incx] = c;
         } else if (later) {
             fetch(s * kWave, ev);
         }
@@ -151,6 +153,228 @@ void launch_trsv_diag(mxb_handle_t h, bool op_lower, bool unit, const TrsvArgs<T
         if (unit) hipLaunchKernelGGL((trsv_diag_kernel<T, NW, false, TRANS, true>), grid, block, 0, h->stream, a);
         else hipLaunchKernelGGL((trsv_diag_kernel<T, NW, false, TRANS, false>), grid, block, 0, h->stream, a);
     }
+}
+
+// ---------------------------------------------------------------------------------------------
+// The same substitution in ONE kernel: no launch per block, and the off-diagonal work of a block
+// of rows overlaps the solves of the blocks before it.
+//
+// A workgroup of 4 wavefronts owns 256 consecutive unknowns (4 sub-blocks of 64, one per
+// wavefront) in solving order.  Workgroups number themselves with a ticket when they start, so
+// that every workgroup with a smaller number is already running or done.  A wavefront first
+// subtracts, sub-block by sub-block, the part of its rows that multiplies unknowns owned by
+// earlier workgroups: the 64 x 64 tile is fetched while the wavefront waits for that sub-block's
+// flag, which its owner sets (release, device scope) after storing the 64 solutions; the waiter
+// reads the flag with device-scope atomic loads, then the solutions (acquire).  The 4 sub-blocks
+// of the workgroup itself are then solved as in the blocked kernel above (LDS and barriers), each
+// one published as soon as it is solved.  Waits are bounded: a wavefront that polls longer than
+// the limit, or sees the error word set, sets the error word and goes on without waiting, so the
+// kernel always drains (the result is then wrong; it cannot happen while every workgroup makes
+// progress, because a workgroup only ever waits for workgroups that started before it).
+template <typename T>
+struct ChainArgs {
+    int n, nsub;         // unknowns; sub-blocks of 64
+    const T* A;
+    int64_t lda;
+    T* x;                // logical element 0
+    int64_t incx;
+    int* flags;          // [nsub] in solving order, then the ticket and the error word; all zero at the start
+    int spin_limit;
+};
+
+constexpr int kChainWaves = 4;
+constexpr int kChainSpinLimit = 1 << 24;      // polls of one flag before a wavefront gives up: tens of seconds
+
+__global__ void __launch_bounds__(256) trsv_chain_init_kernel(int* words, int count)
+{
+    const int k = (int)blockIdx.x * 256 + threadIdx.x;
+    if (k < count) words[k] = 0;
+}
+
+template <typename T, bool OPLOWER, bool TRANS, bool UNIT>
+__global__ void __launch_bounds__(kChainWaves* kWave) trsv_chain_kernel(const ChainArgs<T> p)
+{
+    constexpr int NW = kChainWaves;
+    __shared__ T xs[NW * kWave];
+    __shared__ T tile[TRANS ? 1 : NW][TRANS ? 1 : kWave][TRANS ? 1 : kWave + 1];   // per-wavefront transposition buffer
+    __shared__ int my_ticket;
+    int* const ticket = p.flags + p.nsub;
+    int* const error = p.flags + p.nsub + 1;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (threadIdx.x == 0) my_ticket = atomicAdd(ticket, 1);
+    __syncthreads();
+    const int q0 = my_ticket * NW;       // my workgroup's sub-blocks q0 .. q0 + 3, counted in solving order
+    const int q = q0 + wave;
+    const bool have = q < p.nsub;        // false: a wavefront past the last sub-block only keeps the barriers company
+    auto actual = [&](int qq) { return OPLOWER ? qq : p.nsub - 1 - qq; };      // sub-block number in the matrix
+    const int r0 = actual(have ? q : p.nsub - 1) * kWave;                       // my rows: r0 .. r0 + 63
+    const int i = r0 + lane, last = p.n - 1;
+    const bool active = have && i < p.n;
+
+    // raw[j] = op(T)[r0 + lane][c0 + j], in two halves as the tile is in flight between them:
+    // issue() starts the 64 loads (addresses clamped into the matrix: no predicate), finish() pins
+    // them, zeroes what lies outside the matrix and, if not transposed, turns the tile through LDS.
+    auto issue = [&](int c0, T (&raw)[kWave]) {
+        if (TRANS) {
+            const int ic = min(i, last);
+#pragma unroll
+            for (int j = 0; j < kWave; ++j) raw[j] = (p.A + (int64_t)min(c0 + j, last) * p.lda)[ic];
+        } else {
+            const int cc = min(c0 + lane, last);
+#pragma unroll
+            for (int r = 0; r < kWave; ++r) raw[r] = (p.A + (int64_t)min(r0 + r, last) * p.lda)[cc];
+        }
+    };
+    auto finish = [&](int c0, T (&raw)[kWave]) {
+#pragma unroll
+        for (int j = 0; j < kWave; ++j) asm volatile("" : "+v"(raw[j]));
+        if (TRANS) {
+#pragma unroll
+            for (int j = 0; j < kWave; ++j) raw[j] = (active && c0 + j < p.n) ? raw[j] : T(0);
+        } else {
+            __builtin_amdgcn_wave_barrier();      // earlier reads of the buffer by this wavefront come first
+#pragma unroll
+            for (int r = 0; r < kWave; ++r)
+                tile[TRANS ? 0 : wave][TRANS ? 0 : r][TRANS ? 0 : lane] = (have && r0 + r < p.n && c0 + lane < p.n) ? raw[r] : T(0);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int j = 0; j < kWave; ++j) raw[j] = tile[TRANS ? 0 : wave][TRANS ? 0 : lane][TRANS ? 0 : j];
+        }
+    };
+
+    T b = active ? p.x[(int64_t)i * p.incx] : T(0);
+    T e[kWave];
+    issue(r0, e);                        // my tile on the diagonal: in flight while the other tiles are worked off
+
+    // Tile s of my own workgroup (s = 0 .. wave - 1) multiplies the sub-block solved in step s.
+    // Two of them are in flight at any time, in pa and pb by turns: tile s + 2 is asked for when
+    // tile s has been used, so that a tile has two steps to arrive.  In single precision the first
+    // two are asked for right away and travel during the whole first phase; in double precision
+    // the registers do not allow a third set, pa doubles as the first phase's buffer and the two
+    // tiles are asked for when that phase is over.
+    constexpr bool kEarly = sizeof(T) == 4;
+    T pa[kWave], pb[kWave];
+    auto own_c0 = [&](int s) { return actual(q0 + s) * kWave; };
+    auto wants = [&](int s) { return have && wave > s && q0 + s < p.nsub; };
+    if (kEarly) {
+        if (wants(0)) issue(own_c0(0), pa);
+        if (wants(1)) issue(own_c0(1), pb);
+    }
+
+    // ---- the unknowns of earlier workgroups
+    bool ok = true;
+    auto earlier = [&](T (&t)[kWave]) {
+        for (int qq = 0; qq < q0; ++qq) {
+            const int c0 = actual(qq) * kWave;
+            issue(c0, t);
+            if (ok) {
+                int spins = 0;
+                while (__hip_atomic_load(&p.flags[qq], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) {
+                    if (++spins > p.spin_limit || __hip_atomic_load(error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+                        ok = false;
+                        if (lane == 0) __hip_atomic_store(error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        break;
+                    }
+                    __builtin_amdgcn_s_sleep(2);
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            const T xv = c0 + lane < p.n ? p.x[(int64_t)(c0 + lane) * p.incx] : T(0);
+            finish(c0, t);
+            T part[4] = {T(0), T(0), T(0), T(0)};      // four short chains of FMAs instead of one long one
+#pragma unroll
+            for (int j = 0; j < kWave; ++j) part[j & 3] = fmad(t[j], lane_bcast(xv, j), part[j & 3]);
+            b -= (part[0] + part[1]) + (part[2] + part[3]);
+        }
+    };
+    if (have) {
+        if constexpr (kEarly) {
+            T t[kWave];
+            earlier(t);
+        } else {
+            earlier(pa);
+        }
+    }
+    if (!kEarly) {
+        if (wants(0)) issue(own_c0(0), pa);
+        if (wants(1)) issue(own_c0(1), pb);
+    }
+
+    // ---- my workgroup's own sub-blocks
+    finish(r0, e);
+    T dv = T(1);
+#pragma unroll
+    for (int j = 0; j < kWave; ++j) dv = (!UNIT && active && j == lane) ? e[j] : dv;
+    const T rinv = T(1) / dv;            // 1 in the lanes past the end: their zeros stay zeros
+#pragma unroll
+    for (int j = 0; j < kWave; ++j) {    // my row scaled by 1 / T[i][i], as in the blocked kernel
+        const bool inside = OPLOWER ? j < lane : j > lane;
+        e[j] = inside ? (UNIT ? e[j] : e[j] * rinv) : T(0);
+    }
+    // One step: sub-block q0 + s is solved by wavefront s and published at once; the wavefronts
+    // after it subtract its part.  Only LDS traffic is fenced around the barrier: the tiles still
+    // in flight from global memory must not be waited for there.
+    auto step = [&](int s, T (&tile_s)[kWave]) {
+        if (q0 + s >= p.nsub) return;    // the same for the whole workgroup
+        if (wave == s) {
+            T c = UNIT ? b : b * rinv;
+#pragma unroll
+            for (int jj = 0; jj < kWave; ++jj) {
+                const int j = OPLOWER ? jj : kWave - 1 - jj;
+                c = fmad(-e[j], lane_bcast(c, j), c);
+            }
+            xs[wave * kWave + lane] = c;
+            if (active) p.x[(int64_t)i * p.incx] = c;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+        if (wave == s) {
+            // publish for the other workgroups once my own workgroup is on its way (it reads LDS):
+            // the 64 solutions first (release at device scope writes them back), then the flag
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+            if (lane == 0) __hip_atomic_store(&p.flags[q0 + s], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        if (wants(s)) {
+            finish(own_c0(s), tile_s);
+            T part[4] = {T(0), T(0), T(0), T(0)};
+#pragma unroll
+            for (int j = 0; j < kWave; ++j) part[j & 3] = fmad(tile_s[j], xs[s * kWave + j], part[j & 3]);
+            b -= (part[0] + part[1]) + (part[2] + part[3]);
+            if (wants(s + 2)) issue(own_c0(s + 2), tile_s);
+        }
+    };
+    static_assert(NW == 4, "four steps, two tile buffers by turns");
+    step(0, pa);
+    step(1, pb);
+    step(2, pa);
+    step(3, pb);
+}
+
+// Words of workspace the one-kernel solve needs: a flag per sub-block, the ticket, the error word.
+inline int64_t chain_words(int64_t n) { return ceil_div(n, (int64_t)kWave) + 2; }
+
+template <typename T>
+int trsv_chain(mxb_handle_t h, bool op_lower, bool no_trans, bool unit, int64_t n, const T* A, int64_t lda, T* x0, int64_t incx)
+{
+    const int64_t words = chain_words(n);
+    if (!h->ws || h->ws_bytes < (size_t)words * sizeof(int)) return MXB_ERR_WORKSPACE;
+    int* flags = static_cast<int*>(h->ws);
+    hipLaunchKernelGGL(trsv_chain_init_kernel, dim3((unsigned)ceil_div(words, (int64_t)256)), dim3(256), 0, h->stream, flags, (int)words);
+    int st = launch_status();
+    if (st != MXB_OK) return st;
+    const ChainArgs<T> a{(int)n, (int)ceil_div(n, (int64_t)kWave), A, lda, x0, incx, flags, kChainSpinLimit};
+    const dim3 grid((unsigned)ceil_div((int64_t)a.nsub, (int64_t)kChainWaves)), block(kChainWaves * kWave);
+#define MXB_CHAIN(LOW_, TR_)                                                                                          \
+    if (unit) hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, true>), grid, block, 0, h->stream, a);              \
+    else hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, false>), grid, block, 0, h->stream, a);
+    if (op_lower) { if (no_trans) { MXB_CHAIN(true, false) } else { MXB_CHAIN(true, true) } }
+    else { if (no_trans) { MXB_CHAIN(false, false) } else { MXB_CHAIN(false, true) } }
+#undef MXB_CHAIN
+    return launch_status();
 }
 
 template <typename T>
@@ -176,6 +400,8 @@ int trsv(mxb_handle_t h, int layout, int uplo, int trans, int diag, int64_t n, c
     constexpr int NW = sizeof(T) == 4 ? 8 : 4;        // 64 registers of triangle + 64 of prefetch per lane: 512 / 256 unknowns
     constexpr int64_t NB = NW * kWave;
     T* x0 = vec_base(x, n, incx);
+    if (n >= option(h, MXB_OPT_TRSV_CHAIN_MIN) && n < ((int64_t)1 << 31) - kWave)
+        return trsv_chain<T>(h, op_lower, no_trans, unit, n, A, lda, x0, incx);
     const int64_t nblocks = ceil_div(n, NB);
     for (int64_t step = 0; step < nblocks; ++step) {
         const int64_t k = op_lower ? step : nblocks - 1 - step;

@@ -151,6 +151,8 @@ def test_argument_errors_name_the_argument(B):
                 assert t(h, *ok, 4, P, 4, None, 1) == -8
                 assert t(h, *ok, 4, P, 4, P, 0) == -9
                 assert t(h, *ok, 0, None, 1, None, 1) == 0
+                # the chained solve keeps its flags in the workspace: none set -> error, no launch
+                assert t(h, *ok, 4096, P, 4096, P, 1) == B.ERR_WORKSPACE
             s = f("symv")
             assert s(h, 0, B.LOWER, 4, 1.0, P, 4, P, 1, 0.0, P, 1) == -1
             assert s(h, B.ROW_MAJOR, 0, 4, 1.0, P, 4, P, 1, 0.0, P, 1) == -2

@@ -126,7 +126,7 @@ def test_gemv_deterministic_and_geometry_invariant(blas, ctx, dt):
             for opts in ({}, {}, {blas.OPT_ROWDOT_XCHUNK: 256, blas.OPT_COLACC_TARGET_BLOCKS: 64},
                          {blas.OPT_ROWDOT_XCHUNK: 1024, blas.OPT_ROWDOT_BLOCKS_PER_CU: 1, blas.OPT_COLACC_TARGET_BLOCKS: 4096,
                           blas.OPT_COLACC_MIN_ROWS: 8}):
-                for o in range(11):
+                for o in range(12):
                     ctx.set_option(o, 0)
                 for o, v in opts.items():
                     ctx.set_option(o, v)
@@ -136,7 +136,7 @@ def test_gemv_deterministic_and_geometry_invariant(blas, ctx, dt):
                 check_close(outs[-1], ref, D, lenx, f"gemv trans={trans} opts={opts}")
             assert outs[0].tobytes() == outs[1].tobytes(), "same launch geometry must give the same bits"
     finally:
-        for o in range(11):
+        for o in range(12):
             ctx.set_option(o, 0)
 
 
@@ -517,12 +517,19 @@ def trsv_case(blas, ctx, dt, layout, uplo, trans, diag, n, pad, incx, exact=Fals
 @pytest.mark.parametrize("trans", [O.NO_TRANS, O.TRANS])
 @pytest.mark.parametrize("diag", [O.NON_UNIT, O.UNIT])
 def test_trsv(blas, ctx, dt, layout, uplo, trans, diag):
-    for n in (1, 2, 3, 5, 17, 63, 64, 65, 130, 255, 256, 257, 511, 512, 513, 1000, 1030, 2310):
-        trsv_case(blas, ctx, dt, layout, uplo, trans, diag, n, 0 if n % 2 else 4, 1)
-    trsv_case(blas, ctx, dt, layout, uplo, trans, diag, 700, 1, 2)
-    trsv_case(blas, ctx, dt, layout, uplo, trans, diag, 700, 0, -1)
-    for n in (64, 515, 1536):
-        trsv_case(blas, ctx, dt, layout, uplo, trans, diag, n, 0, 1, exact=True)
+    # every size through both paths: one launch per block, then the single chained kernel
+    for chain_min in (1 << 30, 1):
+        ctx.set_option(blas.OPT_TRSV_CHAIN_MIN, chain_min)
+        try:
+            for n in (1, 2, 3, 5, 17, 63, 64, 65, 130, 255, 256, 257, 511, 512, 513, 1000, 1030, 2310):
+                trsv_case(blas, ctx, dt, layout, uplo, trans, diag, n, 0 if n % 2 else 4, 1)
+            trsv_case(blas, ctx, dt, layout, uplo, trans, diag, 700, 1, 2)
+            trsv_case(blas, ctx, dt, layout, uplo, trans, diag, 700, 0, -1)
+            for n in (64, 515, 1536):
+                trsv_case(blas, ctx, dt, layout, uplo, trans, diag, n, 0, 1, exact=True)
+        finally:
+            ctx.set_option(blas.OPT_TRSV_CHAIN_MIN, 0)
+    trsv_case(blas, ctx, dt, layout, uplo, trans, diag, 5000, 0, 1)      # the default choice at a size with many workgroups
 
 
 # ----------------------------------------------------------------------------- skinny matrices
