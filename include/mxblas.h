@@ -54,7 +54,7 @@ typedef enum { MXB_NON_UNIT = 131, MXB_UNIT = 132 } mxb_diag_t;
 
 typedef enum {
     MXB_AXPY = 1, MXB_SCAL = 2, MXB_DOT = 3, MXB_ASUM = 4, MXB_NRM2 = 5,
-    MXB_GEMV = 6, MXB_TRMV = 7, MXB_SYMV = 8, MXB_GER = 9, MXB_GEMV_BATCHED = 10
+    MXB_GEMV = 6, MXB_TRMV = 7, MXB_SYMV = 8, MXB_GER = 9, MXB_GEMV_BATCHED = 10, MXB_TRSV = 11
 } mxb_routine_t;
 
 #define MXB_OK 0
@@ -206,11 +206,11 @@ int mxb_dtrmv(mxb_handle_t h, mxb_layout_t layout, mxb_uplo_t uplo, mxb_trans_t 
  * elements enter as reciprocals (one extra rounding per unknown).  Below MXB_OPT_TRSV_CHAIN_MIN
  * unknowns: one launch per block of 512 (fp32) or 256 (fp64) unknowns, with the workspace used when
  * the product is transposed (as gemv does).  From there on: one kernel whose workgroups solve 256
- * unknowns each, in order, and hand the solved values on through x and one flag per 64 unknowns
- * in the workspace (4*(ceil(n/64) + 2) bytes, cleared by the call; MXB_ERR_WORKSPACE if it is
- * smaller).  A workgroup waits for a flag a bounded number of polls only; the bound (tens of
- * seconds) is reached only if the device stops scheduling the workgroup that owns the flag, and x
- * is then left unfinished.  mxb_workspace_bytes(MXB_TRMV, ...) covers both paths.
+ * unknowns each, in order, and hand the solved values on through the workspace (16 bytes per
+ * unknown at most, cleared by the call; MXB_ERR_WORKSPACE if it is smaller).  A workgroup waits
+ * for solved values a bounded number of polls only; the bound (tens of seconds) is reached only
+ * if the device stops scheduling the workgroup that owns them, and x is then left unfinished.
+ * mxb_workspace_bytes(MXB_TRSV, elem_size, 0, n) covers both paths.
  * Quick return: n == 0.
  * Errors: as mxb_strmv. */
 int mxb_strsv(mxb_handle_t h, mxb_layout_t layout, mxb_uplo_t uplo, mxb_trans_t trans, mxb_diag_t diag,

@@ -36,7 +36,7 @@ ROW_MAJOR, COL_MAJOR = 101, 102
 NO_TRANS, TRANS = 111, 112
 UPPER, LOWER = 121, 122
 NON_UNIT, UNIT = 131, 132
-AXPY, SCAL, DOT, ASUM, NRM2, GEMV, TRMV, SYMV, GER, GEMV_BATCHED = range(1, 11)
+AXPY, SCAL, DOT, ASUM, NRM2, GEMV, TRMV, SYMV, GER, GEMV_BATCHED, TRSV = range(1, 12)
 OK, ERR_HANDLE, ERR_WORKSPACE, ERR_NOT_IMPLEMENTED, ERR_HIP_BASE = 0, 1, 2, 3, 1000
 (OPT_L1_BLOCKS_PER_CU, OPT_REDUCE_BLOCKS, OPT_ROWDOT_XCHUNK, OPT_ROWDOT_BLOCKS_PER_CU,
  OPT_COLACC_TARGET_BLOCKS, OPT_COLACC_MIN_ROWS, OPT_SYMV_TARGET_BLOCKS, OPT_GER_ROWS_PER_BLOCK,

@@ -155,6 +155,12 @@ size_t mxb_workspace_bytes(int routine, int elem_size, int64_t m, int64_t n)
             return a > b ? a : b;
         }
         case MXB_SYMV: return tri_workspace_bound(n, elem_size);
+        case MXB_TRSV: {
+            // blocked: the transposed product's partial vectors; chained: 8 (fp32) or 16 (fp64) bytes per
+            // unknown of whole sub-blocks of 64, and two counters
+            const size_t a = colacc_bound(n, n), b = align_up((size_t)ceil_div(n, (int64_t)64) * 64 * 16 + 8, 256);
+            return a > b ? a : b;
+        }
         default: return 0;
     }
 }

@@ -1,6 +1,8 @@
 // trsv (Sec. 6.2.2, triangular solve) on a row-major matrix: blocked substitution.  The part of
 // a block's right-hand side that depends on unknowns solved earlier is subtracted with the
 // matrix-vector kernels of matvec.hip; the block on the diagonal is solved by one workgroup.
+#include <type_traits>
+
 #include "matvec.hpp"
 
 #include "options.hpp"
@@ -48,7 +50,7 @@ __device__ __forceinline__ double lane_bcast(double v, int j)
 template <typename T, int NW, bool OPLOWER, bool TRANS, bool UNIT>
 __global__ void __launch_bounds__(NW* kWave) trsv_diag_kernel(const TrsvArgs<T> p)
 {
-    __shared__ T xs[NW * kWave];
+    __shared__ __attribute__((aligned(16))) T xs[NW * kWave];
     __shared__ T tile[TRANS ? 1 : NW][TRANS ? 1 : kWave][TRANS ? 1 : kWave + 1];   // per-wavefront transposition buffer
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -164,13 +166,53 @@ void launch_trsv_diag(mxb_handle_t h, bool op_lower, bool unit, const TrsvArgs<T
 // that every workgroup with a smaller number is already running or done.  A wavefront first
 // subtracts, sub-block by sub-block, the part of its rows that multiplies unknowns owned by
 // earlier workgroups: the 64 x 64 tile is fetched while the wavefront waits for that sub-block's
-// flag, which its owner sets (release, device scope) after storing the 64 solutions; the waiter
-// reads the flag with device-scope atomic loads, then the solutions (acquire).  The 4 sub-blocks
-// of the workgroup itself are then solved as in the blocked kernel above (LDS and barriers), each
-// one published as soon as it is solved.  Waits are bounded: a wavefront that polls longer than
-// the limit, or sees the error word set, sets the error word and goes on without waiting, so the
-// kernel always drains (the result is then wrong; it cannot happen while every workgroup makes
-// progress, because a workgroup only ever waits for workgroups that started before it).
+// solutions.  The 4 sub-blocks of the workgroup itself are then solved as in the blocked kernel
+// above (LDS and barriers), each one handed on as soon as it is solved.
+//
+// Solutions travel between workgroups in words that validate themselves: the solver stores
+// {value bits, tag} as one 64-bit device-scope atomic (two words, one per half, for a double), a
+// reader loads the word the same way and takes the value once the tag is there.  No fence is
+// needed on either side, so no cache is written back or invalidated on the way (the compute
+// dies have a second-level cache each, and a device-scope fence has to reach through it); the
+// solutions go to x as well, with plain stores, for the caller.  Waits are bounded: a wavefront
+// that polls longer than the limit, or sees the error word set, sets the error word and goes on
+// without waiting, so the kernel always drains (the result is then wrong; it cannot happen while
+// every workgroup makes progress, because a workgroup only ever waits for workgroups that
+// started before it).
+template <typename T>
+struct Handover;
+template <>
+struct Handover<float> {
+    static constexpr int kWords = 1;
+    static __device__ __forceinline__ void put(unsigned long long* w, float v)
+    {
+        __hip_atomic_store(w, (1ull << 32) | __float_as_uint(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    static __device__ __forceinline__ bool get(unsigned long long* w, float& v)
+    {
+        const unsigned long long u = __hip_atomic_load(w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        v = __uint_as_float((unsigned)u);
+        return (u >> 32) != 0;
+    }
+};
+template <>
+struct Handover<double> {
+    static constexpr int kWords = 2;
+    static __device__ __forceinline__ void put(unsigned long long* w, double v)
+    {
+        const unsigned long long bits = (unsigned long long)__double_as_longlong(v);
+        __hip_atomic_store(w, (1ull << 32) | (bits & 0xffffffffull), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(w + 1, (1ull << 32) | (bits >> 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    static __device__ __forceinline__ bool get(unsigned long long* w, double& v)
+    {
+        const unsigned long long lo = __hip_atomic_load(w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long hi = __hip_atomic_load(w + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        v = __longlong_as_double((long long)((hi << 32) | (lo & 0xffffffffull)));
+        return (lo >> 32) != 0 && (hi >> 32) != 0;
+    }
+};
+
 template <typename T>
 struct ChainArgs {
     int n, nsub;         // unknowns; sub-blocks of 64
@@ -178,7 +220,8 @@ struct ChainArgs {
     int64_t lda;
     T* x;                // logical element 0
     int64_t incx;
-    int* flags;          // [nsub] in solving order, then the ticket and the error word; all zero at the start
+    unsigned long long* solved;   // [nsub * 64 * Handover<T>::kWords] hand-over words in solving order; all zero at the start
+    int* control;        // the ticket counter and the error word; zero at the start
     int spin_limit;
 };
 
@@ -198,8 +241,9 @@ __global__ void __launch_bounds__(kChainWaves* kWave) trsv_chain_kernel(const Ch
     __shared__ T xs[NW * kWave];
     __shared__ T tile[TRANS ? 1 : NW][TRANS ? 1 : kWave][TRANS ? 1 : kWave + 1];   // per-wavefront transposition buffer
     __shared__ int my_ticket;
-    int* const ticket = p.flags + p.nsub;
-    int* const error = p.flags + p.nsub + 1;
+    constexpr int HW = Handover<T>::kWords;
+    int* const ticket = p.control;
+    int* const error = p.control + 1;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (threadIdx.x == 0) my_ticket = atomicAdd(ticket, 1);
@@ -247,14 +291,13 @@ __global__ void __launch_bounds__(kChainWaves* kWave) trsv_chain_kernel(const Ch
 
     T b = active ? p.x[(int64_t)i * p.incx] : T(0);
     T e[kWave];
-    issue(r0, e);                        // my tile on the diagonal: in flight while the other tiles are worked off
+    issue(r0, e);                        // my tile on the diagonal
 
     // Tile s of my own workgroup (s = 0 .. wave - 1) multiplies the sub-block solved in step s.
     // Two of them are in flight at any time, in pa and pb by turns: tile s + 2 is asked for when
     // tile s has been used, so that a tile has two steps to arrive.  In single precision the first
     // two are asked for right away and travel during the whole first phase; in double precision
-    // the registers do not allow a third set, pa doubles as the first phase's buffer and the two
-    // tiles are asked for when that phase is over.
+    // the registers do not allow that and they are asked for when that phase is over.
     constexpr bool kEarly = sizeof(T) == 4;
     T pa[kWave], pb[kWave];
     auto own_c0 = [&](int s) { return actual(q0 + s) * kWave; };
@@ -264,59 +307,153 @@ __global__ void __launch_bounds__(kChainWaves* kWave) trsv_chain_kernel(const Ch
         if (wants(1)) issue(own_c0(1), pb);
     }
 
-    // ---- the unknowns of earlier workgroups
+    // My row of the diagonal tile, scaled by 1 / T[i][i] as in the blocked kernel.  In single
+    // precision before the wait for the earlier workgroups, which is where a workgroup has time
+    // to spare; in double precision after it: the finished row would not stay in registers over
+    // the first phase, and fetching it back one element at a time inside the solve costs far
+    // more than finishing it late.
+    // (A macro, not a lambda: wrapped in one more closure the register arrays end up in scratch memory.)
+    T rinv = T(1);
+#define MXB_OWN_ROW()                                                                                  \
+    do {                                                                                               \
+        finish(r0, e);                                                                                 \
+        T dv = T(1);                                                                                   \
+        _Pragma("unroll") for (int j = 0; j < kWave; ++j) dv = (!UNIT && active && j == lane) ? e[j] : dv; \
+        rinv = T(1) / dv; /* 1 in the lanes past the end: their zeros stay zeros */                    \
+        _Pragma("unroll") for (int j = 0; j < kWave; ++j) {                                            \
+            const bool inside = OPLOWER ? j < lane : j > lane;                                         \
+            e[j] = inside ? (UNIT ? e[j] : e[j] * rinv) : T(0);                                        \
+            asm volatile("" : "+v"(e[j])); /* here, not when the solve needs it */                     \
+        }                                                                                              \
+    } while (0)
+    if constexpr (kEarly) MXB_OWN_ROW();
+
+    // ---- the unknowns of earlier workgroups: tiles 0 .. q0 - 1 of my block row, in solving order.
+    // A tile travels in pieces of RH rows (columns if transposed), two pieces in flight by turns;
+    // the 64 solutions a tile multiplies are looked for when the piece is asked for and waited
+    // for when it is used.  Transposed, a lane owns its row and subtracts as it goes.  Not
+    // transposed, a lane owns a column of the piece and keeps one partial sum per row; the
+    // partial sums of all tiles but the last are folded over the lanes once, through LDS, and the
+    // last tile, whose solutions arrive last, is turned through LDS before the wait instead, so
+    // that after the wait only its 64 multiply-adds remain; its pieces travel like the others.
+    constexpr int RH = sizeof(T) == 4 ? kWave : kWave / 2;
+    constexpr int CPT = kWave / RH;      // pieces per tile
     bool ok = true;
-    auto earlier = [&](T (&t)[kWave]) {
-        for (int qq = 0; qq < q0; ++qq) {
-            const int c0 = actual(qq) * kWave;
-            issue(c0, t);
-            if (ok) {
-                int spins = 0;
-                while (__hip_atomic_load(&p.flags[qq], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) {
-                    if (++spins > p.spin_limit || __hip_atomic_load(error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
-                        ok = false;
-                        if (lane == 0) __hip_atomic_store(error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        break;
-                    }
-                    __builtin_amdgcn_s_sleep(2);
-                }
+    auto look = [&](int qq, T& xv) { return Handover<T>::get(p.solved + ((int64_t)qq * kWave + lane) * HW, xv); };
+    auto wait_x = [&](int qq, T& xv, bool got) {
+        for (int spins = 0; ok && __ballot(got) != ~0ull;) {
+            if (++spins > p.spin_limit || __hip_atomic_load(error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+                ok = false;
+                if (lane == 0) __hip_atomic_store(error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                break;
             }
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-            const T xv = c0 + lane < p.n ? p.x[(int64_t)(c0 + lane) * p.incx] : T(0);
-            finish(c0, t);
-            T part[4] = {T(0), T(0), T(0), T(0)};      // four short chains of FMAs instead of one long one
-#pragma unroll
-            for (int j = 0; j < kWave; ++j) part[j & 3] = fmad(t[j], lane_bcast(xv, j), part[j & 3]);
-            b -= (part[0] + part[1]) + (part[2] + part[3]);
+            __builtin_amdgcn_s_sleep(1);
+            got = look(qq, xv);
         }
     };
-    if (have) {
-        if constexpr (kEarly) {
-            T t[kWave];
-            earlier(t);
-        } else {
-            earlier(pa);
+    if (have && q0 > 0) {
+        T acc[TRANS ? 1 : kWave];
+        if (!TRANS) {
+#pragma unroll
+            for (int r = 0; r < kWave; ++r) acc[TRANS ? 0 : r] = T(0);
         }
+        const int nch = q0 * CPT;
+        T t0[RH], t1[RH], x0, x1;
+        bool g0, g1;
+        auto start = [&](int ch, T (&raw)[RH], T& xv, bool& got) {
+            const int c0 = actual(ch / CPT) * kWave, h0 = (ch % CPT) * RH;
+            if (TRANS) {
+                const int ic = min(i, last);
+#pragma unroll
+                for (int j = 0; j < RH; ++j) raw[j] = (p.A + (int64_t)min(c0 + h0 + j, last) * p.lda)[ic];
+            } else {
+                const int cc = min(c0 + lane, last);
+#pragma unroll
+                for (int r = 0; r < RH; ++r) raw[r] = (p.A + (int64_t)min(r0 + h0 + r, last) * p.lda)[cc];
+            }
+            got = look(ch / CPT, xv);
+        };
+        auto use = [&](auto piece, int ch, T (&raw)[RH], T& xv, bool got) {
+            constexpr int H0 = decltype(piece)::value * RH;
+            const int qq = ch / CPT, c0 = actual(qq) * kWave;
+#pragma unroll
+            for (int j = 0; j < RH; ++j) asm volatile("" : "+v"(raw[j]));
+            // the clamped addresses of the last row and column of tiles read elements that do not count
+            const bool edge = r0 + kWave > p.n || c0 + kWave > p.n;
+            if (!TRANS && qq == q0 - 1) {
+                if (H0 == 0) {           // partial sums: lane = column  ->  lane = row
+                    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                    for (int r = 0; r < kWave; ++r) tile[TRANS ? 0 : wave][TRANS ? 0 : r][TRANS ? 0 : lane] = acc[TRANS ? 0 : r];
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                    T part[4] = {T(0), T(0), T(0), T(0)};
+#pragma unroll
+                    for (int j = 0; j < kWave; ++j) part[j & 3] += tile[TRANS ? 0 : wave][TRANS ? 0 : lane][TRANS ? 0 : j];
+                    b -= (part[0] + part[1]) + (part[2] + part[3]);
+                    __builtin_amdgcn_wave_barrier();
+                }
+#pragma unroll
+                for (int r = 0; r < RH; ++r)
+                    tile[TRANS ? 0 : wave][TRANS ? 0 : H0 + r][TRANS ? 0 : lane] = (c0 + lane < p.n && r0 + H0 + r < p.n) ? raw[r] : T(0);
+                if (H0 + RH == kWave) {
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                    // my row of the tile, into the registers the partial sums have left; before the wait
+#pragma unroll
+                    for (int j = 0; j < kWave; ++j) acc[TRANS ? 0 : j] = tile[TRANS ? 0 : wave][TRANS ? 0 : lane][TRANS ? 0 : j];
+#pragma unroll
+                    for (int j = 0; j < kWave; ++j) asm volatile("" : "+v"(acc[TRANS ? 0 : j]));
+                    wait_x(qq, xv, got);
+                    T part[4] = {T(0), T(0), T(0), T(0)};
+#pragma unroll
+                    for (int j = 0; j < kWave; ++j) part[j & 3] = fmad(acc[TRANS ? 0 : j], lane_bcast(xv, j), part[j & 3]);
+                    b -= (part[0] + part[1]) + (part[2] + part[3]);
+                }
+                return;
+            }
+            wait_x(qq, xv, got);
+            if (TRANS) {
+                if (edge) {
+#pragma unroll
+                    for (int j = 0; j < RH; ++j) raw[j] = (active && c0 + H0 + j < p.n) ? raw[j] : T(0);
+                }
+                T part[4] = {T(0), T(0), T(0), T(0)};
+#pragma unroll
+                for (int j = 0; j < RH; ++j) part[j & 3] = fmad(raw[j], lane_bcast(xv, H0 + j), part[j & 3]);
+                b -= (part[0] + part[1]) + (part[2] + part[3]);
+            } else {
+                if (edge) {
+#pragma unroll
+                    for (int r = 0; r < RH; ++r) raw[r] = (c0 + lane < p.n && r0 + H0 + r < p.n) ? raw[r] : T(0);
+                }
+#pragma unroll
+                for (int r = 0; r < RH; ++r) acc[TRANS ? 0 : H0 + r] = fmad(raw[r], xv, acc[TRANS ? 0 : H0 + r]);
+            }
+        };
+        int ch = 0;
+        start(0, t0, x0, g0);
+        for (; ch + 1 < nch; ch += 2) {
+            start(ch + 1, t1, x1, g1);
+            use(std::integral_constant<int, 0>(), ch, t0, x0, g0);
+            if (ch + 2 < nch) start(ch + 2, t0, x0, g0);
+            use(std::integral_constant<int, CPT - 1>(), ch + 1, t1, x1, g1);
+        }
+        if (ch < nch) use(std::integral_constant<int, 0>(), ch, t0, x0, g0);
     }
-    if (!kEarly) {
+    if constexpr (!kEarly) {
+        MXB_OWN_ROW();
         if (wants(0)) issue(own_c0(0), pa);
         if (wants(1)) issue(own_c0(1), pb);
     }
+#undef MXB_OWN_ROW
 
-    // ---- my workgroup's own sub-blocks
-    finish(r0, e);
-    T dv = T(1);
-#pragma unroll
-    for (int j = 0; j < kWave; ++j) dv = (!UNIT && active && j == lane) ? e[j] : dv;
-    const T rinv = T(1) / dv;            // 1 in the lanes past the end: their zeros stay zeros
-#pragma unroll
-    for (int j = 0; j < kWave; ++j) {    // my row scaled by 1 / T[i][i], as in the blocked kernel
-        const bool inside = OPLOWER ? j < lane : j > lane;
-        e[j] = inside ? (UNIT ? e[j] : e[j] * rinv) : T(0);
-    }
-    // One step: sub-block q0 + s is solved by wavefront s and published at once; the wavefronts
-    // after it subtract its part.  Only LDS traffic is fenced around the barrier: the tiles still
-    // in flight from global memory must not be waited for there.
+    // ---- my workgroup's own sub-blocks.  One step: sub-block q0 + s is solved by wavefront s and
+    // handed on at once, while the wavefronts after it get their tile ready; after the barrier
+    // they subtract its part.  Only LDS traffic is fenced around the barrier: the tiles still in
+    // flight from global memory must not be waited for there.
     auto step = [&](int s, T (&tile_s)[kWave]) {
         if (q0 + s >= p.nsub) return;    // the same for the whole workgroup
         if (wave == s) {
@@ -327,19 +464,15 @@ __global__ void __launch_bounds__(kChainWaves* kWave) trsv_chain_kernel(const Ch
                 c = fmad(-e[j], lane_bcast(c, j), c);
             }
             xs[wave * kWave + lane] = c;
+            Handover<T>::put(p.solved + ((int64_t)q * kWave + lane) * HW, c);     // all 64, zeros past the end
             if (active) p.x[(int64_t)i * p.incx] = c;
+        } else if (wants(s)) {
+            finish(own_c0(s), tile_s);
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-        if (wave == s) {
-            // publish for the other workgroups once my own workgroup is on its way (it reads LDS):
-            // the 64 solutions first (release at device scope writes them back), then the flag
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-            if (lane == 0) __hip_atomic_store(&p.flags[q0 + s], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-        }
         if (wants(s)) {
-            finish(own_c0(s), tile_s);
             T part[4] = {T(0), T(0), T(0), T(0)};
 #pragma unroll
             for (int j = 0; j < kWave; ++j) part[j & 3] = fmad(tile_s[j], xs[s * kWave + j], part[j & 3]);
@@ -354,19 +487,24 @@ __global__ void __launch_bounds__(kChainWaves* kWave) trsv_chain_kernel(const Ch
     step(3, pb);
 }
 
-// Words of workspace the one-kernel solve needs: a flag per sub-block, the ticket, the error word.
-inline int64_t chain_words(int64_t n) { return ceil_div(n, (int64_t)kWave) + 2; }
+// Workspace of the one-kernel solve: the hand-over words of every sub-block, then the ticket and
+// the error word.
+template <typename T>
+inline size_t chain_bytes(int64_t n) { return (size_t)ceil_div(n, (int64_t)kWave) * kWave * Handover<T>::kWords * 8 + 2 * sizeof(int); }
 
 template <typename T>
 int trsv_chain(mxb_handle_t h, bool op_lower, bool no_trans, bool unit, int64_t n, const T* A, int64_t lda, T* x0, int64_t incx)
 {
-    const int64_t words = chain_words(n);
-    if (!h->ws || h->ws_bytes < (size_t)words * sizeof(int)) return MXB_ERR_WORKSPACE;
-    int* flags = static_cast<int*>(h->ws);
-    hipLaunchKernelGGL(trsv_chain_init_kernel, dim3((unsigned)ceil_div(words, (int64_t)256)), dim3(256), 0, h->stream, flags, (int)words);
+    const size_t bytes = chain_bytes<T>(n);
+    if (!h->ws || h->ws_bytes < bytes) return MXB_ERR_WORKSPACE;
+    const int64_t words = (int64_t)(bytes / sizeof(int));
+    unsigned long long* solved = static_cast<unsigned long long*>(h->ws);
+    int* control = static_cast<int*>(h->ws) + (words - 2);
+    hipLaunchKernelGGL(trsv_chain_init_kernel, dim3((unsigned)ceil_div(words, (int64_t)256)), dim3(256), 0, h->stream,
+                       static_cast<int*>(h->ws), (int)words);
     int st = launch_status();
     if (st != MXB_OK) return st;
-    const ChainArgs<T> a{(int)n, (int)ceil_div(n, (int64_t)kWave), A, lda, x0, incx, flags, kChainSpinLimit};
+    const ChainArgs<T> a{(int)n, (int)ceil_div(n, (int64_t)kWave), A, lda, x0, incx, solved, control, kChainSpinLimit};
     const dim3 grid((unsigned)ceil_div((int64_t)a.nsub, (int64_t)kChainWaves)), block(kChainWaves * kWave);
 #define MXB_CHAIN(LOW_, TR_)                                                                                          \
     if (unit) hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, true>), grid, block, 0, h->stream, a);              \
@@ -400,7 +538,7 @@ int trsv(mxb_handle_t h, int layout, int uplo, int trans, int diag, int64_t n, c
     constexpr int NW = sizeof(T) == 4 ? 8 : 4;        // 64 registers of triangle + 64 of prefetch per lane: 512 / 256 unknowns
     constexpr int64_t NB = NW * kWave;
     T* x0 = vec_base(x, n, incx);
-    if (n >= option(h, MXB_OPT_TRSV_CHAIN_MIN) && n < ((int64_t)1 << 31) - kWave)
+    if (n >= option(h, MXB_OPT_TRSV_CHAIN_MIN) && n < ((int64_t)1 << 24))      // 32-bit counts in the chained kernel; no such matrix fits the device anyway
         return trsv_chain<T>(h, op_lower, no_trans, unit, n, A, lda, x0, incx);
     const int64_t nblocks = ceil_div(n, NB);
     for (int64_t step = 0; step < nblocks; ++step) {

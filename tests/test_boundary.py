@@ -215,6 +215,7 @@ def test_workspace_bound(B):
     assert B.mxb_workspace_bytes(B.GEMV, 4, 1 << 20, 256) == B.mxb_workspace_bytes(B.GEMV, 4, 256, 1 << 20)
     assert B.mxb_workspace_bytes(B.TRMV, 4, 0, 16384) >= 16384 * 4
     assert 0 < B.mxb_workspace_bytes(B.SYMV, 4, 0, 16384) <= 0.03 * 16384 * 16384 * 4
+    assert B.mxb_workspace_bytes(B.TRSV, 4, 0, 1) >= 64 * 8 + 8 and B.mxb_workspace_bytes(B.TRSV, 8, 0, 16385) >= 16448 * 16 + 8
     assert B.mxb_workspace_bytes(B.GEMV, 3, 4, 4) == 0 and B.mxb_workspace_bytes(B.GEMV, 4, -1, 4) == 0
 
 
