@@ -61,6 +61,7 @@ typedef enum {
 #define MXB_ERR_HANDLE 1          /* null or destroyed handle */
 #define MXB_ERR_WORKSPACE 2       /* workspace missing or smaller than this call needs */
 #define MXB_ERR_NOT_IMPLEMENTED 3
+#define MXB_ERR_TIMEOUT 4         /* a kernel gave up a bounded wait (mxb_last_status) */
 #define MXB_ERR_HIP_BASE 1000     /* + hipError_t of a failed launch */
 
 /* ---- handle ------------------------------------------------------------------------------ */
@@ -93,10 +94,18 @@ typedef enum {
     MXB_OPT_TRI_DIAG_WEIGHT = 9,    /* triangle sweep: cost of a row that crosses the diagonal, in quarters of a row that does not (1..8) */
     MXB_OPT_SYMV_SMALL_MAX = 10,    /* symv: largest n that takes the single-kernel path (every element read twice, no workspace) */
     MXB_OPT_TRSV_CHAIN_MIN = 11,    /* trsv: smallest n solved by the single chained kernel instead of one launch per block */
-    MXB_OPT_COUNT = 12
+    MXB_OPT_TRSV_SPIN_LIMIT = 12,   /* chained trsv: polls of one hand-over word before a wavefront gives up (default 2^24: tens of seconds) */
+    MXB_OPT_COUNT = 13
 } mxb_option_t;
 int mxb_set_option(mxb_handle_t h, int option, int64_t value);
 int64_t mxb_get_option(mxb_handle_t h, int option);
+
+/* Waits for the handle's stream and reports what only the device knows about the last call on
+ * this handle that can fail there: MXB_OK, or MXB_ERR_TIMEOUT if the last chained trsv gave up
+ * a bounded wait (x is then unfinished).  Valid until the next call on the handle that uses the
+ * workspace, or mxb_set_workspace.  Synchronises: not for use under stream capture.  Other
+ * routines cannot fail on the device and leave MXB_OK. */
+int mxb_last_status(mxb_handle_t h);
 
 /* ---- level 1 (Sec. 6.2.1) ------------------------------------------------------------------ */
 
@@ -208,8 +217,9 @@ int mxb_dtrmv(mxb_handle_t h, mxb_layout_t layout, mxb_uplo_t uplo, mxb_trans_t 
  * the product is transposed (as gemv does).  From there on: one kernel whose workgroups solve 256
  * unknowns each, in order, and hand the solved values on through the workspace (16 bytes per
  * unknown at most, cleared by the call; MXB_ERR_WORKSPACE if it is smaller).  A workgroup waits
- * for solved values a bounded number of polls only; the bound (tens of seconds) is reached only
- * if the device stops scheduling the workgroup that owns them, and x is then left unfinished.
+ * for solved values a bounded number of polls only (MXB_OPT_TRSV_SPIN_LIMIT); the bound (tens of
+ * seconds) is reached only if the device stops scheduling the workgroup that owns them; x is
+ * then left unfinished and mxb_last_status reports MXB_ERR_TIMEOUT.
  * mxb_workspace_bytes(MXB_TRSV, elem_size, 0, n) covers both paths.
  * Quick return: n == 0.
  * Errors: as mxb_strmv. */

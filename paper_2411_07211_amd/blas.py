@@ -37,10 +37,11 @@ NO_TRANS, TRANS = 111, 112
 UPPER, LOWER = 121, 122
 NON_UNIT, UNIT = 131, 132
 AXPY, SCAL, DOT, ASUM, NRM2, GEMV, TRMV, SYMV, GER, GEMV_BATCHED, TRSV = range(1, 12)
-OK, ERR_HANDLE, ERR_WORKSPACE, ERR_NOT_IMPLEMENTED, ERR_HIP_BASE = 0, 1, 2, 3, 1000
+OK, ERR_HANDLE, ERR_WORKSPACE, ERR_NOT_IMPLEMENTED, ERR_TIMEOUT, ERR_HIP_BASE = 0, 1, 2, 3, 4, 1000
 (OPT_L1_BLOCKS_PER_CU, OPT_REDUCE_BLOCKS, OPT_ROWDOT_XCHUNK, OPT_ROWDOT_BLOCKS_PER_CU,
  OPT_COLACC_TARGET_BLOCKS, OPT_COLACC_MIN_ROWS, OPT_SYMV_TARGET_BLOCKS, OPT_GER_ROWS_PER_BLOCK,
- OPT_SYMV_TILE_VECTORS, OPT_TRI_DIAG_WEIGHT, OPT_SYMV_SMALL_MAX, OPT_TRSV_CHAIN_MIN) = range(12)
+ OPT_SYMV_TILE_VECTORS, OPT_TRI_DIAG_WEIGHT, OPT_SYMV_SMALL_MAX, OPT_TRSV_CHAIN_MIN,
+ OPT_TRSV_SPIN_LIMIT) = range(13)
 
 _i64, _int, _ptr, _sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
 _f, _d = ctypes.c_float, ctypes.c_double
@@ -60,6 +61,7 @@ _set_workspace = _sig("mxb_set_workspace", _int, _ptr, _ptr, _sz)
 _workspace_bytes = _sig("mxb_workspace_bytes", _sz, _int, _int, _i64, _i64)
 _set_option = _sig("mxb_set_option", _int, _ptr, _int, _i64)
 _get_option = _sig("mxb_get_option", _i64, _ptr, _int)
+_last_status = _sig("mxb_last_status", _int, _ptr)
 _probe_copy = _sig("mxb_probe_copy", _int, _ptr, _sz, _ptr, _ptr)
 _probe_read = _sig("mxb_probe_read", _int, _ptr, _sz, _ptr)
 _fn = {}
@@ -129,6 +131,10 @@ def mxb_set_option(h, option, value):
 
 def mxb_get_option(h, option):
     return _get_option(h, option)
+
+
+def mxb_last_status(h):
+    return _last_status(h)
 
 
 def _bytes(t):
@@ -326,6 +332,9 @@ class Context:
 
     def set_option(self, option, value):
         check(mxb_set_option(self.h, option, value), "mxb_set_option")
+
+    def last_status(self):
+        return mxb_last_status(self.h)
 
     def close(self):
         if getattr(self, "h", None):

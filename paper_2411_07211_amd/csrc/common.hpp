@@ -14,6 +14,7 @@ struct mxb_ctx {
     void* ws;
     size_t ws_bytes;
     int64_t opt[MXB_OPT_COUNT];
+    const int* device_status;   // error word of the last call that can fail on the device (in the workspace), or null
 };
 
 namespace mxb {

@@ -72,6 +72,7 @@ int mxb_create(mxb_handle_t* h)
     c->ws = nullptr;
     c->ws_bytes = 0;
     for (int o = 0; o < MXB_OPT_COUNT; ++o) c->opt[o] = 0;
+    c->device_status = nullptr;
     *h = c;
     return MXB_OK;
 }
@@ -98,6 +99,7 @@ int mxb_set_workspace(mxb_handle_t h, void* dev_ptr, size_t bytes)
     if (!dev_ptr && bytes != 0) return -2;
     h->ws = dev_ptr;
     h->ws_bytes = bytes;
+    h->device_status = nullptr;
     return MXB_OK;
 }
 
@@ -113,6 +115,17 @@ int64_t mxb_get_option(mxb_handle_t h, int option)
 {
     if (!mxb::handle_ok(h) || option < 0 || option >= MXB_OPT_COUNT) return 0;
     return mxb::option(h, option);
+}
+
+int mxb_last_status(mxb_handle_t h)
+{
+    if (!mxb::handle_ok(h)) return MXB_ERR_HANDLE;
+    int word = 0;
+    hipError_t e = hipSuccess;
+    if (h->device_status) e = hipMemcpyAsync(&word, h->device_status, sizeof(int), hipMemcpyDeviceToHost, h->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(h->stream);
+    if (e != hipSuccess) return MXB_ERR_HIP_BASE + (int)e;
+    return word != 0 ? MXB_ERR_TIMEOUT : MXB_OK;
 }
 
 size_t mxb_workspace_bytes(int routine, int elem_size, int64_t m, int64_t n)

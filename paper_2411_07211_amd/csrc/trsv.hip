@@ -226,7 +226,6 @@ struct ChainArgs {
 };
 
 constexpr int kChainWaves = 4;
-constexpr int kChainSpinLimit = 1 << 24;      // polls of one flag before a wavefront gives up: tens of seconds
 
 __global__ void __launch_bounds__(256) trsv_chain_init_kernel(int* words, int count)
 {
@@ -504,7 +503,10 @@ int trsv_chain(mxb_handle_t h, bool op_lower, bool no_trans, bool unit, int64_t 
                        static_cast<int*>(h->ws), (int)words);
     int st = launch_status();
     if (st != MXB_OK) return st;
-    const ChainArgs<T> a{(int)n, (int)ceil_div(n, (int64_t)kWave), A, lda, x0, incx, solved, control, kChainSpinLimit};
+    h->device_status = control + 1;
+    int64_t spin_limit = option(h, MXB_OPT_TRSV_SPIN_LIMIT);
+    if (spin_limit > (1 << 30)) spin_limit = 1 << 30;
+    const ChainArgs<T> a{(int)n, (int)ceil_div(n, (int64_t)kWave), A, lda, x0, incx, solved, control, (int)spin_limit};
     const dim3 grid((unsigned)ceil_div((int64_t)a.nsub, (int64_t)kChainWaves)), block(kChainWaves * kWave);
 #define MXB_CHAIN(LOW_, TR_)                                                                                          \
     if (unit) hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, true>), grid, block, 0, h->stream, a);              \
@@ -540,6 +542,7 @@ int trsv(mxb_handle_t h, int layout, int uplo, int trans, int diag, int64_t n, c
     T* x0 = vec_base(x, n, incx);
     if (n >= option(h, MXB_OPT_TRSV_CHAIN_MIN) && n < ((int64_t)1 << 24))      // 32-bit counts in the chained kernel; no such matrix fits the device anyway
         return trsv_chain<T>(h, op_lower, no_trans, unit, n, A, lda, x0, incx);
+    h->device_status = nullptr;                      // nothing in the blocked path waits on the device
     const int64_t nblocks = ceil_div(n, NB);
     for (int64_t step = 0; step < nblocks; ++step) {
         const int64_t k = op_lower ? step : nblocks - 1 - step;

@@ -126,7 +126,7 @@ def test_gemv_deterministic_and_geometry_invariant(blas, ctx, dt):
             for opts in ({}, {}, {blas.OPT_ROWDOT_XCHUNK: 256, blas.OPT_COLACC_TARGET_BLOCKS: 64},
                          {blas.OPT_ROWDOT_XCHUNK: 1024, blas.OPT_ROWDOT_BLOCKS_PER_CU: 1, blas.OPT_COLACC_TARGET_BLOCKS: 4096,
                           blas.OPT_COLACC_MIN_ROWS: 8}):
-                for o in range(12):
+                for o in range(13):
                     ctx.set_option(o, 0)
                 for o, v in opts.items():
                     ctx.set_option(o, v)
@@ -136,7 +136,7 @@ def test_gemv_deterministic_and_geometry_invariant(blas, ctx, dt):
                 check_close(outs[-1], ref, D, lenx, f"gemv trans={trans} opts={opts}")
             assert outs[0].tobytes() == outs[1].tobytes(), "same launch geometry must give the same bits"
     finally:
-        for o in range(12):
+        for o in range(13):
             ctx.set_option(o, 0)
 
 
@@ -530,6 +530,42 @@ def test_trsv(blas, ctx, dt, layout, uplo, trans, diag):
         finally:
             ctx.set_option(blas.OPT_TRSV_CHAIN_MIN, 0)
     trsv_case(blas, ctx, dt, layout, uplo, trans, diag, 5000, 0, 1)      # the default choice at a size with many workgroups
+
+
+def test_trsv_bounded_wait_reports_timeout(blas, ctx):
+    """A wait that the host makes too short to succeed: every wavefront still leaves the kernel, the
+    call returns, mxb_last_status names the timeout, and the next call with the default limit is right."""
+    dt, n, seed = np.float32, 4096, 23
+    A = trsv_matrix(dt, n, O.LOWER, O.NON_UNIT, seed, False)
+    Ab, lda = matrix_buffer(A, O.ROW_MAJOR, 0)
+    bb = synth.strided(synth.uniform(seed, 1, n, dt), 1)
+    O.trmv(O.ROW_MAJOR, O.LOWER, O.NO_TRANS, O.NON_UNIT, n, Ab, lda, bb, 1)
+    ref = bb.copy()
+    D = O.trsv(O.ROW_MAJOR, O.LOWER, O.NO_TRANS, O.NON_UNIT, n, Ab, lda, ref, 1, want_D=True)
+    Ad = mat_dev(Ab)
+
+    def solve():
+        dx = to_dev(bb)
+        st = blas.mxb_strsv(ctx.h, O.ROW_MAJOR, O.LOWER, O.NO_TRANS, O.NON_UNIT, n, Ad, lda, dx, 1)
+        assert st == 0, f"status {st}"
+        return dx
+
+    try:
+        ctx.set_option(blas.OPT_TRSV_CHAIN_MIN, 1)
+        ctx.set_option(blas.OPT_TRSV_SPIN_LIMIT, 1)
+        solve()
+        assert ctx.last_status() == blas.ERR_TIMEOUT
+        ctx.set_option(blas.OPT_TRSV_SPIN_LIMIT, 0)
+        dx = solve()
+        assert ctx.last_status() == blas.OK
+        check_close(to_host(dx), ref, D, n, "trsv after a timed-out call")
+        ctx.set_option(blas.OPT_TRSV_CHAIN_MIN, 1 << 30)      # the blocked path has no waits and says so
+        dx = solve()
+        assert ctx.last_status() == blas.OK
+        check_close(to_host(dx), ref, D, n, "trsv, blocked, after a timed-out call")
+    finally:
+        ctx.set_option(blas.OPT_TRSV_CHAIN_MIN, 0)
+        ctx.set_option(blas.OPT_TRSV_SPIN_LIMIT, 0)
 
 
 # ----------------------------------------------------------------------------- skinny matrices
