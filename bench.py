@@ -287,9 +287,12 @@ def sweep(B, ctx, torch):
         rec("strmv_un", t, tri, lambda: B.mxb_strmv(h, B.ROW_MAJOR, B.UPPER, B.NO_TRANS, B.NON_UNIT, n, A, n, xt, 1), reset)
         rec("strmv_lt", t, tri, lambda: B.mxb_strmv(h, B.ROW_MAJOR, B.LOWER, B.TRANS, B.NON_UNIT, n, A, n, xt, 1), reset)
     # trsv wants a well-conditioned triangle: unit diagonal, small off-diagonal elements
-    T = torch.rand(4096 * 4096, dtype=f32, device=dev).mul_(1e-4)
-    for n in (256, 1024, 4096):
-        rec("strsv_lu", f"{n}x{n}", 4 * (n * (n + 1) // 2), lambda: B.mxb_strsv(h, B.ROW_MAJOR, B.LOWER, B.NO_TRANS, B.UNIT, n, T, n, xt, 1), reset)
+    T = torch.rand(NS * NS, dtype=f32, device=dev).mul_(1e-4)
+    for n in (256, 1024, 4096, 16384):
+        tri = 4 * (n * (n + 1) // 2)
+        rec("strsv_lu", f"{n}x{n}", tri, lambda: B.mxb_strsv(h, B.ROW_MAJOR, B.LOWER, B.NO_TRANS, B.UNIT, n, T, n, xt, 1), reset)
+        rec("strsv_ltu", f"{n}x{n}", tri, lambda: B.mxb_strsv(h, B.ROW_MAJOR, B.LOWER, B.TRANS, B.UNIT, n, T, n, xt, 1), reset)
+    del T
     # skinny matrices (Sec. 6.2.2): N = 40, M powers of 2 and 3
     for M in (2 ** 10, 3 ** 7, 2 ** 13, 3 ** 9, 2 ** 16, 3 ** 11, 2 ** 19, 3 ** 13, 2 ** 22):
         t, full = f"{M}x40", 4 * M * 40
