@@ -426,7 +426,7 @@ def main():
         write_traffic(*args.traffic_from)
         return
     if args.gpus != 1:
-        print(f"bench.py: this build measures one GPU only (got --gpus {args.gpus}); run with --gpus 1", file=sys.stderr)
+        print(f"bench.py: this library runs on one GPU only (got --gpus {args.gpus}); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
     import torch
     from paper_2411_07211_amd import blas as B
