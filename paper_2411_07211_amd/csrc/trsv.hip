@@ -238,7 +238,11 @@ __global__ void __launch_bounds__(kChainWaves* kWave) trsv_chain_kernel(const Ch
 {
     constexpr int NW = kChainWaves;
     __shared__ T xs[NW * kWave];
-    __shared__ T tile[TRANS ? 1 : NW][TRANS ? 1 : kWave][TRANS ? 1 : kWave + 1];   // per-wavefront transposition buffer
+    // per-wavefront buffer: turns tiles when not transposed; holds the wavefront's finished diagonal
+    // rows in double precision when transposed (where nothing needs turning and the registers are short)
+    constexpr bool kPark = sizeof(T) == 8 && TRANS;
+    constexpr bool kTile = !TRANS || kPark;
+    __shared__ T tile[kTile ? NW : 1][kTile ? kWave : 1][kTile ? kWave + 1 : 1];
     __shared__ int my_ticket;
     constexpr int HW = Handover<T>::kWords;
     int* const ticket = p.control;
@@ -296,8 +300,9 @@ __global__ void __launch_bounds__(kChainWaves* kWave) trsv_chain_kernel(const Ch
     // Two of them are in flight at any time, in pa and pb by turns: tile s + 2 is asked for when
     // tile s has been used, so that a tile has two steps to arrive.  In single precision the first
     // two are asked for right away and travel during the whole first phase; in double precision
-    // the registers do not allow that and they are asked for when that phase is over.
-    constexpr bool kEarly = sizeof(T) == 4;
+    // the registers allow that only when the diagonal rows are parked in LDS, otherwise they are
+    // asked for when that phase is over.
+    constexpr bool kEarly = sizeof(T) == 4 || kPark;
     T pa[kWave], pb[kWave];
     auto own_c0 = [&](int s) { return actual(q0 + s) * kWave; };
     auto wants = [&](int s) { return have && wave > s && q0 + s < p.nsub; };
@@ -306,11 +311,11 @@ __global__ void __launch_bounds__(kChainWaves* kWave) trsv_chain_kernel(const Ch
         if (wants(1)) issue(own_c0(1), pb);
     }
 
-    // My row of the diagonal tile, scaled by 1 / T[i][i] as in the blocked kernel.  In single
-    // precision before the wait for the earlier workgroups, which is where a workgroup has time
-    // to spare; in double precision after it: the finished row would not stay in registers over
-    // the first phase, and fetching it back one element at a time inside the solve costs far
-    // more than finishing it late.
+    // My row of the diagonal tile, scaled by 1 / T[i][i] as in the blocked kernel.  Before the
+    // wait for the earlier workgroups, which is where a workgroup has time to spare: in single
+    // precision it stays in registers; in double precision it would not (the compiler would fetch
+    // it back from scratch memory one element at a time inside the solve), so it is parked in LDS
+    // when transposed and finished after the first phase when not.
     // (A macro, not a lambda: wrapped in one more closure the register arrays end up in scratch memory.)
     T rinv = T(1);
 #define MXB_OWN_ROW()                                                                                  \
@@ -326,6 +331,10 @@ __global__ void __launch_bounds__(kChainWaves* kWave) trsv_chain_kernel(const Ch
         }                                                                                              \
     } while (0)
     if constexpr (kEarly) MXB_OWN_ROW();
+    if constexpr (kPark) {
+#pragma unroll
+        for (int j = 0; j < kWave; ++j) tile[wave][j][lane] = e[j];      // read back by this lane only
+    }
 
     // ---- the unknowns of earlier workgroups: tiles 0 .. q0 - 1 of my block row, in solving order.
     // A tile travels in pieces of RH rows (columns if transposed), two pieces in flight by turns;
@@ -460,7 +469,10 @@ __global__ void __launch_bounds__(kChainWaves* kWave) trsv_chain_kernel(const Ch
 #pragma unroll
             for (int jj = 0; jj < kWave; ++jj) {
                 const int j = OPLOWER ? jj : kWave - 1 - jj;
-                c = fmad(-e[j], lane_bcast(c, j), c);
+                T ej;
+                if constexpr (kPark) ej = tile[wave][j][lane];
+                else ej = e[j];
+                c = fmad(-ej, lane_bcast(c, j), c);
             }
             xs[wave * kWave + lane] = c;
             Handover<T>::put(p.solved + ((int64_t)q * kWave + lane) * HW, c);     // all 64, zeros past the end
