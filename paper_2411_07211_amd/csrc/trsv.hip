@@ -225,7 +225,6 @@ struct ChainArgs {
     int spin_limit;
 };
 
-constexpr int kChainWaves = 4;
 
 __global__ void __launch_bounds__(256) trsv_chain_init_kernel(int* words, int count)
 {
@@ -233,16 +232,37 @@ __global__ void __launch_bounds__(256) trsv_chain_init_kernel(int* words, int co
     if (k < count) words[k] = 0;
 }
 
-template <typename T, bool OPLOWER, bool TRANS, bool UNIT>
-__global__ void __launch_bounds__(kChainWaves* kWave) trsv_chain_kernel(const ChainArgs<T> p)
+// raw[k] = A[min(first + k, last)][col], k < COUNT; first is the same for the whole wavefront.  One
+// pointer runs down the rows and stops at the last one.  The empty asm makes first opaque, which
+// keeps the compiler from forming all COUNT row addresses ahead of the loops around the call and
+// holding them in scalar registers (it then spills hundreds of them).
+template <typename T, int COUNT>
+__device__ __forceinline__ void load_rows(const T* A, int64_t lda, int first, int last, int col, T (&raw)[COUNT])
 {
-    constexpr int NW = kChainWaves;
-    __shared__ T xs[NW * kWave];
-    // per-wavefront buffer: turns tiles when not transposed; holds the wavefront's finished diagonal
-    // rows in double precision when transposed (where nothing needs turning and the registers are short)
-    constexpr bool kPark = sizeof(T) == 8 && TRANS;
-    constexpr bool kTile = !TRANS || kPark;
-    __shared__ T tile[kTile ? NW : 1][kTile ? kWave : 1][kTile ? kWave + 1 : 1];
+    asm volatile("" : "+s"(first));
+    const T* row = A + (int64_t)min(first, last) * lda;
+#pragma unroll
+    for (int k = 0; k < COUNT; ++k) {
+        raw[k] = row[col];
+        row += first + k < last ? lda : 0;
+    }
+}
+
+// Wavefronts per workgroup of the chained kernel: 4, but 2 in double precision when not
+// transposed, where LDS has to hold the turning buffer and the parked diagonal rows.
+template <typename T, bool TRANS>
+constexpr int chain_waves() { return (sizeof(T) == 8 && !TRANS) ? 2 : 4; }
+
+template <typename T, bool OPLOWER, bool TRANS, bool UNIT>
+__global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_kernel(const ChainArgs<T> p)
+{
+    constexpr int NW = chain_waves<T, TRANS>();
+    __shared__ __attribute__((aligned(16))) T xs[NW * kWave];
+    // per-wavefront buffers: one turns tiles when not transposed; in double precision, where the
+    // registers are short, another holds the wavefront's finished diagonal rows
+    constexpr bool kPark = sizeof(T) == 8;
+    __shared__ T tile[TRANS ? 1 : NW][TRANS ? 1 : kWave][TRANS ? 1 : kWave + 1];
+    __shared__ T park[kPark ? NW : 1][kPark ? kWave : 1][kPark ? kWave + 1 : 1];
     __shared__ int my_ticket;
     constexpr int HW = Handover<T>::kWords;
     int* const ticket = p.control;
@@ -251,7 +271,7 @@ __global__ void __launch_bounds__(kChainWaves* kWave) trsv_chain_kernel(const Ch
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (threadIdx.x == 0) my_ticket = atomicAdd(ticket, 1);
     __syncthreads();
-    const int q0 = my_ticket * NW;       // my workgroup's sub-blocks q0 .. q0 + 3, counted in solving order
+    const int q0 = my_ticket * NW;       // my workgroup's sub-blocks q0 .. q0 + NW - 1, counted in solving order
     const int q = q0 + wave;
     const bool have = q < p.nsub;        // false: a wavefront past the last sub-block only keeps the barriers company
     auto actual = [&](int qq) { return OPLOWER ? qq : p.nsub - 1 - qq; };      // sub-block number in the matrix
@@ -263,15 +283,8 @@ __global__ void __launch_bounds__(kChainWaves* kWave) trsv_chain_kernel(const Ch
     // issue() starts the 64 loads (addresses clamped into the matrix: no predicate), finish() pins
     // them, zeroes what lies outside the matrix and, if not transposed, turns the tile through LDS.
     auto issue = [&](int c0, T (&raw)[kWave]) {
-        if (TRANS) {
-            const int ic = min(i, last);
-#pragma unroll
-            for (int j = 0; j < kWave; ++j) raw[j] = (p.A + (int64_t)min(c0 + j, last) * p.lda)[ic];
-        } else {
-            const int cc = min(c0 + lane, last);
-#pragma unroll
-            for (int r = 0; r < kWave; ++r) raw[r] = (p.A + (int64_t)min(r0 + r, last) * p.lda)[cc];
-        }
+        if (TRANS) load_rows(p.A, p.lda, c0, last, min(i, last), raw);
+        else load_rows(p.A, p.lda, r0, last, min(c0 + lane, last), raw);
     };
     auto finish = [&](int c0, T (&raw)[kWave]) {
 #pragma unroll
@@ -297,43 +310,30 @@ __global__ void __launch_bounds__(kChainWaves* kWave) trsv_chain_kernel(const Ch
     issue(r0, e);                        // my tile on the diagonal
 
     // Tile s of my own workgroup (s = 0 .. wave - 1) multiplies the sub-block solved in step s.
-    // Two of them are in flight at any time, in pa and pb by turns: tile s + 2 is asked for when
-    // tile s has been used, so that a tile has two steps to arrive.  In single precision the first
-    // two are asked for right away and travel during the whole first phase; in double precision
-    // the registers allow that only when the diagonal rows are parked in LDS, otherwise they are
-    // asked for when that phase is over.
-    constexpr bool kEarly = sizeof(T) == 4 || kPark;
+    // Two of them are in flight at any time, in pa and pb by turns: the first two are asked for
+    // right away and travel during the whole first phase, tile s + 2 is asked for when tile s has
+    // been used, so that a tile has two steps to arrive.
     T pa[kWave], pb[kWave];
     auto own_c0 = [&](int s) { return actual(q0 + s) * kWave; };
-    auto wants = [&](int s) { return have && wave > s && q0 + s < p.nsub; };
-    if (kEarly) {
-        if (wants(0)) issue(own_c0(0), pa);
-        if (wants(1)) issue(own_c0(1), pb);
-    }
+    auto wants = [&](int s) { return s < NW - 1 && have && wave > s && q0 + s < p.nsub; };
+    if (wants(0)) issue(own_c0(0), pa);
+    if (wants(1)) issue(own_c0(1), pb);
 
     // My row of the diagonal tile, scaled by 1 / T[i][i] as in the blocked kernel.  Before the
     // wait for the earlier workgroups, which is where a workgroup has time to spare: in single
     // precision it stays in registers; in double precision it would not (the compiler would fetch
-    // it back from scratch memory one element at a time inside the solve), so it is parked in LDS
-    // when transposed and finished after the first phase when not.
-    // (A macro, not a lambda: wrapped in one more closure the register arrays end up in scratch memory.)
-    T rinv = T(1);
-#define MXB_OWN_ROW()                                                                                  \
-    do {                                                                                               \
-        finish(r0, e);                                                                                 \
-        T dv = T(1);                                                                                   \
-        _Pragma("unroll") for (int j = 0; j < kWave; ++j) dv = (!UNIT && active && j == lane) ? e[j] : dv; \
-        rinv = T(1) / dv; /* 1 in the lanes past the end: their zeros stay zeros */                    \
-        _Pragma("unroll") for (int j = 0; j < kWave; ++j) {                                            \
-            const bool inside = OPLOWER ? j < lane : j > lane;                                         \
-            e[j] = inside ? (UNIT ? e[j] : e[j] * rinv) : T(0);                                        \
-            asm volatile("" : "+v"(e[j])); /* here, not when the solve needs it */                     \
-        }                                                                                              \
-    } while (0)
-    if constexpr (kEarly) MXB_OWN_ROW();
-    if constexpr (kPark) {
+    // it back from scratch memory one element at a time inside the solve), so it is parked in LDS.
+    finish(r0, e);
+    T dv = T(1);
 #pragma unroll
-        for (int j = 0; j < kWave; ++j) tile[wave][j][lane] = e[j];      // read back by this lane only
+    for (int j = 0; j < kWave; ++j) dv = (!UNIT && active && j == lane) ? e[j] : dv;
+    const T rinv = T(1) / dv;            // 1 in the lanes past the end: their zeros stay zeros
+#pragma unroll
+    for (int j = 0; j < kWave; ++j) {
+        const bool inside = OPLOWER ? j < lane : j > lane;
+        e[j] = inside ? (UNIT ? e[j] : e[j] * rinv) : T(0);
+        if constexpr (kPark) park[wave][j][lane] = e[j];      // read back by this lane only
+        else asm volatile("" : "+v"(e[j]));                   // here, not when the solve needs it
     }
 
     // ---- the unknowns of earlier workgroups: tiles 0 .. q0 - 1 of my block row, in solving order.
@@ -370,15 +370,8 @@ __global__ void __launch_bounds__(kChainWaves* kWave) trsv_chain_kernel(const Ch
         bool g0, g1;
         auto start = [&](int ch, T (&raw)[RH], T& xv, bool& got) {
             const int c0 = actual(ch / CPT) * kWave, h0 = (ch % CPT) * RH;
-            if (TRANS) {
-                const int ic = min(i, last);
-#pragma unroll
-                for (int j = 0; j < RH; ++j) raw[j] = (p.A + (int64_t)min(c0 + h0 + j, last) * p.lda)[ic];
-            } else {
-                const int cc = min(c0 + lane, last);
-#pragma unroll
-                for (int r = 0; r < RH; ++r) raw[r] = (p.A + (int64_t)min(r0 + h0 + r, last) * p.lda)[cc];
-            }
+            if (TRANS) load_rows(p.A, p.lda, c0 + h0, last, min(i, last), raw);
+            else load_rows(p.A, p.lda, r0 + h0, last, min(c0 + lane, last), raw);
             got = look(ch / CPT, xv);
         };
         auto use = [&](auto piece, int ch, T (&raw)[RH], T& xv, bool got) {
@@ -451,12 +444,6 @@ __global__ void __launch_bounds__(kChainWaves* kWave) trsv_chain_kernel(const Ch
         }
         if (ch < nch) use(std::integral_constant<int, 0>(), ch, t0, x0, g0);
     }
-    if constexpr (!kEarly) {
-        MXB_OWN_ROW();
-        if (wants(0)) issue(own_c0(0), pa);
-        if (wants(1)) issue(own_c0(1), pb);
-    }
-#undef MXB_OWN_ROW
 
     // ---- my workgroup's own sub-blocks.  One step: sub-block q0 + s is solved by wavefront s and
     // handed on at once, while the wavefronts after it get their tile ready; after the barrier
@@ -470,7 +457,7 @@ __global__ void __launch_bounds__(kChainWaves* kWave) trsv_chain_kernel(const Ch
             for (int jj = 0; jj < kWave; ++jj) {
                 const int j = OPLOWER ? jj : kWave - 1 - jj;
                 T ej;
-                if constexpr (kPark) ej = tile[wave][j][lane];
+                if constexpr (kPark) ej = park[wave][j][lane];
                 else ej = e[j];
                 c = fmad(-ej, lane_bcast(c, j), c);
             }
@@ -491,11 +478,13 @@ __global__ void __launch_bounds__(kChainWaves* kWave) trsv_chain_kernel(const Ch
             if (wants(s + 2)) issue(own_c0(s + 2), tile_s);
         }
     };
-    static_assert(NW == 4, "four steps, two tile buffers by turns");
+    static_assert(NW == 2 || NW == 4, "two tile buffers by turns");
     step(0, pa);
     step(1, pb);
-    step(2, pa);
-    step(3, pb);
+    if constexpr (NW == 4) {
+        step(2, pa);
+        step(3, pb);
+    }
 }
 
 // Workspace of the one-kernel solve: the hand-over words of every sub-block, then the ticket and
@@ -519,10 +508,13 @@ int trsv_chain(mxb_handle_t h, bool op_lower, bool no_trans, bool unit, int64_t 
     int64_t spin_limit = option(h, MXB_OPT_TRSV_SPIN_LIMIT);
     if (spin_limit > (1 << 30)) spin_limit = 1 << 30;
     const ChainArgs<T> a{(int)n, (int)ceil_div(n, (int64_t)kWave), A, lda, x0, incx, solved, control, (int)spin_limit};
-    const dim3 grid((unsigned)ceil_div((int64_t)a.nsub, (int64_t)kChainWaves)), block(kChainWaves * kWave);
 #define MXB_CHAIN(LOW_, TR_)                                                                                          \
-    if (unit) hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, true>), grid, block, 0, h->stream, a);              \
-    else hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, false>), grid, block, 0, h->stream, a);
+    {                                                                                                                 \
+        constexpr int NW = chain_waves<T, TR_>();                                                                     \
+        const dim3 grid((unsigned)ceil_div((int64_t)a.nsub, (int64_t)NW)), block(NW * kWave);                         \
+        if (unit) hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, true>), grid, block, 0, h->stream, a);          \
+        else hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, false>), grid, block, 0, h->stream, a);              \
+    }
     if (op_lower) { if (no_trans) { MXB_CHAIN(true, false) } else { MXB_CHAIN(true, true) } }
     else { if (no_trans) { MXB_CHAIN(false, false) } else { MXB_CHAIN(false, true) } }
 #undef MXB_CHAIN
