@@ -1,0 +1,169 @@
+"""Sizes at which a 32-bit element index or byte offset would wrap: level-1 vectors of 2^31 + 4099
+elements and a 65536 x 65536 matrix with pitch 65600 (4.3e9 elements, 17 GB).  The oracle cannot
+run such sizes whole in reasonable time, so outputs are checked on samples it computes one by one
+(windows of the vectors around 0, 2^31 and the end; single rows and columns of the matrix,
+among them the rows where the element offset crosses 2^32) and through exact integer identities:
+inputs are small periodic integers, every partial sum is exactly representable, and the results
+must agree bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from parity import bits_equal, to_host
+
+pytestmark = pytest.mark.gpu
+
+N1 = (1 << 31) + 4099
+CHUNK = 1 << 27
+
+
+def pattern_dev(n, period, shift, device, mul=1, start=0):
+    """(((start + i) * mul) % period) - shift as fp32, built in chunks on the device."""
+    out = torch.empty(n, dtype=torch.float32, device=device)
+    for s in range(0, n, CHUNK):
+        e = min(n, s + CHUNK)
+        idx = torch.arange(start + s, start + e, dtype=torch.int64, device=device)
+        out[s:e] = ((idx * mul) % period - shift).to(torch.float32)
+    return out
+
+
+def pattern_host(i0, i1, period, shift, mul=1):
+    idx = np.arange(i0, i1, dtype=np.int64)
+    return ((idx * mul) % period - shift).astype(np.float32)
+
+
+def windows(n):
+    w = 1 << 18
+    return [(0, w), ((1 << 31) - w, min((1 << 31) + w, n)), (n - w, n)]
+
+
+@pytest.fixture(scope="module")
+def big_ctx(blas):
+    need = max(blas.mxb_workspace_bytes(blas.GEMV, 4, 65536, 65536), blas.mxb_workspace_bytes(blas.SYMV, 4, 0, 65536),
+               blas.mxb_workspace_bytes(blas.TRMV, 4, 0, 65536), blas.mxb_workspace_bytes(blas.DOT, 4, 0, N1), 64 << 20)
+    c = blas.Context(device="cuda:0", workspace_bytes=int(need))
+    yield c
+    c.close()
+
+
+def test_level1_beyond_2_to_31_elements(blas, big_ctx):
+    B, h = blas, big_ctx.h
+    dev = torch.device("cuda:0")
+    free, _ = torch.cuda.mem_get_info()
+    if free < 24 << 30:
+        pytest.skip("needs 24 GiB of free device memory")
+    x = pattern_dev(N1, 7, 3, dev)
+    y = pattern_dev(N1, 5, 2, dev)
+    r = torch.zeros(1, dtype=torch.float32, device=dev)
+    ri = torch.zeros(1, dtype=torch.int64, device=dev)
+
+    # reductions: whole periods of 35 (7, 7) elements plus a remainder, each summed by the oracle
+    def by_periods(period, fn):
+        whole, rem = divmod(N1, period)
+        return whole * fn(0, period) + fn(whole * period, whole * period + rem)
+
+    dot_exact = by_periods(35, lambda a, b: int(O.dot(b - a, pattern_host(a, b, 7, 3), 1, pattern_host(a, b, 5, 2), 1)))
+    asum_exact = by_periods(7, lambda a, b: int(O.asum(b - a, pattern_host(a, b, 7, 3), 1)))
+    sq_exact = by_periods(7, lambda a, b: int(O.dot(b - a, pattern_host(a, b, 7, 3), 1, pattern_host(a, b, 7, 3), 1)))
+    assert B.mxb_sdot(h, N1, x, 1, y, 1, r) == 0
+    assert bits_equal(to_host(r)[0], np.float32(dot_exact)), (to_host(r)[0], dot_exact)
+    assert B.mxb_sasum(h, N1, x, 1, r) == 0
+    assert bits_equal(to_host(r)[0], np.float32(asum_exact)), (to_host(r)[0], asum_exact)
+    assert B.mxb_snrm2(h, N1, x, 1, r) == 0
+    assert abs(float(to_host(r)[0]) / np.sqrt(float(sq_exact)) - 1.0) <= 2.0 ** -23
+
+    # the largest magnitude planted beyond index 2^31
+    where = (1 << 31) + 17
+    x[where] = 100.0
+    assert B.mxb_isamax(h, N1, x, 1, ri) == 0
+    assert int(to_host(ri)[0]) == where
+    x[where] = float(pattern_host(where, where + 1, 7, 3)[0])
+
+    # element-wise routines, checked on windows against the oracle run on the same windows
+    assert B.mxb_saxpy(h, N1, 2.0, x, 1, y, 1) == 0
+    assert B.mxb_sscal(h, N1, -3.0, x, 1) == 0
+    for a, b in windows(N1):
+        hx, hy = pattern_host(a, b, 7, 3), pattern_host(a, b, 5, 2)
+        O.axpy(b - a, 2.0, hx, 1, hy, 1)
+        O.scal(b - a, -3.0, hx, 1)
+        assert bits_equal(to_host(y[a:b]), hy), f"saxpy window {a}..{b}"
+        assert bits_equal(to_host(x[a:b]), hx), f"sscal window {a}..{b}"
+    # nothing but the n elements is written: the same sum again, from the closed form of the new values
+    assert B.mxb_sasum(h, N1, x, 1, r) == 0
+    assert bits_equal(to_host(r)[0], np.float32(3 * asum_exact))
+
+
+def test_level2_beyond_2_to_32_elements(blas, big_ctx):
+    B, h = blas, big_ctx.h
+    dev = torch.device("cuda:0")
+    free, _ = torch.cuda.mem_get_info()
+    if free < 40 << 30:
+        pytest.skip("needs 40 GiB of free device memory")
+    M = N = 65536
+    lda = 65600
+    total = (M - 1) * lda + N
+    assert total > 1 << 32
+    A = torch.empty(total, dtype=torch.float32, device=dev)
+    rows_per = CHUNK // lda
+    for r0 in range(0, M, rows_per):                      # A[i][j] = ((131 i + 7 j) % 17) - 8, padding included
+        r1 = min(M, r0 + rows_per)
+        e = min(total, r1 * lda)
+        idx = torch.arange(r0 * lda, e, dtype=torch.int64, device=dev)
+        A[r0 * lda:e] = (((idx // lda) * 131 + (idx % lda) * 7) % 17 - 8).to(torch.float32)
+    xn = pattern_dev(N, 5, 2, dev)
+    xm = pattern_dev(M, 7, 3, dev)
+    hxn, hxm = to_host(xn), to_host(xm)
+    y = torch.zeros(M, dtype=torch.float32, device=dev)
+    cross = (1 << 32) // lda                               # the row in which the element offset passes 2^32
+    picks = [0, 1, 31, 32767, cross - 1, cross, cross + 1, 65534, 65535]
+
+    def row(i, lo=0, hi=N):
+        return to_host(A[i * lda + lo:i * lda + hi])
+
+    def col(j, lo=0, hi=M):
+        return to_host(A.as_strided((hi - lo,), (lda,), lo * lda + j))
+
+    def dot_row(v, w):                                     # one output of a matrix-vector product, by the oracle
+        out = np.zeros(1, np.float32)
+        O.gemv(O.ROW_MAJOR, O.NO_TRANS, 1, v.size, 1.0, np.ascontiguousarray(v), v.size, np.ascontiguousarray(w), 1, 0.0, out, 1)
+        return out[0]
+
+    # gemv, both orientations
+    assert B.mxb_sgemv(h, B.ROW_MAJOR, B.NO_TRANS, M, N, 1.0, A, lda, xn, 1, 0.0, y, 1) == 0
+    got = to_host(y)
+    for i in picks:
+        assert bits_equal(got[i], dot_row(row(i), hxn)), f"sgemv N row {i}"
+    assert B.mxb_sgemv(h, B.ROW_MAJOR, B.TRANS, M, N, 1.0, A, lda, xm, 1, 0.0, y, 1) == 0
+    got = to_host(y)
+    for j in picks:
+        assert bits_equal(got[j], dot_row(col(j), hxm)), f"sgemv T column {j}"
+
+    # symv on the lower triangle: row i of S is A[i][:i+1] followed by A[i+1:][i]
+    assert B.mxb_ssymv(h, B.ROW_MAJOR, B.LOWER, N, 1.0, A, lda, xn, 1, 0.0, y, 1) == 0
+    got = to_host(y)
+    for i in picks:
+        srow = np.concatenate([row(i, 0, i + 1), col(i, i + 1, M)])
+        assert bits_equal(got[i], dot_row(srow, hxn)), f"ssymv row {i}"
+
+    # trmv, lower: not transposed (row i up to the diagonal) and transposed (column j from the diagonal down)
+    t = xn.clone()
+    assert B.mxb_strmv(h, B.ROW_MAJOR, B.LOWER, B.NO_TRANS, B.NON_UNIT, N, A, lda, t, 1) == 0
+    got = to_host(t)
+    for i in picks:
+        assert bits_equal(got[i], dot_row(row(i, 0, i + 1), hxn[:i + 1])), f"strmv N row {i}"
+    t = xm.clone()
+    assert B.mxb_strmv(h, B.ROW_MAJOR, B.LOWER, B.TRANS, B.NON_UNIT, N, A, lda, t, 1) == 0
+    got = to_host(t)
+    for j in picks:
+        assert bits_equal(got[j], dot_row(col(j, j, M), hxm[j:])), f"strmv T column {j}"
+
+    # ger last (it changes A): sampled rows against the oracle's rank-1 update of that row
+    before = {i: row(i) for i in picks}
+    pad_before = to_host(A[cross * lda + N:(cross + 1) * lda]).copy()
+    assert B.mxb_sger(h, B.ROW_MAJOR, M, N, 1.0, xm, 1, xn, 1, A, lda) == 0
+    for i in picks:
+        want = before[i].copy()
+        O.ger(O.ROW_MAJOR, 1, N, 1.0, hxm[i:i + 1].copy(), 1, hxn, 1, want, N)
+        assert bits_equal(row(i), want), f"sger row {i}"
+    assert bits_equal(to_host(A[cross * lda + N:(cross + 1) * lda]), pad_before), "sger wrote into the padding"
