@@ -93,6 +93,33 @@ def test_level1_beyond_2_to_31_elements(blas, big_ctx):
     assert B.mxb_sasum(h, N1, x, 1, r) == 0
     assert bits_equal(to_host(r)[0], np.float32(3 * asum_exact))
 
+    # copy, swap and rot over the whole length; increments whose products with the index pass 2^31
+    def expect(a, b):                                      # x and y as they stand now, from the oracle's own steps
+        hx, hy = pattern_host(a, b, 7, 3), pattern_host(a, b, 5, 2)
+        O.axpy(b - a, 2.0, hx, 1, hy, 1)
+        O.scal(b - a, -3.0, hx, 1)
+        return hx, hy
+
+    assert B.mxb_sswap(h, N1, x, 1, y, 1) == 0
+    assert B.mxb_srot(h, N1, x, 1, y, 1, 0.0, 1.0) == 0   # c = 0, s = 1: x' = y, y' = -x, exact
+    for a, b in windows(N1):
+        hx, hy = expect(a, b)
+        O.swap(b - a, hx, 1, hy, 1)
+        O.rot(b - a, hx, 1, hy, 1, 0.0, 1.0)
+        assert bits_equal(to_host(x[a:b]), hx) and bits_equal(to_host(y[a:b]), hy), f"sswap + srot window {a}..{b}"
+    n2 = (1 << 30) + 2049                                  # every other element of x into every other element of y
+    assert B.mxb_scopy(h, n2, x, 2, y, 2) == 0
+    assert B.mxb_saxpy(h, n2, 1.0, x, 2, y, 2) == 0        # y = 2 x on the even places
+    a, b = 2 * n2 - (1 << 18), 2 * n2 - 1
+    hx, hy = expect(a, b)
+    O.swap(b - a, hx, 1, hy, 1); O.rot(b - a, hx, 1, hy, 1, 0.0, 1.0)
+    m = (b - a + 1) // 2
+    O.copy(m, hx, 2, hy, 2); O.axpy(m, 1.0, hx, 2, hy, 2)
+    assert bits_equal(to_host(y[a:b]), hy), "strided scopy + saxpy at the far end"
+    assert B.mxb_sdot(h, n2, x, 2, y, 2, r) == 0           # = 2 sum x_even^2: an exact integer, rounded once
+    xe = x[0:2 * n2 - 1:2].double()
+    assert bits_equal(to_host(r)[0], np.float32(2.0 * float((xe * xe).sum().item())))
+
 
 def test_level2_beyond_2_to_32_elements(blas, big_ctx):
     B, h = blas, big_ctx.h
@@ -167,3 +194,50 @@ def test_level2_beyond_2_to_32_elements(blas, big_ctx):
         O.ger(O.ROW_MAJOR, 1, N, 1.0, hxm[i:i + 1].copy(), 1, hxn, 1, want, N)
         assert bits_equal(row(i), want), f"sger row {i}"
     assert bits_equal(to_host(A[cross * lda + N:(cross + 1) * lda]), pad_before), "sger wrote into the padding"
+
+    # syr2 on the lower triangle: sampled rows, and the element right of the diagonal stays untouched
+    before = {i: row(i, 0, min(i + 2, N)) for i in picks}
+    assert B.mxb_ssyr2(h, B.ROW_MAJOR, B.LOWER, N, 1.0, xn, 1, xm, 1, A, lda) == 0
+    for i in picks:
+        got_row, want = row(i, 0, min(i + 2, N)), before[i].copy()
+        want[:i + 1] += hxn[i] * hxm[:i + 1] + hxm[i] * hxn[:i + 1]      # small integers: exact in any order
+        assert bits_equal(got_row, want), f"ssyr2 row {i}"
+
+    # strided batch over the same memory: 69950 problems of 256 x 240, the last ones beyond element 2^32
+    m_, n_, sA = 256, 240, 256 * 240
+    batch = total // sA
+    assert (batch - 1) * sA > 1 << 32
+    xb = pattern_dev(n_, 5, 2, dev)
+    yb = torch.zeros(batch * m_, dtype=torch.float32, device=dev)
+    assert B.mxb_sgemv_batched(h, B.ROW_MAJOR, B.NO_TRANS, m_, n_, 1.0, A, n_, sA, xb, 1, 0, 0.0, yb, 1, m_, batch) == 0
+    got = to_host(yb).reshape(batch, m_)
+    for pb in (0, (1 << 32) // sA, (1 << 32) // sA + 1, batch - 1):
+        Ap = to_host(A[pb * sA:(pb + 1) * sA])
+        want = np.zeros(m_, np.float32)
+        O.gemv(O.ROW_MAJOR, O.NO_TRANS, m_, n_, 1.0, Ap, n_, to_host(xb), 1, 0.0, want, 1)
+        assert bits_equal(got[pb], want), f"sgemv_batched problem {pb}"
+
+    # the skinny kernels on the same memory as 107 million rows of 40
+    rows40 = total // 40
+    assert (rows40 - 1) * 40 > 1 << 32
+    x40 = pattern_dev(40, 5, 2, dev)
+    y40 = torch.zeros(rows40, dtype=torch.float32, device=dev)
+    assert B.mxb_sgemv(h, B.ROW_MAJOR, B.NO_TRANS, rows40, 40, 1.0, A, 40, x40, 1, 0.0, y40, 1) == 0
+    for i in (0, (1 << 32) // 40, (1 << 32) // 40 + 1, rows40 - 1):
+        assert bits_equal(to_host(y40[i:i + 1])[0], dot_row(to_host(A[i * 40:(i + 1) * 40]), to_host(x40))), f"skinny sgemv N row {i}"
+
+    # trsv at n = 65536 (256 workgroups of the chained kernel): unit diagonal, the integers scaled by
+    # 2^-20 below it (row sums of magnitudes below 1/2: substitution cannot grow)
+    A.mul_(2.0 ** -20)
+    for trans in (B.NO_TRANS, B.TRANS):
+        z = xn.clone()
+        assert B.mxb_strsv(h, B.ROW_MAJOR, B.LOWER, trans, B.UNIT, N, A, lda, z, 1) == 0
+        assert big_ctx.last_status() == B.OK
+        hz = to_host(z)
+        for i in picks:                                    # b_i = z_i + (strictly lower or upper part of op(T)) . z
+            part = dot_row(row(i, 0, i), hz[:i]) if trans == B.NO_TRANS and i > 0 else (
+                dot_row(col(i, i + 1, M), hz[i + 1:]) if trans == B.TRANS and i + 1 < M else np.float32(0))
+            # a row's 63 substitution steps each round a value of size |z_i|: a few units in the last place
+            bound = 32 * 2.0 ** -24 * (abs(float(hxn[i])) + abs(float(hz[i])) + abs(float(part)))
+            assert abs(float(hz[i]) + float(part) - float(hxn[i])) <= bound, f"strsv trans={trans} row {i}"
+
