@@ -335,6 +335,10 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
         if constexpr (kPark) park[wave][j][lane] = e[j];      // read back by this lane only
         else asm volatile("" : "+v"(e[j]));                   // here, not when the solve needs it
     }
+    // the first two tiles of my own workgroup are made ready now as well: turning a tile through LDS
+    // between two steps takes a wavefront longer than the solving wavefront needs for its step
+    if (wants(0)) finish(own_c0(0), pa);
+    if (wants(1)) finish(own_c0(1), pb);
 
     // ---- the unknowns of earlier workgroups: tiles 0 .. q0 - 1 of my block row, in solving order.
     // A tile travels in pieces of RH rows (columns if transposed), two pieces in flight by turns;
@@ -464,8 +468,8 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
             xs[wave * kWave + lane] = c;
             Handover<T>::put(p.solved + ((int64_t)q * kWave + lane) * HW, c);     // all 64, zeros past the end
             if (active) p.x[(int64_t)i * p.incx] = c;
-        } else if (wants(s)) {
-            finish(own_c0(s), tile_s);
+        } else if (s >= 2 && wants(s)) {
+            finish(own_c0(s), tile_s);       // tiles 0 and 1 were made ready at the start
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
         __builtin_amdgcn_s_barrier();
