@@ -159,7 +159,20 @@ class Suite:
              4 * (tri + 3 * NS), None),
             (f"dsymv_l_{NS}", "symv", lambda s: B.mxb_dsymv(h, B.ROW_MAJOR, B.LOWER, NS, 0.52, nextA(A64), lda, xd, 1, 0.49, yd, 1),
              8 * (tri + 3 * NS), None),
+            # trsv: unit diagonal over small off-diagonal elements (a random triangle is exponentially ill conditioned)
+            (f"strsv_ln_{NS}", "trsv", lambda s: B.mxb_strsv(h, B.ROW_MAJOR, B.LOWER, B.NO_TRANS, B.UNIT, NS, self.small(), NS, xt, 1),
+             4 * (tri - NS + 2 * NS), reset),
+            (f"strsv_lt_{NS}", "trsv", lambda s: B.mxb_strsv(h, B.ROW_MAJOR, B.LOWER, B.TRANS, B.UNIT, NS, self.small(), NS, xt, 1),
+             4 * (tri - NS + 2 * NS), reset),
         ]
+        self._small = None
+        self._small_from = A32[0]
+
+    def small(self):
+        """A 16384^2 matrix of elements below 1e-4, made on first use (only the trsv extras want it)."""
+        if self._small is None:
+            self._small = self._small_from * 1e-4
+        return self._small
 
     def add(self, name, family, fn, nbytes, pre=None):
         self.calls.append((name, family, fn, int(nbytes), pre))
