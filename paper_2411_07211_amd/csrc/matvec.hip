@@ -443,6 +443,76 @@ int launch_rowdot(mxb_handle_t h, RowdotArgs<T> a, int mode, bool unit)
 
 namespace {
 
+// y = alpha*A^t*x + beta*y for a matrix small enough to come from the caches, in one kernel and
+// without partial vectors: a block owns 8 vectors of columns (32 in single precision) and all
+// the rows; its 256 lanes are 8 column lanes x 32 row lanes, a lane walks down every 32nd row
+// with 8 loads in flight, the 32 row lanes of a column are folded through LDS in a fixed order.
+// The general kernel gives a block at least 1024 columns, which for such a matrix leaves a
+// handful of blocks or forces many row groups whose partial vectors weigh as much as the matrix.
+constexpr int kSmallColLanes = 8, kSmallRowLanes = 32, kSmallUnroll = 8;
+// Taken for matrices of up to 1024 rows (four rounds of loads per lane): with more rows the few
+// long-running blocks lose against the general kernel's many (measured: 256^2 3.9 -> 2.7 us,
+// 512^2 5.9 -> 3.3, 1024^2 9.3 -> 6.6, 256 x 16384 9.8 -> 4.8; 1536^2 a tie, 2048^2 10.1 -> 12.3).
+constexpr int64_t kSmallMaxRows = 1024;
+
+template <typename T, int VEC>
+__global__ void __launch_bounds__(kSmallColLanes* kSmallRowLanes) colsum_small_kernel(const ColaccArgs<T> p)
+{
+    typedef typename VecOf<T, VEC>::type V;
+    constexpr int CL = kSmallColLanes, RL = kSmallRowLanes, U = kSmallUnroll, W = CL * VEC;
+    __shared__ T red[RL][W + 1];
+    const int cl = threadIdx.x % CL, rl = threadIdx.x / CL;
+    // my vector of columns; the last vector of a ragged width is moved back to end at the last
+    // column and its first `shift` elements, which the lane before it owns, are dropped at the end
+    auto place = [&](int lane_c, int64_t& c, int& shift) {
+        c = (int64_t)blockIdx.x * W + lane_c * VEC;
+        shift = 0;
+        if (c >= p.N) return false;
+        if (c + VEC > p.N) {
+            shift = (int)(c + VEC - p.N);
+            c = p.N - VEC;
+        }
+        return true;
+    };
+    int64_t c;
+    int shift;
+    const bool live = place(cl, c, shift);
+    if (!live) c = 0;
+    const T* col = p.A + c;
+    V acc = V(T(0));
+    for (int64_t r0 = rl; r0 < p.M; r0 += (int64_t)RL * U) {
+        V a[U];
+        T xr[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {        // rows past the end: the last row again, times zero
+            const int64_t r = r0 + (int64_t)u * RL;
+            const int64_t rc = r < p.M ? r : p.M - 1;
+            a[u] = ld_matrix<T, VEC>(col + rc * p.lda);
+            xr[u] = r < p.M ? p.x[rc * p.incx] : T(0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) acc[k] = fmad(a[u][k], xr[u], acc[k]);
+    }
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) red[rl][cl * VEC + k] = acc[k];
+    __syncthreads();
+    if (threadIdx.x < W) {
+        const int lane_c = threadIdx.x / VEC, k = threadIdx.x % VEC;
+        int64_t c2;
+        int shift2;
+        if (place(lane_c, c2, shift2) && k >= shift2) {
+            T tot = T(0);
+#pragma unroll
+            for (int q = 0; q < RL; ++q) tot += red[q][threadIdx.x];
+            T* out = p.y + (c2 + k) * p.incy;
+            *out = p.beta == T(0) ? p.alpha * tot : fmad(p.alpha, tot, p.beta * *out);
+        }
+    }
+}
+
 template <typename T, int VEC>
 void launch_colacc_inst(mxb_handle_t h, const ColaccArgs<T>& a, const ColaccPlan& pl, int64_t batch)
 {
@@ -469,6 +539,11 @@ int launch_colacc(mxb_handle_t h, ColaccArgs<T> a, int64_t batch)
     // alignment only and the kernel moves the last vector of a ragged row back.
     // (a ragged row of up to 64 elements keeps more lanes busy with one element per lane)
     const bool vec = a.N % FV == 0 || a.N > kWave;
+    if (batch == 1 && a.N >= FV && a.M <= kSmallMaxRows && a.M * a.N * (int64_t)sizeof(T) <= option(h, MXB_OPT_GEMVT_SMALL_MAX)) {
+        hipLaunchKernelGGL((colsum_small_kernel<T, FV>), dim3((unsigned)ceil_div(a.N, (int64_t)kSmallColLanes * FV)),
+                           dim3(kSmallColLanes * kSmallRowLanes), 0, h->stream, a);
+        return launch_status();
+    }
     auto share = [&](int64_t blocks) { return blocks / batch > 1 ? blocks / batch : 1; };
     const ColaccPlan pl = colacc_plan(a.M, a.N, (int)sizeof(T), vec ? FV : 1, share(option(h, MXB_OPT_COLACC_TARGET_BLOCKS)),
                                       share(colacc_narrow_target(h)), option(h, MXB_OPT_COLACC_MIN_ROWS));

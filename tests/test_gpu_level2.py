@@ -74,6 +74,18 @@ def test_gemv_shapes(blas, ctx, dt, trans):
     for (m, n) in GEMV_SHAPES:
         for pad in (0, 3, 4):
             gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, 1.5, 0.5, pad, 1, 1)
+    # the transposed product of a small matrix has a kernel of its own: the same shapes through the
+    # general kernels, and shapes around its limits (1024 rows, one vector of columns, ragged widths)
+    try:
+        ctx.set_option(blas.OPT_GEMVT_SMALL_MAX, 1)
+        for (m, n) in GEMV_SHAPES:
+            if m * n <= 1 << 22:
+                gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, 1.5, 0.5, 3, 1, 1)
+    finally:
+        ctx.set_option(blas.OPT_GEMVT_SMALL_MAX, 0)
+    for (m, n) in [(1024, 4), (1024, 5), (1025, 64), (1000, 33), (37, 2049), (1, 700), (1023, 3), (300, 4099), (512, 8191)]:
+        for beta in (0.0, 0.5):
+            gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, 1.5, beta, 1, 2, 3)
 
 
 @pytest.mark.parametrize("dt", DT)
@@ -126,7 +138,7 @@ def test_gemv_deterministic_and_geometry_invariant(blas, ctx, dt):
             for opts in ({}, {}, {blas.OPT_ROWDOT_XCHUNK: 256, blas.OPT_COLACC_TARGET_BLOCKS: 64},
                          {blas.OPT_ROWDOT_XCHUNK: 1024, blas.OPT_ROWDOT_BLOCKS_PER_CU: 1, blas.OPT_COLACC_TARGET_BLOCKS: 4096,
                           blas.OPT_COLACC_MIN_ROWS: 8}):
-                for o in range(13):
+                for o in range(14):
                     ctx.set_option(o, 0)
                 for o, v in opts.items():
                     ctx.set_option(o, v)
@@ -136,7 +148,7 @@ def test_gemv_deterministic_and_geometry_invariant(blas, ctx, dt):
                 check_close(outs[-1], ref, D, lenx, f"gemv trans={trans} opts={opts}")
             assert outs[0].tobytes() == outs[1].tobytes(), "same launch geometry must give the same bits"
     finally:
-        for o in range(13):
+        for o in range(14):
             ctx.set_option(o, 0)
 
 
