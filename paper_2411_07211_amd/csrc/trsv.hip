@@ -161,12 +161,12 @@ void launch_trsv_diag(mxb_handle_t h, bool op_lower, bool unit, const TrsvArgs<T
 // The same substitution in ONE kernel: no launch per block, and the off-diagonal work of a block
 // of rows overlaps the solves of the blocks before it.
 //
-// A workgroup of 4 wavefronts owns 256 consecutive unknowns (4 sub-blocks of 64, one per
-// wavefront) in solving order.  Workgroups number themselves with a ticket when they start, so
+// A workgroup of 4 wavefronts (2 in double precision when not transposed) owns 256 (128)
+// consecutive unknowns, one sub-block of 64 per wavefront, in solving order.  Workgroups number themselves with a ticket when they start, so
 // that every workgroup with a smaller number is already running or done.  A wavefront first
 // subtracts, sub-block by sub-block, the part of its rows that multiplies unknowns owned by
 // earlier workgroups: the 64 x 64 tile is fetched while the wavefront waits for that sub-block's
-// solutions.  The 4 sub-blocks of the workgroup itself are then solved as in the blocked kernel
+// solutions.  The sub-blocks of the workgroup itself are then solved as in the blocked kernel
 // above (LDS and barriers), each one handed on as soon as it is solved.
 //
 // Solutions travel between workgroups in words that validate themselves: the solver stores
