@@ -241,3 +241,46 @@ def test_level2_beyond_2_to_32_elements(blas, big_ctx):
             bound = 32 * 2.0 ** -24 * (abs(float(hxn[i])) + abs(float(hz[i])) + abs(float(part)))
             assert abs(float(hz[i]) + float(part) - float(hxn[i])) <= bound, f"strsv trans={trans} row {i}"
 
+
+def test_trsv_with_more_workgroups_than_the_device_holds(blas, big_ctx):
+    """n = 100000: 391 workgroups of the chained kernel where 256 are resident at a time, so the later
+    ones take their tickets only when earlier ones have left; 1e10 elements (40 GB)."""
+    B, h = blas, big_ctx.h
+    dev = torch.device("cuda:0")
+    free, _ = torch.cuda.mem_get_info()
+    if free < 60 << 30:
+        pytest.skip("needs 60 GiB of free device memory")
+    n = 100000
+    A = torch.empty(n * n, dtype=torch.float32, device=dev)
+    rows_per = CHUNK // n
+    for r0 in range(0, n, rows_per):                      # ((131 i + 7 j) % 17 - 8) * 2^-20: row sums of magnitudes below 0.8
+        r1 = min(n, r0 + rows_per)
+        idx = torch.arange(r0 * n, r1 * n, dtype=torch.int64, device=dev)
+        A[r0 * n:r1 * n] = (((idx // n) * 131 + (idx % n) * 7) % 17 - 8).to(torch.float32) * 2.0 ** -20
+    b = pattern_dev(n, 5, 2, dev)
+    hb = to_host(b)
+    picks = [0, 1, 255, 256, 65535, 65536, 65537, 99742, 99999]
+
+    def dot_row(v, w):
+        out = np.zeros(1, np.float32)
+        O.gemv(O.ROW_MAJOR, O.NO_TRANS, 1, v.size, 1.0, np.ascontiguousarray(v), v.size, np.ascontiguousarray(w), 1, 0.0, out, 1)
+        return out[0]
+
+    for trans in (B.NO_TRANS, B.TRANS):
+        z = b.clone()
+        assert B.mxb_strsv(h, B.ROW_MAJOR, B.LOWER, trans, B.UNIT, n, A, n, z, 1) == 0
+        assert big_ctx.last_status() == B.OK
+        hz = to_host(z)
+        assert np.isfinite(hz).all()
+        for i in picks:
+            if trans == B.NO_TRANS:
+                t, w = (to_host(A[i * n:i * n + i]), hz[:i]) if i > 0 else (np.zeros(1, np.float32), np.zeros(1, np.float32))
+            else:
+                t, w = (to_host(A.as_strided((n - i - 1,), (n,), (i + 1) * n + i)), hz[i + 1:]) if i + 1 < n else (
+                    np.zeros(1, np.float32), np.zeros(1, np.float32))
+            part, spread = dot_row(t, w), dot_row(np.abs(t), np.abs(w))
+            # the substitution steps round values of size |z_i|; the sum of the row is exact to a fraction of
+            # an ulp of the sum of its magnitudes (a tile left out would show as 1e-5 or more)
+            bound = 2.0 ** -24 * (32 * (abs(float(hb[i])) + abs(float(hz[i]))) + 2 * float(spread))
+            assert abs(float(hz[i]) + float(part) - float(hb[i])) <= bound, f"strsv trans={trans} row {i}"
+
