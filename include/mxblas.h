@@ -19,10 +19,11 @@
  *    synchronises: all work is enqueued on the handle's stream and the call returns at once.
  *    Buffers must stay alive until that work has completed.  Input and output buffers must not
  *    overlap each other or the workspace (trmv's x is in place by definition).
- *  Workspace.  Routines that combine per-block partial results (dot, asum, nrm2, gemv, trmv,
- *    symv) use the handle's workspace, a caller-owned device buffer; mxb_workspace_bytes gives an
- *    upper bound on what a call needs.  Partials are combined by a second kernel in a fixed order:
- *    no atomics, results are bitwise reproducible from run to run.
+ *  Workspace.  Routines that combine per-block partial results (dot, asum, nrm2, iamax, gemv,
+ *    trmv, symv) use the handle's workspace, a caller-owned device buffer, and so does trsv, whose
+ *    workgroups hand their solutions on through it; mxb_workspace_bytes gives an upper bound on
+ *    what a call needs.  Partials are combined by a second kernel in a fixed order: no atomic
+ *    additions, results are bitwise reproducible from run to run.
  *  Layout.  Row-major (MXB_ROW_MAJOR) is native: element (i, j) is A[i*lda + j], as in the
  *    paper's object code.  Column-major calls are remapped on the host to the row-major kernel of
  *    the transposed problem.
