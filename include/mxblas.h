@@ -104,9 +104,9 @@ int64_t mxb_get_option(mxb_handle_t h, int option);
 
 /* Waits for the handle's stream and reports what only the device knows about the last call on
  * this handle that can fail there: MXB_OK, or MXB_ERR_TIMEOUT if the last chained trsv gave up
- * a bounded wait (x is then unfinished).  Valid until the next call on the handle that uses the
- * workspace, or mxb_set_workspace.  Synchronises: not for use under stream capture.  Other
- * routines cannot fail on the device and leave MXB_OK. */
+ * a bounded wait (x is then unfinished).  The next call on the handle that uses the workspace,
+ * or mxb_set_workspace, overwrites the status word and makes this MXB_OK again.  Synchronises:
+ * not for use under stream capture.  Other routines cannot fail on the device. */
 int mxb_last_status(mxb_handle_t h);
 
 /* ---- level 1 (Sec. 6.2.1) ------------------------------------------------------------------ */

@@ -25,6 +25,15 @@ constexpr int kCUs = 256;                  // MI355X compute units (8 XCDs x 32)
 
 inline bool handle_ok(mxb_handle_t h) { return h != nullptr && h->magic == kMagic; }
 
+// The handle's workspace if it holds at least `bytes`, else null.  What the last call left there
+// for mxb_last_status is about to be overwritten, so that is forgotten.
+inline void* take_workspace(mxb_handle_t h, size_t bytes)
+{
+    if (!h->ws || h->ws_bytes < bytes) return nullptr;
+    h->device_status = nullptr;
+    return h->ws;
+}
+
 inline int launch_status()
 {
     const hipError_t e = hipGetLastError();

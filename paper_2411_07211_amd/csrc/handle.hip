@@ -202,9 +202,10 @@ int mxb_probe_read(mxb_handle_t h, size_t bytes, const void* src)
     if (!src) return -2;
     const int64_t nvec = (int64_t)(bytes / 16), ntiles = ceil_div(nvec, kThreads * kUnroll);
     const int64_t grid = ntiles < kProbeReadBlocks ? ntiles : kProbeReadBlocks;
-    if (!h->ws || h->ws_bytes < (size_t)grid * sizeof(double)) return MXB_ERR_WORKSPACE;
+    double* sums = static_cast<double*>(take_workspace(h, (size_t)grid * sizeof(double)));
+    if (!sums) return MXB_ERR_WORKSPACE;
     hipLaunchKernelGGL(probe_read_kernel, dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, ntiles,
-                       static_cast<const f4*>(src), static_cast<double*>(h->ws));
+                       static_cast<const f4*>(src), sums);
     return launch_status();
 }
 }

@@ -422,8 +422,8 @@ int reduce(mxb_handle_t h, int64_t n, const T* x, int64_t incx, const T* y, int6
     // One block per compute unit with 16 vector loads in flight per lane reads fastest; a single
     // strided operand, one element per lane and load, wants eight times as many blocks (measured).
     const int64_t max_blocks = option(h, MXB_OPT_REDUCE_BLOCKS) * ((contiguous || TWO) ? 1 : kStridedBlocksFactor);
-    if (!h->ws || h->ws_bytes < (size_t)max_blocks * K * sizeof(double)) return MXB_ERR_WORKSPACE;
-    double* partials = static_cast<double*>(h->ws);
+    double* partials = static_cast<double*>(take_workspace(h, (size_t)max_blocks * K * sizeof(double)));
+    if (!partials) return MXB_ERR_WORKSPACE;
     int64_t grid;
     if (contiguous) {
         const int64_t nvec = n / VEC;
@@ -548,8 +548,8 @@ int iamax(mxb_handle_t h, int64_t n, const T* x, int64_t incx, int64_t* result)
     }
     if (!x) return -2;
     const int64_t max_blocks = option(h, MXB_OPT_REDUCE_BLOCKS);
-    if (!h->ws || h->ws_bytes < (size_t)max_blocks * sizeof(Cand)) return MXB_ERR_WORKSPACE;
-    Cand* partials = static_cast<Cand*>(h->ws);
+    Cand* partials = static_cast<Cand*>(take_workspace(h, (size_t)max_blocks * sizeof(Cand)));
+    if (!partials) return MXB_ERR_WORKSPACE;
     const int64_t nfull = n / (kThreads * kStridedUnroll);
     const int64_t grid = nfull <= kSingleBlockTiles ? 1 : (nfull < max_blocks ? nfull : max_blocks);
     hipLaunchKernelGGL(iamax_kernel<T>, dim3((unsigned)grid), dim3(kThreads), 0, h->stream, n, nfull, x, incx, partials);

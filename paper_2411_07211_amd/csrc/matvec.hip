@@ -552,8 +552,8 @@ int launch_colacc(mxb_handle_t h, ColaccArgs<T> a, int64_t batch)
     a.ppitch = ceil_div(a.N, FV) * FV;
     a.spart = pl.nparts * a.ppitch;
     if (pl.nparts > 1) {
-        if (!h->ws || h->ws_bytes < (size_t)batch * (size_t)a.spart * sizeof(T)) return MXB_ERR_WORKSPACE;
-        a.partials = static_cast<T*>(h->ws);
+        a.partials = static_cast<T*>(take_workspace(h, (size_t)batch * (size_t)a.spart * sizeof(T)));
+        if (!a.partials) return MXB_ERR_WORKSPACE;
     }
     for (int64_t b0 = 0; b0 < batch; b0 += kMaxGridZ) {       // the grid's z extent is limited
         const int64_t nb = batch - b0 < kMaxGridZ ? batch - b0 : kMaxGridZ;
@@ -704,8 +704,8 @@ int trmv(mxb_handle_t h, int layout, int uplo, int trans, int diag, int64_t n, c
 
     // not transposed: rows are written while other blocks still read x, so work from a snapshot
     const size_t snap_bytes = align_up((size_t)n * sizeof(T), 256);
-    if (!h->ws || h->ws_bytes < snap_bytes) return MXB_ERR_WORKSPACE;
-    T* snap = static_cast<T*>(h->ws);
+    T* snap = static_cast<T*>(take_workspace(h, snap_bytes));
+    if (!snap) return MXB_ERR_WORKSPACE;
     hipLaunchKernelGGL(gather_kernel<T>, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, h->stream, n, x0, incx, snap);
     int st = launch_status();
     if (st != MXB_OK) return st;

@@ -301,8 +301,8 @@ int skinny_gemv_t(mxb_handle_t h, int64_t rows, int64_t cols, T alpha, const T* 
 {
     const SkinnyArgs<T> a = make_args<T>(rows, cols, Full<T>::vec, lda, incy, incx, alpha, beta);
     const int64_t blocks = tile_blocks(rows, a.nv, kSkinnyBlocksT);
-    if (!h->ws || h->ws_bytes < (size_t)blocks * (size_t)cols * sizeof(T)) return MXB_ERR_WORKSPACE;
-    T* partials = static_cast<T*>(h->ws);
+    T* partials = static_cast<T*>(take_workspace(h, (size_t)blocks * (size_t)cols * sizeof(T)));
+    if (!partials) return MXB_ERR_WORKSPACE;
     MXB_SKINNY_DISPATCH(skinny_gemv_t_kernel, blocks, A, x0, partials);
     const int st = launch_status();
     if (st != MXB_OK) return st;

@@ -296,12 +296,12 @@ int trisweep(mxb_handle_t h, bool upper, bool unit, int64_t n, T alpha, const T*
                                 h->opt[MXB_OPT_SYMV_TILE_VECTORS], option(h, MXB_OPT_TRI_DIAG_WEIGHT));
     if (!pl.ok) return MXB_ERR_NOT_IMPLEMENTED;
     const size_t need = tri_workspace_elems(n, pl, KIND == TRI_SYMV) * sizeof(T);
-    if (!h->ws || h->ws_bytes < need) return MXB_ERR_WORKSPACE;
+    T* rowpart = static_cast<T*>(take_workspace(h, need));
+    if (!rowpart) return MXB_ERR_WORKSPACE;
     TriArgs a;
     a.n = (int)n; a.ntiles = pl.ntiles; a.tile_cols = pl.tile_cols; a.blocks = pl.blocks;
     a.lda = lda; a.incx = incx;
     for (int t = 0; t <= kTriMaxTiles; ++t) a.first_block[t] = pl.first_block[t <= pl.ntiles ? t : pl.ntiles];
-    T* rowpart = static_cast<T*>(h->ws);
     T* colpart = rowpart + (KIND == TRI_SYMV ? (int64_t)pl.ntiles * kTriWaves * n : 0);
     if (!vec) launch_sweep<T, 1, 1, 4, KIND>(h, upper, unit, a, A, x0, rowpart, colpart);
     else if (pl.cv == 4) launch_sweep<T, FV, 4, 16, KIND>(h, upper, unit, a, A, x0, rowpart, colpart);

@@ -500,12 +500,13 @@ template <typename T>
 int trsv_chain(mxb_handle_t h, bool op_lower, bool no_trans, bool unit, int64_t n, const T* A, int64_t lda, T* x0, int64_t incx)
 {
     const size_t bytes = chain_bytes<T>(n);
-    if (!h->ws || h->ws_bytes < bytes) return MXB_ERR_WORKSPACE;
+    void* ws = take_workspace(h, bytes);
+    if (!ws) return MXB_ERR_WORKSPACE;
     const int64_t words = (int64_t)(bytes / sizeof(int));
-    unsigned long long* solved = static_cast<unsigned long long*>(h->ws);
-    int* control = static_cast<int*>(h->ws) + (words - 2);
+    unsigned long long* solved = static_cast<unsigned long long*>(ws);
+    int* control = static_cast<int*>(ws) + (words - 2);
     hipLaunchKernelGGL(trsv_chain_init_kernel, dim3((unsigned)ceil_div(words, (int64_t)256)), dim3(256), 0, h->stream,
-                       static_cast<int*>(h->ws), (int)words);
+                       static_cast<int*>(ws), (int)words);
     int st = launch_status();
     if (st != MXB_OK) return st;
     h->device_status = control + 1;

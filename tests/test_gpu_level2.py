@@ -567,6 +567,10 @@ def test_trsv_bounded_wait_reports_timeout(blas, ctx):
         ctx.set_option(blas.OPT_TRSV_SPIN_LIMIT, 1)
         solve()
         assert ctx.last_status() == blas.ERR_TIMEOUT
+        # a later call that uses the workspace overwrites the status word: the handle forgets it
+        r = to_dev(np.zeros(1, dt))
+        assert blas.mxb_sdot(ctx.h, n, to_dev(bb), 1, to_dev(bb), 1, r) == 0
+        assert ctx.last_status() == blas.OK
         ctx.set_option(blas.OPT_TRSV_SPIN_LIMIT, 0)
         dx = solve()
         assert ctx.last_status() == blas.OK
