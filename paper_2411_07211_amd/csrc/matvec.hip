@@ -609,6 +609,30 @@ int gemv_rows(mxb_handle_t h, bool no_trans, int64_t rows, int64_t cols, T alpha
     if (tiny_takes<T>(rows, cols, batch))
         return no_trans ? tiny_gemv_n<T>(h, rows, cols, alpha, A, lda, sA, x0, incx, sx, beta, y0, incy, sy, batch)
                         : tiny_gemv_t<T>(h, rows, cols, alpha, A, lda, sA, x0, incx, sx, beta, y0, incy, sy, batch);
+    if (no_trans && batch == 1 && rows <= kWideMaxRows && cols >= 2 * kWideMinChunk) {
+        // Few, very long rows: the row-dot grid wants some 8192 rows to be busy.  The columns are cut
+        // into chunks, the chunks run as a batch of rows x chunk problems that write partial results
+        // (a shorter last chunk in a launch of its own), and the pass that combines the partial
+        // vectors of the transposed product adds them up, in chunk order, with alpha and beta.
+        int64_t parts = ceil_div(kWideFillRows, rows);
+        if (parts > cols / kWideMinChunk) parts = cols / kWideMinChunk;
+        const int64_t chunk = ceil_div(ceil_div(cols, parts), (int64_t)256) * 256;
+        const int64_t nfull = cols / chunk, tail = cols - nfull * chunk, nparts = nfull + (tail > 0 ? 1 : 0);
+        T* partials = static_cast<T*>(take_workspace(h, (size_t)nparts * (size_t)rows * sizeof(T)));
+        if (!partials) return MXB_ERR_WORKSPACE;
+        RowdotArgs<T> a{rows, chunk, A, lda, x0, incx, partials, 1, T(1), T(0), 0, 0, nfull, chunk, chunk * incx, rows};
+        int st = launch_rowdot(h, a, MODE_GENERAL, false);
+        if (st != MXB_OK) return st;
+        if (tail > 0) {
+            RowdotArgs<T> b{rows, tail, A + nfull * chunk, lda, x0 + nfull * chunk * incx, incx, partials + nfull * rows, 1, T(1), T(0),
+                            0, 0, 1, 0, 0, 0};
+            st = launch_rowdot(h, b, MODE_GENERAL, false);
+            if (st != MXB_OK) return st;
+        }
+        hipLaunchKernelGGL(colacc_combine_kernel<T>, dim3((unsigned)ceil_div(rows, (int64_t)kWave), 1u), dim3(kCombineGroups * kWave), 0,
+                           h->stream, nparts, rows, rows, partials, alpha, beta, y0, incy, (int64_t)0, (int64_t)0);
+        return launch_status();
+    }
     if (no_trans) {
         RowdotArgs<T> a{rows, cols, A, lda, x0, incx, y0, incy, alpha, beta, 0, 0, batch, sA, sx, sy};
         return launch_rowdot(h, a, MODE_GENERAL, false);

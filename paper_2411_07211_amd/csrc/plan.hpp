@@ -16,6 +16,12 @@ struct ColaccPlan {
     int64_t nparts;          // row groups = partial vectors per column
 };
 
+// gemv, not transposed, few and very long rows: up to kWideMaxRows rows the columns are split into
+// chunks of at least kWideMinChunk so that rows x chunks reaches kWideFillRows (what keeps the
+// row-dot grid busy); the chunks' partial results take at most kWideFillRows + 2 rows' worth of
+// elements of workspace.
+constexpr int64_t kWideMaxRows = 4096, kWideMinChunk = 16384, kWideFillRows = 8192;
+
 inline ColaccPlan colacc_plan(int64_t rows, int64_t cols, int elem_size, int vec, int64_t target_blocks,
                               int64_t narrow_blocks, int64_t min_rows)
 {

@@ -86,6 +86,13 @@ def test_gemv_shapes(blas, ctx, dt, trans):
     for (m, n) in [(1024, 4), (1024, 5), (1025, 64), (1000, 33), (37, 2049), (1, 700), (1023, 3), (300, 4099), (512, 8191)]:
         for beta in (0.0, 0.5):
             gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, 1.5, beta, 1, 2, 3)
+    # few, very long rows: not transposed, the columns are split into chunks that run as a batch
+    # (whole chunks, a ragged last one, negative increments, a pitch larger than the width)
+    for (m, n, pad, incx, incy) in [(1, 32768, 0, 1, 1), (3, 40000, 5, 1, 1), (300, 65537, 0, -1, 2), (4096, 32768, 0, 1, 1),
+                                    (4097, 32768, 0, 1, 1), (17, 100001, 3, 2, -1)]:
+        for beta in (0.0, -0.5):
+            gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, 1.5, beta, pad, incx, incy)
+    gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, 64, 70000, 2, 1, 0, 1, 1, ints=True)
 
 
 @pytest.mark.parametrize("dt", DT)
