@@ -21,6 +21,9 @@ constexpr int kThreads = 256;
 // ---------------------------------------------------------------------------------------------
 // ger
 
+constexpr int64_t kGerWideRowBytes = 1 << 20;      // rows from this size on are updated one by one, as long vectors
+constexpr int kGerWideRows = 4;                    // ... in groups of this many per block
+
 template <typename T>
 struct GerArgs {
     int64_t M, N;
@@ -88,6 +91,61 @@ __global__ void __launch_bounds__(kThreads) ger_kernel(const GerArgs<T> p)
 #pragma unroll
         for (int k = 0; k < VEC; ++k) a[k] = fmad(ax, yj[k], a[k]);
         st_matrix_from<T, VEC>(acol + i0 * p.lda, a, shift);
+    }
+}
+
+// Rows of a megabyte and more: every row is updated like one long vector, A[i][:] += (alpha*x[i])*y,
+// in the tiles of the streaming level-1 kernels (8 runs of 4 KiB that lie 64 KiB apart inside
+// the row).  The tile of the kernel above stacks 8 rows, which lie a whole pitch apart: with a
+// pitch of several megabytes, and worst a power of two, all 8 runs fall into the same memory
+// channels (1024 x 4194304 floats: 51 % of peak at pitch 4194304, 73 % at pitch 4194304 + 1024).
+// blockIdx.y = group of 4 rows (one tile of y in registers serves them all: a y that does not fit
+// the caches would otherwise be fetched once per row), blockIdx.x = tile of the row; y has unit increment.
+template <typename T>
+__global__ void __launch_bounds__(kThreads) ger_wide_kernel(const GerArgs<T> p, int64_t row0, int64_t nvec, int64_t nfull, int64_t n2d,
+                                                            int tail)
+{
+    constexpr int VEC = Full<T>::vec;
+    constexpr int U = 8, R = kGerWideRows;
+    typedef typename VecOf<T, VEC>::type V;
+    typedef V LooseV __attribute__((aligned(sizeof(T))));
+    const int64_t i0 = row0 + (int64_t)blockIdx.y * R;
+    const int nr = (int)imin((int64_t)R, p.M - i0);
+    for (int64_t t = blockIdx.x; t < nfull; t += gridDim.x) {
+        int64_t base, step;
+        stream_tile<U>(t, n2d, base, step);
+        V b[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) b[u] = *reinterpret_cast<const LooseV*>(p.y + (base + u * step) * VEC);
+        for (int r = 0; r < nr; ++r) {       // the tile of y serves R rows
+            T* arow = p.A + (i0 + r) * p.lda;
+            const T ax = p.alpha * p.x[(i0 + r) * p.incx];
+            V a[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) a[u] = ld_matrix<T, VEC>(arow + (base + u * step) * VEC);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+#pragma unroll
+                for (int k = 0; k < VEC; ++k) a[u][k] = fmad(ax, b[u][k], a[u][k]);
+                st_matrix<T, VEC>(arow + (base + u * step) * VEC, a[u]);
+            }
+        }
+    }
+    if (blockIdx.x != gridDim.x - 1) return;
+    for (int r = 0; r < nr; ++r) {
+        T* arow = p.A + (i0 + r) * p.lda;
+        const T ax = p.alpha * p.x[(i0 + r) * p.incx];
+        for (int64_t v = nfull * (kThreads * U) + threadIdx.x; v < nvec; v += kThreads) {
+            V a = ld_matrix<T, VEC>(arow + v * VEC);
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) a[k] = fmad(ax, p.y[v * VEC + k], a[k]);
+            st_matrix<T, VEC>(arow + v * VEC, a);
+        }
+        if ((int)threadIdx.x < tail) {
+            const int64_t j = nvec * VEC + threadIdx.x;
+            arow[j] = fmad(ax, p.y[j], arow[j]);
+        }
     }
 }
 
@@ -377,6 +435,20 @@ int ger(mxb_handle_t h, int layout, int64_t m, int64_t n, T alpha, const T* x, i
         return skinny_ger<T>(h, a.M, a.N, alpha, a.x, a.incx, a.y, a.incy, a.A, a.lda);
     a.rows_per_block = option(h, MXB_OPT_GER_ROWS_PER_BLOCK);
     constexpr int FV = Full<T>::vec;
+    if (a.incy == 1 && a.N * (int64_t)sizeof(T) >= kGerWideRowBytes) {      // very long rows: row by row, as long vectors
+        const int64_t nvec = a.N / FV, nfull = nvec / (kThreads * 8);
+        if (nfull <= 0x7fffffff) {
+            constexpr int64_t kRowsPerLaunch = (int64_t)65535 * kGerWideRows;
+            for (int64_t r0 = 0; r0 < a.M; r0 += kRowsPerLaunch) {
+                const int64_t nr = ceil_div(a.M - r0 < kRowsPerLaunch ? a.M - r0 : kRowsPerLaunch, (int64_t)kGerWideRows);
+                hipLaunchKernelGGL(ger_wide_kernel<T>, dim3((unsigned)nfull, (unsigned)nr), dim3(kThreads), 0, h->stream, a, r0, nvec, nfull,
+                                   stream_tiles_2d(nvec, 8), (int)(a.N % FV));
+                const int st = launch_status();
+                if (st != MXB_OK) return st;
+            }
+            return MXB_OK;
+        }
+    }
     // Any pitch, any base address and any width of at least one vector: matrix accesses need element
     // alignment only and the kernel moves the last vector of a ragged row back.
     // (a short ragged row keeps more lanes busy with one element per lane)

@@ -424,6 +424,24 @@ def test_ger(blas, ctx, dt, layout):
     assert bits_equal(to_host(dA), A)
 
 
+@pytest.mark.parametrize("dt", DT)
+def test_ger_very_long_rows(blas, ctx, dt):
+    """Rows of a megabyte and more are updated one by one, in the tiles of the level-1 kernels: whole
+    tiles, a ragged rest of vectors and of elements, a pitch beyond the width, a displaced base, a
+    negative increment of x; with a strided y the general kernel takes over."""
+    w = (1 << 20) // np.dtype(dt).itemsize
+    for (m, n, pad, incx) in [(3, w, 0, 1), (2, w + 8192 * 3 + 5, 7, -1), (5, 2 * w + 16384 + 1, 0, 2), (1, 3 * w - 3, 1, 1)]:
+        ger_case(blas, ctx, dt, O.ROW_MAJOR, m, n, 0.3, pad, incx, 1)
+    ger_case(blas, ctx, dt, O.COL_MAJOR, w + 100, 3, -1.5, 0, 1, 1)
+    ger_case(blas, ctx, dt, O.ROW_MAJOR, 4, w + 37, 3, 0, 1, 1, ints=True)
+    ger_case(blas, ctx, dt, O.ROW_MAJOR, 2, w + 64, 0.3, 0, 1, 3)
+    A_OFFSET[0] = 1
+    try:
+        ger_case(blas, ctx, dt, O.ROW_MAJOR, 3, w + 1029, 0.3, 2, 1, 1)
+    finally:
+        A_OFFSET[0] = 0
+
+
 # ----------------------------------------------------------------------------- syr, syr2
 def syr_case(blas, ctx, dt, layout, uplo, n, alpha, pad, incx, incy, two, ints=False, seed=14):
     gen = (lambda t, k: synth.small_ints(seed, t, k, -3, 3, dt)) if ints else (lambda t, k: synth.uniform(seed, t, k, dt))
