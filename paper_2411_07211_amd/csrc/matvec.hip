@@ -339,6 +339,7 @@ __global__ void __launch_bounds__(kColaccThreads) colacc_kernel(const ColaccArgs
 }
 
 constexpr int kCombineGroups = 16;
+constexpr int64_t kMaxCombineBlocks = 1 << 21;      // x 1024 threads: below the 2^32 threads a launch may have
 
 // y[j] = alpha * sum_p partials[p][j] + beta*y[j], p ascending.  64 columns per block; the 16
 // wavefronts of the block each take every 16th slab, LDS folds them in wave order.
@@ -352,22 +353,27 @@ __global__ void __launch_bounds__(kCombineGroups* kWave) colacc_combine_kernel(i
     y += (int64_t)blockIdx.y * sy;
     __shared__ T red[kCombineGroups][kWave];
     const int tx = threadIdx.x & (kWave - 1), ty = threadIdx.x >> 6;
-    const int64_t j = (int64_t)blockIdx.x * kWave + tx;
-    T s = T(0);
-    if (j < N) {
+    // (a loop: the grid is capped, a launch cannot have 2^32 threads or more)
+    for (int64_t jb = blockIdx.x; jb * kWave < N; jb += gridDim.x) {
+        const int64_t j = jb * kWave + tx;
+        T s = T(0);
+        if (j < N) {
 #pragma unroll 4
-        for (int64_t q = ty; q < nparts; q += kCombineGroups) s += partials[q * ppitch + j];
-    }
-    red[ty][tx] = s;
-    __syncthreads();
-    if (ty != 0 || j >= N) return;
-    T tot = red[0][tx];
+            for (int64_t q = ty; q < nparts; q += kCombineGroups) s += partials[q * ppitch + j];
+        }
+        red[ty][tx] = s;
+        __syncthreads();
+        if (ty == 0 && j < N) {
+            T tot = red[0][tx];
 #pragma unroll
-    for (int k = 1; k < kCombineGroups; ++k) tot += red[k][tx];
-    T* yp = y + j * incy;
-    T v = alpha * tot;
-    if (beta != T(0)) v = fmad(beta, *yp, v);
-    *yp = v;
+            for (int k = 1; k < kCombineGroups; ++k) tot += red[k][tx];
+            T* yp = y + j * incy;
+            T v = alpha * tot;
+            if (beta != T(0)) v = fmad(beta, *yp, v);
+            *yp = v;
+        }
+        __syncthreads();
+    }
 }
 
 // dense copy of a strided vector (trmv's snapshot of x)
@@ -565,7 +571,8 @@ int launch_colacc(mxb_handle_t h, ColaccArgs<T> a, int64_t batch)
         int st = launch_status();
         if (st != MXB_OK) return st;
         if (pl.nparts == 1) continue;
-        hipLaunchKernelGGL(colacc_combine_kernel<T>, dim3((unsigned)ceil_div(a.N, kWave), (unsigned)nb), dim3(kCombineGroups * kWave),
+        hipLaunchKernelGGL(colacc_combine_kernel<T>, dim3((unsigned)(ceil_div(a.N, kWave) < kMaxCombineBlocks ? ceil_div(a.N, kWave) : kMaxCombineBlocks), (unsigned)nb),
+                           dim3(kCombineGroups * kWave),
                            0, h->stream, pl.nparts, a.N, a.ppitch, c.partials, a.alpha, a.beta, c.y, a.incy, a.spart, a.sy);
         st = launch_status();
         if (st != MXB_OK) return st;

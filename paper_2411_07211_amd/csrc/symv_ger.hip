@@ -21,6 +21,7 @@ constexpr int kThreads = 256;
 // ---------------------------------------------------------------------------------------------
 // ger
 
+constexpr int64_t kMaxGerBlocks = 1 << 23;          // x 256 threads: below the 2^32 threads a launch may have
 constexpr int64_t kGerWideRowBytes = 1 << 20;      // rows from this size on are updated one by one, as long vectors
 constexpr int kGerWideRows = 4;                    // ... in groups of this many per block
 
@@ -454,8 +455,9 @@ int ger(mxb_handle_t h, int layout, int64_t m, int64_t n, T alpha, const T* x, i
     // (a short ragged row keeps more lanes busy with one element per lane)
     const bool vec = a.N % FV == 0 || a.N >= 2 * kWave;
     a.col_tiles = (uint32_t)ceil_div(a.N, (int64_t)kThreads * (vec ? FV : 1));
+    // a launch cannot have 2^32 threads or more: a very tall matrix gets more rows per block
+    while ((int64_t)a.col_tiles * ceil_div(a.M, a.rows_per_block) > kMaxGerBlocks) a.rows_per_block *= 2;
     const int64_t blocks = (int64_t)a.col_tiles * ceil_div(a.M, a.rows_per_block);
-    if (blocks > 0x7fffffff) return MXB_ERR_NOT_IMPLEMENTED;
     const dim3 grid((unsigned)blocks);
     if (vec) hipLaunchKernelGGL((ger_kernel<T, FV>), grid, dim3(kThreads), 0, h->stream, a);
     else hipLaunchKernelGGL((ger_kernel<T, 1>), grid, dim3(kThreads), 0, h->stream, a);

@@ -284,3 +284,39 @@ def test_trsv_with_more_workgroups_than_the_device_holds(blas, big_ctx):
             bound = 2.0 ** -24 * (32 * (abs(float(hb[i])) + abs(float(hz[i]))) + 2 * float(spread))
             assert abs(float(hz[i]) + float(part) - float(hb[i])) <= bound, f"strsv trans={trans} row {i}"
 
+
+def test_launches_that_would_need_2_to_32_threads(blas, big_ctx):
+    """A launch may not have 2^32 threads or more: shapes whose natural grids would (a rank-1 update of
+    2^28 + 3 rows of 2 columns; the combine pass of a transposed product with 2^28 columns) must run with
+    capped grids, not fail."""
+    B, h = blas, big_ctx.h
+    dev = torch.device("cuda:0")
+    free, _ = torch.cuda.mem_get_info()
+    if free < 30 << 30:
+        pytest.skip("needs 30 GiB of free device memory")
+    m = (1 << 28) + 3
+    A = pattern_dev(2 * m, 9, 4, dev)
+    xm = pattern_dev(m, 7, 3, dev)
+    y2 = pattern_dev(2, 5, 2, dev, start=3)
+    assert B.mxb_sger(h, B.ROW_MAJOR, m, 2, 2.0, xm, 1, y2, 1, A, 2) == 0
+    hy = to_host(y2)
+    for a, b in windows(m):
+        want = pattern_host(2 * a, 2 * b, 9, 4)
+        O.ger(O.ROW_MAJOR, b - a, 2, 2.0, pattern_host(a, b, 7, 3), 1, hy, 1, want, 2)
+        assert bits_equal(to_host(A[2 * a:2 * b]), want), f"sger rows {a}..{b}"
+    del A, xm
+
+    rows, n = 16, 1 << 28
+    M = torch.empty(rows * n, dtype=torch.float32, device=dev)
+    for i in range(rows):
+        M[i * n:(i + 1) * n] = pattern_dev(n, 11, 5, dev, start=3 * i)
+    xr = pattern_dev(rows, 5, 2, dev)
+    y = torch.zeros(n, dtype=torch.float32, device=dev)
+    assert B.mxb_sgemv(h, B.ROW_MAJOR, B.TRANS, rows, n, 1.0, M, n, xr, 1, 0.0, y, 1) == 0
+    hx = to_host(xr)
+    for j in (0, 1, 63, 64, (1 << 27) - 1, 1 << 27, n - 65, n - 2, n - 1):
+        col = np.array([pattern_host(3 * i + j, 3 * i + j + 1, 11, 5)[0] for i in range(rows)], np.float32)
+        want = np.zeros(1, np.float32)
+        O.gemv(O.ROW_MAJOR, O.NO_TRANS, 1, rows, 1.0, col, rows, hx, 1, 0.0, want, 1)
+        assert bits_equal(to_host(y[j:j + 1])[0], want[0]), f"sgemv T column {j}"
+
