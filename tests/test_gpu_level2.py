@@ -639,6 +639,32 @@ def test_gemv_skinny(blas, ctx):
             A_OFFSET[0] = 0
 
 
+def test_gemv_skinny_double(blas, ctx):
+    """The same kernels in double precision: up to 16 (8 transposed) columns from 100000 rows, up to 46
+    (40) columns from a million (half a million) rows; whole and ragged widths, pitches, increments."""
+    dt = np.float64
+    for (m, n) in [(100000, 2), (100001, 3), (120000, 8), (100000, 16)]:
+        for pad in (0, 1):
+            gemv_case(blas, ctx, dt, O.ROW_MAJOR, O.NO_TRANS, m, n, 1.5, 0.5, pad, 1, 1)
+    for (m, n) in [(100000, 2), (100001, 5), (120000, 8)]:
+        for pad in (0, 1):
+            gemv_case(blas, ctx, dt, O.ROW_MAJOR, O.TRANS, m, n, 1.5, 0.5, pad, 1, 1)
+    for (m, n) in [(1000000, 41), (1000001, 46), (1000000, 24)]:
+        gemv_case(blas, ctx, dt, O.ROW_MAJOR, O.NO_TRANS, m, n, 1.5, 0.5, 1, 1, 1)
+    for (m, n) in [(500000, 40), (500001, 33), (600000, 12)]:
+        gemv_case(blas, ctx, dt, O.ROW_MAJOR, O.TRANS, m, n, 1.5, 0.5, 1, 1, 1)
+    for trans in (O.NO_TRANS, O.TRANS):
+        for incx, incy in [(2, 3), (-1, 1), (1, -2)]:
+            gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, 500000, 8, 1.5, 0.0, 4, incx, incy)
+        gemv_case(blas, ctx, dt, O.COL_MAJOR, trans, 8, 500000, 1.5, 0.5, 0, 1, 1)
+        gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, 500000, 7, 3, -2, 0, 1, 1, ints=True)
+        A_OFFSET[0] = 1
+        try:
+            gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, 500000, 5, 1.5, 0.5, 1, 1, 1)
+        finally:
+            A_OFFSET[0] = 0
+
+
 @pytest.mark.parametrize("dt", DT)
 def test_ger_skinny(blas, ctx, dt):
     for (m, n) in [(100000, 40), (131072, 16), (100001, 24), (150000, 4), (100000, 8)] + ([(120000, 48)] if dt == np.float32 else []):
