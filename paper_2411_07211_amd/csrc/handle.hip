@@ -152,7 +152,7 @@ size_t mxb_workspace_bytes(int routine, int elem_size, int64_t m, int64_t n)
             a = a > b ? a : b;
             // the skinny transposed product keeps one partial vector per block
             const int64_t narrow = m < n ? m : n;
-            b = narrow <= 48 ? skinny_workspace_bytes(narrow, elem_size) : 0;
+            b = narrow <= 68 ? skinny_workspace_bytes(narrow, elem_size) : 0;
             a = a > b ? a : b;
             // few long rows, not transposed: partial results of the column chunks
             b = align_up((size_t)(kWideFillRows + 2 * kWideMaxRows) * (size_t)elem_size, 256);

@@ -8,13 +8,17 @@ namespace mxb {
 enum SkinnyOp { SKINNY_GEMV_N, SKINNY_GEMV_T, SKINNY_GER };
 
 // Does the skinny path take this operation on a rows x cols row-major matrix with this base and
-// pitch?  The limits are where the skinny kernels measured faster than the general ones: in fp32
-// rows of up to 12 vectors of 16 bytes (48 columns); in fp64 up to 23 vectors (46 columns; 20 transposed) for
-// the products when there are a million rows (half a million transposed), up to 16 (8) columns from
-// 100000 rows, and up to 20 vectors (40 columns) for the rank-1 update; at least one vector per
-// row, and enough rows that the run is not launch-bound (the transposed product also has to pay
-// for its second kernel).  With 4194304 rows of 2 .. 16 doubles the general kernels take 136-183
-// us whatever the width, the skinny ones 21-101 us.
+// pitch?  The limits are where the skinny kernels measured faster than the general ones (nv =
+// 16-byte vectors per row, the last one moved back when the width is ragged):
+//   fp32  A*x     nv <= 32 (128 columns), and 48 <= nv <= 64 where a row fills most of a wavefront
+//                 (2097152 x 127: 49 -> 80 % of peak, x 100: 55 -> 78 %, x 255: 59 -> 80 %);
+//         A^t*x   nv <= 17 (68 columns), from 500000 rows (it pays for a second kernel);
+//         x*y^t   nv <= 12, and up to 16 for whole vectors (x 64: 52 -> 70 %; ragged rows lose);
+//   fp64  A*x     nv <= 8 from 100000 rows, nv <= 32 (64 columns) from a million (4194304 rows of
+//                 2 .. 16 doubles: the general kernels take 136-183 us whatever the width, these
+//                 21-101 us);
+//         A^t*x   nv <= 4 from 100000 rows, nv <= 20 from 500000;   x*y^t   nv <= 20.
+// At least one vector per row, and enough rows that the run is not launch-bound.
 template <typename T>
 inline bool skinny_takes(SkinnyOp op, int64_t rows, int64_t cols, const T* A, int64_t lda)
 {
@@ -24,10 +28,12 @@ inline bool skinny_takes(SkinnyOp op, int64_t rows, int64_t cols, const T* A, in
     const int64_t nv = (cols + fv - 1) / fv;  // a ragged last vector is moved back to end at the last column
     if (sizeof(T) == 8) {
         if (op == SKINNY_GER) return nv <= 20 && rows >= 100000;
-        if (op == SKINNY_GEMV_N) return (nv <= 8 && rows >= 100000) || (nv <= 23 && rows >= 1000000);
+        if (op == SKINNY_GEMV_N) return (nv <= 8 && rows >= 100000) || (nv <= 32 && rows >= 1000000);
         return (nv <= 4 && rows >= 100000) || (nv <= 20 && rows >= 500000);
     }
-    return nv <= 12 && rows >= (op == SKINNY_GEMV_T ? 500000 : 100000);
+    if (op == SKINNY_GER) return (nv <= 12 || (nv <= 16 && cols % fv == 0)) && rows >= 100000;
+    if (op == SKINNY_GEMV_N) return (nv <= 32 || (nv >= 48 && nv <= 64)) && rows >= 100000;
+    return nv <= 17 && rows >= 500000;
 }
 
 // y = alpha*A*x + beta*y (A rows x cols, x has cols elements).  Pointers at logical element 0.

@@ -626,6 +626,16 @@ def test_gemv_skinny(blas, ctx):
         gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, 500000, 16, 3, -2, 0, 1, 1, ints=True)
     for (m, n) in [(100000, 40), (131072, 16), (100001, 24), (150000, 48)]:             # not transposed: from 100000 rows
         gemv_case(blas, ctx, dt, O.ROW_MAJOR, O.NO_TRANS, m, n, 1.5, 0.5, 0, 1, 1)
+    # not transposed: up to 32 vectors per row (two or more rows per wavefront), and 48 to 64 (one row)
+    for (m, n) in [(100000, 49), (100001, 65), (100000, 100), (120000, 127), (100000, 128), (100000, 200), (100003, 255), (100000, 256),
+                   (100000, 190), (100000, 129)]:
+        for pad in (0, 1):
+            gemv_case(blas, ctx, dt, O.ROW_MAJOR, O.NO_TRANS, m, n, 1.5, 0.5, pad, 1, 1)
+    gemv_case(blas, ctx, dt, O.ROW_MAJOR, O.NO_TRANS, 100000, 255, 3, -2, 0, 2, -1, ints=True)
+    # transposed: up to 17 vectors per row
+    for (m, n) in [(500000, 56), (500001, 65), (500000, 68), (500000, 69)]:
+        gemv_case(blas, ctx, dt, O.ROW_MAJOR, O.TRANS, m, n, 1.5, 0.5, 1, 1, 1)
+    gemv_case(blas, ctx, dt, O.ROW_MAJOR, O.TRANS, 500000, 64, 3, -2, 0, 1, 1, ints=True)
     # rows that are not a whole number of vectors, odd pitches, a displaced base
     for off in (0, 1):
         A_OFFSET[0] = off
@@ -649,7 +659,7 @@ def test_gemv_skinny_double(blas, ctx):
     for (m, n) in [(100000, 2), (100001, 5), (120000, 8)]:
         for pad in (0, 1):
             gemv_case(blas, ctx, dt, O.ROW_MAJOR, O.TRANS, m, n, 1.5, 0.5, pad, 1, 1)
-    for (m, n) in [(1000000, 41), (1000001, 46), (1000000, 24)]:
+    for (m, n) in [(1000000, 41), (1000001, 46), (1000000, 24), (1000000, 49), (1000000, 64), (1000000, 63), (1000000, 65)]:
         gemv_case(blas, ctx, dt, O.ROW_MAJOR, O.NO_TRANS, m, n, 1.5, 0.5, 1, 1, 1)
     for (m, n) in [(500000, 40), (500001, 33), (600000, 12)]:
         gemv_case(blas, ctx, dt, O.ROW_MAJOR, O.TRANS, m, n, 1.5, 0.5, 1, 1, 1)
@@ -667,7 +677,8 @@ def test_gemv_skinny_double(blas, ctx):
 
 @pytest.mark.parametrize("dt", DT)
 def test_ger_skinny(blas, ctx, dt):
-    for (m, n) in [(100000, 40), (131072, 16), (100001, 24), (150000, 4), (100000, 8)] + ([(120000, 48)] if dt == np.float32 else []):
+    for (m, n) in [(100000, 40), (131072, 16), (100001, 24), (150000, 4), (100000, 8)] + (
+            [(120000, 48), (100000, 56), (100000, 64), (100000, 60), (100000, 68)] if dt == np.float32 else []):
         for pad in (0, 4):
             ger_case(blas, ctx, dt, O.ROW_MAJOR, m, n, 0.3, pad, 1, 1)
     ger_case(blas, ctx, dt, O.ROW_MAJOR, 100000, 40, -1.5, 4, 2, -3)
