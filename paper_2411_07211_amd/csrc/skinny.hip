@@ -69,7 +69,7 @@ __device__ __forceinline__ LaneMap lane_map(int nv, int N, int vec)
 
 // Rows are dealt in tiles of kSlots*G adjacent rows per wavefront, tiles cyclically to all
 // wavefronts of the grid: slot u of a tile holds rows tile*kSlots*G + u*G + g.
-template <typename T, int VEC>
+template <typename T, int VEC, bool BETA>
 __global__ void __launch_bounds__(kThreads) skinny_gemv_n_kernel(const SkinnyArgs<T> p, const T* __restrict__ A,
                                                                  const T* __restrict__ x, T* __restrict__ y)
 {
@@ -95,6 +95,16 @@ __global__ void __launch_bounds__(kThreads) skinny_gemv_n_kernel(const SkinnyArg
                 if (i < p.M) a[u] = ld_matrix<T, VEC>(A + i * p.lda + m.c);
             }
         }
+        // the old y of the tile's rows travels with the matrix (every lane of a row asks for the same
+        // element): read one by one after the sums, each would cost a round trip of its own
+        T yo[kSlots];
+        if (BETA) {
+#pragma unroll
+            for (int u = 0; u < kSlots; ++u) {
+                const int64_t i = row0 + (int64_t)u * m.G;
+                yo[u] = y[(i < p.M ? i : p.M - 1) * p.incl];
+            }
+        }
         __builtin_amdgcn_sched_barrier(0);   // every load of the tile is in flight before the first FMA
 #pragma unroll
         for (int u = 0; u < kSlots; ++u) {
@@ -113,7 +123,7 @@ __global__ void __launch_bounds__(kThreads) skinny_gemv_n_kernel(const SkinnyArg
             if (m.active && m.k == 0 && i < p.M) {
                 T* yp = y + i * p.incl;
                 T v = p.alpha * s;
-                if (p.beta != T(0)) v = fmad(p.beta, *yp, v);
+                if (BETA) v = fmad(p.beta, yo[u], v);
                 *yp = v;
             }
         }
@@ -291,7 +301,9 @@ int skinny_gemv_n(mxb_handle_t h, int64_t rows, int64_t cols, T alpha, const T* 
                   T* y0, int64_t incy)
 {
     const SkinnyArgs<T> a = make_args<T>(rows, cols, Full<T>::vec, lda, incx, incy, alpha, beta);
-    MXB_SKINNY_DISPATCH(skinny_gemv_n_kernel, tile_blocks(rows, a.nv, (int64_t)kCUs * 16), A, x0, y0);
+    const dim3 grid((unsigned)tile_blocks(rows, a.nv, (int64_t)kCUs * 16));
+    if (beta != T(0)) hipLaunchKernelGGL((skinny_gemv_n_kernel<T, Full<T>::vec, true>), grid, dim3(kThreads), 0, h->stream, a, A, x0, y0);
+    else hipLaunchKernelGGL((skinny_gemv_n_kernel<T, Full<T>::vec, false>), grid, dim3(kThreads), 0, h->stream, a, A, x0, y0);
     return launch_status();
 }
 

@@ -14,7 +14,8 @@ enum SkinnyOp { SKINNY_GEMV_N, SKINNY_GEMV_T, SKINNY_GER };
 //                 (2097152 x 127: 49 -> 80 % of peak, x 100: 55 -> 78 %, x 255: 59 -> 80 %);
 //         A^t*x   nv <= 17 (68 columns), from 500000 rows (it pays for a second kernel);
 //         x*y^t   nv <= 12, and up to 16 for whole vectors (x 64: 52 -> 70 %; ragged rows lose);
-//   fp64  A*x     nv <= 8 from 100000 rows, nv <= 32 (64 columns) from a million (4194304 rows of
+//   fp64  A*x     nv <= 8 from 100000 rows; from a million nv <= 20, and up to 32 for odd widths,
+//                 which the general kernel takes badly (4194304 x 41: 410 -> 253 us) (4194304 rows of
 //                 2 .. 16 doubles: the general kernels take 136-183 us whatever the width, these
 //                 21-101 us);
 //         A^t*x   nv <= 4 from 100000 rows, nv <= 20 from 500000;   x*y^t   nv <= 20.
@@ -28,7 +29,7 @@ inline bool skinny_takes(SkinnyOp op, int64_t rows, int64_t cols, const T* A, in
     const int64_t nv = (cols + fv - 1) / fv;  // a ragged last vector is moved back to end at the last column
     if (sizeof(T) == 8) {
         if (op == SKINNY_GER) return nv <= 20 && rows >= 100000;
-        if (op == SKINNY_GEMV_N) return (nv <= 8 && rows >= 100000) || (nv <= 32 && rows >= 1000000);
+        if (op == SKINNY_GEMV_N) return (nv <= 8 && rows >= 100000) || ((nv <= 20 || (nv <= 32 && cols % 2 == 1)) && rows >= 1000000);
         return (nv <= 4 && rows >= 100000) || (nv <= 20 && rows >= 500000);
     }
     if (op == SKINNY_GER) return (nv <= 12 || (nv <= 16 && cols % fv == 0)) && rows >= 100000;
