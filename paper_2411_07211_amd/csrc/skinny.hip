@@ -74,15 +74,19 @@ __global__ void __launch_bounds__(kThreads) skinny_gemv_n_kernel(const SkinnyArg
                                                                  const T* __restrict__ x, T* __restrict__ y)
 {
     typedef typename VecOf<T, VEC>::type V;
+    // the sums of a tile, in row order: written by the first lane of each row, read back one row per
+    // lane, so that y is read and written in whole runs of adjacent elements
+    __shared__ T sums[kWaves][kSlots * kWave];
     const LaneMap m = lane_map(p.nv, p.N, VEC);
+    T* const mine = sums[threadIdx.x >> 6];
     T xr[VEC];
 #pragma unroll
     for (int e = 0; e < VEC; ++e) xr[e] = m.active ? x[(int64_t)(m.c + e) * p.incs] : T(0);
-    const int64_t rows_per_tile = (int64_t)kSlots * m.G;
+    const int rows_per_tile = kSlots * m.G;
     const int64_t ntiles = (p.M + rows_per_tile - 1) / rows_per_tile;
     const int64_t wave0 = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6), nwaves = (int64_t)gridDim.x * kWaves;
     for (int64_t t = wave0; t < ntiles; t += nwaves) {
-        const int64_t row0 = t * rows_per_tile + m.g;
+        const int64_t tile0 = t * rows_per_tile, row0 = tile0 + m.g;
         V a[kSlots];
         if ((t + 1) * rows_per_tile <= p.M) {      // whole tile: no predicate, so that all loads issue back to back
 #pragma unroll
@@ -95,14 +99,15 @@ __global__ void __launch_bounds__(kThreads) skinny_gemv_n_kernel(const SkinnyArg
                 if (i < p.M) a[u] = ld_matrix<T, VEC>(A + i * p.lda + m.c);
             }
         }
-        // the old y of the tile's rows travels with the matrix (every lane of a row asks for the same
-        // element): read one by one after the sums, each would cost a round trip of its own
+        // the old y of the tile's rows travels with the matrix, 64 adjacent rows per load: read after
+        // the sums it would cost a round trip of its own
         T yo[kSlots];
         if (BETA) {
 #pragma unroll
-            for (int u = 0; u < kSlots; ++u) {
-                const int64_t i = row0 + (int64_t)u * m.G;
-                yo[u] = y[(i < p.M ? i : p.M - 1) * p.incl];
+            for (int q = 0; q < kSlots; ++q) {
+                const int r = q * kWave + m.lane;
+                const int64_t i = tile0 + r;
+                if (r < rows_per_tile && i < p.M) yo[q] = y[i * p.incl];
             }
         }
         __builtin_amdgcn_sched_barrier(0);   // every load of the tile is in flight before the first FMA
@@ -119,14 +124,23 @@ __global__ void __launch_bounds__(kThreads) skinny_gemv_n_kernel(const SkinnyArg
                     s += (m.k + off < p.nv) ? o : T(0);
                 }
             }
-            const int64_t i = row0 + (int64_t)u * m.G;
-            if (m.active && m.k == 0 && i < p.M) {
-                T* yp = y + i * p.incl;
-                T v = p.alpha * s;
-                if (BETA) v = fmad(p.beta, yo[u], v);
-                *yp = v;
+            if (m.active && m.k == 0) mine[u * m.G + m.g] = s;
+        }
+        // the wavefront's own LDS traffic runs in order: only the compiler has to keep it so
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront", "local");
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int q = 0; q < kSlots; ++q) {
+            const int r = q * kWave + m.lane;
+            const int64_t i = tile0 + r;
+            if (r < rows_per_tile && i < p.M) {
+                T v = p.alpha * mine[r];
+                if (BETA) v = fmad(p.beta, yo[q], v);
+                y[i * p.incl] = v;
             }
         }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront", "local");
+        __builtin_amdgcn_wave_barrier();
     }
 }
 

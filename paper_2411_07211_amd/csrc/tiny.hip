@@ -38,7 +38,7 @@ __device__ __forceinline__ T group_sum(T v)
     return v;
 }
 
-template <typename T, int VEC, int LPR>
+template <typename T, int VEC, int LPR, bool BETA>
 __global__ void __launch_bounds__(kThreads) tiny_gemv_n_kernel(const TinyArgs<T> p)
 {
     typedef typename VecOf<T, VEC>::type V;
@@ -53,6 +53,7 @@ __global__ void __launch_bounds__(kThreads) tiny_gemv_n_kernel(const TinyArgs<T>
     const uint32_t wave0 = blockIdx.x * kWaves + (threadIdx.x >> 6), nwaves = gridDim.x * kWaves;
     for (uint32_t t = wave0; t < ntiles; t += nwaves) {
         V a[kSlots], xv[kSlots];
+        T yo[kSlots];
         uint32_t b[kSlots], i[kSlots];
 #pragma unroll
         for (int u = 0; u < kSlots; ++u) {
@@ -60,6 +61,8 @@ __global__ void __launch_bounds__(kThreads) tiny_gemv_n_kernel(const TinyArgs<T>
             b[u] = row / (uint32_t)p.M;
             i[u] = row - b[u] * (uint32_t)p.M;
             a[u] = ld_matrix<T, VEC>(p.A + (int64_t)b[u] * p.sA + (int64_t)i[u] * p.lda + cl);
+            // the old y travels with the tile: read after the sums, each would cost a round trip of its own
+            if (BETA) yo[u] = p.y[(int64_t)b[u] * p.sy + (int64_t)i[u] * p.incy];
             const T* xb = p.x + (int64_t)b[u] * p.sx;
             if (p.incx == 1) {
                 xv[u] = ld_matrix<T, VEC>(xb + cl);
@@ -79,7 +82,7 @@ __global__ void __launch_bounds__(kThreads) tiny_gemv_n_kernel(const TinyArgs<T>
             if (l == 0 && row < p.total) {
                 T* yp = p.y + (int64_t)b[u] * p.sy + (int64_t)i[u] * p.incy;
                 T v = p.alpha * s;
-                if (p.beta != T(0)) v = fmad(p.beta, *yp, v);
+                if (BETA) v = fmad(p.beta, yo[u], v);
                 *yp = v;
             }
         }
@@ -117,7 +120,7 @@ __device__ __forceinline__ T strided_sum(T v, int lane)
     return v;
 }
 
-template <typename T, int VEC, int LPR>
+template <typename T, int VEC, int LPR, bool BETA>
 __global__ void __launch_bounds__(kThreads) tiny_gemv_t_kernel(const TinyArgs<T> p, uint32_t batch)
 {
     typedef typename VecOf<T, VEC>::type V;
@@ -138,6 +141,7 @@ __global__ void __launch_bounds__(kThreads) tiny_gemv_t_kernel(const TinyArgs<T>
     for (uint64_t it = 0; it < items; it += kSlots) {
         V a[kSlots];
         T xi[kSlots];
+        T yo[kSlots][VEC];
         uint32_t bb = b, ss = s;
 #pragma unroll
         for (int u = 0; u < kSlots; ++u) {
@@ -145,7 +149,14 @@ __global__ void __launch_bounds__(kThreads) tiny_gemv_t_kernel(const TinyArgs<T>
             const uint32_t i = min(ss * G + g, (uint32_t)p.M - 1);        // clamp: loads stay in bounds
             a[u] = ld_matrix<T, VEC>(p.A + (int64_t)bu * p.sA + (int64_t)i * p.lda + cl);
             xi[u] = p.x[(int64_t)bu * p.sx + (int64_t)i * p.incx];
-            if (++ss == groups) { ss = 0; ++bb; }
+            if (++ss == groups) {             // this slot completes a problem: its old y travels with the tile
+                if (BETA && g == 0) {
+#pragma unroll
+                    for (int k = 0; k < VEC; ++k) yo[u][k] = p.y[(int64_t)bu * p.sy + (int64_t)(cl + k) * p.incy];
+                }
+                ss = 0;
+                ++bb;
+            }
         }
         __builtin_amdgcn_sched_barrier(0);   // every load of the batch is in flight before the first FMA
 #pragma unroll
@@ -161,7 +172,7 @@ __global__ void __launch_bounds__(kThreads) tiny_gemv_t_kernel(const TinyArgs<T>
                         if (g == 0 && cl + k >= c) {
                             T* yp = p.y + (int64_t)b * p.sy + (int64_t)(cl + k) * p.incy;
                             T v = p.alpha * tot;
-                            if (p.beta != T(0)) v = fmad(p.beta, *yp, v);
+                            if (BETA) v = fmad(p.beta, yo[u][k], v);
                             *yp = v;
                         }
                         acc[k] = T(0);
@@ -188,9 +199,13 @@ int tiny_gemv_n(mxb_handle_t h, int64_t rows, int64_t cols, T alpha, const T* A,
     int64_t grid = ceil_div(tiles, (int64_t)kWaves);
     if (grid > (int64_t)kCUs * 16) grid = (int64_t)kCUs * 16;
     const dim3 g((unsigned)grid), blk(kThreads);
-    if (lpr == 4) hipLaunchKernelGGL((tiny_gemv_n_kernel<T, VEC, 4>), g, blk, 0, h->stream, a);
-    else if (lpr == 8) hipLaunchKernelGGL((tiny_gemv_n_kernel<T, VEC, 8>), g, blk, 0, h->stream, a);
-    else hipLaunchKernelGGL((tiny_gemv_n_kernel<T, VEC, 16>), g, blk, 0, h->stream, a);
+#define MXB_TINY_N(LPR_)                                                                                   \
+    if (beta != T(0)) hipLaunchKernelGGL((tiny_gemv_n_kernel<T, VEC, LPR_, true>), g, blk, 0, h->stream, a); \
+    else hipLaunchKernelGGL((tiny_gemv_n_kernel<T, VEC, LPR_, false>), g, blk, 0, h->stream, a)
+    if (lpr == 4) { MXB_TINY_N(4); }
+    else if (lpr == 8) { MXB_TINY_N(8); }
+    else { MXB_TINY_N(16); }
+#undef MXB_TINY_N
     return launch_status();
 }
 
@@ -206,9 +221,13 @@ int tiny_gemv_t(mxb_handle_t h, int64_t rows, int64_t cols, T alpha, const T* A,
     int64_t waves = (int64_t)kCUs * 16 * kWaves;
     if (waves > batch) waves = batch;
     const dim3 g((unsigned)ceil_div(waves, (int64_t)kWaves)), blk(kThreads);
-    if (lpr == 4) hipLaunchKernelGGL((tiny_gemv_t_kernel<T, VEC, 4>), g, blk, 0, h->stream, a, (uint32_t)batch);
-    else if (lpr == 8) hipLaunchKernelGGL((tiny_gemv_t_kernel<T, VEC, 8>), g, blk, 0, h->stream, a, (uint32_t)batch);
-    else hipLaunchKernelGGL((tiny_gemv_t_kernel<T, VEC, 16>), g, blk, 0, h->stream, a, (uint32_t)batch);
+#define MXB_TINY_T(LPR_)                                                                                                      \
+    if (beta != T(0)) hipLaunchKernelGGL((tiny_gemv_t_kernel<T, VEC, LPR_, true>), g, blk, 0, h->stream, a, (uint32_t)batch); \
+    else hipLaunchKernelGGL((tiny_gemv_t_kernel<T, VEC, LPR_, false>), g, blk, 0, h->stream, a, (uint32_t)batch)
+    if (lpr == 4) { MXB_TINY_T(4); }
+    else if (lpr == 8) { MXB_TINY_T(8); }
+    else { MXB_TINY_T(16); }
+#undef MXB_TINY_T
     return launch_status();
 }
 
