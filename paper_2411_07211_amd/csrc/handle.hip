@@ -156,6 +156,8 @@ size_t mxb_workspace_bytes(int routine, int elem_size, int64_t m, int64_t n)
             a = a > b ? a : b;
             // few long rows, not transposed: partial results of the column chunks
             b = align_up((size_t)(kWideFillRows + 2 * kWideMaxRows) * (size_t)elem_size, 256);
+            a = a > b ? a : b;
+            b = align_up((size_t)(kFewBlocks * kFewMaxRows) * (size_t)elem_size, 256);     // a handful of rows
             return a > b ? a : b;
         }
         case MXB_GEMV_BATCHED: {

@@ -338,6 +338,91 @@ __global__ void __launch_bounds__(kColaccThreads) colacc_kernel(const ColaccArgs
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// few long rows, not transposed
+
+constexpr int kFewThreads = 256;
+
+// A*x for at most MR rows of any length: the result is a handful of dot products that share x.
+// The columns are dealt to the blocks in tiles of U runs of 256 vectors; a lane keeps its vector
+// of x and the matching vector of every row in flight, so x is read once whatever the number of
+// rows, and sums one partial result per row.  Block b writes its M sums to partials[b][0..M);
+// the pass that combines partial vectors adds them in block order.
+template <typename T, int VEC, int MR>
+__global__ void __launch_bounds__(kFewThreads) fewrows_kernel(int M, int64_t N, const T* __restrict__ A, int64_t lda,
+                                                              const T* __restrict__ x, int64_t incx, T* __restrict__ partials)
+{
+    typedef typename VecOf<T, VEC>::type V;
+    constexpr int U = MR <= 2 ? 8 : (MR <= 4 ? 4 : (MR <= 8 ? 2 : 1));   // 16 to 33 loads in flight per lane
+    constexpr int NW = kFewThreads / kWave;
+    __shared__ T red[NW][MR];
+    const int64_t nvec = N / VEC, tile = (int64_t)kFewThreads * U, nfull = nvec / tile;
+    T acc[MR];
+#pragma unroll
+    for (int i = 0; i < MR; ++i) acc[i] = T(0);
+
+    auto load_x = [&](int64_t v) -> V {
+        if (incx == 1) return ld_matrix<T, VEC>(x + v * VEC);
+        V r;
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) r[k] = x[(v * VEC + k) * incx];
+        return r;
+    };
+    for (int64_t t = blockIdx.x; t < nfull; t += gridDim.x) {
+        const int64_t v0 = t * tile + threadIdx.x;
+        V xv[U], a[U][MR];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            xv[u] = load_x(v0 + u * kFewThreads);
+#pragma unroll
+            for (int i = 0; i < MR; ++i)
+                if (i < M) a[u][i] = ld_matrix<T, VEC>(A + i * lda + (v0 + u * kFewThreads) * VEC);     // wave-uniform
+        }
+        __builtin_amdgcn_sched_barrier(0);   // every load of the tile is in flight before the first FMA
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int i = 0; i < MR; ++i)
+                if (i < M)
+#pragma unroll
+                    for (int k = 0; k < VEC; ++k) acc[i] = fmad(a[u][i][k], xv[u][k], acc[i]);
+    }
+    // the vectors after the last whole tile go to the block whose turn it is; the elements after
+    // the last whole vector to that block's first lane
+    if ((int64_t)blockIdx.x == nfull % gridDim.x) {
+        for (int64_t v = nfull * tile + threadIdx.x; v < nvec; v += kFewThreads) {
+            const V xv = load_x(v);
+#pragma unroll
+            for (int i = 0; i < MR; ++i)
+                if (i < M) {
+                    const V a = ld_matrix<T, VEC>(A + i * lda + v * VEC);
+#pragma unroll
+                    for (int k = 0; k < VEC; ++k) acc[i] = fmad(a[k], xv[k], acc[i]);
+                }
+        }
+        if (threadIdx.x == 0)
+            for (int64_t j = nvec * VEC; j < N; ++j) {
+                const T xj = x[j * incx];
+#pragma unroll
+                for (int i = 0; i < MR; ++i)
+                    if (i < M) acc[i] = fmad(A[i * lda + j], xj, acc[i]);
+            }
+    }
+    const int wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int i = 0; i < MR; ++i) {
+        const T w = wave_sum(acc[i]);
+        if ((threadIdx.x & (kWave - 1)) == 0) red[wave][i] = w;
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < M) {
+        T tot = red[0][threadIdx.x];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) tot += red[w][threadIdx.x];
+        partials[(int64_t)blockIdx.x * M + threadIdx.x] = tot;
+    }
+}
+
 constexpr int kCombineGroups = 16;
 constexpr int64_t kMaxCombineBlocks = 1 << 21;      // x 1024 threads: below the 2^32 threads a launch may have
 
@@ -616,7 +701,34 @@ int gemv_rows(mxb_handle_t h, bool no_trans, int64_t rows, int64_t cols, T alpha
     if (tiny_takes<T>(rows, cols, batch))
         return no_trans ? tiny_gemv_n<T>(h, rows, cols, alpha, A, lda, sA, x0, incx, sx, beta, y0, incy, sy, batch)
                         : tiny_gemv_t<T>(h, rows, cols, alpha, A, lda, sA, x0, incx, sx, beta, y0, incy, sy, batch);
-    if (no_trans && batch == 1 && rows <= kWideMaxRows && cols >= 2 * kWideMinChunk) {
+    if (no_trans && batch == 1 && cols >= kWideMinCols && (rows <= kFewRows || (rows <= kFewMaxRows && cols >= kFewManyMinCols))) {
+        // A handful of very long rows: dot products that share x, one partial result per row and block.
+        constexpr int FV = Full<T>::vec;
+        const int mr = rows <= 1 ? 1 : (rows <= 2 ? 2 : (rows <= 4 ? 4 : (rows <= 8 ? 8 : (rows <= 16 ? 16 : 32))));
+        const int u = mr <= 2 ? 8 : (mr <= 4 ? 4 : (mr <= 8 ? 2 : 1));          // as in the kernel
+        const int64_t tiles = cols / FV / ((int64_t)kFewThreads * u);
+        const int64_t grid = tiles < 1 ? 1 : (tiles < kFewBlocks ? tiles : kFewBlocks);
+        T* partials = static_cast<T*>(take_workspace(h, (size_t)grid * (size_t)rows * sizeof(T)));
+        if (!partials) return MXB_ERR_WORKSPACE;
+#define MXB_FEW(MR_)                                                                                                          \
+    hipLaunchKernelGGL((fewrows_kernel<T, FV, MR_>), dim3((unsigned)grid), dim3(kFewThreads), 0, h->stream, (int)rows, cols, A, lda, \
+                       x0, incx, partials)
+        switch (mr) {
+            case 1: MXB_FEW(1); break;
+            case 2: MXB_FEW(2); break;
+            case 4: MXB_FEW(4); break;
+            case 8: MXB_FEW(8); break;
+            case 16: MXB_FEW(16); break;
+            default: MXB_FEW(32); break;
+        }
+#undef MXB_FEW
+        const int st = launch_status();
+        if (st != MXB_OK) return st;
+        hipLaunchKernelGGL(colacc_combine_kernel<T>, dim3(1u, 1u), dim3(kCombineGroups * kWave), 0, h->stream, grid, rows, rows, partials,
+                           alpha, beta, y0, incy, (int64_t)0, (int64_t)0);
+        return launch_status();
+    }
+    if (no_trans && batch == 1 && rows <= kWideMaxRows && cols >= kWideMinCols) {
         // Few, very long rows: the row-dot grid wants some 8192 rows to be busy.  The columns are cut
         // into chunks, the chunks run as a batch of rows x chunk problems that write partial results
         // (a shorter last chunk in a launch of its own), and the pass that combines the partial

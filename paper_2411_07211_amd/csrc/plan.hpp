@@ -16,11 +16,15 @@ struct ColaccPlan {
     int64_t nparts;          // row groups = partial vectors per column
 };
 
-// gemv, not transposed, few and very long rows: up to kWideMaxRows rows the columns are split into
-// chunks of at least kWideMinChunk so that rows x chunks reaches kWideFillRows (what keeps the
-// row-dot grid busy); the chunks' partial results take at most kWideFillRows + 2 rows' worth of
-// elements of workspace.
-constexpr int64_t kWideMaxRows = 4096, kWideMinChunk = 16384, kWideFillRows = 8192;
+// gemv, not transposed, few and very long rows: up to kWideMaxRows rows of at least kWideMinCols
+// columns, the columns are split into chunks of at least kWideMinChunk so that rows x chunks
+// reaches kWideFillRows (what keeps the row-dot grid busy); the chunks' partial results take at
+// most kWideFillRows + 2 rows' worth of elements of workspace.
+constexpr int64_t kWideMaxRows = 4096, kWideMinCols = 32768, kWideMinChunk = 2048, kWideFillRows = 8192;
+// Up to kFewRows rows of that length (up to kFewMaxRows rows of at least kFewManyMinCols columns)
+// are a handful of dot products sharing x: at most kFewBlocks blocks (two per compute unit read
+// fastest, measured from 256 to 4096), each with one partial result per row.
+constexpr int64_t kFewRows = 16, kFewMaxRows = 32, kFewManyMinCols = (int64_t)1 << 21, kFewBlocks = 512;
 
 inline ColaccPlan colacc_plan(int64_t rows, int64_t cols, int elem_size, int vec, int64_t target_blocks,
                               int64_t narrow_blocks, int64_t min_rows)

@@ -93,6 +93,16 @@ def test_gemv_shapes(blas, ctx, dt, trans):
         for beta in (0.0, -0.5):
             gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, 1.5, beta, pad, incx, incy)
     gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, 64, 70000, 2, 1, 0, 1, 1, ints=True)
+    # a handful of very long rows: not transposed, dot products that share x (every row count the
+    # kernel is built for and the ones between, whole tiles only, ragged vectors and elements,
+    # several tiles per block, strided and reversed x)
+    for (m, n, pad, incx, incy) in [(1, 32768, 0, 1, 1), (1, 5000003, 0, 1, 1), (2, 65536, 3, 1, 1), (3, 40001, 5, -1, 1),
+                                    (4, 32770, 0, 1, 2), (5, 100003, 1, 3, 1), (8, 1200007, 0, 1, 1), (9, 32768, 0, 1, -1),
+                                    (13, 70001, 7, 1, 1), (16, 300000, 0, 1, 1), (16, 33333, 2, -2, 3), (17, 2097152, 0, 1, 1),
+                                    (29, 2100001, 1, 1, 1), (32, 2097155, 0, 1, 1)]:
+        for beta in (0.0, -0.5):
+            gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, 1.5, beta, pad, incx, incy)
+    gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, 7, 90001, 2, 1, 0, 1, 1, ints=True)
 
 
 @pytest.mark.parametrize("dt", DT)
