@@ -423,6 +423,91 @@ __global__ void __launch_bounds__(kFewThreads) fewrows_kernel(int M, int64_t N, 
     }
 }
 
+// The transposed product for at most MR rows: y = alpha * sum_i x[i] * row i + beta * y, a stream
+// over the columns.  A lane keeps the matching vector of every row in flight for U vectors of y
+// (tiles of U runs of 256 vectors, one or a few tiles per block), x[i] in registers; no partial
+// results.
+template <typename T, int VEC, int MR, bool BETA>
+__global__ void __launch_bounds__(kFewThreads) fewrows_t_kernel(int M, int64_t N, const T* __restrict__ A, int64_t lda,
+                                                                const T* __restrict__ x, int64_t incx, T alpha, T beta,
+                                                                T* __restrict__ y, int64_t incy)
+{
+    typedef typename VecOf<T, VEC>::type V;
+    constexpr int U = MR <= 2 ? 8 : (MR <= 4 ? 4 : (MR <= 8 ? 2 : 1));
+    const int64_t nvec = N / VEC, tile = (int64_t)kFewThreads * U, nfull = nvec / tile;
+    T xr[MR];
+#pragma unroll
+    for (int i = 0; i < MR; ++i) xr[i] = i < M ? x[i * incx] : T(0);
+
+    auto load_y = [&](int64_t v) -> V {
+        if (incy == 1) return ld_matrix<T, VEC>(y + v * VEC);
+        V r;
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) r[k] = y[(v * VEC + k) * incy];
+        return r;
+    };
+    auto finish = [&](int64_t v, V acc, V yo) {
+        V out;
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) {
+            out[k] = alpha * acc[k];
+            if (BETA) out[k] = fmad(beta, yo[k], out[k]);
+        }
+        if (incy == 1) st_matrix<T, VEC>(y + v * VEC, out);
+        else
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) y[(v * VEC + k) * incy] = out[k];
+    };
+    for (int64_t t = blockIdx.x; t < nfull; t += gridDim.x) {
+        const int64_t v0 = t * tile + threadIdx.x;
+        V a[U][MR], yo[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+#pragma unroll
+            for (int i = 0; i < MR; ++i)
+                if (i < M) a[u][i] = ld_matrix<T, VEC>(A + i * lda + (v0 + u * kFewThreads) * VEC);     // wave-uniform
+            if (BETA) yo[u] = load_y(v0 + u * kFewThreads);
+        }
+        __builtin_amdgcn_sched_barrier(0);   // every load of the tile is in flight before the first FMA
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            V acc = V(T(0));
+#pragma unroll
+            for (int i = 0; i < MR; ++i)
+                if (i < M)
+#pragma unroll
+                    for (int k = 0; k < VEC; ++k) acc[k] = fmad(a[u][i][k], xr[i], acc[k]);
+            finish(v0 + u * kFewThreads, acc, yo[u]);
+        }
+    }
+    // the vectors after the last whole tile go to the block whose turn it is; the elements after
+    // the last whole vector to that block's first lane
+    if ((int64_t)blockIdx.x == nfull % gridDim.x) {
+        for (int64_t v = nfull * tile + threadIdx.x; v < nvec; v += kFewThreads) {
+            V acc = V(T(0)), yo = V(T(0));
+            if (BETA) yo = load_y(v);
+#pragma unroll
+            for (int i = 0; i < MR; ++i)
+                if (i < M) {
+                    const V a = ld_matrix<T, VEC>(A + i * lda + v * VEC);
+#pragma unroll
+                    for (int k = 0; k < VEC; ++k) acc[k] = fmad(a[k], xr[i], acc[k]);
+                }
+            finish(v, acc, yo);
+        }
+        if (threadIdx.x == 0)
+            for (int64_t j = nvec * VEC; j < N; ++j) {
+                T acc = T(0);
+#pragma unroll
+                for (int i = 0; i < MR; ++i)
+                    if (i < M) acc = fmad(A[i * lda + j], xr[i], acc);
+                T out = alpha * acc;
+                if (BETA) out = fmad(beta, y[j * incy], out);
+                y[j * incy] = out;
+            }
+    }
+}
+
 constexpr int kCombineGroups = 16;
 constexpr int64_t kMaxCombineBlocks = 1 << 21;      // x 1024 threads: below the 2^32 threads a launch may have
 
@@ -726,6 +811,28 @@ int gemv_rows(mxb_handle_t h, bool no_trans, int64_t rows, int64_t cols, T alpha
         if (st != MXB_OK) return st;
         hipLaunchKernelGGL(colacc_combine_kernel<T>, dim3(1u, 1u), dim3(kCombineGroups * kWave), 0, h->stream, grid, rows, rows, partials,
                            alpha, beta, y0, incy, (int64_t)0, (int64_t)0);
+        return launch_status();
+    }
+    if (!no_trans && batch == 1 && rows <= kFewStreamRows && rows * cols * (int64_t)sizeof(T) >= (rows <= 2 ? 1 : 2) * kFewStreamMinBytes) {
+        // The transposed product of a handful of very long rows: a stream over the columns.
+        constexpr int FV = Full<T>::vec;
+        const int mr = rows <= 1 ? 1 : (rows <= 2 ? 2 : 4);
+        const int u = mr <= 2 ? 8 : 4;                                           // as in the kernel
+        const int64_t tiles = cols / FV / ((int64_t)kFewThreads * u);
+        const int64_t grid = tiles < 1 ? 1 : (tiles < kFewStreamBlocks ? tiles : kFewStreamBlocks);
+#define MXB_FEW_T(MR_)                                                                                                       \
+    if (beta != T(0))                                                                                                        \
+        hipLaunchKernelGGL((fewrows_t_kernel<T, FV, MR_, true>), dim3((unsigned)grid), dim3(kFewThreads), 0, h->stream, (int)rows, \
+                           cols, A, lda, x0, incx, alpha, beta, y0, incy);                                                   \
+    else                                                                                                                     \
+        hipLaunchKernelGGL((fewrows_t_kernel<T, FV, MR_, false>), dim3((unsigned)grid), dim3(kFewThreads), 0, h->stream, (int)rows, \
+                           cols, A, lda, x0, incx, alpha, beta, y0, incy)
+        switch (mr) {
+            case 1: MXB_FEW_T(1); break;
+            case 2: MXB_FEW_T(2); break;
+            default: MXB_FEW_T(4); break;
+        }
+#undef MXB_FEW_T
         return launch_status();
     }
     if (no_trans && batch == 1 && rows <= kWideMaxRows && cols >= kWideMinCols) {

@@ -25,6 +25,11 @@ constexpr int64_t kWideMaxRows = 4096, kWideMinCols = 32768, kWideMinChunk = 204
 // are a handful of dot products sharing x: at most kFewBlocks blocks (two per compute unit read
 // fastest, measured from 256 to 4096), each with one partial result per row.
 constexpr int64_t kFewRows = 16, kFewMaxRows = 32, kFewManyMinCols = (int64_t)1 << 21, kFewBlocks = 512;
+// The transposed product of one to kFewStreamRows rows is a read-and-write stream over the columns:
+// one tile per block, as in the level-1 kernels (the cap keeps a launch below 2^32 threads); from
+// kFewStreamMinBytes of matrix for one or two rows, twice that for more (measured; below, and for
+// more rows, the column-accumulate kernels are as fast or faster).
+constexpr int64_t kFewStreamRows = 4, kFewStreamBlocks = (int64_t)1 << 22, kFewStreamMinBytes = (int64_t)48 << 20;
 
 inline ColaccPlan colacc_plan(int64_t rows, int64_t cols, int elem_size, int vec, int64_t target_blocks,
                               int64_t narrow_blocks, int64_t min_rows)

@@ -103,6 +103,13 @@ def test_gemv_shapes(blas, ctx, dt, trans):
         for beta in (0.0, -0.5):
             gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, 1.5, beta, pad, incx, incy)
     gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, 7, 90001, 2, 1, 0, 1, 1, ints=True)
+    # transposed, one to four rows of tens of megabytes: a stream over the columns (whole tiles and
+    # a ragged end, y strided and reversed, a pitch larger than the width)
+    if trans == O.TRANS:
+        for (m, n, pad, incx, incy) in [(1, 13000003, 0, 1, 1), (2, 7000001, 5, -1, 1), (3, 9000002, 0, 2, 2), (4, 7000003, 1, 1, -1)]:
+            for beta in (0.0, -0.5):
+                gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, 1.5, beta, pad, incx, incy)
+        gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, 4, 7000001, 2, 1, 0, 1, 1, ints=True)
 
 
 @pytest.mark.parametrize("dt", DT)
