@@ -319,6 +319,11 @@ def sweep(B, ctx, torch):
             rec(f"sgemv_{tn}_b", f"{n}x{n} x{batch}", 4 * n * n * batch,
                 lambda: B.mxb_sgemv_batched(h, B.ROW_MAJOR, tr, n, n, 1.0, A, n, n * n, xv, 1, n, 0.0, yv, 1, n, batch))
 
+    # a few rows of millions of columns (256 MiB and 1 GiB of matrix; the long vector counts in the bytes)
+    for m, n in ((1, 1 << 26), (4, 1 << 24), (16, 1 << 22), (256, 1 << 18), (2, 1 << 27), (4, 1 << 26), (16, 1 << 24), (256, 1 << 20)):
+        rec("sgemv_n_w", f"{m}x{n}", 4 * (m * n + n), lambda: B.mxb_sgemv(h, B.ROW_MAJOR, B.NO_TRANS, m, n, 1.0, A, n, y, 1, 0.0, yv, 1))
+        rec("sgemv_t_w", f"{m}x{n}", 4 * (m * n + n), lambda: B.mxb_sgemv(h, B.ROW_MAJOR, B.TRANS, m, n, 1.0, A, n, xv, 1, 0.0, y, 1))
+
     def bucket(nb):
         return "small (< 4 MiB)" if nb < (4 << 20) else "medium (< 256 MiB)" if nb < (256 << 20) else "large"
 
