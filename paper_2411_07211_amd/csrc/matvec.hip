@@ -374,9 +374,17 @@ __global__ void __launch_bounds__(kFewThreads) fewrows_kernel(int M, int64_t N, 
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             xv[u] = load_x(v0 + u * kFewThreads);
+            // one pointer walks down the rows, its step hidden from the compiler, which would
+            // otherwise keep every row's offset in scalar registers and spill them
+            const T* at = A + (v0 + u * kFewThreads) * VEC;
 #pragma unroll
             for (int i = 0; i < MR; ++i)
-                if (i < M) a[u][i] = ld_matrix<T, VEC>(A + i * lda + (v0 + u * kFewThreads) * VEC);     // wave-uniform
+                if (i < M) {                                                         // wave-uniform
+                    a[u][i] = ld_matrix<T, VEC>(at);
+                    int64_t step = lda;
+                    asm volatile("" : "+s"(step));
+                    at += step;
+                }
         }
         __builtin_amdgcn_sched_barrier(0);   // every load of the tile is in flight before the first FMA
 #pragma unroll
@@ -392,20 +400,30 @@ __global__ void __launch_bounds__(kFewThreads) fewrows_kernel(int M, int64_t N, 
     if ((int64_t)blockIdx.x == nfull % gridDim.x) {
         for (int64_t v = nfull * tile + threadIdx.x; v < nvec; v += kFewThreads) {
             const V xv = load_x(v);
+            const T* at = A + v * VEC;
 #pragma unroll
             for (int i = 0; i < MR; ++i)
                 if (i < M) {
-                    const V a = ld_matrix<T, VEC>(A + i * lda + v * VEC);
+                    const V a = ld_matrix<T, VEC>(at);
 #pragma unroll
                     for (int k = 0; k < VEC; ++k) acc[i] = fmad(a[k], xv[k], acc[i]);
+                    int64_t step = lda;
+                    asm volatile("" : "+s"(step));
+                    at += step;
                 }
         }
         if (threadIdx.x == 0)
             for (int64_t j = nvec * VEC; j < N; ++j) {
                 const T xj = x[j * incx];
+                const T* at = A + j;
 #pragma unroll
                 for (int i = 0; i < MR; ++i)
-                    if (i < M) acc[i] = fmad(A[i * lda + j], xj, acc[i]);
+                    if (i < M) {
+                        acc[i] = fmad(*at, xj, acc[i]);
+                        int64_t step = lda;
+                        asm volatile("" : "+s"(step));
+                        at += step;
+                    }
             }
     }
     const int wave = threadIdx.x >> 6;
@@ -792,7 +810,8 @@ int gemv_rows(mxb_handle_t h, bool no_trans, int64_t rows, int64_t cols, T alpha
         const int mr = rows <= 1 ? 1 : (rows <= 2 ? 2 : (rows <= 4 ? 4 : (rows <= 8 ? 8 : (rows <= 16 ? 16 : 32))));
         const int u = mr <= 2 ? 8 : (mr <= 4 ? 4 : (mr <= 8 ? 2 : 1));          // as in the kernel
         const int64_t tiles = cols / FV / ((int64_t)kFewThreads * u);
-        const int64_t grid = tiles < 1 ? 1 : (tiles < kFewBlocks ? tiles : kFewBlocks);
+        const int64_t cap = mr >= 16 ? kFewBlocks / 2 : kFewBlocks;     // 16 rows and more: one block per compute unit (measured)
+        const int64_t grid = tiles < 1 ? 1 : (tiles < cap ? tiles : cap);
         T* partials = static_cast<T*>(take_workspace(h, (size_t)grid * (size_t)rows * sizeof(T)));
         if (!partials) return MXB_ERR_WORKSPACE;
 #define MXB_FEW(MR_)                                                                                                          \
