@@ -11,11 +11,14 @@ enum SkinnyOp { SKINNY_GEMV_N, SKINNY_GEMV_T, SKINNY_GER };
 // pitch?  The limits are where the skinny kernels measured faster than the general ones (nv =
 // 16-byte vectors per row, the last one moved back when the width is ragged):
 //   fp32  A*x     nv <= 32 (128 columns), and 48 <= nv <= 64 where a row fills most of a wavefront
-//                 (2097152 x 127: 49 -> 80 % of peak, x 100: 55 -> 78 %, x 255: 59 -> 80 %);
+//                 (2097152 x 127: 49 -> 80 % of peak, x 100: 55 -> 78 %, x 255: 59 -> 80 %); 37 <= nv <= 47
+//                 unless the width is a multiple of 32 (x 170: 305 -> 248 us, x 188: 308 -> 254 us, but
+//                 x 160: 217 against 240 us; below, x 129 .. 140: 215-243 against 250-278 us);
 //         A^t*x   nv <= 17 (68 columns), from 500000 rows (it pays for a second kernel);
 //         x*y^t   nv <= 12, and up to 16 for whole vectors (x 64: 52 -> 70 %; ragged rows lose);
-//   fp64  A*x     nv <= 8 from 100000 rows; from a million nv <= 20, and up to 32 for odd widths,
-//                 which the general kernel takes badly (4194304 x 41: 410 -> 253 us) (4194304 rows of
+//   fp64  A*x     nv <= 8 from 100000 rows; from a million nv <= 31, and 32 for the odd width
+//                 (2097152 x 42: 167 -> 126 us, x 50: 205 -> 155 us, x 63: 258 -> 182 us; x 64 ties; one
+//                 row per wavefront, x 65 .. 96, loses: 230-270 against 314-325 us) (4194304 rows of
 //                 2 .. 16 doubles: the general kernels take 136-183 us whatever the width, these
 //                 21-101 us);
 //         A^t*x   nv <= 4 from 100000 rows, nv <= 20 from 500000;   x*y^t   nv <= 20.
@@ -29,11 +32,12 @@ inline bool skinny_takes(SkinnyOp op, int64_t rows, int64_t cols, const T* A, in
     const int64_t nv = (cols + fv - 1) / fv;  // a ragged last vector is moved back to end at the last column
     if (sizeof(T) == 8) {
         if (op == SKINNY_GER) return nv <= 20 && rows >= 100000;
-        if (op == SKINNY_GEMV_N) return (nv <= 8 && rows >= 100000) || ((nv <= 20 || (nv <= 32 && cols % 2 == 1)) && rows >= 1000000);
+        if (op == SKINNY_GEMV_N) return (nv <= 8 && rows >= 100000) || ((nv <= 31 || (nv == 32 && cols % 2 == 1)) && rows >= 1000000);
         return (nv <= 4 && rows >= 100000) || (nv <= 20 && rows >= 500000);
     }
     if (op == SKINNY_GER) return (nv <= 12 || (nv <= 16 && cols % fv == 0)) && rows >= 100000;
-    if (op == SKINNY_GEMV_N) return (nv <= 32 || (nv >= 48 && nv <= 64 && cols != 256)) && rows >= 100000;   // 256: the row-dot kernel is 1 % ahead
+    if (op == SKINNY_GEMV_N)      // 256: the row-dot kernel is 1 % ahead
+        return (nv <= 32 || (nv >= 37 && nv <= 47 && cols % 32 != 0) || (nv >= 48 && nv <= 64 && cols != 256)) && rows >= 100000;
     return nv <= 17 && rows >= 500000;
 }
 

@@ -645,7 +645,7 @@ def test_gemv_skinny(blas, ctx):
         gemv_case(blas, ctx, dt, O.ROW_MAJOR, O.NO_TRANS, m, n, 1.5, 0.5, 0, 1, 1)
     # not transposed: up to 32 vectors per row (two or more rows per wavefront), and 48 to 64 (one row)
     for (m, n) in [(100000, 49), (100001, 65), (100000, 100), (120000, 127), (100000, 128), (100000, 200), (100003, 255), (100000, 256),
-                   (100000, 190), (100000, 129)]:
+                   (100000, 190), (100000, 129), (100000, 145), (100001, 150), (100000, 160), (100000, 170), (100003, 188)]:
         for pad in (0, 1):
             gemv_case(blas, ctx, dt, O.ROW_MAJOR, O.NO_TRANS, m, n, 1.5, 0.5, pad, 1, 1)
     gemv_case(blas, ctx, dt, O.ROW_MAJOR, O.NO_TRANS, 100000, 255, 3, -2, 0, 2, -1, ints=True)
@@ -676,7 +676,8 @@ def test_gemv_skinny_double(blas, ctx):
     for (m, n) in [(100000, 2), (100001, 5), (120000, 8)]:
         for pad in (0, 1):
             gemv_case(blas, ctx, dt, O.ROW_MAJOR, O.TRANS, m, n, 1.5, 0.5, pad, 1, 1)
-    for (m, n) in [(1000000, 41), (1000001, 46), (1000000, 24), (1000000, 49), (1000000, 64), (1000000, 63), (1000000, 65)]:
+    for (m, n) in [(1000000, 41), (1000001, 46), (1000000, 24), (1000000, 49), (1000000, 64), (1000000, 63), (1000000, 65),
+                   (1000000, 42), (1000003, 50), (1000000, 62)]:
         gemv_case(blas, ctx, dt, O.ROW_MAJOR, O.NO_TRANS, m, n, 1.5, 0.5, 1, 1, 1)
     for (m, n) in [(500000, 40), (500001, 33), (600000, 12)]:
         gemv_case(blas, ctx, dt, O.ROW_MAJOR, O.TRANS, m, n, 1.5, 0.5, 1, 1, 1)
