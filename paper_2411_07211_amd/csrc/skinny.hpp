@@ -15,7 +15,8 @@ enum SkinnyOp { SKINNY_GEMV_N, SKINNY_GEMV_T, SKINNY_GER };
 //                 unless the width is a multiple of 32 (x 170: 305 -> 248 us, x 188: 308 -> 254 us, but
 //                 x 160: 217 against 240 us; below, x 129 .. 140: 215-243 against 250-278 us);
 //         A^t*x   nv <= 17 (68 columns), from 500000 rows (it pays for a second kernel);
-//         x*y^t   nv <= 12, and up to 16 for whole vectors (x 64: 52 -> 70 %; ragged rows lose);
+//         x*y^t   nv <= 12, and up to 20 for whole vectors (x 64: 52 -> 70 %, x 72: 273 -> 236 us, x 80:
+//                 282 -> 249 us; x 96 ties; ragged rows lose);
 //   fp64  A*x     nv <= 8 from 100000 rows; from a million nv <= 31, and 32 for the odd width
 //                 (2097152 x 42: 167 -> 126 us, x 50: 205 -> 155 us, x 63: 258 -> 182 us; x 64 ties; one
 //                 row per wavefront, x 65 .. 96, loses: 230-270 against 314-325 us) (4194304 rows of
@@ -35,7 +36,7 @@ inline bool skinny_takes(SkinnyOp op, int64_t rows, int64_t cols, const T* A, in
         if (op == SKINNY_GEMV_N) return (nv <= 8 && rows >= 100000) || ((nv <= 31 || (nv == 32 && cols % 2 == 1)) && rows >= 1000000);
         return (nv <= 4 && rows >= 100000) || (nv <= 20 && rows >= 500000);
     }
-    if (op == SKINNY_GER) return (nv <= 12 || (nv <= 16 && cols % fv == 0)) && rows >= 100000;
+    if (op == SKINNY_GER) return (nv <= 12 || (nv <= 20 && cols % fv == 0)) && rows >= 100000;
     if (op == SKINNY_GEMV_N)      // 256: the row-dot kernel is 1 % ahead
         return (nv <= 32 || (nv >= 37 && nv <= 47 && cols % 32 != 0) || (nv >= 48 && nv <= 64 && cols != 256)) && rows >= 100000;
     return nv <= 17 && rows >= 500000;

@@ -696,7 +696,7 @@ def test_gemv_skinny_double(blas, ctx):
 @pytest.mark.parametrize("dt", DT)
 def test_ger_skinny(blas, ctx, dt):
     for (m, n) in [(100000, 40), (131072, 16), (100001, 24), (150000, 4), (100000, 8)] + (
-            [(120000, 48), (100000, 56), (100000, 64), (100000, 60), (100000, 68)] if dt == np.float32 else []):
+            [(120000, 48), (100000, 56), (100000, 64), (100000, 60), (100000, 68), (100001, 72), (100000, 80), (100000, 84)] if dt == np.float32 else []):
         for pad in (0, 4):
             ger_case(blas, ctx, dt, O.ROW_MAJOR, m, n, 0.3, pad, 1, 1)
     ger_case(blas, ctx, dt, O.ROW_MAJOR, 100000, 40, -1.5, 4, 2, -3)
