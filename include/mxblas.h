@@ -63,6 +63,7 @@ typedef enum {
 #define MXB_ERR_WORKSPACE 2       /* workspace missing or smaller than this call needs */
 #define MXB_ERR_NOT_IMPLEMENTED 3
 #define MXB_ERR_TIMEOUT 4         /* a kernel gave up a bounded wait (mxb_last_status) */
+#define MXB_ERR_STATIC_LIMIT 5    /* mxb_sgemv_static: the call needs more scratch memory than the library's static array holds */
 #define MXB_ERR_HIP_BASE 1000     /* + hipError_t of a failed launch */
 
 /* ---- handle ------------------------------------------------------------------------------ */
@@ -180,6 +181,31 @@ int mxb_sgemv(mxb_handle_t h, mxb_layout_t layout, mxb_trans_t trans, int64_t m,
               const float* A, int64_t lda, const float* x, int64_t incx, float beta, float* y, int64_t incy);
 int mxb_dgemv(mxb_handle_t h, mxb_layout_t layout, mxb_trans_t trans, int64_t m, int64_t n, double alpha,
               const double* A, int64_t lda, const double* x, int64_t incx, double beta, double* y, int64_t incy);
+
+/* mxb_sgemv for callers that cannot allocate device memory: code that runs under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and
+ * bitwise the same result as mxb_sgemv, but the partial vectors that mxb_sgemv keeps in the
+ * handle's workspace live in a static device array of MXB_STATIC_SCRATCH_BYTES inside the library
+ * (every GPU the library runs on holds one copy until the process ends), so no workspace has to
+ * be set.  The handle's workspace, if any, is neither used nor changed.  Neither this call nor
+ * anything it calls allocates or frees memory; the first call on a device looks the array's
+ * address up once.
+ * Limit: a call whose partial vectors need more than MXB_STATIC_SCRATCH_BYTES returns
+ * MXB_ERR_STATIC_LIMIT and launches nothing.  Products that are not transposed (row-major) need at
+ * most 64 KiB.  A transposed product of a row-major matrix needs one partial vector per row group,
+ * about 3 MiB in all with the default options whatever the shape (16384 x 16384: 48 vectors of
+ * 16384 floats), and more only for rows of several hundred thousand columns, where even two row
+ * groups exceed the array (512 x 782336: 6 MiB, rejected), or with raised launch-geometry options.
+ * mxb_workspace_bytes(MXB_GEMV, 4, m, n) <= MXB_STATIC_SCRATCH_BYTES is sufficient for any
+ * orientation.
+ * All calls on one GPU share the one array: two calls that may run at the same time on one GPU
+ * (different streams, different handles, different threads) race on it; calls on one stream are
+ * ordered and safe.  The array keeps the last call's partial vectors; every call overwrites what
+ * it reads, so nothing is cleared.
+ * Errors: as mxb_sgemv, plus MXB_ERR_STATIC_LIMIT. */
+#define MXB_STATIC_SCRATCH_BYTES (4u << 20)
+int mxb_sgemv_static(mxb_handle_t h, mxb_layout_t layout, mxb_trans_t trans, int64_t m, int64_t n, float alpha,
+                     const float* A, int64_t lda, const float* x, int64_t incx, float beta, float* y, int64_t incy);
 
 /* `batch` independent gemv problems of one shape in one call (Sec. 6.2.2 gemv; for matrices so
  * small that a single product cannot fill the device): for b in [0, batch)

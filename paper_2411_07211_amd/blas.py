@@ -37,7 +37,8 @@ NO_TRANS, TRANS = 111, 112
 UPPER, LOWER = 121, 122
 NON_UNIT, UNIT = 131, 132
 AXPY, SCAL, DOT, ASUM, NRM2, GEMV, TRMV, SYMV, GER, GEMV_BATCHED, TRSV = range(1, 12)
-OK, ERR_HANDLE, ERR_WORKSPACE, ERR_NOT_IMPLEMENTED, ERR_TIMEOUT, ERR_HIP_BASE = 0, 1, 2, 3, 4, 1000
+OK, ERR_HANDLE, ERR_WORKSPACE, ERR_NOT_IMPLEMENTED, ERR_TIMEOUT, ERR_STATIC_LIMIT, ERR_HIP_BASE = 0, 1, 2, 3, 4, 5, 1000
+STATIC_SCRATCH_BYTES = 4 << 20
 (OPT_L1_BLOCKS_PER_CU, OPT_REDUCE_BLOCKS, OPT_ROWDOT_XCHUNK, OPT_ROWDOT_BLOCKS_PER_CU,
  OPT_COLACC_TARGET_BLOCKS, OPT_COLACC_MIN_ROWS, OPT_SYMV_TARGET_BLOCKS, OPT_GER_ROWS_PER_BLOCK,
  OPT_SYMV_TILE_VECTORS, OPT_TRI_DIAG_WEIGHT, OPT_SYMV_SMALL_MAX, OPT_TRSV_CHAIN_MIN,
@@ -90,6 +91,7 @@ for _p, _t in (("s", _f), ("d", _d)):
 
 
 _fn["dsdot"] = _sig("mxb_dsdot", _int, _ptr, _i64, _ptr, _i64, _ptr, _i64, _ptr)
+_fn["sgemv_static"] = _sig("mxb_sgemv_static", _int, _ptr, _int, _int, _i64, _i64, _f, _ptr, _i64, _ptr, _i64, _f, _ptr, _i64)
 
 
 def _dp(t):
@@ -294,6 +296,12 @@ def _mk_level2():
 
 
 _mk_level2()
+
+
+def mxb_sgemv_static(h, layout, trans, m, n, alpha, A, lda, x, incx, beta, y, incy):
+    lenx, leny = (n, m) if trans == NO_TRANS else (m, n)
+    return _fn["sgemv_static"](h, layout, trans, m, n, alpha, _m(A, layout, m, n, lda, "A", "s"), lda,
+                               _v(x, lenx, incx, "x", "s"), incx, beta, _v(y, leny, incy, "y", "s"), incy)
 
 
 def routine(prefix: str, name: str):

@@ -20,6 +20,8 @@
 // result.  Transposed trmv is the triangle sweep of trisweep.hip.
 #include "matvec.hpp"
 
+#include <mutex>
+
 #include "options.hpp"
 #include "plan.hpp"
 #include "skinny.hpp"
@@ -886,9 +888,11 @@ int gemv_rows(mxb_handle_t h, bool no_trans, int64_t rows, int64_t cols, T alpha
     return launch_colacc(h, a, batch);
 }
 
+// Argument checks of gemv.  Returns the status to hand back, or kProceed when there is work to launch.
+constexpr int kProceed = 1 << 30;
 template <typename T>
-int gemv(mxb_handle_t h, int layout, int trans, int64_t m, int64_t n, T alpha, const T* A, int64_t lda, const T* x,
-         int64_t incx, T beta, T* y, int64_t incy)
+int gemv_check(mxb_handle_t h, int layout, int trans, int64_t m, int64_t n, T alpha, const T* A, int64_t lda, const T* x,
+               int64_t incx, T beta, T* y, int64_t incy)
 {
     if (!handle_ok(h)) return MXB_ERR_HANDLE;
     if (!layout_ok(layout)) return -1;
@@ -901,17 +905,82 @@ int gemv(mxb_handle_t h, int layout, int trans, int64_t m, int64_t n, T alpha, c
     if (incy == 0) return -12;
     if (m == 0 || n == 0 || (alpha == T(0) && beta == T(1))) return MXB_OK;
     if (!y) return -11;
+    if (alpha != T(0)) {
+        if (!A) return -6;
+        if (!x) return -8;
+    }
+    return kProceed;
+}
+
+template <typename T>
+int gemv(mxb_handle_t h, int layout, int trans, int64_t m, int64_t n, T alpha, const T* A, int64_t lda, const T* x,
+         int64_t incx, T beta, T* y, int64_t incy)
+{
+    const int chk = gemv_check<T>(h, layout, trans, m, n, alpha, A, lda, x, incx, beta, y, incy);
+    if (chk != kProceed) return chk;
     // a column-major m x n matrix is the row-major n x m matrix of the transposed problem
     const bool row_major = layout == MXB_ROW_MAJOR;
     const int64_t rows = row_major ? m : n, cols = row_major ? n : m;
     const bool no_trans = (trans == MXB_NO_TRANS) == row_major;
     const int64_t lenx = no_trans ? cols : rows, leny = no_trans ? rows : cols;
-    if (alpha != T(0)) {
-        if (!A) return -6;
-        if (!x) return -8;
-    }
     return gemv_rows<T>(h, no_trans, rows, cols, alpha, A, lda, 0, x ? vec_base(x, lenx, incx) : x, incx, 0, beta,
                         vec_base(y, leny, incy), incy, 0, 1);
+}
+
+// ---------------------------------------------------------------------------------------------
+// gemv without a caller's workspace
+
+// Scratch memory of mxb_sgemv_static: the partial vectors that the handle's workspace holds for
+// mxb_sgemv.  One copy per GPU, there from the moment the library is loaded until the process
+// ends.  In host code the array's name stands for the symbol, not for device memory: its address
+// on a GPU comes from hipGetSymbolAddress, asked for once per device with that device current.
+static __device__ __align__(256) unsigned char scratch[MXB_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];      // per device; null until the first call on it
+
+// Device address of `scratch` on the current GPU, or null with a status in `st`.
+void* static_scratch(int& st)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) { st = MXB_ERR_HIP_BASE + (int)e; return nullptr; }
+    if (dev < 0 || dev >= kMaxDevices) { st = MXB_ERR_NOT_IMPLEMENTED; return nullptr; }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) { st = MXB_ERR_HIP_BASE + (int)e; return nullptr; }
+        g_scratch_ptr[dev] = p;
+    }
+    st = MXB_OK;
+    return g_scratch_ptr[dev];
+}
+
+int sgemv_static(mxb_handle_t h, int layout, int trans, int64_t m, int64_t n, float alpha, const float* A, int64_t lda,
+                 const float* x, int64_t incx, float beta, float* y, int64_t incy)
+{
+    // the argument checks first: they touch no device state
+    const int chk = gemv_check<float>(h, layout, trans, m, n, alpha, A, lda, x, incx, beta, y, incy);
+    if (chk != kProceed) return chk;
+    int st;
+    void* ptr = static_scratch(st);
+    if (!ptr) return st;
+    // The same launchers as mxb_sgemv, with the static array standing in for the handle's
+    // workspace for the length of this call.  Every kernel that reads partial results reads only
+    // what this call's first pass wrote, so nothing has to be cleared between calls.
+    void* const ws = h->ws;
+    const size_t ws_bytes = h->ws_bytes;
+    const int* const status = h->device_status;
+    h->ws = ptr;
+    h->ws_bytes = MXB_STATIC_SCRATCH_BYTES;
+    st = gemv<float>(h, layout, trans, m, n, alpha, A, lda, x, incx, beta, y, incy);
+    h->ws = ws;
+    h->ws_bytes = ws_bytes;
+    h->device_status = status;
+    // every launcher asks for its partial vectors before it launches anything
+    return st == MXB_ERR_WORKSPACE ? MXB_ERR_STATIC_LIMIT : st;
 }
 
 // `batch` gemv problems of one shape; problem b uses A + b*strideA, x + b*stridex, y + b*stridey.
@@ -992,6 +1061,9 @@ int mxb_sgemv(mxb_handle_t h, mxb_layout_t layout, mxb_trans_t trans, int64_t m,
 int mxb_dgemv(mxb_handle_t h, mxb_layout_t layout, mxb_trans_t trans, int64_t m, int64_t n, double alpha, const double* A,
               int64_t lda, const double* x, int64_t incx, double beta, double* y, int64_t incy)
 { return mxb::gemv<double>(h, layout, trans, m, n, alpha, A, lda, x, incx, beta, y, incy); }
+int mxb_sgemv_static(mxb_handle_t h, mxb_layout_t layout, mxb_trans_t trans, int64_t m, int64_t n, float alpha, const float* A,
+                     int64_t lda, const float* x, int64_t incx, float beta, float* y, int64_t incy)
+{ return mxb::sgemv_static(h, layout, trans, m, n, alpha, A, lda, x, incx, beta, y, incy); }
 int mxb_sgemv_batched(mxb_handle_t h, mxb_layout_t layout, mxb_trans_t trans, int64_t m, int64_t n, float alpha,
                       const float* A, int64_t lda, int64_t strideA, const float* x, int64_t incx, int64_t stridex,
                       float beta, float* y, int64_t incy, int64_t stridey, int64_t batch)
