@@ -179,6 +179,121 @@ __device__ __forceinline__ A lanes_sum(A v)
     else return row16_sum(v);
 }
 
+// ------------------------------------------------------------------------------------------------
+// NR sums at once (NR = 4, 8, 16 or 32 per lane, each to be added up over the 64 lanes): instead of
+// NR full folds, the values are folded pairwise so that every step halves the number of live
+// values.  gfx950's lane-swap instructions do the two cross-row steps: permlane32_swap exchanges
+// the upper half of one register with the lower half of another, so that a + b afterwards holds
+// value 0's sum over both halves in lanes 0-31 and value 1's in lanes 32-63; permlane16_swap does
+// the same with odd and even rows of 16.  Inside a row, quad permutes pair lanes l and l^1, l^2
+// the same way (the lane's bit picks which value it keeps and which it hands over).  What is left
+// of the 64 lanes per value is folded plainly: l^1, l^2 by quad permutes, then the four lanes
+// l, l+4, l+8, l+12 by two row rotations.  NR = 8 costs 18 instructions instead of 64.
+// Fixed order, so results are reproducible.  The lane's value belongs to row rows_fold_lane().
+constexpr int kDppRor4 = 0x124, kDppRor8 = 0x128;   // row_ror: lane l reads lane (l - n) mod 16 of its row
+
+__device__ __forceinline__ void lane_swap32(float& a, float& b)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(unsigned, a), __builtin_bit_cast(unsigned, b), false, false);
+    const unsigned r0 = r[0], r1 = r[1];     // (a bit cast straight from r[1] reads r[0] with this compiler)
+    a = __builtin_bit_cast(float, r0);
+    b = __builtin_bit_cast(float, r1);
+}
+__device__ __forceinline__ void lane_swap16(float& a, float& b)
+{
+    const auto r = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(unsigned, a), __builtin_bit_cast(unsigned, b), false, false);
+    const unsigned r0 = r[0], r1 = r[1];     // (a bit cast straight from r[1] reads r[0] with this compiler)
+    a = __builtin_bit_cast(float, r0);
+    b = __builtin_bit_cast(float, r1);
+}
+__device__ __forceinline__ void lane_swap32(double& a, double& b)
+{
+    const uint64_t x = __builtin_bit_cast(uint64_t, a), y = __builtin_bit_cast(uint64_t, b);
+    const auto lo = __builtin_amdgcn_permlane32_swap((unsigned)x, (unsigned)y, false, false);
+    const auto hi = __builtin_amdgcn_permlane32_swap((unsigned)(x >> 32), (unsigned)(y >> 32), false, false);
+    a = __builtin_bit_cast(double, ((uint64_t)hi[0] << 32) | lo[0]);
+    b = __builtin_bit_cast(double, ((uint64_t)hi[1] << 32) | lo[1]);
+}
+__device__ __forceinline__ void lane_swap16(double& a, double& b)
+{
+    const uint64_t x = __builtin_bit_cast(uint64_t, a), y = __builtin_bit_cast(uint64_t, b);
+    const auto lo = __builtin_amdgcn_permlane16_swap((unsigned)x, (unsigned)y, false, false);
+    const auto hi = __builtin_amdgcn_permlane16_swap((unsigned)(x >> 32), (unsigned)(y >> 32), false, false);
+    a = __builtin_bit_cast(double, ((uint64_t)hi[0] << 32) | lo[0]);
+    b = __builtin_bit_cast(double, ((uint64_t)hi[1] << 32) | lo[1]);
+}
+
+// Row whose sum rows_fold<NR> leaves in this lane; true for the one lane per row that should write it.
+template <int NR>
+__device__ __forceinline__ bool rows_fold_lane(int lane, int& row)
+{
+    static_assert(NR == 4 || NR == 8 || NR == 16 || NR == 32, "rows per batch");
+    row = ((lane >> 5) & 1) | (((lane >> 4) & 1) << 1);
+    int used = 0x30;
+    if (NR >= 8) { row |= (lane & 1) << 2; used |= 1; }
+    if (NR >= 16) { row |= ((lane >> 1) & 1) << 3; used |= 2; }
+    if (NR >= 32) { row |= ((lane >> 3) & 1) << 4; used |= 8; }
+    return (lane & ~used & 63) == 0;
+}
+
+template <int NR, typename A>
+__device__ __forceinline__ A rows_fold(const A (&v)[NR], int lane)
+{
+    static_assert(NR == 4 || NR == 8 || NR == 16 || NR == 32, "rows per batch");
+    A w[NR / 2];
+#pragma unroll
+    for (int i = 0; i < NR / 2; ++i) {        // lanes 0-31: row 2i, lanes 32-63: row 2i + 1
+        A a = v[2 * i], b = v[2 * i + 1];
+        lane_swap32(a, b);
+        w[i] = a + b;
+    }
+    A z[NR / 4];
+#pragma unroll
+    for (int i = 0; i < NR / 4; ++i) {        // even rows of 16 lanes: w[2i], odd rows: w[2i + 1]
+        A a = w[2 * i], b = w[2 * i + 1];
+        lane_swap16(a, b);
+        z[i] = a + b;
+    }
+    if constexpr (NR == 4) {
+        A s = z[0];
+        s += dpp_mov<kDppXor1>(s);
+        s += dpp_mov<kDppXor2>(s);
+        s += dpp_mov<kDppRor8>(s);
+        s += dpp_mov<kDppRor4>(s);
+        return s;
+    } else {
+        const bool b0 = lane & 1;
+        A y[NR / 8];
+#pragma unroll
+        for (int i = 0; i < NR / 8; ++i) {    // even lanes: z[2i], odd lanes: z[2i + 1]
+            const A keep = b0 ? z[2 * i + 1] : z[2 * i], give = b0 ? z[2 * i] : z[2 * i + 1];
+            y[i] = keep + dpp_mov<kDppXor1>(give);
+        }
+        if constexpr (NR == 8) {
+            A s = y[0];
+            s += dpp_mov<kDppXor2>(s);
+            s += dpp_mov<kDppRor8>(s);
+            s += dpp_mov<kDppRor4>(s);
+            return s;
+        } else {
+            const bool b1 = lane & 2;
+            A t[NR / 16];
+#pragma unroll
+            for (int i = 0; i < NR / 16; ++i) {   // lanes with bit 1 clear: y[2i], set: y[2i + 1]
+                const A keep = b1 ? y[2 * i + 1] : y[2 * i], give = b1 ? y[2 * i] : y[2 * i + 1];
+                t[i] = keep + dpp_mov<kDppXor2>(give);
+            }
+#pragma unroll
+            for (int i = 0; i < NR / 16; ++i) {   // lanes l, l+4, l+8, l+12 of a row of 16
+                t[i] += dpp_mov<kDppRor8>(t[i]);
+                t[i] += dpp_mov<kDppRor4>(t[i]);
+            }
+            if constexpr (NR == 16) return t[0];
+            else return (lane & 8) ? t[1] : t[0];
+        }
+    }
+}
+
 // Sum over a thread block of NW wavefronts in fixed wave order; every thread gets the result.
 // `slots` is LDS room for NW values and may be reused after the call returns.
 template <int NW, typename A>

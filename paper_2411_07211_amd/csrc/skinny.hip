@@ -6,7 +6,9 @@
 // G*nv idle), and every lane needs just ONE vector of the short operand, which it keeps in
 // registers for its whole life.  U such slots are in flight per lane.
 //   A*x:      per slot a 4-term dot, then a sum over the nv lanes of each row (ds_bpermute
-//             shuffles; the groups are not powers of two, so DPP rows do not fit);
+//             shuffles; the groups are not powers of two, so DPP rows do not fit); a row of more
+//             than 32 vectors has the wavefront to itself, and the 8 sums of a tile are folded
+//             over all 64 lanes at once (rows_fold);
 //   A^t*x:    per lane one running sum per owned column; at the end the G lanes that own the same
 //             columns and then the wavefronts of the block are folded through LDS, and a second
 //             kernel adds the per-block partial vectors in a fixed order;
@@ -69,6 +71,55 @@ __device__ __forceinline__ LaneMap lane_map(int nv, int N, int vec)
 
 // Rows are dealt in tiles of kSlots*G adjacent rows per wavefront, tiles cyclically to all
 // wavefronts of the grid: slot u of a tile holds rows tile*kSlots*G + u*G + g.
+// Rows that take more than half a wavefront (33 to 64 vectors): one row per wavefront load, SLOTS
+// rows in flight, the lanes past the row idle.  The SLOTS sums of a tile are folded over the
+// wavefront all at once and leave one row's sum in each of SLOTS lanes, which load the old y of
+// their row with the tile and store the new one: SLOTS adjacent elements of y per tile.
+template <typename T, int VEC, bool BETA, int SLOTS>
+__global__ void __launch_bounds__(kThreads) skinny_gemv_n_onerow_kernel(const SkinnyArgs<T> p, const T* __restrict__ A,
+                                                                        const T* __restrict__ x, T* __restrict__ y)
+{
+    typedef typename VecOf<T, VEC>::type V;
+    const LaneMap m = lane_map(p.nv, p.N, VEC);
+    T xr[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) xr[e] = (m.active && e >= m.kmin) ? x[(int64_t)(m.c + e) * p.incs] : T(0);
+    int mine;
+    const bool writer = rows_fold_lane<SLOTS>(m.lane, mine);
+    const int64_t ntiles = (p.M + SLOTS - 1) / SLOTS;
+    const int64_t wave0 = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6), nwaves = (int64_t)gridDim.x * kWaves;
+    for (int64_t t = wave0; t < ntiles; t += nwaves) {
+        const int64_t tile0 = t * SLOTS;
+        V a[SLOTS];
+        if (tile0 + SLOTS <= p.M) {      // whole tile: no predicate, so that all loads issue back to back
+#pragma unroll
+            for (int u = 0; u < SLOTS; ++u) a[u] = ld_matrix<T, VEC>(A + (tile0 + u) * p.lda + m.c);
+        } else {
+#pragma unroll
+            for (int u = 0; u < SLOTS; ++u) {
+                a[u] = V(T(0));
+                if (tile0 + u < p.M) a[u] = ld_matrix<T, VEC>(A + (tile0 + u) * p.lda + m.c);
+            }
+        }
+        const int64_t i = tile0 + mine;
+        T yo = T(0);
+        if (BETA && writer && i < p.M) yo = y[i * p.incl];
+        __builtin_amdgcn_sched_barrier(0);   // every load of the tile is in flight before the first FMA
+        T s[SLOTS];
+#pragma unroll
+        for (int u = 0; u < SLOTS; ++u) {
+            s[u] = T(0);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) s[u] = fmad(a[u][e], xr[e], s[u]);     // xr is zero where the element does not count
+        }
+        T v = p.alpha * rows_fold<SLOTS>(s, m.lane);
+        if (writer && i < p.M) {
+            if (BETA) v = fmad(p.beta, yo, v);
+            y[i * p.incl] = v;
+        }
+    }
+}
+
 template <typename T, int VEC, bool BETA>
 __global__ void __launch_bounds__(kThreads) skinny_gemv_n_kernel(const SkinnyArgs<T> p, const T* __restrict__ A,
                                                                  const T* __restrict__ x, T* __restrict__ y)
@@ -315,6 +366,16 @@ int skinny_gemv_n(mxb_handle_t h, int64_t rows, int64_t cols, T alpha, const T* 
                   T* y0, int64_t incy)
 {
     const SkinnyArgs<T> a = make_args<T>(rows, cols, Full<T>::vec, lda, incx, incy, alpha, beta);
+    if (a.nv > kWave / 2) {
+        // one tile of 8 rows per wavefront, or two: many short-lived blocks read this flat stream
+        // fastest (1048576 x 256: 2 to 16 blocks per compute unit 166-170 us, 64 and more 160-164)
+        constexpr int SLOTS = 8;
+        const int64_t blocks = ceil_div(ceil_div(rows, (int64_t)SLOTS), (int64_t)kWaves), cap = (int64_t)kCUs * 64;
+        const dim3 g1((unsigned)(blocks < cap ? blocks : cap));
+        if (beta != T(0)) hipLaunchKernelGGL((skinny_gemv_n_onerow_kernel<T, Full<T>::vec, true, SLOTS>), g1, dim3(kThreads), 0, h->stream, a, A, x0, y0);
+        else hipLaunchKernelGGL((skinny_gemv_n_onerow_kernel<T, Full<T>::vec, false, SLOTS>), g1, dim3(kThreads), 0, h->stream, a, A, x0, y0);
+        return launch_status();
+    }
     const dim3 grid((unsigned)tile_blocks(rows, a.nv, (int64_t)kCUs * 16));
     if (beta != T(0)) hipLaunchKernelGGL((skinny_gemv_n_kernel<T, Full<T>::vec, true>), grid, dim3(kThreads), 0, h->stream, a, A, x0, y0);
     else hipLaunchKernelGGL((skinny_gemv_n_kernel<T, Full<T>::vec, false>), grid, dim3(kThreads), 0, h->stream, a, A, x0, y0);

@@ -11,7 +11,8 @@ enum SkinnyOp { SKINNY_GEMV_N, SKINNY_GEMV_T, SKINNY_GER };
 // pitch?  The limits are where the skinny kernels measured faster than the general ones (nv =
 // 16-byte vectors per row, the last one moved back when the width is ragged):
 //   fp32  A*x     nv <= 32 (128 columns), and 48 <= nv <= 64 where a row fills most of a wavefront
-//                 (2097152 x 127: 49 -> 80 % of peak, x 100: 55 -> 78 %, x 255: 59 -> 80 %); 37 <= nv <= 47
+//                 (2097152 x 127: 49 -> 80 % of peak, x 100: 55 -> 78 %, x 255: 59 -> 80 %; 1048576 x 256:
+//                 161-166 us against the row-dot kernel's 167-172 on the same machine); 37 <= nv <= 47
 //                 unless the width is a multiple of 32 (x 170: 305 -> 248 us, x 188: 308 -> 254 us, but
 //                 x 160: 217 against 240 us; below, x 129 .. 140: 215-243 against 250-278 us);
 //         A^t*x   nv <= 17 (68 columns), from 500000 rows (it pays for a second kernel);
@@ -37,8 +38,8 @@ inline bool skinny_takes(SkinnyOp op, int64_t rows, int64_t cols, const T* A, in
         return (nv <= 4 && rows >= 100000) || (nv <= 20 && rows >= 500000);
     }
     if (op == SKINNY_GER) return (nv <= 12 || (nv <= 20 && cols % fv == 0)) && rows >= 100000;
-    if (op == SKINNY_GEMV_N)      // 256: the row-dot kernel is 1 % ahead
-        return (nv <= 32 || (nv >= 37 && nv <= 47 && cols % 32 != 0) || (nv >= 48 && nv <= 64 && cols != 256)) && rows >= 100000;
+    if (op == SKINNY_GEMV_N)
+        return (nv <= 32 || (nv >= 37 && nv <= 47 && cols % 32 != 0) || (nv >= 48 && nv <= 64)) && rows >= 100000;
     return nv <= 17 && rows >= 500000;
 }
 

@@ -47,12 +47,11 @@ namespace {
 enum { TRI_PLAIN = 0, TRI_MASKED = 1, TRI_EDGE = 2 };
 
 template <typename T, int VEC, int CV, int U, bool UPPER, int KIND, bool UNIT, int MODE>
-__device__ __forceinline__ void tri_batch(const TriArgs& p, const T* __restrict__ A, const T* __restrict__ x, int rb, int r1, int c,
+__device__ __forceinline__ void tri_batch(const TriArgs& p, const T* __restrict__ A, const T* __restrict__ x, int rb, int r1, const int (&cfull)[CV],
                                           const int (&col)[CV], const int (&kmin)[CV], const bool (&col_ok)[CV], const T (&xj)[CV][VEC], T (&cacc)[CV][VEC],
                                           T* __restrict__ rowpart_wave, int lane)
 {
     typedef typename VecOf<T, VEC>::type V;
-    constexpr int SPAN = kTriThreads * VEC;
     constexpr int WSPAN = kWave * VEC;          // columns one wavefront covers with one vector
     constexpr bool ROWS = KIND == TRI_SYMV;
     V a[U][CV];
@@ -61,7 +60,7 @@ __device__ __forceinline__ void tri_batch(const TriArgs& p, const T* __restrict_
     bool dead[CV], plain[CV];
 #pragma unroll
     for (int v = 0; v < CV; ++v) {
-        const int cw = __builtin_amdgcn_readfirstlane(c - lane * VEC) + v * SPAN;   // first column of the wavefront's vector v
+        const int cw = __builtin_amdgcn_readfirstlane(cfull[v] - lane * VEC);       // first column of the wavefront's vector v
         dead[v] = (MASKED && (UPPER ? cw + WSPAN - 1 < rb : cw > rb + U - 1)) || (EDGE && cw >= p.n);
         plain[v] = MODE == TRI_PLAIN || (EDGE && cw + WSPAN <= p.n) ||
                    (MASKED && (UPPER ? cw > rb + U - 1 : cw + WSPAN - 1 < rb) && rb + U <= r1 && cw + WSPAN <= p.n);
@@ -86,7 +85,7 @@ __device__ __forceinline__ void tri_batch(const TriArgs& p, const T* __restrict_
                 cc = min(cc, p.n - VEC);                     // lanes past the last column
                 a[u][v] = ld_matrix<T, VEC>(arow + cc);
             } else {
-                a[u][v] = ld_matrix<T, VEC>(arow + (c + v * SPAN));
+                a[u][v] = ld_matrix<T, VEC>(arow + cfull[v]);
             }
         }
         xi[u] = x[(int64_t)i * p.incx];
@@ -135,15 +134,12 @@ __device__ __forceinline__ void tri_batch(const TriArgs& p, const T* __restrict_
         }
     }
     if (ROWS) {
-        // fold each row over the wavefront; lane u then stores row u's partial
-        T out = T(0);
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const T sum = wave_sum(rs[u]);
-            out = lane == u ? sum : out;
-        }
-        const int i = rb + lane;
-        if (lane < U && i < r1) rowpart_wave[i] = out;
+        // fold all rows of the batch over the wavefront at once; a lane ends up with one row's sum
+        int mine;
+        const bool writer = rows_fold_lane<U>(lane, mine);
+        const T out = rows_fold<U>(rs, lane);
+        const int i = rb + mine;
+        if (writer && i < r1) rowpart_wave[i] = out;
     }
 }
 
@@ -169,7 +165,9 @@ __global__ void __launch_bounds__(kTriThreads) trisweep_kernel(const TriArgs p, 
     const int s = g - p.first_block[t], S = p.first_block[t + 1] - p.first_block[t];
     const int cb0 = t * TC, cb1 = min(n, cb0 + TC);
     const bool full_tile = cb0 + TC <= n;
-    const int c = cb0 + (int)threadIdx.x * VEC;
+    int cfull[CV];       // first column of the lane's vector v, before a ragged end moves it back
+#pragma unroll
+    for (int v = 0; v < CV; ++v) cfull[v] = cb0 + ((v * kTriWaves + wave) * kWave + lane) * VEC;
 
     // col[v]: first column of the lane's vector v.  A vector that would run past column n is moved
     // back so that it ends at n (n >= VEC here; element alignment is all a matrix load needs); its
@@ -179,7 +177,7 @@ __global__ void __launch_bounds__(kTriThreads) trisweep_kernel(const TriArgs p, 
     T xj[CV][VEC], cacc[CV][VEC];
 #pragma unroll
     for (int v = 0; v < CV; ++v) {
-        const int cv = c + v * SPAN;
+        const int cv = cfull[v];
         col_ok[v] = cv < n;
         kmin[v] = (VEC > 1 && col_ok[v] && cv + VEC > n) ? cv + VEC - n : 0;
         col[v] = cv - kmin[v];
@@ -197,17 +195,17 @@ __global__ void __launch_bounds__(kTriThreads) trisweep_kernel(const TriArgs p, 
     const int f0 = UPPER ? 0 : cb1, f1 = UPPER ? cb0 : n;
     auto diagonal_rows = [&]() {
         for (int64_t rb = cb0 + (int64_t)s * UD; rb < cb1; rb += (int64_t)S * UD)
-            tri_batch<T, VEC, CV, UD, UPPER, KIND, UNIT, TRI_MASKED>(p, A, x, (int)rb, cb1, c, col, kmin, col_ok, xj, cacc, rowpart_wave, lane);
+            tri_batch<T, VEC, CV, UD, UPPER, KIND, UNIT, TRI_MASKED>(p, A, x, (int)rb, cb1, cfull, col, kmin, col_ok, xj, cacc, rowpart_wave, lane);
     };
     auto inside_rows = [&]() {
         for (int64_t rb64 = f0 + (int64_t)s * U; rb64 < f1; rb64 += (int64_t)S * U) {
             const int rb = (int)rb64;
             if (rb + U > f1)
-                tri_batch<T, VEC, CV, U, UPPER, KIND, UNIT, TRI_MASKED>(p, A, x, rb, f1, c, col, kmin, col_ok, xj, cacc, rowpart_wave, lane);
+                tri_batch<T, VEC, CV, U, UPPER, KIND, UNIT, TRI_MASKED>(p, A, x, rb, f1, cfull, col, kmin, col_ok, xj, cacc, rowpart_wave, lane);
             else if (full_tile)
-                tri_batch<T, VEC, CV, U, UPPER, KIND, UNIT, TRI_PLAIN>(p, A, x, rb, f1, c, col, kmin, col_ok, xj, cacc, rowpart_wave, lane);
+                tri_batch<T, VEC, CV, U, UPPER, KIND, UNIT, TRI_PLAIN>(p, A, x, rb, f1, cfull, col, kmin, col_ok, xj, cacc, rowpart_wave, lane);
             else
-                tri_batch<T, VEC, CV, U, UPPER, KIND, UNIT, TRI_EDGE>(p, A, x, rb, f1, c, col, kmin, col_ok, xj, cacc, rowpart_wave, lane);
+                tri_batch<T, VEC, CV, U, UPPER, KIND, UNIT, TRI_EDGE>(p, A, x, rb, f1, cfull, col, kmin, col_ok, xj, cacc, rowpart_wave, lane);
         }
     };
     if (UPPER) { inside_rows(); diagonal_rows(); }
