@@ -98,7 +98,8 @@ typedef enum {
     MXB_OPT_TRSV_CHAIN_MIN = 11,    /* trsv: smallest n solved by the single chained kernel instead of one launch per block */
     MXB_OPT_TRSV_SPIN_LIMIT = 12,   /* chained trsv: polls of one hand-over word before a wavefront gives up (default 2^24: tens of seconds) */
     MXB_OPT_GEMVT_SMALL_MAX = 13,   /* transposed gemv: largest matrix in bytes that takes the single-kernel path (no workspace) */
-    MXB_OPT_COUNT = 14
+    MXB_OPT_GEMVN_SMALL_MAX = 14,   /* gemv, not transposed: largest matrix in bytes that takes the kernel for cache-resident matrices */
+    MXB_OPT_COUNT = 15
 } mxb_option_t;
 int mxb_set_option(mxb_handle_t h, int option, int64_t value);
 int64_t mxb_get_option(mxb_handle_t h, int option);

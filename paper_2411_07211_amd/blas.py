@@ -42,7 +42,7 @@ STATIC_SCRATCH_BYTES = 4 << 20
 (OPT_L1_BLOCKS_PER_CU, OPT_REDUCE_BLOCKS, OPT_ROWDOT_XCHUNK, OPT_ROWDOT_BLOCKS_PER_CU,
  OPT_COLACC_TARGET_BLOCKS, OPT_COLACC_MIN_ROWS, OPT_SYMV_TARGET_BLOCKS, OPT_GER_ROWS_PER_BLOCK,
  OPT_SYMV_TILE_VECTORS, OPT_TRI_DIAG_WEIGHT, OPT_SYMV_SMALL_MAX, OPT_TRSV_CHAIN_MIN,
- OPT_TRSV_SPIN_LIMIT, OPT_GEMVT_SMALL_MAX) = range(14)
+ OPT_TRSV_SPIN_LIMIT, OPT_GEMVT_SMALL_MAX, OPT_GEMVN_SMALL_MAX) = range(15)
 
 _i64, _int, _ptr, _sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
 _f, _d = ctypes.c_float, ctypes.c_double

@@ -1,4 +1,5 @@
 // Handle management, workspace sizing and the two bandwidth probes.
+#include <mutex>
 #include <new>
 
 #include "common.hpp"
@@ -57,7 +58,51 @@ __global__ void __launch_bounds__(kThreads) probe_read_kernel(int64_t nvec, int6
     if (threadIdx.x == 0) out[blockIdx.x] = tot;
 }
 
+// Arrival counters of the kernels that combine their own partial results (see common.hpp).
+static __device__ unsigned arrive_words[kArriveSlots * kArriveCounters];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_arrive_mutex;
+bool g_slot_taken[kArriveSlots];
+unsigned* g_arrive_base[kMaxDevices];      // device address of arrive_words, per device; null until first asked
+
+int take_arrive_slot()
+{
+    std::lock_guard<std::mutex> lock(g_arrive_mutex);
+    for (int s = 0; s < kArriveSlots; ++s)
+        if (!g_slot_taken[s]) { g_slot_taken[s] = true; return s; }
+    return -1;
+}
+
+void release_arrive_slot(int s)
+{
+    if (s < 0) return;
+    std::lock_guard<std::mutex> lock(g_arrive_mutex);
+    g_slot_taken[s] = false;
+}
+
 }  // namespace
+
+unsigned* arrive_counters(mxb_handle_t h)
+{
+    if (h->arrive_slot < 0) return nullptr;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(g_arrive_mutex);
+    if (!g_arrive_base[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(arrive_words)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        g_arrive_base[dev] = static_cast<unsigned*>(p);
+    }
+    return g_arrive_base[dev] + (size_t)h->arrive_slot * kArriveCounters;
+}
+
 }  // namespace mxb
 
 extern "C" {
@@ -73,6 +118,7 @@ int mxb_create(mxb_handle_t* h)
     c->ws_bytes = 0;
     for (int o = 0; o < MXB_OPT_COUNT; ++o) c->opt[o] = 0;
     c->device_status = nullptr;
+    c->arrive_slot = mxb::take_arrive_slot();      // host-side bookkeeping only
     *h = c;
     return MXB_OK;
 }
@@ -81,6 +127,7 @@ int mxb_destroy(mxb_handle_t h)
 {
     if (!mxb::handle_ok(h)) return MXB_ERR_HANDLE;
     h->magic = 0;
+    mxb::release_arrive_slot(h->arrive_slot);
     delete h;
     return MXB_OK;
 }
@@ -158,7 +205,8 @@ size_t mxb_workspace_bytes(int routine, int elem_size, int64_t m, int64_t n)
             b = align_up((size_t)(kWideFillRows + 2 * kWideMaxRows) * (size_t)elem_size, 256);
             a = a > b ? a : b;
             b = align_up((size_t)(kFewBlocks * kFewMaxRows) * (size_t)elem_size, 256);     // a handful of rows
-            return a > b ? a : b;
+            a = a > b ? a : b;
+            return a;
         }
         case MXB_GEMV_BATCHED: {
             // the blocks a plan aims at are shared among the problems: over all problems there are at most

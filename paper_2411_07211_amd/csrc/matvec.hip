@@ -191,8 +191,104 @@ __global__ void __launch_bounds__(kRowdotThreads, 4) rowdot_kernel(const RowdotA
         }
         const int64_t i = grow0 + l;
         if (l < R && i < p.M) {
-            T* yp = y + i * p.incy;
-            T v = p.alpha * out;
+            if (MODE != MODE_GENERAL && p.arrive) {
+                st_agent(p.held + i, p.alpha * out);          // in place: held back until every block has read x
+            } else {
+                T* yp = y + i * p.incy;
+                T v = p.alpha * out;
+                if (p.beta != T(0)) v = fmad(p.beta, *yp, v);
+                *yp = v;
+            }
+        }
+    }
+    if (MODE != MODE_GENERAL && p.arrive) {
+        __shared__ bool last_flag;
+        if (!arrive_is_last(p.arrive, gridDim.x, &last_flag)) return;
+        // (batches of 8 loads per thread: one at a time, each would cost a round trip to memory)
+        for (int64_t i0 = threadIdx.x; i0 < p.M; i0 += 8 * kRowdotThreads) {
+            T t[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) t[e] = ld_agent(p.held + imin(i0 + e * kRowdotThreads, p.M - 1));
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (i0 + e * kRowdotThreads < p.M) p.y[(i0 + e * kRowdotThreads) * p.incy] = t[e];
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// row-dot for a matrix that comes from the caches
+
+// A product this small is bound by launches and latency, not by bytes: the persistent row-dot
+// grid gives a 1024 x 1024 matrix 128 blocks, each of which first stages x in LDS behind two
+// barriers.  Here a wavefront takes R rows from end to end on its own: x comes straight from
+// the second-level cache (a few KiB that every wavefront reads), up to U loads of 16 bytes per
+// row are in flight per lane, no LDS, no barrier, two wavefronts per block so that a matrix of
+// 1024 rows already makes 512 blocks.
+constexpr int kRowSmallThreads = 128;
+
+// WC == 1: the block's two wavefronts take R rows each.  WC > 1 (few, long rows): the block's WC
+// wavefronts share one row, batch b of its columns goes to wavefront b % WC, LDS folds them in
+// wave order.
+template <typename T, int VEC, int R, int U, int WC>
+__global__ void __launch_bounds__(WC == 1 ? kRowSmallThreads : WC * kWave) rowsmall_kernel(const RowdotArgs<T> p)
+{
+    typedef typename VecOf<T, VEC>::type V;
+    static_assert(WC == 1 || R == 1, "wavefronts that share a row take one row");
+    constexpr int SPANV = kWave * VEC;             // columns a wavefront covers with one load
+    __shared__ T part[WC];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t row0 = WC == 1 ? ((int64_t)blockIdx.x * (kRowSmallThreads / kWave) + wave) * R : (int64_t)blockIdx.x;
+    if (row0 >= p.M) return;
+    const T* arow[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) arow[r] = p.A + imin(row0 + r, p.M - 1) * p.lda;      // clamp: loads stay in bounds
+    T acc[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) acc[r] = T(0);
+    // Batches of U loads per row, all in flight before the first use and none predicated: a vector
+    // that would start past column N, or run past it, is moved back to end at N (N >= VEC), and
+    // the elements that are not its own (a neighbour's, or all of them) meet a zero of x.
+    for (int64_t c0 = (int64_t)lane * VEC + (WC == 1 ? 0 : wave * (SPANV * U)); c0 - lane * VEC < p.N; c0 += (int64_t)SPANV * U * WC) {
+        V a[U][R], xv[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t cu = c0 + u * SPANV, c = imin(cu, p.N - VEC);
+#pragma unroll
+            for (int r = 0; r < R; ++r) a[u][r] = ld_matrix<T, VEC>(arow[r] + c);
+            if (p.incx == 1) {
+                xv[u] = *reinterpret_cast<const V __attribute__((aligned(sizeof(T))))*>(p.x + c);
+            } else {
+#pragma unroll
+                for (int k = 0; k < VEC; ++k) xv[u][k] = p.x[(c + k) * p.incx];
+            }
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) xv[u][k] = (c + k >= cu && cu < p.N) ? xv[u][k] : T(0);
+        }
+        __builtin_amdgcn_sched_barrier(0);   // keep every load of the batch ahead of the first FMA
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int k = 0; k < VEC; ++k) acc[r] = fmad(a[u][r][k], xv[u][k], acc[r]);
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        T s = wave_sum(acc[r]);
+        if (WC > 1) {
+            if (lane == 0) part[wave] = s;
+            __syncthreads();
+            if (wave != 0) return;
+            s = part[0];
+#pragma unroll
+            for (int w = 1; w < WC; ++w) s += part[w];
+        }
+        const int64_t i = row0 + r;
+        if (lane == 0 && i < p.M) {
+            T* yp = p.y + i * p.incy;
+            T v = p.alpha * s;
             if (p.beta != T(0)) v = fmad(p.beta, *yp, v);
             *yp = v;
         }
@@ -721,6 +817,7 @@ void launch_colacc_inst(mxb_handle_t h, const ColaccArgs<T>& a, const ColaccPlan
 }
 
 constexpr int64_t kMaxGridZ = 65535;
+constexpr int64_t kRowSmallOneRow = 2048;      // up to here a wavefront takes one row, beyond two
 
 }  // namespace
 
@@ -878,6 +975,22 @@ int gemv_rows(mxb_handle_t h, bool no_trans, int64_t rows, int64_t cols, T alpha
         }
         hipLaunchKernelGGL(colacc_combine_kernel<T>, dim3((unsigned)ceil_div(rows, (int64_t)kWave), 1u), dim3(kCombineGroups * kWave), 0,
                            h->stream, nparts, rows, rows, partials, alpha, beta, y0, incy, (int64_t)0, (int64_t)0);
+        return launch_status();
+    }
+    if (no_trans && batch == 1 && cols >= kWave * Full<T>::vec / 2 && rows * cols * (int64_t)sizeof(T) <= option(h, MXB_OPT_GEMVN_SMALL_MAX)) {
+        // a matrix that comes from the caches, rows of at least half a wavefront of vectors: one or two
+        // rows per wavefront, no LDS, no barrier
+        constexpr int FV = Full<T>::vec;
+        RowdotArgs<T> a{rows, cols, A, lda, x0, incx, y0, incy, alpha, beta, 0, 0};
+        constexpr int WPB = kRowSmallThreads / kWave;
+        const int64_t loads = ceil_div(cols, (int64_t)kWave * FV);          // loads that cover a row
+        const dim3 g1((unsigned)ceil_div(rows, (int64_t)WPB)), g2((unsigned)ceil_div(rows, (int64_t)WPB * 2)), blk(kRowSmallThreads);
+        if (rows > kRowSmallOneRow) hipLaunchKernelGGL((rowsmall_kernel<T, FV, 2, 4, 1>), g2, blk, 0, h->stream, a);
+        else if (rows <= 256 && loads >= 32) hipLaunchKernelGGL((rowsmall_kernel<T, FV, 1, 4, 8>), dim3((unsigned)rows), dim3(8 * kWave), 0, h->stream, a);
+        else if (rows <= 512 && loads >= 16) hipLaunchKernelGGL((rowsmall_kernel<T, FV, 1, 4, 4>), dim3((unsigned)rows), dim3(4 * kWave), 0, h->stream, a);
+        else if (loads <= 2) hipLaunchKernelGGL((rowsmall_kernel<T, FV, 1, 2, 1>), g1, blk, 0, h->stream, a);
+        else if (loads <= 4) hipLaunchKernelGGL((rowsmall_kernel<T, FV, 1, 4, 1>), g1, blk, 0, h->stream, a);
+        else hipLaunchKernelGGL((rowsmall_kernel<T, FV, 1, 8, 1>), g1, blk, 0, h->stream, a);
         return launch_status();
     }
     if (no_trans) {
@@ -1040,10 +1153,18 @@ int trmv(mxb_handle_t h, int layout, int uplo, int trans, int diag, int64_t n, c
     // transposed: the triangle sweep reads x, its combine pass writes x afterwards: no copy needed
     if (!no_trans) return trisweep_trmv_t<T>(h, upper, unit, n, A, lda, x0, incx);
 
-    // not transposed: rows are written while other blocks still read x, so work from a snapshot
+    // not transposed: rows are finished while other blocks still read x
     const size_t snap_bytes = align_up((size_t)n * sizeof(T), 256);
     T* snap = static_cast<T*>(take_workspace(h, snap_bytes));
     if (!snap) return MXB_ERR_WORKSPACE;
+    if (unsigned* counters = arrive_counters(h)) {
+        // one kernel: the results are held in the workspace and the last block to finish copies them to x
+        RowdotArgs<T> a{n, n, A, lda, x0, incx, x0, incx, T(1), T(0), 0, 0};
+        a.held = snap;
+        a.arrive = counters;
+        return launch_rowdot(h, a, mode, unit);
+    }
+    // no arrival counters for this handle: work from a snapshot of x made by a kernel of its own
     hipLaunchKernelGGL(gather_kernel<T>, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, h->stream, n, x0, incx, snap);
     int st = launch_status();
     if (st != MXB_OK) return st;

@@ -83,6 +83,23 @@ def test_gemv_shapes(blas, ctx, dt, trans):
                 gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, 1.5, 0.5, 3, 1, 1)
     finally:
         ctx.set_option(blas.OPT_GEMVT_SMALL_MAX, 0)
+    # not transposed, a cache-sized matrix has a kernel of its own too (rows of at least half a
+    # wavefront of vectors): the same shapes through the persistent row-dot grid, and shapes around
+    # the new kernel's limits (narrowest rows, one and two rows per wavefront, ragged widths and
+    # row counts, strided and reversed vectors, batches that end in the middle of a vector)
+    try:
+        ctx.set_option(blas.OPT_GEMVN_SMALL_MAX, 1)
+        for (m, n) in GEMV_SHAPES:
+            if m * n <= 1 << 22:
+                gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, 1.5, 0.5, 3, 1, 1)
+    finally:
+        ctx.set_option(blas.OPT_GEMVN_SMALL_MAX, 0)
+    fv = 16 // np.dtype(dt).itemsize
+    for (m, n) in [(3, 32 * fv), (1, 32 * fv + 1), (2047, 64 * fv * 8), (2048, 64 * fv * 8 + 1), (2049, 64 * fv * 8 - 1), (4099, 64 * fv * 4 + 3),
+                   (5, 64 * fv * 8 * 2 + 2 * fv + 1), (700, 1027), (256, 64 * fv * 32), (255, 64 * fv * 33 + 1), (300, 64 * fv * 16 - 1),
+                   (512, 64 * fv * 20 + 5)]:
+        for beta, incx, incy in ((0.0, 1, 1), (0.5, 2, 3), (-1.0, -1, -2)):
+            gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, 1.5, beta, 1, incx, incy)
     for (m, n) in [(1024, 4), (1024, 5), (1025, 64), (1000, 33), (37, 2049), (1, 700), (1023, 3), (300, 4099), (512, 8191)]:
         for beta in (0.0, 0.5):
             gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, 1.5, beta, 1, 2, 3)

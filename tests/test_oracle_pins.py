@@ -686,3 +686,130 @@ def test_trsv_against_independent_fp64_library(dt, tol, uplo, trans, diag):
     opT = Tm if trans == O.NO_TRANS else Tm.T
     r = np.abs(b.astype(np.float64) - opT @ x.astype(np.float64))
     assert (r <= 2 * np.finfo(dt).eps * (np.abs(opT) @ np.abs(x.astype(np.float64)) + np.abs(b))).all()
+
+
+# ----------------------------------------------------------------------------- condition denominators
+# The tolerance gate of the GPU parity tests divides by the oracle's side output D (the sum of the
+# absolute values of the terms of each output).  An inflated D would loosen that gate, so every
+# routine's D is pinned here against an expression of numpy's own, built from explicit dense
+# operands (|M| @ |v| and the like) instead of the oracle's element loops.  Integer-valued inputs
+# make every term exact, so the comparison is for equality up to fp64 summation order; each check
+# is followed by one that shows D reacts when a term is left out (a D that ignored alpha, beta,
+# the diagonal or the second operand would pass neither).
+def small(seed, tid, n, dt, lo=-4, hi=4):
+    return synth.small_ints(seed, tid, n, lo, hi, dt)
+
+
+def rel_eq(a, b, tol=1e-12):
+    a = np.asarray(a, np.float64); b = np.asarray(b, np.float64)
+    return np.all(np.abs(a - b) <= tol * np.maximum(np.abs(b), 1e-300))
+
+
+@pytest.mark.parametrize("dt", DT)
+@pytest.mark.parametrize("incx,incy", [(1, 1), (2, 3), (-1, 2)])
+def test_D_level1(dt, incx, incy):
+    n = 53
+    x, y = small(40, 1, n, dt), small(40, 2, n, dt)
+    alpha = dt(-3)
+    xb, yb = synth.strided(x, incx), synth.strided(y, incy)
+    D = O.axpy(n, alpha, xb, incx, yb.copy(), incy, want_D=True)
+    want = np.abs(np.float64(alpha)) * np.abs(x.astype(np.float64)) + np.abs(y.astype(np.float64))
+    assert rel_eq(D, want) and not rel_eq(D, np.abs(y.astype(np.float64)))
+    D = O.scal(n, alpha, synth.strided(x, abs(incx)), abs(incx), want_D=True)
+    assert rel_eq(D, 3 * np.abs(x.astype(np.float64)))
+    _, D = O.dot(n, xb, incx, yb, incy, want_D=True)
+    assert rel_eq(D, np.abs(x.astype(np.float64)) @ np.abs(y.astype(np.float64)))
+    r, D = O.asum(n, synth.strided(x, abs(incx)), abs(incx), want_D=True)
+    assert rel_eq(D, np.abs(x).sum()) and r == np.abs(x).sum()
+    r, D = O.nrm2(n, synth.strided(x, abs(incx)), abs(incx), want_D=True)
+    assert rel_eq(D, np.sqrt((x.astype(np.float64) ** 2).sum()), 1e-6 if dt == np.float32 else 1e-12)
+    _, D = O.dsdot(n, synth.strided(x.astype(np.float32), incx), incx, synth.strided(y.astype(np.float32), incy), incy, want_D=True)
+    assert rel_eq(D, np.abs(x.astype(np.float64)) @ np.abs(y.astype(np.float64)))
+    c, s = dt(3), dt(-2)
+    D = O.rot(n, synth.strided(x, incx), incx, synth.strided(y, incy), incy, c, s, want_D=True)
+    ax, ay = np.abs(x.astype(np.float64)), np.abs(y.astype(np.float64))
+    assert rel_eq(D[0::2], 3 * ax + 2 * ay) and rel_eq(D[1::2], 3 * ay + 2 * ax)
+    for param, H in (([-1, 2, -3, 4, 5], [[2, 4], [-3, 5]]), ([0, 9, -3, 4, 9], [[1, 4], [-3, 1]]), ([1, 2, 9, 9, 5], [[2, 1], [-1, 5]])):
+        D = O.rotm(n, synth.strided(x, incx), incx, synth.strided(y, incy), incy, np.array(param, dt), want_D=True)
+        H = np.abs(np.array(H, np.float64))
+        assert rel_eq(D[0::2], H[0, 0] * ax + H[0, 1] * ay) and rel_eq(D[1::2], H[1, 0] * ax + H[1, 1] * ay)
+
+
+@pytest.mark.parametrize("dt", DT)
+@pytest.mark.parametrize("layout", [O.ROW_MAJOR, O.COL_MAJOR])
+def test_D_level2_dense_and_structured(dt, layout):
+    n, m = 19, 23
+    f64 = np.float64
+    alpha, beta = dt(-2), dt(3)
+    # gemv / gemv_batched
+    A = small(41, 0, m * n, dt).reshape(m, n)
+    buf = np.ascontiguousarray(A if layout == O.ROW_MAJOR else A.T).ravel()
+    lda = n if layout == O.ROW_MAJOR else m
+    for trans, op in ((O.NO_TRANS, A), (O.TRANS, A.T)):
+        lenx, leny = op.shape[1], op.shape[0]
+        x, y = small(41, 1, lenx, dt), small(41, 2, leny, dt)
+        D = O.gemv(layout, trans, m, n, alpha, buf, lda, x, 1, beta, y.copy(), 1, want_D=True)
+        want = 2 * (np.abs(op.astype(f64)) @ np.abs(x.astype(f64))) + 3 * np.abs(y.astype(f64))
+        assert rel_eq(D, want)
+        assert not rel_eq(D, 2 * (np.abs(op.astype(f64)) @ np.abs(x.astype(f64))))          # beta*y counts
+        D0 = O.gemv(layout, trans, m, n, alpha, buf, lda, x, 1, dt(0), y.copy(), 1, want_D=True)
+        assert rel_eq(D0, 2 * (np.abs(op.astype(f64)) @ np.abs(x.astype(f64))))             # and does not when beta == 0
+        Db = O.gemv_batched(layout, trans, m, n, alpha, np.concatenate([buf, buf]), lda, m * n, np.concatenate([x, x]), 1, lenx, beta,
+                            np.concatenate([y, y]), 1, leny, 2, want_D=True)
+        assert rel_eq(Db, np.concatenate([want, want]))
+    # trmv, trsv, symv: explicit triangle / explicitly symmetrised matrix
+    S = small(42, 0, n * n, dt).reshape(n, n)
+    x, y = small(42, 1, n, dt), small(42, 2, n, dt)
+    for uplo in (O.UPPER, O.LOWER):
+        for diag in (O.NON_UNIT, O.UNIT):
+            Tm = explicit_tri(S.copy(), uplo, diag).astype(f64)
+            tb, tlda, _ = tri_buffer(S, layout, uplo, 2, dt, unit=(diag == O.UNIT))
+            for trans in (O.NO_TRANS, O.TRANS):
+                opT = Tm if trans == O.NO_TRANS else Tm.T
+                D = O.trmv(layout, uplo, trans, diag, n, tb.ravel(), tlda, x.copy(), 1, want_D=True)
+                assert rel_eq(D, np.abs(opT) @ np.abs(x.astype(f64)))
+                if diag == O.UNIT:       # the implied 1 on the diagonal counts as a term
+                    assert not rel_eq(D, np.abs(opT - np.eye(n)) @ np.abs(x.astype(f64)))
+        tri = np.triu(S) if uplo == O.UPPER else np.tril(S)
+        full = (tri + tri.T - np.diag(np.diag(S))).astype(f64)
+        sb, slda, _ = tri_buffer(S, layout, uplo, 1, dt)
+        D = O.symv(layout, uplo, n, alpha, sb.ravel(), slda, x, 1, beta, y.copy(), 1, want_D=True)
+        assert rel_eq(D, 2 * (np.abs(full) @ np.abs(x.astype(f64))) + 3 * np.abs(y.astype(f64)))
+        assert not rel_eq(D, 2 * (np.abs(tri.astype(f64)) @ np.abs(x.astype(f64))) + 3 * np.abs(y.astype(f64)))   # the mirrored half counts
+    # ger, syr, syr2: |A_old| + |alpha x_i y_j| (+ the second product), row-major D[i*n + j] of the logical matrix
+    G = small(43, 0, m * n, dt).reshape(m, n)
+    gx, gy = small(43, 1, m, dt), small(43, 2, n, dt)
+    gbuf = np.ascontiguousarray(G if layout == O.ROW_MAJOR else G.T).ravel()
+    D = O.ger(layout, m, n, alpha, gx, 1, gy, 1, gbuf.copy(), lda, want_D=True)
+    assert rel_eq(D.reshape(m, n), np.abs(G.astype(f64)) + 2 * np.outer(np.abs(gx.astype(f64)), np.abs(gy.astype(f64))))
+    for uplo in (O.UPPER, O.LOWER):
+        inside = np.triu(np.ones((n, n), bool)) if uplo == O.UPPER else np.tril(np.ones((n, n), bool))
+        sb, slda, _ = tri_buffer(S, layout, uplo, 1, dt)
+        ax, ay = np.abs(x.astype(f64)), np.abs(y.astype(f64))
+        D = O.syr(layout, uplo, n, alpha, x, 1, sb.copy().ravel(), slda, want_D=True).reshape(n, n)
+        assert rel_eq(D[inside], (np.abs(S.astype(f64)) + 2 * np.outer(ax, ax))[inside]) and (D[~inside] == 0).all()
+        D = O.syr2(layout, uplo, n, alpha, x, 1, y, 1, sb.copy().ravel(), slda, want_D=True).reshape(n, n)
+        assert rel_eq(D[inside], (np.abs(S.astype(f64)) + 2 * np.outer(ax, ay) + 2 * np.outer(ay, ax))[inside]) and (D[~inside] == 0).all()
+
+
+@pytest.mark.parametrize("dt", DT)
+@pytest.mark.parametrize("uplo", [O.UPPER, O.LOWER])
+@pytest.mark.parametrize("trans", [O.NO_TRANS, O.TRANS])
+@pytest.mark.parametrize("diag", [O.NON_UNIT, O.UNIT])
+def test_D_trsv(dt, uplo, trans, diag):
+    """D[o] = (|b_o| + sum_{k != o} |op(T)[o][k] z_k|) / |op(T)[o][o]| with z the solution: checked
+    with the solution of an independent fp64 solver put into that expression by dense numpy."""
+    import scipy.linalg
+    n = 40
+    A = synth.uniform(44, 0, n * n, dt).reshape(n, n) / dt(8)
+    A[np.arange(n), np.arange(n)] = dt(1) + np.abs(synth.uniform(44, 5, n, dt))
+    b = synth.uniform(44, 1, n, dt)
+    Tm = explicit_tri(A.copy(), uplo, diag).astype(np.float64)
+    opT = Tm if trans == O.NO_TRANS else Tm.T
+    z = scipy.linalg.solve_triangular(opT, b.astype(np.float64), lower=((uplo == O.LOWER) == (trans == O.NO_TRANS)))
+    off = np.abs(opT - np.diag(np.diag(opT)))
+    want = (np.abs(b.astype(np.float64)) + off @ np.abs(z)) / np.abs(np.diag(opT))
+    buf, lda, _ = tri_buffer(A, O.ROW_MAJOR, uplo, 1, dt, unit=(diag == O.UNIT))
+    D = O.trsv(O.ROW_MAJOR, uplo, trans, diag, n, buf.ravel(), lda, b.copy(), 1, want_D=True)
+    assert rel_eq(D, want, 1e-5 if dt == np.float32 else 1e-12)
+    assert not rel_eq(D, np.abs(b.astype(np.float64)) / np.abs(np.diag(opT)), 1e-3)     # the off-diagonal terms count
