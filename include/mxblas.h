@@ -71,6 +71,7 @@ typedef enum {
 /* Creates a host-side handle (stream = default stream, no workspace).  Allocates no device
  * memory and makes no GPU call.  Returns -1 if h is NULL. */
 int mxb_create(mxb_handle_t* h);
+/* The work enqueued through the handle must have completed. */
 int mxb_destroy(mxb_handle_t h);
 /* hip_stream is a hipStream_t (borrowed); NULL selects the default stream. */
 int mxb_set_stream(mxb_handle_t h, void* hip_stream);
@@ -79,6 +80,10 @@ int mxb_set_workspace(mxb_handle_t h, void* dev_ptr, size_t bytes);
 /* Upper bound on the workspace a call of `routine` (mxb_routine_t) with element size 4 or 8 and
  * problem size (m, n) needs; level-1 routines and trmv/symv use n only.  0 for bad arguments. */
 size_t mxb_workspace_bytes(int routine, int elem_size, int64_t m, int64_t n);
+/* The same bound for the launch-geometry options set on handle h (mxb_workspace_bytes assumes the
+ * defaults; an option that asks for more blocks also asks for more partial results).  h == NULL
+ * gives mxb_workspace_bytes.  0 for bad arguments or a bad handle. */
+size_t mxb_workspace_bytes_for(mxb_handle_t h, int routine, int elem_size, int64_t m, int64_t n);
 
 /* Launch-geometry options (per handle).  Results stay within the documented tolerance for any
  * setting and are bitwise reproducible for a fixed setting; mxb_workspace_bytes assumes the

@@ -60,6 +60,7 @@ _destroy = _sig("mxb_destroy", _int, _ptr)
 _set_stream = _sig("mxb_set_stream", _int, _ptr, _ptr)
 _set_workspace = _sig("mxb_set_workspace", _int, _ptr, _ptr, _sz)
 _workspace_bytes = _sig("mxb_workspace_bytes", _sz, _int, _int, _i64, _i64)
+_workspace_bytes_for = _sig("mxb_workspace_bytes_for", _sz, _ptr, _int, _int, _i64, _i64)
 _set_option = _sig("mxb_set_option", _int, _ptr, _int, _i64)
 _get_option = _sig("mxb_get_option", _i64, _ptr, _int)
 _last_status = _sig("mxb_last_status", _int, _ptr)
@@ -125,6 +126,10 @@ def mxb_set_workspace(h, dev_ptr, nbytes):
 
 def mxb_workspace_bytes(routine, elem_size, m, n):
     return _workspace_bytes(routine, elem_size, m, n)
+
+
+def mxb_workspace_bytes_for(h, routine, elem_size, m, n):
+    return _workspace_bytes_for(h, routine, elem_size, m, n)
 
 
 def mxb_set_option(h, option, value):

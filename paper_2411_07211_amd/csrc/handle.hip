@@ -177,14 +177,24 @@ int mxb_last_status(mxb_handle_t h)
 
 size_t mxb_workspace_bytes(int routine, int elem_size, int64_t m, int64_t n)
 {
+    return mxb_workspace_bytes_for(nullptr, routine, elem_size, m, n);
+}
+
+size_t mxb_workspace_bytes_for(mxb_handle_t h, int routine, int elem_size, int64_t m, int64_t n)
+{
     using namespace mxb;
     if ((elem_size != 4 && elem_size != 8) || m < 0 || n < 0) return 0;
+    if (h && !handle_ok(h)) return 0;
+    // the launch-geometry options that size partial results: the handle's, or the defaults
+    auto opt = [&](int o) { return h ? option(h, o) : option_default(o); };
+    auto raw = [&](int o) { return h ? h->opt[o] : (int64_t)0; };
     const int full = 16 / elem_size;
     auto colacc_bound = [&](int64_t rows, int64_t cols) {
         size_t b = 0;
         for (int vec : {1, full}) {
-            const ColaccPlan p = colacc_plan(rows, cols, elem_size, vec, option_default(MXB_OPT_COLACC_TARGET_BLOCKS),
-                                             kColaccNarrowBlocks, option_default(MXB_OPT_COLACC_MIN_ROWS));
+            const ColaccPlan p = colacc_plan(rows, cols, elem_size, vec, opt(MXB_OPT_COLACC_TARGET_BLOCKS),
+                                             raw(MXB_OPT_COLACC_TARGET_BLOCKS) > 0 ? 2 * raw(MXB_OPT_COLACC_TARGET_BLOCKS) : kColaccNarrowBlocks,
+                                             opt(MXB_OPT_COLACC_MIN_ROWS));
             const size_t need = p.nparts > 1 ? (size_t)p.nparts * (size_t)(ceil_div(cols, full) * full) * (size_t)elem_size : 0;
             b = need > b ? need : b;
         }
@@ -193,7 +203,7 @@ size_t mxb_workspace_bytes(int routine, int elem_size, int64_t m, int64_t n)
     switch (routine) {
         case MXB_AXPY: case MXB_SCAL: case MXB_GER: return 0;
         case MXB_DOT: case MXB_ASUM: case MXB_NRM2:
-            return (size_t)option_default(MXB_OPT_REDUCE_BLOCKS) * kStridedBlocksFactor * 3 * sizeof(double);
+            return (size_t)opt(MXB_OPT_REDUCE_BLOCKS) * kStridedBlocksFactor * 3 * sizeof(double);
         case MXB_GEMV: {
             size_t a = colacc_bound(m, n), b = colacc_bound(n, m);
             a = a > b ? a : b;
@@ -211,16 +221,19 @@ size_t mxb_workspace_bytes(int routine, int elem_size, int64_t m, int64_t n)
         case MXB_GEMV_BATCHED: {
             // the blocks a plan aims at are shared among the problems: over all problems there are at most
             // one and a half times as many partial vectors as the largest target
-            int64_t t = 4 * option_default(MXB_OPT_COLACC_TARGET_BLOCKS);
+            int64_t t = 4 * opt(MXB_OPT_COLACC_TARGET_BLOCKS);
+            if (raw(MXB_OPT_COLACC_TARGET_BLOCKS) > 0 && 2 * raw(MXB_OPT_COLACC_TARGET_BLOCKS) > t) t = 2 * raw(MXB_OPT_COLACC_TARGET_BLOCKS);
             if (t < kColaccNarrowBlocks) t = kColaccNarrowBlocks;
             const int64_t len = ceil_div(m > n ? m : n, (int64_t)full) * full;
             return align_up((size_t)(t + t / 2) * (size_t)len * (size_t)elem_size, 256);
         }
         case MXB_TRMV: {
-            const size_t a = align_up((size_t)n * elem_size, 256), b = tri_workspace_bound(n, elem_size);
+            const size_t a = align_up((size_t)n * elem_size, 256),
+                         b = tri_workspace_bound(n, elem_size, raw(MXB_OPT_SYMV_TARGET_BLOCKS), raw(MXB_OPT_SYMV_TILE_VECTORS), opt(MXB_OPT_TRI_DIAG_WEIGHT));
             return a > b ? a : b;
         }
-        case MXB_SYMV: return tri_workspace_bound(n, elem_size);
+        case MXB_SYMV:
+            return tri_workspace_bound(n, elem_size, raw(MXB_OPT_SYMV_TARGET_BLOCKS), raw(MXB_OPT_SYMV_TILE_VECTORS), opt(MXB_OPT_TRI_DIAG_WEIGHT));
         case MXB_TRSV: {
             // blocked: the transposed product's partial vectors; chained: 8 (fp32) or 16 (fp64) bytes per
             // unknown of whole sub-blocks of 64, and two counters

@@ -87,13 +87,13 @@ inline size_t tri_workspace_elems(int64_t n, const TriPlan& p, bool row_sums)
     return rows + (size_t)p.blocks * (size_t)p.tile_cols;
 }
 
-// Upper bound over both vector widths and both triangles with the default options.
-inline size_t tri_workspace_bound(int64_t n, int elem_size)
+// Upper bound over both vector widths and both triangles for the given options (0: default).
+inline size_t tri_workspace_bound(int64_t n, int elem_size, int64_t want_blocks = 0, int64_t force_cv = 0, int64_t diag_weight = 3)
 {
     size_t b = 0;
     for (int vec : {1, 16 / elem_size})
         for (bool upper : {false, true}) {
-            const TriPlan p = tri_plan(n, vec, elem_size, upper, 0, 0, 3);
+            const TriPlan p = tri_plan(n, vec, elem_size, upper, want_blocks, force_cv, diag_weight);
             const size_t need = tri_workspace_elems(n, p, true) * (size_t)elem_size;
             b = need > b ? need : b;
         }

@@ -221,6 +221,23 @@ def test_workspace_bound(B):
     assert B.mxb_workspace_bytes(B.GEMV, 3, 4, 4) == 0 and B.mxb_workspace_bytes(B.GEMV, 4, -1, 4) == 0
 
 
+def test_workspace_bound_follows_the_handles_options(B):
+    st, h = B.mxb_create()
+    try:
+        for r, e, m, n in ((B.DOT, 4, 0, 1 << 20), (B.GEMV, 4, 5000, 3000), (B.SYMV, 8, 0, 5000), (B.GEMV_BATCHED, 4, 100, 100)):
+            assert B.mxb_workspace_bytes_for(h, r, e, m, n) == B.mxb_workspace_bytes(r, e, m, n)
+            assert B.mxb_workspace_bytes_for(None, r, e, m, n) == B.mxb_workspace_bytes(r, e, m, n)
+        base = B.mxb_workspace_bytes(B.DOT, 4, 0, 1 << 20)
+        assert B.mxb_set_option(h, B.OPT_REDUCE_BLOCKS, 1024) == 0
+        assert B.mxb_workspace_bytes_for(h, B.DOT, 4, 0, 1 << 20) == 4 * base
+        g = B.mxb_workspace_bytes(B.GEMV, 4, 100000, 3000)
+        assert B.mxb_set_option(h, B.OPT_COLACC_TARGET_BLOCKS, 1536) == 0
+        assert B.mxb_workspace_bytes_for(h, B.GEMV, 4, 100000, 3000) > g
+        assert B.mxb_workspace_bytes_for(h, B.GEMV, 3, 4, 4) == 0
+    finally:
+        B.mxb_destroy(h)
+
+
 def test_binding_refuses_operands_that_are_too_small_or_of_the_wrong_type(B):
     """The Python binding knows the size of a tensor operand and refuses, on the host, a call that
     would overrun it (nothing is launched; CPU tensors suffice to show it)."""
@@ -257,3 +274,18 @@ def test_binding_refuses_operands_that_are_too_small_or_of_the_wrong_type(B):
         assert B.mxb_sgemv(h, B.ROW_MAJOR, B.NO_TRANS, 8, 8, 1.0, v(7 * 10 + 8), 10, v(8), 0, 0.0, v(8), 1) == -9
     finally:
         B.mxb_destroy(h)
+
+
+def test_build_refuses_chained_trsv_kernels_that_spill_too_many_scalars():
+    """The build reads hipcc's resource-usage remarks for trsv.hip and refuses a library whose chained
+    solve spills more scalar registers than has been seen to work (host logic, checked on made-up reports)."""
+    from paper_2411_07211_amd import build as b
+    line = "trsv.hip:257:1: remark: Function Name: _ZN3mxb12_GLOBAL__N_117trsv_chain_kernelI{}Lb1ELb0ELb1EEEvNS0_9ChainArgsIT_EE [-Rpass-analysis=kernel-resource-usage]\n" \
+           "trsv.hip:257:1: remark:     SGPRs Spill: {} [-Rpass-analysis=kernel-resource-usage]\n"
+    other = "trsv.hip:51:1: remark: Function Name: _ZN3mxb16trsv_diag_kernelIfEE [-Rpass-analysis=kernel-resource-usage]\ntrsv.hip:51:1: remark:     SGPRs Spill: 900 [x]\n"
+    got = b.check_chain_spills(line.format("f", 85) + other + line.format("d", 22))
+    assert sorted(got.values()) == [22, 85]                      # other kernels are not judged
+    with pytest.raises(RuntimeError):
+        b.check_chain_spills(line.format("f", 85) + line.format("d", b.MAX_CHAIN_SGPR_SPILLS + 1))
+    with pytest.raises(RuntimeError):
+        b.check_chain_spills(other)                              # nothing to check: refuse rather than pass

@@ -10,7 +10,7 @@ import pytest
 import torch
 
 import oracle as O
-from parity import bits_equal, to_host
+from parity import bits_equal, check_close, to_host
 
 pytestmark = pytest.mark.gpu
 
@@ -255,6 +255,14 @@ def test_level2_beyond_2_to_32_elements(blas, big_ctx):
             # a row's 63 substitution steps each round a value of size |z_i|: a few units in the last place
             bound = 32 * 2.0 ** -24 * (abs(float(hxn[i])) + abs(float(hz[i])) + abs(float(part)))
             assert abs(float(hz[i]) + float(part) - float(hxn[i])) <= bound, f"strsv trans={trans} row {i}"
+        if trans == B.NO_TRANS:
+            # and every unknown against the oracle's substitution on the same matrix (17 GB brought to the host once)
+            print("strsv n=65536: oracle solve on the host", flush=True)
+            hA = to_host(A)
+            ref = hxn.copy()
+            D = O.trsv(O.ROW_MAJOR, O.LOWER, O.NO_TRANS, O.UNIT, N, hA, lda, ref, 1, want_D=True)
+            del hA
+            check_close(hz, ref, D, N, "strsv lower N unit n=65536")
 
 
 def test_trsv_with_more_workgroups_than_the_device_holds(blas, big_ctx):

@@ -311,3 +311,30 @@ def test_iamax(blas, ctx, dt):
             assert gpu(t.size, t, 1) == O.iamax(t.size, t, 1)
     finally:
         ctx.set_option(blas.OPT_REDUCE_BLOCKS, 0)
+
+
+def test_workspace_sized_for_raised_options(blas):
+    """mxb_workspace_bytes_for gives the bound for the options set on a handle: a workspace of
+    exactly that size serves the calls, the default bound does not once an option asks for more
+    partial results."""
+    import torch
+    n = 1 << 22
+    x = to_dev(synth.small_ints(30, 1, 2 * n, -2, 2, np.float32))
+    r = torch.zeros(1, dtype=torch.float32, device="cuda")
+    st, h = blas.mxb_create()
+    assert st == 0
+    try:
+        assert blas.mxb_set_stream(h, torch.cuda.current_stream().cuda_stream) == 0
+        assert blas.mxb_set_option(h, blas.OPT_REDUCE_BLOCKS, 2048) == 0
+        small, need = blas.mxb_workspace_bytes(blas.ASUM, 4, 0, n), blas.mxb_workspace_bytes_for(h, blas.ASUM, 4, 0, n)
+        assert need > small
+        ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+        assert blas.mxb_set_workspace(h, ws, small) == 0
+        assert blas.mxb_sasum(h, n, x, 2, r) == blas.ERR_WORKSPACE
+        assert blas.mxb_set_workspace(h, ws, need) == 0
+        for inc in (1, 2):
+            assert blas.mxb_sasum(h, n, x, inc, r) == 0
+            want = float(np.abs(to_host(x)[::inc][:n].astype(np.float64)).sum())
+            assert float(r.item()) == want
+    finally:
+        blas.mxb_destroy(h)
