@@ -476,8 +476,10 @@ CALL_KERNELS = {
     "sgemv_n_1024": ["rowsmall_kernel<float, 4, 1, 4, 1>"],
     "dgemv_n_16384": ["rowdot_kernel<double, 2, 64, 2, 4, 0, false>"],
     "dgemv_t_16384": ["colacc_kernel<double, 2, 4, 1>", "colacc_combine_kernel<double>"],
-    "strmv_un_16384": ["rowdot_kernel<float, 4, 64, 2, 4, 1, false>"], "strmv_uu_16384": ["rowdot_kernel<float, 4, 64, 2, 4, 1, true>"],
-    "strmv_ln_16384": ["rowdot_kernel<float, 4, 64, 2, 4, 2, false>"], "strmv_lu_16384": ["rowdot_kernel<float, 4, 64, 2, 4, 2, true>"],
+    "strmv_un_16384": ["gather_kernel<float>", "rowdot_kernel<float, 4, 64, 2, 4, 1, false>"],
+    "strmv_uu_16384": ["gather_kernel<float>", "rowdot_kernel<float, 4, 64, 2, 4, 1, true>"],
+    "strmv_ln_16384": ["gather_kernel<float>", "rowdot_kernel<float, 4, 64, 2, 4, 2, false>"],
+    "strmv_lu_16384": ["gather_kernel<float>", "rowdot_kernel<float, 4, 64, 2, 4, 2, true>"],
     "ssymv_l_16384": SWEEP("float", 4, "false", 0), "sger_16384": ["ger_kernel<float, 4>"],
     "strmv_ut_16384": SWEEP("float", 4, "true", 1), "strmv_lt_16384": SWEEP("float", 4, "false", 1),
     "ssymv_u_16384": SWEEP("float", 4, "true", 0), "dsymv_l_16384": SWEEP("double", 2, "false", 0),

@@ -71,7 +71,6 @@ typedef enum {
 /* Creates a host-side handle (stream = default stream, no workspace).  Allocates no device
  * memory and makes no GPU call.  Returns -1 if h is NULL. */
 int mxb_create(mxb_handle_t* h);
-/* The work enqueued through the handle must have completed. */
 int mxb_destroy(mxb_handle_t h);
 /* hip_stream is a hipStream_t (borrowed); NULL selects the default stream. */
 int mxb_set_stream(mxb_handle_t h, void* hip_stream);

@@ -15,7 +15,6 @@ struct mxb_ctx {
     size_t ws_bytes;
     int64_t opt[MXB_OPT_COUNT];
     const int* device_status;   // error word of the last call that can fail on the device (in the workspace), or null
-    int arrive_slot;            // this handle's block of arrival counters in the library's static device array, or -1
 };
 
 namespace mxb {
@@ -309,60 +308,6 @@ __device__ __forceinline__ A block_sum(A v, A* slots)
 #pragma unroll
     for (int k = 1; k < NW; ++k) s += slots[k];
     return s;
-}
-
-// ------------------------------------------------------------------------------------------------
-// Kernels that finish their own cross-block combine: every block writes its partial result,
-// arrives at a counter, and the block that arrives last adds the partial results up in a fixed
-// order (so the result does not depend on which block that is).  The counters live in a static
-// device array inside the library (zero when the library is loaded; the last block puts its
-// counter back to zero), one block of kArriveCounters counters per handle so that handles on
-// different streams do not share any.  arrive_counters() returns the handle's counters on the
-// current device, or null when the handle has none (more than kArriveSlots live handles) or no
-// device can be asked: callers then take their two-kernel path.
-constexpr int kArriveSlots = 64, kArriveCounters = 1024;
-unsigned* arrive_counters(mxb_handle_t h);
-
-// What blocks hand to each other inside one kernel goes through device-scope atomic stores and
-// loads: they are written through, resp. read past, the second-level cache of the compute die the
-// block runs on (each die has its own, and they are not coherent with each other).  No fence is
-// used anywhere: a device-scope release or acquire fence writes back, resp. invalidates, a die's
-// whole second-level cache, and a thousand blocks doing that turned a 12 us product into 144 us.
-__device__ __forceinline__ void st_agent(float* p, float v)
-{
-    __hip_atomic_store(reinterpret_cast<unsigned*>(p), __builtin_bit_cast(unsigned, v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void st_agent(double* p, double v)
-{
-    __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), __builtin_bit_cast(unsigned long long, v), __ATOMIC_RELAXED,
-                       __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ float ld_agent(const float* p)
-{
-    return __builtin_bit_cast(float, __hip_atomic_load(reinterpret_cast<const unsigned*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-}
-__device__ __forceinline__ double ld_agent(const double* p)
-{
-    return __builtin_bit_cast(double,
-                              __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-}
-
-// True, in every thread of the block, in the last of `expected` blocks to arrive at *counter.
-// Before it arrives a block waits until its own st_agent stores have been acknowledged, so when
-// the last block has arrived every block's partial results are in memory, and it reads them with
-// ld_agent.  flag: one bool of LDS.
-__device__ __forceinline__ bool arrive_is_last(unsigned* counter, unsigned expected, bool* flag)
-{
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const unsigned t = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const bool last = t == expected - 1;
-        if (last) __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        *flag = last;
-    }
-    __syncthreads();
-    return *flag;
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -1,5 +1,4 @@
 // Handle management, workspace sizing and the two bandwidth probes.
-#include <mutex>
 #include <new>
 
 #include "common.hpp"
@@ -58,51 +57,7 @@ __global__ void __launch_bounds__(kThreads) probe_read_kernel(int64_t nvec, int6
     if (threadIdx.x == 0) out[blockIdx.x] = tot;
 }
 
-// Arrival counters of the kernels that combine their own partial results (see common.hpp).
-static __device__ unsigned arrive_words[kArriveSlots * kArriveCounters];
-
-constexpr int kMaxDevices = 64;
-std::mutex g_arrive_mutex;
-bool g_slot_taken[kArriveSlots];
-unsigned* g_arrive_base[kMaxDevices];      // device address of arrive_words, per device; null until first asked
-
-int take_arrive_slot()
-{
-    std::lock_guard<std::mutex> lock(g_arrive_mutex);
-    for (int s = 0; s < kArriveSlots; ++s)
-        if (!g_slot_taken[s]) { g_slot_taken[s] = true; return s; }
-    return -1;
-}
-
-void release_arrive_slot(int s)
-{
-    if (s < 0) return;
-    std::lock_guard<std::mutex> lock(g_arrive_mutex);
-    g_slot_taken[s] = false;
-}
-
 }  // namespace
-
-unsigned* arrive_counters(mxb_handle_t h)
-{
-    if (h->arrive_slot < 0) return nullptr;
-    int dev = -1;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
-        (void)hipGetLastError();
-        return nullptr;
-    }
-    std::lock_guard<std::mutex> lock(g_arrive_mutex);
-    if (!g_arrive_base[dev]) {
-        void* p = nullptr;
-        if (hipGetSymbolAddress(&p, HIP_SYMBOL(arrive_words)) != hipSuccess || !p) {
-            (void)hipGetLastError();
-            return nullptr;
-        }
-        g_arrive_base[dev] = static_cast<unsigned*>(p);
-    }
-    return g_arrive_base[dev] + (size_t)h->arrive_slot * kArriveCounters;
-}
-
 }  // namespace mxb
 
 extern "C" {
@@ -118,7 +73,6 @@ int mxb_create(mxb_handle_t* h)
     c->ws_bytes = 0;
     for (int o = 0; o < MXB_OPT_COUNT; ++o) c->opt[o] = 0;
     c->device_status = nullptr;
-    c->arrive_slot = mxb::take_arrive_slot();      // host-side bookkeeping only
     *h = c;
     return MXB_OK;
 }
@@ -127,7 +81,6 @@ int mxb_destroy(mxb_handle_t h)
 {
     if (!mxb::handle_ok(h)) return MXB_ERR_HANDLE;
     h->magic = 0;
-    mxb::release_arrive_slot(h->arrive_slot);
     delete h;
     return MXB_OK;
 }

@@ -191,27 +191,10 @@ __global__ void __launch_bounds__(kRowdotThreads, 4) rowdot_kernel(const RowdotA
         }
         const int64_t i = grow0 + l;
         if (l < R && i < p.M) {
-            if (MODE != MODE_GENERAL && p.arrive) {
-                st_agent(p.held + i, p.alpha * out);          // in place: held back until every block has read x
-            } else {
-                T* yp = y + i * p.incy;
-                T v = p.alpha * out;
-                if (p.beta != T(0)) v = fmad(p.beta, *yp, v);
-                *yp = v;
-            }
-        }
-    }
-    if (MODE != MODE_GENERAL && p.arrive) {
-        __shared__ bool last_flag;
-        if (!arrive_is_last(p.arrive, gridDim.x, &last_flag)) return;
-        // (batches of 8 loads per thread: one at a time, each would cost a round trip to memory)
-        for (int64_t i0 = threadIdx.x; i0 < p.M; i0 += 8 * kRowdotThreads) {
-            T t[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) t[e] = ld_agent(p.held + imin(i0 + e * kRowdotThreads, p.M - 1));
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-                if (i0 + e * kRowdotThreads < p.M) p.y[(i0 + e * kRowdotThreads) * p.incy] = t[e];
+            T* yp = y + i * p.incy;
+            T v = p.alpha * out;
+            if (p.beta != T(0)) v = fmad(p.beta, *yp, v);
+            *yp = v;
         }
     }
 }
@@ -977,7 +960,9 @@ int gemv_rows(mxb_handle_t h, bool no_trans, int64_t rows, int64_t cols, T alpha
                            h->stream, nparts, rows, rows, partials, alpha, beta, y0, incy, (int64_t)0, (int64_t)0);
         return launch_status();
     }
-    if (no_trans && batch == 1 && cols >= kWave * Full<T>::vec / 2 && rows * cols * (int64_t)sizeof(T) <= option(h, MXB_OPT_GEMVN_SMALL_MAX)) {
+    // (a ragged width costs the persistent row-dot grid more than it costs this kernel: up to four times the limit, 6001^2: 26.8 against 30.7 us)
+    if (no_trans && batch == 1 && cols >= kWave * Full<T>::vec / 2 &&
+        rows * cols * (int64_t)sizeof(T) <= option(h, MXB_OPT_GEMVN_SMALL_MAX) * (cols % Full<T>::vec != 0 ? 4 : 1)) {
         // a matrix that comes from the caches, rows of at least half a wavefront of vectors: one or two
         // rows per wavefront, no LDS, no barrier
         constexpr int FV = Full<T>::vec;
@@ -1153,18 +1138,10 @@ int trmv(mxb_handle_t h, int layout, int uplo, int trans, int diag, int64_t n, c
     // transposed: the triangle sweep reads x, its combine pass writes x afterwards: no copy needed
     if (!no_trans) return trisweep_trmv_t<T>(h, upper, unit, n, A, lda, x0, incx);
 
-    // not transposed: rows are finished while other blocks still read x
+    // not transposed: rows are written while other blocks still read x, so work from a snapshot
     const size_t snap_bytes = align_up((size_t)n * sizeof(T), 256);
     T* snap = static_cast<T*>(take_workspace(h, snap_bytes));
     if (!snap) return MXB_ERR_WORKSPACE;
-    if (unsigned* counters = arrive_counters(h)) {
-        // one kernel: the results are held in the workspace and the last block to finish copies them to x
-        RowdotArgs<T> a{n, n, A, lda, x0, incx, x0, incx, T(1), T(0), 0, 0};
-        a.held = snap;
-        a.arrive = counters;
-        return launch_rowdot(h, a, mode, unit);
-    }
-    // no arrival counters for this handle: work from a snapshot of x made by a kernel of its own
     hipLaunchKernelGGL(gather_kernel<T>, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, h->stream, n, x0, incx, snap);
     int st = launch_status();
     if (st != MXB_OK) return st;

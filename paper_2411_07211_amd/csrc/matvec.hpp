@@ -21,11 +21,6 @@ struct RowdotArgs {
     int x_contig;        // x has unit increment and is 16-byte aligned: stage it with 128-bit loads
     // a batch of problems of this shape: problem b uses A + b*sA, x + b*sx, y + b*sy
     int64_t batch = 1, sA = 0, sx = 0, sy = 0;
-    // In place (trmv, y is x): when `arrive` is set, the results go to the dense vector `held`
-    // with device-scope stores while other blocks still read x, every block arrives at *arrive
-    // when its rows are done, and the block that arrives last copies `held` to y.
-    T* held = nullptr;
-    unsigned* arrive = nullptr;
 };
 
 template <typename T>
