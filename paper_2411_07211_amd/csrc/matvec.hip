@@ -724,18 +724,19 @@ namespace {
 // with 8 loads in flight, the 32 row lanes of a column are folded through LDS in a fixed order.
 // The general kernel gives a block at least 1024 columns, which for such a matrix leaves a
 // handful of blocks or forces many row groups whose partial vectors weigh as much as the matrix.
-constexpr int kSmallColLanes = 8, kSmallRowLanes = 32, kSmallUnroll = 8;
-// Taken for matrices of up to 1024 rows (four rounds of loads per lane): with more rows the few
-// long-running blocks lose against the general kernel's many (measured: 256^2 3.9 -> 2.7 us,
-// 512^2 5.9 -> 3.3, 1024^2 9.3 -> 6.6, 256 x 16384 9.8 -> 4.8; 1536^2 a tie, 2048^2 10.1 -> 12.3).
-constexpr int64_t kSmallMaxRows = 1024;
+constexpr int kSmallUnroll = 8;
 
-template <typename T, int VEC>
-__global__ void __launch_bounds__(kSmallColLanes* kSmallRowLanes) colsum_small_kernel(const ColaccArgs<T> p)
+// CL column lanes (CL vectors of columns per block) x RL row lanes; a lane walks down every RL-th
+// row.  The RL partial sums of a column are folded through LDS in two fixed stages: groups of
+// RL / 8 adjacent row lanes first, then the 8 group sums.
+template <typename T, int VEC, int CL, int RL>
+__global__ void __launch_bounds__(CL* RL) colsum_small_kernel(const ColaccArgs<T> p)
 {
     typedef typename VecOf<T, VEC>::type V;
-    constexpr int CL = kSmallColLanes, RL = kSmallRowLanes, U = kSmallUnroll, W = CL * VEC;
+    constexpr int U = kSmallUnroll, W = CL * VEC, G = 8, PER = RL / G;
+    static_assert(RL % G == 0 && CL * RL >= G * W, "two-stage fold");
     __shared__ T red[RL][W + 1];
+    __shared__ T red2[G][W + 1];
     const int cl = threadIdx.x % CL, rl = threadIdx.x / CL;
     // my vector of columns; the last vector of a ragged width is moved back to end at the last
     // column and its first `shift` elements, which the lane before it owns, are dropped at the end
@@ -774,6 +775,14 @@ __global__ void __launch_bounds__(kSmallColLanes* kSmallRowLanes) colsum_small_k
 #pragma unroll
     for (int k = 0; k < VEC; ++k) red[rl][cl * VEC + k] = acc[k];
     __syncthreads();
+    if (threadIdx.x < G * W) {
+        const int g = threadIdx.x / W, w = threadIdx.x % W;
+        T tot = T(0);
+#pragma unroll
+        for (int q = 0; q < PER; ++q) tot += red[g * PER + q][w];
+        red2[g][w] = tot;
+    }
+    __syncthreads();
     if (threadIdx.x < W) {
         const int lane_c = threadIdx.x / VEC, k = threadIdx.x % VEC;
         int64_t c2;
@@ -781,11 +790,32 @@ __global__ void __launch_bounds__(kSmallColLanes* kSmallRowLanes) colsum_small_k
         if (place(lane_c, c2, shift2) && k >= shift2) {
             T tot = T(0);
 #pragma unroll
-            for (int q = 0; q < RL; ++q) tot += red[q][threadIdx.x];
+            for (int g = 0; g < G; ++g) tot += red2[g][threadIdx.x];
             T* out = p.y + (c2 + k) * p.incy;
             *out = p.beta == T(0) ? p.alpha * tot : fmad(p.alpha, tot, p.beta * *out);
         }
     }
+}
+
+// Shape of the kernel above for an M x N matrix, as column lanes * 100 + row lanes: row lanes so
+// that a lane has one or two rounds of loads (per call in a replayed graph, 8 x 32 / 8 x 64 /
+// 4 x 128 / 8 x 128 lanes: 256^2 2.7 / 2.8 / 3.1 / 3.2 us, 512^2 3.3 / 2.9 / 3.2 / 3.4, 1024^2 4.4 /
+// 3.6 / 3.3 / 3.5, 1536^2 5.6 / 4.3 / 3.9 / 4.6, 2048^2 6.8 / 5.0 / 6.5 / 4.8; the general kernels:
+// 4.5, 6.1, 6.3, 6.6, 8.1).  From 2049 rows on the general kernels win (3000^2: 11.6 against 16 us).
+// 0: not taken.
+constexpr int64_t kSmallMaxRows = 2048;
+template <typename T>
+int colsum_small_shape(mxb_handle_t h, int64_t M, int64_t N)
+{
+    constexpr int FV = Full<T>::vec;
+    if (N < FV || M > kSmallMaxRows || M * N * (int64_t)sizeof(T) > option(h, MXB_OPT_GEMVT_SMALL_MAX)) return 0;
+    return M <= 256 ? 832 : (M <= 512 ? 864 : (M <= 1536 ? 428 : 928));
+}
+
+template <typename T, int VEC, int CL, int RL>
+void launch_colsum_small(mxb_handle_t h, const ColaccArgs<T>& a)
+{
+    hipLaunchKernelGGL((colsum_small_kernel<T, VEC, CL, RL>), dim3((unsigned)ceil_div(a.N, (int64_t)CL * VEC)), dim3(CL * RL), 0, h->stream, a);
 }
 
 template <typename T, int VEC>
@@ -815,10 +845,14 @@ int launch_colacc(mxb_handle_t h, ColaccArgs<T> a, int64_t batch)
     // alignment only and the kernel moves the last vector of a ragged row back.
     // (a ragged row of up to 64 elements keeps more lanes busy with one element per lane)
     const bool vec = a.N % FV == 0 || a.N > kWave;
-    if (batch == 1 && a.N >= FV && a.M <= kSmallMaxRows && a.M * a.N * (int64_t)sizeof(T) <= option(h, MXB_OPT_GEMVT_SMALL_MAX)) {
-        hipLaunchKernelGGL((colsum_small_kernel<T, FV>), dim3((unsigned)ceil_div(a.N, (int64_t)kSmallColLanes * FV)),
-                           dim3(kSmallColLanes * kSmallRowLanes), 0, h->stream, a);
-        return launch_status();
+    if (batch == 1) {
+        switch (colsum_small_shape<T>(h, a.M, a.N)) {
+            case 832: launch_colsum_small<T, FV, 8, 32>(h, a); return launch_status();
+            case 864: launch_colsum_small<T, FV, 8, 64>(h, a); return launch_status();
+            case 428: launch_colsum_small<T, FV, 4, 128>(h, a); return launch_status();
+            case 928: launch_colsum_small<T, FV, 8, 128>(h, a); return launch_status();
+            default: break;
+        }
     }
     auto share = [&](int64_t blocks) { return blocks / batch > 1 ? blocks / batch : 1; };
     const ColaccPlan pl = colacc_plan(a.M, a.N, (int)sizeof(T), vec ? FV : 1, share(option(h, MXB_OPT_COLACC_TARGET_BLOCKS)),

@@ -17,7 +17,7 @@ inline int64_t option_default(int o)
         case MXB_OPT_GER_ROWS_PER_BLOCK: return 8;     // one batch of 8 rows per block: short read-then-write bursts stream best
         case MXB_OPT_SYMV_TILE_VECTORS: return 0;     // 0: chosen from n
         case MXB_OPT_TRI_DIAG_WEIGHT: return 3;
-        case MXB_OPT_GEMVT_SMALL_MAX: return 32 << 20;   // and at most 1024 rows; larger matrices stream better through the general kernels
+        case MXB_OPT_GEMVT_SMALL_MAX: return 32 << 20;   // and at most 2048 rows; larger matrices stream better through the general kernels
         case MXB_OPT_GEMVN_SMALL_MAX: return 48 << 20;   // beyond, the persistent row-dot grid with x in LDS is faster (measured: 3000^2 8.8 against 10.4 us, 4096^2 13.3 against 12.6)
         case MXB_OPT_TRSV_SPIN_LIMIT: return 1 << 24;  // polls of one hand-over word before a wavefront gives up: tens of seconds
         case MXB_OPT_TRSV_CHAIN_MIN: return 512;       // from here the chained kernel is faster than a launch per block (measured: 32 against 37 us here, 88 against 146 at 2048)

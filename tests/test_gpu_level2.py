@@ -75,7 +75,7 @@ def test_gemv_shapes(blas, ctx, dt, trans):
         for pad in (0, 3, 4):
             gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, 1.5, 0.5, pad, 1, 1)
     # the transposed product of a small matrix has a kernel of its own: the same shapes through the
-    # general kernels, and shapes around its limits (1024 rows, one vector of columns, ragged widths)
+    # general kernels, and shapes around its limits (2048 rows, one vector of columns, ragged widths)
     try:
         ctx.set_option(blas.OPT_GEMVT_SMALL_MAX, 1)
         for (m, n) in GEMV_SHAPES:
@@ -100,7 +100,9 @@ def test_gemv_shapes(blas, ctx, dt, trans):
                    (512, 64 * fv * 20 + 5)]:
         for beta, incx, incy in ((0.0, 1, 1), (0.5, 2, 3), (-1.0, -1, -2)):
             gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, 1.5, beta, 1, incx, incy)
-    for (m, n) in [(1024, 4), (1024, 5), (1025, 64), (1000, 33), (37, 2049), (1, 700), (1023, 3), (300, 4099), (512, 8191)]:
+    # (transposed: every lane shape of the single-kernel path: up to 256, 512, 1536 and 2048 rows, and the first size beyond)
+    for (m, n) in [(1024, 4), (1024, 5), (1025, 64), (1000, 33), (37, 2049), (1, 700), (1023, 3), (300, 4099), (512, 8191),
+                   (256, 130), (257, 1031), (513, 29), (1536, 515), (1537, 64), (2048, 1037), (2049, 70)]:
         for beta in (0.0, 0.5):
             gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, 1.5, beta, 1, 2, 3)
     # few, very long rows: not transposed, the columns are split into chunks that run as a batch
