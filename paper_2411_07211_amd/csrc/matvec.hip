@@ -213,11 +213,15 @@ constexpr int kRowSmallThreads = 128;
 // WC == 1: the block's two wavefronts take R rows each.  WC > 1 (few, long rows): the block's WC
 // wavefronts share one row, batch b of its columns goes to wavefront b % WC, LDS folds them in
 // wave order.
-template <typename T, int VEC, int R, int U, int WC>
+// MODE upper / lower (trmv): a wavefront's columns start at the vector that holds the diagonal
+// of its first row, resp. end with the one of its last row, and what a load brings from outside
+// the triangle is discarded by a select.
+template <typename T, int VEC, int R, int U, int WC, int MODE = MODE_GENERAL, bool UNIT = false>
 __global__ void __launch_bounds__(WC == 1 ? kRowSmallThreads : WC * kWave) rowsmall_kernel(const RowdotArgs<T> p)
 {
     typedef typename VecOf<T, VEC>::type V;
     static_assert(WC == 1 || R == 1, "wavefronts that share a row take one row");
+    static_assert(WC == 1 || MODE == MODE_GENERAL, "triangular rows are not shared");
     constexpr int SPANV = kWave * VEC;             // columns a wavefront covers with one load
     __shared__ T part[WC];
     const int lane = threadIdx.x & (kWave - 1);
@@ -233,7 +237,8 @@ __global__ void __launch_bounds__(WC == 1 ? kRowSmallThreads : WC * kWave) rowsm
     // Batches of U loads per row, all in flight before the first use and none predicated: a vector
     // that would start past column N, or run past it, is moved back to end at N (N >= VEC), and
     // the elements that are not its own (a neighbour's, or all of them) meet a zero of x.
-    for (int64_t c0 = (int64_t)lane * VEC + (WC == 1 ? 0 : wave * (SPANV * U)); c0 - lane * VEC < p.N; c0 += (int64_t)SPANV * U * WC) {
+    const int64_t cbeg = MODE == MODE_UPPER ? row0 / VEC * VEC : 0, cend = MODE == MODE_LOWER ? imin(p.N, row0 + R) : p.N;
+    for (int64_t c0 = cbeg + (int64_t)lane * VEC + (WC == 1 ? 0 : wave * (SPANV * U)); c0 - lane * VEC < cend; c0 += (int64_t)SPANV * U * WC) {
         V a[U][R], xv[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -255,7 +260,10 @@ __global__ void __launch_bounds__(WC == 1 ? kRowSmallThreads : WC * kWave) rowsm
 #pragma unroll
             for (int r = 0; r < R; ++r)
 #pragma unroll
-                for (int k = 0; k < VEC; ++k) acc[r] = fmad(a[u][r][k], xv[u][k], acc[r]);
+                for (int k = 0; k < VEC; ++k) {
+                    const int64_t j = imin(c0 + u * SPANV, p.N - VEC) + k;
+                    acc[r] = fmad(tri_value<T, MODE, UNIT>(a[u][r][k], row0 + r, j), xv[u][k], acc[r]);
+                }
     }
 #pragma unroll
     for (int r = 0; r < R; ++r) {
@@ -1180,6 +1188,27 @@ int trmv(mxb_handle_t h, int layout, int uplo, int trans, int diag, int64_t n, c
     int st = launch_status();
     if (st != MXB_OK) return st;
     RowdotArgs<T> a{n, n, A, lda, snap, 1, x0, incx, T(1), T(0), 0, 0};
+    constexpr int FV = Full<T>::vec;
+    if (n >= kWave * FV / 2 && n * (n + 1) / 2 * (int64_t)sizeof(T) <= option(h, MXB_OPT_GEMVN_SMALL_MAX)) {
+        // a triangle that comes from the caches: one or two rows per wavefront, as for gemv
+        constexpr int WPB = kRowSmallThreads / kWave;
+        const int64_t loads = ceil_div(n, (int64_t)kWave * FV);
+        const dim3 g1((unsigned)ceil_div(n, (int64_t)WPB)), g2((unsigned)ceil_div(n, (int64_t)WPB * 2)), blk(kRowSmallThreads);
+#define MXB_ROWSMALL_TRI(R_, U_, G_)                                                                                         \
+    if (mode == MODE_UPPER) {                                                                                                \
+        if (unit) hipLaunchKernelGGL((rowsmall_kernel<T, FV, R_, U_, 1, MODE_UPPER, true>), G_, blk, 0, h->stream, a);        \
+        else hipLaunchKernelGGL((rowsmall_kernel<T, FV, R_, U_, 1, MODE_UPPER, false>), G_, blk, 0, h->stream, a);            \
+    } else {                                                                                                                 \
+        if (unit) hipLaunchKernelGGL((rowsmall_kernel<T, FV, R_, U_, 1, MODE_LOWER, true>), G_, blk, 0, h->stream, a);        \
+        else hipLaunchKernelGGL((rowsmall_kernel<T, FV, R_, U_, 1, MODE_LOWER, false>), G_, blk, 0, h->stream, a);            \
+    }
+        if (n > kRowSmallOneRow) { MXB_ROWSMALL_TRI(2, 4, g2) }
+        else if (loads <= 2) { MXB_ROWSMALL_TRI(1, 2, g1) }
+        else if (loads <= 4) { MXB_ROWSMALL_TRI(1, 4, g1) }
+        else { MXB_ROWSMALL_TRI(1, 8, g1) }
+#undef MXB_ROWSMALL_TRI
+        return launch_status();
+    }
     return launch_rowdot(h, a, mode, unit);
 }
 

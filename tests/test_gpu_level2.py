@@ -336,6 +336,20 @@ def test_trmv(blas, ctx, dt, layout, uplo, trans, diag):
     trmv_case(blas, ctx, dt, layout, uplo, trans, diag, 515, 1, 2)
     trmv_case(blas, ctx, dt, layout, uplo, trans, diag, 515, 0, -1)
     trmv_case(blas, ctx, dt, layout, uplo, trans, diag, 1536, 0, 1, ints=True)
+    if trans == O.NO_TRANS:
+        # not transposed, a cache-sized triangle takes the wavefront-per-row kernel: sizes around its
+        # limits (narrowest rows, 2, 4 and 8 loads per row, one and two rows per wavefront), and the
+        # same sizes through the persistent row-dot grid
+        for small_max in (0, 1):
+            try:
+                ctx.set_option(blas.OPT_GEMVN_SMALL_MAX, small_max)
+                fv = 16 // np.dtype(dt).itemsize
+                for n in (32 * fv - 1, 32 * fv, 128 * fv, 128 * fv + 1, 256 * fv + 3, 513 * fv, 2047, 2048, 2049, 3001):
+                    trmv_case(blas, ctx, dt, layout, uplo, trans, diag, n, 0 if n % 2 else 4, 1)
+                trmv_case(blas, ctx, dt, layout, uplo, trans, diag, 700, 1, -2)
+                trmv_case(blas, ctx, dt, layout, uplo, trans, diag, 2100, 0, 1, ints=True)
+            finally:
+                ctx.set_option(blas.OPT_GEMVN_SMALL_MAX, 0)
     # sizes at which the triangle sweep takes its medium and its long batches
     trmv_case(blas, ctx, dt, layout, uplo, trans, diag, 7001, 0, 1)
     if dt == np.float32 and layout == O.ROW_MAJOR and diag == O.NON_UNIT:
