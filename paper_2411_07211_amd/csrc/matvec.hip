@@ -737,7 +737,10 @@ constexpr int kSmallUnroll = 8;
 // CL column lanes (CL vectors of columns per block) x RL row lanes; a lane walks down every RL-th
 // row.  The RL partial sums of a column are folded through LDS in two fixed stages: groups of
 // RL / 8 adjacent row lanes first, then the 8 group sums.
-template <typename T, int VEC, int CL, int RL>
+// MODE upper / lower (transposed trmv): a block's rows end with, resp. start at, the rows that
+// cross the diagonal in its columns, and what a load brings from outside the triangle is
+// discarded by a select.
+template <typename T, int VEC, int CL, int RL, int MODE = MODE_GENERAL, bool UNIT = false>
 __global__ void __launch_bounds__(CL* RL) colsum_small_kernel(const ColaccArgs<T> p)
 {
     typedef typename VecOf<T, VEC>::type V;
@@ -764,21 +767,26 @@ __global__ void __launch_bounds__(CL* RL) colsum_small_kernel(const ColaccArgs<T
     if (!live) c = 0;
     const T* col = p.A + c;
     V acc = V(T(0));
-    for (int64_t r0 = rl; r0 < p.M; r0 += (int64_t)RL * U) {
+    const int64_t rbeg = MODE == MODE_LOWER ? imin((int64_t)blockIdx.x * W, p.M) : 0;
+    const int64_t rend = MODE == MODE_UPPER ? imin(p.M, (int64_t)(blockIdx.x + 1) * W) : p.M;
+    for (int64_t r0 = rbeg + rl; r0 < rend; r0 += (int64_t)RL * U) {
         V a[U];
         T xr[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {        // rows past the end: the last row again, times zero
             const int64_t r = r0 + (int64_t)u * RL;
-            const int64_t rc = r < p.M ? r : p.M - 1;
+            const int64_t rc = r < rend ? r : rend - 1;
             a[u] = ld_matrix<T, VEC>(col + rc * p.lda);
-            xr[u] = r < p.M ? p.x[rc * p.incx] : T(0);
+            xr[u] = r < rend ? p.x[rc * p.incx] : T(0);
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
-            for (int k = 0; k < VEC; ++k) acc[k] = fmad(a[u][k], xr[u], acc[k]);
+            for (int k = 0; k < VEC; ++k) {
+                const int64_t r = r0 + (int64_t)u * RL;
+                acc[k] = fmad(tri_value<T, MODE, UNIT>(a[u][k], r < rend ? r : rend - 1, c + k), xr[u], acc[k]);
+            }
     }
 #pragma unroll
     for (int k = 0; k < VEC; ++k) red[rl][cl * VEC + k] = acc[k];
@@ -820,10 +828,10 @@ int colsum_small_shape(mxb_handle_t h, int64_t M, int64_t N)
     return M <= 256 ? 832 : (M <= 512 ? 864 : (M <= 1536 ? 428 : 928));
 }
 
-template <typename T, int VEC, int CL, int RL>
+template <typename T, int VEC, int CL, int RL, int MODE = MODE_GENERAL, bool UNIT = false>
 void launch_colsum_small(mxb_handle_t h, const ColaccArgs<T>& a)
 {
-    hipLaunchKernelGGL((colsum_small_kernel<T, VEC, CL, RL>), dim3((unsigned)ceil_div(a.N, (int64_t)CL * VEC)), dim3(CL * RL), 0, h->stream, a);
+    hipLaunchKernelGGL((colsum_small_kernel<T, VEC, CL, RL, MODE, UNIT>), dim3((unsigned)ceil_div(a.N, (int64_t)CL * VEC)), dim3(CL * RL), 0, h->stream, a);
 }
 
 template <typename T, int VEC>
@@ -1177,6 +1185,31 @@ int trmv(mxb_handle_t h, int layout, int uplo, int trans, int diag, int64_t n, c
     const bool unit = diag == MXB_UNIT;
 
     T* x0 = vec_base(x, n, incx);
+    if (!no_trans && n >= Full<T>::vec && n <= kSmallMaxRows) {
+        // transposed, a small triangle: a snapshot of x, then the single-kernel column sums of a small
+        // transposed gemv in triangular mode (no partial vectors)
+        T* snap = static_cast<T*>(take_workspace(h, align_up((size_t)n * sizeof(T), 256)));
+        if (!snap) return MXB_ERR_WORKSPACE;
+        hipLaunchKernelGGL(gather_kernel<T>, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, h->stream, n, x0, incx, snap);
+        const int st = launch_status();
+        if (st != MXB_OK) return st;
+        constexpr int FV = Full<T>::vec;
+        ColaccArgs<T> a{n, n, A, lda, snap, 1, x0, incx, T(1), T(0), nullptr, 0, 0};
+#define MXB_COLSUM_TRI(CL_, RL_)                                                                     \
+    if (upper) {                                                                                     \
+        if (unit) launch_colsum_small<T, FV, CL_, RL_, MODE_UPPER, true>(h, a);                       \
+        else launch_colsum_small<T, FV, CL_, RL_, MODE_UPPER, false>(h, a);                           \
+    } else {                                                                                         \
+        if (unit) launch_colsum_small<T, FV, CL_, RL_, MODE_LOWER, true>(h, a);                       \
+        else launch_colsum_small<T, FV, CL_, RL_, MODE_LOWER, false>(h, a);                           \
+    }
+        if (n <= 256) { MXB_COLSUM_TRI(8, 32) }
+        else if (n <= 512) { MXB_COLSUM_TRI(8, 64) }
+        else if (n <= 1536) { MXB_COLSUM_TRI(4, 128) }
+        else { MXB_COLSUM_TRI(8, 128) }
+#undef MXB_COLSUM_TRI
+        return launch_status();
+    }
     // transposed: the triangle sweep reads x, its combine pass writes x afterwards: no copy needed
     if (!no_trans) return trisweep_trmv_t<T>(h, upper, unit, n, A, lda, x0, incx);
 
