@@ -374,7 +374,7 @@ def sweep(B, ctx, torch):
     reset3 = lambda: xt3.copy_(xs3)
     for n in (1024, 4096, 16384):
         t, full, tri = f"{n}x{n}", 4 * n * n, 4 * (n * (n + 1) // 2)
-        rec("sgemv_n inc", t, full, lambda: B.mxb_sgemv(h, B.ROW_MAJOR, B.NO_TRANS, n, n, 1.0, A, n, xv, 2, 0.5, yv, 3))
+        rec("sgemv_n (inc 2,3)", t, full, lambda: B.mxb_sgemv(h, B.ROW_MAJOR, B.NO_TRANS, n, n, 1.0, A, n, xv, 2, 0.5, yv, 3))
         rec("sgemv_t (inc 2,3)", t, full, lambda: B.mxb_sgemv(h, B.ROW_MAJOR, B.TRANS, n, n, 1.0, A, n, xv, 2, 0.5, yv, 3))
         rec("ssymv_l (inc 2,3)", t, tri, lambda: B.mxb_ssymv(h, B.ROW_MAJOR, B.LOWER, n, 0.5, A, n, xv, 2, 0.5, yv, 3))
         rec("sger (inc 2,3)", t, 2 * full, lambda: B.mxb_sger(h, B.ROW_MAJOR, n, n, 1e-6, xv, 2, yv, 3, A, n))
@@ -433,12 +433,17 @@ def sweep(B, ctx, torch):
     def bucket(nb):
         return "small (< 4 MiB)" if nb < (4 << 20) else "medium (< 256 MiB)" if nb < (256 << 20) else "large"
 
-    print("| routine | shape | MiB | us, one call | GB/s | % of 8 TB/s | us per call, 20 calls in a replayed graph | GB/s |")
-    print("|---|---|---|---|---|---|---|---|")
-    for name, shape, nb, us, gus in rows:
-        print(f"| {name} | {shape} | {nb / 2**20:.2f} | {us:.1f} | {nb / us / 1e3:.0f} | {nb / us / 1e3 / 80:.1f} | "
-              + (f"{gus:.1f} | {nb / gus / 1e3:.0f} |" if gus else "| |"))
-    print()
+    # the whole of profiles/size_sweep.md
+    print("# Size sweep: every routine from launch-bound to HBM-bound sizes, single calls and graph replay\n")
+    print("Command (one MI355X, committed files only): `python bench.py --sweep > profiles/size_sweep.md`.  Times are medians of 20\n"
+          "event-timed calls after 3 warm-ups; the last two columns are the time per call of 20 calls captured into one HIP graph and\n"
+          "replayed (only where a single call takes less than 60 us): what the GPU needs once the host's launch cost is out of the\n"
+          "way.  Buckets by the bytes a call moves: small < 4 MiB, medium < 256 MiB (fits the last-level cache), large beyond.  s/d:\n"
+          "fp32 / fp64; trmv and symv variants: u/l = upper / lower, n/t = not transposed / transposed, a trailing u = unit diagonal;\n"
+          "(inc 2,3): the same call with incx = 2, incy = 3 (trmv: incx = 3); N = 40 shapes are the skinny matrices of Sec. 6.2.2 (M\n"
+          "powers of 2 and 3); sgemv_n_b / sgemv_t_b are strided batches of square matrices in one call; sgemv_n_w / sgemv_t_w are a few\n"
+          "rows of millions of columns (the long vector counts in the bytes); strsv: unit diagonal over small off-diagonal elements.\n")
+    print("## Geometric means per bucket\n")
     print("| routine | bucket | cases | geometric mean GB/s, one call | in a replayed graph |")
     print("|---|---|---|---|---|")
     label = lambda name, shape: name + (" (N=40)" if shape.endswith("x40") else "")
@@ -451,6 +456,12 @@ def sweep(B, ctx, torch):
         gm = float(np.exp(np.mean([np.log(nb / us / 1e3) for nb, us, gus in sel])))
         gg = float(np.exp(np.mean([np.log(nb / (gus or us) / 1e3) for nb, us, gus in sel])))
         print(f"| {k[0]} | {k[1]} | {len(sel)} | {gm:.0f} | {gg:.0f} |")
+    print("\n## Every case\n")
+    print("| routine | shape | MiB | us, one call | GB/s | % of 8 TB/s | us per call, 20 calls in a replayed graph | GB/s |")
+    print("|---|---|---|---|---|---|---|---|")
+    for name, shape, nb, us, gus in rows:
+        print(f"| {name} | {shape} | {nb / 2**20:.2f} | {us:.1f} | {nb / us / 1e3:.0f} | {nb / us / 1e3 / 80:.1f} | "
+              + (f"{gus:.1f} | {nb / gus / 1e3:.0f} |" if gus else "| |"))
 
 
 CSRC = os.path.join(ROOT, "paper_2411_07211_amd", "csrc")
@@ -473,7 +484,7 @@ CALL_KERNELS = {
     "sgemv_n_1048576x256_b0": ["skinny_gemv_n_onerow_kernel<float, 4, false, 8>"],
     "sgemv_n_1048576x256_b0.5": ["skinny_gemv_n_onerow_kernel<float, 4, true, 8>"],
     "sgemv_t_1048576x256_b0": ["colacc_kernel<float, 4, 1, 4>", "colacc_combine_kernel<float>"],
-    "sgemv_n_1024": ["rowsmall_kernel<float, 4, 1, 4, 1>"],
+    "sgemv_n_1024": ["rowsmall_kernel<float, 4, 1, 4, 1, 0, false>"],
     "dgemv_n_16384": ["rowdot_kernel<double, 2, 64, 2, 4, 0, false>"],
     "dgemv_t_16384": ["colacc_kernel<double, 2, 4, 1>", "colacc_combine_kernel<double>"],
     "strmv_un_16384": ["gather_kernel<float>", "rowdot_kernel<float, 4, 64, 2, 4, 1, false>"],
@@ -644,10 +655,12 @@ and the kernel next to it).
             avgs = [x[1] / x[0] / 1e3 for x in st]
             avg, mn = sum(avgs), sum(x[2] for x in st) / 1e3
             hb = T["calls"].get(call, {}).get("hbm_bytes")
+            # a strided call is compared with the whole lines it has to move (incx = 2, incy = 3)
+            whole = nb * {"axpy": 8 / 3, "dot": 5 / 2, "scal": 2, "asum": 2, "nrm2": 2}[call[1:].split("_")[0]] if call.endswith("_strided") else nb
             out.append(f"| {label} | " + " + ".join(f"`{k}`" for k in ks) + f" | {' + '.join(str(x[0]) for x in st)} | "
                        + " + ".join(f"{a:.2f}" for a in avgs) + (f" = {avg:.2f}" if len(avgs) > 1 else "")
                        + f" | {mn:.2f} | {nb:,} | {nb / avg / 1e3:.0f} | {nb / avg / 1e3 / 80:.1f} % | "
-                       + (f"{hb:,} | {(hb / nb - 1) * 100:+.2f} % |" if hb else "- | - |"))
+                       + (f"{hb:,} | {(hb / whole - 1) * 100:+.2f} %{' (of the whole lines)' if whole != nb else ''} |" if hb else "- | - |"))
         text = f"# rocprofv3 summary: {title}\n\n" + head + "\n" + "\n".join(out) + "\n"
         open(os.path.join(ROOT, "profiles", fn), "w").write(text)
         print("\n".join(out))
