@@ -22,7 +22,7 @@ constexpr int kScalUnroll = 2;  // scal reads and writes the same lines: shorter
 // Tiles of kThreads*U vectors (shaped by stream_tile).  Whole tiles carry no predicate, so that
 // all loads of a tile are issued back to back; the ragged rest (fewer than one tile of vectors,
 // then fewer than VEC elements) is handled by the last block, one vector resp. one element per thread.
-template <typename T>
+template <typename T, bool KEEP>
 __global__ void __launch_bounds__(kThreads) axpy_vec_kernel(int64_t nvec, int64_t nfull, int64_t n2d, int tail, T alpha,
                                                             const T* __restrict__ x, T* __restrict__ y)
 {
@@ -34,9 +34,9 @@ __global__ void __launch_bounds__(kThreads) axpy_vec_kernel(int64_t nvec, int64_
         stream_tile<U>(t, n2d, base, step);
         V a[U], b[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) a[u] = ld_matrix<T, VEC>(x + (base + u * step) * VEC);
+        for (int u = 0; u < U; ++u) a[u] = ld_matrix_as<T, VEC, KEEP>(x + (base + u * step) * VEC);
 #pragma unroll
-        for (int u = 0; u < U; ++u) b[u] = ld_matrix<T, VEC>(y + (base + u * step) * VEC);
+        for (int u = 0; u < U; ++u) b[u] = ld_matrix_as<T, VEC, KEEP>(y + (base + u * step) * VEC);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -47,8 +47,8 @@ __global__ void __launch_bounds__(kThreads) axpy_vec_kernel(int64_t nvec, int64_
     }
     if (blockIdx.x != gridDim.x - 1) return;
     for (int64_t i = nfull * (kThreads * U) + threadIdx.x; i < nvec; i += kThreads) {
-        V b = ld_matrix<T, VEC>(y + i * VEC);
-        const V a = ld_matrix<T, VEC>(x + i * VEC);
+        V b = ld_matrix_as<T, VEC, KEEP>(y + i * VEC);
+        const V a = ld_matrix_as<T, VEC, KEEP>(x + i * VEC);
 #pragma unroll
         for (int k = 0; k < VEC; ++k) b[k] = fmad(alpha, a[k], b[k]);
         st_matrix<T, VEC>(y + i * VEC, b);
@@ -59,7 +59,7 @@ __global__ void __launch_bounds__(kThreads) axpy_vec_kernel(int64_t nvec, int64_
     }
 }
 
-template <typename T>
+template <typename T, bool KEEP>
 __global__ void __launch_bounds__(kThreads) scal_vec_kernel(int64_t nvec, int64_t nfull, int64_t n2d, int tail, T alpha,
                                                             T* __restrict__ x)
 {
@@ -71,7 +71,7 @@ __global__ void __launch_bounds__(kThreads) scal_vec_kernel(int64_t nvec, int64_
         stream_tile<U>(t, n2d, base, step);
         V a[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) a[u] = ld_matrix<T, VEC>(x + (base + u * step) * VEC);
+        for (int u = 0; u < U; ++u) a[u] = ld_matrix_as<T, VEC, KEEP>(x + (base + u * step) * VEC);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -82,7 +82,7 @@ __global__ void __launch_bounds__(kThreads) scal_vec_kernel(int64_t nvec, int64_
     }
     if (blockIdx.x != gridDim.x - 1) return;
     for (int64_t i = nfull * (kThreads * U) + threadIdx.x; i < nvec; i += kThreads) {
-        V a = ld_matrix<T, VEC>(x + i * VEC);
+        V a = ld_matrix_as<T, VEC, KEEP>(x + i * VEC);
 #pragma unroll
         for (int k = 0; k < VEC; ++k) a[k] = alpha * a[k];
         st_matrix<T, VEC>(x + i * VEC, a);
@@ -237,7 +237,7 @@ __device__ __forceinline__ void block_partial(const Acc<T, OP>* acc, int nacc, d
 
 // pass 1 on contiguous data: whole tiles without predicates, the ragged rest by the
 // last block.
-template <typename T, int OP, typename RES>
+template <typename T, int OP, typename RES, bool KEEP>
 __global__ void __launch_bounds__(kThreads) reduce_vec_kernel(int64_t nvec, int64_t nfull, int tail,
                                                               const T* __restrict__ x, const T* __restrict__ y,
                                                               double* __restrict__ partials, RES* __restrict__ result)
@@ -252,8 +252,8 @@ __global__ void __launch_bounds__(kThreads) reduce_vec_kernel(int64_t nvec, int6
         V a[U], b[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            a[u] = ld_matrix<T, VEC>(x + (base + u * kThreads) * VEC);
-            b[u] = TWO ? ld_matrix<T, VEC>(y + (base + u * kThreads) * VEC) : V(T(0));
+            a[u] = ld_matrix_as<T, VEC, KEEP>(x + (base + u * kThreads) * VEC);
+            b[u] = TWO ? ld_matrix_as<T, VEC, KEEP>(y + (base + u * kThreads) * VEC) : V(T(0));
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -263,8 +263,8 @@ __global__ void __launch_bounds__(kThreads) reduce_vec_kernel(int64_t nvec, int6
     }
     if (blockIdx.x == gridDim.x - 1) {
         for (int64_t i = nfull * (kThreads * U) + threadIdx.x; i < nvec; i += kThreads) {
-            const V a = ld_matrix<T, VEC>(x + i * VEC);
-            const V b = TWO ? ld_matrix<T, VEC>(y + i * VEC) : V(T(0));
+            const V a = ld_matrix_as<T, VEC, KEEP>(x + i * VEC);
+            const V b = TWO ? ld_matrix_as<T, VEC, KEEP>(y + i * VEC) : V(T(0));
 #pragma unroll
             for (int k = 0; k < VEC; ++k) acc[k].add(a[k], b[k]);
         }
@@ -372,8 +372,12 @@ int axpy(mxb_handle_t h, int64_t n, T alpha, const T* x, int64_t incx, T* y, int
         const int64_t nvec = n / VEC;
         const int64_t nfull = nvec / (kThreads * kUnroll);
         const int64_t grid = nfull < 1 ? 1 : (nfull < kCUs * bpc ? nfull : kCUs * bpc);
-        hipLaunchKernelGGL(axpy_vec_kernel<T>, dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, nfull,
-                           stream_tiles_2d(nvec, kUnroll), (int)(n % VEC), alpha, x, y);
+        if (keeps_vectors(2 * n * (int64_t)sizeof(T)))
+            hipLaunchKernelGGL((axpy_vec_kernel<T, true>), dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, nfull,
+                               stream_tiles_2d(nvec, kUnroll), (int)(n % VEC), alpha, x, y);
+        else
+            hipLaunchKernelGGL((axpy_vec_kernel<T, false>), dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, nfull,
+                               stream_tiles_2d(nvec, kUnroll), (int)(n % VEC), alpha, x, y);
     } else {
         const int64_t nfull = n / (kThreads * kStridedUnroll);
         const int64_t grid = nfull < 1 ? 1 : (nfull < kCUs * bpc ? nfull : kCUs * bpc);
@@ -396,8 +400,12 @@ int scal(mxb_handle_t h, int64_t n, T alpha, T* x, int64_t incx)
         const int64_t nvec = n / VEC;
         const int64_t nfull = nvec / (kThreads * kScalUnroll);
         const int64_t grid = nfull < 1 ? 1 : (nfull < kCUs * bpc ? nfull : kCUs * bpc);
-        hipLaunchKernelGGL(scal_vec_kernel<T>, dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, nfull,
-                           stream_tiles_2d(nvec, kScalUnroll), (int)(n % VEC), alpha, x);
+        if (keeps_vectors(n * (int64_t)sizeof(T)))
+            hipLaunchKernelGGL((scal_vec_kernel<T, true>), dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, nfull,
+                               stream_tiles_2d(nvec, kScalUnroll), (int)(n % VEC), alpha, x);
+        else
+            hipLaunchKernelGGL((scal_vec_kernel<T, false>), dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, nfull,
+                               stream_tiles_2d(nvec, kScalUnroll), (int)(n % VEC), alpha, x);
     } else {
         const int64_t nfull = n / (kThreads * kStridedUnroll);
         const int64_t grid = nfull < 1 ? 1 : (nfull < kCUs * bpc ? nfull : kCUs * bpc);
@@ -429,8 +437,12 @@ int reduce(mxb_handle_t h, int64_t n, const T* x, int64_t incx, const T* y, int6
         const int64_t nvec = n / VEC;
         const int64_t nfull = nvec / (kThreads * (TWO ? kUnroll : 2 * kUnroll));
         grid = nfull <= kSingleBlockTiles ? 1 : (nfull < max_blocks ? nfull : max_blocks);
-        hipLaunchKernelGGL((reduce_vec_kernel<T, OP, RES>), dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, nfull,
-                           (int)(n % VEC), x, y, partials, result);
+        if (keeps_vectors((TWO ? 2 : 1) * n * (int64_t)sizeof(T)))
+            hipLaunchKernelGGL((reduce_vec_kernel<T, OP, RES, true>), dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, nfull,
+                               (int)(n % VEC), x, y, partials, result);
+        else
+            hipLaunchKernelGGL((reduce_vec_kernel<T, OP, RES, false>), dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, nfull,
+                               (int)(n % VEC), x, y, partials, result);
     } else {
         const int64_t nfull = n / (kThreads * kStridedUnroll);
         grid = nfull <= kSingleBlockTiles ? 1 : (nfull < max_blocks ? nfull : max_blocks);

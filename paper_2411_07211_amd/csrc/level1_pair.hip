@@ -33,7 +33,7 @@ template <typename T> struct OpLinear {
     }
 };
 
-template <typename T, typename Op>
+template <typename T, typename Op, bool KEEP>
 __global__ void __launch_bounds__(kThreads) pair_vec_kernel(int64_t nvec, int64_t nfull, int64_t n2d, int tail, T* __restrict__ x,
                                                             T* __restrict__ y, const Op op)
 {
@@ -45,9 +45,9 @@ __global__ void __launch_bounds__(kThreads) pair_vec_kernel(int64_t nvec, int64_
         stream_tile<U>(t, n2d, base, step);
         V a[U], b[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) a[u] = ld_matrix<T, VEC>(x + (base + u * step) * VEC);
+        for (int u = 0; u < U; ++u) a[u] = ld_matrix_as<T, VEC, KEEP>(x + (base + u * step) * VEC);
 #pragma unroll
-        for (int u = 0; u < U; ++u) b[u] = Op::kReadY ? ld_matrix<T, VEC>(y + (base + u * step) * VEC) : V(T(0));
+        for (int u = 0; u < U; ++u) b[u] = Op::kReadY ? ld_matrix_as<T, VEC, KEEP>(y + (base + u * step) * VEC) : V(T(0));
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -118,8 +118,12 @@ int pair_op(mxb_handle_t h, int64_t n, T* x, int64_t incx, T* y, int64_t incy, c
     if (incx == 1 && incy == 1) {   // any base address: the vector accesses need element alignment only
         const int64_t nvec = n / VEC, nfull = nvec / (kThreads * kUnroll);
         const int64_t grid = nfull < 1 ? 1 : (nfull < cap ? nfull : cap);
-        hipLaunchKernelGGL((pair_vec_kernel<T, Op>), dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, nfull,
-                           stream_tiles_2d(nvec, kUnroll), (int)(n % VEC), x, y, op);
+        if (keeps_vectors((Op::kReadY ? 2 : 1) * n * (int64_t)sizeof(T)))
+            hipLaunchKernelGGL((pair_vec_kernel<T, Op, true>), dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, nfull,
+                               stream_tiles_2d(nvec, kUnroll), (int)(n % VEC), x, y, op);
+        else
+            hipLaunchKernelGGL((pair_vec_kernel<T, Op, false>), dim3((unsigned)grid), dim3(kThreads), 0, h->stream, nvec, nfull,
+                               stream_tiles_2d(nvec, kUnroll), (int)(n % VEC), x, y, op);
     } else {
         const int64_t nfull = n / (kThreads * kStridedUnroll);
         const int64_t grid = nfull < 1 ? 1 : (nfull < cap ? nfull : cap);

@@ -244,7 +244,7 @@ __global__ void __launch_bounds__(WC == 1 ? kRowSmallThreads : WC * kWave) rowsm
         for (int u = 0; u < U; ++u) {
             const int64_t cu = c0 + u * SPANV, c = imin(cu, p.N - VEC);
 #pragma unroll
-            for (int r = 0; r < R; ++r) a[u][r] = ld_matrix<T, VEC>(arow[r] + c);
+            for (int r = 0; r < R; ++r) a[u][r] = ld_resident<T, VEC>(arow[r] + c);
             if (p.incx == 1) {
                 xv[u] = *reinterpret_cast<const V __attribute__((aligned(sizeof(T))))*>(p.x + c);
             } else {
@@ -301,7 +301,7 @@ constexpr int kColaccThreads = 256;
 //    sequential stream, which is what HBM serves fastest.
 //  WR == 4 (narrow matrices, CV == 1): one wavefront spans the row, the 4 wavefronts of a block
 //    interleave over the rows of a contiguous slab and are folded through LDS.
-template <typename T, int VEC, int CV, int WR>
+template <typename T, int VEC, int CV, int WR, bool KEEP>
 __global__ void __launch_bounds__(kColaccThreads) colacc_kernel(const ColaccArgs<T> p)
 {
     const T* __restrict__ A = p.A + (int64_t)blockIdx.z * p.sA;
@@ -366,7 +366,7 @@ __global__ void __launch_bounds__(kColaccThreads) colacc_kernel(const ColaccArgs
         for (int u = 0; u < U; ++u) {
             const int64_t i = r0 + (int64_t)u * rstep;
 #pragma unroll
-            for (int v = 0; v < CV; ++v) a[u][v] = ld_matrix<T, VEC>(acol[v] + i * p.lda);
+            for (int v = 0; v < CV; ++v) a[u][v] = ld_matrix_as<T, VEC, KEEP>(acol[v] + i * p.lda);
             xi[u] = x[i * p.incx];
         }
         __builtin_amdgcn_sched_barrier(0);   // keep every load of the batch ahead of the first FMA
@@ -382,7 +382,7 @@ __global__ void __launch_bounds__(kColaccThreads) colacc_kernel(const ColaccArgs
         const T xi = x[r0 * p.incx];
 #pragma unroll
         for (int v = 0; v < CV; ++v) {
-            const V a = ld_matrix<T, VEC>(acol[v] + r0 * p.lda);
+            const V a = ld_matrix_as<T, VEC, KEEP>(acol[v] + r0 * p.lda);
 #pragma unroll
             for (int k = 0; k < VEC; ++k) acc[v][k] = fmad(a[k], xi, acc[v][k]);
         }
@@ -776,7 +776,7 @@ __global__ void __launch_bounds__(CL* RL) colsum_small_kernel(const ColaccArgs<T
         for (int u = 0; u < U; ++u) {        // rows past the end: the last row again, times zero
             const int64_t r = r0 + (int64_t)u * RL;
             const int64_t rc = r < rend ? r : rend - 1;
-            a[u] = ld_matrix<T, VEC>(col + rc * p.lda);
+            a[u] = ld_resident<T, VEC>(col + rc * p.lda);
             xr[u] = r < rend ? p.x[rc * p.incx] : T(0);
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -839,10 +839,13 @@ void launch_colacc_inst(mxb_handle_t h, const ColaccArgs<T>& a, const ColaccPlan
 {
     const dim3 grid((unsigned)pl.col_tiles, (unsigned)pl.nparts, (unsigned)batch);
     const dim3 block(kColaccThreads);
-    if (pl.wr == 4) hipLaunchKernelGGL((colacc_kernel<T, VEC, 1, 4>), grid, block, 0, h->stream, a);
-    else if (pl.cv == 4) hipLaunchKernelGGL((colacc_kernel<T, VEC, 4, 1>), grid, block, 0, h->stream, a);
-    else if (pl.cv == 2) hipLaunchKernelGGL((colacc_kernel<T, VEC, 2, 1>), grid, block, 0, h->stream, a);
-    else hipLaunchKernelGGL((colacc_kernel<T, VEC, 1, 1>), grid, block, 0, h->stream, a);
+#define MXB_COLACC(KEEP_)                                                                                       \
+    if (pl.wr == 4) hipLaunchKernelGGL((colacc_kernel<T, VEC, 1, 4, KEEP_>), grid, block, 0, h->stream, a);         \
+    else if (pl.cv == 4) hipLaunchKernelGGL((colacc_kernel<T, VEC, 4, 1, KEEP_>), grid, block, 0, h->stream, a);    \
+    else if (pl.cv == 2) hipLaunchKernelGGL((colacc_kernel<T, VEC, 2, 1, KEEP_>), grid, block, 0, h->stream, a);    \
+    else hipLaunchKernelGGL((colacc_kernel<T, VEC, 1, 1, KEEP_>), grid, block, 0, h->stream, a)
+    if (keeps_matrix(batch * a.M * a.N * (int64_t)sizeof(T))) { MXB_COLACC(true); } else { MXB_COLACC(false); }
+#undef MXB_COLACC
 }
 
 constexpr int64_t kMaxGridZ = 65535;
@@ -1010,9 +1013,7 @@ int gemv_rows(mxb_handle_t h, bool no_trans, int64_t rows, int64_t cols, T alpha
                            h->stream, nparts, rows, rows, partials, alpha, beta, y0, incy, (int64_t)0, (int64_t)0);
         return launch_status();
     }
-    // (a ragged width costs the persistent row-dot grid more than it costs this kernel: up to four times the limit, 6001^2: 26.8 against 30.7 us)
-    if (no_trans && batch == 1 && cols >= kWave * Full<T>::vec / 2 &&
-        rows * cols * (int64_t)sizeof(T) <= option(h, MXB_OPT_GEMVN_SMALL_MAX) * (cols % Full<T>::vec != 0 ? 4 : 1)) {
+    if (no_trans && batch == 1 && cols >= kWave * Full<T>::vec / 2 && rows * cols * (int64_t)sizeof(T) <= option(h, MXB_OPT_GEMVN_SMALL_MAX)) {
         // a matrix that comes from the caches, rows of at least half a wavefront of vectors: one or two
         // rows per wavefront, no LDS, no barrier
         constexpr int FV = Full<T>::vec;

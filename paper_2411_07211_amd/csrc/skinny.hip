@@ -120,7 +120,7 @@ __global__ void __launch_bounds__(kThreads) skinny_gemv_n_onerow_kernel(const Sk
     }
 }
 
-template <typename T, int VEC, bool BETA>
+template <typename T, int VEC, bool BETA, bool KEEP>
 __global__ void __launch_bounds__(kThreads) skinny_gemv_n_kernel(const SkinnyArgs<T> p, const T* __restrict__ A,
                                                                  const T* __restrict__ x, T* __restrict__ y)
 {
@@ -141,13 +141,13 @@ __global__ void __launch_bounds__(kThreads) skinny_gemv_n_kernel(const SkinnyArg
         V a[kSlots];
         if ((t + 1) * rows_per_tile <= p.M) {      // whole tile: no predicate, so that all loads issue back to back
 #pragma unroll
-            for (int u = 0; u < kSlots; ++u) a[u] = ld_matrix<T, VEC>(A + (row0 + (int64_t)u * m.G) * p.lda + m.c);
+            for (int u = 0; u < kSlots; ++u) a[u] = ld_matrix_as<T, VEC, KEEP>(A + (row0 + (int64_t)u * m.G) * p.lda + m.c);
         } else {
 #pragma unroll
             for (int u = 0; u < kSlots; ++u) {
                 const int64_t i = row0 + (int64_t)u * m.G;
                 a[u] = V(T(0));
-                if (i < p.M) a[u] = ld_matrix<T, VEC>(A + i * p.lda + m.c);
+                if (i < p.M) a[u] = ld_matrix_as<T, VEC, KEEP>(A + i * p.lda + m.c);
             }
         }
         // the old y of the tile's rows travels with the matrix, 64 adjacent rows per load: read after
@@ -195,7 +195,7 @@ __global__ void __launch_bounds__(kThreads) skinny_gemv_n_kernel(const SkinnyArg
     }
 }
 
-template <typename T, int VEC>
+template <typename T, int VEC, bool KEEP>
 __global__ void __launch_bounds__(kThreads) skinny_gemv_t_kernel(const SkinnyArgs<T> p, const T* __restrict__ A,
                                                                  const T* __restrict__ x, T* __restrict__ partials)
 {
@@ -217,7 +217,7 @@ __global__ void __launch_bounds__(kThreads) skinny_gemv_t_kernel(const SkinnyArg
 #pragma unroll
             for (int u = 0; u < kSlots; ++u) {
                 const int64_t i = row0 + (int64_t)u * m.G;
-                a[u] = ld_matrix<T, VEC>(A + i * p.lda + m.c);
+                a[u] = ld_matrix_as<T, VEC, KEEP>(A + i * p.lda + m.c);
                 xi[u] = x[i * p.incl];
             }
         } else {
@@ -227,7 +227,7 @@ __global__ void __launch_bounds__(kThreads) skinny_gemv_t_kernel(const SkinnyArg
                 a[u] = V(T(0));
                 xi[u] = T(0);
                 if (i < p.M) {
-                    a[u] = ld_matrix<T, VEC>(A + i * p.lda + m.c);
+                    a[u] = ld_matrix_as<T, VEC, KEEP>(A + i * p.lda + m.c);
                     xi[u] = x[i * p.incl];
                 }
             }
@@ -279,7 +279,7 @@ __global__ void __launch_bounds__(kCombineGroups* kWave) skinny_combine_kernel(i
     *yp = v;
 }
 
-template <typename T, int VEC>
+template <typename T, int VEC, bool KEEP>
 __global__ void __launch_bounds__(kThreads) skinny_ger_kernel(const SkinnyArgs<T> p, T* __restrict__ A, const T* __restrict__ x,
                                                               const T* __restrict__ y)
 {
@@ -300,7 +300,7 @@ __global__ void __launch_bounds__(kThreads) skinny_ger_kernel(const SkinnyArgs<T
 #pragma unroll
             for (int u = 0; u < kSlots; ++u) {
                 const int64_t i = row0 + (int64_t)u * m.G;
-                a[u] = ld_matrix<T, VEC>(A + i * p.lda + m.c);
+                a[u] = ld_matrix_as<T, VEC, KEEP>(A + i * p.lda + m.c);
                 ax[u] = p.alpha * x[i * p.incl];
             }
         } else {
@@ -310,7 +310,7 @@ __global__ void __launch_bounds__(kThreads) skinny_ger_kernel(const SkinnyArgs<T
                 a[u] = V(T(0));
                 ax[u] = T(0);
                 if (i < p.M) {
-                    a[u] = ld_matrix<T, VEC>(A + i * p.lda + m.c);
+                    a[u] = ld_matrix_as<T, VEC, KEEP>(A + i * p.lda + m.c);
                     ax[u] = p.alpha * x[i * p.incl];
                 }
             }
@@ -351,8 +351,11 @@ inline int64_t tile_blocks(int64_t rows, int nv, int64_t cap)
     return b < cap ? b : cap;
 }
 
-#define MXB_SKINNY_DISPATCH(KERNEL, GRID, ...) \
-    hipLaunchKernelGGL((KERNEL<T, Full<T>::vec>), dim3((unsigned)(GRID)), dim3(kThreads), 0, h->stream, a, __VA_ARGS__)
+#define MXB_SKINNY_DISPATCH(KERNEL, GRID, ...)                                                                                        \
+    if (keeps_matrix(rows * cols * (int64_t)sizeof(T)))                                                                               \
+        hipLaunchKernelGGL((KERNEL<T, Full<T>::vec, true>), dim3((unsigned)(GRID)), dim3(kThreads), 0, h->stream, a, __VA_ARGS__);    \
+    else                                                                                                                              \
+        hipLaunchKernelGGL((KERNEL<T, Full<T>::vec, false>), dim3((unsigned)(GRID)), dim3(kThreads), 0, h->stream, a, __VA_ARGS__)
 
 }  // namespace
 
@@ -377,8 +380,13 @@ int skinny_gemv_n(mxb_handle_t h, int64_t rows, int64_t cols, T alpha, const T* 
         return launch_status();
     }
     const dim3 grid((unsigned)tile_blocks(rows, a.nv, (int64_t)kCUs * 16));
-    if (beta != T(0)) hipLaunchKernelGGL((skinny_gemv_n_kernel<T, Full<T>::vec, true>), grid, dim3(kThreads), 0, h->stream, a, A, x0, y0);
-    else hipLaunchKernelGGL((skinny_gemv_n_kernel<T, Full<T>::vec, false>), grid, dim3(kThreads), 0, h->stream, a, A, x0, y0);
+#define MXB_SKINNY_N(BETA_)                                                                                                          \
+    if (keeps_matrix(rows * cols * (int64_t)sizeof(T)))                                                                              \
+        hipLaunchKernelGGL((skinny_gemv_n_kernel<T, Full<T>::vec, BETA_, true>), grid, dim3(kThreads), 0, h->stream, a, A, x0, y0);  \
+    else                                                                                                                             \
+        hipLaunchKernelGGL((skinny_gemv_n_kernel<T, Full<T>::vec, BETA_, false>), grid, dim3(kThreads), 0, h->stream, a, A, x0, y0)
+    if (beta != T(0)) { MXB_SKINNY_N(true); } else { MXB_SKINNY_N(false); }
+#undef MXB_SKINNY_N
     return launch_status();
 }
 

@@ -54,7 +54,7 @@ __device__ __forceinline__ void st_matrix_from(T* p, typename VecOf<T, VEC>::typ
     }
 }
 
-template <typename T, int VEC>
+template <typename T, int VEC, bool KEEP>
 __global__ void __launch_bounds__(kThreads) ger_kernel(const GerArgs<T> p)
 {
     typedef typename VecOf<T, VEC>::type V;
@@ -75,7 +75,7 @@ __global__ void __launch_bounds__(kThreads) ger_kernel(const GerArgs<T> p)
         T ax[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            a[u] = ld_matrix<T, VEC>(acol + (i0 + u) * p.lda);
+            a[u] = ld_matrix_as<T, VEC, KEEP>(acol + (i0 + u) * p.lda);
             ax[u] = p.alpha * p.x[(i0 + u) * p.incx];
         }
         __builtin_amdgcn_sched_barrier(0);   // all loads of the batch are in flight before the first store
@@ -87,7 +87,7 @@ __global__ void __launch_bounds__(kThreads) ger_kernel(const GerArgs<T> p)
         }
     }
     for (; i0 < rhi; ++i0) {
-        V a = ld_matrix<T, VEC>(acol + i0 * p.lda);
+        V a = ld_matrix_as<T, VEC, KEEP>(acol + i0 * p.lda);
         const T ax = p.alpha * p.x[i0 * p.incx];
 #pragma unroll
         for (int k = 0; k < VEC; ++k) a[k] = fmad(ax, yj[k], a[k]);
@@ -174,7 +174,7 @@ struct SyrArgs {
 // in the tiles that straddle the diagonal every lane decides per row whether its vector lies
 // inside (vector access), outside (nothing is loaded or stored) or across the diagonal (loaded
 // whole, stored element by element).
-template <typename T, int VEC, bool UPPER, bool TWO>
+template <typename T, int VEC, bool UPPER, bool TWO, bool KEEP>
 __global__ void __launch_bounds__(kThreads) syr_kernel(const SyrArgs<T> p)
 {
     typedef typename VecOf<T, VEC>::type V;
@@ -215,7 +215,7 @@ __global__ void __launch_bounds__(kThreads) syr_kernel(const SyrArgs<T> p)
     if (inside) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            a[u] = ld_matrix<T, VEC>(acol + (r0 + u) * p.lda);
+            a[u] = ld_matrix_as<T, VEC, KEEP>(acol + (r0 + u) * p.lda);
             ax[u] = p.alpha * p.x[(r0 + u) * p.incx];
             ay[u] = TWO ? p.alpha * p.y[(r0 + u) * p.incy] : T(0);
         }
@@ -239,7 +239,7 @@ __global__ void __launch_bounds__(kThreads) syr_kernel(const SyrArgs<T> p)
         const int64_t i = imin(r0 + u, r1 - 1), d = i - c;
         const bool none = (UPPER ? d > VEC - 1 : d < 0) || r0 + u >= r1;
         a[u] = V(T(0));
-        if (!none) a[u] = ld_matrix<T, VEC>(acol + i * p.lda);
+        if (!none) a[u] = ld_matrix_as<T, VEC, KEEP>(acol + i * p.lda);
         ax[u] = p.alpha * p.x[i * p.incx];
         ay[u] = TWO ? p.alpha * p.y[i * p.incy] : T(0);
     }
@@ -307,7 +307,7 @@ __global__ void __launch_bounds__(kThreads) symv_small_kernel(int n, T alpha, co
             V a[RPW];
             T xv[VEC];
 #pragma unroll
-            for (int u = 0; u < RPW; ++u) a[u] = ld_matrix<T, VEC>(A + (int64_t)min(i0 + wave * RPW + u, n - 1) * lda + cl);
+            for (int u = 0; u < RPW; ++u) a[u] = ld_resident<T, VEC>(A + (int64_t)min(i0 + wave * RPW + u, n - 1) * lda + cl);
 #pragma unroll
             for (int k = 0; k < VEC; ++k) xv[k] = x[(int64_t)(cl + k) * incx];
 #pragma unroll
@@ -343,7 +343,7 @@ __global__ void __launch_bounds__(kThreads) symv_small_kernel(int n, T alpha, co
 #pragma unroll
             for (int u = 0; u < UB; ++u) {
                 const int r = min(r0 + u * NW * RL + rl, n - 1);
-                a[u] = ld_matrix<T, VEC>(A + (int64_t)r * lda + cl);
+                a[u] = ld_resident<T, VEC>(A + (int64_t)r * lda + cl);
                 xr[u] = x[(int64_t)r * incx];
             }
 #pragma unroll
@@ -460,8 +460,9 @@ int ger(mxb_handle_t h, int layout, int64_t m, int64_t n, T alpha, const T* x, i
     while ((int64_t)a.col_tiles * ceil_div(a.M, a.rows_per_block) > kMaxGerBlocks) a.rows_per_block *= 2;
     const int64_t blocks = (int64_t)a.col_tiles * ceil_div(a.M, a.rows_per_block);
     const dim3 grid((unsigned)blocks);
-    if (vec) hipLaunchKernelGGL((ger_kernel<T, FV>), grid, dim3(kThreads), 0, h->stream, a);
-    else hipLaunchKernelGGL((ger_kernel<T, 1>), grid, dim3(kThreads), 0, h->stream, a);
+    if (!vec) hipLaunchKernelGGL((ger_kernel<T, 1, false>), grid, dim3(kThreads), 0, h->stream, a);
+    else if (keeps_update(a.M * a.N * (int64_t)sizeof(T))) hipLaunchKernelGGL((ger_kernel<T, FV, true>), grid, dim3(kThreads), 0, h->stream, a);
+    else hipLaunchKernelGGL((ger_kernel<T, FV, false>), grid, dim3(kThreads), 0, h->stream, a);
     return launch_status();
 }
 
@@ -494,10 +495,12 @@ int syr(mxb_handle_t h, int layout, int uplo, int64_t n, T alpha, const T* x, in
     const int64_t blocks = (nt / 2) * (nt + 1) * (w / 8) + (nt % 2) * (nt / 2 + 1) * (w / 8);
     if (blocks > 0x7fffffff) return MXB_ERR_NOT_IMPLEMENTED;
     const dim3 grid((unsigned)blocks);
-#define MXB_SYR(VEC_)                                                                                        \
-    if (upper) hipLaunchKernelGGL((syr_kernel<T, VEC_, true, TWO>), grid, dim3(kThreads), 0, h->stream, a);  \
-    else hipLaunchKernelGGL((syr_kernel<T, VEC_, false, TWO>), grid, dim3(kThreads), 0, h->stream, a);
-    if (vec) { MXB_SYR(FV) } else { MXB_SYR(1) }
+#define MXB_SYR(VEC_, KEEP_)                                                                                        \
+    if (upper) hipLaunchKernelGGL((syr_kernel<T, VEC_, true, TWO, KEEP_>), grid, dim3(kThreads), 0, h->stream, a);  \
+    else hipLaunchKernelGGL((syr_kernel<T, VEC_, false, TWO, KEEP_>), grid, dim3(kThreads), 0, h->stream, a);
+    if (!vec) { MXB_SYR(1, true) }        // narrower than one vector
+    else if (keeps_matrix(n * (n + 1) / 2 * (int64_t)sizeof(T))) { MXB_SYR(FV, true) }
+    else { MXB_SYR(FV, false) }
 #undef MXB_SYR
     return launch_status();
 }

@@ -745,3 +745,15 @@ def test_ger_skinny(blas, ctx, dt):
             ger_case(blas, ctx, dt, O.ROW_MAJOR, 100000, 37, 3, 1, 1, 1, ints=True)
         finally:
             A_OFFSET[0] = 0
+
+
+def test_streaming_variants_just_past_the_cache_limits(blas, ctx):
+    """Kernels come in two variants, for a matrix that stays in the caches between calls and for one
+    that streams from HBM (192 MiB apart).  The other tests of this file are on the small side; these
+    shapes lie just past the limit: 1300000 x 40 floats (short rows: A*x, A^t*x, rank-1 update), a
+    7300^2 double triangle (syr), 7200^2 floats (A^t*x through the partial vectors)."""
+    for trans in (O.NO_TRANS, O.TRANS):
+        gemv_case(blas, ctx, np.float32, O.ROW_MAJOR, trans, 1300000, 40, 0.75, 0.5, 0, 1, 1)
+    ger_case(blas, ctx, np.float32, O.ROW_MAJOR, 1300000, 40, 0.3, 0, 1, 1)
+    syr_case(blas, ctx, np.float64, O.ROW_MAJOR, O.UPPER, 7300, 0.3, 0, 1, 1, False)
+    gemv_case(blas, ctx, np.float32, O.ROW_MAJOR, O.TRANS, 7200, 7200, 0.75, 0.5, 0, 1, 1)
