@@ -23,7 +23,9 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
 constexpr int kSlots = 8;                     // rows in flight per lane
-constexpr int64_t kSkinnyBlocksT = 1024;      // blocks (= partial vectors) of the transposed product
+constexpr int64_t kSkinnyBlocksT = 512;       // blocks (= partial vectors) of the transposed product: 256 to 512 measure alike, 128 and 1024 and
+                                              // more slower (524288 x 40: 22.0, 18.3, 18.3, 19.6, 22.1 us per call for 128 ... 2048; blocks of 16
+                                              // wavefronts: 25 to 43 us)
 
 template <typename T>
 struct SkinnyArgs {
@@ -265,8 +267,10 @@ __global__ void __launch_bounds__(kCombineGroups* kWave) skinny_combine_kernel(i
     const int tx = threadIdx.x & (kWave - 1), ty = threadIdx.x >> 6;
     const int j = (int)blockIdx.x * kWave + tx;
     T s = T(0);
-    if (j < N)
+    if (j < N) {
+#pragma unroll 8
         for (int64_t q = ty; q < nparts; q += kCombineGroups) s += partials[q * N + j];
+    }
     red[ty][tx] = s;
     __syncthreads();
     if (ty != 0 || j >= N) return;

@@ -15,7 +15,9 @@ enum SkinnyOp { SKINNY_GEMV_N, SKINNY_GEMV_T, SKINNY_GER };
 //                 161-166 us against the row-dot kernel's 167-172 on the same machine); 37 <= nv <= 47
 //                 unless the width is a multiple of 32 (x 170: 305 -> 248 us, x 188: 308 -> 254 us, but
 //                 x 160: 217 against 240 us; below, x 129 .. 140: 215-243 against 250-278 us);
-//         A^t*x   nv <= 17 (68 columns), from 500000 rows (it pays for a second kernel);
+//         A^t*x   nv <= 17 (68 columns), from 2049 rows (up to 2048 the single kernel for cache-sized matrices
+//                 takes them; per call 177147 x 40: 8.4 against 12.9 us, 65536 x 64: 7.0 against 9.3, x 16: 5.7
+//                 against 7.8; 19683 x 40 is the one loss, 6.8 against 6.5);
 //         x*y^t   nv <= 12, and up to 20 for whole vectors (x 64: 52 -> 70 %, x 72: 273 -> 236 us, x 80:
 //                 282 -> 249 us; x 96 ties; ragged rows lose);
 //   fp64  A*x     nv <= 8 from 100000 rows; from a million nv <= 31, and 32 for the odd width
@@ -23,7 +25,8 @@ enum SkinnyOp { SKINNY_GEMV_N, SKINNY_GEMV_T, SKINNY_GER };
 //                 row per wavefront, x 65 .. 96, loses: 230-270 against 314-325 us) (4194304 rows of
 //                 2 .. 16 doubles: the general kernels take 136-183 us whatever the width, these
 //                 21-101 us);
-//         A^t*x   nv <= 4 from 100000 rows, nv <= 20 from 500000;   x*y^t   nv <= 20.
+//         A^t*x   nv <= 8 from 2049 rows (177147 x 16: 10.4 against 14.2 us), nv <= 20 from 500000 (x 40 loses
+//                 below: 65536 rows 10.1 against 7.8 us);   x*y^t   nv <= 20.
 // At least one vector per row, and enough rows that the run is not launch-bound.
 template <typename T>
 inline bool skinny_takes(SkinnyOp op, int64_t rows, int64_t cols, const T* A, int64_t lda)
@@ -35,12 +38,12 @@ inline bool skinny_takes(SkinnyOp op, int64_t rows, int64_t cols, const T* A, in
     if (sizeof(T) == 8) {
         if (op == SKINNY_GER) return nv <= 20 && rows >= 100000;
         if (op == SKINNY_GEMV_N) return (nv <= 8 && rows >= 100000) || ((nv <= 31 || (nv == 32 && cols % 2 == 1)) && rows >= 1000000);
-        return (nv <= 4 && rows >= 100000) || (nv <= 20 && rows >= 500000);
+        return (nv <= 8 && rows > 2048) || (nv <= 20 && rows >= 500000);
     }
     if (op == SKINNY_GER) return (nv <= 12 || (nv <= 20 && cols % fv == 0)) && rows >= 100000;
     if (op == SKINNY_GEMV_N)
         return (nv <= 32 || (nv >= 37 && nv <= 47 && cols % 32 != 0) || (nv >= 48 && nv <= 64)) && rows >= 100000;
-    return nv <= 17 && rows >= 500000;
+    return nv <= 17 && rows > 2048;
 }
 
 // y = alpha*A*x + beta*y (A rows x cols, x has cols elements).  Pointers at logical element 0.
