@@ -226,7 +226,9 @@ __global__ void __launch_bounds__(WC == 1 ? kRowSmallThreads : WC * kWave) rowsm
     __shared__ T part[WC];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t row0 = WC == 1 ? ((int64_t)blockIdx.x * (kRowSmallThreads / kWave) + wave) * R : (int64_t)blockIdx.x;
+    // (the rows of a lower triangle grow towards the end: the last blocks first, so that the long rows start early)
+    const int64_t blk = MODE == MODE_LOWER ? (int64_t)gridDim.x - 1 - blockIdx.x : (int64_t)blockIdx.x;
+    const int64_t row0 = WC == 1 ? (blk * (kRowSmallThreads / kWave) + wave) * R : blk;
     if (row0 >= p.M) return;
     const T* arow[R];
 #pragma unroll

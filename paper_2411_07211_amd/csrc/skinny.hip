@@ -77,7 +77,7 @@ __device__ __forceinline__ LaneMap lane_map(int nv, int N, int vec)
 // rows in flight, the lanes past the row idle.  The SLOTS sums of a tile are folded over the
 // wavefront all at once and leave one row's sum in each of SLOTS lanes, which load the old y of
 // their row with the tile and store the new one: SLOTS adjacent elements of y per tile.
-template <typename T, int VEC, bool BETA, int SLOTS>
+template <typename T, int VEC, bool BETA, int SLOTS, bool KEEP>
 __global__ void __launch_bounds__(kThreads) skinny_gemv_n_onerow_kernel(const SkinnyArgs<T> p, const T* __restrict__ A,
                                                                         const T* __restrict__ x, T* __restrict__ y)
 {
@@ -95,12 +95,12 @@ __global__ void __launch_bounds__(kThreads) skinny_gemv_n_onerow_kernel(const Sk
         V a[SLOTS];
         if (tile0 + SLOTS <= p.M) {      // whole tile: no predicate, so that all loads issue back to back
 #pragma unroll
-            for (int u = 0; u < SLOTS; ++u) a[u] = ld_matrix<T, VEC>(A + (tile0 + u) * p.lda + m.c);
+            for (int u = 0; u < SLOTS; ++u) a[u] = ld_matrix_as<T, VEC, KEEP>(A + (tile0 + u) * p.lda + m.c);
         } else {
 #pragma unroll
             for (int u = 0; u < SLOTS; ++u) {
                 a[u] = V(T(0));
-                if (tile0 + u < p.M) a[u] = ld_matrix<T, VEC>(A + (tile0 + u) * p.lda + m.c);
+                if (tile0 + u < p.M) a[u] = ld_matrix_as<T, VEC, KEEP>(A + (tile0 + u) * p.lda + m.c);
             }
         }
         const int64_t i = tile0 + mine;
@@ -379,8 +379,13 @@ int skinny_gemv_n(mxb_handle_t h, int64_t rows, int64_t cols, T alpha, const T* 
         constexpr int SLOTS = 8;
         const int64_t blocks = ceil_div(ceil_div(rows, (int64_t)SLOTS), (int64_t)kWaves), cap = (int64_t)kCUs * 64;
         const dim3 g1((unsigned)(blocks < cap ? blocks : cap));
-        if (beta != T(0)) hipLaunchKernelGGL((skinny_gemv_n_onerow_kernel<T, Full<T>::vec, true, SLOTS>), g1, dim3(kThreads), 0, h->stream, a, A, x0, y0);
-        else hipLaunchKernelGGL((skinny_gemv_n_onerow_kernel<T, Full<T>::vec, false, SLOTS>), g1, dim3(kThreads), 0, h->stream, a, A, x0, y0);
+#define MXB_SKINNY_ONEROW(BETA_)                                                                                                              \
+    if (keeps_matrix(rows * cols * (int64_t)sizeof(T)))                                                                                       \
+        hipLaunchKernelGGL((skinny_gemv_n_onerow_kernel<T, Full<T>::vec, BETA_, SLOTS, true>), g1, dim3(kThreads), 0, h->stream, a, A, x0, y0);  \
+    else                                                                                                                                      \
+        hipLaunchKernelGGL((skinny_gemv_n_onerow_kernel<T, Full<T>::vec, BETA_, SLOTS, false>), g1, dim3(kThreads), 0, h->stream, a, A, x0, y0)
+        if (beta != T(0)) { MXB_SKINNY_ONEROW(true); } else { MXB_SKINNY_ONEROW(false); }
+#undef MXB_SKINNY_ONEROW
         return launch_status();
     }
     const dim3 grid((unsigned)tile_blocks(rows, a.nv, (int64_t)kCUs * 16));

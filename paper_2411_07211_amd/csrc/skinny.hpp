@@ -40,9 +40,12 @@ inline bool skinny_takes(SkinnyOp op, int64_t rows, int64_t cols, const T* A, in
         if (op == SKINNY_GEMV_N) return (nv <= 8 && rows >= 100000) || ((nv <= 31 || (nv == 32 && cols % 2 == 1)) && rows >= 1000000);
         return (nv <= 8 && rows > 2048) || (nv <= 20 && rows >= 500000);
     }
-    if (op == SKINNY_GER) return (nv <= 12 || (nv <= 20 && cols % fv == 0)) && rows >= 100000;
+    // rows from which these kernels win (per call, 65536 rows: x*y^t of 40 columns 5.6 against 9.0 us, A*x of
+    // 128 columns 6.9 against 14.5, of 64 columns 5.4 against 6.2; 8192 rows: 4.0 against 3.5, 5.1 against 3.9)
+    if (op == SKINNY_GER) return (nv <= 12 || (nv <= 20 && cols % fv == 0)) && rows >= 16384;
     if (op == SKINNY_GEMV_N)
-        return (nv <= 32 || (nv >= 37 && nv <= 47 && cols % 32 != 0) || (nv >= 48 && nv <= 64)) && rows >= 100000;
+        return (nv <= 32 || (nv >= 37 && nv <= 47 && cols % 32 != 0) || (nv >= 48 && nv <= 64)) &&
+               rows >= (nv >= 32 ? 16384 : (nv >= 16 ? 65536 : 100000));
     return nv <= 17 && rows > 2048;
 }
 
