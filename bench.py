@@ -470,28 +470,28 @@ TRAFFIC_JSON = os.path.join(ROOT, "profiles", "traffic.json")
 # library dispatches them at these sizes; a second kernel is the combine pass of the first.
 NS_, N1_ = 16384, 1 << 28
 TRI_ = NS_ * (NS_ + 1) // 2
-RED = lambda t, op: [f"reduce_vec_kernel<{t}, {op}, {t}>", f"reduce_final_kernel<{t}, {op}, {t}>"]
+RED = lambda t, op: [f"reduce_vec_kernel<{t}, {op}, {t}, false>", f"reduce_final_kernel<{t}, {op}, {t}>"]
 REDS = lambda t, op: [f"reduce_strided_kernel<{t}, {op}, {t}>", f"reduce_final_kernel<{t}, {op}, {t}>"]
 SWEEP = lambda t, v, up, kind: [f"trisweep_kernel<{t}, {v}, 2, 16, {up}, {kind}, false>", f"trisweep_combine_kernel<{t}, {up}, {kind}>"]
 CALL_KERNELS = {
-    "saxpy": ["axpy_vec_kernel<float>"], "daxpy": ["axpy_vec_kernel<double>"], "sscal": ["scal_vec_kernel<float>"],
+    "saxpy": ["axpy_vec_kernel<float, false>"], "daxpy": ["axpy_vec_kernel<double, false>"], "sscal": ["scal_vec_kernel<float, false>"],
     "sdot": RED("float", 0), "ddot": RED("double", 0), "sasum": RED("float", 1), "snrm2": RED("float", 2),
     "saxpy_strided": ["axpy_strided_kernel<float>"], "daxpy_strided": ["axpy_strided_kernel<double>"],
     "sscal_strided": ["scal_strided_kernel<float>"], "sdot_strided": REDS("float", 0), "ddot_strided": REDS("double", 0),
     "sasum_strided": REDS("float", 1), "snrm2_strided": REDS("float", 2),
     "sgemv_n_16384_b0": ["rowdot_kernel<float, 4, 64, 2, 4, 0, false>"],
-    "sgemv_t_16384_b0": ["colacc_kernel<float, 4, 4, 1>", "colacc_combine_kernel<float>"],
-    "sgemv_n_1048576x256_b0": ["skinny_gemv_n_onerow_kernel<float, 4, false, 8>"],
-    "sgemv_n_1048576x256_b0.5": ["skinny_gemv_n_onerow_kernel<float, 4, true, 8>"],
-    "sgemv_t_1048576x256_b0": ["colacc_kernel<float, 4, 1, 4>", "colacc_combine_kernel<float>"],
+    "sgemv_t_16384_b0": ["colacc_kernel<float, 4, 4, 1, false>", "colacc_combine_kernel<float>"],
+    "sgemv_n_1048576x256_b0": ["skinny_gemv_n_onerow_kernel<float, 4, false, 8, false>"],
+    "sgemv_n_1048576x256_b0.5": ["skinny_gemv_n_onerow_kernel<float, 4, true, 8, false>"],
+    "sgemv_t_1048576x256_b0": ["colacc_kernel<float, 4, 1, 4, false>", "colacc_combine_kernel<float>"],
     "sgemv_n_1024": ["rowsmall_kernel<float, 4, 1, 4, 1, 0, false>"],
     "dgemv_n_16384": ["rowdot_kernel<double, 2, 64, 2, 4, 0, false>"],
-    "dgemv_t_16384": ["colacc_kernel<double, 2, 4, 1>", "colacc_combine_kernel<double>"],
+    "dgemv_t_16384": ["colacc_kernel<double, 2, 4, 1, false>", "colacc_combine_kernel<double>"],
     "strmv_un_16384": ["gather_kernel<float>", "rowdot_kernel<float, 4, 64, 2, 4, 1, false>"],
     "strmv_uu_16384": ["gather_kernel<float>", "rowdot_kernel<float, 4, 64, 2, 4, 1, true>"],
     "strmv_ln_16384": ["gather_kernel<float>", "rowdot_kernel<float, 4, 64, 2, 4, 2, false>"],
     "strmv_lu_16384": ["gather_kernel<float>", "rowdot_kernel<float, 4, 64, 2, 4, 2, true>"],
-    "ssymv_l_16384": SWEEP("float", 4, "false", 0), "sger_16384": ["ger_kernel<float, 4>"],
+    "ssymv_l_16384": SWEEP("float", 4, "false", 0), "sger_16384": ["ger_kernel<float, 4, false>"],
     "strmv_ut_16384": SWEEP("float", 4, "true", 1), "strmv_lt_16384": SWEEP("float", 4, "false", 1),
     "ssymv_u_16384": SWEEP("float", 4, "true", 0), "dsymv_l_16384": SWEEP("double", 2, "false", 0),
     "strsv_ln_16384": ["trsv_chain_init_kernel", "trsv_chain_kernel<float, true, false, true>"],

@@ -819,7 +819,9 @@ __global__ void __launch_bounds__(CL* RL) colsum_small_kernel(const ColaccArgs<T
 // that a lane has one or two rounds of loads (per call in a replayed graph, 8 x 32 / 8 x 64 /
 // 4 x 128 / 8 x 128 lanes: 256^2 2.7 / 2.8 / 3.1 / 3.2 us, 512^2 3.3 / 2.9 / 3.2 / 3.4, 1024^2 4.4 /
 // 3.6 / 3.3 / 3.5, 1536^2 5.6 / 4.3 / 3.9 / 4.6, 2048^2 6.8 / 5.0 / 6.5 / 4.8; the general kernels:
-// 4.5, 6.1, 6.3, 6.6, 8.1).  From 2049 rows on the general kernels win (3000^2: 11.6 against 16 us).
+// 4.5, 6.1, 6.3, 6.6, 8.1).  From 2049 rows on the general kernels win (2500^2: 8.8 against 9.7 us at
+// best, 4096 x 2048: 8.9 against 9.9, 8192 x 512: 7.0 against 11.9; 4096 x 512 is the exception, 6.6
+// against 4.9).
 // 0: not taken.
 constexpr int64_t kSmallMaxRows = 2048;
 template <typename T>
