@@ -249,7 +249,13 @@ __device__ __forceinline__ void load_rows(const T* A, int64_t lda, int first, in
 }
 
 // Wavefronts per workgroup of the chained kernel: 4, but 2 in double precision when not
-// transposed, where LDS has to hold the turning buffer and the parked diagonal rows.
+// transposed, where LDS has to hold the turning buffer and the parked diagonal rows.  (The hand-over
+// between workgroups, from the last solution of one to the first of the next, takes 3.4 us, a step
+// inside a workgroup 0.6 us of solve and 0.9 us until the next solve begins, so fewer, larger
+// workgroups would be faster; but 8 wavefronts are two per SIMD unit, 256 registers each, and
+// the kernel then spills 260 to 620 of them.  Without the barrier, the solver handing its unknowns
+// on through LDS in four groups of 16 as they become final and the others polling for them, a
+// step inside a workgroup took 1.15 us instead of 0.9.)
 template <typename T, bool TRANS>
 constexpr int chain_waves() { return (sizeof(T) == 8 && !TRANS) ? 2 : 4; }
 
@@ -354,7 +360,9 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
     auto look = [&](int qq, T& xv) { return Handover<T>::get(p.solved + ((int64_t)qq * kWave + lane) * HW, xv); };
     auto wait_x = [&](int qq, T& xv, bool got) {
         for (int spins = 0; ok && __ballot(got) != ~0ull;) {
-            if (++spins > p.spin_limit || __hip_atomic_load(error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+            // (the error word every 64th round only: a round would otherwise be two trips to memory, one after the
+            // other; from the last solution of a workgroup to the first of the next: 4.3 -> 3.4 us)
+            if (++spins > p.spin_limit || (spins % 64 == 0 && __hip_atomic_load(error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
                 ok = false;
                 if (lane == 0) __hip_atomic_store(error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 break;
@@ -549,7 +557,12 @@ int trsv(mxb_handle_t h, int layout, int uplo, int trans, int diag, int64_t n, c
     constexpr int NW = sizeof(T) == 4 ? 8 : 4;        // 64 registers of triangle + 64 of prefetch per lane: 512 / 256 unknowns
     constexpr int64_t NB = NW * kWave;
     T* x0 = vec_base(x, n, incx);
-    if (n >= option(h, MXB_OPT_TRSV_CHAIN_MIN) && n < ((int64_t)1 << 24))      // 32-bit counts in the chained kernel; no such matrix fits the device anyway
+    // From where the chained kernel is faster than one launch per block (per call: single precision,
+    // not transposed, n = 128: 10.2 against 15.1 us, 256: 15.6 against 22.1, 384: 19.6 against 28.8;
+    // transposed 128: 9.1 against 8.4, 256 the same, 384: 17.1 against 21.6; double precision 256: 26.7
+    // against 22.3, 384: 32.6 against 38.7).
+    const int64_t chain_min = h->opt[MXB_OPT_TRSV_CHAIN_MIN] > 0 ? h->opt[MXB_OPT_TRSV_CHAIN_MIN] : ((sizeof(T) == 4 && no_trans) ? 65 : 257);
+    if (n >= chain_min && n < ((int64_t)1 << 24))      // 32-bit counts in the chained kernel; no such matrix fits the device anyway
         return trsv_chain<T>(h, op_lower, no_trans, unit, n, A, lda, x0, incx);
     h->device_status = nullptr;                      // nothing in the blocked path waits on the device
     const int64_t nblocks = ceil_div(n, NB);
