@@ -147,7 +147,8 @@ __global__ void __launch_bounds__(NW* kWave) trsv_diag_kernel(const TrsvArgs<T> 
 template <typename T, int NW, bool TRANS>
 void launch_trsv_diag(mxb_handle_t h, bool op_lower, bool unit, const TrsvArgs<T>& a)
 {
-    const dim3 grid(1), block(NW * kWave);
+    // only the wavefronts that own unknowns: the others would still fetch and turn their (empty) tiles
+    const dim3 grid(1), block((unsigned)(ceil_div((int64_t)a.nb, (int64_t)kWave) * kWave));
     if (op_lower) {
         if (unit) hipLaunchKernelGGL((trsv_diag_kernel<T, NW, true, TRANS, true>), grid, block, 0, h->stream, a);
         else hipLaunchKernelGGL((trsv_diag_kernel<T, NW, true, TRANS, false>), grid, block, 0, h->stream, a);
