@@ -439,7 +439,7 @@ constexpr int kFewThreads = 256;
 // of x and the matching vector of every row in flight, so x is read once whatever the number of
 // rows, and sums one partial result per row.  Block b writes its M sums to partials[b][0..M);
 // the pass that combines partial vectors adds them in block order.
-template <typename T, int VEC, int MR>
+template <typename T, int VEC, int MR, bool KEEP>
 __global__ void __launch_bounds__(kFewThreads) fewrows_kernel(int M, int64_t N, const T* __restrict__ A, int64_t lda,
                                                               const T* __restrict__ x, int64_t incx, T* __restrict__ partials)
 {
@@ -453,7 +453,7 @@ __global__ void __launch_bounds__(kFewThreads) fewrows_kernel(int M, int64_t N, 
     for (int i = 0; i < MR; ++i) acc[i] = T(0);
 
     auto load_x = [&](int64_t v) -> V {
-        if (incx == 1) return ld_matrix<T, VEC>(x + v * VEC);
+        if (incx == 1) return ld_matrix_as<T, VEC, KEEP>(x + v * VEC);
         V r;
 #pragma unroll
         for (int k = 0; k < VEC; ++k) r[k] = x[(v * VEC + k) * incx];
@@ -471,7 +471,7 @@ __global__ void __launch_bounds__(kFewThreads) fewrows_kernel(int M, int64_t N, 
 #pragma unroll
             for (int i = 0; i < MR; ++i)
                 if (i < M) {                                                         // wave-uniform
-                    a[u][i] = ld_matrix<T, VEC>(at);
+                    a[u][i] = ld_matrix_as<T, VEC, KEEP>(at);
                     int64_t step = lda;
                     asm volatile("" : "+s"(step));
                     at += step;
@@ -495,7 +495,7 @@ __global__ void __launch_bounds__(kFewThreads) fewrows_kernel(int M, int64_t N, 
 #pragma unroll
             for (int i = 0; i < MR; ++i)
                 if (i < M) {
-                    const V a = ld_matrix<T, VEC>(at);
+                    const V a = ld_matrix_as<T, VEC, KEEP>(at);
 #pragma unroll
                     for (int k = 0; k < VEC; ++k) acc[i] = fmad(a[k], xv[k], acc[i]);
                     int64_t step = lda;
@@ -536,7 +536,7 @@ __global__ void __launch_bounds__(kFewThreads) fewrows_kernel(int M, int64_t N, 
 // over the columns.  A lane keeps the matching vector of every row in flight for U vectors of y
 // (tiles of U runs of 256 vectors, one or a few tiles per block), x[i] in registers; no partial
 // results.
-template <typename T, int VEC, int MR, bool BETA>
+template <typename T, int VEC, int MR, bool BETA, bool KEEP>
 __global__ void __launch_bounds__(kFewThreads) fewrows_t_kernel(int M, int64_t N, const T* __restrict__ A, int64_t lda,
                                                                 const T* __restrict__ x, int64_t incx, T alpha, T beta,
                                                                 T* __restrict__ y, int64_t incy)
@@ -549,7 +549,7 @@ __global__ void __launch_bounds__(kFewThreads) fewrows_t_kernel(int M, int64_t N
     for (int i = 0; i < MR; ++i) xr[i] = i < M ? x[i * incx] : T(0);
 
     auto load_y = [&](int64_t v) -> V {
-        if (incy == 1) return ld_matrix<T, VEC>(y + v * VEC);
+        if (incy == 1) return ld_matrix_as<T, VEC, KEEP>(y + v * VEC);
         V r;
 #pragma unroll
         for (int k = 0; k < VEC; ++k) r[k] = y[(v * VEC + k) * incy];
@@ -574,7 +574,7 @@ __global__ void __launch_bounds__(kFewThreads) fewrows_t_kernel(int M, int64_t N
         for (int u = 0; u < U; ++u) {
 #pragma unroll
             for (int i = 0; i < MR; ++i)
-                if (i < M) a[u][i] = ld_matrix<T, VEC>(A + i * lda + (v0 + u * kFewThreads) * VEC);     // wave-uniform
+                if (i < M) a[u][i] = ld_matrix_as<T, VEC, KEEP>(A + i * lda + (v0 + u * kFewThreads) * VEC);     // wave-uniform
             if (BETA) yo[u] = load_y(v0 + u * kFewThreads);
         }
         __builtin_amdgcn_sched_barrier(0);   // every load of the tile is in flight before the first FMA
@@ -598,7 +598,7 @@ __global__ void __launch_bounds__(kFewThreads) fewrows_t_kernel(int M, int64_t N
 #pragma unroll
             for (int i = 0; i < MR; ++i)
                 if (i < M) {
-                    const V a = ld_matrix<T, VEC>(A + i * lda + v * VEC);
+                    const V a = ld_matrix_as<T, VEC, KEEP>(A + i * lda + v * VEC);
 #pragma unroll
                     for (int k = 0; k < VEC; ++k) acc[k] = fmad(a[k], xr[i], acc[k]);
                 }
@@ -953,9 +953,14 @@ int gemv_rows(mxb_handle_t h, bool no_trans, int64_t rows, int64_t cols, T alpha
         const int64_t grid = tiles < 1 ? 1 : (tiles < cap ? tiles : cap);
         T* partials = static_cast<T*>(take_workspace(h, (size_t)grid * (size_t)rows * sizeof(T)));
         if (!partials) return MXB_ERR_WORKSPACE;
+        const bool keep = keeps_matrix((rows + 1) * cols * (int64_t)sizeof(T));
 #define MXB_FEW(MR_)                                                                                                          \
-    hipLaunchKernelGGL((fewrows_kernel<T, FV, MR_>), dim3((unsigned)grid), dim3(kFewThreads), 0, h->stream, (int)rows, cols, A, lda, \
-                       x0, incx, partials)
+    if (keep)                                                                                                                 \
+        hipLaunchKernelGGL((fewrows_kernel<T, FV, MR_, true>), dim3((unsigned)grid), dim3(kFewThreads), 0, h->stream, (int)rows, cols, A, lda, \
+                           x0, incx, partials);                                                                               \
+    else                                                                                                                      \
+        hipLaunchKernelGGL((fewrows_kernel<T, FV, MR_, false>), dim3((unsigned)grid), dim3(kFewThreads), 0, h->stream, (int)rows, cols, A, lda, \
+                           x0, incx, partials)
         switch (mr) {
             case 1: MXB_FEW(1); break;
             case 2: MXB_FEW(2); break;
@@ -971,26 +976,33 @@ int gemv_rows(mxb_handle_t h, bool no_trans, int64_t rows, int64_t cols, T alpha
                            alpha, beta, y0, incy, (int64_t)0, (int64_t)0);
         return launch_status();
     }
-    if (!no_trans && batch == 1 && rows <= kFewStreamRows && rows * cols * (int64_t)sizeof(T) >= (rows <= 2 ? 1 : 2) * kFewStreamMinBytes) {
+    if (!no_trans && batch == 1 && cols >= kFewStreamMinCols &&
+        (rows <= kFewStreamRows || (rows <= 2 * kFewStreamRows && rows * cols * (int64_t)sizeof(T) <= kFewStreamManyMaxBytes))) {
         // The transposed product of a handful of very long rows: a stream over the columns.
         constexpr int FV = Full<T>::vec;
-        const int mr = rows <= 1 ? 1 : (rows <= 2 ? 2 : 4);
-        const int u = mr <= 2 ? 8 : 4;                                           // as in the kernel
+        const int mr = rows <= 1 ? 1 : (rows <= 2 ? 2 : (rows <= 4 ? 4 : (rows <= 8 ? 8 : 16)));
+        const int u = mr <= 2 ? 8 : (mr <= 4 ? 4 : (mr <= 8 ? 2 : 1));           // as in the kernel
         const int64_t tiles = cols / FV / ((int64_t)kFewThreads * u);
         const int64_t grid = tiles < 1 ? 1 : (tiles < kFewStreamBlocks ? tiles : kFewStreamBlocks);
-#define MXB_FEW_T(MR_)                                                                                                       \
-    if (beta != T(0))                                                                                                        \
-        hipLaunchKernelGGL((fewrows_t_kernel<T, FV, MR_, true>), dim3((unsigned)grid), dim3(kFewThreads), 0, h->stream, (int)rows, \
+#define MXB_FEW_T2(MR_, BETA_)                                                                                               \
+    if (keep)                                                                                                                \
+        hipLaunchKernelGGL((fewrows_t_kernel<T, FV, MR_, BETA_, true>), dim3((unsigned)grid), dim3(kFewThreads), 0, h->stream, (int)rows, \
                            cols, A, lda, x0, incx, alpha, beta, y0, incy);                                                   \
     else                                                                                                                     \
-        hipLaunchKernelGGL((fewrows_t_kernel<T, FV, MR_, false>), dim3((unsigned)grid), dim3(kFewThreads), 0, h->stream, (int)rows, \
+        hipLaunchKernelGGL((fewrows_t_kernel<T, FV, MR_, BETA_, false>), dim3((unsigned)grid), dim3(kFewThreads), 0, h->stream, (int)rows, \
                            cols, A, lda, x0, incx, alpha, beta, y0, incy)
+#define MXB_FEW_T(MR_)                                                                                                       \
+    if (beta != T(0)) { MXB_FEW_T2(MR_, true); } else { MXB_FEW_T2(MR_, false); }
+        const bool keep = keeps_matrix((rows + 1) * cols * (int64_t)sizeof(T));
         switch (mr) {
             case 1: MXB_FEW_T(1); break;
             case 2: MXB_FEW_T(2); break;
-            default: MXB_FEW_T(4); break;
+            case 4: MXB_FEW_T(4); break;
+            case 8: MXB_FEW_T(8); break;
+            default: MXB_FEW_T(16); break;
         }
 #undef MXB_FEW_T
+#undef MXB_FEW_T2
         return launch_status();
     }
     if (no_trans && batch == 1 && rows <= kWideMaxRows && cols >= kWideMinCols) {

@@ -25,11 +25,15 @@ constexpr int64_t kWideMaxRows = 4096, kWideMinCols = 32768, kWideMinChunk = 204
 // are a handful of dot products sharing x: at most kFewBlocks blocks (two per compute unit read
 // fastest, measured from 256 to 4096), each with one partial result per row.
 constexpr int64_t kFewRows = 16, kFewMaxRows = 32, kFewManyMinCols = (int64_t)1 << 21, kFewBlocks = 512;
-// The transposed product of one to kFewStreamRows rows is a read-and-write stream over the columns:
-// one tile per block, as in the level-1 kernels (the cap keeps a launch below 2^32 threads); from
-// kFewStreamMinBytes of matrix for one or two rows, twice that for more (measured; below, and for
-// more rows, the column-accumulate kernels are as fast or faster).
-constexpr int64_t kFewStreamRows = 4, kFewStreamBlocks = (int64_t)1 << 22, kFewStreamMinBytes = (int64_t)48 << 20;
+// The transposed product of up to kFewStreamRows rows of at least kFewStreamMinCols columns is a
+// read-and-write stream over the columns: one tile per block, as in the level-1 kernels (the cap
+// keeps a launch below 2^32 threads); up to twice as many rows while the matrix is small.  The
+// column-accumulate kernel keeps 16 rows in flight and falls back to one load at a time when there
+// are fewer (per call, repeated: 1 x 4194304 69 -> 5.9 us, 2 x 4194304 81 -> 11.6, 4 x 1048576 20.1 ->
+// 4.0, 8 x 1048576 23.2 -> 8.1, 8 x 16777216 122 -> 112, 16 x 262144 8.0 -> 4.0, but 16 x 1048576 14.9
+// against 17.1; at 65536 columns the column-accumulate kernels are 0.2 us faster).
+constexpr int64_t kFewStreamRows = 8, kFewStreamBlocks = (int64_t)1 << 22, kFewStreamMinCols = (int64_t)1 << 17,
+                  kFewStreamManyMaxBytes = (int64_t)32 << 20;
 
 inline ColaccPlan colacc_plan(int64_t rows, int64_t cols, int elem_size, int vec, int64_t target_blocks,
                               int64_t narrow_blocks, int64_t min_rows)

@@ -122,10 +122,15 @@ def test_gemv_shapes(blas, ctx, dt, trans):
         for beta in (0.0, -0.5):
             gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, 1.5, beta, pad, incx, incy)
     gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, 7, 90001, 2, 1, 0, 1, 1, ints=True)
-    # transposed, one to four rows of tens of megabytes: a stream over the columns (whole tiles and
-    # a ragged end, y strided and reversed, a pitch larger than the width)
+    # transposed, up to eight rows of at least 131072 columns, up to sixteen while the matrix is small:
+    # a stream over the columns (every row count the kernel is built for and the ones between, whole
+    # tiles and a ragged end, y strided and reversed, a pitch larger than the width, and the widths just
+    # below and at the limit)
     if trans == O.TRANS:
-        for (m, n, pad, incx, incy) in [(1, 13000003, 0, 1, 1), (2, 7000001, 5, -1, 1), (3, 9000002, 0, 2, 2), (4, 7000003, 1, 1, -1)]:
+        for (m, n, pad, incx, incy) in [(1, 13000003, 0, 1, 1), (2, 7000001, 5, -1, 1), (3, 9000002, 0, 2, 2), (4, 7000003, 1, 1, -1),
+                                        (1, 131072, 0, 1, 1), (2, 131071, 0, 1, 1), (5, 131075, 3, 1, 1), (6, 200001, 0, -1, 2),
+                                        (7, 1000003, 1, 1, 1), (8, 3000001, 0, 2, -1), (9, 131072, 0, 1, 1), (12, 400003, 5, 1, 3),
+                                        (16, 131073, 0, -2, 1), (16, 524288, 0, 1, 1), (16, 524289, 0, 1, 1)]:
             for beta in (0.0, -0.5):
                 gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, 1.5, beta, pad, incx, incy)
         gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, 4, 7000001, 2, 1, 0, 1, 1, ints=True)
