@@ -355,11 +355,19 @@ inline int64_t tile_blocks(int64_t rows, int nv, int64_t cap)
     return b < cap ? b : cap;
 }
 
-#define MXB_SKINNY_DISPATCH(KERNEL, GRID, ...)                                                                                        \
-    if (keeps_matrix(rows * cols * (int64_t)sizeof(T)))                                                                               \
-        hipLaunchKernelGGL((KERNEL<T, Full<T>::vec, true>), dim3((unsigned)(GRID)), dim3(kThreads), 0, h->stream, a, __VA_ARGS__);    \
-    else                                                                                                                              \
-        hipLaunchKernelGGL((KERNEL<T, Full<T>::vec, false>), dim3((unsigned)(GRID)), dim3(kThreads), 0, h->stream, a, __VA_ARGS__)
+// Rows narrower than one 16-byte vector (1 to 3 floats, 1 double) take the same kernels with
+// one element per lane: 64, 32 or 21 rows side by side per wavefront load.
+#define MXB_SKINNY_DISPATCH_VEC(KERNEL, VEC_, GRID, ...)                                                                         \
+    if (keeps_matrix(rows * cols * (int64_t)sizeof(T)))                                                                          \
+        hipLaunchKernelGGL((KERNEL<T, VEC_, true>), dim3((unsigned)(GRID)), dim3(kThreads), 0, h->stream, a, __VA_ARGS__);       \
+    else                                                                                                                         \
+        hipLaunchKernelGGL((KERNEL<T, VEC_, false>), dim3((unsigned)(GRID)), dim3(kThreads), 0, h->stream, a, __VA_ARGS__)
+#define MXB_SKINNY_DISPATCH(KERNEL, GRID, ...)                                              \
+    if (cols < Full<T>::vec) { MXB_SKINNY_DISPATCH_VEC(KERNEL, 1, GRID, __VA_ARGS__); }     \
+    else { MXB_SKINNY_DISPATCH_VEC(KERNEL, Full<T>::vec, GRID, __VA_ARGS__); }
+
+template <typename T>
+inline int vec_for(int64_t cols) { return cols < Full<T>::vec ? 1 : Full<T>::vec; }
 
 }  // namespace
 
@@ -372,7 +380,7 @@ template <typename T>
 int skinny_gemv_n(mxb_handle_t h, int64_t rows, int64_t cols, T alpha, const T* A, int64_t lda, const T* x0, int64_t incx, T beta,
                   T* y0, int64_t incy)
 {
-    const SkinnyArgs<T> a = make_args<T>(rows, cols, Full<T>::vec, lda, incx, incy, alpha, beta);
+    const SkinnyArgs<T> a = make_args<T>(rows, cols, vec_for<T>(cols), lda, incx, incy, alpha, beta);
     if (a.nv > kWave / 2) {
         // one tile of 8 rows per wavefront, or two: many short-lived blocks read this flat stream
         // fastest (1048576 x 256: 2 to 16 blocks per compute unit 166-170 us, 64 and more 160-164)
@@ -389,12 +397,16 @@ int skinny_gemv_n(mxb_handle_t h, int64_t rows, int64_t cols, T alpha, const T* 
         return launch_status();
     }
     const dim3 grid((unsigned)tile_blocks(rows, a.nv, (int64_t)kCUs * 16));
-#define MXB_SKINNY_N(BETA_)                                                                                                          \
-    if (keeps_matrix(rows * cols * (int64_t)sizeof(T)))                                                                              \
-        hipLaunchKernelGGL((skinny_gemv_n_kernel<T, Full<T>::vec, BETA_, true>), grid, dim3(kThreads), 0, h->stream, a, A, x0, y0);  \
-    else                                                                                                                             \
-        hipLaunchKernelGGL((skinny_gemv_n_kernel<T, Full<T>::vec, BETA_, false>), grid, dim3(kThreads), 0, h->stream, a, A, x0, y0)
-    if (beta != T(0)) { MXB_SKINNY_N(true); } else { MXB_SKINNY_N(false); }
+#define MXB_SKINNY_N(VEC_, BETA_)                                                                                       \
+    if (keeps_matrix(rows * cols * (int64_t)sizeof(T)))                                                                     \
+        hipLaunchKernelGGL((skinny_gemv_n_kernel<T, VEC_, BETA_, true>), grid, dim3(kThreads), 0, h->stream, a, A, x0, y0); \
+    else                                                                                                                    \
+        hipLaunchKernelGGL((skinny_gemv_n_kernel<T, VEC_, BETA_, false>), grid, dim3(kThreads), 0, h->stream, a, A, x0, y0)
+    if (cols < Full<T>::vec) {
+        if (beta != T(0)) { MXB_SKINNY_N(1, true); } else { MXB_SKINNY_N(1, false); }
+    } else {
+        if (beta != T(0)) { MXB_SKINNY_N(Full<T>::vec, true); } else { MXB_SKINNY_N(Full<T>::vec, false); }
+    }
 #undef MXB_SKINNY_N
     return launch_status();
 }
@@ -403,7 +415,7 @@ template <typename T>
 int skinny_gemv_t(mxb_handle_t h, int64_t rows, int64_t cols, T alpha, const T* A, int64_t lda, const T* x0, int64_t incx, T beta,
                   T* y0, int64_t incy)
 {
-    const SkinnyArgs<T> a = make_args<T>(rows, cols, Full<T>::vec, lda, incy, incx, alpha, beta);
+    const SkinnyArgs<T> a = make_args<T>(rows, cols, vec_for<T>(cols), lda, incy, incx, alpha, beta);
     const int64_t blocks = tile_blocks(rows, a.nv, kSkinnyBlocksT);
     T* partials = static_cast<T*>(take_workspace(h, (size_t)blocks * (size_t)cols * sizeof(T)));
     if (!partials) return MXB_ERR_WORKSPACE;
@@ -419,7 +431,7 @@ template <typename T>
 int skinny_ger(mxb_handle_t h, int64_t rows, int64_t cols, T alpha, const T* x0, int64_t incx, const T* y0, int64_t incy, T* A,
                int64_t lda)
 {
-    const SkinnyArgs<T> a = make_args<T>(rows, cols, Full<T>::vec, lda, incy, incx, alpha, T(0));
+    const SkinnyArgs<T> a = make_args<T>(rows, cols, vec_for<T>(cols), lda, incy, incx, alpha, T(0));
     MXB_SKINNY_DISPATCH(skinny_ger_kernel, tile_blocks(rows, a.nv, (int64_t)kCUs * 16), A, x0, y0);
     return launch_status();
 }

@@ -27,13 +27,16 @@ enum SkinnyOp { SKINNY_GEMV_N, SKINNY_GEMV_T, SKINNY_GER };
 //                 21-101 us);
 //         A^t*x   nv <= 8 from 2049 rows (177147 x 16: 10.4 against 14.2 us), nv <= 20 from 500000 (x 40 loses
 //                 below: 65536 rows 10.1 against 7.8 us);   x*y^t   nv <= 20.
-// At least one vector per row, and enough rows that the run is not launch-bound.
+// Enough rows that the run is not launch-bound.
 template <typename T>
 inline bool skinny_takes(SkinnyOp op, int64_t rows, int64_t cols, const T* A, int64_t lda)
 {
     const int64_t fv = 16 / (int64_t)sizeof(T);
     (void)A; (void)lda;                       // any base and pitch: matrix accesses need element alignment only
-    if (cols < fv) return false;
+    // rows narrower than one vector (1 to 3 floats, 1 double): the same kernels with one element per lane.  The
+    // general kernels give such a row a lane (per call: 8388608 x 1 A*x 186 -> 20 us, A^t*x 211 -> 20, x*y^t
+    // 535 -> 20; x 3: 186 -> 36, 212 -> 26, 536 -> 41; 65536 x 1: 4.5 -> 4.2, 6.9 against 8.8, 7.8 -> 4.1)
+    if (cols < fv) return rows >= (op == SKINNY_GER ? 16384 : (op == SKINNY_GEMV_N ? 65536 : 200000));
     const int64_t nv = (cols + fv - 1) / fv;  // a ragged last vector is moved back to end at the last column
     if (sizeof(T) == 8) {
         if (op == SKINNY_GER) return nv <= 20 && rows >= 100000;

@@ -762,3 +762,36 @@ def test_streaming_variants_just_past_the_cache_limits(blas, ctx):
     ger_case(blas, ctx, np.float32, O.ROW_MAJOR, 1300000, 40, 0.3, 0, 1, 1)
     syr_case(blas, ctx, np.float64, O.ROW_MAJOR, O.UPPER, 7300, 0.3, 0, 1, 1, False)
     gemv_case(blas, ctx, np.float32, O.ROW_MAJOR, O.TRANS, 7200, 7200, 0.75, 0.5, 0, 1, 1)
+
+
+@pytest.mark.parametrize("dt", DT)
+def test_rows_narrower_than_one_vector(blas, ctx, dt):
+    """Matrices of 1 to 3 columns (1 in double precision) with many rows take the side-by-side kernels
+    with one element per lane: A*x from 65536 rows, A^t*x from 200000, x*y^t from 16384; whole and
+    ragged tiles, a pitch larger than the width, increments, a displaced base, exact integers, and the
+    sizes just below the limits, which stay with the general kernels."""
+    widths = (1, 2, 3) if dt == np.float32 else (1,)
+    for n in widths:
+        for m in (65535, 65536, 200001, 262144 + 7):
+            for pad in (0, 1, 5):
+                gemv_case(blas, ctx, dt, O.ROW_MAJOR, O.NO_TRANS, m, n, 1.5, 0.5, pad, 1, 1)
+        for m in (199999, 200000, 300007):
+            for pad in (0, 2):
+                gemv_case(blas, ctx, dt, O.ROW_MAJOR, O.TRANS, m, n, 1.5, 0.5, pad, 1, 1)
+        for m in (16383, 16384, 70001):
+            for pad in (0, 3):
+                ger_case(blas, ctx, dt, O.ROW_MAJOR, m, n, 0.3, pad, 1, 1)
+        for trans, m in ((O.NO_TRANS, 100003), (O.TRANS, 250000)):
+            gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, 1.5, 0.0, 0, 2, -3)
+            gemv_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, 3, -2, 1, -1, 1, ints=True)
+            gemv_case(blas, ctx, dt, O.COL_MAJOR, trans, n, m, 1.5, 0.5, 0, 1, 1)     # the same bytes seen column-major
+        ger_case(blas, ctx, dt, O.ROW_MAJOR, 50001, n, -1.5, 1, 2, -3)
+        ger_case(blas, ctx, dt, O.ROW_MAJOR, 40000, n, 3, 0, 1, 1, ints=True)
+        ger_case(blas, ctx, dt, O.COL_MAJOR, n, 40000, 0.3, 0, 1, 1)
+    A_OFFSET[0] = 1
+    try:
+        gemv_case(blas, ctx, dt, O.ROW_MAJOR, O.NO_TRANS, 100000, widths[-1], 1.5, 0.5, 1, 1, 1)
+        gemv_case(blas, ctx, dt, O.ROW_MAJOR, O.TRANS, 250001, widths[-1], 1.5, 0.5, 1, 1, 1)
+        ger_case(blas, ctx, dt, O.ROW_MAJOR, 30000, widths[-1], 0.3, 1, 1, 1)
+    finally:
+        A_OFFSET[0] = 0
