@@ -20,13 +20,13 @@ enum SkinnyOp { SKINNY_GEMV_N, SKINNY_GEMV_T, SKINNY_GER };
 //                 against 7.8; 19683 x 40 is the one loss, 6.8 against 6.5);
 //         x*y^t   nv <= 12, and up to 20 for whole vectors (x 64: 52 -> 70 %, x 72: 273 -> 236 us, x 80:
 //                 282 -> 249 us; x 96 ties; ragged rows lose);
-//   fp64  A*x     nv <= 8 from 100000 rows; from a million nv <= 31, and 32 for the odd width
+//   fp64  A*x     nv <= 8 from 65536 rows; from a million nv <= 31, and 32 for the odd width
 //                 (2097152 x 42: 167 -> 126 us, x 50: 205 -> 155 us, x 63: 258 -> 182 us; x 64 ties; one
 //                 row per wavefront, x 65 .. 96, loses: 230-270 against 314-325 us) (4194304 rows of
 //                 2 .. 16 doubles: the general kernels take 136-183 us whatever the width, these
 //                 21-101 us);
 //         A^t*x   nv <= 8 from 2049 rows (177147 x 16: 10.4 against 14.2 us), nv <= 20 from 500000 (x 40 loses
-//                 below: 65536 rows 10.1 against 7.8 us);   x*y^t   nv <= 20.
+//                 below: 65536 rows 10.1 against 7.8 us);   x*y^t   nv <= 20, from 16384 rows.
 // Enough rows that the run is not launch-bound.
 template <typename T>
 inline bool skinny_takes(SkinnyOp op, int64_t rows, int64_t cols, const T* A, int64_t lda)
@@ -39,8 +39,9 @@ inline bool skinny_takes(SkinnyOp op, int64_t rows, int64_t cols, const T* A, in
     if (cols < fv) return rows >= (op == SKINNY_GER ? 16384 : (op == SKINNY_GEMV_N ? 65536 : 200000));
     const int64_t nv = (cols + fv - 1) / fv;  // a ragged last vector is moved back to end at the last column
     if (sizeof(T) == 8) {
-        if (op == SKINNY_GER) return nv <= 20 && rows >= 100000;
-        if (op == SKINNY_GEMV_N) return (nv <= 8 && rows >= 100000) || ((nv <= 31 || (nv == 32 && cols % 2 == 1)) && rows >= 1000000);
+        // (per call, 65536 rows: x*y^t of 2 / 16 / 40 doubles 9.2 / 10.1 / 11.2 -> 4.5 / 5.5 / 8.0 us, A*x of 2 / 16: 5.1 / 5.9 -> 4.4 / 5.2)
+        if (op == SKINNY_GER) return nv <= 20 && rows >= 16384;
+        if (op == SKINNY_GEMV_N) return (nv <= 8 && rows >= 65536) || ((nv <= 31 || (nv == 32 && cols % 2 == 1)) && rows >= 1000000);
         return (nv <= 8 && rows > 2048) || (nv <= 20 && rows >= 500000);
     }
     // rows from which these kernels win (per call, 65536 rows: x*y^t of 40 columns 5.6 against 9.0 us, A*x of

@@ -705,10 +705,10 @@ def test_gemv_skinny(blas, ctx):
 
 
 def test_gemv_skinny_double(blas, ctx):
-    """The same kernels in double precision: up to 16 (8 transposed) columns from 100000 rows, up to 46
+    """The same kernels in double precision: up to 16 columns from 65536 rows (transposed from 2049), up to 46
     (40) columns from a million (half a million) rows; whole and ragged widths, pitches, increments."""
     dt = np.float64
-    for (m, n) in [(100000, 2), (100001, 3), (120000, 8), (100000, 16)]:
+    for (m, n) in [(100000, 2), (100001, 3), (120000, 8), (100000, 16), (65535, 4), (65536, 2), (65537, 16), (70000, 5)]:
         for pad in (0, 1):
             gemv_case(blas, ctx, dt, O.ROW_MAJOR, O.NO_TRANS, m, n, 1.5, 0.5, pad, 1, 1)
     for (m, n) in [(100000, 2), (100001, 5), (120000, 8)]:
@@ -733,7 +733,7 @@ def test_gemv_skinny_double(blas, ctx):
 
 @pytest.mark.parametrize("dt", DT)
 def test_ger_skinny(blas, ctx, dt):
-    for (m, n) in [(100000, 40), (131072, 16), (100001, 24), (150000, 4), (100000, 8)] + (
+    for (m, n) in [(100000, 40), (131072, 16), (100001, 24), (150000, 4), (100000, 8), (16383, 4), (16384, 8), (20001, 40), (30000, 6)] + (
             [(120000, 48), (100000, 56), (100000, 64), (100000, 60), (100000, 68), (100001, 72), (100000, 80), (100000, 84)] if dt == np.float32 else []):
         for pad in (0, 4):
             ger_case(blas, ctx, dt, O.ROW_MAJOR, m, n, 0.3, pad, 1, 1)
