@@ -336,6 +336,7 @@ def sweep(B, ctx, torch):
     nmax = 1 << 28
     x = torch.rand(nmax, dtype=f32, device=dev); y = torch.rand(nmax, dtype=f32, device=dev)
     r = torch.zeros(1, dtype=f32, device=dev)
+    ri = torch.zeros(1, dtype=torch.int64, device=dev)
     for e in range(10, 29, 2):
         n = 1 << e
         for n_ in (n, n - 3 if e < 28 else n):
@@ -345,6 +346,8 @@ def sweep(B, ctx, torch):
             rec("sdot", t, 8 * n_, lambda: B.mxb_sdot(h, n_, x, 1, y, 1, r))
             rec("sasum", t, 4 * n_, lambda: B.mxb_sasum(h, n_, x, 1, r))
             rec("snrm2", t, 4 * n_, lambda: B.mxb_snrm2(h, n_, x, 1, r))
+            rec("isamax", t, 4 * n_, lambda: B.mxb_isamax(h, n_, x, 1, ri))
+            rec("scopy", t, 8 * n_, lambda: B.mxb_scopy(h, n_, x, 1, y, 1))
     NS = 16384
     A = x                       # 2^28 floats hold a 16384 x 16384 matrix
     xv = torch.rand(1 << 22, dtype=f32, device=dev); yv = torch.rand(1 << 22, dtype=f32, device=dev)
@@ -442,7 +445,8 @@ def sweep(B, ctx, torch):
           "fp32 / fp64; trmv and symv variants: u/l = upper / lower, n/t = not transposed / transposed, a trailing u = unit diagonal;\n"
           "(inc 2,3): the same call with incx = 2, incy = 3 (trmv: incx = 3); N = 40 shapes are the skinny matrices of Sec. 6.2.2 (M\n"
           "powers of 2 and 3); sgemv_n_b / sgemv_t_b are strided batches of square matrices in one call; sgemv_n_w / sgemv_t_w are a few\n"
-          "rows of millions of columns (the long vector counts in the bytes); strsv: unit diagonal over small off-diagonal elements.\n")
+          "rows of millions of columns (the long vector counts in the bytes); strsv: unit diagonal over small off-diagonal elements;\n"
+          "isamax writes an index; scopy moves 2 n elements.\n")
     print("## Geometric means per bucket\n")
     print("| routine | bucket | cases | geometric mean GB/s, one call | in a replayed graph |")
     print("|---|---|---|---|---|")
