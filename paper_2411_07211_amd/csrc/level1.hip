@@ -514,7 +514,7 @@ __device__ __forceinline__ Cand block_best(Cand c, Cand* slots)
 
 template <typename T>
 __global__ void __launch_bounds__(kThreads) iamax_kernel(int64_t n, int64_t nfull, const T* __restrict__ x, int64_t incx,
-                                                         Cand* __restrict__ partials)
+                                                         Cand* __restrict__ partials, int64_t* __restrict__ result)
 {
     constexpr int U = kStridedUnroll;
     __shared__ Cand slots[kThreads];
@@ -531,7 +531,14 @@ __global__ void __launch_bounds__(kThreads) iamax_kernel(int64_t n, int64_t nful
     if (blockIdx.x == gridDim.x - 1)
         for (int64_t i = nfull * (kThreads * U) + threadIdx.x; i < n; i += kThreads) best = better(best, cand_of(x[i * incx], i));
     const Cand b = block_best(best, slots);
-    if (threadIdx.x == 0) partials[blockIdx.x] = b;
+    if (threadIdx.x == 0) {
+        if (result) {                      // the only block: no second pass
+            const T x0 = x[0];
+            *result = (x0 != x0) ? 0 : b.i;
+        } else {
+            partials[blockIdx.x] = b;
+        }
+    }
 }
 
 // The same on contiguous data: 128-bit loads at element alignment, whole tiles without predicates,
@@ -539,7 +546,7 @@ __global__ void __launch_bounds__(kThreads) iamax_kernel(int64_t n, int64_t nful
 // block (one element per lane and load moves 32 MiB at 1.6 TB/s).
 template <typename T, bool KEEP>
 __global__ void __launch_bounds__(kThreads) iamax_vec_kernel(int64_t n, int64_t nvec, int64_t nfull, const T* __restrict__ x,
-                                                             Cand* __restrict__ partials)
+                                                             Cand* __restrict__ partials, int64_t* __restrict__ result)
 {
     constexpr int VEC = Full<T>::vec;
     constexpr int U = 2 * kUnroll;
@@ -587,7 +594,14 @@ __global__ void __launch_bounds__(kThreads) iamax_vec_kernel(int64_t n, int64_t 
 #pragma unroll
         for (int k = 0; k < VEC; ++k) best = better(best, Cand{(double)bv[c][k], bi[c][k]});
     const Cand b = block_best(best, slots);
-    if (threadIdx.x == 0) partials[blockIdx.x] = b;
+    if (threadIdx.x == 0) {
+        if (result) {                      // the only block: no second pass
+            const T x0 = x[0];
+            *result = (x0 != x0) ? 0 : b.i;
+        } else {
+            partials[blockIdx.x] = b;
+        }
+    }
 }
 
 template <typename T>
@@ -626,16 +640,16 @@ int iamax(mxb_handle_t h, int64_t n, const T* x, int64_t incx, int64_t* result)
         const int64_t nvec = n / VEC, nfull = nvec / (kThreads * 2 * kUnroll);
         grid = nfull <= kSingleBlockTiles ? 1 : (nfull < 2 * max_blocks ? nfull : 2 * max_blocks);
         if (keeps_vectors(n * (int64_t)sizeof(T)))
-            hipLaunchKernelGGL((iamax_vec_kernel<T, true>), dim3((unsigned)grid), dim3(kThreads), 0, h->stream, n, nvec, nfull, x, partials);
+            hipLaunchKernelGGL((iamax_vec_kernel<T, true>), dim3((unsigned)grid), dim3(kThreads), 0, h->stream, n, nvec, nfull, x, partials, grid == 1 ? result : nullptr);
         else
-            hipLaunchKernelGGL((iamax_vec_kernel<T, false>), dim3((unsigned)grid), dim3(kThreads), 0, h->stream, n, nvec, nfull, x, partials);
+            hipLaunchKernelGGL((iamax_vec_kernel<T, false>), dim3((unsigned)grid), dim3(kThreads), 0, h->stream, n, nvec, nfull, x, partials, grid == 1 ? result : nullptr);
     } else {
         const int64_t nfull = n / (kThreads * kStridedUnroll);
         grid = nfull <= kSingleBlockTiles ? 1 : (nfull < max_blocks ? nfull : max_blocks);
-        hipLaunchKernelGGL(iamax_kernel<T>, dim3((unsigned)grid), dim3(kThreads), 0, h->stream, n, nfull, x, incx, partials);
+        hipLaunchKernelGGL(iamax_kernel<T>, dim3((unsigned)grid), dim3(kThreads), 0, h->stream, n, nfull, x, incx, partials, grid == 1 ? result : nullptr);
     }
     int st = launch_status();
-    if (st != MXB_OK) return st;
+    if (st != MXB_OK || grid == 1) return st;      // a single block has written the result itself
     hipLaunchKernelGGL(iamax_final_kernel<T>, dim3(1), dim3(kThreads), 0, h->stream, (int)grid, partials, x, result);
     return launch_status();
 }
