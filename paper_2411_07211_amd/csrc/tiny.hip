@@ -202,7 +202,12 @@ int tiny_gemv_n(mxb_handle_t h, int64_t rows, int64_t cols, T alpha, const T* A,
 #define MXB_TINY_N(LPR_)                                                                                   \
     if (beta != T(0)) hipLaunchKernelGGL((tiny_gemv_n_kernel<T, VEC, LPR_, true>), g, blk, 0, h->stream, a); \
     else hipLaunchKernelGGL((tiny_gemv_n_kernel<T, VEC, LPR_, false>), g, blk, 0, h->stream, a)
-    if (lpr == 4) { MXB_TINY_N(4); }
+    if (cols < VEC) {
+        // rows narrower than one vector: one element per lane, a quad of lanes per row
+        if (beta != T(0)) hipLaunchKernelGGL((tiny_gemv_n_kernel<T, 1, 4, true>), g, blk, 0, h->stream, a);
+        else hipLaunchKernelGGL((tiny_gemv_n_kernel<T, 1, 4, false>), g, blk, 0, h->stream, a);
+    }
+    else if (lpr == 4) { MXB_TINY_N(4); }
     else if (lpr == 8) { MXB_TINY_N(8); }
     else { MXB_TINY_N(16); }
 #undef MXB_TINY_N
@@ -224,7 +229,11 @@ int tiny_gemv_t(mxb_handle_t h, int64_t rows, int64_t cols, T alpha, const T* A,
 #define MXB_TINY_T(LPR_)                                                                                                      \
     if (beta != T(0)) hipLaunchKernelGGL((tiny_gemv_t_kernel<T, VEC, LPR_, true>), g, blk, 0, h->stream, a, (uint32_t)batch); \
     else hipLaunchKernelGGL((tiny_gemv_t_kernel<T, VEC, LPR_, false>), g, blk, 0, h->stream, a, (uint32_t)batch)
-    if (lpr == 4) { MXB_TINY_T(4); }
+    if (cols < VEC) {
+        if (beta != T(0)) hipLaunchKernelGGL((tiny_gemv_t_kernel<T, 1, 4, true>), g, blk, 0, h->stream, a, (uint32_t)batch);
+        else hipLaunchKernelGGL((tiny_gemv_t_kernel<T, 1, 4, false>), g, blk, 0, h->stream, a, (uint32_t)batch);
+    }
+    else if (lpr == 4) { MXB_TINY_T(4); }
     else if (lpr == 8) { MXB_TINY_T(8); }
     else { MXB_TINY_T(16); }
 #undef MXB_TINY_T

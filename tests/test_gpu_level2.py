@@ -260,6 +260,18 @@ def test_gemv_batched(blas, ctx, dt, trans):
         gemv_batched_case(blas, ctx, dt, layout, trans, 96, 200, 11, 3, -2, 2, 1, 1, ints=True)
         gemv_batched_case(blas, ctx, dt, layout, trans, 96, 200, 4, 0, 0.5, 0, 1, 2)          # alpha == 0: A, x never read
         gemv_batched_case(blas, ctx, dt, layout, trans, 96, 200, 4, 0, 0, 0, 1, 1)
+    # rows narrower than one vector, in small and large batches; transposed, short rows go to the
+    # whole-problem-per-wavefront kernel only when the batch fills the device or the problems are short
+    for (m, n, batch) in [(8, 1, 5), (100, 1, 3000), (7, 2, 2500), (300, 3, 40), (33, 3, 2100), (700, 40, 8), (700, 40, 2048),
+                          (64, 8, 512), (64, 8, 511), (32, 40, 20), (33, 40, 20), (2048, 8, 16)]:
+        if dt == np.float64 and n in (2, 3): continue          # two doubles are a vector
+        gemv_batched_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, batch, 1.5, 0.5, 0, 1, 1)
+        gemv_batched_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, batch, -1, 0, 1, 2, -1, gaps=(3, 1, 2))
+    # problems of a few rows each (up to 32 rows take one wavefront per row over the rows of all problems)
+    for (m, n, batch) in [(1, 65, 7), (1, 100, 3000), (2, 257, 33), (5, 1030, 9), (32, 130, 5), (33, 130, 5), (3, 5001, 4), (1, 70000, 3)]:
+        gemv_batched_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, batch, 1.5, 0.5, 0, 1, 1)
+        gemv_batched_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, batch, -1, 0, 3, -1, 2, gaps=(5, 2, 3))
+    gemv_batched_case(blas, ctx, dt, O.ROW_MAJOR, trans, 4, 300, 11, 3, -2, 1, 1, 1, ints=True, share=(True, False))
     # more problems than one grid dimension holds
     gemv_batched_case(blas, ctx, dt, O.ROW_MAJOR, trans, 3, 5, 70000, 1.5, 0.5, 0, 1, 1, share=(True, False), ints=True)
     # one large problem goes the same way as gemv
