@@ -55,6 +55,10 @@ def parse():
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the step: time every routine over a sweep of sizes (small, medium, large buckets, "
                          "skinny N = 40 shapes) and print a markdown table with the geometric mean per bucket")
+    ap.add_argument("--scan", action="store_true",
+                    help="instead of the step: time gemv N/T, ger and gemv_batched over a grid of shapes (1 to millions of rows "
+                         "and columns, up to 192 MiB) in a replayed graph and list the shapes that take more than 1.8 times "
+                         "2.5 us + bytes / 5 TB/s, i.e. the shapes no kernel serves well")
     ap.add_argument("--scale", type=int, default=1, help="divide every problem size by this (debugging only; "
                     "a scaled run is not the benchmark and says so in its output)")
     return ap.parse_args()
@@ -281,6 +285,64 @@ def cpu_baseline(reps=1):
                   f"lower; sger; single thread of {os.cpu_count()} host cores, gcc -O2, long-double accumulation, best of {max(reps, 1)}; "
                   f"{total / 1e9:.2f} GB algorithmic in {t_total:.1f} s",
     }
+
+
+def scan(B, ctx, torch):
+    """Looks for shapes that fall between the kernels: every combination of the row and column counts
+    below, fp32 and fp64, gemv N / T and ger as single calls and gemv_batched at 1 and 64 MiB per
+    call, timed as 10 calls in a replayed graph, against a plain model of a call (2.5 us of launch +
+    bytes at 5 TB/s).  Prints every case and, at the end, those beyond 1.8 times the model."""
+    h = ctx.h
+
+    def replayed(fn, calls=10, reps=5):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            ctx.use_current_stream()
+            for _ in range(calls):
+                assert fn() == 0
+        ctx.use_current_stream()
+        g.replay()
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for a, b in ev:
+            a.record(); g.replay(); b.record()
+        torch.cuda.synchronize()
+        ts = sorted(a.elapsed_time(b) for a, b in ev)
+        return ts[len(ts) // 2] * 1e3 / calls
+
+    bad = []
+
+    def rec(name, shape, nbytes, us):
+        r = us / (2.5 + nbytes / 5e6)
+        line = f"{name:10s} {shape:>28s} {nbytes / 2**20:9.2f} MiB {us:9.2f} us  {r:6.2f} x model"
+        print(line, flush=True)
+        if r > 1.8: bad.append(line)
+
+    dims = [1, 2, 3, 5, 8, 16, 33, 64, 100, 256, 700, 1024, 3000, 8192, 20000, 65536, 200000, 1 << 20, 3000000, 1 << 23]
+    bdims = (1, 3, 8, 16, 40, 64, 100, 256, 700, 2048)
+    for dt, T, e in (("s", torch.float32, 4), ("d", torch.float64, 8)):
+        A = torch.rand((1 << 28) // e, dtype=T, device=ctx.device); x = torch.rand(1 << 24, dtype=T, device=ctx.device)
+        y = torch.rand(1 << 24, dtype=T, device=ctx.device)
+        gemv, ger, gemvb = getattr(B, f"mxb_{dt}gemv"), getattr(B, f"mxb_{dt}ger"), getattr(B, f"mxb_{dt}gemv_batched")
+        for m in dims:
+            for n in dims:
+                nb = m * n * e
+                if nb > (192 << 20) or nb < 4096: continue
+                rec(dt + "gemv_n", f"{m}x{n}", nb + (n + 2 * m) * e, replayed(lambda: gemv(h, B.ROW_MAJOR, B.NO_TRANS, m, n, 1.0, A, n, x, 1, 0.5, y, 1)))
+                rec(dt + "gemv_t", f"{m}x{n}", nb + (m + 2 * n) * e, replayed(lambda: gemv(h, B.ROW_MAJOR, B.TRANS, m, n, 1.0, A, n, x, 1, 0.5, y, 1)))
+                rec(dt + "ger", f"{m}x{n}", 2 * nb + (m + n) * e, replayed(lambda: ger(h, B.ROW_MAJOR, m, n, 1e-6, x, 1, y, 1, A, n)))
+        for total in (1 << 20, 64 << 20):
+            for m in bdims:
+                for n in bdims:
+                    batch = total // (m * n * e)
+                    if batch < 2 or batch > 1 << 22 or max(m, n) * batch > 1 << 24: continue
+                    for nm, tr in (("n", B.NO_TRANS), ("t", B.TRANS)):
+                        lx, ly = (n, m) if tr == B.NO_TRANS else (m, n)
+                        us = replayed(lambda: gemvb(h, B.ROW_MAJOR, tr, m, n, 1.0, A, n, m * n, x, 1, lx, 0.5, y, 1, ly, batch))
+                        rec(f"{dt}gemvb_{nm}", f"{m}x{n} x{batch}", batch * (m * n + lx + 2 * ly) * e, us)
+        del A, x, y
+    print("---- more than 1.8 times the model (launch-bound calls of two kernels sit at 2-2.8):")
+    for line in bad: print(line)
 
 
 def sweep(B, ctx, torch):
@@ -697,6 +759,9 @@ def main():
     ctx = B.Context("cuda:0", workspace_bytes=256 << 20)
     if args.sweep:
         sweep(B, ctx, torch)
+        return
+    if args.scan:
+        scan(B, ctx, torch)
         return
     suite = Suite(B, ctx, torch, scale=args.scale)
     calls = suite.calls
