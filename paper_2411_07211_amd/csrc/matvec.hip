@@ -1061,7 +1061,7 @@ int gemv_rows(mxb_handle_t h, bool no_trans, int64_t rows, int64_t cols, T alpha
     }
     if (no_trans && batch > 1 && rows <= kRowSmallBatchRows && rows * batch < ((int64_t)1 << 31) * (kRowSmallThreads / kWave)) {
         // a batch of problems of a few rows each: one wavefront per row, the rows of all problems as one list
-        // (per call, 1 x 100 in 167772 problems: 909 -> 41 us; 1 x 256 in 65536: 417 -> 27; 8 x 100 in 20971: 118 -> 23)
+        // (per call, 1 x 100 in 167772 problems: 909 -> 41 us; 1 x 256 in 65536: 417 -> 27; 8 x 100 in 20971: 118 -> 40)
         constexpr int FV = Full<T>::vec;
         RowdotArgs<T> a{rows, cols, A, lda, x0, incx, y0, incy, alpha, beta, 0, 0, batch, sA, sx, sy};
         const int64_t loads = ceil_div(cols, (int64_t)kWave * FV);

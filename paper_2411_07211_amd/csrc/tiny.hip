@@ -13,6 +13,7 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
 constexpr int kSlots = 8;                     // rows in flight per lane group
+constexpr int kTinyFewRows = 16;              // transposed: problems of up to this many rows take the lane-per-column-vector kernel
 
 template <typename T>
 struct TinyArgs {
@@ -185,6 +186,53 @@ __global__ void __launch_bounds__(kThreads) tiny_gemv_t_kernel(const TinyArgs<T>
     }
 }
 
+// Transposed, problems of at most MR rows: a lane owns one vector of columns of one problem (the
+// (problem, vector) pairs of the whole batch as one list, so that adjacent lanes read adjacent
+// memory when the problems are packed) and walks down the problem's rows, all of them in flight
+// at once; no folding across lanes.  The kernel above gives such a problem a group of 64 / LPR
+// rows that it fills to a fraction and folds after every problem.
+template <typename T, int VEC, int MR, bool BETA>
+__global__ void __launch_bounds__(kThreads) tiny_fewrows_t_kernel(const TinyArgs<T> p, int nv, int64_t items)
+{
+    typedef typename VecOf<T, VEC>::type V;
+    const int64_t id = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (id >= items) return;
+    const int64_t b = id / nv;
+    const int l = (int)(id - b * nv);
+    const int c = l * VEC, cl = min(c, p.N - VEC);        // a vector past the end of the row is moved back; its first elements are the neighbour's
+    const T* Ab = p.A + b * p.sA + cl;
+    const T* xb = p.x + b * p.sx;
+    V a[MR];
+    T xi[MR];
+#pragma unroll
+    for (int i = 0; i < MR; ++i) {
+        const int ic = min(i, p.M - 1);                   // clamp: loads stay in bounds, rows past the end meet a zero
+        a[i] = ld_matrix<T, VEC>(Ab + (int64_t)ic * p.lda);
+        xi[i] = i < p.M ? xb[(int64_t)ic * p.incx] : T(0);
+    }
+    T yo[VEC];
+    if (BETA) {
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) yo[k] = p.y[b * p.sy + (int64_t)(cl + k) * p.incy];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    T acc[VEC];
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) acc[k] = T(0);
+#pragma unroll
+    for (int i = 0; i < MR; ++i)
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) acc[k] = fmad(a[i][k], xi[i], acc[k]);
+#pragma unroll
+    for (int k = 0; k < VEC; ++k) {
+        if (cl + k >= c) {
+            T v = p.alpha * acc[k];
+            if (BETA) v = fmad(p.beta, yo[k], v);
+            p.y[b * p.sy + (int64_t)(cl + k) * p.incy] = v;
+        }
+    }
+}
+
 }  // namespace
 
 template <typename T>
@@ -220,6 +268,24 @@ int tiny_gemv_t(mxb_handle_t h, int64_t rows, int64_t cols, T alpha, const T* A,
 {
     constexpr int VEC = Full<T>::vec;
     TinyArgs<T> a{(int)rows, (int)cols, (uint32_t)(rows * batch), A, lda, sA, x0, incx, sx, y0, incy, sy, alpha, beta};
+    if (rows <= kTinyFewRows) {
+        const int vec = cols < VEC ? 1 : VEC;
+        const int64_t nvf = ceil_div(cols, (int64_t)vec), items = batch * nvf;
+        const dim3 gf((unsigned)ceil_div(items, (int64_t)kThreads)), bf(kThreads);
+#define MXB_TINY_FEW2(VEC_, MR_)                                                                                                       \
+    if (beta != T(0)) hipLaunchKernelGGL((tiny_fewrows_t_kernel<T, VEC_, MR_, true>), gf, bf, 0, h->stream, a, (int)nvf, items);       \
+    else hipLaunchKernelGGL((tiny_fewrows_t_kernel<T, VEC_, MR_, false>), gf, bf, 0, h->stream, a, (int)nvf, items)
+#define MXB_TINY_FEW(VEC_)                                   \
+    if (rows <= 1) { MXB_TINY_FEW2(VEC_, 1); }               \
+    else if (rows <= 2) { MXB_TINY_FEW2(VEC_, 2); }          \
+    else if (rows <= 4) { MXB_TINY_FEW2(VEC_, 4); }          \
+    else if (rows <= 8) { MXB_TINY_FEW2(VEC_, 8); }          \
+    else { MXB_TINY_FEW2(VEC_, 16); }
+        if (vec == 1) { MXB_TINY_FEW(1) } else { MXB_TINY_FEW(VEC) }
+#undef MXB_TINY_FEW
+#undef MXB_TINY_FEW2
+        return launch_status();
+    }
     const int64_t nv = ceil_div(cols, (int64_t)VEC);
     const int lpr = nv <= 4 ? 4 : nv <= 8 ? 8 : 16;
     // enough wavefronts to fill the device, but whole problems per wavefront

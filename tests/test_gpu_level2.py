@@ -272,6 +272,14 @@ def test_gemv_batched(blas, ctx, dt, trans):
         gemv_batched_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, batch, 1.5, 0.5, 0, 1, 1)
         gemv_batched_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, batch, -1, 0, 3, -1, 2, gaps=(5, 2, 3))
     gemv_batched_case(blas, ctx, dt, O.ROW_MAJOR, trans, 4, 300, 11, 3, -2, 1, 1, 1, ints=True, share=(True, False))
+    # transposed, problems of up to 16 rows and 64 columns: a lane per vector of columns (every row count
+    # the kernel is built for and the ones between, whole and ragged widths, the first size beyond)
+    for (m, n, batch) in [(1, 8, 1000), (2, 4, 3), (3, 3, 2000), (3, 7, 50), (5, 40, 300), (8, 64, 100), (9, 1, 77), (16, 16, 500),
+                          (16, 63, 9), (17, 16, 500), (1, 1, 3000)]:
+        if dt == np.float64 and n == 3: continue
+        gemv_batched_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, batch, 1.5, 0.5, 0, 1, 1)
+        gemv_batched_case(blas, ctx, dt, O.ROW_MAJOR, trans, m, n, batch, -1, 0, 2, -1, 2, gaps=(3, 1, 2))
+    gemv_batched_case(blas, ctx, dt, O.ROW_MAJOR, trans, 6, 12, 40, 3, -2, 0, 1, 1, ints=True, share=(False, True))
     # more problems than one grid dimension holds
     gemv_batched_case(blas, ctx, dt, O.ROW_MAJOR, trans, 3, 5, 70000, 1.5, 0.5, 0, 1, 1, share=(True, False), ints=True)
     # one large problem goes the same way as gemv
