@@ -310,12 +310,13 @@ def scan(B, ctx, torch):
         ts = sorted(a.elapsed_time(b) for a, b in ev)
         return ts[len(ts) // 2] * 1e3 / calls
 
-    bad = []
+    bad, every = [], []
 
     def rec(name, shape, nbytes, us):
         r = us / (2.5 + nbytes / 5e6)
         line = f"{name:10s} {shape:>28s} {nbytes / 2**20:9.2f} MiB {us:9.2f} us  {r:6.2f} x model"
         print(line, flush=True)
+        every.append(line)
         if r > 1.8: bad.append(line)
 
     dims = [1, 2, 3, 5, 8, 16, 33, 64, 100, 256, 700, 1024, 3000, 8192, 20000, 65536, 200000, 1 << 20, 3000000, 1 << 23]
@@ -341,8 +342,24 @@ def scan(B, ctx, torch):
                         us = replayed(lambda: gemvb(h, B.ROW_MAJOR, tr, m, n, 1.0, A, n, m * n, x, 1, lx, 0.5, y, 1, ly, batch))
                         rec(f"{dt}gemvb_{nm}", f"{m}x{n} x{batch}", batch * (m * n + lx + 2 * ly) * e, us)
         del A, x, y
-    print("---- more than 1.8 times the model (launch-bound calls of two kernels sit at 2-2.8):")
-    for line in bad: print(line)
+    # the summary kept in profiles/shape_scan.md
+    import statistics
+    ratio = lambda line: float(line.split()[-3])
+    fam = {}
+    for line in every: fam.setdefault(line.split()[0], []).append(ratio(line))
+    print("# Shape scan: gemv N / T, ger and gemv_batched over a grid of shapes against a plain model of a call\n")
+    print("Command (one MI355X, committed files only): `python bench.py --scan | sed -n '/^# Shape scan/,$p' > profiles/shape_scan.md`.\n"
+          "Every combination of 20 row and column counts from 1 to 8388608 (up to 192 MiB per matrix), single and double precision,\n"
+          "and gemv_batched over 10 x 10 problem shapes at 1 and 64 MiB per call; 10 calls in a replayed HIP graph, median of 5\n"
+          "replays; the model of a call is 2.5 us + bytes / 5 TB/s.  A call that needs two kernels on little data sits at 2-3 times\n"
+          "the model.\n")
+    print("| routine | cases | median ratio to the model | worst | cases beyond 1.8 |\n|---|---|---|---|---|")
+    for k, v in fam.items():
+        print(f"| {k} | {len(v)} | {statistics.median(v):.2f} | {max(v):.2f} | {sum(1 for r in v if r > 1.8)} |")
+    print("\n## Cases beyond 2.5 times the model\n\n```")
+    for line in bad:
+        if ratio(line) > 2.5: print(line)
+    print("```")
 
 
 def sweep(B, ctx, torch):
