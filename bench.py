@@ -56,7 +56,7 @@ def parse():
                     help="instead of the step: time every routine over a sweep of sizes (small, medium, large buckets, "
                          "skinny N = 40 shapes) and print a markdown table with the geometric mean per bucket")
     ap.add_argument("--scan", action="store_true",
-                    help="instead of the step: time gemv N/T, ger and gemv_batched over a grid of shapes (1 to millions of rows "
+                    help="instead of the step: time every routine (gemv N/T, ger and gemv_batched over a grid of shapes of 1 to millions of rows "
                          "and columns, up to 192 MiB) in a replayed graph and list the shapes that take more than 1.8 times "
                          "2.5 us + bytes / 5 TB/s, i.e. the shapes no kernel serves well")
     ap.add_argument("--scale", type=int, default=1, help="divide every problem size by this (debugging only; "
@@ -341,18 +341,40 @@ def scan(B, ctx, torch):
                         lx, ly = (n, m) if tr == B.NO_TRANS else (m, n)
                         us = replayed(lambda: gemvb(h, B.ROW_MAJOR, tr, m, n, 1.0, A, n, m * n, x, 1, lx, 0.5, y, 1, ly, batch))
                         rec(f"{dt}gemvb_{nm}", f"{m}x{n} x{batch}", batch * (m * n + lx + 2 * ly) * e, us)
+        # level 1 (unit and strided) and the structured level-2 routines over n
+        r = torch.zeros(4, dtype=T, device=ctx.device); ri = torch.zeros(2, dtype=torch.int64, device=ctx.device)
+        f = lambda nm: getattr(B, f"mxb_{dt}{nm}")
+        for n in (100, 4096, 65536, 300000, 1 << 20, 3000001, 1 << 23):
+            for inc, tag in ((1, ""), (2, "/inc2")):
+                if n * inc > 1 << 24: continue
+                rec(f"{dt}axpy{tag}", str(n), 3 * n * e, replayed(lambda: f("axpy")(h, n, 1e-3, x, inc, y, inc)))
+                rec(f"{dt}scal{tag}", str(n), 2 * n * e, replayed(lambda: f("scal")(h, n, 1.0, x, inc)))
+                rec(f"{dt}dot{tag}", str(n), 2 * n * e, replayed(lambda: f("dot")(h, n, x, inc, y, inc, r)))
+                rec(f"{dt}nrm2{tag}", str(n), n * e, replayed(lambda: f("nrm2")(h, n, x, inc, r)))
+                rec(f"{dt}swap{tag}", str(n), 4 * n * e, replayed(lambda: f("swap")(h, n, x, inc, y, inc)))
+                rec(f"i{dt}amax{tag}", str(n), n * e, replayed(lambda: getattr(B, f"mxb_i{dt}amax")(h, n, x, inc, ri)))
+        A.mul_(1e-4)       # small off-diagonal elements: trmv repeated on one vector stays finite
+        for n in (33, 100, 300, 700, 1500, 2500, 3500, 5000):
+            tri = n * (n + 1) // 2 * e
+            for up, ut in ((B.UPPER, "u"), (B.LOWER, "l")):
+                rec(f"{dt}symv_{ut}", str(n), tri, replayed(lambda: f("symv")(h, B.ROW_MAJOR, up, n, 0.5, A, n, x, 1, 0.5, y, 1)))
+                rec(f"{dt}syr_{ut}", str(n), 2 * tri, replayed(lambda: f("syr")(h, B.ROW_MAJOR, up, n, 1e-9, x, 1, A, n)))
+                rec(f"{dt}syr2_{ut}", str(n), 2 * tri, replayed(lambda: f("syr2")(h, B.ROW_MAJOR, up, n, 1e-9, x, 1, y, 1, A, n)))
+                for tr, tt in ((B.NO_TRANS, "n"), (B.TRANS, "t")):
+                    rec(f"{dt}trmv_{ut}{tt}", str(n), tri, replayed(lambda: f("trmv")(h, B.ROW_MAJOR, up, tr, B.UNIT, n, A, n, x, 1)))
         del A, x, y
     # the summary kept in profiles/shape_scan.md
     import statistics
     ratio = lambda line: float(line.split()[-3])
     fam = {}
     for line in every: fam.setdefault(line.split()[0], []).append(ratio(line))
-    print("# Shape scan: gemv N / T, ger and gemv_batched over a grid of shapes against a plain model of a call\n")
+    print("# Shape scan: every routine over a grid of shapes against a plain model of a call\n")
     print("Command (one MI355X, committed files only): `python bench.py --scan | sed -n '/^# Shape scan/,$p' > profiles/shape_scan.md`.\n"
           "Every combination of 20 row and column counts from 1 to 8388608 (up to 192 MiB per matrix), single and double precision,\n"
-          "and gemv_batched over 10 x 10 problem shapes at 1 and 64 MiB per call; 10 calls in a replayed HIP graph, median of 5\n"
-          "replays; the model of a call is 2.5 us + bytes / 5 TB/s.  A call that needs two kernels on little data sits at 2-3 times\n"
-          "the model.\n")
+          "for gemv N / T and ger; gemv_batched over 10 x 10 problem shapes at 1 and 64 MiB per call; the level-1 routines at 7\n"
+          "lengths, unit increment and increment 2; symv, syr, syr2 and trmv at 8 orders, both triangles.  10 calls in a replayed\n"
+          "HIP graph, median of 5 replays; the model of a call is 2.5 us + bytes / 5 TB/s.  A call that needs two kernels on\n"
+          "little data (reductions, trmv, the transposed product of a tall matrix) sits at 2-3 times the model.\n")
     print("| routine | cases | median ratio to the model | worst | cases beyond 1.8 |\n|---|---|---|---|---|")
     for k, v in fam.items():
         print(f"| {k} | {len(v)} | {statistics.median(v):.2f} | {max(v):.2f} | {sum(1 for r in v if r > 1.8)} |")

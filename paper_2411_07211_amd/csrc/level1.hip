@@ -502,14 +502,24 @@ __device__ __forceinline__ Cand cand_of(T x, int64_t i)
 
 __device__ __forceinline__ Cand block_best(Cand c, Cand* slots)
 {
-    // fold through LDS in a fixed tree (once per block: speed is irrelevant here)
+    // One barrier: every lane of the first wavefront takes the candidates of its own lane number in all
+    // wavefronts, then the wavefront folds its 64 through shuffles.  `better` is a total order, so the
+    // result does not depend on the shape of the tree.  Valid in the first wavefront only.
+    // (a tree through LDS with a barrier per level: 65536 elements 6.5 us per call instead of 5.4, 100 elements
+    // 3.5 instead of 2.8)
     slots[threadIdx.x] = c;
     __syncthreads();
-    for (int w = kThreads / 2; w > 0; w >>= 1) {
-        if ((int)threadIdx.x < w) slots[threadIdx.x] = better(slots[threadIdx.x], slots[threadIdx.x + w]);
-        __syncthreads();
+    if (threadIdx.x >= kWave) return c;
+#pragma unroll
+    for (int w = 1; w < kThreads / kWave; ++w) c = better(c, slots[w * kWave + threadIdx.x]);
+#pragma unroll
+    for (int m = kWave / 2; m > 0; m >>= 1) {
+        Cand o;
+        o.v = __shfl_xor(c.v, m);
+        o.i = (int64_t)__shfl_xor((long long)c.i, m);
+        c = better(c, o);
     }
-    return slots[0];
+    return c;
 }
 
 template <typename T>
