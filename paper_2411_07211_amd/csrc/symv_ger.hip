@@ -273,30 +273,32 @@ __global__ void __launch_bounds__(kThreads) syr_kernel(const SyrArgs<T> p)
 // ---------------------------------------------------------------------------------------------
 // symv of a small matrix in one kernel (no workspace, no second pass): a call on a few thousand
 // unknowns is bound by launches and latency, not by bytes, so every stored element is read twice
-// instead of once.  Block b owns the 32 unknowns I = [32b, 32b + 32) and forms both halves of
+// instead of once.  Block b owns the 16 unknowns I = [16b, 16b + 16) and forms both halves of
 // their results itself:
 //   row part     sum over the stored part of rows I (columns <= i if lower, >= i if upper): each
-//                wavefront takes 8 rows, its lanes stride across the columns with 128-bit loads;
+//                wavefront takes 4 rows, its lanes stride across the columns with 128-bit loads;
 //   column part  sum over the stored part of columns I in the other rows (rows > j if lower,
-//                < j if upper), i.e. the mirrored elements: 32 columns = CL lanes, 64 / CL rows
+//                < j if upper), i.e. the mirrored elements: 16 columns = CL lanes, 64 / CL rows
 //                side by side per wavefront load, column sums in registers, folded through LDS.
-// Every block reads about 32 n elements, whatever b is.  The order of all sums is fixed.
-constexpr int kSmallTile = 32;
+// Every block reads about 16 n elements, whatever b is.  The order of all sums is fixed.
+// (unknowns per block, measured per call: 8 / 16 / 32 at n = 256 4.1 / 3.7 / 4.0 us, 1024 5.0 / 4.8 / 6.0, 1536 5.8 / 5.4 / 7.2,
+// 2048 9.1 / 7.6 / 8.5; double precision 1024 5.3 / 5.6 / 8.0, 1536 8.1 / 8.5 / 10.4)
+constexpr int kSmallTile = 16;
 
-template <typename T, int VEC, bool UPPER>
+template <typename T, int VEC, bool UPPER, int TILE>
 __global__ void __launch_bounds__(kThreads) symv_small_kernel(int n, T alpha, const T* __restrict__ A, int64_t lda,
                                                               const T* __restrict__ x, int64_t incx, T beta, T* __restrict__ y,
                                                               int64_t incy)
 {
     typedef typename VecOf<T, VEC>::type V;
-    constexpr int NW = kThreads / kWave, RPW = kSmallTile / NW;   // wavefronts; rows of the row part per wavefront
-    constexpr int CL = kSmallTile / VEC, RL = kWave / CL;         // column part: lanes per row, rows per wavefront load
+    constexpr int NW = kThreads / kWave, RPW = TILE / NW;   // wavefronts; rows of the row part per wavefront
+    constexpr int CL = TILE / VEC, RL = kWave / CL;         // column part: lanes per row, rows per wavefront load
     constexpr int UB = 4;                                         // column part: loads in flight per lane
-    __shared__ T ya[kSmallTile];
+    __shared__ T ya[TILE];
     __shared__ T red[NW][kWave][VEC];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int i0 = (int)blockIdx.x * kSmallTile, i1 = min(n, i0 + kSmallTile);
+    const int i0 = (int)blockIdx.x * TILE, i1 = min(n, i0 + TILE);
 
     // ---- row part: rows i0 + wave*RPW + u, columns [ca, cb)
     {
@@ -365,7 +367,7 @@ __global__ void __launch_bounds__(kThreads) symv_small_kernel(int n, T alpha, co
     }
     __syncthreads();
     const int t = threadIdx.x;
-    if (t < kSmallTile && i0 + t < n) {
+    if (t < TILE && i0 + t < n) {
         // column i0 + t sits in element k of the vector of lanes cq + CL*rl (rl = 0..RL-1)
         const int cq = t / VEC, cl = max(min(i0 + cq * VEC, n - VEC), 0), k = i0 + t - cl;
         T s = ya[t];
@@ -409,8 +411,8 @@ int symv(mxb_handle_t h, int layout, int uplo, int64_t n, T alpha, const T* A, i
     // (in double precision a lane walks twice the rows: the sweep is ahead from two thirds of the limit on, n = 1536: 12 against 19 us)
     if (n >= FV && n <= option(h, MXB_OPT_SYMV_SMALL_MAX) * (sizeof(T) == 8 ? 2 : 3) / 3) {
         const dim3 grid((unsigned)ceil_div(n, (int64_t)kSmallTile));
-        if (upper) hipLaunchKernelGGL((symv_small_kernel<T, FV, true>), grid, dim3(kThreads), 0, h->stream, (int)n, alpha, A, lda, x0, incx, beta, y0, incy);
-        else hipLaunchKernelGGL((symv_small_kernel<T, FV, false>), grid, dim3(kThreads), 0, h->stream, (int)n, alpha, A, lda, x0, incx, beta, y0, incy);
+        if (upper) hipLaunchKernelGGL((symv_small_kernel<T, FV, true, kSmallTile>), grid, dim3(kThreads), 0, h->stream, (int)n, alpha, A, lda, x0, incx, beta, y0, incy);
+        else hipLaunchKernelGGL((symv_small_kernel<T, FV, false, kSmallTile>), grid, dim3(kThreads), 0, h->stream, (int)n, alpha, A, lda, x0, incx, beta, y0, incy);
         return launch_status();
     }
     return trisweep_symv<T>(h, upper, n, alpha, A, lda, x0, incx, beta, y0, incy);

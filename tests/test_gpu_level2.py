@@ -428,7 +428,7 @@ def test_symv(blas, ctx, dt, layout, uplo):
     for small_max in (0, 1):
         ctx.set_option(blas.OPT_SYMV_SMALL_MAX, small_max)
         try:
-            for n in (1, 2, 3, 4, 5, 17, 31, 32, 33, 64, 65, 130, 257, 1000, 1024, 2047, 2048, 2310):
+            for n in (1, 2, 3, 4, 5, 15, 16, 17, 31, 32, 33, 64, 65, 130, 257, 1000, 1024, 1600, 1601, 2047, 2048, 2310, 2400, 2401):
                 symv_case(blas, ctx, dt, layout, uplo, n, 1.5, 0.5, 0 if n % 2 else 4, 1, 1)
             symv_case(blas, ctx, dt, layout, uplo, 515, 1.5, 0.5, 1, 2, -3)
             symv_case(blas, ctx, dt, layout, uplo, 1536, 3, -2, 0, 1, 1, ints=True)
