@@ -99,7 +99,7 @@ typedef enum {
     MXB_OPT_SYMV_TILE_VECTORS = 8,  /* triangle sweep: 128-bit vectors per lane and row (1, 2 or 4); tile = 256 lanes x this */
     MXB_OPT_TRI_DIAG_WEIGHT = 9,    /* triangle sweep: cost of a row that crosses the diagonal, in quarters of a row that does not (1..8) */
     MXB_OPT_SYMV_SMALL_MAX = 10,    /* symv: largest n that takes the single-kernel path (every element read twice, no workspace); two thirds of it in double precision */
-    MXB_OPT_TRSV_CHAIN_MIN = 11,    /* trsv: smallest n solved by the single chained kernel instead of one launch per block (default 257; 65 in single precision when the row-major product is not transposed) */
+    MXB_OPT_TRSV_CHAIN_MIN = 11,    /* trsv: smallest n solved by the single chained kernel instead of one launch per block (default 129) */
     MXB_OPT_TRSV_SPIN_LIMIT = 12,   /* chained trsv: polls of one hand-over word before a wavefront gives up (default 2^24: tens of seconds) */
     MXB_OPT_GEMVT_SMALL_MAX = 13,   /* transposed gemv: largest matrix in bytes that takes the single-kernel path (no workspace) */
     MXB_OPT_GEMVN_SMALL_MAX = 14,   /* gemv, not transposed: largest matrix in bytes that takes the kernel for cache-resident matrices */

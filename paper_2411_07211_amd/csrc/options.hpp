@@ -20,7 +20,7 @@ inline int64_t option_default(int o)
         case MXB_OPT_GEMVT_SMALL_MAX: return 32 << 20;   // and at most 2048 rows; larger matrices stream better through the general kernels
         case MXB_OPT_GEMVN_SMALL_MAX: return kKeepMatrixBytes;   // what stays in the last-level cache; beyond, the persistent row-dot grid with x in LDS and streaming loads (per call, repeated: 5000^2 16.9 against 22.6 us, 7000^2 29.0 against 33.3, 8192^2 39.4 against 40.5, 10000^2 71.5 against 65.6)
         case MXB_OPT_TRSV_SPIN_LIMIT: return 1 << 24;  // polls of one hand-over word before a wavefront gives up: tens of seconds
-        case MXB_OPT_TRSV_CHAIN_MIN: return 257;       // (65 in single precision when not transposed: trsv decides) from here the chained kernel is faster than a launch per block
+        case MXB_OPT_TRSV_CHAIN_MIN: return 129;       // from here the chained kernel is faster than a launch per block
         case MXB_OPT_SYMV_SMALL_MAX: return 2400;      // beyond this the triangle sweep is faster (measured per call: 2048 7.6 against 8.7 us, 2500 9.8 against 10.2, 3000 12.1 against 10.6; double precision, two thirds of it: 1536 8.5 against 9.4, 2048 11.6 against 10.4)
         default: return 0;
     }

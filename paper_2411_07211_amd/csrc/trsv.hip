@@ -162,13 +162,22 @@ void launch_trsv_diag(mxb_handle_t h, bool op_lower, bool unit, const TrsvArgs<T
 // The same substitution in ONE kernel: no launch per block, and the off-diagonal work of a block
 // of rows overlaps the solves of the blocks before it.
 //
-// A workgroup of 4 wavefronts (2 in double precision when not transposed) owns 256 (128)
-// consecutive unknowns, one sub-block of 64 per wavefront, in solving order.  Workgroups number themselves with a ticket when they start, so
-// that every workgroup with a smaller number is already running or done.  A wavefront first
-// subtracts, sub-block by sub-block, the part of its rows that multiplies unknowns owned by
-// earlier workgroups: the 64 x 64 tile is fetched while the wavefront waits for that sub-block's
+// A workgroup of 2 wavefronts owns 128 consecutive unknowns, one sub-block of 64 per wavefront,
+// in solving order.  Workgroups number themselves with a ticket when they start, so that every
+// workgroup with a smaller number is already running or done.  A wavefront first subtracts,
+// sub-block by sub-block, the part of its rows that multiplies unknowns owned by earlier
+// workgroups: the 64 x 64 tile is fetched while the wavefront waits for that sub-block's
 // solutions.  The sub-blocks of the workgroup itself are then solved as in the blocked kernel
 // above (LDS and barriers), each one handed on as soon as it is solved.
+//
+// Every wavefront has to take one tile per sub-block that the chain solves, so the chain runs
+// no faster than the slowest wavefront gets through a tile.  That, not the hand-over, was the
+// limit while a tile was 64 loads of one element per lane (per tile: 0.8 to 1.2 us to issue the
+// loads, 0.3 to 0.6 us of polls queued behind them, since loads return in order, and 0.5 us of
+// broadcasts and multiply-adds when transposed; the wavefront that a workgroup's first solve
+// waits for began to look for the last solutions 3 us after they were there).  Rows that begin on
+// 16-byte boundaries are therefore read with 128-bit loads (WIDE, below); others keep the
+// element-wise path.
 //
 // Solutions travel between workgroups in words that validate themselves: the solver stores
 // {value bits, tag} as one 64-bit device-scope atomic (two words, one per half, for a double), a
@@ -233,44 +242,75 @@ __global__ void __launch_bounds__(256) trsv_chain_init_kernel(int* words, int co
     if (k < count) words[k] = 0;
 }
 
-// raw[k] = A[min(first + k, last)][col], k < COUNT; first is the same for the whole wavefront.  One
-// pointer runs down the rows and stops at the last one.  The empty asm makes first opaque, which
-// keeps the compiler from forming all COUNT row addresses ahead of the loops around the call and
-// holding them in scalar registers (it then spills hundreds of them).
+// raw[k] = A[min(first + k, last)][col], k < COUNT; first is the same for the whole wavefront.
+// Buffer loads: the descriptor holds the address of row `first`, the lane's column is the vector
+// offset (the same for every row) and the row is a scalar offset that grows by one pitch per
+// load, so a load costs one scalar addition beside itself (with flat addresses: a 64-bit vector
+// addition and half a dozen scalar instructions, and a wavefront alone on its SIMD unit issues
+// one instruction every four or five cycles: asking for a tile then took 1.4 to 1.7 us, more than
+// the solve of a sub-block).  All addresses are clamped into the matrix, so the descriptor's own
+// range check is left wide open.  The scalar offset is 32 bits: the caller makes sure that COUNT
+// rows are less than 2^31 bytes apart.  The empty asm keeps the compiler from forming all COUNT
+// offsets ahead of the loops around the call and holding them in scalar registers.
+__device__ __forceinline__ float buffer_load(__amdgpu_buffer_rsrc_t r, int voff, int soff, float)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0));
+}
+__device__ __forceinline__ double buffer_load(__amdgpu_buffer_rsrc_t r, int voff, int soff, double)
+{
+    return __builtin_bit_cast(double, __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0));
+}
+constexpr int kBufferRawDword3 = 0x00020000;      // 32-bit raw data, no swizzle
 template <typename T, int COUNT>
 __device__ __forceinline__ void load_rows(const T* A, int64_t lda, int first, int last, int col, T (&raw)[COUNT])
 {
     asm volatile("" : "+s"(first));
-    const T* row = A + (int64_t)min(first, last) * lda;
+    const __amdgpu_buffer_rsrc_t rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(A + (int64_t)min(first, last) * lda), 0, -1, kBufferRawDword3);
+    const int voff = col * (int)sizeof(T), pitch = (int)lda * (int)sizeof(T);
+    int soff = 0;
+    if (first + COUNT - 1 <= last) {
 #pragma unroll
-    for (int k = 0; k < COUNT; ++k) {
-        raw[k] = row[col];
-        row += first + k < last ? lda : 0;
+        for (int k = 0; k < COUNT; ++k) {
+            raw[k] = buffer_load(rsrc, voff, soff, T());
+            soff += pitch;
+            asm volatile("" : "+s"(soff));
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < COUNT; ++k) {
+            raw[k] = buffer_load(rsrc, voff, soff, T());
+            soff += first + k < last ? pitch : 0;
+            asm volatile("" : "+s"(soff));
+        }
     }
 }
 
-// Wavefronts per workgroup of the chained kernel: 4, but 2 in double precision when not
-// transposed, where LDS has to hold the turning buffer and the parked diagonal rows.  (The hand-over
-// between workgroups, from the last solution of one to the first of the next, takes 3.4 us, a step
-// inside a workgroup 0.6 us of solve and 0.9 us until the next solve begins, so fewer, larger
-// workgroups would be faster; but 8 wavefronts are two per SIMD unit, 256 registers each, and
-// the kernel then spills 260 to 620 of them.  Without the barrier, the solver handing its unknowns
-// on through LDS in four groups of 16 as they become final and the others polling for them, a
-// step inside a workgroup took 1.15 us instead of 0.9; with one flag in LDS per sub-block in place
-// of the barrier, which also waits for the wavefronts that are busy asking for a tile two steps
-// ahead, n = 16384 took 582 us instead of 570.)
+// Wavefronts per workgroup of the chained kernel.  A step from one sub-block to the next costs
+// 0.45 us inside a workgroup (LDS, one barrier) and 1.3 us between workgroups, beside 0.6 us of
+// solve, which speaks for large workgroups; but the wavefronts of a workgroup share a compute unit
+// and its path to memory, all of them ask for a tile at the same moment, and the other compute
+// units idle.  Measured at n = 16384, single precision, not transposed / transposed, element-wise
+// loads: 4 wavefronts 615 / 502 us, 2: 531 / 455, 1: 554 / 486; 128-bit loads: 4: 425 / 449, 2: 401 /
+// 364, 1: 457 / 423.  (8 wavefronts are two per SIMD unit, 256 registers each: the kernel then spills
+// 260 to 620 of them.  Handing the unknowns on through LDS in groups of 16 as they become final,
+// with the others polling instead of a barrier, or one LDS flag per sub-block in place of the
+// barrier, were both slower than the barrier.)
 template <typename T, bool TRANS>
-constexpr int chain_waves() { return (sizeof(T) == 8 && !TRANS) ? 2 : 4; }
+constexpr int chain_waves() { return 2; }
 
-template <typename T, bool OPLOWER, bool TRANS, bool UNIT>
+template <typename T, bool OPLOWER, bool TRANS, bool UNIT, bool WIDE>
 __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_kernel(const ChainArgs<T> p)
 {
     constexpr int NW = chain_waves<T, TRANS>();
+    constexpr int V = 16 / (int)sizeof(T);       // elements of a 128-bit load
     __shared__ __attribute__((aligned(16))) T xs[NW * kWave];
+    __shared__ __attribute__((aligned(16))) T fold[(TRANS && WIDE) ? NW : 1][(TRANS && WIDE) ? V * kWave : 1];
     // per-wavefront buffers: one turns tiles when not transposed; in double precision, where the
-    // registers are short, another holds the wavefront's finished diagonal rows
-    constexpr bool kPark = sizeof(T) == 8;
-    __shared__ T tile[TRANS ? 1 : NW][TRANS ? 1 : kWave][TRANS ? 1 : kWave + 1];
+    // registers are short, another holds the wavefront's finished diagonal rows (not needed on the
+    // element-wise transposed path, which keeps them in registers without spilling)
+    constexpr bool kPark = sizeof(T) == 8 && (!TRANS || WIDE);
+    __shared__ __attribute__((aligned(16))) T tile[TRANS ? 1 : NW][TRANS ? 1 : kWave][TRANS ? 1 : kWave + 1];
     __shared__ T park[kPark ? NW : 1][kPark ? kWave : 1][kPark ? kWave + 1 : 1];
     __shared__ int my_ticket;
     constexpr int HW = Handover<T>::kWords;
@@ -374,6 +414,158 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
             got = look(qq, xv);
         }
     };
+    if constexpr (WIDE) {
+      if (have && q0 > 0) {
+        // 128-bit loads: lane (g, m), g = lane / CG, m = lane % CG, fetches for t < NL the V elements
+        // at memory row row0 + g * NL + t, columns col0 + m * V .., of a piece of RH = V * NL rows, so
+        // a piece is NL loads instead of RH (a wavefront alone on its SIMD unit issues slowly, and
+        // asking for the tiles is what the streaming wavefronts spend their time on).  Transposed,
+        // the rows of the piece are solved unknowns and the columns mine: a lane keeps V partial
+        // sums, for unknowns m * V .., over the rows it loads.  Not transposed, the rows are my
+        // unknowns: a lane keeps one partial sum per row it loads, over its V columns.  Either way
+        // the partial sums are folded over the lanes once, through LDS, after the last tile, and
+        // the 64 solutions a tile multiplies reach the lanes that need them through LDS.
+        constexpr int CG = kWave / V;
+        constexpr int RH = sizeof(T) == 4 ? kWave : kWave / 2;
+        constexpr int CPT = kWave / RH, NL = RH / V;
+        typedef T vec_t __attribute__((ext_vector_type(V)));
+        const int m = lane % CG, g = lane / CG;
+        const int pitch = (int)p.lda * (int)sizeof(T);
+        const int lastvec = last / V * V;
+        const int voff_inside = g * NL * pitch + m * V * (int)sizeof(T);
+        T* const xb = xs + wave * kWave;          // my slot of xs is free until my own solve
+        auto startv = [&](int ch, vec_t (&raw)[NL]) {
+            const int cblk = actual(ch / CPT) * kWave, h0 = (ch % CPT) * RH;
+            int row0 = (TRANS ? cblk : r0) + h0;
+            const int col0 = TRANS ? r0 : cblk;
+            asm volatile("" : "+s"(row0));
+            const int rowb = min(row0, last);
+            const __amdgpu_buffer_rsrc_t rsrc =
+                __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(p.A + (int64_t)rowb * p.lda + col0), 0, -1, kBufferRawDword3);
+            if (row0 + RH <= p.n && col0 + kWave <= p.n) {
+                int soff = 0;
+#pragma unroll
+                for (int t = 0; t < NL; ++t) {
+                    raw[t] = __builtin_bit_cast(vec_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff_inside, soff, 0));
+                    soff += pitch;
+                    asm volatile("" : "+s"(soff));
+                }
+            } else {      // the last rows or columns of the matrix: addresses clamped into it, lane by lane
+                const int cofs = (min(col0 + m * V, lastvec) - col0) * (int)sizeof(T);
+#pragma unroll
+                for (int t = 0; t < NL; ++t) {
+                    const int r = min(row0 + g * NL + t, last) - rowb;
+                    raw[t] = __builtin_bit_cast(vec_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc, r * pitch + cofs, 0, 0));
+                }
+            }
+        };
+        T pv[V];
+        T acc[TRANS ? 1 : CG];
+        vec_t xmine;                              // not transposed: the V solutions my columns multiply
+#pragma unroll
+        for (int v = 0; v < V; ++v) { pv[v] = T(0); xmine[v] = T(0); }
+        if (!TRANS) {
+#pragma unroll
+            for (int k = 0; k < CG; ++k) acc[TRANS ? 0 : k] = T(0);
+        }
+        auto usev = [&](auto piece, int ch, vec_t (&raw)[NL]) {
+            constexpr int PIECE = decltype(piece)::value, H0 = PIECE * RH;
+            const int qq = ch / CPT, cblk = actual(qq) * kWave;
+            const int row0 = (TRANS ? cblk : r0) + H0, col0 = TRANS ? r0 : cblk;
+            if (PIECE == 0) {
+                T xv;
+                const bool got = look(qq, xv);
+                wait_x(qq, xv, got);
+                __builtin_amdgcn_wave_barrier();      // my earlier reads of the buffer come first
+                xb[lane] = xv;
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                if (!TRANS) xmine = *reinterpret_cast<const vec_t*>(xb + m * V);
+            }
+#pragma unroll
+            for (int t = 0; t < NL; ++t) asm volatile("" : "+v"(raw[t]));
+            if (row0 + RH > p.n || col0 + kWave > p.n) {
+#pragma unroll
+                for (int t = 0; t < NL; ++t)
+#pragma unroll
+                    for (int v = 0; v < V; ++v)
+                        raw[t][v] = (row0 + g * NL + t < p.n && col0 + m * V + v < p.n) ? raw[t][v] : T(0);
+            }
+            if (TRANS) {
+                T xk[NL];
+#pragma unroll
+                for (int t = 0; t < NL; t += V) {
+                    const vec_t xq = *reinterpret_cast<const vec_t*>(xb + H0 + g * NL + t);
+#pragma unroll
+                    for (int v = 0; v < V; ++v) xk[t + v] = xq[v];
+                }
+#pragma unroll
+                for (int t = 0; t < NL; ++t)
+#pragma unroll
+                    for (int v = 0; v < V; ++v) pv[v] = fmad(raw[t][v], xk[t], pv[v]);
+            } else {
+#pragma unroll
+                for (int t = 0; t < NL; ++t) {
+                    T sum = acc[TRANS ? 0 : PIECE * NL + t];
+#pragma unroll
+                    for (int v = 0; v < V; ++v) sum = fmad(raw[t][v], xmine[v], sum);
+                    acc[TRANS ? 0 : PIECE * NL + t] = sum;
+                }
+            }
+        };
+        const int nch = q0 * CPT;
+        vec_t t0[NL], t1[NL];
+        startv(0, t0);
+        if (nch > 1) startv(1, t1);
+        int ch = 0;
+        for (; ch + 1 < nch; ch += 2) {
+            usev(std::integral_constant<int, 0>(), ch, t0);
+            if (ch + 2 < nch) startv(ch + 2, t0);
+            usev(std::integral_constant<int, CPT - 1>(), ch + 1, t1);
+            if (ch + 3 < nch) startv(ch + 3, t1);
+        }
+        if (ch < nch) usev(std::integral_constant<int, 0>(), ch, t0);
+        // the partial sums, folded over the lanes: lane = unknown from here on
+        __builtin_amdgcn_wave_barrier();
+        if (TRANS) {
+            T* const red = &fold[(TRANS && WIDE) ? wave : 0][0];
+            vec_t out;
+#pragma unroll
+            for (int v = 0; v < V; ++v) out[v] = pv[v];
+            *reinterpret_cast<vec_t*>(red + ((TRANS && WIDE) ? g * kWave + m * V : 0)) = out;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            T sum = T(0);
+#pragma unroll
+            for (int gg = 0; gg < V; ++gg) sum += red[(TRANS && WIDE) ? gg * kWave + lane : 0];
+            b -= sum;
+        } else {
+            // unknown h * RH + g * NL + t is acc[h * NL + t] of the lanes (g, 0 .. CG - 1); rows of the buffer V apart
+            // from a power of two, so that the 128-bit stores spread over the banks
+            constexpr int STRIDE = kWave + V;
+            T* const red = &tile[TRANS ? 0 : wave][0][0];
+#pragma unroll
+            for (int h = 0; h < CPT; ++h)
+#pragma unroll
+                for (int t = 0; t < NL; t += V) {
+                    vec_t out;
+#pragma unroll
+                    for (int v = 0; v < V; ++v) out[v] = acc[TRANS ? 0 : h * NL + t + v];
+                    *reinterpret_cast<vec_t*>(red + (TRANS ? 0 : m * STRIDE + h * RH + g * NL + t)) = out;
+                }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            T part[4] = {T(0), T(0), T(0), T(0)};
+#pragma unroll
+            for (int mm = 0; mm < CG; ++mm) part[mm & 3] += red[TRANS ? 0 : mm * STRIDE + lane];
+            b -= (part[0] + part[1]) + (part[2] + part[3]);
+            __builtin_amdgcn_wave_barrier();
+        }
+      }
+    } else
     if (have && q0 > 0) {
         T acc[TRANS ? 1 : kWave];
         if (!TRANS) {
@@ -468,13 +660,32 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
         if (q0 + s >= p.nsub) return;    // the same for the whole workgroup
         if (wave == s) {
             T c = UNIT ? b : b * rinv;
+            if constexpr (kPark) {
+                // the parked row comes back in groups of kGroup, each asked for one group ahead of the
+                // steps that use it (left to itself the compiler reads each element right before its
+                // step, and the chain of 64 dependent steps waits for LDS 64 times)
+                constexpr int kGroup = 8;
+                T eb[2][kGroup];
+                auto column = [](int jj) { return OPLOWER ? jj : kWave - 1 - jj; };
 #pragma unroll
-            for (int jj = 0; jj < kWave; ++jj) {
-                const int j = OPLOWER ? jj : kWave - 1 - jj;
-                T ej;
-                if constexpr (kPark) ej = park[wave][j][lane];
-                else ej = e[j];
-                c = fmad(-ej, lane_bcast(c, j), c);
+                for (int k = 0; k < kGroup; ++k) eb[0][k] = park[wave][column(k)][lane];
+#pragma unroll
+                for (int j0 = 0; j0 < kWave; j0 += kGroup) {
+                    if (j0 + kGroup < kWave) {
+#pragma unroll
+                        for (int k = 0; k < kGroup; ++k) eb[(j0 / kGroup + 1) & 1][k] = park[wave][column(j0 + kGroup + k)][lane];
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int k = 0; k < kGroup; ++k) c = fmad(-eb[(j0 / kGroup) & 1][k], lane_bcast(c, column(j0 + k)), c);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            } else {
+#pragma unroll
+                for (int jj = 0; jj < kWave; ++jj) {
+                    const int j = OPLOWER ? jj : kWave - 1 - jj;
+                    c = fmad(-e[j], lane_bcast(c, j), c);
+                }
             }
             xs[wave * kWave + lane] = c;
             Handover<T>::put(p.solved + ((int64_t)q * kWave + lane) * HW, c);     // all 64, zeros past the end
@@ -493,9 +704,9 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
             if (wants(s + 2)) issue(own_c0(s + 2), tile_s);
         }
     };
-    static_assert(NW == 2 || NW == 4, "two tile buffers by turns");
+    static_assert(NW == 1 || NW == 2 || NW == 4, "two tile buffers by turns");
     step(0, pa);
-    step(1, pb);
+    if constexpr (NW >= 2) step(1, pb);
     if constexpr (NW == 4) {
         step(2, pa);
         step(3, pb);
@@ -524,12 +735,19 @@ int trsv_chain(mxb_handle_t h, bool op_lower, bool no_trans, bool unit, int64_t 
     int64_t spin_limit = option(h, MXB_OPT_TRSV_SPIN_LIMIT);
     if (spin_limit > (1 << 30)) spin_limit = 1 << 30;
     const ChainArgs<T> a{(int)n, (int)ceil_div(n, (int64_t)kWave), A, lda, x0, incx, solved, control, (int)spin_limit};
+    // 128-bit loads need rows that begin on 16-byte boundaries
+    const bool wide = reinterpret_cast<uintptr_t>(A) % 16 == 0 && (lda * (int64_t)sizeof(T)) % 16 == 0;
 #define MXB_CHAIN(LOW_, TR_)                                                                                          \
     {                                                                                                                 \
         constexpr int NW = chain_waves<T, TR_>();                                                                     \
         const dim3 grid((unsigned)ceil_div((int64_t)a.nsub, (int64_t)NW)), block(NW * kWave);                         \
-        if (unit) hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, true>), grid, block, 0, h->stream, a);          \
-        else hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, false>), grid, block, 0, h->stream, a);              \
+        if (wide) {                                                                                                   \
+            if (unit) hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, true, true>), grid, block, 0, h->stream, a);    \
+            else hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, false, true>), grid, block, 0, h->stream, a);        \
+        } else {                                                                                                      \
+            if (unit) hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, true, false>), grid, block, 0, h->stream, a);   \
+            else hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, false, false>), grid, block, 0, h->stream, a);       \
+        }                                                                                                             \
     }
     if (op_lower) { if (no_trans) { MXB_CHAIN(true, false) } else { MXB_CHAIN(true, true) } }
     else { if (no_trans) { MXB_CHAIN(false, false) } else { MXB_CHAIN(false, true) } }
@@ -560,12 +778,13 @@ int trsv(mxb_handle_t h, int layout, int uplo, int trans, int diag, int64_t n, c
     constexpr int NW = sizeof(T) == 4 ? 8 : 4;        // 64 registers of triangle + 64 of prefetch per lane: 512 / 256 unknowns
     constexpr int64_t NB = NW * kWave;
     T* x0 = vec_base(x, n, incx);
-    // From where the chained kernel is faster than one launch per block (per call: single precision,
-    // not transposed, n = 128: 10.2 against 15.1 us, 256: 15.6 against 22.1, 384: 19.6 against 28.8;
-    // transposed 128: 9.1 against 8.4, 256 the same, 384: 17.1 against 21.6; double precision 256: 26.7
-    // against 22.3, 384: 32.6 against 38.7).
-    const int64_t chain_min = h->opt[MXB_OPT_TRSV_CHAIN_MIN] > 0 ? h->opt[MXB_OPT_TRSV_CHAIN_MIN] : ((sizeof(T) == 4 && no_trans) ? 65 : 257);
-    if (n >= chain_min && n < ((int64_t)1 << 24))      // 32-bit counts in the chained kernel; no such matrix fits the device anyway
+    // From where the chained kernel is faster than one launch per block (per call, 20 calls back to
+    // back: n = 128 9.3 against 9.5 us in single precision, 8.5 against 8.0 transposed, 11.7 against 12.0
+    // and 10.7 against 10.1 in double precision; n = 192: 10.8 / 9.9 / 13.8 / 12.4 against 12.3 / 10.9 / 16.9 /
+    // 14.9; n = 512: 17.8 against 29.7).
+    const int64_t chain_min = option(h, MXB_OPT_TRSV_CHAIN_MIN);
+    // 32-bit counts in the chained kernel, and 64 rows of a tile within 2^31 bytes of each other; no such matrix fits the device anyway
+    if (n >= chain_min && n < ((int64_t)1 << 24) && lda <= (((int64_t)1 << 25) / (int64_t)sizeof(T)))
         return trsv_chain<T>(h, op_lower, no_trans, unit, n, A, lda, x0, incx);
     h->device_status = nullptr;                      // nothing in the blocked path waits on the device
     const int64_t nblocks = ceil_div(n, NB);

@@ -40,7 +40,7 @@ def test_handle_lifecycle_and_options(B):
     assert B.mxb_set_workspace(h, None, 0) == 0
     assert B.mxb_set_workspace(h, 0x1001, 16) == -1          # not 256-byte aligned
     assert B.mxb_get_option(h, B.OPT_REDUCE_BLOCKS) == 256
-    assert B.mxb_get_option(h, B.OPT_TRSV_SPIN_LIMIT) == 1 << 24 and B.mxb_get_option(h, B.OPT_TRSV_CHAIN_MIN) == 257
+    assert B.mxb_get_option(h, B.OPT_TRSV_SPIN_LIMIT) == 1 << 24 and B.mxb_get_option(h, B.OPT_TRSV_CHAIN_MIN) == 129
     assert B.mxb_last_status(None) == B.ERR_HANDLE
     assert B.mxb_set_option(h, B.OPT_REDUCE_BLOCKS, 7) == 0 and B.mxb_get_option(h, B.OPT_REDUCE_BLOCKS) == 7
     assert B.mxb_set_option(h, B.OPT_REDUCE_BLOCKS, 0) == 0 and B.mxb_get_option(h, B.OPT_REDUCE_BLOCKS) == 256
