@@ -198,12 +198,19 @@ struct Handover<float> {
     {
         __hip_atomic_store(w, (1ull << 32) | __float_as_uint(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    static __device__ __forceinline__ bool get(unsigned long long* w, float& v)
+    // the load and the reading of what came back are apart, so that a caller can ask, do other
+    // things, and only then wait for the answer
+    struct Raw { unsigned long long u; };
+    static __device__ __forceinline__ Raw ask(unsigned long long* w)
     {
-        const unsigned long long u = __hip_atomic_load(w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        v = __uint_as_float((unsigned)u);
-        return (u >> 32) != 0;
+        return Raw{__hip_atomic_load(w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)};
     }
+    static __device__ __forceinline__ bool read(const Raw& r, float& v)
+    {
+        v = __uint_as_float((unsigned)r.u);
+        return (r.u >> 32) != 0;
+    }
+    static __device__ __forceinline__ bool get(unsigned long long* w, float& v) { return read(ask(w), v); }
 };
 template <>
 struct Handover<double> {
@@ -214,14 +221,31 @@ struct Handover<double> {
         __hip_atomic_store(w, (1ull << 32) | (bits & 0xffffffffull), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __hip_atomic_store(w + 1, (1ull << 32) | (bits >> 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    static __device__ __forceinline__ bool get(unsigned long long* w, double& v)
+    struct Raw { unsigned long long lo, hi; };
+    static __device__ __forceinline__ Raw ask(unsigned long long* w)
     {
-        const unsigned long long lo = __hip_atomic_load(w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const unsigned long long hi = __hip_atomic_load(w + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        v = __longlong_as_double((long long)((hi << 32) | (lo & 0xffffffffull)));
-        return (lo >> 32) != 0 && (hi >> 32) != 0;
+        return Raw{__hip_atomic_load(w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT),
+                   __hip_atomic_load(w + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)};
     }
+    static __device__ __forceinline__ bool read(const Raw& r, double& v)
+    {
+        v = __longlong_as_double((long long)((r.hi << 32) | (r.lo & 0xffffffffull)));
+        return (r.lo >> 32) != 0 && (r.hi >> 32) != 0;
+    }
+    static __device__ __forceinline__ bool get(unsigned long long* w, double& v) { return read(ask(w), v); }
 };
+
+// the value of lane s of each lane's group of four
+template <typename T>
+__device__ __forceinline__ T quad_bcast(T v, int s)
+{
+    switch (s) {
+        case 0: return dpp_mov<0x00>(v);
+        case 1: return dpp_mov<0x55>(v);
+        case 2: return dpp_mov<0xAA>(v);
+        default: return dpp_mov<0xFF>(v);
+    }
+}
 
 template <typename T>
 struct ChainArgs {
@@ -299,7 +323,7 @@ __device__ __forceinline__ void load_rows(const T* A, int64_t lda, int first, in
 template <typename T, bool TRANS>
 constexpr int chain_waves() { return 2; }
 
-template <typename T, bool OPLOWER, bool TRANS, bool UNIT, bool WIDE>
+template <typename T, bool OPLOWER, bool TRANS, bool UNIT, bool WIDE, bool AHEAD>
 __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_kernel(const ChainArgs<T> p)
 {
     constexpr int NW = chain_waves<T, TRANS>();
@@ -381,8 +405,40 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
     for (int j = 0; j < kWave; ++j) {
         const bool inside = OPLOWER ? j < lane : j > lane;
         e[j] = inside ? (UNIT ? e[j] : e[j] * rinv) : T(0);
-        if constexpr (kPark) park[wave][j][lane] = e[j];      // read back by this lane only
-        else asm volatile("" : "+v"(e[j]));                   // here, not when the solve needs it
+    }
+    // Four unknowns per step of the substitution: the rows of every group of four lanes are
+    // multiplied by the inverse of the group's own 4 x 4 unit triangle (held by the group itself:
+    // quad permutes), which makes that triangle the identity.  The four unknowns of a group then no
+    // longer depend on each other, and a step is four independent broadcasts and four multiply-adds
+    // instead of four rounds of broadcast-then-multiply-add, each waiting for the one before.  The
+    // right-hand side takes the same 4 x 4 product when the solve begins (qinv).
+    T qinv[4];
+    {
+        const int r = lane & 3;
+        T nq[4] = {T(0), T(0), T(0), T(0)};      // my row of my group's triangle, without the diagonal
+#pragma unroll
+        for (int j = 0; j < kWave; ++j) nq[j & 3] = (j >> 2) == (lane >> 2) ? e[j] : nq[j & 3];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) qinv[k] = k == r ? T(1) : T(0);
+        // row r of the inverse: unit vector r minus the earlier (lower) or later (upper) rows, each final in its turn
+#pragma unroll
+        for (int ss = 0; ss < 3; ++ss) {
+            const int sidx = OPLOWER ? ss : 3 - ss;
+            const T coef = (OPLOWER ? r > sidx : r < sidx) ? nq[sidx] : T(0);
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                if (OPLOWER ? k <= sidx : k >= sidx) qinv[k] = fmad(-coef, quad_bcast(qinv[k], sidx), qinv[k]);
+        }
+#pragma unroll
+        for (int j = 0; j < kWave; ++j) {
+            const bool beyond = OPLOWER ? j < (lane & ~3) : j > (lane | 3);      // outside my group's triangle
+            T v = qinv[0] * quad_bcast(e[j], 0);
+#pragma unroll
+            for (int k = 1; k < 4; ++k) v = fmad(qinv[k], quad_bcast(e[j], k), v);
+            e[j] = beyond ? v : T(0);
+            if constexpr (kPark) park[wave][j][lane] = e[j];      // read back by this lane only
+            else asm volatile("" : "+v"(e[j]));                   // here, not when the solve needs it
+        }
     }
     // the first two tiles of my own workgroup are made ready now as well: turning a tile through LDS
     // between two steps takes a wavefront longer than the solving wavefront needs for its step
@@ -468,13 +524,26 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
 #pragma unroll
             for (int k = 0; k < CG; ++k) acc[TRANS ? 0 : k] = T(0);
         }
+        // Where memory is slow to answer (AHEAD: a matrix larger than the last-level cache), the
+        // solutions of the next tile are asked for once before the next piece is, and the answer is
+        // read after.  Loads return in order, so a poll behind a piece just asked for comes back when
+        // the piece does, and a wavefront that has fallen behind the chain, whose solutions are there
+        // already, would wait for the piece for nothing; a wait for the answer before the next piece
+        // is asked for would wait for the piece before it, leaving one piece in flight instead of
+        // two.  (n = 16384, transposed: 361 -> 340 us, double precision 700 -> 636 and 698 -> 665; single
+        // precision not transposed, where a tile follows the last one along the same rows: 328 -> 340,
+        // and n = 4096: 83 -> 88, so neither asks ahead.)
+        auto ask_x = [&](int qq) { return Handover<T>::ask(p.solved + ((int64_t)qq * kWave + lane) * HW); };
+        typename Handover<T>::Raw ahead;
+        if (AHEAD) ahead = ask_x(0);
+
         auto usev = [&](auto piece, int ch, vec_t (&raw)[NL]) {
             constexpr int PIECE = decltype(piece)::value, H0 = PIECE * RH;
             const int qq = ch / CPT, cblk = actual(qq) * kWave;
             const int row0 = (TRANS ? cblk : r0) + H0, col0 = TRANS ? r0 : cblk;
             if (PIECE == 0) {
                 T xv;
-                const bool got = look(qq, xv);
+                const bool got = AHEAD ? Handover<T>::read(ahead, xv) : look(qq, xv);
                 wait_x(qq, xv, got);
                 __builtin_amdgcn_wave_barrier();      // my earlier reads of the buffer come first
                 xb[lane] = xv;
@@ -513,6 +582,7 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
                     acc[TRANS ? 0 : PIECE * NL + t] = sum;
                 }
             }
+            if (AHEAD && PIECE == CPT - 1 && qq + 1 < q0) ahead = ask_x(qq + 1);
         };
         const int nch = q0 * CPT;
         vec_t t0[NL], t1[NL];
@@ -660,13 +730,19 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
         if (q0 + s >= p.nsub) return;    // the same for the whole workgroup
         if (wave == s) {
             T c = UNIT ? b : b * rinv;
+            {
+                T t = qinv[0] * quad_bcast(c, 0);
+#pragma unroll
+                for (int k = 1; k < 4; ++k) t = fmad(qinv[k], quad_bcast(c, k), t);
+                c = t;
+            }
+            auto column = [](int jj) { return OPLOWER ? jj : kWave - 1 - jj; };
             if constexpr (kPark) {
                 // the parked row comes back in groups of kGroup, each asked for one group ahead of the
                 // steps that use it (left to itself the compiler reads each element right before its
-                // step, and the chain of 64 dependent steps waits for LDS 64 times)
+                // step, and the chain of dependent steps waits for LDS every time)
                 constexpr int kGroup = 8;
                 T eb[2][kGroup];
-                auto column = [](int jj) { return OPLOWER ? jj : kWave - 1 - jj; };
 #pragma unroll
                 for (int k = 0; k < kGroup; ++k) eb[0][k] = park[wave][column(k)][lane];
 #pragma unroll
@@ -677,14 +753,23 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
                     }
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int k = 0; k < kGroup; ++k) c = fmad(-eb[(j0 / kGroup) & 1][k], lane_bcast(c, column(j0 + k)), c);
+                    for (int k0 = 0; k0 < kGroup; k0 += 4) {
+                        T xq[4];
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) xq[k] = lane_bcast(c, column(j0 + k0 + k));
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) c = fmad(-eb[(j0 / kGroup) & 1][k0 + k], xq[k], c);
+                    }
                     __builtin_amdgcn_sched_barrier(0);
                 }
             } else {
 #pragma unroll
-                for (int jj = 0; jj < kWave; ++jj) {
-                    const int j = OPLOWER ? jj : kWave - 1 - jj;
-                    c = fmad(-e[j], lane_bcast(c, j), c);
+                for (int j0 = 0; j0 < kWave; j0 += 4) {
+                    T xq[4];
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) xq[k] = lane_bcast(c, column(j0 + k));
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) c = fmad(-e[column(j0 + k)], xq[k], c);
                 }
             }
             xs[wave * kWave + lane] = c;
@@ -715,6 +800,8 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
 
 // Workspace of the one-kernel solve: the hand-over words of every sub-block, then the ticket and
 // the error word.
+constexpr int64_t kChainAskAheadBytes = (int64_t)384 << 20;   // between 8192 and 12288 in single precision, 6144 and 8192 in double
+
 template <typename T>
 inline size_t chain_bytes(int64_t n) { return (size_t)ceil_div(n, (int64_t)kWave) * kWave * Handover<T>::kWords * 8 + 2 * sizeof(int); }
 
@@ -734,6 +821,7 @@ int trsv_chain(mxb_handle_t h, bool op_lower, bool no_trans, bool unit, int64_t 
     h->device_status = control + 1;
     int64_t spin_limit = option(h, MXB_OPT_TRSV_SPIN_LIMIT);
     if (spin_limit > (1 << 30)) spin_limit = 1 << 30;
+    const bool ask_ahead = (!no_trans || sizeof(T) == 8) && n * n * (int64_t)sizeof(T) >= kChainAskAheadBytes;
     const ChainArgs<T> a{(int)n, (int)ceil_div(n, (int64_t)kWave), A, lda, x0, incx, solved, control, (int)spin_limit};
     // 128-bit loads need rows that begin on 16-byte boundaries
     const bool wide = reinterpret_cast<uintptr_t>(A) % 16 == 0 && (lda * (int64_t)sizeof(T)) % 16 == 0;
@@ -741,12 +829,17 @@ int trsv_chain(mxb_handle_t h, bool op_lower, bool no_trans, bool unit, int64_t 
     {                                                                                                                 \
         constexpr int NW = chain_waves<T, TR_>();                                                                     \
         const dim3 grid((unsigned)ceil_div((int64_t)a.nsub, (int64_t)NW)), block(NW * kWave);                         \
-        if (wide) {                                                                                                   \
-            if (unit) hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, true, true>), grid, block, 0, h->stream, a);    \
-            else hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, false, true>), grid, block, 0, h->stream, a);        \
+        if (wide && ask_ahead) {                                                                                      \
+            if constexpr (TR_ || sizeof(T) == 8) {      /* the others never ask ahead */                              \
+                if (unit) hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, true, true, true>), grid, block, 0, h->stream, a);   \
+                else hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, false, true, true>), grid, block, 0, h->stream, a);       \
+            }                                                                                                         \
+        } else if (wide) {                                                                                            \
+            if (unit) hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, true, true, false>), grid, block, 0, h->stream, a);  \
+            else hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, false, true, false>), grid, block, 0, h->stream, a);      \
         } else {                                                                                                      \
-            if (unit) hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, true, false>), grid, block, 0, h->stream, a);   \
-            else hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, false, false>), grid, block, 0, h->stream, a);       \
+            if (unit) hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, true, false, false>), grid, block, 0, h->stream, a); \
+            else hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, false, false, false>), grid, block, 0, h->stream, a);     \
         }                                                                                                             \
     }
     if (op_lower) { if (no_trans) { MXB_CHAIN(true, false) } else { MXB_CHAIN(true, true) } }
