@@ -330,10 +330,13 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
     constexpr int V = 16 / (int)sizeof(T);       // elements of a 128-bit load
     __shared__ __attribute__((aligned(16))) T xs[NW * kWave];
     __shared__ __attribute__((aligned(16))) T fold[(TRANS && WIDE) ? NW : 1][(TRANS && WIDE) ? V * kWave : 1];
-    // per-wavefront buffers: one turns tiles when not transposed; in double precision, where the
-    // registers are short, another holds the wavefront's finished diagonal rows (not needed on the
-    // element-wise transposed path, which keeps them in registers without spilling)
-    constexpr bool kPark = sizeof(T) == 8 && (!TRANS || WIDE);
+    // per-wavefront buffers: one turns tiles when not transposed; where the registers are short another
+    // holds the wavefront's finished diagonal rows: double precision (but not on the element-wise
+    // transposed path, which keeps them in registers without spilling), and the single precision
+    // transposed kernel that asks ahead (23 registers spilled otherwise, n = 16384: 557 us instead of 313;
+    // its sibling that does not ask ahead spills 5 and is faster so than parked, n = 4096: 73 against 80 us)
+    constexpr bool NEAR = WIDE && sizeof(T) == 4;
+    constexpr bool kPark = (sizeof(T) == 8 && (!TRANS || WIDE)) || (NEAR && TRANS && AHEAD);
     __shared__ __attribute__((aligned(16))) T tile[TRANS ? 1 : NW][TRANS ? 1 : kWave][TRANS ? 1 : kWave + 1];
     __shared__ T park[kPark ? NW : 1][kPark ? kWave : 1][kPark ? kWave + 1 : 1];
     __shared__ int my_ticket;
@@ -391,6 +394,13 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
     auto wants = [&](int s) { return s < NW - 1 && have && wave > s && q0 + s < p.nsub; };
     if (wants(0)) issue(own_c0(0), pa);
     if (wants(1)) issue(own_c0(1), pb);
+    // NEAR: the last tile before my workgroup's own, the one whose solutions arrive last and that the
+    // first solve of the workgroup waits for, is taken like a tile of my own workgroup: fetched now,
+    // turned so that a lane holds its row, and applied from LDS when the solutions are there (single
+    // precision; in double precision the registers do not hold another tile)
+    T pc[NEAR ? kWave : 1];
+    const bool near_tile = NEAR && have && q0 > 0;
+    if constexpr (NEAR) { if (near_tile) issue(actual(q0 - 1) * kWave, pc); }
 
     // My row of the diagonal tile, scaled by 1 / T[i][i] as in the blocked kernel.  Before the
     // wait for the earlier workgroups, which is where a workgroup has time to spare: in single
@@ -444,6 +454,7 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
     // between two steps takes a wavefront longer than the solving wavefront needs for its step
     if (wants(0)) finish(own_c0(0), pa);
     if (wants(1)) finish(own_c0(1), pb);
+    if constexpr (NEAR) { if (near_tile) finish(actual(q0 - 1) * kWave, pc); }
 
     // ---- the unknowns of earlier workgroups: tiles 0 .. q0 - 1 of my block row, in solving order.
     // A tile travels in pieces of RH rows (columns if transposed), two pieces in flight by turns;
@@ -471,7 +482,8 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
         }
     };
     if constexpr (WIDE) {
-      if (have && q0 > 0) {
+      const int nstream = NEAR ? q0 - 1 : q0;     // tiles taken by the streaming loop
+      if (have && nstream > 0) {
         // 128-bit loads: lane (g, m), g = lane / CG, m = lane % CG, fetches for t < NL the V elements
         // at memory row row0 + g * NL + t, columns col0 + m * V .., of a piece of RH = V * NL rows, so
         // a piece is NL loads instead of RH (a wavefront alone on its SIMD unit issues slowly, and
@@ -562,17 +574,14 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
                         raw[t][v] = (row0 + g * NL + t < p.n && col0 + m * V + v < p.n) ? raw[t][v] : T(0);
             }
             if (TRANS) {
-                T xk[NL];
 #pragma unroll
                 for (int t = 0; t < NL; t += V) {
                     const vec_t xq = *reinterpret_cast<const vec_t*>(xb + H0 + g * NL + t);
 #pragma unroll
-                    for (int v = 0; v < V; ++v) xk[t + v] = xq[v];
+                    for (int u = 0; u < V; ++u)
+#pragma unroll
+                        for (int v = 0; v < V; ++v) pv[v] = fmad(raw[t + u][v], xq[u], pv[v]);
                 }
-#pragma unroll
-                for (int t = 0; t < NL; ++t)
-#pragma unroll
-                    for (int v = 0; v < V; ++v) pv[v] = fmad(raw[t][v], xk[t], pv[v]);
             } else {
 #pragma unroll
                 for (int t = 0; t < NL; ++t) {
@@ -582,9 +591,9 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
                     acc[TRANS ? 0 : PIECE * NL + t] = sum;
                 }
             }
-            if (AHEAD && PIECE == CPT - 1 && qq + 1 < q0) ahead = ask_x(qq + 1);
+            if (AHEAD && PIECE == CPT - 1 && qq + 1 < nstream) ahead = ask_x(qq + 1);
         };
-        const int nch = q0 * CPT;
+        const int nch = nstream * CPT;
         vec_t t0[NL], t1[NL];
         startv(0, t0);
         if (nch > 1) startv(1, t1);
@@ -633,6 +642,23 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
             for (int mm = 0; mm < CG; ++mm) part[mm & 3] += red[TRANS ? 0 : mm * STRIDE + lane];
             b -= (part[0] + part[1]) + (part[2] + part[3]);
             __builtin_amdgcn_wave_barrier();
+        }
+      }
+      if constexpr (NEAR) {
+        if (near_tile) {
+            T* const xb = xs + wave * kWave;
+            T xv;
+            const bool got = look(q0 - 1, xv);
+            wait_x(q0 - 1, xv, got);
+            __builtin_amdgcn_wave_barrier();
+            xb[lane] = xv;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            T part[4] = {T(0), T(0), T(0), T(0)};
+#pragma unroll
+            for (int j = 0; j < kWave; ++j) part[j & 3] = fmad(pc[NEAR ? j : 0], xb[j], part[j & 3]);
+            b -= (part[0] + part[1]) + (part[2] + part[3]);
         }
       }
     } else
