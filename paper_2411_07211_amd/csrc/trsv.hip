@@ -330,15 +330,18 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
     constexpr int V = 16 / (int)sizeof(T);       // elements of a 128-bit load
     __shared__ __attribute__((aligned(16))) T xs[NW * kWave];
     __shared__ __attribute__((aligned(16))) T fold[(TRANS && WIDE) ? NW : 1][(TRANS && WIDE) ? V * kWave : 1];
-    // per-wavefront buffers: one turns tiles when not transposed; where the registers are short another
-    // holds the wavefront's finished diagonal rows: double precision (but not on the element-wise
-    // transposed path, which keeps them in registers without spilling), and the single precision
-    // transposed kernel that asks ahead (23 registers spilled otherwise, n = 16384: 557 us instead of 313;
-    // its sibling that does not ask ahead spills 5 and is faster so than parked, n = 4096: 73 against 80 us)
+    // per-wavefront buffers: one turns tiles when not transposed; in double precision, where the
+    // registers are short, another holds the wavefront's finished diagonal rows (not needed on the
+    // element-wise transposed path, which keeps them in registers without spilling); transposed,
+    // single precision, a third holds the tile next to the workgroup's own while the others stream
+    // (kept in registers, the kernel spills 4 to 23 of them, and 14 are enough to take n = 4096 from
+    // 72 to 105 us)
     constexpr bool NEAR = WIDE && sizeof(T) == 4;
-    constexpr bool kPark = (sizeof(T) == 8 && (!TRANS || WIDE)) || (NEAR && TRANS && AHEAD);
+    constexpr bool kPark = sizeof(T) == 8 && (!TRANS || WIDE);
+    constexpr bool kParkNear = NEAR && TRANS;
     __shared__ __attribute__((aligned(16))) T tile[TRANS ? 1 : NW][TRANS ? 1 : kWave][TRANS ? 1 : kWave + 1];
     __shared__ T park[kPark ? NW : 1][kPark ? kWave : 1][kPark ? kWave + 1 : 1];
+    __shared__ T near_park[kParkNear ? NW : 1][kParkNear ? kWave : 1][kParkNear ? kWave + 1 : 1];
     __shared__ int my_ticket;
     constexpr int HW = Handover<T>::kWords;
     int* const ticket = p.control;
@@ -454,7 +457,15 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
     // between two steps takes a wavefront longer than the solving wavefront needs for its step
     if (wants(0)) finish(own_c0(0), pa);
     if (wants(1)) finish(own_c0(1), pb);
-    if constexpr (NEAR) { if (near_tile) finish(actual(q0 - 1) * kWave, pc); }
+    if constexpr (NEAR) {
+        if (near_tile) {
+            finish(actual(q0 - 1) * kWave, pc);
+            if constexpr (kParkNear) {
+#pragma unroll
+                for (int j = 0; j < kWave; ++j) near_park[wave][j][lane] = pc[j];      // read back by this lane only
+            }
+        }
+    }
 
     // ---- the unknowns of earlier workgroups: tiles 0 .. q0 - 1 of my block row, in solving order.
     // A tile travels in pieces of RH rows (columns if transposed), two pieces in flight by turns;
@@ -647,6 +658,12 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
       if constexpr (NEAR) {
         if (near_tile) {
             T* const xb = xs + wave * kWave;
+            if constexpr (kParkNear) {            // back into the registers that the streamed tiles have left
+#pragma unroll
+                for (int j = 0; j < kWave; ++j) pc[j] = near_park[wave][j][lane];
+#pragma unroll
+                for (int j = 0; j < kWave; ++j) asm volatile("" : "+v"(pc[j]));
+            }
             T xv;
             const bool got = look(q0 - 1, xv);
             wait_x(q0 - 1, xv, got);
