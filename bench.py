@@ -599,7 +599,7 @@ CALL_KERNELS = {
     "ssymv_l_16384": SWEEP("float", 4, "false", 0), "sger_16384": ["ger_kernel<float, 4, false>"],
     "strmv_ut_16384": SWEEP("float", 4, "true", 1), "strmv_lt_16384": SWEEP("float", 4, "false", 1),
     "ssymv_u_16384": SWEEP("float", 4, "true", 0), "dsymv_l_16384": SWEEP("double", 2, "false", 0),
-    "strsv_ln_16384": ["trsv_chain_init_kernel", "trsv_chain_kernel<float, true, false, true, true, false>"],
+    "strsv_ln_16384": ["trsv_chain_init_kernel", "trsv_chain_kernel<float, true, false, true, true, true>"],
     "strsv_lt_16384": ["trsv_chain_init_kernel", "trsv_chain_kernel<float, false, true, true, true, true>"],
     "probe_copy": ["probe_copy_kernel"], "probe_read": ["probe_read_kernel"],
 }

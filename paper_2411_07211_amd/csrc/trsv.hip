@@ -553,9 +553,8 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
         // the piece does, and a wavefront that has fallen behind the chain, whose solutions are there
         // already, would wait for the piece for nothing; a wait for the answer before the next piece
         // is asked for would wait for the piece before it, leaving one piece in flight instead of
-        // two.  (n = 16384, transposed: 361 -> 340 us, double precision 700 -> 636 and 698 -> 665; single
-        // precision not transposed, where a tile follows the last one along the same rows: 328 -> 340,
-        // and n = 4096: 83 -> 88, so neither asks ahead.)
+        // two.  (n = 16384, transposed: 361 -> 340 us, double precision 700 -> 636 and 698 -> 665; smaller
+        // matrices lose: n = 4096 transposed 73 -> 77 us.)
         auto ask_x = [&](int qq) { return Handover<T>::ask(p.solved + ((int64_t)qq * kWave + lane) * HW); };
         typename Handover<T>::Raw ahead;
         if (AHEAD) ahead = ask_x(0);
@@ -843,7 +842,11 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
 
 // Workspace of the one-kernel solve: the hand-over words of every sub-block, then the ticket and
 // the error word.
-constexpr int64_t kChainAskAheadBytes = (int64_t)384 << 20;   // between 8192 and 12288 in single precision, 6144 and 8192 in double
+// From where asking ahead pays (see the kernel): transposed between n = 8192 and 12288 in single precision
+// (132 against 140 us, 263 against 232), in double precision between 6144 and 8192 (203 / 187 against 216 / 199 us, 328 /
+// 326 against 319 / 302); single precision not transposed, where a tile follows the last one along the same rows and
+// memory answers sooner, from 4096 (upper: 82 against 79 us, 8192: 150 against 143, 16384: 318 against 302).
+constexpr int64_t kChainAskAheadBytes = (int64_t)384 << 20, kChainAskAheadBytesAlongRows = (int64_t)64 << 20;
 
 template <typename T>
 inline size_t chain_bytes(int64_t n) { return (size_t)ceil_div(n, (int64_t)kWave) * kWave * Handover<T>::kWords * 8 + 2 * sizeof(int); }
@@ -864,7 +867,7 @@ int trsv_chain(mxb_handle_t h, bool op_lower, bool no_trans, bool unit, int64_t 
     h->device_status = control + 1;
     int64_t spin_limit = option(h, MXB_OPT_TRSV_SPIN_LIMIT);
     if (spin_limit > (1 << 30)) spin_limit = 1 << 30;
-    const bool ask_ahead = (!no_trans || sizeof(T) == 8) && n * n * (int64_t)sizeof(T) >= kChainAskAheadBytes;
+    const bool ask_ahead = n * n * (int64_t)sizeof(T) >= ((sizeof(T) == 4 && no_trans) ? kChainAskAheadBytesAlongRows : kChainAskAheadBytes);
     const ChainArgs<T> a{(int)n, (int)ceil_div(n, (int64_t)kWave), A, lda, x0, incx, solved, control, (int)spin_limit};
     // 128-bit loads need rows that begin on 16-byte boundaries
     const bool wide = reinterpret_cast<uintptr_t>(A) % 16 == 0 && (lda * (int64_t)sizeof(T)) % 16 == 0;
@@ -873,7 +876,7 @@ int trsv_chain(mxb_handle_t h, bool op_lower, bool no_trans, bool unit, int64_t 
         constexpr int NW = chain_waves<T, TR_>();                                                                     \
         const dim3 grid((unsigned)ceil_div((int64_t)a.nsub, (int64_t)NW)), block(NW * kWave);                         \
         if (wide && ask_ahead) {                                                                                      \
-            if constexpr (TR_ || sizeof(T) == 8) {      /* the others never ask ahead */                              \
+            {                                                                                                         \
                 if (unit) hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, true, true, true>), grid, block, 0, h->stream, a);   \
                 else hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, false, true, true>), grid, block, 0, h->stream, a);       \
             }                                                                                                         \
