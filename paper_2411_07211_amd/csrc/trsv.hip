@@ -332,11 +332,11 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
     __shared__ __attribute__((aligned(16))) T fold[(TRANS && WIDE) ? NW : 1][(TRANS && WIDE) ? V * kWave : 1];
     // per-wavefront buffers: one turns tiles when not transposed; in double precision, where the
     // registers are short, another holds the wavefront's finished diagonal rows (not needed on the
-    // element-wise transposed path, which keeps them in registers without spilling); transposed,
-    // single precision, a third holds the tile next to the workgroup's own while the others stream
-    // (kept in registers, the kernel spills 4 to 23 of them, and 14 are enough to take n = 4096 from
-    // 72 to 105 us)
-    constexpr bool NEAR = WIDE && sizeof(T) == 4;
+    // element-wise transposed path, which keeps them in registers without spilling); transposed, a
+    // third holds the tile next to the workgroup's own while the others stream (kept in registers,
+    // the single precision kernel spills 4 to 23 of them, and 14 are enough to take n = 4096 from 72
+    // to 105 us)
+    constexpr bool NEAR = WIDE && (sizeof(T) == 4 || TRANS);
     constexpr bool kPark = sizeof(T) == 8 && (!TRANS || WIDE);
     constexpr bool kParkNear = NEAR && TRANS;
     __shared__ __attribute__((aligned(16))) T tile[TRANS ? 1 : NW][TRANS ? 1 : kWave][TRANS ? 1 : kWave + 1];
@@ -399,8 +399,9 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
     if (wants(1)) issue(own_c0(1), pb);
     // NEAR: the last tile before my workgroup's own, the one whose solutions arrive last and that the
     // first solve of the workgroup waits for, is taken like a tile of my own workgroup: fetched now,
-    // turned so that a lane holds its row, and applied from LDS when the solutions are there (single
-    // precision; in double precision the registers do not hold another tile)
+    // turned so that a lane holds its row, and applied from LDS when the solutions are there (not in
+    // double precision when not transposed: the tile waits in LDS while the others stream, and there
+    // the turning buffer and the parked diagonal rows leave no room for it)
     T pc[NEAR ? kWave : 1];
     const bool near_tile = NEAR && have && q0 > 0;
     if constexpr (NEAR) { if (near_tile) issue(actual(q0 - 1) * kWave, pc); }
