@@ -644,6 +644,16 @@ def test_trsv(blas, ctx, dt, layout, uplo, trans, diag):
     trsv_case(blas, ctx, dt, layout, uplo, trans, diag, 5000, 0, 1)      # the default choice at a size with many workgroups
 
 
+def test_trsv_matrices_beyond_the_last_level_cache(blas, ctx):
+    """From 384 MiB on (64 MiB in single precision, not transposed, which test_trsv's n = 5000 covers) the
+    chained kernel asks for a tile's solutions ahead of the next piece; ragged last blocks, both triangles."""
+    for dt, n, pad in ((np.float32, 10250, 2), (np.float64, 7170, 2)):
+        for uplo, trans, diag in ((O.LOWER, O.TRANS, O.NON_UNIT), (O.UPPER, O.TRANS, O.UNIT)):
+            trsv_case(blas, ctx, dt, O.ROW_MAJOR, uplo, trans, diag, n, pad, 1)
+    for uplo, diag in ((O.LOWER, O.UNIT), (O.UPPER, O.NON_UNIT)):
+        trsv_case(blas, ctx, np.float64, O.ROW_MAJOR, uplo, O.NO_TRANS, diag, 7170, 2, 1)
+
+
 def test_trsv_bounded_wait_reports_timeout(blas, ctx):
     """A wait that the host makes too short to succeed: every wavefront still leaves the kernel, the
     call returns, mxb_last_status names the timeout, and the next call with the default limit is right."""
