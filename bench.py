@@ -149,6 +149,7 @@ class Suite:
         # ---- structured level 2, fp32, n = 16384, seed 4 ---------------------------------------
         x0 = uni(NS, f32, 410)
         xt = x0.clone()
+        xdt = xd.clone()
         tri = NS * (NS + 1) // 2
         for uname, uplo in (("u", B.UPPER), ("l", B.LOWER)):
             for dname, diag in (("n", B.NON_UNIT), ("u", B.UNIT)):
@@ -162,7 +163,7 @@ class Suite:
                  4 * (tri + 3 * NS))
         self.add(f"sger_{NS}", "ger", lambda s: B.mxb_sger(h, B.ROW_MAJOR, NS, NS, 1e-3, xs, 1, x0, 1, nextA(A32), NS),
                  4 * (2 * NS * NS + 2 * NS))
-        self.keep = (A32, A64, xs, ys, xd, yd, x0, xt)
+        self.keep = (A32, A64, xs, ys, xd, yd, x0, xt, xdt)
 
         # ---- bandwidth probes: not part of a step, selectable with --only ----------------------
         nb = NS * NS * 4
@@ -179,6 +180,11 @@ class Suite:
              4 * (tri + 3 * NS), None),
             (f"dsymv_l_{NS}", "symv", lambda s: B.mxb_dsymv(h, B.ROW_MAJOR, B.LOWER, NS, 0.52, nextA(A64), lda, xd, 1, 0.49, yd, 1),
              8 * (tri + 3 * NS), None),
+            # the same matrices with rows that begin on 128-byte boundaries (lda = n): the odd pitch of 16392 costs the sweep 8-12 %
+            (f"dsymv_u_{NS}_dense", "symv", lambda s: B.mxb_dsymv(h, B.ROW_MAJOR, B.UPPER, NS, 0.52, nextA(A64), NS, xd, 1, 0.49, yd, 1),
+             8 * (tri + 3 * NS), None),
+            (f"dtrmv_lt_{NS}_dense", "trmv_t", lambda s: B.mxb_dtrmv(h, B.ROW_MAJOR, B.LOWER, B.TRANS, B.NON_UNIT, NS, nextA(A64), NS, xdt, 1),
+             8 * (tri + 2 * NS), lambda: xdt.copy_(xd)),
             # trsv: unit diagonal over small off-diagonal elements (a random triangle is exponentially ill conditioned)
             (f"strsv_ln_{NS}", "trsv", lambda s: B.mxb_strsv(h, B.ROW_MAJOR, B.LOWER, B.NO_TRANS, B.UNIT, NS, self.small(), NS, xt, 1),
              4 * (tri - NS + 2 * NS), reset),
@@ -599,6 +605,7 @@ CALL_KERNELS = {
     "ssymv_l_16384": SWEEP("float", 4, "false", 0), "sger_16384": ["ger_kernel<float, 4, false>"],
     "strmv_ut_16384": SWEEP("float", 4, "true", 1), "strmv_lt_16384": SWEEP("float", 4, "false", 1),
     "ssymv_u_16384": SWEEP("float", 4, "true", 0), "dsymv_l_16384": SWEEP("double", 2, "false", 0),
+    "dsymv_u_16384_dense": SWEEP("double", 2, "true", 0), "dtrmv_lt_16384_dense": SWEEP("double", 2, "false", 1),
     "strsv_ln_16384": ["trsv_chain_init_kernel", "trsv_chain_kernel<float, true, false, true, true, true>"],
     "strsv_lt_16384": ["trsv_chain_init_kernel", "trsv_chain_kernel<float, false, true, true, true, true>"],
     "probe_copy": ["probe_copy_kernel"], "probe_read": ["probe_read_kernel"],
@@ -610,7 +617,7 @@ TRAFFIC_CALLS = ["sgemv_n_16384_b0", "sgemv_t_16384_b0", "dgemv_n_16384", "dgemv
                  "probe_copy", "probe_read"]
 TRAFFIC_KERNELS = {c: CALL_KERNELS[c] for c in TRAFFIC_CALLS}
 TRAFFIC_ONLY = ",".join(TRAFFIC_KERNELS)
-EXTRA_ONLY = "strmv_ut_16384,strmv_lt_16384,ssymv_u_16384,dsymv_l_16384,strsv_ln_16384,strsv_lt_16384,probe_copy,probe_read"
+EXTRA_ONLY = "strmv_ut_16384,strmv_lt_16384,ssymv_u_16384,dsymv_l_16384,dsymv_u_16384_dense,dtrmv_lt_16384_dense,strsv_ln_16384,strsv_lt_16384,probe_copy,probe_read"
 # (title of the summary, file, [(row label, call, algorithmic bytes)])
 PROFILE_TABLES = [
     ("gemv at 16384 x 16384 (fp32; fp64 with lda = 16392), 1048576 x 256, 1024 x 1024, and the bandwidth probes", "gemv_16384_rocprofv3.md", [
@@ -623,12 +630,13 @@ PROFILE_TABLES = [
         ("sgemv T 1048576x256", "sgemv_t_1048576x256_b0", 4 * ((1 << 20) * 256 + 256 + (1 << 20))),
         ("sgemv N 1024^2 (cache-resident, launch-bound)", "sgemv_n_1024", 4 * (1024 * 1024 + 3 * 1024)),
         ("probe_read 1 GiB", "probe_read", NS_ * NS_ * 4), ("probe_copy 1 GiB", "probe_copy", 2 * NS_ * NS_ * 4)]),
-    ("trmv, symv, ger and trsv at n = 16384 (fp32; dsymv with lda = 16392)", "triangular_16384_rocprofv3.md", [
+    ("trmv, symv, ger and trsv at n = 16384 (fp32; dsymv and dtrmv with lda = 16392 and 16384)", "triangular_16384_rocprofv3.md", [
         ("strmv upper N non-unit", "strmv_un_16384", 4 * (TRI_ + 2 * NS_)), ("strmv upper N unit", "strmv_uu_16384", 4 * (TRI_ + NS_)),
         ("strmv lower N non-unit", "strmv_ln_16384", 4 * (TRI_ + 2 * NS_)), ("strmv lower N unit", "strmv_lu_16384", 4 * (TRI_ + NS_)),
         ("strmv upper T non-unit", "strmv_ut_16384", 4 * (TRI_ + 2 * NS_)), ("strmv lower T non-unit", "strmv_lt_16384", 4 * (TRI_ + 2 * NS_)),
         ("ssymv lower", "ssymv_l_16384", 4 * (TRI_ + 3 * NS_)), ("ssymv upper", "ssymv_u_16384", 4 * (TRI_ + 3 * NS_)),
-        ("dsymv lower lda 16392", "dsymv_l_16384", 8 * (TRI_ + 3 * NS_)), ("sger 16384^2", "sger_16384", 4 * (2 * NS_ * NS_ + 2 * NS_)),
+        ("dsymv lower lda 16392", "dsymv_l_16384", 8 * (TRI_ + 3 * NS_)), ("dsymv upper lda 16384", "dsymv_u_16384_dense", 8 * (TRI_ + 3 * NS_)),
+        ("dtrmv lower T non-unit lda 16384", "dtrmv_lt_16384_dense", 8 * (TRI_ + 2 * NS_)), ("sger 16384^2", "sger_16384", 4 * (2 * NS_ * NS_ + 2 * NS_)),
         ("strsv lower N unit (latency-bound chain)", "strsv_ln_16384", 4 * (TRI_ + NS_)),
         ("strsv lower T unit (latency-bound chain)", "strsv_lt_16384", 4 * (TRI_ + NS_))]),
     ("level-1 routines at n = 2^28 (unit stride and incx = 2 / incy = 3)", "level1_n2p28_rocprofv3.md", [
