@@ -175,9 +175,11 @@ void launch_trsv_diag(mxb_handle_t h, bool op_lower, bool unit, const TrsvArgs<T
 // limit while a tile was 64 loads of one element per lane (per tile: 0.8 to 1.2 us to issue the
 // loads, 0.3 to 0.6 us of polls queued behind them, since loads return in order, and 0.5 us of
 // broadcasts and multiply-adds when transposed; the wavefront that a workgroup's first solve
-// waits for began to look for the last solutions 3 us after they were there).  Rows that begin on
-// 16-byte boundaries are therefore read with 128-bit loads (WIDE, below); others keep the
-// element-wise path.
+// waits for began to look for the last solutions 3 us after they were there).  The streamed tiles
+// are therefore read with 128-bit loads, 16 per tile, whatever the pitch and the base address
+// (a matrix load needs element alignment only; rows that begin off a 16-byte boundary cost nothing
+// measurable: n = 8192, lda = 8193 against 8196: 144.5 / 130.7 against 145.2 / 129.8 us, and the
+// element-wise loads that used to serve them took 226 / 185).
 //
 // Solutions travel between workgroups in words that validate themselves: the solver stores
 // {value bits, tag} as one 64-bit device-scope atomic (two words, one per half, for a double), a
@@ -323,21 +325,21 @@ __device__ __forceinline__ void load_rows(const T* A, int64_t lda, int first, in
 template <typename T, bool TRANS>
 constexpr int chain_waves() { return 2; }
 
-template <typename T, bool OPLOWER, bool TRANS, bool UNIT, bool WIDE, bool AHEAD>
+template <typename T, bool OPLOWER, bool TRANS, bool UNIT, bool AHEAD>
 __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_kernel(const ChainArgs<T> p)
 {
     constexpr int NW = chain_waves<T, TRANS>();
     constexpr int V = 16 / (int)sizeof(T);       // elements of a 128-bit load
     __shared__ __attribute__((aligned(16))) T xs[NW * kWave];
-    __shared__ __attribute__((aligned(16))) T fold[(TRANS && WIDE) ? NW : 1][(TRANS && WIDE) ? V * kWave : 1];
+    __shared__ __attribute__((aligned(16))) T fold[TRANS ? NW : 1][TRANS ? V * kWave : 1];
     // per-wavefront buffers: one turns tiles when not transposed; in double precision, where the
     // registers are short, another holds the wavefront's finished diagonal rows (not needed on the
     // element-wise transposed path, which keeps them in registers without spilling); transposed, a
     // third holds the tile next to the workgroup's own while the others stream (kept in registers,
     // the single precision kernel spills 4 to 23 of them, and 14 are enough to take n = 4096 from 72
     // to 105 us)
-    constexpr bool NEAR = WIDE && (sizeof(T) == 4 || TRANS);
-    constexpr bool kPark = sizeof(T) == 8 && (!TRANS || WIDE);
+    constexpr bool NEAR = sizeof(T) == 4 || TRANS;
+    constexpr bool kPark = sizeof(T) == 8;
     constexpr bool kParkNear = NEAR && TRANS;
     __shared__ __attribute__((aligned(16))) T tile[TRANS ? 1 : NW][TRANS ? 1 : kWave][TRANS ? 1 : kWave + 1];
     __shared__ T park[kPark ? NW : 1][kPark ? kWave : 1][kPark ? kWave + 1 : 1];
@@ -469,15 +471,8 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
     }
 
     // ---- the unknowns of earlier workgroups: tiles 0 .. q0 - 1 of my block row, in solving order.
-    // A tile travels in pieces of RH rows (columns if transposed), two pieces in flight by turns;
-    // the 64 solutions a tile multiplies are looked for when the piece is asked for and waited
-    // for when it is used.  Transposed, a lane owns its row and subtracts as it goes.  Not
-    // transposed, a lane owns a column of the piece and keeps one partial sum per row; the
-    // partial sums of all tiles but the last are folded over the lanes once, through LDS, and the
-    // last tile, whose solutions arrive last, is turned through LDS before the wait instead, so
-    // that after the wait only its 64 multiply-adds remain; its pieces travel like the others.
-    constexpr int RH = sizeof(T) == 4 ? kWave : kWave / 2;
-    constexpr int CPT = kWave / RH;      // pieces per tile
+    // A tile travels in pieces of RH memory rows, two pieces in flight by turns; the 64 solutions a
+    // tile multiplies are waited for when its first piece is used.
     bool ok = true;
     auto look = [&](int qq, T& xv) { return Handover<T>::get(p.solved + ((int64_t)qq * kWave + lane) * HW, xv); };
     auto wait_x = [&](int qq, T& xv, bool got) {
@@ -493,7 +488,7 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
             got = look(qq, xv);
         }
     };
-    if constexpr (WIDE) {
+    {
       const int nstream = NEAR ? q0 - 1 : q0;     // tiles taken by the streaming loop
       if (have && nstream > 0) {
         // 128-bit loads: lane (g, m), g = lane / CG, m = lane % CG, fetches for t < NL the V elements
@@ -619,17 +614,17 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
         // the partial sums, folded over the lanes: lane = unknown from here on
         __builtin_amdgcn_wave_barrier();
         if (TRANS) {
-            T* const red = &fold[(TRANS && WIDE) ? wave : 0][0];
+            T* const red = &fold[TRANS ? wave : 0][0];
             vec_t out;
 #pragma unroll
             for (int v = 0; v < V; ++v) out[v] = pv[v];
-            *reinterpret_cast<vec_t*>(red + ((TRANS && WIDE) ? g * kWave + m * V : 0)) = out;
+            *reinterpret_cast<vec_t*>(red + (TRANS ? g * kWave + m * V : 0)) = out;
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             T sum = T(0);
 #pragma unroll
-            for (int gg = 0; gg < V; ++gg) sum += red[(TRANS && WIDE) ? gg * kWave + lane : 0];
+            for (int gg = 0; gg < V; ++gg) sum += red[TRANS ? gg * kWave + lane : 0];
             b -= sum;
         } else {
             // unknown h * RH + g * NL + t is acc[h * NL + t] of the lanes (g, 0 .. CG - 1); rows of the buffer V apart
@@ -678,91 +673,6 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
             b -= (part[0] + part[1]) + (part[2] + part[3]);
         }
       }
-    } else
-    if (have && q0 > 0) {
-        T acc[TRANS ? 1 : kWave];
-        if (!TRANS) {
-#pragma unroll
-            for (int r = 0; r < kWave; ++r) acc[TRANS ? 0 : r] = T(0);
-        }
-        const int nch = q0 * CPT;
-        T t0[RH], t1[RH], x0, x1;
-        bool g0, g1;
-        auto start = [&](int ch, T (&raw)[RH], T& xv, bool& got) {
-            const int c0 = actual(ch / CPT) * kWave, h0 = (ch % CPT) * RH;
-            if (TRANS) load_rows(p.A, p.lda, c0 + h0, last, min(i, last), raw);
-            else load_rows(p.A, p.lda, r0 + h0, last, min(c0 + lane, last), raw);
-            got = look(ch / CPT, xv);
-        };
-        auto use = [&](auto piece, int ch, T (&raw)[RH], T& xv, bool got) {
-            constexpr int H0 = decltype(piece)::value * RH;
-            const int qq = ch / CPT, c0 = actual(qq) * kWave;
-#pragma unroll
-            for (int j = 0; j < RH; ++j) asm volatile("" : "+v"(raw[j]));
-            // the clamped addresses of the last row and column of tiles read elements that do not count
-            const bool edge = r0 + kWave > p.n || c0 + kWave > p.n;
-            if (!TRANS && qq == q0 - 1) {
-                if (H0 == 0) {           // partial sums: lane = column  ->  lane = row
-                    __builtin_amdgcn_wave_barrier();
-#pragma unroll
-                    for (int r = 0; r < kWave; ++r) tile[TRANS ? 0 : wave][TRANS ? 0 : r][TRANS ? 0 : lane] = acc[TRANS ? 0 : r];
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                    __builtin_amdgcn_wave_barrier();
-                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                    T part[4] = {T(0), T(0), T(0), T(0)};
-#pragma unroll
-                    for (int j = 0; j < kWave; ++j) part[j & 3] += tile[TRANS ? 0 : wave][TRANS ? 0 : lane][TRANS ? 0 : j];
-                    b -= (part[0] + part[1]) + (part[2] + part[3]);
-                    __builtin_amdgcn_wave_barrier();
-                }
-#pragma unroll
-                for (int r = 0; r < RH; ++r)
-                    tile[TRANS ? 0 : wave][TRANS ? 0 : H0 + r][TRANS ? 0 : lane] = (c0 + lane < p.n && r0 + H0 + r < p.n) ? raw[r] : T(0);
-                if (H0 + RH == kWave) {
-                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                    __builtin_amdgcn_wave_barrier();
-                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                    // my row of the tile, into the registers the partial sums have left; before the wait
-#pragma unroll
-                    for (int j = 0; j < kWave; ++j) acc[TRANS ? 0 : j] = tile[TRANS ? 0 : wave][TRANS ? 0 : lane][TRANS ? 0 : j];
-#pragma unroll
-                    for (int j = 0; j < kWave; ++j) asm volatile("" : "+v"(acc[TRANS ? 0 : j]));
-                    wait_x(qq, xv, got);
-                    T part[4] = {T(0), T(0), T(0), T(0)};
-#pragma unroll
-                    for (int j = 0; j < kWave; ++j) part[j & 3] = fmad(acc[TRANS ? 0 : j], lane_bcast(xv, j), part[j & 3]);
-                    b -= (part[0] + part[1]) + (part[2] + part[3]);
-                }
-                return;
-            }
-            wait_x(qq, xv, got);
-            if (TRANS) {
-                if (edge) {
-#pragma unroll
-                    for (int j = 0; j < RH; ++j) raw[j] = (active && c0 + H0 + j < p.n) ? raw[j] : T(0);
-                }
-                T part[4] = {T(0), T(0), T(0), T(0)};
-#pragma unroll
-                for (int j = 0; j < RH; ++j) part[j & 3] = fmad(raw[j], lane_bcast(xv, H0 + j), part[j & 3]);
-                b -= (part[0] + part[1]) + (part[2] + part[3]);
-            } else {
-                if (edge) {
-#pragma unroll
-                    for (int r = 0; r < RH; ++r) raw[r] = (c0 + lane < p.n && r0 + H0 + r < p.n) ? raw[r] : T(0);
-                }
-#pragma unroll
-                for (int r = 0; r < RH; ++r) acc[TRANS ? 0 : H0 + r] = fmad(raw[r], xv, acc[TRANS ? 0 : H0 + r]);
-            }
-        };
-        int ch = 0;
-        start(0, t0, x0, g0);
-        for (; ch + 1 < nch; ch += 2) {
-            start(ch + 1, t1, x1, g1);
-            use(std::integral_constant<int, 0>(), ch, t0, x0, g0);
-            if (ch + 2 < nch) start(ch + 2, t0, x0, g0);
-            use(std::integral_constant<int, CPT - 1>(), ch + 1, t1, x1, g1);
-        }
-        if (ch < nch) use(std::integral_constant<int, 0>(), ch, t0, x0, g0);
     }
 
     // ---- my workgroup's own sub-blocks.  One step: sub-block q0 + s is solved by wavefront s and
@@ -870,23 +780,16 @@ int trsv_chain(mxb_handle_t h, bool op_lower, bool no_trans, bool unit, int64_t 
     if (spin_limit > (1 << 30)) spin_limit = 1 << 30;
     const bool ask_ahead = n * n * (int64_t)sizeof(T) >= ((sizeof(T) == 4 && no_trans) ? kChainAskAheadBytesAlongRows : kChainAskAheadBytes);
     const ChainArgs<T> a{(int)n, (int)ceil_div(n, (int64_t)kWave), A, lda, x0, incx, solved, control, (int)spin_limit};
-    // 128-bit loads need rows that begin on 16-byte boundaries
-    const bool wide = reinterpret_cast<uintptr_t>(A) % 16 == 0 && (lda * (int64_t)sizeof(T)) % 16 == 0;
 #define MXB_CHAIN(LOW_, TR_)                                                                                          \
     {                                                                                                                 \
         constexpr int NW = chain_waves<T, TR_>();                                                                     \
         const dim3 grid((unsigned)ceil_div((int64_t)a.nsub, (int64_t)NW)), block(NW * kWave);                         \
-        if (wide && ask_ahead) {                                                                                      \
-            {                                                                                                         \
-                if (unit) hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, true, true, true>), grid, block, 0, h->stream, a);   \
-                else hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, false, true, true>), grid, block, 0, h->stream, a);       \
-            }                                                                                                         \
-        } else if (wide) {                                                                                            \
-            if (unit) hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, true, true, false>), grid, block, 0, h->stream, a);  \
-            else hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, false, true, false>), grid, block, 0, h->stream, a);      \
+        if (ask_ahead) {                                                                                              \
+            if (unit) hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, true, true>), grid, block, 0, h->stream, a);        \
+            else hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, false, true>), grid, block, 0, h->stream, a);            \
         } else {                                                                                                      \
-            if (unit) hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, true, false, false>), grid, block, 0, h->stream, a); \
-            else hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, false, false, false>), grid, block, 0, h->stream, a);     \
+            if (unit) hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, true, false>), grid, block, 0, h->stream, a);       \
+            else hipLaunchKernelGGL((trsv_chain_kernel<T, LOW_, TR_, false, false>), grid, block, 0, h->stream, a);           \
         }                                                                                                             \
     }
     if (op_lower) { if (no_trans) { MXB_CHAIN(true, false) } else { MXB_CHAIN(true, true) } }

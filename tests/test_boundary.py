@@ -289,9 +289,9 @@ def test_build_refuses_chained_trsv_kernels_that_spill_too_many_scalars():
         b.check_chain_spills(line.format("f", 85) + line.format("d", b.MAX_CHAIN_SGPR_SPILLS + 1))
     with pytest.raises(RuntimeError):
         b.check_chain_spills(other)                              # nothing to check: refuse rather than pass
-    # instances with 128-bit loads (fifth template argument) must not spill vector registers; the others may
-    wide = "trsv.hip:300:1: remark: Function Name: _ZN3mxb12_GLOBAL__N_117trsv_chain_kernelIfLb0ELb1ELb1ELb{}ELb0EEEvNS0_9ChainArgsIT_EE [x]\n" \
-           "trsv.hip:300:1: remark:     SGPRs Spill: 5 [x]\ntrsv.hip:300:1: remark:     VGPRs Spill: {} [x]\n"
-    assert list(b.check_chain_spills(wide.format(1, 0) + wide.format(0, 288)).values()) == [5, 5]
+    # no instance may spill vector registers (right but much slower)
+    vec = "trsv.hip:300:1: remark: Function Name: _ZN3mxb12_GLOBAL__N_117trsv_chain_kernelIfLb0ELb1ELb1ELb{}EEEvNS0_9ChainArgsIT_EE [x]\n" \
+          "trsv.hip:300:1: remark:     SGPRs Spill: 5 [x]\ntrsv.hip:300:1: remark:     VGPRs Spill: {} [x]\n"
+    assert list(b.check_chain_spills(vec.format(1, 0) + vec.format(0, 0)).values()) == [5, 5]
     with pytest.raises(RuntimeError):
-        b.check_chain_spills(wide.format(1, 14))
+        b.check_chain_spills(vec.format(1, 0) + vec.format(0, 14))
