@@ -119,6 +119,8 @@ __global__ void __launch_bounds__(NW* kWave) trsv_diag_kernel(const TrsvArgs<T> 
         const bool inside = OPLOWER ? j < lane : j > lane;
         e[j] = inside ? (UNIT ? e[j] : e[j] * rinv) : T(0);
     }
+    // (The chained kernel's four unknowns per step do not pay here: the premultiplication of the rows, which
+    // that kernel does while it waits, costs one solve more than it saves: n = 64 in 9.2 us instead of 6.8.)
 
     for (int step = 0; step < nsub; ++step) {
         const int s = OPLOWER ? step : nsub - 1 - step;
