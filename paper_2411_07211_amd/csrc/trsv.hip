@@ -334,18 +334,19 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
     constexpr int V = 16 / (int)sizeof(T);       // elements of a 128-bit load
     __shared__ __attribute__((aligned(16))) T xs[NW * kWave];
     __shared__ __attribute__((aligned(16))) T fold[TRANS ? NW : 1][TRANS ? V * kWave : 1];
-    // per-wavefront buffers: one turns tiles when not transposed; in double precision, where the
-    // registers are short, another holds the wavefront's finished diagonal rows (not needed on the
-    // element-wise transposed path, which keeps them in registers without spilling); transposed, a
-    // third holds the tile next to the workgroup's own while the others stream (kept in registers,
-    // the single precision kernel spills 4 to 23 of them, and 14 are enough to take n = 4096 from 72
-    // to 105 us)
-    constexpr bool NEAR = sizeof(T) == 4 || TRANS;
+    // Per-wavefront buffers.  tile: turns a tile when not transposed (row-wise loads, a lane wants its row).
+    // park: in double precision, where the registers are short, the wavefront's finished diagonal rows.
+    // near_park: transposed, the tile next to the workgroup's own while the others stream; not transposed
+    // that tile waits in tile[] (double precision) or in registers (single; transposed, the single
+    // precision kernel would spill 4 to 23 registers with it, and 14 are enough to take n = 4096 from
+    // 72 to 105 us).  fold / foldn: the partial sums on their way from lane = column to lane = unknown.
     constexpr bool kPark = sizeof(T) == 8;
-    constexpr bool kParkNear = NEAR && TRANS;
+    constexpr bool kParkNear = TRANS || sizeof(T) == 8;      // single precision, not transposed: it stays in registers
     __shared__ __attribute__((aligned(16))) T tile[TRANS ? 1 : NW][TRANS ? 1 : kWave][TRANS ? 1 : kWave + 1];
     __shared__ T park[kPark ? NW : 1][kPark ? kWave : 1][kPark ? kWave + 1 : 1];
-    __shared__ T near_park[kParkNear ? NW : 1][kParkNear ? kWave : 1][kParkNear ? kWave + 1 : 1];
+    __shared__ T near_park[TRANS ? NW : 1][TRANS ? kWave : 1][TRANS ? kWave + 1 : 1];      // (not transposed: in tile[])
+    constexpr int kFoldRows = sizeof(T) == 4 ? kWave : kWave / 2;       // unknowns folded in one pass (a piece of a tile)
+    __shared__ __attribute__((aligned(16))) T foldn[TRANS ? 1 : NW][TRANS ? 1 : (kWave / V) * (kFoldRows + V)];
     __shared__ int my_ticket;
     constexpr int HW = Handover<T>::kWords;
     int* const ticket = p.control;
@@ -401,14 +402,14 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
     auto wants = [&](int s) { return s < NW - 1 && have && wave > s && q0 + s < p.nsub; };
     if (wants(0)) issue(own_c0(0), pa);
     if (wants(1)) issue(own_c0(1), pb);
-    // NEAR: the last tile before my workgroup's own, the one whose solutions arrive last and that the
-    // first solve of the workgroup waits for, is taken like a tile of my own workgroup: fetched now,
-    // turned so that a lane holds its row, and applied from LDS when the solutions are there (not in
-    // double precision when not transposed: the tile waits in LDS while the others stream, and there
-    // the turning buffer and the parked diagonal rows leave no room for it)
-    T pc[NEAR ? kWave : 1];
-    const bool near_tile = NEAR && have && q0 > 0;
-    if constexpr (NEAR) { if (near_tile) issue(actual(q0 - 1) * kWave, pc); }
+    // The last tile before my workgroup's own, the one whose solutions arrive last and that the first
+    // solve of the workgroup waits for, is taken like a tile of my own workgroup: fetched now, turned
+    // so that a lane holds its row, and applied from LDS when the solutions are there.  Except in
+    // single precision when not transposed, where the registers hold it, it waits in LDS while the
+    // other tiles stream (not transposed: in the turning buffer, which nothing else needs until then).
+    T pc[kWave];
+    const bool near_tile = have && q0 > 0;
+    if (near_tile) issue(actual(q0 - 1) * kWave, pc);
 
     // My row of the diagonal tile, scaled by 1 / T[i][i] as in the blocked kernel.  Before the
     // wait for the earlier workgroups, which is where a workgroup has time to spare: in single
@@ -462,12 +463,16 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
     // between two steps takes a wavefront longer than the solving wavefront needs for its step
     if (wants(0)) finish(own_c0(0), pa);
     if (wants(1)) finish(own_c0(1), pb);
-    if constexpr (NEAR) {
+    {
         if (near_tile) {
             finish(actual(q0 - 1) * kWave, pc);
-            if constexpr (kParkNear) {
+            if constexpr (kParkNear) {            // read back by this lane only
+                if constexpr (!TRANS) __builtin_amdgcn_wave_barrier();      // finish() has read the turning buffer
 #pragma unroll
-                for (int j = 0; j < kWave; ++j) near_park[wave][j][lane] = pc[j];      // read back by this lane only
+                for (int j = 0; j < kWave; ++j) {
+                    if constexpr (TRANS) near_park[TRANS ? wave : 0][TRANS ? j : 0][TRANS ? lane : 0] = pc[j];
+                    else tile[TRANS ? 0 : wave][TRANS ? 0 : j][TRANS ? 0 : lane] = pc[j];
+                }
             }
         }
     }
@@ -491,7 +496,7 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
         }
     };
     {
-      const int nstream = NEAR ? q0 - 1 : q0;     // tiles taken by the streaming loop
+      const int nstream = q0 - 1;                 // tiles taken by the streaming loop: all but the near one
       if (have && nstream > 0) {
         // 128-bit loads: lane (g, m), g = lane / CG, m = lane % CG, fetches for t < NL the V elements
         // at memory row row0 + g * NL + t, columns col0 + m * V .., of a piece of RH = V * NL rows, so
@@ -629,35 +634,45 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
             for (int gg = 0; gg < V; ++gg) sum += red[TRANS ? gg * kWave + lane : 0];
             b -= sum;
         } else {
-            // unknown h * RH + g * NL + t is acc[h * NL + t] of the lanes (g, 0 .. CG - 1); rows of the buffer V apart
-            // from a power of two, so that the 128-bit stores spread over the banks
-            constexpr int STRIDE = kWave + V;
-            T* const red = &tile[TRANS ? 0 : wave][0][0];
+            // unknown h * RH + g * NL + t is acc[h * NL + t] of the lanes (g, 0 .. CG - 1): one pass per piece h of
+            // a tile (the buffer is small because the turning buffer may hold the near tile meanwhile); rows of
+            // the buffer V apart from a power of two, so that the 128-bit stores spread over the banks
+            static_assert(RH == kFoldRows, "a pass folds the unknowns of one piece");
+            constexpr int STRIDE = RH + V;
+            T* const red = &foldn[TRANS ? 0 : wave][0];
 #pragma unroll
-            for (int h = 0; h < CPT; ++h)
+            for (int h = 0; h < CPT; ++h) {
+                __builtin_amdgcn_wave_barrier();      // the pass before has read the buffer
 #pragma unroll
                 for (int t = 0; t < NL; t += V) {
                     vec_t out;
 #pragma unroll
                     for (int v = 0; v < V; ++v) out[v] = acc[TRANS ? 0 : h * NL + t + v];
-                    *reinterpret_cast<vec_t*>(red + (TRANS ? 0 : m * STRIDE + h * RH + g * NL + t)) = out;
+                    *reinterpret_cast<vec_t*>(red + (TRANS ? 0 : m * STRIDE + g * NL + t)) = out;
                 }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            T part[4] = {T(0), T(0), T(0), T(0)};
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                const int u = lane - h * RH;
+                if (u >= 0 && u < RH) {
+                    T part[4] = {T(0), T(0), T(0), T(0)};
 #pragma unroll
-            for (int mm = 0; mm < CG; ++mm) part[mm & 3] += red[TRANS ? 0 : mm * STRIDE + lane];
-            b -= (part[0] + part[1]) + (part[2] + part[3]);
+                    for (int mm = 0; mm < CG; ++mm) part[mm & 3] += red[TRANS ? 0 : mm * STRIDE + u];
+                    b -= (part[0] + part[1]) + (part[2] + part[3]);
+                }
+            }
             __builtin_amdgcn_wave_barrier();
         }
       }
-      if constexpr (NEAR) {
+      {
         if (near_tile) {
             T* const xb = xs + wave * kWave;
             if constexpr (kParkNear) {            // back into the registers that the streamed tiles have left
 #pragma unroll
-                for (int j = 0; j < kWave; ++j) pc[j] = near_park[wave][j][lane];
+                for (int j = 0; j < kWave; ++j) {
+                    if constexpr (TRANS) pc[j] = near_park[TRANS ? wave : 0][TRANS ? j : 0][TRANS ? lane : 0];
+                    else pc[j] = tile[TRANS ? 0 : wave][TRANS ? 0 : j][TRANS ? 0 : lane];
+                }
 #pragma unroll
                 for (int j = 0; j < kWave; ++j) asm volatile("" : "+v"(pc[j]));
             }
@@ -671,7 +686,7 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             T part[4] = {T(0), T(0), T(0), T(0)};
 #pragma unroll
-            for (int j = 0; j < kWave; ++j) part[j & 3] = fmad(pc[NEAR ? j : 0], xb[j], part[j & 3]);
+            for (int j = 0; j < kWave; ++j) part[j & 3] = fmad(pc[j], xb[j], part[j & 3]);
             b -= (part[0] + part[1]) + (part[2] + part[3]);
         }
       }
