@@ -770,11 +770,12 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
 
 // Workspace of the one-kernel solve: the hand-over words of every sub-block, then the ticket and
 // the error word.
-// From where asking ahead pays (see the kernel): transposed between n = 8192 and 12288 in single precision
-// (132 against 140 us, 263 against 232), in double precision between 6144 and 8192 (203 / 187 against 216 / 199 us, 328 /
-// 326 against 319 / 302); single precision not transposed, where a tile follows the last one along the same rows and
-// memory answers sooner, from 4096 (upper: 82 against 79 us, 8192: 150 against 143, 16384: 318 against 302).
-constexpr int64_t kChainAskAheadBytes = (int64_t)384 << 20, kChainAskAheadBytesAlongRows = (int64_t)64 << 20;
+// From where asking ahead pays (see the kernel), MiB of matrix, [double precision][transposed]; per call, without
+// against with: single precision not transposed (a tile follows the last one along the same rows, memory answers
+// sooner) n = 2048 49.2 / 46.7 against 46.8 / 47.0 us (lower / upper), 8192 153 / 143 against 144 / 143; transposed 8192
+// 131 against 141, 12288 263 against 232; double precision not transposed 6144 195 against 205, 8192 335 against
+// 306; transposed 2048 70.8 against 70.5, 4096 129 against 126, 8192 309 against 274.
+constexpr int kChainAskAheadMiB[2][2] = {{16, 384}, {384, 128}};
 
 template <typename T>
 inline size_t chain_bytes(int64_t n) { return (size_t)ceil_div(n, (int64_t)kWave) * kWave * Handover<T>::kWords * 8 + 2 * sizeof(int); }
@@ -795,7 +796,7 @@ int trsv_chain(mxb_handle_t h, bool op_lower, bool no_trans, bool unit, int64_t 
     h->device_status = control + 1;
     int64_t spin_limit = option(h, MXB_OPT_TRSV_SPIN_LIMIT);
     if (spin_limit > (1 << 30)) spin_limit = 1 << 30;
-    const bool ask_ahead = n * n * (int64_t)sizeof(T) >= ((sizeof(T) == 4 && no_trans) ? kChainAskAheadBytesAlongRows : kChainAskAheadBytes);
+    const bool ask_ahead = n * n * (int64_t)sizeof(T) >= ((int64_t)kChainAskAheadMiB[sizeof(T) == 8][!no_trans] << 20);
     const ChainArgs<T> a{(int)n, (int)ceil_div(n, (int64_t)kWave), A, lda, x0, incx, solved, control, (int)spin_limit};
 #define MXB_CHAIN(LOW_, TR_)                                                                                          \
     {                                                                                                                 \
