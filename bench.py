@@ -606,8 +606,8 @@ CALL_KERNELS = {
     "strmv_ut_16384": SWEEP("float", 4, "true", 1), "strmv_lt_16384": SWEEP("float", 4, "false", 1),
     "ssymv_u_16384": SWEEP("float", 4, "true", 0), "dsymv_l_16384": SWEEP("double", 2, "false", 0),
     "dsymv_u_16384_dense": SWEEP("double", 2, "true", 0), "dtrmv_lt_16384_dense": SWEEP("double", 2, "false", 1),
-    "strsv_ln_16384": ["trsv_chain_kernel<float, true, false, true, true>"],
-    "strsv_lt_16384": ["trsv_chain_kernel<float, false, true, true, true>"],
+    "strsv_ln_16384": ["trsv_chain_init_kernel", "trsv_chain_kernel<float, true, false, true, true>"],
+    "strsv_lt_16384": ["trsv_chain_init_kernel", "trsv_chain_kernel<float, false, true, true, true>"],
     "probe_copy": ["probe_copy_kernel"], "probe_read": ["probe_read_kernel"],
 }
 # The calls whose HBM traffic is recorded from counters (the dense ones share no kernel with each

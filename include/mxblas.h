@@ -20,11 +20,9 @@
  *    Buffers must stay alive until that work has completed.  Input and output buffers must not
  *    overlap each other or the workspace (trmv's x is in place by definition).
  *  Workspace.  Routines that combine per-block partial results (dot, asum, nrm2, iamax, gemv,
- *    trmv, symv) use the handle's workspace, a caller-owned device buffer, and so may trsv, whose
- *    workgroups hand their solutions on through memory; mxb_workspace_bytes gives an upper bound on
- *    what a call needs.  (The library holds about 6 MB of device memory of its own, part of its image:
- *    the 4 MB scratch of mxb_sgemv_static and, for the first four handles alive, hand-over memory for
- *    trsv of up to 32768 unknowns, which saves those calls the kernel that clears the workspace.)  Partials are combined by a second kernel in a fixed order: no atomic
+ *    trmv, symv) use the handle's workspace, a caller-owned device buffer, and so does trsv, whose
+ *    workgroups hand their solutions on through it; mxb_workspace_bytes gives an upper bound on
+ *    what a call needs.  Partials are combined by a second kernel in a fixed order: no atomic
  *    additions, results are bitwise reproducible from run to run.
  *  Layout.  Row-major (MXB_ROW_MAJOR) is native: element (i, j) is A[i*lda + j], as in the
  *    paper's object code.  Column-major calls are remapped on the host to the row-major kernel of
@@ -112,8 +110,8 @@ int64_t mxb_get_option(mxb_handle_t h, int option);
 
 /* Waits for the handle's stream and reports what only the device knows about the last call on
  * this handle that can fail there: MXB_OK, or MXB_ERR_TIMEOUT if the last chained trsv gave up
- * a bounded wait (x is then unfinished).  The next call on the handle that uses the workspace or
- * solves a triangular system, or mxb_set_workspace, makes this MXB_OK again.  Synchronises:
+ * a bounded wait (x is then unfinished).  The next call on the handle that uses the workspace,
+ * or mxb_set_workspace, overwrites the status word and makes this MXB_OK again.  Synchronises:
  * not for use under stream capture.  Other routines cannot fail on the device. */
 int mxb_last_status(mxb_handle_t h);
 
@@ -249,10 +247,9 @@ int mxb_dtrmv(mxb_handle_t h, mxb_layout_t layout, mxb_uplo_t uplo, mxb_trans_t 
  * the triangle are never used.  No test for singularity.  Blocked substitution: the diagonal
  * elements enter as reciprocals (one extra rounding per unknown).  Below MXB_OPT_TRSV_CHAIN_MIN
  * unknowns: one launch per block of 512 (fp32) or 256 (fp64) unknowns, with the workspace used when
- * the product is transposed (as gemv does).  From there on: one kernel whose workgroups solve 128
- * unknowns each, in order, and hand the solved values on through memory: the library's own where
- * the handle has a share of it and n <= 32768, else the workspace (16 bytes per unknown at most,
- * cleared by the call; MXB_ERR_WORKSPACE if it is smaller).  Calls on one handle must not overlap.  A workgroup waits
+ * the product is transposed (as gemv does).  From there on: one kernel whose workgroups solve 256
+ * unknowns each, in order, and hand the solved values on through the workspace (16 bytes per
+ * unknown at most, cleared by the call; MXB_ERR_WORKSPACE if it is smaller).  A workgroup waits
  * for solved values a bounded number of polls only (MXB_OPT_TRSV_SPIN_LIMIT); the bound (tens of
  * seconds) is reached only if the device stops scheduling the workgroup that owns them; x is
  * then left unfinished and mxb_last_status reports MXB_ERR_TIMEOUT.

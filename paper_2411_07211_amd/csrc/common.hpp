@@ -14,10 +14,7 @@ struct mxb_ctx {
     void* ws;
     size_t ws_bytes;
     int64_t opt[MXB_OPT_COUNT];
-    const int* device_status;   // error word of the last call that can fail on the device, or null
-    int device_status_error;    // what that word holds when the call failed
-    int chain_slot;             // this handle's block of the library's own hand-over memory (trsv), or -1
-    int chain_epoch;            // number of the last trsv call that used it: the value its error word takes
+    const int* device_status;   // error word of the last call that can fail on the device (in the workspace), or null
 };
 
 namespace mxb {

@@ -2,7 +2,6 @@
 #include <new>
 
 #include "common.hpp"
-#include "matvec.hpp"
 #include "options.hpp"
 #include "plan.hpp"
 #include "skinny.hpp"
@@ -74,9 +73,6 @@ int mxb_create(mxb_handle_t* h)
     c->ws_bytes = 0;
     for (int o = 0; o < MXB_OPT_COUNT; ++o) c->opt[o] = 0;
     c->device_status = nullptr;
-    c->device_status_error = 1;
-    c->chain_slot = mxb::chain_slot_acquire();
-    c->chain_epoch = 0;
     *h = c;
     return MXB_OK;
 }
@@ -85,7 +81,6 @@ int mxb_destroy(mxb_handle_t h)
 {
     if (!mxb::handle_ok(h)) return MXB_ERR_HANDLE;
     h->magic = 0;
-    mxb::chain_slot_release(h->chain_slot);
     delete h;
     return MXB_OK;
 }
@@ -130,7 +125,7 @@ int mxb_last_status(mxb_handle_t h)
     if (h->device_status) e = hipMemcpyAsync(&word, h->device_status, sizeof(int), hipMemcpyDeviceToHost, h->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(h->stream);
     if (e != hipSuccess) return MXB_ERR_HIP_BASE + (int)e;
-    return (h->device_status && word == h->device_status_error) ? MXB_ERR_TIMEOUT : MXB_OK;
+    return word != 0 ? MXB_ERR_TIMEOUT : MXB_OK;
 }
 
 size_t mxb_workspace_bytes(int routine, int elem_size, int64_t m, int64_t n)

@@ -51,10 +51,4 @@ int launch_rowdot(mxb_handle_t h, RowdotArgs<T> a, int mode, bool unit);
 template <typename T>
 int launch_colacc(mxb_handle_t h, ColaccArgs<T> a, int64_t batch = 1);
 
-// The chained triangular solve keeps its hand-over words in memory of the library's own where it can
-// (trsv.hip): a handle takes one of a few blocks of it when it is created and gives it back when
-// it is destroyed; -1: none was free.
-int chain_slot_acquire();
-void chain_slot_release(int slot);
-
 }  // namespace mxb

@@ -1,7 +1,6 @@
 // trsv (Sec. 6.2.2, triangular solve) on a row-major matrix: blocked substitution.  The part of
 // a block's right-hand side that depends on unknowns solved earlier is subtracted with the
 // matrix-vector kernels of matvec.hip; the block on the diagonal is solved by one workgroup.
-#include <mutex>
 #include <type_traits>
 
 #include "matvec.hpp"
@@ -262,8 +261,6 @@ struct ChainArgs {
     unsigned long long* solved;   // [nsub * 64 * Handover<T>::kWords] hand-over words in solving order; all zero at the start
     int* control;        // the ticket counter and the error word; zero at the start
     int spin_limit;
-    int failed;          // what the error word takes when a wait gives up (not 0)
-    int tidy;            // not 0: the last workgroup leaves hand-over words and ticket at zero for the next call
 };
 
 
@@ -489,9 +486,9 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
         for (int spins = 0; ok && __ballot(got) != ~0ull;) {
             // (the error word every 64th round only: a round would otherwise be two trips to memory, one after the
             // other; from the last solution of a workgroup to the first of the next: 4.3 -> 3.4 us)
-            if (++spins > p.spin_limit || (spins % 64 == 0 && __hip_atomic_load(error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == p.failed)) {
+            if (++spins > p.spin_limit || (spins % 64 == 0 && __hip_atomic_load(error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
                 ok = false;
-                if (lane == 0) __hip_atomic_store(error, p.failed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (lane == 0) __hip_atomic_store(error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 break;
             }
             __builtin_amdgcn_s_sleep(1);
@@ -769,16 +766,6 @@ __global__ void __launch_bounds__((chain_waves<T, TRANS>() * kWave)) trsv_chain_
         step(2, pa);
         step(3, pb);
     }
-    // In the library's own memory the words are left as the next call wants them.  The workgroup that
-    // solves last can do that: every other one has finished its solves, which come after all its looks at
-    // hand-over words, and its own two wavefronts are past theirs behind the barrier (which also has their
-    // hand-over stores acknowledged).
-    if (p.tidy && my_ticket == (p.nsub + NW - 1) / NW - 1) {
-        __syncthreads();
-        const int words = p.nsub * kWave * HW;      // (n < 2^24)
-        for (int k = threadIdx.x; k < words; k += NW * kWave) p.solved[k] = 0;
-        if (threadIdx.x == 0) *ticket = 0;
-    }
 }
 
 // Workspace of the one-kernel solve: the hand-over words of every sub-block, then the ticket and
@@ -793,72 +780,24 @@ constexpr int kChainAskAheadMiB[2][2] = {{16, 384}, {384, 128}};
 template <typename T>
 inline size_t chain_bytes(int64_t n) { return (size_t)ceil_div(n, (int64_t)kWave) * kWave * Handover<T>::kWords * 8 + 2 * sizeof(int); }
 
-// Hand-over memory of the library's own.  In the caller's workspace the words have to be cleared by a
-// kernel before every solve (4.4 us: a fifth of a call at n = 256), because any other routine may have
-// written there since.  Memory that only the chained kernel touches stays as its last call left it, and that
-// call's last workgroup leaves it cleared, so no clearing kernel is needed.  A handle owns one of kChainSlots
-// blocks (calls on one handle do not overlap, as with its workspace), each for systems of up to
-// kChainSlotUnknowns unknowns; larger systems and further handles use the workspace.  The error word is not
-// cleared but given a new value by every call (the handle's count of them), so that an old failure reads as none.
-// One copy per GPU, zero when the library is loaded; its address on a GPU comes from hipGetSymbolAddress.
-constexpr int kChainSlots = 4, kChainHeaderWords = 32;
-constexpr int64_t kChainSlotUnknowns = 32768;
-constexpr int64_t kChainSlotWords = kChainHeaderWords + kChainSlotUnknowns * 2;      // ticket and error word, then two words per unknown (double)
-static __device__ __align__(256) unsigned long long chain_slot_memory[kChainSlots * kChainSlotWords];
-
-constexpr int kChainMaxDevices = 64;
-std::mutex g_chain_mutex;
-unsigned long long* g_chain_ptr[kChainMaxDevices];      // per device; null until the first call on it
-bool g_chain_slot_taken[kChainSlots];
-
-// Block `slot` on the current GPU, or null (then the caller uses the workspace).
-unsigned long long* chain_slot_address(int slot)
-{
-    int dev = -1;
-    if (slot < 0 || slot >= kChainSlots || hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kChainMaxDevices) return nullptr;
-    std::lock_guard<std::mutex> lock(g_chain_mutex);
-    if (!g_chain_ptr[dev]) {
-        void* p = nullptr;
-        if (hipGetSymbolAddress(&p, HIP_SYMBOL(chain_slot_memory)) != hipSuccess || !p) {
-            (void)hipGetLastError();
-            return nullptr;
-        }
-        g_chain_ptr[dev] = static_cast<unsigned long long*>(p);
-    }
-    return g_chain_ptr[dev] + (int64_t)slot * kChainSlotWords;
-}
-
 template <typename T>
 int trsv_chain(mxb_handle_t h, bool op_lower, bool no_trans, bool unit, int64_t n, const T* A, int64_t lda, T* x0, int64_t incx)
 {
-    unsigned long long* solved;
-    int* control;
-    int failed = 1, tidy = 0;
-    unsigned long long* const own = n <= kChainSlotUnknowns ? chain_slot_address(h->chain_slot) : nullptr;
-    if (own) {
-        control = reinterpret_cast<int*>(own);
-        solved = own + kChainHeaderWords;
-        h->chain_epoch = h->chain_epoch % 0x7ffffff0 + 1;
-        failed = h->chain_epoch;
-        tidy = 1;
-    } else {
-        const size_t bytes = chain_bytes<T>(n);
-        void* ws = take_workspace(h, bytes);
-        if (!ws) return MXB_ERR_WORKSPACE;
-        const int64_t words = (int64_t)(bytes / sizeof(int));
-        solved = static_cast<unsigned long long*>(ws);
-        control = static_cast<int*>(ws) + (words - 2);
-        hipLaunchKernelGGL(trsv_chain_init_kernel, dim3((unsigned)ceil_div(words, (int64_t)256)), dim3(256), 0, h->stream,
-                           static_cast<int*>(ws), (int)words);
-        const int st = launch_status();
-        if (st != MXB_OK) return st;
-    }
+    const size_t bytes = chain_bytes<T>(n);
+    void* ws = take_workspace(h, bytes);
+    if (!ws) return MXB_ERR_WORKSPACE;
+    const int64_t words = (int64_t)(bytes / sizeof(int));
+    unsigned long long* solved = static_cast<unsigned long long*>(ws);
+    int* control = static_cast<int*>(ws) + (words - 2);
+    hipLaunchKernelGGL(trsv_chain_init_kernel, dim3((unsigned)ceil_div(words, (int64_t)256)), dim3(256), 0, h->stream,
+                       static_cast<int*>(ws), (int)words);
+    int st = launch_status();
+    if (st != MXB_OK) return st;
     h->device_status = control + 1;
-    h->device_status_error = failed;
     int64_t spin_limit = option(h, MXB_OPT_TRSV_SPIN_LIMIT);
     if (spin_limit > (1 << 30)) spin_limit = 1 << 30;
     const bool ask_ahead = n * n * (int64_t)sizeof(T) >= ((int64_t)kChainAskAheadMiB[sizeof(T) == 8][!no_trans] << 20);
-    const ChainArgs<T> a{(int)n, (int)ceil_div(n, (int64_t)kWave), A, lda, x0, incx, solved, control, (int)spin_limit, failed, tidy};
+    const ChainArgs<T> a{(int)n, (int)ceil_div(n, (int64_t)kWave), A, lda, x0, incx, solved, control, (int)spin_limit};
 #define MXB_CHAIN(LOW_, TR_)                                                                                          \
     {                                                                                                                 \
         constexpr int NW = chain_waves<T, TR_>();                                                                     \
@@ -936,21 +875,6 @@ int trsv(mxb_handle_t h, int layout, int uplo, int trans, int diag, int64_t n, c
 }
 
 }  // namespace
-
-int chain_slot_acquire()
-{
-    std::lock_guard<std::mutex> lock(g_chain_mutex);
-    for (int s = 0; s < kChainSlots; ++s)
-        if (!g_chain_slot_taken[s]) { g_chain_slot_taken[s] = true; return s; }
-    return -1;
-}
-
-void chain_slot_release(int slot)
-{
-    std::lock_guard<std::mutex> lock(g_chain_mutex);
-    if (slot >= 0 && slot < kChainSlots) g_chain_slot_taken[slot] = false;
-}
-
 }  // namespace mxb
 
 extern "C" {

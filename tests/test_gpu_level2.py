@@ -654,22 +654,6 @@ def test_trsv_matrices_beyond_the_last_level_cache(blas, ctx):
         trsv_case(blas, ctx, np.float64, O.ROW_MAJOR, uplo, O.NO_TRANS, diag, 7170, 2, 1)
 
 
-def test_trsv_hand_over_memory_of_the_library(blas, ctx):
-    """Up to 32768 unknowns the chained solve keeps its hand-over words in memory of the library's own, one block
-    per handle, that each call leaves cleared for the next; there are fewer blocks than handles here, so the
-    later handles use their workspace (cleared by a kernel per call).  Repeated solves, sizes in turn, handles in turn."""
-    extra = [blas.Context("cuda:0", workspace_bytes=8 << 20) for _ in range(6)]
-    try:
-        for rep in range(2):
-            for c in [ctx] + extra:
-                for n in (1500, 300, 2310):
-                    trsv_case(blas, c, np.float32, O.ROW_MAJOR, O.LOWER, O.NO_TRANS, O.NON_UNIT, n, 0, 1, seed=15 + rep)
-                trsv_case(blas, c, np.float64, O.ROW_MAJOR, O.UPPER, O.TRANS, O.UNIT, 1030, 2, 1)
-    finally:
-        for c in extra:
-            c.close()
-
-
 def test_trsv_bounded_wait_reports_timeout(blas, ctx):
     """A wait that the host makes too short to succeed: every wavefront still leaves the kernel, the
     call returns, mxb_last_status names the timeout, and the next call with the default limit is right."""
