@@ -654,6 +654,21 @@ def test_trsv_matrices_beyond_the_last_level_cache(blas, ctx):
         trsv_case(blas, ctx, np.float64, O.ROW_MAJOR, uplo, O.NO_TRANS, diag, 7170, 2, 1)
 
 
+def test_trsv_on_several_handles_in_turn(blas, ctx):
+    """Each handle has hand-over words of its own (in its workspace, cleared by every call): repeated solves,
+    sizes in turn, handles in turn."""
+    extra = [blas.Context("cuda:0", workspace_bytes=8 << 20) for _ in range(3)]
+    try:
+        for rep in range(2):
+            for c in [ctx] + extra:
+                for n in (1500, 300, 2310):
+                    trsv_case(blas, c, np.float32, O.ROW_MAJOR, O.LOWER, O.NO_TRANS, O.NON_UNIT, n, 0, 1, seed=15 + rep)
+                trsv_case(blas, c, np.float64, O.ROW_MAJOR, O.UPPER, O.TRANS, O.UNIT, 1030, 2, 1)
+    finally:
+        for c in extra:
+            c.close()
+
+
 def test_trsv_bounded_wait_reports_timeout(blas, ctx):
     """A wait that the host makes too short to succeed: every wavefront still leaves the kernel, the
     call returns, mxb_last_status names the timeout, and the next call with the default limit is right."""
