@@ -60,3 +60,19 @@ def test_random_triangular_and_symmetric(blas, ctx, dt):
             L2.trsv_case(blas, ctx, dt, layout, uplo, trans, diag, n, pad, incx)
         finally:
             L2.A_OFFSET[0] = 0
+
+
+@pytest.mark.parametrize("dt", DT)
+def test_random_trsv_many_workgroups(blas, ctx, dt):
+    """Triangular solves of a few thousand unknowns (tens of workgroups of the chained kernel, tiles streamed
+    with 128-bit loads) at any base offset, pitch and increment."""
+    rng = np.random.default_rng(104)
+    for _ in range(10):
+        n = int(rng.integers(3000, 9000 if dt == np.float32 else 6500))
+        L2.A_OFFSET[0] = int(rng.integers(0, 4))
+        try:
+            L2.trsv_case(blas, ctx, dt, int(rng.choice([O.ROW_MAJOR, O.COL_MAJOR])), int(rng.choice([O.UPPER, O.LOWER])),
+                         int(rng.choice([O.NO_TRANS, O.TRANS])), int(rng.choice([O.NON_UNIT, O.UNIT])), n,
+                         int(rng.integers(0, 6)), int(rng.choice([1, 1, 2, -1, 3])), seed=int(rng.integers(1, 1000)))
+        finally:
+            L2.A_OFFSET[0] = 0
