@@ -190,15 +190,20 @@ class Suite:
              4 * (tri - NS + 2 * NS), reset),
             (f"strsv_lt_{NS}", "trsv", lambda s: B.mxb_strsv(h, B.ROW_MAJOR, B.LOWER, B.TRANS, B.UNIT, NS, self.small(), NS, xt, 1),
              4 * (tri - NS + 2 * NS), reset),
+            (f"dtrsv_ln_{NS}_dense", "trsv", lambda s: B.mxb_dtrsv(h, B.ROW_MAJOR, B.LOWER, B.NO_TRANS, B.UNIT, NS, self.small(f64), NS, xdt, 1),
+             8 * (tri - NS + 2 * NS), lambda: xdt.copy_(xd)),
+            (f"dtrsv_lt_{NS}_dense", "trsv", lambda s: B.mxb_dtrsv(h, B.ROW_MAJOR, B.LOWER, B.TRANS, B.UNIT, NS, self.small(f64), NS, xdt, 1),
+             8 * (tri - NS + 2 * NS), lambda: xdt.copy_(xd)),
         ]
-        self._small = None
-        self._small_from = A32[0]
+        self._small = {}
+        self._small_from = {f32: A32[0], f64: A64[0][:NS * NS]}
 
-    def small(self):
+    def small(self, dtype=None):
         """A 16384^2 matrix of elements below 1e-4, made on first use (only the trsv extras want it)."""
-        if self._small is None:
-            self._small = self._small_from * 1e-4
-        return self._small
+        dtype = dtype or next(iter(self._small_from))
+        if dtype not in self._small:
+            self._small[dtype] = self._small_from[dtype] * 1e-4
+        return self._small[dtype]
 
     def add(self, name, family, fn, nbytes, pre=None):
         self.calls.append((name, family, fn, int(nbytes), pre))
@@ -522,6 +527,12 @@ def sweep(B, ctx, torch):
         rec("strsv_lu", f"{n}x{n}", tri, lambda: B.mxb_strsv(h, B.ROW_MAJOR, B.LOWER, B.NO_TRANS, B.UNIT, n, T, n, xt, 1), reset)
         rec("strsv_ltu", f"{n}x{n}", tri, lambda: B.mxb_strsv(h, B.ROW_MAJOR, B.LOWER, B.TRANS, B.UNIT, n, T, n, xt, 1), reset)
     del T
+    T = torch.rand(NS * NS, dtype=f64, device=dev).mul_(1e-4)
+    for n in (1024, 4096, 16384):
+        tri = 8 * (n * (n + 1) // 2)
+        rec("dtrsv_lu", f"{n}x{n}", tri, lambda: B.mxb_dtrsv(h, B.ROW_MAJOR, B.LOWER, B.NO_TRANS, B.UNIT, n, T, n, xdt, 1), resetd)
+        rec("dtrsv_ltu", f"{n}x{n}", tri, lambda: B.mxb_dtrsv(h, B.ROW_MAJOR, B.LOWER, B.TRANS, B.UNIT, n, T, n, xdt, 1), resetd)
+    del T
     # skinny matrices (Sec. 6.2.2): N = 40, M powers of 2 and 3
     for M in (2 ** 10, 3 ** 7, 2 ** 13, 3 ** 9, 2 ** 16, 3 ** 11, 2 ** 19, 3 ** 13, 2 ** 22):
         t, full = f"{M}x40", 4 * M * 40
@@ -608,6 +619,8 @@ CALL_KERNELS = {
     "dsymv_u_16384_dense": SWEEP("double", 2, "true", 0), "dtrmv_lt_16384_dense": SWEEP("double", 2, "false", 1),
     "strsv_ln_16384": ["trsv_chain_init_kernel", "trsv_chain_kernel<float, true, false, true, true>"],
     "strsv_lt_16384": ["trsv_chain_init_kernel", "trsv_chain_kernel<float, false, true, true, true>"],
+    "dtrsv_ln_16384_dense": ["trsv_chain_init_kernel", "trsv_chain_kernel<double, true, false, true, true>"],
+    "dtrsv_lt_16384_dense": ["trsv_chain_init_kernel", "trsv_chain_kernel<double, false, true, true, true>"],
     "probe_copy": ["probe_copy_kernel"], "probe_read": ["probe_read_kernel"],
 }
 # The calls whose HBM traffic is recorded from counters (the dense ones share no kernel with each
@@ -617,7 +630,7 @@ TRAFFIC_CALLS = ["sgemv_n_16384_b0", "sgemv_t_16384_b0", "dgemv_n_16384", "dgemv
                  "probe_copy", "probe_read"]
 TRAFFIC_KERNELS = {c: CALL_KERNELS[c] for c in TRAFFIC_CALLS}
 TRAFFIC_ONLY = ",".join(TRAFFIC_KERNELS)
-EXTRA_ONLY = "strmv_ut_16384,strmv_lt_16384,ssymv_u_16384,dsymv_l_16384,dsymv_u_16384_dense,dtrmv_lt_16384_dense,strsv_ln_16384,strsv_lt_16384,probe_copy,probe_read"
+EXTRA_ONLY = "strmv_ut_16384,strmv_lt_16384,ssymv_u_16384,dsymv_l_16384,dsymv_u_16384_dense,dtrmv_lt_16384_dense,strsv_ln_16384,strsv_lt_16384,dtrsv_ln_16384_dense,dtrsv_lt_16384_dense,probe_copy,probe_read"
 # (title of the summary, file, [(row label, call, algorithmic bytes)])
 PROFILE_TABLES = [
     ("gemv at 16384 x 16384 (fp32; fp64 with lda = 16392), 1048576 x 256, 1024 x 1024, and the bandwidth probes", "gemv_16384_rocprofv3.md", [
@@ -630,7 +643,7 @@ PROFILE_TABLES = [
         ("sgemv T 1048576x256", "sgemv_t_1048576x256_b0", 4 * ((1 << 20) * 256 + 256 + (1 << 20))),
         ("sgemv N 1024^2 (cache-resident, launch-bound)", "sgemv_n_1024", 4 * (1024 * 1024 + 3 * 1024)),
         ("probe_read 1 GiB", "probe_read", NS_ * NS_ * 4), ("probe_copy 1 GiB", "probe_copy", 2 * NS_ * NS_ * 4)]),
-    ("trmv, symv, ger and trsv at n = 16384 (fp32; dsymv and dtrmv with lda = 16392 and 16384)", "triangular_16384_rocprofv3.md", [
+    ("trmv, symv, ger and trsv at n = 16384 (fp32; dsymv, dtrmv and dtrsv with lda = 16392 and 16384)", "triangular_16384_rocprofv3.md", [
         ("strmv upper N non-unit", "strmv_un_16384", 4 * (TRI_ + 2 * NS_)), ("strmv upper N unit", "strmv_uu_16384", 4 * (TRI_ + NS_)),
         ("strmv lower N non-unit", "strmv_ln_16384", 4 * (TRI_ + 2 * NS_)), ("strmv lower N unit", "strmv_lu_16384", 4 * (TRI_ + NS_)),
         ("strmv upper T non-unit", "strmv_ut_16384", 4 * (TRI_ + 2 * NS_)), ("strmv lower T non-unit", "strmv_lt_16384", 4 * (TRI_ + 2 * NS_)),
@@ -638,7 +651,9 @@ PROFILE_TABLES = [
         ("dsymv lower lda 16392", "dsymv_l_16384", 8 * (TRI_ + 3 * NS_)), ("dsymv upper lda 16384", "dsymv_u_16384_dense", 8 * (TRI_ + 3 * NS_)),
         ("dtrmv lower T non-unit lda 16384", "dtrmv_lt_16384_dense", 8 * (TRI_ + 2 * NS_)), ("sger 16384^2", "sger_16384", 4 * (2 * NS_ * NS_ + 2 * NS_)),
         ("strsv lower N unit (latency-bound chain)", "strsv_ln_16384", 4 * (TRI_ + NS_)),
-        ("strsv lower T unit (latency-bound chain)", "strsv_lt_16384", 4 * (TRI_ + NS_))]),
+        ("strsv lower T unit (latency-bound chain)", "strsv_lt_16384", 4 * (TRI_ + NS_)),
+        ("dtrsv lower N unit lda 16384 (latency-bound chain)", "dtrsv_ln_16384_dense", 8 * (TRI_ + NS_)),
+        ("dtrsv lower T unit lda 16384 (latency-bound chain)", "dtrsv_lt_16384_dense", 8 * (TRI_ + NS_))]),
     ("level-1 routines at n = 2^28 (unit stride and incx = 2 / incy = 3)", "level1_n2p28_rocprofv3.md", [
         ("saxpy", "saxpy", 3 * N1_ * 4), ("daxpy", "daxpy", 3 * N1_ * 8), ("sscal", "sscal", 2 * N1_ * 4), ("sdot", "sdot", 2 * N1_ * 4),
         ("ddot", "ddot", 2 * N1_ * 8), ("sasum", "sasum", N1_ * 4), ("snrm2", "snrm2", N1_ * 4),
