@@ -33,6 +33,17 @@ def test_every_declared_symbol_is_exported(B):
             assert f"mxb_{p}{r}" in names
 
 
+@pytest.mark.parametrize("compiler,std,suffix", [("gcc", "-std=c99", ".c"), ("g++", "-std=c++11", ".cpp")])
+def test_header_is_plain_c_and_cxx(tmp_path, compiler, std, suffix):
+    """The public header stands alone for a C99 and a C++11 caller: no torch or HIP types, no extensions."""
+    import subprocess
+    src = tmp_path / ("caller" + suffix)
+    src.write_text('#include "mxblas.h"\nint main(void) { mxb_handle_t h = 0; (void)h; return (int)MXB_OPT_COUNT * 0; }\n')
+    r = subprocess.run([compiler, std, "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only",
+                        "-I", os.path.join(ROOT, "include"), str(src)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+
+
 def test_handle_lifecycle_and_options(B):
     st, h = B.mxb_create()
     assert st == 0 and h
